@@ -1,0 +1,447 @@
+"""Pins for the CPU oracle: closed forms, quadrature, brute force, symmetry (CPU only).
+
+Each test fixes one part of oracle/egnn_oracle.py against something other than itself,
+so that a dropped term, a wrong sign or index or a transposed operand fails a test.
+"""
+from math import factorial, sqrt, pi
+import itertools
+import numpy as np
+import pytest
+
+from oracle import egnn_oracle as O
+from paper_2507_03840_amd import synth
+
+
+def _unit(n, seed):
+    v = np.random.default_rng(seed).standard_normal((n, 3))
+    return v / np.linalg.norm(v, axis=1, keepdims=True)
+
+
+def _rotation(seed):
+    q = np.random.default_rng(seed).standard_normal(4)
+    q /= np.linalg.norm(q)
+    a, b, c, d = q
+    return np.array([[a*a+b*b-c*c-d*d, 2*(b*c-a*d), 2*(b*d+a*c)],
+                     [2*(b*c+a*d), a*a-b*b+c*c-d*d, 2*(c*d-a*b)],
+                     [2*(b*d-a*c), 2*(c*d+a*b), a*a-b*b-c*c+d*d]])
+
+
+# ------------------------------------------------------------------ shape arithmetic from the paper
+def test_paper_shape_arithmetic():
+    # Sec. 4.2: a message of 3 x (l_max+1)^2 x E fp32 values is 4.8 KiB at E=16 and 38.4 KiB at E=128 (l_max=4)
+    assert 3 * (4 + 1) ** 2 * 16 * 4 == 4800 and 3 * 25 * 128 * 4 == 38400
+    # Sec. 6: 13 orbitals = 2 x s + 2 x p + 1 x d ; Sec. 4.4: 1000 Hf x 10 + 2000 O x 4 = 18k
+    assert sum(2 * l + 1 for l in (0, 0, 1, 1, 2)) == 13
+    assert 1000 * 10 + 2000 * 4 == 18000
+    # Sec. 2.2: (2la+1)(2lb+1) = sum_{L=|la-lb|}^{la+lb} (2L+1)
+    for la, lb in itertools.product(range(5), repeat=2):
+        assert (2*la+1)*(2*lb+1) == sum(2*L+1 for L in range(abs(la-lb), la+lb+1))
+
+
+def test_path_counts_and_slots():
+    assert [len(O.tp_paths(l, l, l)) for l in (0, 1, 2, 3, 4)] == [1, 4, 11, 23, 42]
+    assert len(O.tp_paths(3, 3, 4)) == 27
+    for (l1, l2, l3) in O.tp_paths(4, 4, 4):
+        assert abs(l1 - l2) <= l3 <= l1 + l2 and (l1 + l2 + l3) % 2 == 0
+    slots, n_out = O.readout_slots((0, 0, 1, 1, 2))
+    assert n_out == [9, 17, 13, 5, 1]
+    assert sum(n * (2 * L + 1) for L, n in enumerate(n_out)) == 169
+    a = O.path_norm(O.tp_paths(2, 2, 2))
+    # sum over the paths ending in one l3 of alpha^2 is 1
+    for l3 in range(3):
+        assert np.isclose(sum(a[p] ** 2 for p, t in enumerate(O.tp_paths(2, 2, 2)) if t[2] == l3), 1.0)
+
+
+# ------------------------------------------------------------------ spherical harmonics
+def test_sh_closed_forms_l_le_2():
+    r = _unit(50, 1)
+    x, y, z = r.T
+    Y = O.sph_harm_real(2, r) / sqrt(4 * pi)
+    ref = np.stack([
+        0.5 * sqrt(1 / pi) * np.ones_like(x),
+        sqrt(3 / (4 * pi)) * y, sqrt(3 / (4 * pi)) * z, sqrt(3 / (4 * pi)) * x,
+        0.5 * sqrt(15 / pi) * x * y, 0.5 * sqrt(15 / pi) * y * z, 0.25 * sqrt(5 / pi) * (3 * z * z - 1),
+        0.5 * sqrt(15 / pi) * x * z, 0.25 * sqrt(15 / pi) * (x * x - y * y)], 1)
+    assert np.allclose(Y, ref, atol=1e-14)
+
+
+def test_sh_closed_forms_l3_l4_samples():
+    # textbook real harmonics: Y_{3,-3} = 1/4 sqrt(35/2pi) y(3x^2-y^2); Y_{3,0} = 1/4 sqrt(7/pi) (5z^3-3z);
+    # Y_{4,4} = 3/16 sqrt(35/pi) (x^4 - 6x^2y^2 + y^4); Y_{4,-1} = 3/4 sqrt(5/2pi) yz(7z^2-3)
+    r = _unit(40, 2)
+    x, y, z = r.T
+    Y = O.sph_harm_real(4, r) / sqrt(4 * pi)
+    assert np.allclose(Y[:, 9 + 0], 0.25 * sqrt(35 / (2 * pi)) * y * (3 * x * x - y * y), atol=1e-14)
+    assert np.allclose(Y[:, 9 + 3], 0.25 * sqrt(7 / pi) * (5 * z ** 3 - 3 * z), atol=1e-14)
+    assert np.allclose(Y[:, 16 + 8], 3 / 16 * sqrt(35 / pi) * (x**4 - 6 * x*x*y*y + y**4), atol=1e-14)
+    assert np.allclose(Y[:, 16 + 3], 0.75 * sqrt(5 / (2 * pi)) * y * z * (7 * z * z - 3), atol=1e-14)
+
+
+def _sphere_quadrature(n_theta=24, n_phi=49):
+    t, wt = np.polynomial.legendre.leggauss(n_theta)
+    phi = 2 * pi * np.arange(n_phi) / n_phi
+    T, P = np.meshgrid(t, phi, indexing="ij")
+    s = np.sqrt(1 - T * T)
+    pts = np.stack([s * np.cos(P), s * np.sin(P), T], -1).reshape(-1, 3)
+    w = (wt[:, None] * np.full(n_phi, 2 * pi / n_phi)[None, :]).reshape(-1)
+    return pts, w
+
+
+def test_sh_orthonormal_and_addition_theorem_and_parity():
+    pts, w = _sphere_quadrature()
+    Y = O.sph_harm_real(4, pts) / sqrt(4 * pi)
+    G = np.einsum("n,na,nb->ab", w, Y, Y)
+    assert np.allclose(G, np.eye(25), atol=1e-13)
+    a, b = _unit(30, 3), _unit(30, 4)
+    Ya, Yb = O.sph_harm_real(4, a), O.sph_harm_real(4, b)
+    cosg = np.einsum("ia,ia->i", a, b)
+    for l in range(5):
+        Pl = np.polynomial.legendre.Legendre.basis(l)(cosg)
+        assert np.allclose(np.einsum("im,im->i", Ya[:, O.sl(l)], Yb[:, O.sl(l)]), (2 * l + 1) * Pl, atol=1e-12)
+        assert np.allclose(O.sph_harm_real(4, -a)[:, O.sl(l)], (-1) ** l * Ya[:, O.sl(l)], atol=1e-14)
+    # on the z axis only m = 0 survives, with value sqrt(2l+1)
+    Yz = O.sph_harm_real(4, np.array([[0.0, 0.0, 1.0]]))[0]
+    for l in range(5):
+        e = np.zeros(2 * l + 1); e[l] = sqrt(2 * l + 1)
+        assert np.allclose(Yz[O.sl(l)], e, atol=1e-14)
+
+
+# ------------------------------------------------------------------ Clebsch-Gordan
+def test_cg_complex_textbook_values():
+    # <1 0 1 0|2 0> = sqrt(2/3), <1 1 1 -1|0 0> = 1/sqrt3, <1 0 1 0|0 0> = -1/sqrt3, <1 1 1 -1|1 0> = 1/sqrt2,
+    # <2 0 2 0|4 0> = sqrt(18/35), <1 1 1 0|2 1> = 1/sqrt2
+    assert np.isclose(O.cg_complex(1, 0, 1, 0, 2, 0), sqrt(2 / 3))
+    assert np.isclose(O.cg_complex(1, 1, 1, -1, 0, 0), 1 / sqrt(3))
+    assert np.isclose(O.cg_complex(1, 0, 1, 0, 0, 0), -1 / sqrt(3))
+    assert np.isclose(O.cg_complex(1, 1, 1, -1, 1, 0), 1 / sqrt(2))
+    assert np.isclose(O.cg_complex(2, 0, 2, 0, 4, 0), sqrt(18 / 35))
+    assert np.isclose(O.cg_complex(1, 1, 1, 0, 2, 1), 1 / sqrt(2))
+
+
+def test_cg_real_orthogonality_completeness():
+    for l1, l2 in itertools.product(range(5), repeat=2):
+        total = np.zeros(((2*l1+1)*(2*l2+1),) * 2)
+        for L in range(abs(l1 - l2), l1 + l2 + 1):
+            C = O.cg_real(l1, l2, L)
+            assert np.allclose(np.einsum("abm,abn->mn", C, C), np.eye(2 * L + 1), atol=1e-13)
+            for L2 in range(abs(l1 - l2), l1 + l2 + 1):
+                if L2 != L:
+                    assert np.allclose(np.einsum("abm,abn->mn", C, O.cg_real(l1, l2, L2)), 0, atol=1e-13)
+            M = C.reshape(-1, 2 * L + 1)
+            total += M @ M.T
+        assert np.allclose(total, np.eye(total.shape[0]), atol=1e-13)
+
+
+def test_cg_real_special_cases():
+    for l in range(5):
+        assert np.allclose(O.cg_real(l, 0, l)[:, 0, :], np.eye(2 * l + 1), atol=1e-14)
+        assert np.allclose(O.cg_real(0, l, l)[0], np.eye(2 * l + 1), atol=1e-14)
+    # 1 x 1 -> 0 is -delta/sqrt3 (sign from <1 0 1 0|0 0> = -1/sqrt3 and Y_10 real)
+    assert np.allclose(O.cg_real(1, 1, 0)[:, :, 0], -np.eye(3) / sqrt(3), atol=1e-14)
+    # 1 x 1 -> 1 is the cross product up to one global sign: antisymmetric, |C| = 1/sqrt2 on the epsilon pattern.
+    # Component order (y, z, x) is a cyclic permutation of (x, y, z), so epsilon keeps its form.
+    C = O.cg_real(1, 1, 1)
+    eps = np.zeros((3, 3, 3))
+    for i, j, k in [(0, 1, 2), (1, 2, 0), (2, 0, 1)]:
+        eps[i, j, k], eps[j, i, k] = 1, -1
+    s = C[0, 1, 2] * sqrt(2)
+    assert np.isclose(abs(s), 1.0) and np.allclose(C, s * eps / sqrt(2), atol=1e-14)
+    assert s < 0   # the convention adopted: imaginary part of the transformed tensor, (y, z) -> x entry negative
+    assert np.allclose(C, -C.transpose(1, 0, 2))
+
+
+def _cg000_closed_form(l1, l2, l3):
+    g2 = l1 + l2 + l3
+    if g2 % 2:
+        return 0.0
+    g = g2 // 2
+    f = factorial
+    return ((-1) ** (g - l3) * sqrt(2 * l3 + 1) * f(g) / (f(g - l1) * f(g - l2) * f(g - l3))
+            * sqrt(f(2*g - 2*l1) * f(2*g - 2*l2) * f(2*g - 2*l3) / f(2 * g + 1)))
+
+
+def test_cg_real_equals_gaunt_for_every_even_path():
+    """Fixes sign and scale of every even-sum real coupling independently of Racah + basis change:
+    C[m1,m2,m3] = Int Y_l1m1 Y_l2m2 Y_l3m3 dOmega / ( sqrt((2l1+1)(2l2+1)/(4 pi (2l3+1))) <l1 0 l2 0|l3 0> )."""
+    pts, w = _sphere_quadrature(24, 49)
+    Y = O.sph_harm_real(4, pts) / sqrt(4 * pi)
+    paths = sorted(set(O.tp_paths(4, 4, 4)) | set(O.tp_paths(2, 2, 4)) | set(O.tp_paths(3, 3, 4)))
+    assert len(paths) >= 42
+    for (l1, l2, l3) in paths:
+        gaunt = np.einsum("n,na,nb,nc->abc", w, Y[:, O.sl(l1)], Y[:, O.sl(l2)], Y[:, O.sl(l3)])
+        scale = sqrt((2*l1+1) * (2*l2+1) / (4 * pi * (2*l3+1))) * _cg000_closed_form(l1, l2, l3)
+        assert abs(scale) > 1e-6
+        assert np.allclose(O.cg_real(l1, l2, l3), gaunt / scale, atol=1e-12), (l1, l2, l3)
+
+
+def test_cg_real_is_rotation_invariant_including_odd_paths():
+    R = _rotation(5)
+    for (l1, l2, l3) in [(1, 1, 1), (1, 2, 2), (2, 2, 1), (2, 2, 3), (2, 1, 2), (1, 1, 2), (2, 2, 4), (4, 3, 2)]:
+        D1, D2, D3 = (O.wigner_d_real(l, R) for l in (l1, l2, l3))
+        C = O.cg_real(l1, l2, l3)
+        assert np.allclose(np.einsum("ia,jb,kc,abc->ijk", D1, D2, D3, C), C, atol=1e-12)
+
+
+def test_wigner_d_properties():
+    R1, R2 = _rotation(6), _rotation(7)
+    for l in range(5):
+        D1, D2 = O.wigner_d_real(l, R1), O.wigner_d_real(l, R2)
+        assert np.allclose(D1 @ D1.T, np.eye(2 * l + 1), atol=1e-12)
+        assert np.allclose(O.wigner_d_real(l, R1 @ R2), D1 @ D2, atol=1e-12)
+    # l = 1 in (y, z, x) order is the rotation matrix itself, permuted
+    perm = [1, 2, 0]
+    assert np.allclose(O.wigner_d_real(1, R1), R1[np.ix_(perm, perm)], atol=1e-12)
+
+
+# ------------------------------------------------------------------ radial part
+def test_radial_basis_and_envelope_values():
+    d = np.array([0.0, 2.0, 3.0, 6.0])
+    B = O.radial_basis(d, 4, 6.0)   # centres 0, 2, 4, 6 ; sigma 2
+    assert np.allclose(B[0], [1, np.exp(-0.5), np.exp(-2), np.exp(-4.5)])
+    assert np.allclose(B[1], [np.exp(-0.5), 1, np.exp(-0.5), np.exp(-2)])
+    assert np.allclose(B[2, 1], np.exp(-0.125)) and np.allclose(B[3, 3], 1.0)
+    assert np.allclose(O.envelope(d, 6.0), [1.0, 0.75, 0.5, 0.0])
+    assert np.isclose(O.silu(np.array([0.0, 1.0]))[1], 1 / (1 + np.exp(-1.0)))
+    # w is linear in W_r2, scaled by alpha and f_c: one basis, one hidden unit, weights 1
+    paths = O.tp_paths(1, 1, 1)
+    w = O.radial_weights(np.array([3.0]), np.ones((1, 2)), np.ones((len(paths) * 2, 1)), paths, 2, 2, 6.0)
+    g = O.silu(np.array([np.exp(-0.125) * 2]))[0]   # centres 0 and 6, sigma 6 -> both exp(-9/72)
+    assert np.allclose(w[0, :, 0], 0.5 * g * O.path_norm(paths))
+
+
+# ------------------------------------------------------------------ edge set
+def _brute_pairs(pos, n_owned, box, pbc, r_cut):
+    p = pos.astype(np.float64)
+    out = []
+    for j in range(n_owned):
+        for i in range(len(p)):
+            if i == j:
+                continue
+            best = None
+            # all images in {-1,0,1}^3 on periodic axes: the minimum image is among them
+            rng = [(-1, 0, 1) if pbc[a] else (0,) for a in range(3)]
+            for s in itertools.product(*rng):
+                d = p[i] + np.array(s) * box.astype(np.float64) - p[j]
+                d2 = float(d @ d)
+                if best is None or d2 < best[0]:
+                    best = (d2, s)
+            if best[0] < float(np.float32(r_cut)) ** 2:
+                out.append((j, i, best[1]))
+    return out
+
+
+@pytest.mark.parametrize("periodic", [False, True])
+def test_neighbour_list_vs_python_brute_force(periodic):
+    w = synth.small_cluster(40, 33, 1, 4, 4, r_cut=3.0, seed=1, periodic=periodic, density=0.08)
+    src, dst, shift, row_ptr = O.neighbour_list(w.pos, w.n_owned, w.box, w.pbc, w.r_cut)
+    ref = _brute_pairs(w.pos, w.n_owned, w.box, w.pbc, w.r_cut)
+    got = [(int(j), int(i), tuple(int(s) for s in sh)) for i, j, sh in zip(src, dst, shift)]
+    assert got == ref and len(ref) > 100
+    assert row_ptr[-1] == len(src) and np.all(np.diff(row_ptr) == np.bincount(dst, minlength=w.n_owned))
+    if periodic:
+        assert np.any(shift != 0)
+
+
+def test_neighbour_list_perfect_diamond_shells():
+    # perfect diamond: 4 neighbours at a sqrt3/4, 12 at a/sqrt2, 12 at a sqrt11/4, 6 at a, 12 at a sqrt19/4
+    rng = np.random.default_rng(0)
+    pos, _ = synth._diamond((3, 3, 3), 0.0, rng)
+    a = synth.DIAMOND_A
+    box = np.array([3 * a] * 3, np.float32)
+    pbc = np.ones(3, np.uint8)
+    for r_cut, deg in [(a * 0.5, 4), (a * 0.75, 16), (a * 0.9, 28), (a * 1.05, 34), (a * 1.1, 46)]:
+        src, dst, shift, row_ptr = O.neighbour_list(pos.astype(np.float32), len(pos), box, pbc, r_cut)
+        assert np.all(np.diff(row_ptr) == deg), (r_cut, deg)
+    # symmetric: i->j present iff j->i present with the opposite shift
+    fwd = set(zip(src.tolist(), dst.tolist(), map(tuple, shift.tolist())))
+    assert all((j, i, tuple(-s for s in sh)) in fwd for (i, j, sh) in fwd)
+
+
+def test_neighbour_list_permutation_and_halo():
+    w = synth.small_cluster(60, 60, 1, 4, 4, r_cut=3.5, seed=2, periodic=True)
+    src, dst, shift, _ = O.neighbour_list(w.pos, 60, w.box, w.pbc, w.r_cut)
+    perm = np.random.default_rng(3).permutation(60)
+    src2, dst2, shift2, _ = O.neighbour_list(w.pos[perm], 60, w.box, w.pbc, w.r_cut)
+    a = set(zip(src.tolist(), dst.tolist(), map(tuple, shift.tolist())))
+    b = set(zip(perm[src2].tolist(), perm[dst2].tolist(), map(tuple, shift2.tolist())))
+    assert a == b
+    # owning only the first 25 atoms keeps exactly the edges whose destination is owned
+    src3, dst3, shift3, rp3 = O.neighbour_list(w.pos, 25, w.box, w.pbc, w.r_cut)
+    keep = dst < 25
+    assert np.array_equal(src3, src[keep]) and np.array_equal(dst3, dst[keep]) and len(rp3) == 26
+    # sorted by (dst, src)
+    key = dst.astype(np.int64) * 1000 + src
+    assert np.all(np.diff(key) > 0)
+
+
+# ------------------------------------------------------------------ layer and readout
+def _setup(lmax=2, E=4, n_rbf=5, n=24, n_owned=24, seed=0, periodic=False, r_cut=3.5):
+    w = synth.small_cluster(n, n_owned, lmax, E, n_rbf, r_cut=r_cut, seed=seed, periodic=periodic, density=0.06)
+    rng = np.random.default_rng(seed + 100)
+    P = len(O.tp_paths(lmax, lmax, lmax))
+    W = synth.layer_weights(rng, lmax, E, n_rbf, 8, P)
+    x = synth.node_features(rng, n, lmax, E)
+    g = O.neighbour_list(w.pos, w.n_owned, w.box, w.pbc, w.r_cut)
+    return w, W, x, g
+
+
+def _layer(w, W, x, g, pos=None, **kw):
+    return O.layer_forward(g, w.pos if pos is None else pos, w.box, x, W, w.lmax, w.lmax, w.channels,
+                           w.n_rbf, w.r_cut, agg_norm=kw.pop("agg_norm", 7.0), **kw)
+
+
+@pytest.mark.parametrize("lmax", [1, 2, 4])
+def test_layer_rotation_equivariance(lmax):
+    w, W, x, g = _setup(lmax=lmax, E=3, n=14, n_owned=10)
+    R = _rotation(11)
+    D = O.wigner_d_block(lmax, R)
+    y = _layer(w, W, x, g)
+    pos_r = (w.pos.astype(np.float64) @ R.T)
+    # rotate in fp64: bypass the fp32 cast by passing a float64 array through a subclass-free path
+    y_r = _layer_fp64_pos(w, W, np.einsum("ab,nbc->nac", D, x.astype(np.float64)), g, pos_r)
+    assert np.allclose(y_r, np.einsum("ab,nbc->nac", D, y), atol=1e-11 * max(1.0, np.abs(y).max()))
+    assert np.abs(y).max() > 1e-2
+
+
+def _layer_fp64_pos(w, W, x, g, pos64):
+    """layer_forward casts positions to fp32; for symmetry tests feed exact fp64 positions instead."""
+    saved = O.edge_vectors
+    src, dst, shift, row_ptr = g
+    def ev(pos, box, s, d, sh):
+        return pos64[s] + sh.astype(np.float64) * np.asarray(box, np.float64) * 0.0 - pos64[d]
+    O.edge_vectors = ev
+    try:
+        assert not np.any(shift)
+        return _layer(w, W, x, g)
+    finally:
+        O.edge_vectors = saved
+
+
+def test_layer_permutation_equivariance_and_translation():
+    w, W, x, g = _setup(lmax=2, E=3, n=20, n_owned=20, periodic=True, r_cut=3.0)
+    y = _layer(w, W, x, g)
+    perm = np.random.default_rng(5).permutation(20)
+    g2 = O.neighbour_list(w.pos[perm], 20, w.box, w.pbc, w.r_cut)
+    y2 = O.layer_forward(g2, w.pos[perm], w.box, x[perm], W, 2, 2, 3, w.n_rbf, w.r_cut, agg_norm=7.0)
+    assert np.allclose(y2, y[perm], atol=1e-12)
+
+
+def test_layer_linearity_and_norm():
+    w, W, x, g = _setup(lmax=2, E=3, n=16, n_owned=12)
+    x2 = synth.node_features(np.random.default_rng(9), 16, 2, 3)
+    y1, y2 = _layer(w, W, x, g), _layer(w, W, x2, g)
+    y12 = _layer(w, W, 2.0 * x.astype(np.float64) - 0.5 * x2, g)
+    assert np.allclose(y12, 2.0 * y1 - 0.5 * y2, atol=1e-12)
+    # only owned rows are produced and halo rows only act as sources
+    assert y1.shape == (12, 9, 3)
+    # 1/sqrt(agg_norm) scaling acts on the message term only
+    W0 = dict(W, W_self=np.zeros_like(W["W_self"]))
+    assert np.allclose(_layer(w, W0, x, g, agg_norm=4.0) * 2.0, _layer(w, W0, x, g, agg_norm=1.0), atol=1e-12)
+    # linear in W_r2
+    Wb = dict(W0, W_r2=4.0 * W0["W_r2"])  # power of two: exact in fp32
+    assert np.allclose(_layer(w, Wb, x, g), 4.0 * _layer(w, W0, x, g), atol=1e-12)
+
+
+def test_layer_lmax0_is_scalar_continuous_filter_convolution():
+    """With l_max = 0 the layer is x'_j = W_post sum_k w_k * (W_pre x)_src(k) / sqrt(nbar) + W_self x_j,
+    w_k[c] = f_c(d) (W_r2 SiLU(W_r1 B(d)))[c]  (one path, alpha = 1, C = 1, Yhat_00 = 1)."""
+    w, W, x, g = _setup(lmax=0, E=4, n=18, n_owned=18)
+    src, dst, shift, row_ptr = g
+    y = _layer(w, W, x, g)
+    p = w.pos.astype(np.float64)
+    d = np.linalg.norm(p[src] - p[dst], axis=1)
+    mu = np.arange(w.n_rbf) * w.r_cut / (w.n_rbf - 1)
+    B = np.exp(-(d[:, None] - mu) ** 2 / (2 * (w.r_cut / (w.n_rbf - 1)) ** 2))
+    t = B @ W["W_r1"].T.astype(np.float64)
+    wk = (t / (1 + np.exp(-t))) @ W["W_r2"].T.astype(np.float64) * (0.5 * (1 + np.cos(pi * d / w.r_cut)))[:, None]
+    h = x[:, 0, :].astype(np.float64) @ W["W_pre"][0].T
+    agg = np.zeros((18, 4))
+    np.add.at(agg, dst, wk * h[src])
+    ref = agg / sqrt(7.0) @ W["W_post"][0].T + x[:, 0, :].astype(np.float64) @ W["W_self"][0].T
+    assert np.allclose(y[:, 0, :], ref, atol=1e-12)
+
+
+def test_layer_single_edge_on_z_axis_hand_example():
+    """Two atoms on the z axis, source above the destination: Yhat_lm = sqrt(2l+1) delta_m0.
+    With identity channel mixes, W_self = 0, unit weights, the message into atom 0 from a source carrying
+    only (l1=1, m=0) = 1 is  sum over paths (1, l2, l3) of C[0,0,0] sqrt(2 l2+1) in component (l3, m=0)."""
+    lmax, E = 2, 1
+    pos = np.array([[0, 0, 0], [0, 0, 1.5]], np.float32)
+    g = O.neighbour_list(pos, 1, np.ones(3, np.float32), np.zeros(3, np.uint8), 2.0)
+    assert g[0].tolist() == [1] and g[1].tolist() == [0]
+    paths = O.tp_paths(lmax, lmax, lmax)
+    x = np.zeros((2, 9, 1)); x[1, 2, 0] = 1.0          # (l=1, m=0) is flat index 1 + 1
+    eye = np.ones((lmax + 1, 1, 1))
+    W = dict(W_pre=eye, W_post=eye, W_self=0 * eye)
+    y = O.layer_forward(g, pos, np.ones(3), x, W, lmax, lmax, E, 4, 2.0, agg_norm=1.0,
+                        w_edge=np.ones((1, len(paths), 1)))
+    # hand values: <1 0 0 0|1 0> = 1 ; <1 0 1 0|0 0> = -1/sqrt3, <1 0 1 0|2 0> = sqrt(2/3) ; <1 0 2 0|1 0> = -sqrt(2/5)
+    expect = np.zeros(9)
+    expect[0] = -1 / sqrt(3) * sqrt(3)                 # (1,1,0)
+    expect[2] = 1.0 * 1 + (-sqrt(2 / 5)) * sqrt(5)     # (1,0,1) + (1,2,1)
+    expect[6] = sqrt(2 / 3) * sqrt(3)                  # (1,1,2)
+    assert np.allclose(y[0, :, 0], expect, atol=1e-13)
+
+
+def _readout_setup(lmax, seed=0):
+    w, _, x, g = _setup(lmax=lmax, E=3, n=10, n_owned=8, seed=seed)
+    rng = np.random.default_rng(seed + 50)
+    slots, n_out = O.readout_slots(w.orb_l)
+    Wr = synth.readout_weights(rng, lmax, 3, w.n_rbf, 8, len(O.tp_paths(lmax, lmax, 4)), sum(n_out))
+    return w, Wr, x, g
+
+
+@pytest.mark.parametrize("lmax", [2, 4])
+def test_readout_rotation_covariance(lmax):
+    """H' = D^{l_a}(R) H D^{l_b}(R)^T per orbital sub-block (Sec. 2.2)."""
+    w, Wr, x, g = _readout_setup(lmax)
+    H = O.readout_hij(g, w.pos, w.box, x, Wr, lmax, lmax, 3, w.n_rbf, w.r_cut, w.orb_l)
+    R = _rotation(21)
+    D = O.wigner_d_block(lmax, R)
+    pos64 = w.pos.astype(np.float64) @ R.T
+    saved = O.edge_vectors
+    O.edge_vectors = lambda pos, box, s, d, sh: pos64[s] - pos64[d]
+    try:
+        Hr = O.readout_hij(g, w.pos, w.box, np.einsum("ab,nbc->nac", D, x.astype(np.float64)), Wr,
+                           lmax, lmax, 3, w.n_rbf, w.r_cut, w.orb_l)
+    finally:
+        O.edge_vectors = saved
+    Dorb = np.zeros((13, 13))
+    off = 0
+    for l in w.orb_l:
+        Dorb[off:off + 2*l+1, off:off + 2*l+1] = O.wigner_d_real(l, R)
+        off += 2 * l + 1
+    assert H.shape[1:] == (13, 13) and np.abs(H).max() > 1e-3
+    assert np.allclose(Hr, np.einsum("ab,kbc,dc->kad", Dorb, H, Dorb), atol=1e-11 * np.abs(H).max())
+
+
+def test_readout_ss_block_is_the_collapsed_scalar():
+    """The (s, s) entry is C^{(0,0)}_{(00)(00)} q = sum_c V_0[o, c] u[L=0, c]; with l_max = 0 features the only path
+    into L=0 is (0,0,0), so H[0,0] = sum_c V[0,c] w[c] (W_s x_src + W_t x_dst)[c]."""
+    w, Wr, x, g = _readout_setup(2, seed=3)
+    lmax = 0
+    rng = np.random.default_rng(1)
+    slots, n_out = O.readout_slots(w.orb_l)
+    paths = O.tp_paths(0, 0, 4)
+    assert paths == [(0, 0, 0)]
+    Wr = synth.readout_weights(rng, 0, 3, w.n_rbf, 8, 1, sum(n_out))
+    x0 = x[:, :1, :]
+    H = O.readout_hij(g, w.pos, w.box, x0, Wr, 0, 0, 3, w.n_rbf, w.r_cut, w.orb_l)
+    src, dst = g[0], g[1]
+    p = w.pos.astype(np.float64)
+    d = np.linalg.norm(p[src] - p[dst], axis=1)
+    wk = O.radial_weights(d, Wr["W_r1"], Wr["W_r2"], paths, 3, w.n_rbf, w.r_cut)[:, 0, :]
+    z = x0[src, 0].astype(np.float64) @ Wr["W_s"][0].T + x0[dst, 0].astype(np.float64) @ Wr["W_t"][0].T
+    # slot order: (alpha=0,beta=0,L=0) is the first L=0 slot, (0,1,0) the second
+    assert np.allclose(H[:, 0, 0], (wk * z) @ Wr["V"][0].astype(np.float64), atol=1e-12)
+    assert np.allclose(H[:, 0, 1], (wk * z) @ Wr["V"][1].astype(np.float64), atol=1e-12)
+    # nothing but L = 0 can be produced from scalar features and Y_00: p and d rows/cols vanish off the diagonal-L0 part
+    assert np.allclose(H[:, 0, 2:5], 0) and np.allclose(H[:, 8:, 0], 0)
+    # p-p block from L=0 only: -delta/sqrt3 times its scalar
+    assert np.allclose(H[:, 2, 3], 0) and np.abs(H[:, 2, 2]).max() > 0
+    assert np.allclose(H[:, 2, 2], H[:, 3, 3]) and np.allclose(H[:, 2, 2], H[:, 4, 4])
+
+
+def test_mse_loss_value():
+    H = np.arange(8.0).reshape(2, 2, 2)
+    assert np.isclose(O.loss_mse(H, H + 2.0), 4.0) and np.isclose(O.loss_mse(H, 0 * H), np.mean(np.arange(8.0) ** 2))
