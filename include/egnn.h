@@ -1,0 +1,153 @@
+/*
+ * egnn.h -- C ABI of the MI355X (gfx950) hot path of the equivariant message-passing network of
+ * arXiv 2507.03840 ("Distributed Equivariant Graph Neural Networks for Large-Scale Electronic
+ * Structure Prediction"): radius graph -> per-edge equivariant messages -> sums over incoming
+ * edges -> per-degree channel mixes -> orbital blocks H_ij.
+ *
+ * General conventions
+ *   - Every pointer is a DEVICE pointer unless its comment says "host".  The caller owns every
+ *     buffer, including the workspace; the library allocates no device memory, keeps no pointer
+ *     after a call returns, and enqueues all work on the stream passed in (a hipStream_t, passed
+ *     as void*; NULL = the default stream).  Only egnn_nlist_count synchronises the stream.
+ *   - Node tensors: float [n_nodes][(lmax+1)^2][channels], channel fastest; the (l, m) axis is
+ *     flattened as l*l + l + m, m = -l..l  (Sec. 3 "Initialization": T^node of shape
+ *     (l_max+1)^2 x E per atom).
+ *   - Real spherical harmonics: z polar axis; m > 0 ~ cos(m phi), m < 0 ~ sin(|m| phi); no
+ *     Condon-Shortley sign in the real form; component normalisation (sum_m Y_lm^2 = 2l+1).
+ *   - Coupling paths P(l_in, l_sh, l_out): all (l1, l2, l3) with l1 <= l_in, l2 <= l_sh,
+ *     |l1-l2| <= l3 <= min(l1+l2, l_out), l1+l2+l3 even, in lexicographic order; the path index p
+ *     is the position in that list.  Real coupling tensors are the real (even l1+l2+l3) or imaginary
+ *     (odd) part of the Condon-Shortley Clebsch-Gordan coefficients of Eq. 1 in the real basis.
+ *   - Edge k = (src i -> dst j); its vector is r_k = pos[i] + shift_k * box - pos[j].  Edges are
+ *     sorted by (dst, src); row_ptr[j] .. row_ptr[j+1] are the edges into owned node j
+ *     ("incoming edge" ownership, Sec. 3 "Distribution").  Owned nodes are rows 0 .. n_owned-1,
+ *     halo nodes (read-only sources) follow.
+ *   - Return value: 0 on success, a negative EGNN_E* code otherwise; egnn_last_error() gives text.
+ *     Nothing throws or aborts across this boundary.  Identical inputs give bit-identical
+ *     outputs (no floating-point atomics anywhere).
+ */
+#ifndef EGNN_H
+#define EGNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EGNN_OK 0
+#define EGNN_EINVAL (-1) /* bad descriptor, null pointer, unsupported shape            */
+#define EGNN_EBOX (-2)   /* periodic box edge < 2*r_cut: minimum image not unique      */
+#define EGNN_EWS (-3)    /* workspace too small                                        */
+#define EGNN_EHIP (-4)   /* a HIP call failed; text in egnn_last_error                 */
+
+#define EGNN_MAX_SHELLS 8
+
+typedef struct egnn_ctx egnn_ctx; /* opaque: host-side constant tables and the last error text */
+
+/* Model description, filled by the caller.  .size = sizeof(egnn_model_desc).
+ * Supported: lmax == lmax_sh in 0..4; channels in {8,16,32,64,128}; n_rbf in 2..32;
+ * n_radial_hidden == 64; orbital shells with l <= 2 (Sec. 6: 13 orbitals = 2s + 2p + 1d). */
+typedef struct {
+  uint32_t size;
+  int32_t lmax, lmax_sh, channels, n_rbf, n_radial_hidden, n_layers;
+  float r_cut;
+  float agg_norm; /* nbar > 0: messages are summed and divided by sqrt(nbar) */
+  int32_t n_orb_shells;
+  int32_t orb_l[EGNN_MAX_SHELLS];
+} egnn_model_desc;
+
+typedef struct {
+  const int32_t* src;     /* [n_edges] */
+  const int32_t* dst;     /* [n_edges] */
+  const int32_t* row_ptr; /* [n_owned+1] */
+  const int8_t* shift;    /* [n_edges][3], periodic image of the source; may be NULL (all zero) */
+  int64_t n_edges;
+  int32_t n_owned, n_total;
+} egnn_graph;
+
+int egnn_create(const egnn_model_desc* desc, egnn_ctx** out);
+void egnn_destroy(egnn_ctx* ctx);
+const char* egnn_last_error(const egnn_ctx* ctx); /* ctx-owned string; ctx may be NULL (create errors) */
+
+/* Number of coupling paths: which = 0 -> layers, P(lmax, lmax_sh, lmax); 1 -> readout, P(lmax, lmax_sh, 4).
+ * If paths (host, [n][3]) is not NULL the (l1,l2,l3) triples are written to it. */
+int egnn_path_count(const egnn_ctx* ctx, int which, int32_t* n_paths, int32_t* paths);
+
+/* Rows of the packed collapse matrix V of the readout per coupled degree L = 0..4 (host, [5]). */
+int egnn_readout_widths(const egnn_ctx* ctx, int32_t n_out[5]);
+
+/* Bytes of workspace egnn_layer_forward / egnn_readout_hij need when they build the radial
+ * weights themselves (with_weights != 0) or get them from the caller (0). */
+int egnn_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, int32_t n_total,
+                         int with_weights, size_t* bytes);
+
+/* ---- S1  radius graph (Sec. 3 "Initialization": edges i -> j within r_cut; Sec. 4.4: periodic) ----
+ * Ordered pairs (i, j), i != j, j < n_owned, i < n_total, |pos_i + shift*box - pos_j| < r_cut with
+ * the minimum image on periodic axes; fp64 predicate on the fp32 data; strict '<'.
+ * Two phases because n_edges depends on the data: count fills row_ptr and returns n_edges (host),
+ * the caller allocates src/dst/shift, fill writes them sorted by (dst, src).
+ * box, pbc: host arrays of 3.  EGNN_EBOX if a periodic edge is shorter than 2*r_cut. */
+int egnn_nlist_count(egnn_ctx* ctx, const float* pos, int32_t n_owned, int32_t n_total,
+                     const float box[3], const uint8_t pbc[3], int32_t* row_ptr, int64_t* n_edges,
+                     void* stream);
+int egnn_nlist_fill(egnn_ctx* ctx, const float* pos, int32_t n_owned, int32_t n_total,
+                    const float box[3], const uint8_t pbc[3], const int32_t* row_ptr,
+                    int32_t* src, int32_t* dst, int8_t* shift /* may be NULL */, void* stream);
+
+/* ---- node initialisation (Sec. 3: the L=0 plane carries the atomic species) ----
+ * x[i][0][c] += table[species[i]][c]. */
+int egnn_species_embed(egnn_ctx* ctx, const int32_t* species, const float* table, int32_t n_species,
+                       float* x, int32_t n_nodes, void* stream);
+
+/* ---- S2  edge geometry (Sec. 3: distances in a Gaussian basis; Sec. 2.2: Y^l_m of the direction) ----
+ * rhat_d[k] = (r_k / |r_k|, |r_k|) as 4 floats.  Optional outputs (NULL to skip):
+ * Y [n_edges][(lmax_sh+1)^2] component-normalised real harmonics; rbf [n_edges][n_rbf] with
+ * B_b(d) = exp(-(d - b*r_cut/(n_rbf-1))^2 / (2 (r_cut/(n_rbf-1))^2)); fc [n_edges] = (1+cos(pi d/r_cut))/2. */
+int egnn_edge_geometry(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
+                       float* rhat_d, float* Y, float* rbf, float* fc, void* stream);
+
+/* ---- S3  radial weights ----
+ * w[k][p][c] = fc(d_k) * alpha_p * (W_r2 SiLU(W_r1 B(d_k)))[p*channels + c], alpha_p = 1/sqrt(#paths
+ * with the same l3).  which = 0 (layer paths) or 1 (readout paths).  W_r1 [64][n_rbf], W_r2 [P*channels][64]. */
+int egnn_radial_weights(egnn_ctx* ctx, int which, const float* rhat_d, int64_t n_edges,
+                        const float* W_r1, const float* W_r2, float* w, void* stream);
+
+/* ---- S4  tensor-product messages summed over incoming edges (Sec. 3 "Message passing";
+ *          Sec. 2.1, 2.2, Eq. 1 for the coupling) ----
+ * a[j][(l3,m3)][c] = agg_norm^-1/2 * sum_{k: dst(k)=j} sum_p w[k][p][c] *
+ *                    sum_{m1,m2} C_p[m1][m2][m3] h[src(k)][(l1,m1)][c] Yhat_{l2,m2}(rhat_k),   j < n_owned.
+ * h [n_total][...], w [n_edges][P][channels], a [n_owned][...].  Deterministic (sorted segments). */
+int egnn_tp_segsum(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, const float* h,
+                   const float* w, float* a, void* stream);
+
+/* ---- S5  per-degree channel mix (the per-l linear of Fig. 2(d)) ----
+ * y[n][(l,m)][c] = sum_c' W1[l][c][c'] x1[n][(l,m)][c'] (+ sum_c' W2[l][c][c'] x2[n][(l,m)][c'] if W2 != NULL). */
+int egnn_node_mix(egnn_ctx* ctx, const float* x1, const float* W1, const float* x2, const float* W2,
+                  float* y, int32_t n_nodes, void* stream);
+
+/* ---- one message-passing layer, forward: S2 (if needed) -> S3 -> S5(pre) -> S4 -> S5(post) ----
+ * x_out[j] = W_post a_j + W_self x_in[j] for j < n_owned, with h = W_pre x_in.  x_in has n_total rows;
+ * x_out has n_owned rows and must not alias x_in.  If w_edge != NULL it is used as the radial
+ * weights (W_r1, W_r2 ignored).  ws: at least egnn_workspace_bytes(...) bytes, 256-byte aligned. */
+int egnn_layer_forward(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
+                       const float* x_in, const float* W_pre, const float* W_post, const float* W_self,
+                       const float* W_r1, const float* W_r2, const float* w_edge, float* x_out,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/* ---- S6  readout of the orbital blocks (Fig. 2(e); Sec. 2.2; Sec. 3) ----
+ * z_k = (W_s x)[src] + (W_t x)[dst];  u_k = tensor product of z_k with Yhat(rhat_k) over P(lmax, lmax_sh, 4)
+ * with its own radial weights;  q_k[o][M] = sum_c V_L[o][c] u_k[(L,M)][c];
+ * H_k[(a,m_a)][(b,m_b)] = sum_{L,M} C^{(L,M)}_{(l_a m_a)(l_b m_b)} q_k[o(a,b,L)][M], rows = source-atom
+ * orbitals, columns = destination-atom orbitals, o(a,b,L) counting ordered shell pairs in row-major
+ * shell order with L ascending, separately per L.  V packs V_0 .. V_4, each [n_out(L)][channels].
+ * H [n_edges][n_orb][n_orb]. */
+int egnn_readout_hij(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
+                     const float* x, const float* W_s, const float* W_t, const float* W_r1,
+                     const float* W_r2, const float* V, float* H, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EGNN_H */

@@ -1,0 +1,229 @@
+"""Thin ctypes binding of libegnn_hip.so: argument marshalling only, same names as include/egnn.h.
+
+torch supplies device memory and the stream; every step of the path runs in the library's kernels.
+There is no fallback: if the library is missing or a call fails, an exception is raised.
+"""
+import ctypes as C
+import os
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libegnn_hip.so")
+MAX_SHELLS = 8
+
+SYMBOLS = [
+    "egnn_create", "egnn_destroy", "egnn_last_error", "egnn_path_count", "egnn_readout_widths",
+    "egnn_workspace_bytes", "egnn_nlist_count", "egnn_nlist_fill", "egnn_species_embed",
+    "egnn_edge_geometry", "egnn_radial_weights", "egnn_tp_segsum", "egnn_node_mix",
+    "egnn_layer_forward", "egnn_readout_hij",
+]
+
+
+class ModelDesc(C.Structure):
+    _fields_ = [("size", C.c_uint32), ("lmax", C.c_int32), ("lmax_sh", C.c_int32), ("channels", C.c_int32),
+                ("n_rbf", C.c_int32), ("n_radial_hidden", C.c_int32), ("n_layers", C.c_int32),
+                ("r_cut", C.c_float), ("agg_norm", C.c_float), ("n_orb_shells", C.c_int32),
+                ("orb_l", C.c_int32 * MAX_SHELLS)]
+
+
+class GraphDesc(C.Structure):
+    _fields_ = [("src", C.c_void_p), ("dst", C.c_void_p), ("row_ptr", C.c_void_p), ("shift", C.c_void_p),
+                ("n_edges", C.c_int64), ("n_owned", C.c_int32), ("n_total", C.c_int32)]
+
+
+class EgnnError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"egnn error {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library():
+    """Loads the built library; raises if it has not been built (python -m paper_2507_03840_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} not built; run `python -m paper_2507_03840_amd.build`")
+        lib = C.CDLL(LIB_PATH)
+        lib.egnn_last_error.restype = C.c_char_p
+        lib.egnn_last_error.argtypes = [C.c_void_p]
+        lib.egnn_destroy.restype = None
+        lib.egnn_destroy.argtypes = [C.c_void_p]
+        _lib = lib
+    return _lib
+
+
+def _ptr(t):
+    if t is None:
+        return C.c_void_p(0)
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensor required"
+    return C.c_void_p(t.data_ptr())
+
+
+def _f3(a):
+    return (C.c_float * 3)(*[float(v) for v in a])
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Graph:
+    """Device-resident edge list sorted by (dst, src) with its CSR index."""
+
+    def __init__(self, src, dst, row_ptr, shift, n_owned, n_total):
+        self.src, self.dst, self.row_ptr, self.shift = src, dst, row_ptr, shift
+        self.n_edges, self.n_owned, self.n_total = int(src.numel()), int(n_owned), int(n_total)
+
+    def desc(self):
+        return GraphDesc(_ptr(self.src).value, _ptr(self.dst).value, _ptr(self.row_ptr).value,
+                         _ptr(self.shift).value if self.shift is not None else None,
+                         self.n_edges, self.n_owned, self.n_total)
+
+
+class Egnn:
+    """One model context (egnn_ctx) plus the calls of the C ABI."""
+
+    def __init__(self, lmax, channels, n_rbf, r_cut, agg_norm, n_layers=1, orb_l=(0, 0, 1, 1, 2), lmax_sh=None,
+                 n_radial_hidden=64):
+        self.lib = load_library()
+        d = ModelDesc()
+        d.size = C.sizeof(ModelDesc)
+        d.lmax, d.lmax_sh = lmax, lmax if lmax_sh is None else lmax_sh
+        d.channels, d.n_rbf, d.n_radial_hidden, d.n_layers = channels, n_rbf, n_radial_hidden, n_layers
+        d.r_cut, d.agg_norm = r_cut, agg_norm
+        d.n_orb_shells = len(orb_l)
+        for i, l in enumerate(orb_l):
+            d.orb_l[i] = l
+        self.desc = d
+        self.ctx = C.c_void_p()
+        rc = self.lib.egnn_create(C.byref(d), C.byref(self.ctx))
+        if rc:
+            raise EgnnError(rc, self.lib.egnn_last_error(None).decode())
+        self.lmax, self.channels, self.n_rbf = lmax, channels, n_rbf
+        self.dim = (lmax + 1) ** 2
+        self.n_orb = sum(2 * l + 1 for l in orb_l)
+        self.n_paths, self.paths = self.egnn_path_count(0)
+        self.n_paths_readout, self.paths_readout = self.egnn_path_count(1)
+        self.n_out = self.egnn_readout_widths()
+
+    def __del__(self):
+        ctx = getattr(self, "ctx", None)
+        if ctx is not None and ctx.value:
+            self.lib.egnn_destroy(ctx)
+            self.ctx = None
+
+    def _check(self, rc):
+        if rc:
+            raise EgnnError(rc, self.lib.egnn_last_error(self.ctx).decode())
+
+    # ---- queries
+    def egnn_path_count(self, which):
+        n = C.c_int32()
+        self._check(self.lib.egnn_path_count(self.ctx, which, C.byref(n), None))
+        buf = (C.c_int32 * (3 * n.value))()
+        self._check(self.lib.egnn_path_count(self.ctx, which, C.byref(n), buf))
+        return n.value, [tuple(buf[3 * p:3 * p + 3]) for p in range(n.value)]
+
+    def egnn_readout_widths(self):
+        buf = (C.c_int32 * 5)()
+        self._check(self.lib.egnn_readout_widths(self.ctx, buf))
+        return list(buf)
+
+    def egnn_workspace_bytes(self, n_edges, n_owned, n_total, with_weights=True):
+        out = C.c_size_t()
+        self._check(self.lib.egnn_workspace_bytes(self.ctx, C.c_int64(n_edges), n_owned, n_total,
+                                                  1 if with_weights else 0, C.byref(out)))
+        return out.value
+
+    def workspace(self, graph, with_weights=True):
+        nbytes = self.egnn_workspace_bytes(graph.n_edges, graph.n_owned, graph.n_total, with_weights)
+        return torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+
+    # ---- S1
+    def egnn_nlist(self, pos, n_owned, box, pbc, with_shift=True):
+        """count + allocate + fill; returns a Graph."""
+        n_total = pos.shape[0]
+        pbc_c = (C.c_uint8 * 3)(*[int(v) for v in pbc])
+        row_ptr = torch.empty(n_owned + 1, dtype=torch.int32, device="cuda")
+        n_edges = C.c_int64()
+        self._check(self.lib.egnn_nlist_count(self.ctx, _ptr(pos), n_owned, n_total, _f3(box), pbc_c, _ptr(row_ptr),
+                                              C.byref(n_edges), _stream()))
+        n = n_edges.value
+        src = torch.empty(n, dtype=torch.int32, device="cuda")
+        dst = torch.empty(n, dtype=torch.int32, device="cuda")
+        shift = torch.empty((n, 3), dtype=torch.int8, device="cuda") if with_shift else None
+        self._check(self.lib.egnn_nlist_fill(self.ctx, _ptr(pos), n_owned, n_total, _f3(box), pbc_c, _ptr(row_ptr),
+                                             _ptr(src), _ptr(dst), _ptr(shift), _stream()))
+        return Graph(src, dst, row_ptr, shift, n_owned, n_total)
+
+    # ---- node init
+    def egnn_species_embed(self, species, table, x):
+        self._check(self.lib.egnn_species_embed(self.ctx, _ptr(species), _ptr(table), table.shape[0], _ptr(x),
+                                                x.shape[0], _stream()))
+
+    # ---- S2
+    def egnn_edge_geometry(self, graph, pos, box, want_Y=False, want_rbf=False, want_fc=False):
+        n = graph.n_edges
+        rhat_d = torch.empty((n, 4), dtype=torch.float32, device="cuda")
+        Y = torch.empty((n, self.dim), dtype=torch.float32, device="cuda") if want_Y else None
+        rbf = torch.empty((n, self.n_rbf), dtype=torch.float32, device="cuda") if want_rbf else None
+        fc = torch.empty(n, dtype=torch.float32, device="cuda") if want_fc else None
+        g = graph.desc()
+        self._check(self.lib.egnn_edge_geometry(self.ctx, C.byref(g), _ptr(pos), _f3(box), _ptr(rhat_d), _ptr(Y),
+                                                _ptr(rbf), _ptr(fc), _stream()))
+        return rhat_d, Y, rbf, fc
+
+    # ---- S3
+    def egnn_radial_weights(self, which, rhat_d, W_r1, W_r2, out=None):
+        n = rhat_d.shape[0]
+        P = self.n_paths if which == 0 else self.n_paths_readout
+        w = out if out is not None else torch.empty((n, P, self.channels), dtype=torch.float32, device="cuda")
+        self._check(self.lib.egnn_radial_weights(self.ctx, which, _ptr(rhat_d), C.c_int64(n), _ptr(W_r1), _ptr(W_r2),
+                                                 _ptr(w), _stream()))
+        return w
+
+    # ---- S4
+    def egnn_tp_segsum(self, graph, rhat_d, h, w, out=None):
+        a = out if out is not None else torch.empty((graph.n_owned, self.dim, self.channels), dtype=torch.float32,
+                                                    device="cuda")
+        g = graph.desc()
+        self._check(self.lib.egnn_tp_segsum(self.ctx, C.byref(g), _ptr(rhat_d), _ptr(h), _ptr(w), _ptr(a), _stream()))
+        return a
+
+    # ---- S5
+    def egnn_node_mix(self, x1, W1, x2=None, W2=None, out=None):
+        y = out if out is not None else torch.empty_like(x1)
+        self._check(self.lib.egnn_node_mix(self.ctx, _ptr(x1), _ptr(W1), _ptr(x2), _ptr(W2), _ptr(y), x1.shape[0],
+                                           _stream()))
+        return y
+
+    # ---- layer / readout
+    def egnn_layer_forward(self, graph, pos, box, x_in, W, ws, w_edge=None, out=None):
+        x_out = out if out is not None else torch.empty((graph.n_owned, self.dim, self.channels),
+                                                        dtype=torch.float32, device="cuda")
+        g = graph.desc()
+        self._check(self.lib.egnn_layer_forward(
+            self.ctx, C.byref(g), _ptr(pos), _f3(box), _ptr(x_in), _ptr(W["W_pre"]), _ptr(W["W_post"]),
+            _ptr(W["W_self"]), _ptr(W.get("W_r1")), _ptr(W.get("W_r2")), _ptr(w_edge), _ptr(x_out), _ptr(ws),
+            C.c_size_t(ws.numel()), _stream()))
+        return x_out
+
+    def egnn_readout_hij(self, graph, pos, box, x, W, ws, out=None):
+        H = out if out is not None else torch.empty((graph.n_edges, self.n_orb, self.n_orb), dtype=torch.float32,
+                                                    device="cuda")
+        g = graph.desc()
+        self._check(self.lib.egnn_readout_hij(
+            self.ctx, C.byref(g), _ptr(pos), _f3(box), _ptr(x), _ptr(W["W_s"]), _ptr(W["W_t"]), _ptr(W["W_r1"]),
+            _ptr(W["W_r2"]), _ptr(W["V"]), _ptr(H), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+        return H
+
+
+def to_device(d):
+    """numpy array / dict of arrays -> contiguous device tensors."""
+    if isinstance(d, dict):
+        return {k: to_device(v) for k, v in d.items()}
+    return torch.from_numpy(np.ascontiguousarray(d)).cuda()

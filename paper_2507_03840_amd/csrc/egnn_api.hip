@@ -1,0 +1,302 @@
+// Context, argument checks, workspace carving and the composite entry points of the C ABI.
+#include <math.h>
+#include <string.h>
+#include "egnn_internal.h"
+#define EGNN_GEN_HOST_TABLES
+#include "egnn_gen.inc"
+
+static thread_local std::string g_create_error;
+
+int egnn_fail(egnn_ctx* ctx, int code, const std::string& msg) {
+  if (ctx) ctx->err = msg; else g_create_error = msg;
+  return code;
+}
+
+int egnn_check_hip(egnn_ctx* ctx, hipError_t e, const char* what) {
+  return egnn_fail(ctx, EGNN_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+static const EgnnPathList* find_paths(int l_in, int l_sh, int l_out) {
+  for (int i = 0; i < egnn_n_path_lists; ++i) {
+    const EgnnPathList& p = egnn_path_lists[i];
+    if (p.l_in == l_in && p.l_sh == l_sh && p.l_out == l_out) return &p;
+  }
+  return nullptr;
+}
+
+static size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+extern "C" int egnn_create(const egnn_model_desc* d, egnn_ctx** out) {
+  if (!d || !out) return egnn_fail(nullptr, EGNN_EINVAL, "create: null pointer");
+  *out = nullptr;
+  if (d->size != sizeof(egnn_model_desc)) return egnn_fail(nullptr, EGNN_EINVAL, "create: desc.size mismatch");
+  if (d->lmax < 0 || d->lmax > 4 || d->lmax_sh != d->lmax)
+    return egnn_fail(nullptr, EGNN_EINVAL, "create: need 0 <= lmax == lmax_sh <= 4");
+  int log2E = -1;
+  for (int s = 3; s <= 7; ++s)
+    if (d->channels == (1 << s)) log2E = s;
+  if (log2E < 0) return egnn_fail(nullptr, EGNN_EINVAL, "create: channels must be 8, 16, 32, 64 or 128");
+  if (d->n_rbf < 2 || d->n_rbf > 32) return egnn_fail(nullptr, EGNN_EINVAL, "create: n_rbf must be in 2..32");
+  if (d->n_radial_hidden != EGNN_HIDDEN) return egnn_fail(nullptr, EGNN_EINVAL, "create: n_radial_hidden must be 64");
+  if (!(d->r_cut > 0.0f) || !(d->agg_norm > 0.0f)) return egnn_fail(nullptr, EGNN_EINVAL, "create: r_cut, agg_norm must be > 0");
+  if (d->n_orb_shells < 0 || d->n_orb_shells > EGNN_MAX_SHELLS)
+    return egnn_fail(nullptr, EGNN_EINVAL, "create: n_orb_shells out of range");
+  for (int s = 0; s < d->n_orb_shells; ++s)
+    if (d->orb_l[s] < 0 || d->orb_l[s] > 2) return egnn_fail(nullptr, EGNN_EINVAL, "create: orbital shells need l <= 2");
+
+  egnn_ctx* ctx = new egnn_ctx();
+  ctx->desc = *d;
+  ctx->log2_channels = log2E;
+  const int l_outs[2] = {d->lmax, EGNN_L_READOUT};
+  for (int which = 0; which < 2; ++which) {
+    const EgnnPathList* pl = find_paths(d->lmax, d->lmax_sh, l_outs[which]);
+    if (!pl || pl->n > EGNN_MAX_PATHS) {
+      delete ctx;
+      return egnn_fail(nullptr, EGNN_EINVAL, "create: no path table for this (lmax, lmax_sh)");
+    }
+    ctx->n_paths[which] = pl->n;
+    int per_l3[16] = {0};
+    for (int p = 0; p < pl->n; ++p) {
+      for (int t = 0; t < 3; ++t) ctx->paths[which][p][t] = pl->l[p][t];
+      per_l3[pl->l[p][2]]++;
+    }
+    for (int p = 0; p < pl->n; ++p) ctx->alpha[which][p] = (float)(1.0 / sqrt((double)per_l3[pl->l[p][2]]));
+  }
+
+  // readout tables
+  const int ns = d->n_orb_shells;
+  int orb_off[EGNN_MAX_SHELLS + 1] = {0};
+  for (int s = 0; s < ns; ++s) orb_off[s + 1] = orb_off[s] + 2 * d->orb_l[s] + 1;
+  ctx->n_orb = orb_off[ns];
+  for (int L = 0; L <= EGNN_L_READOUT; ++L) ctx->n_out[L] = 0;
+  for (int a = 0; a < ns; ++a)
+    for (int b = 0; b < ns; ++b)
+      for (int L = abs(d->orb_l[a] - d->orb_l[b]); L <= d->orb_l[a] + d->orb_l[b]; ++L) ctx->n_out[L]++;
+  int v_off[EGNN_L_READOUT + 2] = {0};
+  for (int L = 0; L <= EGNN_L_READOUT; ++L) v_off[L + 1] = v_off[L] + ctx->n_out[L];
+  const int nq = ctx->n_orb * ctx->n_orb;
+  std::vector<std::vector<std::pair<int, float>>> unc(nq);
+  int running[EGNN_L_READOUT + 1] = {0};
+  int qoff = 0;
+  for (int a = 0; a < ns; ++a) {
+    for (int b = 0; b < ns; ++b) {
+      const int la = d->orb_l[a], lb = d->orb_l[b];
+      for (int L = abs(la - lb); L <= la + lb; ++L) {
+        ctx->slot_L.push_back(L);
+        ctx->slot_vrow.push_back(v_off[L] + running[L]++);
+        ctx->slot_qoff.push_back(qoff);
+        const double* C = egnn_cg_values + egnn_cg_offset[la][lb][L];
+        for (int ma = 0; ma < 2 * la + 1; ++ma)
+          for (int mb = 0; mb < 2 * lb + 1; ++mb)
+            for (int M = 0; M < 2 * L + 1; ++M) {
+              const double cv = C[(ma * (2 * lb + 1) + mb) * (2 * L + 1) + M];
+              if (cv != 0.0) unc[(orb_off[a] + ma) * ctx->n_orb + orb_off[b] + mb].push_back({qoff + M, (float)cv});
+            }
+        qoff += 2 * L + 1;
+      }
+    }
+  }
+  ctx->n_slots = (int)ctx->slot_L.size();
+  ctx->unc_ptr.assign(nq + 1, 0);
+  for (int q = 0; q < nq; ++q) {
+    ctx->unc_ptr[q + 1] = ctx->unc_ptr[q] + (int)unc[q].size();
+    for (auto& e : unc[q]) {
+      ctx->unc_q.push_back(e.first);
+      ctx->unc_c.push_back(e.second);
+    }
+  }
+  *out = ctx;
+  return EGNN_OK;
+}
+
+extern "C" void egnn_destroy(egnn_ctx* ctx) { delete ctx; }
+
+extern "C" const char* egnn_last_error(const egnn_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+
+extern "C" int egnn_path_count(const egnn_ctx* ctx, int which, int32_t* n_paths, int32_t* paths) {
+  if (!ctx || !n_paths || which < 0 || which > 1) return EGNN_EINVAL;
+  *n_paths = ctx->n_paths[which];
+  if (paths)
+    for (int p = 0; p < ctx->n_paths[which]; ++p)
+      for (int t = 0; t < 3; ++t) paths[3 * p + t] = ctx->paths[which][p][t];
+  return EGNN_OK;
+}
+
+extern "C" int egnn_readout_widths(const egnn_ctx* ctx, int32_t n_out[5]) {
+  if (!ctx || !n_out) return EGNN_EINVAL;
+  for (int L = 0; L <= EGNN_L_READOUT; ++L) n_out[L] = ctx->n_out[L];
+  return EGNN_OK;
+}
+
+// ---- workspace carving -------------------------------------------------------------------------
+struct Carver {
+  char* base;
+  size_t used;
+  void* take(size_t bytes) {
+    void* p = base ? base + used : nullptr;
+    used += align256(bytes);
+    return p;
+  }
+};
+
+static size_t readout_tab_ints(const egnn_ctx* ctx) {
+  const int nq = ctx->n_orb * ctx->n_orb;
+  return (size_t)2 * nq + 2 * ctx->n_slots + nq + 1 + ctx->unc_q.size();
+}
+
+static size_t layer_ws(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, int32_t n_total, int with_w) {
+  const size_t row = (size_t)(ctx->desc.lmax + 1) * (ctx->desc.lmax + 1) * ctx->desc.channels * sizeof(float);
+  Carver c{nullptr, 0};
+  c.take((size_t)n_edges * 16);
+  c.take((size_t)n_total * row);
+  c.take((size_t)n_owned * row);
+  if (with_w) c.take((size_t)n_edges * ctx->n_paths[0] * ctx->desc.channels * sizeof(float));
+  return c.used;
+}
+
+static size_t readout_ws(const egnn_ctx* ctx, int64_t n_edges, int32_t n_total) {
+  const size_t row = (size_t)(ctx->desc.lmax + 1) * (ctx->desc.lmax + 1) * ctx->desc.channels * sizeof(float);
+  Carver c{nullptr, 0};
+  c.take((size_t)n_edges * 16);
+  c.take((size_t)n_total * row);
+  c.take((size_t)n_total * row);
+  c.take(readout_tab_ints(ctx) * sizeof(int));
+  c.take(ctx->unc_c.size() * sizeof(float));
+  c.take((size_t)n_edges * ctx->n_paths[1] * ctx->desc.channels * sizeof(float));
+  return c.used;
+}
+
+extern "C" int egnn_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, int32_t n_total,
+                                    int with_weights, size_t* bytes) {
+  if (!ctx || !bytes || n_edges < 0 || n_owned < 0 || n_total < n_owned) return EGNN_EINVAL;
+  size_t a = layer_ws(ctx, n_edges, n_owned, n_total, with_weights);
+  size_t b = ctx->n_orb > 0 ? readout_ws(ctx, n_edges, n_total) : 0;
+  *bytes = (a > b ? a : b) + 256;
+  return EGNN_OK;
+}
+
+static int check_graph(egnn_ctx* ctx, const egnn_graph* g, const char* who) {
+  if (!g) return egnn_fail(ctx, EGNN_EINVAL, std::string(who) + ": null graph");
+  if (g->n_edges < 0 || g->n_edges > 2147483647LL || g->n_owned < 0 || g->n_total < g->n_owned)
+    return egnn_fail(ctx, EGNN_EINVAL, std::string(who) + ": bad graph sizes");
+  if (!g->row_ptr || (g->n_edges > 0 && (!g->src || !g->dst)))
+    return egnn_fail(ctx, EGNN_EINVAL, std::string(who) + ": null graph arrays");
+  return EGNN_OK;
+}
+
+// ---- stage entry points ------------------------------------------------------------------------
+extern "C" int egnn_edge_geometry(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
+                                  float* rhat_d, float* Y, float* rbf, float* fc, void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  int rc = check_graph(ctx, g, "edge_geometry");
+  if (rc) return rc;
+  if (!pos || !box || !rhat_d) return egnn_fail(ctx, EGNN_EINVAL, "edge_geometry: null pointer");
+  return egnn_launch_geometry(ctx, g, pos, box, rhat_d, Y, rbf, fc, (hipStream_t)stream);
+}
+
+extern "C" int egnn_radial_weights(egnn_ctx* ctx, int which, const float* rhat_d, int64_t n_edges,
+                                   const float* W_r1, const float* W_r2, float* w, void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  if (which < 0 || which > 1 || n_edges < 0 || !rhat_d || !W_r1 || !W_r2 || !w)
+    return egnn_fail(ctx, EGNN_EINVAL, "radial_weights: bad argument");
+  return egnn_launch_radial(ctx, which, rhat_d, n_edges, W_r1, W_r2, w, (hipStream_t)stream);
+}
+
+extern "C" int egnn_tp_segsum(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, const float* h,
+                              const float* w, float* a, void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  int rc = check_graph(ctx, g, "tp_segsum");
+  if (rc) return rc;
+  if (!rhat_d || !h || !w || !a) return egnn_fail(ctx, EGNN_EINVAL, "tp_segsum: null pointer");
+  return egnn_launch_tp_segsum(ctx, g, rhat_d, h, w, a, (hipStream_t)stream);
+}
+
+extern "C" int egnn_node_mix(egnn_ctx* ctx, const float* x1, const float* W1, const float* x2, const float* W2,
+                             float* y, int32_t n_nodes, void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  if (!x1 || !W1 || !y || n_nodes < 0 || ((x2 == nullptr) != (W2 == nullptr)))
+    return egnn_fail(ctx, EGNN_EINVAL, "node_mix: bad argument");
+  return egnn_launch_node_mix(ctx, x1, W1, x2, W2, y, n_nodes, (hipStream_t)stream);
+}
+
+// ---- composite entry points ----------------------------------------------------------------------
+extern "C" int egnn_layer_forward(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
+                                  const float* x_in, const float* W_pre, const float* W_post, const float* W_self,
+                                  const float* W_r1, const float* W_r2, const float* w_edge, float* x_out,
+                                  void* ws, size_t ws_bytes, void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  int rc = check_graph(ctx, g, "layer_forward");
+  if (rc) return rc;
+  if (!pos || !box || !x_in || !W_pre || !W_post || !W_self || !x_out || !ws || (!w_edge && (!W_r1 || !W_r2)))
+    return egnn_fail(ctx, EGNN_EINVAL, "layer_forward: null pointer");
+  if (x_in == x_out) return egnn_fail(ctx, EGNN_EINVAL, "layer_forward: x_out must not alias x_in");
+  if (((uintptr_t)ws & 255) != 0) return egnn_fail(ctx, EGNN_EINVAL, "layer_forward: workspace not 256-byte aligned");
+  const int with_w = w_edge ? 0 : 1;
+  if (ws_bytes < layer_ws(ctx, g->n_edges, g->n_owned, g->n_total, with_w))
+    return egnn_fail(ctx, EGNN_EWS, "layer_forward: workspace too small");
+  hipStream_t st = (hipStream_t)stream;
+  const size_t row = (size_t)(ctx->desc.lmax + 1) * (ctx->desc.lmax + 1) * ctx->desc.channels * sizeof(float);
+  Carver c{(char*)ws, 0};
+  float* rhat_d = (float*)c.take((size_t)g->n_edges * 16);
+  float* h = (float*)c.take((size_t)g->n_total * row);
+  float* a = (float*)c.take((size_t)g->n_owned * row);
+  float* w = with_w ? (float*)c.take((size_t)g->n_edges * ctx->n_paths[0] * ctx->desc.channels * sizeof(float))
+                    : nullptr;
+  if ((rc = egnn_launch_geometry(ctx, g, pos, box, rhat_d, nullptr, nullptr, nullptr, st))) return rc;
+  if (with_w && (rc = egnn_launch_radial(ctx, 0, rhat_d, g->n_edges, W_r1, W_r2, w, st))) return rc;
+  if ((rc = egnn_launch_node_mix(ctx, x_in, W_pre, nullptr, nullptr, h, g->n_total, st))) return rc;
+  if ((rc = egnn_launch_tp_segsum(ctx, g, rhat_d, h, with_w ? w : w_edge, a, st))) return rc;
+  return egnn_launch_node_mix(ctx, a, W_post, x_in, W_self, x_out, g->n_owned, st);
+}
+
+extern "C" int egnn_readout_hij(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
+                                const float* x, const float* W_s, const float* W_t, const float* W_r1,
+                                const float* W_r2, const float* V, float* H, void* ws, size_t ws_bytes,
+                                void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  int rc = check_graph(ctx, g, "readout_hij");
+  if (rc) return rc;
+  if (ctx->n_orb <= 0 || ctx->n_orb > 32) return egnn_fail(ctx, EGNN_EINVAL, "readout_hij: need 1..32 orbitals per atom");
+  if (!pos || !box || !x || !W_s || !W_t || !W_r1 || !W_r2 || !V || !H || !ws)
+    return egnn_fail(ctx, EGNN_EINVAL, "readout_hij: null pointer");
+  if (((uintptr_t)ws & 255) != 0) return egnn_fail(ctx, EGNN_EINVAL, "readout_hij: workspace not 256-byte aligned");
+  if (ws_bytes < readout_ws(ctx, g->n_edges, g->n_total)) return egnn_fail(ctx, EGNN_EWS, "readout_hij: workspace too small");
+  hipStream_t st = (hipStream_t)stream;
+  const size_t row = (size_t)(ctx->desc.lmax + 1) * (ctx->desc.lmax + 1) * ctx->desc.channels * sizeof(float);
+  Carver c{(char*)ws, 0};
+  float* rhat_d = (float*)c.take((size_t)g->n_edges * 16);
+  float* zs = (float*)c.take((size_t)g->n_total * row);
+  float* zt = (float*)c.take((size_t)g->n_total * row);
+  int* tab_i = (int*)c.take(readout_tab_ints(ctx) * sizeof(int));
+  float* tab_f = (float*)c.take(ctx->unc_c.size() * sizeof(float));
+  float* w = (float*)c.take((size_t)g->n_edges * ctx->n_paths[1] * ctx->desc.channels * sizeof(float));
+
+  // integer table: q_row[nq] q_vrow[nq] slot_L[n_slots] slot_qoff[n_slots] unc_ptr[nq+1] unc_q[nnz]
+  const int nq = ctx->n_orb * ctx->n_orb;
+  std::vector<int> ti;
+  ti.reserve(readout_tab_ints(ctx));
+  std::vector<int> q_row(nq), q_vrow(nq);
+  for (int s = 0; s < ctx->n_slots; ++s) {
+    const int L = ctx->slot_L[s];
+    for (int M = 0; M < 2 * L + 1; ++M) {
+      q_row[ctx->slot_qoff[s] + M] = L * L + M;
+      q_vrow[ctx->slot_qoff[s] + M] = ctx->slot_vrow[s];
+    }
+  }
+  ti.insert(ti.end(), q_row.begin(), q_row.end());
+  ti.insert(ti.end(), q_vrow.begin(), q_vrow.end());
+  ti.insert(ti.end(), ctx->slot_L.begin(), ctx->slot_L.end());
+  ti.insert(ti.end(), ctx->slot_qoff.begin(), ctx->slot_qoff.end());
+  ti.insert(ti.end(), ctx->unc_ptr.begin(), ctx->unc_ptr.end());
+  ti.insert(ti.end(), ctx->unc_q.begin(), ctx->unc_q.end());
+  EGNN_HIP(ctx, hipMemcpyAsync(tab_i, ti.data(), ti.size() * sizeof(int), hipMemcpyHostToDevice, st));
+  EGNN_HIP(ctx, hipMemcpyAsync(tab_f, ctx->unc_c.data(), ctx->unc_c.size() * sizeof(float), hipMemcpyHostToDevice, st));
+  // the table copies read pageable host memory that dies with this frame
+  EGNN_HIP(ctx, hipStreamSynchronize(st));
+
+  if ((rc = egnn_launch_geometry(ctx, g, pos, box, rhat_d, nullptr, nullptr, nullptr, st))) return rc;
+  if ((rc = egnn_launch_radial(ctx, 1, rhat_d, g->n_edges, W_r1, W_r2, w, st))) return rc;
+  if ((rc = egnn_launch_node_mix(ctx, x, W_s, nullptr, nullptr, zs, g->n_total, st))) return rc;
+  if ((rc = egnn_launch_node_mix(ctx, x, W_t, nullptr, nullptr, zt, g->n_total, st))) return rc;
+  return egnn_launch_readout(ctx, g, rhat_d, zs, zt, w, V, tab_i, tab_f, H, st);
+}

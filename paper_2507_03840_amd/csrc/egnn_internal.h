@@ -1,0 +1,56 @@
+// Internal declarations shared by the translation units of libegnn_hip.so (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+#include "../../include/egnn.h"
+
+#define EGNN_MAX_PATHS 64
+#define EGNN_HIDDEN 64
+#define EGNN_L_READOUT 4
+
+struct egnn_ctx {
+  egnn_model_desc desc;
+  int n_paths[2];                        // 0: layers, 1: readout
+  int paths[2][EGNN_MAX_PATHS][3];
+  float alpha[2][EGNN_MAX_PATHS];        // 1/sqrt(#paths ending in the same l3)
+  int log2_channels;
+  // readout tables (host copies; uploaded into the workspace by egnn_readout_hij)
+  int n_orb;
+  int n_out[EGNN_L_READOUT + 1];         // rows of V per coupled degree
+  int n_slots;                           // number of (alpha, beta, L) triples
+  std::vector<int> slot_L, slot_vrow, slot_qoff;   // per slot: degree, row in packed V, offset of its 2L+1 values
+  std::vector<int> unc_ptr, unc_q;       // CSR over the n_orb^2 outputs: indices into q
+  std::vector<float> unc_c;              //   and coupling coefficients
+  std::string err;
+};
+
+struct PathAlpha { float a[EGNN_MAX_PATHS]; };
+
+int egnn_fail(egnn_ctx* ctx, int code, const std::string& msg);
+int egnn_check_hip(egnn_ctx* ctx, hipError_t e, const char* what);
+
+#define EGNN_HIP(ctx, call)                                              \
+  do {                                                                   \
+    hipError_t e__ = (call);                                             \
+    if (e__ != hipSuccess) return egnn_check_hip(ctx, e__, #call);       \
+  } while (0)
+
+#define EGNN_LAUNCH_CHECK(ctx, name)                                     \
+  do {                                                                   \
+    hipError_t e__ = hipGetLastError();                                  \
+    if (e__ != hipSuccess) return egnn_check_hip(ctx, e__, name);        \
+  } while (0)
+
+// stage launchers (one per translation unit)
+int egnn_launch_node_mix(egnn_ctx*, const float* x1, const float* W1, const float* x2, const float* W2,
+                         float* y, int n_nodes, hipStream_t);
+int egnn_launch_tp_segsum(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* h, const float* w,
+                          float* a, hipStream_t);
+int egnn_launch_radial(egnn_ctx*, int which, const float* rhat_d, int64_t n_edges, const float* W_r1,
+                       const float* W_r2, float* w, hipStream_t);
+int egnn_launch_geometry(egnn_ctx*, const egnn_graph*, const float* pos, const float box[3], float* rhat_d,
+                         float* Y, float* rbf, float* fc, hipStream_t);
+int egnn_launch_readout(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* zs, const float* zt,
+                        const float* w, const float* V, const int* tab_i, const float* tab_f, float* H, hipStream_t);

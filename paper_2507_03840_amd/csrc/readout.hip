@@ -1,0 +1,171 @@
+// S6: readout of the orbital blocks H_ij (Fig. 2(e); Sec. 2.2; Sec. 3 "Message passing", last paragraph).
+//
+// Per edge k: z = zs[src] + zt[dst] (already channel-mixed), tensor product with the harmonics of the
+// edge direction up to coupled degree 4, collapse of the channel axis by V_L (E -> 1), and the inverse
+// Clebsch-Gordan transform (Eq. 1 read backwards) from the coupled components q[o][M] to the orbital
+// block H[(a,m_a)][(b,m_b)].
+//
+// As in the message kernel the product is evaluated in the bond frame.  The collapse acts on the channel
+// axis only, so it commutes with the rotation: the E-channel result is collapsed while still in the bond
+// frame and only the n_orb^2 collapsed numbers are rotated back (one (2L+1)-vector per coupled slot).
+//
+// A group of E lanes (a "slot") works on one edge: lane = channel for the product, then the lanes share
+// the n_orb^2 collapsed outputs among themselves through LDS.
+#include "egnn_internal.h"
+#include "bond_frame.h"
+
+#define RO_ITERS 8   // edges per slot per workgroup
+#define RO_D 25      // (L_READOUT+1)^2
+
+struct ReadoutTabs {
+  const int* q_row;     // [nq]  row (L^2+L+M) of the bond-frame product feeding collapsed value t
+  const int* q_vrow;    // [nq]  row of the packed V used for it
+  const int* slot_L;    // [n_slots]
+  const int* slot_qoff; // [n_slots]
+  const int* unc_ptr;   // [nq+1]
+  const int* unc_q;     // [nnz]
+  const float* unc_c;   // [nnz]
+  int nq, n_slots, n_vrows;
+};
+
+template <int L>
+__device__ __forceinline__ void rotate_slot_back(float* q, const BondTrig& t) {
+  float v[2 * L + 1];
+#pragma unroll
+  for (int i = 0; i < 2 * L + 1; ++i) v[i] = q[i];
+  egnn_from_bond_frame_l<L>(v, t);
+#pragma unroll
+  for (int i = 0; i < 2 * L + 1; ++i) q[i] = v[i];
+}
+
+template <int LMAX>
+__global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ src, const int* __restrict__ dst,
+                                                      const float4* __restrict__ rhat_d,
+                                                      const float* __restrict__ zs, const float* __restrict__ zt,
+                                                      const float* __restrict__ w, const float* __restrict__ V,
+                                                      ReadoutTabs tb, float* __restrict__ H, long n_edges,
+                                                      int log2E) {
+  using Mid = typename ReadoutMid<LMAX>::T;
+  constexpr int D = (LMAX + 1) * (LMAX + 1);
+  constexpr int P = Mid::P;
+  extern __shared__ float smem[];
+  const int E = 1 << log2E;
+  const int tid = threadIdx.x;
+  const int c = tid & (E - 1), slot = tid >> log2E;
+  const int n_slots = 256 >> log2E;
+  const int us = E + 1;                 // padded row of su
+  const int vs = tb.n_vrows | 1;        // odd row length of sVt
+  float* sVt = smem;                                    // [E][vs]
+  float* su = sVt + (size_t)E * vs + (size_t)slot * RO_D * us;            // this slot: [25][E+1]
+  float* sq = smem + (size_t)E * vs + (size_t)n_slots * RO_D * us + (size_t)slot * tb.nq;  // this slot: [nq]
+
+  for (int i = tid; i < tb.n_vrows * E; i += 256) {
+    const int r = i >> log2E, cc = i & (E - 1);
+    sVt[cc * vs + r] = V[i];
+  }
+
+  const long k_base = (long)blockIdx.x * n_slots * RO_ITERS;
+  for (int it = 0; it < RO_ITERS; ++it) {
+    const long k = k_base + (long)it * n_slots + slot;
+    const bool live = k < n_edges;
+    BondTrig t;
+    if (live) {
+      const int s = src[k], d = dst[k];
+      const float4 g = rhat_d[k];
+      const float* zsp = zs + ((size_t)s * D << log2E) + c;
+      const float* ztp = zt + ((size_t)d * D << log2E) + c;
+      const float* wp = w + ((size_t)k * P << log2E) + c;
+      float v[D], wr[P], o[RO_D];
+#pragma unroll
+      for (int p = 0; p < P; ++p) wr[p] = wp[(size_t)p << log2E];
+#pragma unroll
+      for (int i = 0; i < D; ++i) v[i] = zsp[(size_t)i << log2E] + ztp[(size_t)i << log2E];
+      egnn_bond_trig<4>(g.x, g.y, g.z, t);
+      egnn_to_bond_frame<LMAX>(v, t);
+      Mid::run(v, wr, o);
+#pragma unroll
+      for (int i = 0; i < RO_D; ++i) su[i * us + c] = o[i];
+    }
+    __syncthreads();
+    if (live) {
+      for (int q = c; q < tb.nq; q += E) {
+        const float* ur = su + tb.q_row[q] * us;
+        const float* vr = sVt + tb.q_vrow[q];
+        float sum = 0.0f;
+        for (int cc = 0; cc < E; ++cc) sum += vr[cc * vs] * ur[cc];
+        sq[q] = sum;
+      }
+    }
+    __syncthreads();
+    if (live) {
+      for (int sl = c; sl < tb.n_slots; sl += E) {
+        float* q = sq + tb.slot_qoff[sl];
+        switch (tb.slot_L[sl]) {
+          case 1: rotate_slot_back<1>(q, t); break;
+          case 2: rotate_slot_back<2>(q, t); break;
+          case 3: rotate_slot_back<3>(q, t); break;
+          case 4: rotate_slot_back<4>(q, t); break;
+          default: break;
+        }
+      }
+    }
+    __syncthreads();
+    if (live) {
+      float* out = H + (size_t)k * tb.nq;
+      for (int q = c; q < tb.nq; q += E) {
+        float sum = 0.0f;
+        for (int n = tb.unc_ptr[q]; n < tb.unc_ptr[q + 1]; ++n) sum += tb.unc_c[n] * sq[tb.unc_q[n]];
+        out[q] = sum;
+      }
+    }
+  }
+}
+
+int egnn_launch_readout(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, const float* zs, const float* zt,
+                        const float* w, const float* V, const int* tab_i, const float* tab_f, float* H,
+                        hipStream_t stream) {
+  const long n = g->n_edges;
+  if (n == 0) return EGNN_OK;
+  const int E = ctx->desc.channels;
+  const int nq = ctx->n_orb * ctx->n_orb;
+  ReadoutTabs tb;
+  tb.nq = nq;
+  tb.n_slots = ctx->n_slots;
+  tb.n_vrows = 0;
+  for (int L = 0; L <= EGNN_L_READOUT; ++L) tb.n_vrows += ctx->n_out[L];
+  // layout of the integer table: q_row[nq] q_vrow[nq] slot_L[n_slots] slot_qoff[n_slots] unc_ptr[nq+1] unc_q[nnz]
+  tb.q_row = tab_i;
+  tb.q_vrow = tab_i + nq;
+  tb.slot_L = tab_i + 2 * nq;
+  tb.slot_qoff = tb.slot_L + ctx->n_slots;
+  tb.unc_ptr = tb.slot_qoff + ctx->n_slots;
+  tb.unc_q = tb.unc_ptr + nq + 1;
+  tb.unc_c = tab_f;
+  const int n_slots = 256 / E;
+  const int vs = tb.n_vrows | 1;
+  const size_t shmem = ((size_t)E * vs + (size_t)n_slots * RO_D * (E + 1) + (size_t)n_slots * nq) * sizeof(float);
+  const long per_wg = (long)n_slots * RO_ITERS;
+  dim3 grid((unsigned)((n + per_wg - 1) / per_wg)), block(256);
+  const float4* rd = reinterpret_cast<const float4*>(rhat_d);
+#define LAUNCH(L)                                                                                             \
+  do {                                                                                                        \
+    if (shmem > 64 * 1024) {                                                                                  \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(readout_kernel<L>),                    \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);             \
+      if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(readout_kernel)");              \
+    }                                                                                                         \
+    hipLaunchKernelGGL(readout_kernel<L>, grid, block, shmem, stream, g->src, g->dst, rd, zs, zt, w, V, tb, H, \
+                       n, ctx->log2_channels);                                                                \
+  } while (0)
+  switch (ctx->desc.lmax) {
+    case 0: LAUNCH(0); break;
+    case 1: LAUNCH(1); break;
+    case 2: LAUNCH(2); break;
+    case 3: LAUNCH(3); break;
+    case 4: LAUNCH(4); break;
+    default: return egnn_fail(ctx, EGNN_EINVAL, "readout: lmax out of range");
+  }
+#undef LAUNCH
+  EGNN_LAUNCH_CHECK(ctx, "readout_kernel");
+  return EGNN_OK;
+}

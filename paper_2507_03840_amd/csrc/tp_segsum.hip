@@ -1,0 +1,99 @@
+// S4: tensor-product messages summed over the incoming edges of every owned node.
+//
+//   a[j][(l3,m3)][c] = nbar^-1/2 * sum_{k: dst(k)=j} sum_p w[k][p][c] sum_{m1,m2} C_p[m1][m2][m3]
+//                      h[src(k)][(l1,m1)][c] Yhat_{l2,m2}(rhat_k)
+//
+// (message passing and aggregation of Sec. 3, with the coupling of Sec. 2.2 / Eq. 1 evaluated in the
+// bond-aligned frame of Sec. 2.1 / Fig. 2(d)).
+//
+// Mapping: one workgroup per destination node; a lane owns one channel of one edge "slot"
+// (256 / channels slots per workgroup), walks the node's edges with stride = #slots, and keeps the
+// (lmax+1)^2 partial sums of its channel in registers.  Both streams it reads -- the weight row
+// w[k][:][c] and the gathered source row h[src][:][c] -- are contiguous over the lanes of a slot.
+// The slots are then added in a fixed order through LDS and the node row is written once, so the
+// result does not depend on scheduling (no atomics).
+#include "egnn_internal.h"
+#include "bond_frame.h"
+
+template <int LMAX>
+__global__ __launch_bounds__(256) void tp_segsum_kernel(const int* __restrict__ row_ptr,
+                                                        const int* __restrict__ src,
+                                                        const float4* __restrict__ rhat_d,
+                                                        const float* __restrict__ h,
+                                                        const float* __restrict__ w,
+                                                        float* __restrict__ a, int n_owned, int log2E,
+                                                        int nodes_per_xcd, float scale) {
+  using Mid = typename LayerMid<LMAX>::T;
+  constexpr int D = (LMAX + 1) * (LMAX + 1);
+  constexpr int P = Mid::P;
+  __shared__ float red[256 * D];
+
+  // consecutive nodes (which share most of their sources) go to the same XCD, i.e. the same L2
+  const int j = (blockIdx.x & 7) * nodes_per_xcd + (blockIdx.x >> 3);
+  if (j >= n_owned || (int)(blockIdx.x >> 3) >= nodes_per_xcd) return;
+
+  const int E = 1 << log2E;
+  const int tid = threadIdx.x;
+  const int c = tid & (E - 1);
+  const int slot = tid >> log2E;
+  const int n_slots = 256 >> log2E;
+  const int k0 = row_ptr[j], k1 = row_ptr[j + 1];
+
+  float acc[D];
+#pragma unroll
+  for (int i = 0; i < D; ++i) acc[i] = 0.0f;
+
+  for (int k = k0 + slot; k < k1; k += n_slots) {
+    const int s = src[k];
+    const float4 g = rhat_d[k];
+    const float* hp = h + ((size_t)s * D << log2E) + c;
+    const float* wp = w + ((size_t)k * P << log2E) + c;
+    float v[D], wr[P], o[D];
+#pragma unroll
+    for (int p = 0; p < P; ++p) wr[p] = wp[(size_t)p << log2E];
+#pragma unroll
+    for (int i = 0; i < D; ++i) v[i] = hp[(size_t)i << log2E];
+    BondTrig t;
+    egnn_bond_trig<LMAX>(g.x, g.y, g.z, t);
+    egnn_to_bond_frame<LMAX>(v, t);
+    Mid::run(v, wr, o);
+    egnn_from_bond_frame<LMAX>(o, t);
+#pragma unroll
+    for (int i = 0; i < D; ++i) acc[i] += o[i];
+  }
+
+#pragma unroll
+  for (int i = 0; i < D; ++i) red[((slot * D + i) << log2E) + c] = acc[i];
+  __syncthreads();
+  const int row = D << log2E;
+  float* out = a + (size_t)j * row;
+  for (int idx = tid; idx < row; idx += 256) {
+    float sum = 0.0f;
+    for (int s = 0; s < n_slots; ++s) sum += red[s * row + idx];
+    out[idx] = sum * scale;
+  }
+}
+
+int egnn_launch_tp_segsum(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, const float* h,
+                          const float* w, float* a, hipStream_t stream) {
+  const int n = g->n_owned;
+  if (n == 0) return EGNN_OK;
+  const int per_xcd = (n + 7) / 8;
+  dim3 grid(per_xcd * 8), block(256);
+  const float scale = 1.0f / sqrtf(ctx->desc.agg_norm);
+  const float4* rd = reinterpret_cast<const float4*>(rhat_d);
+#define LAUNCH(L)                                                                                   \
+  hipLaunchKernelGGL(tp_segsum_kernel<L>, grid, block, 0, stream, g->row_ptr, g->src, rd, h, w, a, \
+                     n, ctx->log2_channels, per_xcd, scale)
+  switch (ctx->desc.lmax) {
+    case 0: LAUNCH(0); break;
+    case 1: LAUNCH(1); break;
+    case 2: LAUNCH(2); break;
+    case 3: LAUNCH(3); break;
+    case 4: LAUNCH(4); break;
+    default: return egnn_fail(ctx, EGNN_EINVAL, "tp_segsum: lmax out of range");
+  }
+#undef LAUNCH
+  EGNN_LAUNCH_CHECK(ctx, "tp_segsum_kernel");
+  return EGNN_OK;
+}

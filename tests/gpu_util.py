@@ -1,0 +1,76 @@
+"""Shared helpers of the GPU parity tests: build both sides from one seeded workload."""
+import numpy as np
+from oracle import egnn_oracle as O
+from paper_2507_03840_amd import synth
+
+TOL = 1e-4   # max|gpu - oracle| / max|oracle| per output tensor (fp32 path vs fp64 oracle)
+
+
+def rel_err(gpu, ref):
+    ref = np.asarray(ref, np.float64)
+    gpu = np.asarray(gpu, np.float64)
+    scale = np.abs(ref).max()
+    return float(np.abs(gpu - ref).max() / (scale if scale > 0 else 1.0))
+
+
+def model_weights(w, seed_offset=0):
+    """Random weights for every layer and the readout of workload w (dict of numpy arrays)."""
+    rng = np.random.default_rng([w.seed, 1000 + seed_offset])
+    P = len(O.tp_paths(w.lmax, w.lmax, w.lmax))
+    P_ro = len(O.tp_paths(w.lmax, w.lmax, O.L_READOUT))
+    _, n_out = O.readout_slots(w.orb_l)
+    layers = [synth.layer_weights(rng, w.lmax, w.channels, w.n_rbf, w.n_hidden, P) for _ in range(w.n_layers)]
+    ro = synth.readout_weights(rng, w.lmax, w.channels, w.n_rbf, w.n_hidden, P_ro, sum(n_out))
+    x0 = synth.node_features(rng, w.n_total, w.lmax, w.channels)
+    table = synth.species_table(rng, w.n_species, w.channels)
+    halo = [synth.node_features(rng, w.n_total - w.n_owned, w.lmax, w.channels) for _ in range(w.n_layers)]
+    return dict(layers=layers, readout=ro, x0=x0, table=table, halo=halo)
+
+
+def oracle_graph(w):
+    return O.neighbour_list(w.pos, w.n_owned, w.box, w.pbc, w.r_cut)
+
+
+def mean_degree(g, n_owned):
+    return float(len(g[0])) / max(1, n_owned)
+
+
+def oracle_forward(w, wt, g, agg_norm, with_readout=True):
+    """Whole model on the oracle: species embedding, n_layers layers, readout.  Returns (xs, H)."""
+    x = O.species_embed(wt["x0"], w.species, wt["table"])
+    xs = []
+    for t in range(w.n_layers):
+        y = O.layer_forward(g, w.pos, w.box, x, wt["layers"][t], w.lmax, w.lmax, w.channels, w.n_rbf, w.r_cut,
+                            agg_norm)
+        xs.append(y)
+        if t + 1 < w.n_layers:
+            x = np.concatenate([y, wt["halo"][t + 1].astype(np.float64)], axis=0)
+    H = None
+    if with_readout:
+        xr = np.concatenate([xs[-1], wt["halo"][0].astype(np.float64)], axis=0) if w.n_total > w.n_owned else xs[-1]
+        H = O.readout_hij(g, w.pos, w.box, xr, wt["readout"], w.lmax, w.lmax, w.channels, w.n_rbf, w.r_cut, w.orb_l)
+    return xs, H
+
+
+def gpu_forward(w, wt, agg_norm, with_readout=True):
+    """Same model through the C ABI.  Returns (model, graph, xs (device tensors), H)."""
+    import torch
+    from paper_2507_03840_amd import binding as B
+    m = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, agg_norm, n_layers=w.n_layers, orb_l=w.orb_l)
+    pos = B.to_device(w.pos)
+    graph = m.egnn_nlist(pos, w.n_owned, w.box, w.pbc)
+    ws = m.workspace(graph)
+    x = B.to_device(wt["x0"])
+    m.egnn_species_embed(B.to_device(w.species), B.to_device(wt["table"]), x)
+    xs = []
+    for t in range(w.n_layers):
+        y = m.egnn_layer_forward(graph, pos, w.box, x, B.to_device(wt["layers"][t]), ws)
+        xs.append(y)
+        if t + 1 < w.n_layers:
+            x = torch.cat([y, B.to_device(wt["halo"][t + 1])], dim=0).contiguous()
+    H = None
+    if with_readout:
+        xr = torch.cat([xs[-1], B.to_device(wt["halo"][0])], dim=0).contiguous() if w.n_total > w.n_owned else xs[-1]
+        H = m.egnn_readout_hij(graph, pos, w.box, xr, B.to_device(wt["readout"]), ws)
+    torch.cuda.synchronize()
+    return m, graph, xs, H
