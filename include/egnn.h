@@ -87,13 +87,14 @@ int egnn_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, 
  * Ordered pairs (i, j), i != j, j < n_owned, i < n_total, |pos_i + shift*box - pos_j| < r_cut with
  * the minimum image on periodic axes; fp64 predicate on the fp32 data; strict '<'.
  * Two phases because n_edges depends on the data: count fills row_ptr and returns n_edges (host),
- * the caller allocates src/dst/shift, fill writes them sorted by (dst, src).
+ * the caller allocates src/dst/shift (n_edges entries; may be NULL when n_edges == 0) and passes the
+ * same n_edges back, fill writes them sorted by (dst, src).
  * box, pbc: host arrays of 3.  EGNN_EBOX if a periodic edge is shorter than 2*r_cut. */
 int egnn_nlist_count(egnn_ctx* ctx, const float* pos, int32_t n_owned, int32_t n_total,
                      const float box[3], const uint8_t pbc[3], int32_t* row_ptr, int64_t* n_edges,
                      void* stream);
 int egnn_nlist_fill(egnn_ctx* ctx, const float* pos, int32_t n_owned, int32_t n_total,
-                    const float box[3], const uint8_t pbc[3], const int32_t* row_ptr,
+                    const float box[3], const uint8_t pbc[3], const int32_t* row_ptr, int64_t n_edges,
                     int32_t* src, int32_t* dst, int8_t* shift /* may be NULL */, void* stream);
 
 /* ---- node initialisation (Sec. 3: the L=0 plane carries the atomic species) ----

@@ -157,7 +157,7 @@ class Egnn:
         dst = torch.empty(n, dtype=torch.int32, device="cuda")
         shift = torch.empty((n, 3), dtype=torch.int8, device="cuda") if with_shift else None
         self._check(self.lib.egnn_nlist_fill(self.ctx, _ptr(pos), n_owned, n_total, _f3(box), pbc_c, _ptr(row_ptr),
-                                             _ptr(src), _ptr(dst), _ptr(shift), _stream()))
+                                             C.c_int64(n), _ptr(src), _ptr(dst), _ptr(shift), _stream()))
         return Graph(src, dst, row_ptr, shift, n_owned, n_total)
 
     # ---- node init

@@ -130,14 +130,15 @@ extern "C" int egnn_nlist_count(egnn_ctx* ctx, const float* pos, int32_t n_owned
 }
 
 extern "C" int egnn_nlist_fill(egnn_ctx* ctx, const float* pos, int32_t n_owned, int32_t n_total,
-                               const float box[3], const uint8_t pbc[3], const int32_t* row_ptr, int32_t* src,
-                               int32_t* dst, int8_t* shift, void* stream) {
+                               const float box[3], const uint8_t pbc[3], const int32_t* row_ptr, int64_t n_edges,
+                               int32_t* src, int32_t* dst, int8_t* shift, void* stream) {
   if (!ctx) return EGNN_EINVAL;
   NlistGeom g;
   int rc = nlist_geom(ctx, pos, n_owned, n_total, box, pbc, &g);
   if (rc) return rc;
-  if (!row_ptr || !src || !dst) return egnn_fail(ctx, EGNN_EINVAL, "nlist_fill: null pointer");
-  if (n_owned == 0) return EGNN_OK;
+  if (!row_ptr || n_edges < 0 || (n_edges > 0 && (!src || !dst)))
+    return egnn_fail(ctx, EGNN_EINVAL, "nlist_fill: null pointer");
+  if (n_owned == 0 || n_edges == 0) return EGNN_OK;
   hipLaunchKernelGGL(nlist_sweep_kernel<true>, dim3((n_owned + 3) / 4), dim3(256), 0, (hipStream_t)stream, pos,
                      n_owned, n_total, g, const_cast<int*>(row_ptr), src, dst, shift);
   EGNN_LAUNCH_CHECK(ctx, "nlist_sweep_kernel<fill>");
