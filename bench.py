@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole hot path on one MI355X.
+
+A step = neighbour list (S1) + species embedding + n_layers message-passing layers (S2-S5 each) + H_ij
+readout (S6) of one synthetic structure, all through the C ABI, inputs resident in HBM.  The headline value
+is edge-layer evaluations per second: n_edges * n_layers / step time.  The roofline object prices the
+longest-running kernel of the step; per-stage times come from HIP events recorded by the library on the
+stream the kernels run on, inside the timed region.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+FP32_MFMA_PEAK_TFLOPS = 157.3  # dense fp32 matrix peak
+
+
+def stage_model(w, n_edges, n_paths):
+    """Algorithmic bytes / flops per launch of the two heavy kernels."""
+    E, D = w.channels, (w.lmax + 1) ** 2
+    # S4: per edge the weight row (P*E floats), the gathered source row (D*E floats), indices and unit vector
+    # (24 bytes); per owned node one output row.
+    s4_bytes = n_edges * (4 * (n_paths * E + D * E) + 24) + w.n_owned * 4 * D * E
+    # S3: [n_edges x 64] x [64 x P*E] contraction plus the 64 x n_rbf first layer
+    s3_flops = n_edges * 2.0 * (w.n_rbf * 64 + 64 * n_paths * E)
+    s3_bytes = n_edges * (4 * n_paths * E + 16)
+    return s4_bytes, s3_flops, s3_bytes
+
+
+def read_traffic(kernel, workload):
+    """HBM bytes per launch measured with rocprofv3 --pmc, if a summary for this kernel/workload is committed."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch:"):
+            return float(line.split(":")[1])
+    return None
+
+
+def cpu_baseline(w, wt, g, agg, n_nodes):
+    """The oracle's layer_forward, as it stands, on the first n_nodes destination nodes of the workload."""
+    import numpy as np
+    from threadpoolctl import threadpool_limits
+    from oracle import egnn_oracle as O
+    src, dst, shift, row_ptr = g
+    k1 = int(row_ptr[n_nodes])
+    sub = (src[:k1], dst[:k1], shift[:k1], row_ptr[:n_nodes + 1])
+    x = O.species_embed(wt["x0"], w.species, wt["table"])
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        O.layer_forward(sub, w.pos, w.box, x, wt["layers"][0], w.lmax, w.lmax, w.channels, w.n_rbf, w.r_cut, agg)
+        dt = time.perf_counter() - t0
+    return dict(value=k1 / dt, unit="edge-layer evaluations/s", cores=1, kind="oracle",
+                sample=f"one layer forward into the first {n_nodes} destination nodes ({k1} edges) of the same "
+                       f"workload, {dt:.1f} s, numpy fp64, 1 thread")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-nodes", type=int, default=1024)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch a plain 1 GiB -> 1 GiB elementwise copy 3 times (reference for rocprofv3 --pmc)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2507_03840_amd import binding as B
+    from paper_2507_03840_amd import synth
+    from tests import gpu_util as U
+
+    assert torch.cuda.is_available(), "bench.py needs an MI355X"
+    B.load_library()
+    w = synth.workload(args.config, check_cutoff=False)
+    wt = U.model_weights(w)
+    pos = B.to_device(w.pos)
+    species = B.to_device(w.species)
+    table = B.to_device(wt["table"])
+    x0 = B.to_device(wt["x0"])
+    layers = [B.to_device(l) for l in wt["layers"]]
+    halo = [B.to_device(h) for h in wt["halo"]]
+    ro = B.to_device(wt["readout"])
+
+    # the mean degree (aggregation norm) comes from a first neighbour-list build
+    probe = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, 1.0, orb_l=w.orb_l)
+    g0 = probe.egnn_nlist(pos, w.n_owned, w.box, w.pbc)
+    n_edges = g0.n_edges
+    agg = n_edges / max(1, w.n_owned)
+    m = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, agg, n_layers=w.n_layers, orb_l=w.orb_l)
+    ws = m.workspace(g0)
+    x_out = [torch.empty((w.n_owned, m.dim, w.channels), dtype=torch.float32, device="cuda") for _ in range(2)]
+    H = torch.empty((n_edges, m.n_orb, m.n_orb), dtype=torch.float32, device="cuda") if w.readout else None
+    x_full = torch.empty((w.n_total, m.dim, w.channels), dtype=torch.float32, device="cuda")
+    del g0, probe
+
+    def step():
+        graph = m.egnn_nlist(pos, w.n_owned, w.box, w.pbc)
+        x_full.copy_(x0)
+        m.egnn_species_embed(species, table, x_full)
+        x = x_full
+        for t in range(w.n_layers):
+            y = m.egnn_layer_forward(graph, pos, w.box, x, layers[t], ws, out=x_out[t % 2])
+            if w.n_total > w.n_owned:
+                nxt = halo[(t + 1) % w.n_layers]
+                x_full[:w.n_owned].copy_(y)
+                x_full[w.n_owned:].copy_(nxt)
+                x = x_full
+            else:
+                x = y
+        if w.readout:
+            m.egnn_readout_hij(graph, pos, w.box, x, ro, ws, out=H)
+        return graph
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    m.egnn_timing_enable(args.steps * (w.n_layers + 1))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms, n_calls = m.egnn_timing_read()
+    m.egnn_timing_enable(0)
+
+    if args.copy_calibration:
+        a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(3):
+            torch.mul(a, 1.0, out=b)
+        torch.cuda.synchronize()
+        del a, b
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = n_edges * w.n_layers / (elapsed / args.steps)
+    layer_ms = {n: ms[i] / max(1, n_calls[0]) for i, n in enumerate(B.LAYER_STAGES)}
+    ro_ms = {n: ms[5 + i] / max(1, n_calls[1]) for i, n in enumerate(B.READOUT_STAGES)}
+
+    s4_bytes, s3_flops, s3_bytes = stage_model(w, n_edges, m.n_paths)
+    s4_t, s3_t = layer_ms["tp_segsum"] * 1e-3, layer_ms["radial_weights"] * 1e-3
+    roof_s4 = dict(kernel="tp_segsum_kernel", bound="hbm", achieved=s4_bytes / s4_t / 1e9, peak=HBM_PEAK_GBS,
+                   unit="GB/s", frac=s4_bytes / s4_t / 1e9 / HBM_PEAK_GBS,
+                   traffic=read_traffic("tp_segsum_kernel", w.name), avg_ms=layer_ms["tp_segsum"],
+                   algorithmic_bytes=s4_bytes, edges_per_s=n_edges / s4_t)
+    roof_s3 = dict(kernel="radial_weights_kernel", bound="mfma", achieved=s3_flops / s3_t / 1e12,
+                   peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=s3_flops / s3_t / 1e12 / FP32_MFMA_PEAK_TFLOPS,
+                   traffic=read_traffic("radial_weights_kernel", w.name), avg_ms=layer_ms["radial_weights"],
+                   algorithmic_flops=s3_flops, write_GBs=s3_bytes / s3_t / 1e9)
+    dominant, other = (roof_s4, roof_s3) if s4_t >= s3_t else (roof_s3, roof_s4)
+
+    out = {
+        "metric": "edges/sec per eGNN message-passing layer (fwd) + % of peak HBM GB/s on 1 GPU",
+        "value": value, "unit": "edge-layer evaluations/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"config {args.config}: {w.name}", "n_atoms_owned": w.n_owned, "n_atoms_total": w.n_total,
+                   "n_edges": n_edges, "lmax": w.lmax, "channels": w.channels, "n_rbf": w.n_rbf,
+                   "n_layers": w.n_layers, "readout": bool(w.readout), "r_cut": w.r_cut,
+                   "step": "nlist + species embed + layers fwd + H_ij readout"},
+        "roofline": dominant, "roofline_other": other,
+        "stage_ms": {"layer": layer_ms, "readout": ro_ms if w.readout else None,
+                     "layer_total": sum(layer_ms.values()),
+                     "layer_edges_per_s": n_edges / (sum(layer_ms.values()) * 1e-3)},
+    }
+    if not args.no_cpu_baseline:
+        g = U.oracle_graph(w)
+        out["cpu_baseline"] = cpu_baseline(w, wt, g, agg, min(args.cpu_nodes, w.n_owned))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -8,7 +8,8 @@
  *   - Every pointer is a DEVICE pointer unless its comment says "host".  The caller owns every
  *     buffer, including the workspace; the library allocates no device memory, keeps no pointer
  *     after a call returns, and enqueues all work on the stream passed in (a hipStream_t, passed
- *     as void*; NULL = the default stream).  Only egnn_nlist_count synchronises the stream.
+ *     as void*; NULL = the default stream).  egnn_nlist_count (edge count read-back) and
+ *     egnn_readout_hij (upload of its small index tables) synchronise the stream; nothing else does.
  *   - Node tensors: float [n_nodes][(lmax+1)^2][channels], channel fastest; the (l, m) axis is
  *     flattened as l*l + l + m, m = -l..l  (Sec. 3 "Initialization": T^node of shape
  *     (l_max+1)^2 x E per atom).
@@ -147,6 +148,18 @@ int egnn_layer_forward(egnn_ctx* ctx, const egnn_graph* g, const float* pos, con
 int egnn_readout_hij(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
                      const float* x, const float* W_s, const float* W_t, const float* W_r1,
                      const float* W_r2, const float* V, float* H, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- stage timing (measurement aid; follows the paper's protocol of timing the blocks of the forward
+ *      pass separately, Sec. 4.4 / Fig. 6(c)) ----
+ * egnn_timing_enable(ctx, max_calls > 0) creates HIP events; from then on every egnn_layer_forward /
+ * egnn_readout_hij records one event per stage on the caller's stream, for at most max_calls calls
+ * (further calls are not recorded).  max_calls = 0 turns it off.  egnn_timing_read waits for the recorded
+ * calls, sums the elapsed milliseconds per stage and clears the record:
+ *   ms[0..4]  layer:   geometry, radial weights, pre mix, tensor-product + segmented sum, post mix
+ *   ms[5..9]  readout: geometry, radial weights, source mix, destination mix, product + collapse + uncoupling
+ *   n_calls[0], n_calls[1]: recorded layer / readout calls (host arrays). */
+int egnn_timing_enable(egnn_ctx* ctx, int32_t max_calls);
+int egnn_timing_read(egnn_ctx* ctx, float ms[10], int32_t n_calls[2]);
 
 #ifdef __cplusplus
 }

@@ -16,7 +16,7 @@ SYMBOLS = [
     "egnn_create", "egnn_destroy", "egnn_last_error", "egnn_path_count", "egnn_readout_widths",
     "egnn_workspace_bytes", "egnn_nlist_count", "egnn_nlist_fill", "egnn_species_embed",
     "egnn_edge_geometry", "egnn_radial_weights", "egnn_tp_segsum", "egnn_node_mix",
-    "egnn_layer_forward", "egnn_readout_hij",
+    "egnn_layer_forward", "egnn_readout_hij", "egnn_timing_enable", "egnn_timing_read",
 ]
 
 
@@ -82,6 +82,10 @@ class Graph:
         return GraphDesc(_ptr(self.src).value, _ptr(self.dst).value, _ptr(self.row_ptr).value,
                          _ptr(self.shift).value if self.shift is not None else None,
                          self.n_edges, self.n_owned, self.n_total)
+
+
+LAYER_STAGES = ["geometry", "radial_weights", "mix_pre", "tp_segsum", "mix_post"]
+READOUT_STAGES = ["geometry", "radial_weights", "mix_src", "mix_dst", "readout"]
 
 
 class Egnn:
@@ -220,6 +224,17 @@ class Egnn:
             self.ctx, C.byref(g), _ptr(pos), _f3(box), _ptr(x), _ptr(W["W_s"]), _ptr(W["W_t"]), _ptr(W["W_r1"]),
             _ptr(W["W_r2"]), _ptr(W["V"]), _ptr(H), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
         return H
+
+
+    # ---- stage timing
+    def egnn_timing_enable(self, max_calls):
+        self._check(self.lib.egnn_timing_enable(self.ctx, int(max_calls)))
+
+    def egnn_timing_read(self):
+        ms = (C.c_float * 10)()
+        n = (C.c_int32 * 2)()
+        self._check(self.lib.egnn_timing_read(self.ctx, ms, n))
+        return list(ms), list(n)
 
 
 def to_device(d):

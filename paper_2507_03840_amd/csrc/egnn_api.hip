@@ -109,7 +109,58 @@ extern "C" int egnn_create(const egnn_model_desc* d, egnn_ctx** out) {
   return EGNN_OK;
 }
 
-extern "C" void egnn_destroy(egnn_ctx* ctx) { delete ctx; }
+extern "C" void egnn_destroy(egnn_ctx* ctx) {
+  if (!ctx) return;
+  for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
+  delete ctx;
+}
+
+// ---- stage timing ------------------------------------------------------------------------------
+StageTimer::StageTimer(egnn_ctx* c, hipStream_t s, int kind) : ctx(c), st(s), slot(-1) {
+  if (c->ev_max_calls > 0 && (int)c->ev_kind.size() < c->ev_max_calls) {
+    slot = (int)c->ev_kind.size();
+    c->ev_kind.push_back(kind);
+    (void)hipEventRecord(c->ev[(size_t)slot * (EGNN_STAGES + 1)], st);
+  }
+}
+
+void StageTimer::mark(int stage) {
+  if (slot >= 0) (void)hipEventRecord(ctx->ev[(size_t)slot * (EGNN_STAGES + 1) + stage + 1], st);
+}
+
+extern "C" int egnn_timing_enable(egnn_ctx* ctx, int32_t max_calls) {
+  if (!ctx || max_calls < 0 || max_calls > 65536) return EGNN_EINVAL;
+  for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
+  ctx->ev.clear();
+  ctx->ev_kind.clear();
+  ctx->ev_max_calls = 0;
+  for (int i = 0; i < max_calls * (EGNN_STAGES + 1); ++i) {
+    hipEvent_t e;
+    EGNN_HIP(ctx, hipEventCreate(&e));
+    ctx->ev.push_back(e);
+  }
+  ctx->ev_max_calls = max_calls;
+  return EGNN_OK;
+}
+
+extern "C" int egnn_timing_read(egnn_ctx* ctx, float ms[2 * EGNN_STAGES], int32_t n_calls[2]) {
+  if (!ctx || !ms || !n_calls) return EGNN_EINVAL;
+  for (int i = 0; i < 2 * EGNN_STAGES; ++i) ms[i] = 0.0f;
+  n_calls[0] = n_calls[1] = 0;
+  for (size_t c = 0; c < ctx->ev_kind.size(); ++c) {
+    const int kind = ctx->ev_kind[c];
+    hipEvent_t* e = &ctx->ev[c * (EGNN_STAGES + 1)];
+    EGNN_HIP(ctx, hipEventSynchronize(e[EGNN_STAGES]));
+    for (int s = 0; s < EGNN_STAGES; ++s) {
+      float t = 0.0f;
+      EGNN_HIP(ctx, hipEventElapsedTime(&t, e[s], e[s + 1]));
+      ms[kind * EGNN_STAGES + s] += t;
+    }
+    n_calls[kind]++;
+  }
+  ctx->ev_kind.clear();
+  return EGNN_OK;
+}
 
 extern "C" const char* egnn_last_error(const egnn_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
 
@@ -242,11 +293,18 @@ extern "C" int egnn_layer_forward(egnn_ctx* ctx, const egnn_graph* g, const floa
   float* a = (float*)c.take((size_t)g->n_owned * row);
   float* w = with_w ? (float*)c.take((size_t)g->n_edges * ctx->n_paths[0] * ctx->desc.channels * sizeof(float))
                     : nullptr;
+  StageTimer tm(ctx, st, 0);
   if ((rc = egnn_launch_geometry(ctx, g, pos, box, rhat_d, nullptr, nullptr, nullptr, st))) return rc;
+  tm.mark(0);
   if (with_w && (rc = egnn_launch_radial(ctx, 0, rhat_d, g->n_edges, W_r1, W_r2, w, st))) return rc;
+  tm.mark(1);
   if ((rc = egnn_launch_node_mix(ctx, x_in, W_pre, nullptr, nullptr, h, g->n_total, st))) return rc;
+  tm.mark(2);
   if ((rc = egnn_launch_tp_segsum(ctx, g, rhat_d, h, with_w ? w : w_edge, a, st))) return rc;
-  return egnn_launch_node_mix(ctx, a, W_post, x_in, W_self, x_out, g->n_owned, st);
+  tm.mark(3);
+  rc = egnn_launch_node_mix(ctx, a, W_post, x_in, W_self, x_out, g->n_owned, st);
+  tm.mark(4);
+  return rc;
 }
 
 extern "C" int egnn_readout_hij(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
@@ -294,9 +352,16 @@ extern "C" int egnn_readout_hij(egnn_ctx* ctx, const egnn_graph* g, const float*
   // the table copies read pageable host memory that dies with this frame
   EGNN_HIP(ctx, hipStreamSynchronize(st));
 
+  StageTimer tm(ctx, st, 1);
   if ((rc = egnn_launch_geometry(ctx, g, pos, box, rhat_d, nullptr, nullptr, nullptr, st))) return rc;
+  tm.mark(0);
   if ((rc = egnn_launch_radial(ctx, 1, rhat_d, g->n_edges, W_r1, W_r2, w, st))) return rc;
+  tm.mark(1);
   if ((rc = egnn_launch_node_mix(ctx, x, W_s, nullptr, nullptr, zs, g->n_total, st))) return rc;
+  tm.mark(2);
   if ((rc = egnn_launch_node_mix(ctx, x, W_t, nullptr, nullptr, zt, g->n_total, st))) return rc;
-  return egnn_launch_readout(ctx, g, rhat_d, zs, zt, w, V, tab_i, tab_f, H, st);
+  tm.mark(3);
+  rc = egnn_launch_readout(ctx, g, rhat_d, zs, zt, w, V, tab_i, tab_f, H, st);
+  tm.mark(4);
+  return rc;
 }

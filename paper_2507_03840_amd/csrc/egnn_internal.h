@@ -23,7 +23,20 @@ struct egnn_ctx {
   std::vector<int> slot_L, slot_vrow, slot_qoff;   // per slot: degree, row in packed V, offset of its 2L+1 values
   std::vector<int> unc_ptr, unc_q;       // CSR over the n_orb^2 outputs: indices into q
   std::vector<float> unc_c;              //   and coupling coefficients
+  // optional stage timing (egnn_timing_enable): EGNN_STAGES+1 events per recorded composite call
+  std::vector<hipEvent_t> ev;
+  std::vector<int> ev_kind;              // per recorded call: 0 = layer, 1 = readout
+  int ev_max_calls = 0;
   std::string err;
+};
+
+#define EGNN_STAGES 5   // stages per composite call
+
+// Records the event that closes stage `stage` (or opens the call for stage = -1) if timing is on.
+struct StageTimer {
+  egnn_ctx* ctx; hipStream_t st; int slot;
+  StageTimer(egnn_ctx* c, hipStream_t s, int kind);
+  void mark(int stage);
 };
 
 struct PathAlpha { float a[EGNN_MAX_PATHS]; };
