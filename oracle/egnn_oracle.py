@@ -356,6 +356,127 @@ def loss_mse(H, T):
 
 
 # --------------------------------------------------------------------------------------
+# O7  reverse pass (training step: "torch's computational graph constructs gradients", Sec. 4.1;
+#     here written out by hand, adjoint of each function above in reverse order)
+# --------------------------------------------------------------------------------------
+def loss_mse_backward(H, T):
+    """dL/dH for L = mean (H - T)^2."""
+    diff = np.asarray(H, F64) - np.asarray(T, F64)
+    return 2.0 * diff / diff.size
+
+
+def mix_channels_backward(x, W, dy, lmax):
+    """Adjoint of mix_channels: returns (dx, dW)."""
+    x = np.asarray(x, F64)
+    dx = np.zeros_like(x)
+    dW = np.zeros(np.shape(W), F64)
+    for l in range(lmax + 1):
+        dW[l] = np.einsum("nmd,nmc->dc", dy[:, sl(l), :], x[:, sl(l), :])
+        dx[:, sl(l), :] = np.einsum("dc,nmd->nmc", np.asarray(W[l], F64), dy[:, sl(l), :])
+    return dx, dW
+
+
+def tensor_product_backward(h, Y, w, paths, du):
+    """Adjoint of tensor_product w.r.t. the features and the weights: returns (dh, dw)."""
+    dh = np.zeros_like(h)
+    dw = np.zeros_like(w)
+    for p, (l1, l2, l3) in enumerate(paths):
+        C = cg_real(l1, l2, l3)
+        CY = np.einsum("abm,kb->kam", C, Y[:, sl(l2)])
+        t = np.einsum("kam,kmc->kac", CY, du[:, sl(l3), :])
+        dh[:, sl(l1), :] += w[:, p, None, :] * t
+        dw[:, p, :] = np.einsum("kac,kac->kc", h[:, sl(l1), :], t)
+    return dh, dw
+
+
+def radial_weights_backward(d, W_r1, W_r2, paths, channels, n_rbf, r_cut, dw):
+    """Adjoint of radial_weights w.r.t. its two matrices: returns (dW_r1, dW_r2)."""
+    W_r1, W_r2 = np.asarray(W_r1, F64), np.asarray(W_r2, F64)
+    B = radial_basis(d, n_rbf, r_cut)
+    pre = B @ W_r1.T
+    sig = 1.0 / (1.0 + np.exp(-pre))
+    g = pre * sig
+    dwl = (dw * envelope(d, r_cut)[:, None, None] * path_norm(paths)[None, :, None]).reshape(len(d), -1)
+    dW_r2 = dwl.T @ g
+    dpre = (dwl @ W_r2) * (sig * (1.0 + pre * (1.0 - sig)))
+    return dpre.T @ B, dW_r2
+
+
+def layer_backward(graph, pos, box, x_in, W, lmax, l_sh, channels, n_rbf, r_cut, agg_norm, dx_out):
+    """Adjoint of layer_forward.  Returns (dx_in [n_total rows], dict of weight gradients)."""
+    src, dst, shift, row_ptr = graph
+    x = np.asarray(x_in, F64)
+    n_owned = len(row_ptr) - 1
+    paths = tp_paths(lmax, l_sh, lmax)
+    h = mix_channels(x, W["W_pre"], lmax)
+    # forward quantities needed again: a (for dW_post)
+    fn = lambda d, k0, k1, pth: radial_weights(d, W["W_r1"], W["W_r2"], pth, channels, n_rbf, r_cut)
+    a = edge_messages_sum(graph, pos, box, h, fn, lmax, l_sh, agg_norm)
+    da, dW_post = mix_channels_backward(a, W["W_post"], dx_out, lmax)
+    dx_self, dW_self = mix_channels_backward(x[:n_owned], W["W_self"], dx_out, lmax)
+    dh = np.zeros_like(h)
+    dW_r1 = np.zeros(np.shape(W["W_r1"]), F64)
+    dW_r2 = np.zeros(np.shape(W["W_r2"]), F64)
+    step = 4096
+    for k0 in range(0, len(src), step):
+        k1 = min(len(src), k0 + step)
+        r = edge_vectors(pos, box, src[k0:k1], dst[k0:k1], shift[k0:k1])
+        d = np.sqrt(np.einsum("ka,ka->k", r, r))
+        Y = sph_harm_real(l_sh, r / d[:, None])
+        w = radial_weights(d, W["W_r1"], W["W_r2"], paths, channels, n_rbf, r_cut)
+        du = da[dst[k0:k1]] / sqrt(agg_norm)
+        dh_k, dw_k = tensor_product_backward(h[src[k0:k1]], Y, w, paths, du)
+        np.add.at(dh, src[k0:k1], dh_k)
+        g1, g2 = radial_weights_backward(d, W["W_r1"], W["W_r2"], paths, channels, n_rbf, r_cut, dw_k)
+        dW_r1 += g1
+        dW_r2 += g2
+    dx, dW_pre = mix_channels_backward(x, W["W_pre"], dh, lmax)
+    dx[:n_owned] += dx_self
+    return dx, dict(W_pre=dW_pre, W_post=dW_post, W_self=dW_self, W_r1=dW_r1, W_r2=dW_r2)
+
+
+def readout_backward(graph, pos, box, x, W, lmax, l_sh, channels, n_rbf, r_cut, orb_l, dH):
+    """Adjoint of readout_hij.  Returns (dx [n_total rows], dict of weight gradients)."""
+    src, dst, shift, row_ptr = graph
+    x = np.asarray(x, F64)
+    xs = mix_channels(x, W["W_s"], lmax)
+    xt = mix_channels(x, W["W_t"], lmax)
+    paths = tp_paths(lmax, l_sh, L_READOUT)
+    slots, n_out = readout_slots(orb_l)
+    v_off = np.concatenate([[0], np.cumsum(n_out)])
+    V = np.asarray(W["V"], F64)
+    orb_off = np.concatenate([[0], np.cumsum([2 * l + 1 for l in orb_l])])
+    dxs, dxt = np.zeros_like(xs), np.zeros_like(xt)
+    dV = np.zeros_like(V)
+    dW_r1 = np.zeros(np.shape(W["W_r1"]), F64)
+    dW_r2 = np.zeros(np.shape(W["W_r2"]), F64)
+    step = 4096
+    for k0 in range(0, len(src), step):
+        k1 = min(len(src), k0 + step)
+        r = edge_vectors(pos, box, src[k0:k1], dst[k0:k1], shift[k0:k1])
+        d = np.sqrt(np.einsum("ka,ka->k", r, r))
+        Y = sph_harm_real(l_sh, r / d[:, None])
+        w = radial_weights(d, W["W_r1"], W["W_r2"], paths, channels, n_rbf, r_cut)
+        z = xs[src[k0:k1]] + xt[dst[k0:k1]]
+        u = tensor_product(z, Y, w, paths, L_READOUT)
+        du = np.zeros_like(u)
+        for (a, b, L, o) in slots:
+            C = cg_real(orb_l[a], orb_l[b], L)
+            dq = np.einsum("abm,kab->km", C, dH[k0:k1, orb_off[a]:orb_off[a + 1], orb_off[b]:orb_off[b + 1]])
+            dV[v_off[L] + o] += np.einsum("km,kmc->c", dq, u[:, sl(L), :])
+            du[:, sl(L), :] += dq[:, :, None] * V[v_off[L] + o][None, None, :]
+        dz, dw_k = tensor_product_backward(z, Y, w, paths, du)
+        np.add.at(dxs, src[k0:k1], dz)
+        np.add.at(dxt, dst[k0:k1], dz)
+        g1, g2 = radial_weights_backward(d, W["W_r1"], W["W_r2"], paths, channels, n_rbf, r_cut, dw_k)
+        dW_r1 += g1
+        dW_r2 += g2
+    dx1, dW_s = mix_channels_backward(x, W["W_s"], dxs, lmax)
+    dx2, dW_t = mix_channels_backward(x, W["W_t"], dxt, lmax)
+    return dx1 + dx2, dict(W_s=dW_s, W_t=dW_t, W_r1=dW_r1, W_r2=dW_r2, V=dV)
+
+
+# --------------------------------------------------------------------------------------
 # test tool: Wigner-D matrices from their defining property (Sec. 2.2)
 # --------------------------------------------------------------------------------------
 def wigner_d_real(l, R, rng=None):
