@@ -149,6 +149,42 @@ int egnn_readout_hij(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const
                      const float* x, const float* W_s, const float* W_t, const float* W_r1,
                      const float* W_r2, const float* V, float* H, void* ws, size_t ws_bytes, void* stream);
 
+/* ---- S7  training step: loss and reverse pass (Sec. 4.1: gradients of the forward pass; the loss is the
+ *          mean squared error over the elements of the H blocks) ----
+ * Gradient outputs are overwritten, not accumulated.  Forward quantities are recomputed from the inputs of
+ * the call; nothing has to be saved by the caller except each layer's input x_in.  All sums over edges and
+ * nodes are taken in a fixed order (no floating-point atomics): results are bit-reproducible.
+ *
+ * egnn_graph_transpose: source-sorted index of the edge list.  col_ptr [n_total+1]; perm [n_edges] lists, for
+ * each source node i, the ids of its outgoing edges in ascending order (= ascending destination).
+ * ws: at least egnn_backward_workspace_bytes. */
+int egnn_backward_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, int32_t n_total,
+                                  size_t* bytes);
+int egnn_graph_transpose(egnn_ctx* ctx, const egnn_graph* g, int32_t* col_ptr, int32_t* perm, void* ws,
+                         size_t ws_bytes, void* stream);
+
+/* loss[0] = mean_i (H[i] - T[i])^2 over n_values entries (device scalar); if dH != NULL,
+ * dH[i] = 2 (H[i] - T[i]) / n_values.  ws: at least 8 * ceil(n_values / 4096) bytes. */
+int egnn_loss_mse(egnn_ctx* ctx, const float* H, const float* T, int64_t n_values, float* loss, float* dH,
+                  void* ws, size_t ws_bytes, void* stream);
+
+/* Adjoint of egnn_layer_forward.  dx_out [n_owned][...] is the gradient w.r.t. the layer output; dx_in
+ * [n_total][...] receives the gradient w.r.t. the layer input (halo rows included); dW_* have the shapes of
+ * the corresponding weights. */
+int egnn_layer_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm,
+                        const float* pos, const float box[3], const float* x_in, const float* W_pre,
+                        const float* W_post, const float* W_self, const float* W_r1, const float* W_r2,
+                        const float* dx_out, float* dx_in, float* dW_pre, float* dW_post, float* dW_self,
+                        float* dW_r1, float* dW_r2, void* ws, size_t ws_bytes, void* stream);
+
+/* Adjoint of egnn_readout_hij.  dH [n_edges][n_orb][n_orb]; dx [n_total][...]; dV packed like V.
+ * Synchronises the stream once (upload of its index tables). */
+int egnn_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm,
+                          const float* pos, const float box[3], const float* x, const float* W_s,
+                          const float* W_t, const float* W_r1, const float* W_r2, const float* V,
+                          const float* dH, float* dx, float* dW_s, float* dW_t, float* dW_r1, float* dW_r2,
+                          float* dV, void* ws, size_t ws_bytes, void* stream);
+
 /* ---- stage timing (measurement aid; follows the paper's protocol of timing the blocks of the forward
  *      pass separately, Sec. 4.4 / Fig. 6(c)) ----
  * egnn_timing_enable(ctx, max_calls > 0) creates HIP events; from then on every egnn_layer_forward /

@@ -17,6 +17,8 @@ SYMBOLS = [
     "egnn_workspace_bytes", "egnn_nlist_count", "egnn_nlist_fill", "egnn_species_embed",
     "egnn_edge_geometry", "egnn_radial_weights", "egnn_tp_segsum", "egnn_node_mix",
     "egnn_layer_forward", "egnn_readout_hij", "egnn_timing_enable", "egnn_timing_read",
+    "egnn_backward_workspace_bytes", "egnn_graph_transpose", "egnn_loss_mse", "egnn_layer_backward",
+    "egnn_readout_backward",
 ]
 
 
@@ -225,6 +227,54 @@ class Egnn:
             _ptr(W["W_r2"]), _ptr(W["V"]), _ptr(H), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
         return H
 
+
+    # ---- S7: loss and reverse pass
+    def egnn_backward_workspace_bytes(self, n_edges, n_owned, n_total):
+        out = C.c_size_t()
+        self._check(self.lib.egnn_backward_workspace_bytes(self.ctx, C.c_int64(n_edges), n_owned, n_total,
+                                                           C.byref(out)))
+        return out.value
+
+    def backward_workspace(self, graph):
+        nbytes = self.egnn_backward_workspace_bytes(graph.n_edges, graph.n_owned, graph.n_total)
+        return torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+
+    def egnn_graph_transpose(self, graph, ws):
+        col_ptr = torch.empty(graph.n_total + 1, dtype=torch.int32, device="cuda")
+        perm = torch.empty(graph.n_edges, dtype=torch.int32, device="cuda")
+        g = graph.desc()
+        self._check(self.lib.egnn_graph_transpose(self.ctx, C.byref(g), _ptr(col_ptr), _ptr(perm), _ptr(ws),
+                                                  C.c_size_t(ws.numel()), _stream()))
+        return col_ptr, perm
+
+    def egnn_loss_mse(self, H, T, ws, want_grad=True):
+        loss = torch.empty(1, dtype=torch.float32, device="cuda")
+        dH = torch.empty_like(H) if want_grad else None
+        self._check(self.lib.egnn_loss_mse(self.ctx, _ptr(H), _ptr(T), C.c_int64(H.numel()), _ptr(loss), _ptr(dH),
+                                           _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+        return loss, dH
+
+    def egnn_layer_backward(self, graph, col_ptr, perm, pos, box, x_in, W, dx_out, ws):
+        dx_in = torch.empty((graph.n_total, self.dim, self.channels), dtype=torch.float32, device="cuda")
+        grads = {k: torch.empty_like(W[k]) for k in ("W_pre", "W_post", "W_self", "W_r1", "W_r2")}
+        g = graph.desc()
+        self._check(self.lib.egnn_layer_backward(
+            self.ctx, C.byref(g), _ptr(col_ptr), _ptr(perm), _ptr(pos), _f3(box), _ptr(x_in), _ptr(W["W_pre"]),
+            _ptr(W["W_post"]), _ptr(W["W_self"]), _ptr(W["W_r1"]), _ptr(W["W_r2"]), _ptr(dx_out), _ptr(dx_in),
+            _ptr(grads["W_pre"]), _ptr(grads["W_post"]), _ptr(grads["W_self"]), _ptr(grads["W_r1"]),
+            _ptr(grads["W_r2"]), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+        return dx_in, grads
+
+    def egnn_readout_backward(self, graph, col_ptr, perm, pos, box, x, W, dH, ws):
+        dx = torch.empty((graph.n_total, self.dim, self.channels), dtype=torch.float32, device="cuda")
+        grads = {k: torch.empty_like(W[k]) for k in ("W_s", "W_t", "W_r1", "W_r2", "V")}
+        g = graph.desc()
+        self._check(self.lib.egnn_readout_backward(
+            self.ctx, C.byref(g), _ptr(col_ptr), _ptr(perm), _ptr(pos), _f3(box), _ptr(x), _ptr(W["W_s"]),
+            _ptr(W["W_t"]), _ptr(W["W_r1"]), _ptr(W["W_r2"]), _ptr(W["V"]), _ptr(dH), _ptr(dx), _ptr(grads["W_s"]),
+            _ptr(grads["W_t"]), _ptr(grads["W_r1"]), _ptr(grads["W_r2"]), _ptr(grads["V"]), _ptr(ws),
+            C.c_size_t(ws.numel()), _stream()))
+        return dx, grads
 
     # ---- stage timing
     def egnn_timing_enable(self, max_calls):

@@ -7,7 +7,8 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libegnn_hip.so")
-SOURCES = ["egnn_api.hip", "nlist.hip", "edge_radial.hip", "node_mix.hip", "tp_segsum.hip", "readout.hip"]
+SOURCES = ["egnn_api.hip", "egnn_api_backward.hip", "nlist.hip", "edge_radial.hip", "node_mix.hip", "tp_segsum.hip",
+           "readout.hip", "graph_util.hip", "tp_backward.hip", "radial_backward.hip", "readout_backward.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          # keep the compiler from forming packed fp32 instructions
@@ -32,7 +33,7 @@ def build(verbose=True, extra_flags=()):
         out = _run([HIPCC, *FLAGS, *extra_flags, "-c", src, "-o", obj])
         return obj, out
 
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         results = list(ex.map(compile_one, SOURCES))
     for obj, out in results:
         if verbose and out.strip():

@@ -1,0 +1,214 @@
+// Composite entry points of the reverse pass (training step): egnn_layer_backward, egnn_readout_backward.
+// Forward quantities are recomputed from the layer input rather than saved (the radial weights alone are
+// 3.4 GB per layer at 3,000 atoms; Sec. 3 "Implementation" quotes 115 GB of saved activations for that size).
+#include <math.h>
+#include "egnn_internal.h"
+
+static size_t a256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+struct Carver2 {
+  char* base;
+  size_t used;
+  void* take(size_t bytes) {
+    void* p = base ? base + used : nullptr;
+    used += a256(bytes);
+    return p;
+  }
+};
+
+static size_t row_bytes(const egnn_ctx* ctx) {
+  return (size_t)(ctx->desc.lmax + 1) * (ctx->desc.lmax + 1) * ctx->desc.channels * sizeof(float);
+}
+
+static int vrows(const egnn_ctx* ctx) {
+  int n = 0;
+  for (int L = 0; L <= EGNN_L_READOUT; ++L) n += ctx->n_out[L];
+  return n;
+}
+
+struct LayerBwdBufs {
+  float *rhat_d, *h, *a, *w, *da, *dh, *dw, *wgrad_partial;
+  void* radial;
+};
+
+static size_t carve_layer_bwd(const egnn_ctx* ctx, const egnn_graph* g, char* base, LayerBwdBufs* b) {
+  const size_t row = row_bytes(ctx);
+  const size_t wbytes = (size_t)g->n_edges * ctx->n_paths[0] * ctx->desc.channels * sizeof(float);
+  Carver2 c{base, 0};
+  b->rhat_d = (float*)c.take((size_t)g->n_edges * 16);
+  b->h = (float*)c.take((size_t)g->n_total * row);
+  b->a = (float*)c.take((size_t)g->n_owned * row);
+  b->da = (float*)c.take((size_t)g->n_owned * row);
+  b->dh = (float*)c.take((size_t)g->n_total * row);
+  b->w = (float*)c.take(wbytes);
+  b->dw = (float*)c.take(wbytes);
+  b->wgrad_partial = (float*)c.take(egnn_mix_wgrad_ws_bytes(ctx));
+  b->radial = c.take(egnn_radial_backward_ws_bytes(ctx, 0, g->n_edges));
+  return c.used;
+}
+
+struct ReadoutBwdBufs {
+  float *rhat_d, *zs, *zt, *dzs, *dzt, *w, *dw, *dz, *wgrad_partial, *dV_partial, *tab_f;
+  int* tab_i;
+  void* radial;
+};
+
+static size_t readout_bwd_tab_ints(const egnn_ctx* ctx) {
+  const int nq = ctx->n_orb * ctx->n_orb;
+  return (size_t)nq + 1 + ctx->unc_q.size() + 2 * ctx->n_slots + vrows(ctx);
+}
+
+static size_t carve_readout_bwd(const egnn_ctx* ctx, const egnn_graph* g, char* base, ReadoutBwdBufs* b) {
+  const size_t row = row_bytes(ctx);
+  const size_t wbytes = (size_t)g->n_edges * ctx->n_paths[1] * ctx->desc.channels * sizeof(float);
+  Carver2 c{base, 0};
+  b->rhat_d = (float*)c.take((size_t)g->n_edges * 16);
+  b->zs = (float*)c.take((size_t)g->n_total * row);
+  b->zt = (float*)c.take((size_t)g->n_total * row);
+  b->dzs = (float*)c.take((size_t)g->n_total * row);
+  b->dzt = (float*)c.take((size_t)g->n_total * row);
+  b->w = (float*)c.take(wbytes);
+  b->dw = (float*)c.take(wbytes);
+  b->dz = (float*)c.take((size_t)g->n_edges * row);
+  b->wgrad_partial = (float*)c.take(egnn_mix_wgrad_ws_bytes(ctx));
+  b->dV_partial = (float*)c.take(egnn_readout_backward_partial_bytes(ctx, g->n_edges));
+  b->tab_i = (int*)c.take(readout_bwd_tab_ints(ctx) * sizeof(int));
+  b->tab_f = (float*)c.take(ctx->unc_c.size() * sizeof(float));
+  b->radial = c.take(egnn_radial_backward_ws_bytes(ctx, 1, g->n_edges));
+  return c.used;
+}
+
+extern "C" int egnn_backward_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, int32_t n_total,
+                                             size_t* bytes) {
+  if (!ctx || !bytes || n_edges < 0 || n_owned < 0 || n_total < n_owned) return EGNN_EINVAL;
+  egnn_graph g = {nullptr, nullptr, nullptr, nullptr, n_edges, n_owned, n_total};
+  LayerBwdBufs lb;
+  ReadoutBwdBufs rb;
+  size_t a = carve_layer_bwd(ctx, &g, nullptr, &lb);
+  size_t b = ctx->n_orb > 0 ? carve_readout_bwd(ctx, &g, nullptr, &rb) : 0;
+  size_t c = egnn_transpose_ws_bytes(n_edges, n_total);
+  size_t m = a > b ? a : b;
+  *bytes = (m > c ? m : c) + 256;
+  return EGNN_OK;
+}
+
+static int check_bwd_graph(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm,
+                           const char* who) {
+  if (!g) return egnn_fail(ctx, EGNN_EINVAL, std::string(who) + ": null graph");
+  if (g->n_edges < 0 || g->n_edges > 2147483647LL || g->n_owned < 0 || g->n_total < g->n_owned)
+    return egnn_fail(ctx, EGNN_EINVAL, std::string(who) + ": bad graph sizes");
+  if (!g->row_ptr || !col_ptr || (g->n_edges > 0 && (!g->src || !g->dst || !perm)))
+    return egnn_fail(ctx, EGNN_EINVAL, std::string(who) + ": null graph arrays");
+  return EGNN_OK;
+}
+
+extern "C" int egnn_layer_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm,
+                                   const float* pos, const float box[3], const float* x_in, const float* W_pre,
+                                   const float* W_post, const float* W_self, const float* W_r1, const float* W_r2,
+                                   const float* dx_out, float* dx_in, float* dW_pre, float* dW_post, float* dW_self,
+                                   float* dW_r1, float* dW_r2, void* ws, size_t ws_bytes, void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  int rc = check_bwd_graph(ctx, g, col_ptr, perm, "layer_backward");
+  if (rc) return rc;
+  if (!pos || !box || !x_in || !W_pre || !W_post || !W_self || !W_r1 || !W_r2 || !dx_out || !dx_in || !dW_pre ||
+      !dW_post || !dW_self || !dW_r1 || !dW_r2 || !ws)
+    return egnn_fail(ctx, EGNN_EINVAL, "layer_backward: null pointer");
+  if (((uintptr_t)ws & 255) != 0) return egnn_fail(ctx, EGNN_EINVAL, "layer_backward: workspace not 256-byte aligned");
+  LayerBwdBufs b;
+  if (ws_bytes < carve_layer_bwd(ctx, g, nullptr, &b)) return egnn_fail(ctx, EGNN_EWS, "layer_backward: workspace too small");
+  carve_layer_bwd(ctx, g, (char*)ws, &b);
+  hipStream_t st = (hipStream_t)stream;
+  const size_t row_f = row_bytes(ctx) / sizeof(float);
+  const int n_o = g->n_owned, n_t = g->n_total;
+
+  // forward quantities
+  if ((rc = egnn_launch_geometry(ctx, g, pos, box, b.rhat_d, nullptr, nullptr, nullptr, st))) return rc;
+  if ((rc = egnn_launch_radial(ctx, 0, b.rhat_d, g->n_edges, W_r1, W_r2, b.w, st))) return rc;
+  if ((rc = egnn_launch_node_mix(ctx, x_in, W_pre, nullptr, nullptr, b.h, n_t, st))) return rc;
+  if ((rc = egnn_launch_tp_segsum(ctx, g, b.rhat_d, b.h, b.w, b.a, st))) return rc;
+  // x_out = W_post a + W_self x_in[:n_owned]
+  if ((rc = egnn_launch_node_mix(ctx, dx_out, W_post, nullptr, nullptr, b.da, n_o, st, 1))) return rc;
+  if ((rc = egnn_launch_mix_wgrad(ctx, dx_out, b.a, dW_post, b.wgrad_partial, n_o, st))) return rc;
+  if ((rc = egnn_launch_mix_wgrad(ctx, dx_out, x_in, dW_self, b.wgrad_partial, n_o, st))) return rc;
+  // messages
+  if ((rc = egnn_launch_tp_backward(ctx, g, col_ptr, perm, b.rhat_d, b.h, b.w, b.da, b.dh, b.dw, st))) return rc;
+  // h = W_pre x_in ; owned rows also receive the self term
+  if ((rc = egnn_launch_node_mix(ctx, b.dh, W_pre, dx_out, W_self, dx_in, n_o, st, 1))) return rc;
+  if (n_t > n_o &&
+      (rc = egnn_launch_node_mix(ctx, b.dh + (size_t)n_o * row_f, W_pre, nullptr, nullptr, dx_in + (size_t)n_o * row_f,
+                                 n_t - n_o, st, 1)))
+    return rc;
+  if ((rc = egnn_launch_mix_wgrad(ctx, b.dh, x_in, dW_pre, b.wgrad_partial, n_t, st))) return rc;
+  // radial MLP
+  return egnn_launch_radial_backward(ctx, 0, b.rhat_d, g->n_edges, W_r1, W_r2, b.dw, dW_r1, dW_r2, b.radial, st);
+}
+
+extern "C" int egnn_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm,
+                                     const float* pos, const float box[3], const float* x, const float* W_s,
+                                     const float* W_t, const float* W_r1, const float* W_r2, const float* V,
+                                     const float* dH, float* dx, float* dW_s, float* dW_t, float* dW_r1,
+                                     float* dW_r2, float* dV, void* ws, size_t ws_bytes, void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  int rc = check_bwd_graph(ctx, g, col_ptr, perm, "readout_backward");
+  if (rc) return rc;
+  if (ctx->n_orb <= 0 || ctx->n_orb > 32) return egnn_fail(ctx, EGNN_EINVAL, "readout_backward: need 1..32 orbitals per atom");
+  if (!pos || !box || !x || !W_s || !W_t || !W_r1 || !W_r2 || !V || !dH || !dx || !dW_s || !dW_t || !dW_r1 || !dW_r2 ||
+      !dV || !ws)
+    return egnn_fail(ctx, EGNN_EINVAL, "readout_backward: null pointer");
+  if (((uintptr_t)ws & 255) != 0) return egnn_fail(ctx, EGNN_EINVAL, "readout_backward: workspace not 256-byte aligned");
+  const int nq = ctx->n_orb * ctx->n_orb, nv = vrows(ctx), E = ctx->desc.channels;
+  if (((size_t)(256 / E) * nq + (size_t)(256 / E) * nv * E) * sizeof(float) > 160 * 1024)
+    return egnn_fail(ctx, EGNN_EINVAL, "readout_backward: orbital basis too large for the LDS tiles");
+  ReadoutBwdBufs b;
+  if (ws_bytes < carve_readout_bwd(ctx, g, nullptr, &b)) return egnn_fail(ctx, EGNN_EWS, "readout_backward: workspace too small");
+  carve_readout_bwd(ctx, g, (char*)ws, &b);
+  hipStream_t st = (hipStream_t)stream;
+  const int n_t = g->n_total;
+  const int row_len = (int)(row_bytes(ctx) / sizeof(float));
+
+  // tables: transposed uncoupling (q <- H), slots, and the q offset of every row of V
+  std::vector<std::vector<std::pair<int, float>>> byq(nq);
+  for (int hidx = 0; hidx < nq; ++hidx)
+    for (int n = ctx->unc_ptr[hidx]; n < ctx->unc_ptr[hidx + 1]; ++n) byq[ctx->unc_q[n]].push_back({hidx, ctx->unc_c[n]});
+  std::vector<int> ti;
+  std::vector<float> tf;
+  int run = 0;
+  ti.push_back(0);
+  for (int q = 0; q < nq; ++q) {
+    run += (int)byq[q].size();
+    ti.push_back(run);
+  }
+  for (int q = 0; q < nq; ++q)
+    for (auto& e : byq[q]) {
+      ti.push_back(e.first);
+      tf.push_back(e.second);
+    }
+  ti.insert(ti.end(), ctx->slot_L.begin(), ctx->slot_L.end());
+  ti.insert(ti.end(), ctx->slot_qoff.begin(), ctx->slot_qoff.end());
+  std::vector<int> vq(nv, 0);
+  for (int s = 0; s < ctx->n_slots; ++s) vq[ctx->slot_vrow[s]] = ctx->slot_qoff[s];
+  ti.insert(ti.end(), vq.begin(), vq.end());
+  EGNN_HIP(ctx, hipMemcpyAsync(b.tab_i, ti.data(), ti.size() * sizeof(int), hipMemcpyHostToDevice, st));
+  EGNN_HIP(ctx, hipMemcpyAsync(b.tab_f, tf.data(), tf.size() * sizeof(float), hipMemcpyHostToDevice, st));
+  EGNN_HIP(ctx, hipStreamSynchronize(st));   // the tables live in pageable host memory of this frame
+
+  if ((rc = egnn_launch_geometry(ctx, g, pos, box, b.rhat_d, nullptr, nullptr, nullptr, st))) return rc;
+  if ((rc = egnn_launch_radial(ctx, 1, b.rhat_d, g->n_edges, W_r1, W_r2, b.w, st))) return rc;
+  if ((rc = egnn_launch_node_mix(ctx, x, W_s, nullptr, nullptr, b.zs, n_t, st))) return rc;
+  if ((rc = egnn_launch_node_mix(ctx, x, W_t, nullptr, nullptr, b.zt, n_t, st))) return rc;
+  if ((rc = egnn_launch_readout_backward(ctx, g, b.rhat_d, b.zs, b.zt, b.w, V, b.tab_i, b.tab_f, dH, b.dz, b.dw, dV,
+                                         b.dV_partial, st)))
+    return rc;
+  // dz_k feeds the source row (zs) and the destination row (zt, owned nodes only)
+  if ((rc = egnn_launch_segsum_rows(ctx, b.dz, col_ptr, perm, b.dzs, n_t, row_len, st))) return rc;
+  if ((rc = egnn_launch_segsum_rows(ctx, b.dz, g->row_ptr, nullptr, b.dzt, g->n_owned, row_len, st))) return rc;
+  if (n_t > g->n_owned) {
+    const long tail = (long)(n_t - g->n_owned) * row_len;
+    // halo nodes are never destinations: their dzt rows are zero
+    if ((rc = egnn_launch_reduce_partials(ctx, nullptr, 0, tail, b.dzt + (size_t)g->n_owned * row_len, 1.0f, st))) return rc;
+  }
+  if ((rc = egnn_launch_node_mix(ctx, b.dzs, W_s, b.dzt, W_t, dx, n_t, st, 1))) return rc;
+  if ((rc = egnn_launch_mix_wgrad(ctx, b.dzs, x, dW_s, b.wgrad_partial, n_t, st))) return rc;
+  if ((rc = egnn_launch_mix_wgrad(ctx, b.dzt, x, dW_t, b.wgrad_partial, n_t, st))) return rc;
+  return egnn_launch_radial_backward(ctx, 1, b.rhat_d, g->n_edges, W_r1, W_r2, b.dw, dW_r1, dW_r2, b.radial, st);
+}

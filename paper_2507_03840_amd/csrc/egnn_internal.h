@@ -58,7 +58,27 @@ int egnn_check_hip(egnn_ctx* ctx, hipError_t e, const char* what);
 
 // stage launchers (one per translation unit)
 int egnn_launch_node_mix(egnn_ctx*, const float* x1, const float* W1, const float* x2, const float* W2,
-                         float* y, int n_nodes, hipStream_t);
+                         float* y, int n_nodes, hipStream_t, int transpose = 0);
+int egnn_launch_mix_wgrad(egnn_ctx*, const float* dy, const float* x, float* dW, float* partial, int n_nodes,
+                          hipStream_t);
+size_t egnn_mix_wgrad_ws_bytes(const egnn_ctx*);
+int egnn_launch_row_scan(egnn_ctx*, int* row_ptr, int n, hipStream_t);
+int egnn_launch_fill_int(egnn_ctx*, int* p, long n, int v, hipStream_t);
+int egnn_launch_segsum_rows(egnn_ctx*, const float* rows, const int* ptr, const int* perm, float* out, int n_segments,
+                            int row_len, hipStream_t);
+int egnn_launch_reduce_partials(egnn_ctx*, const float* partial, int n_partials, long n, float* out, float scale,
+                                hipStream_t);
+size_t egnn_transpose_ws_bytes(int64_t n_edges, int32_t n_total);
+int egnn_launch_tp_backward(egnn_ctx*, const egnn_graph*, const int* col_ptr, const int* perm, const float* rhat_d,
+                            const float* h, const float* w, const float* da, float* dh, float* dw, hipStream_t);
+size_t egnn_radial_backward_ws_bytes(const egnn_ctx*, int which, int64_t n_edges);
+int egnn_launch_radial_backward(egnn_ctx*, int which, const float* rhat_d, int64_t n_edges, const float* W_r1,
+                                const float* W_r2, const float* dw, float* dW_r1, float* dW_r2, void* ws,
+                                hipStream_t);
+size_t egnn_readout_backward_partial_bytes(const egnn_ctx*, int64_t n_edges);
+int egnn_launch_readout_backward(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* zs, const float* zt,
+                                 const float* w, const float* V, const int* tab_i, const float* tab_f,
+                                 const float* dH, float* dz, float* dw, float* dV, float* partial, hipStream_t);
 int egnn_launch_tp_segsum(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* h, const float* w,
                           float* a, hipStream_t);
 int egnn_launch_radial(egnn_ctx*, int which, const float* rhat_d, int64_t n_edges, const float* W_r1,

@@ -288,6 +288,32 @@ def emit_mid(l_in, l_sh, l_out, paths, groups):
     for oi in range((l_out + 1) ** 2):
         if oi not in touched:
             lines.append(f"    o[{oi}] = 0.0f;")
+    lines.append("  }")
+    # adjoint: given d(o) returns d(v) and d(w) (both overwritten)
+    lines.append("  __device__ __forceinline__ static void run_bwd(const float* v, const float* w, const float* go,")
+    lines.append("                                                 float* gv, float* gw) {")
+    tv, tw = set(), set()
+    for (l1, l3) in sorted(groups):
+        for m in sorted(groups[(l1, l3)]):
+            terms = groups[(l1, l3)][m]
+            g = " + ".join(f"{f32(k)} * w[{p}]" for p, k in terms)
+            pairs = [(l3 * l3 + l3 + mm, l1 * l1 + l1 + mm) for mm in ([m, -m] if m else [0])]
+            dg = " + ".join(f"go[{oi}] * v[{vi}]" for oi, vi in pairs)
+            lines.append(f"    {{ const float g = {g};")
+            lines.append(f"      const float dg = {dg};")
+            for oi, vi in pairs:
+                lines.append(f"      gv[{vi}] {'+=' if vi in tv else '='} g * go[{oi}];")
+                tv.add(vi)
+            for p, k in terms:
+                lines.append(f"      gw[{p}] {'+=' if p in tw else '='} {f32(k)} * dg;")
+                tw.add(p)
+            lines.append("    }")
+    for vi in range((l_in + 1) ** 2):
+        if vi not in tv:
+            lines.append(f"    gv[{vi}] = 0.0f;")
+    for p in range(len(paths)):
+        if p not in tw:
+            lines.append(f"    gw[{p}] = 0.0f;")
     lines += ["  }", "};"]
     return "\n".join(lines)
 

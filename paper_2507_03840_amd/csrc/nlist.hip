@@ -90,6 +90,12 @@ __global__ __launch_bounds__(1024) void row_scan_kernel(int* __restrict__ row_pt
   }
 }
 
+int egnn_launch_row_scan(egnn_ctx* ctx, int* row_ptr, int n, hipStream_t st) {
+  hipLaunchKernelGGL(row_scan_kernel, dim3(1), dim3(1024), 0, st, row_ptr, n);
+  EGNN_LAUNCH_CHECK(ctx, "row_scan_kernel");
+  return EGNN_OK;
+}
+
 static int nlist_geom(egnn_ctx* ctx, const float* pos, int32_t n_owned, int32_t n_total, const float box[3],
                       const uint8_t pbc[3], NlistGeom* g) {
   if (!pos || !box || !pbc || n_owned < 0 || n_total < n_owned)

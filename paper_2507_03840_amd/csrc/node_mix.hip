@@ -11,7 +11,8 @@
 
 __global__ __launch_bounds__(256) void node_mix_kernel(const float* __restrict__ x1, const float* __restrict__ W1,
                                                        const float* __restrict__ x2, const float* __restrict__ W2,
-                                                       float* __restrict__ y, int n_nodes, int lmax, int log2E) {
+                                                       float* __restrict__ y, int n_nodes, int lmax, int log2E,
+                                                       int transpose) {
   extern __shared__ float smem[];
   const int E = 1 << log2E;
   const int l = blockIdx.y;
@@ -27,9 +28,11 @@ __global__ __launch_bounds__(256) void node_mix_kernel(const float* __restrict__
   const int c = tid & (E - 1), rg = tid >> log2E;
 
   for (int i = tid; i < E * E; i += 256) {
-    const int co = i >> log2E, ci = i & (E - 1);  // W[l][co][ci]
-    sWt[ci * E + co] = W1[(size_t)l * E * E + i];
-    if (W2) sWt[E * E + ci * E + co] = W2[(size_t)l * E * E + i];
+    // forward: y[co] = sum_ci W[l][co][ci] x[ci]; transposed (reverse pass): y[co] = sum_ci W[l][ci][co] x[ci]
+    const int r = i >> log2E, q = i & (E - 1);
+    const int at = transpose ? i : q * E + r;
+    sWt[at] = W1[(size_t)l * E * E + i];
+    if (W2) sWt[E * E + at] = W2[(size_t)l * E * E + i];
   }
 
   for (int t = 0; t < MIX_TILES; ++t) {
@@ -76,7 +79,7 @@ __global__ __launch_bounds__(256) void node_mix_kernel(const float* __restrict__
 }
 
 int egnn_launch_node_mix(egnn_ctx* ctx, const float* x1, const float* W1, const float* x2, const float* W2,
-                         float* y, int n_nodes, hipStream_t stream) {
+                         float* y, int n_nodes, hipStream_t stream, int transpose) {
   if (n_nodes == 0) return EGNN_OK;
   const int E = ctx->desc.channels, lmax = ctx->desc.lmax;
   const int rows_per_tile = MIX_RPT * (256 / E);
@@ -91,9 +94,101 @@ int egnn_launch_node_mix(egnn_ctx* ctx, const float* x1, const float* W1, const 
     if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(node_mix_kernel)");
   }
   hipLaunchKernelGGL(node_mix_kernel, grid, block, shmem, stream, x1, W1, x2, W2, y, n_nodes, lmax,
-                     ctx->log2_channels);
+                     ctx->log2_channels, transpose);
   EGNN_LAUNCH_CHECK(ctx, "node_mix_kernel");
   return EGNN_OK;
+}
+
+// Weight gradient of the mix: dW[l][d][c] = sum over rows (node, m) of dy[row][d] x[row][c].
+// grid = (row chunks, degrees); each workgroup writes one partial [E][E] block; a second pass adds the
+// partials in fixed order.
+#define WG_ROWS 16
+// PT = outputs per thread = max(1, E*E/256).  A thread owns input channel c = tid % E and the output channels
+// d = tid / E + q * (256 / E), q < PT.
+template <int PT>
+__global__ __launch_bounds__(256) void mix_wgrad_kernel(const float* __restrict__ dy, const float* __restrict__ x,
+                                                        float* __restrict__ partial, int n_nodes, int lmax, int log2E,
+                                                        int nodes_per_chunk) {
+  extern __shared__ float smem[];
+  const int E = 1 << log2E;
+  const int l = blockIdx.y;
+  const int D = (lmax + 1) * (lmax + 1);
+  const int nm = 2 * l + 1;
+  float* sdy = smem;                  // [WG_ROWS][E]
+  float* sx = smem + WG_ROWS * E;     // [WG_ROWS][E]
+  const int tid = threadIdx.x;
+  const int c = tid & (E - 1), d0 = tid >> log2E, dstep = 256 >> log2E;
+  const bool active = d0 < E;         // E = 8: only the first 64 threads own an output
+  float acc[PT];
+#pragma unroll
+  for (int q = 0; q < PT; ++q) acc[q] = 0.0f;
+  const long r_begin = (long)blockIdx.x * nodes_per_chunk * nm;
+  long r_end = r_begin + (long)nodes_per_chunk * nm;
+  const long n_rows = (long)n_nodes * nm;
+  if (r_end > n_rows) r_end = n_rows;
+  for (long r0 = r_begin; r0 < r_end; r0 += WG_ROWS) {
+    __syncthreads();
+    for (int i = tid; i < WG_ROWS * E; i += 256) {
+      const int rr = i >> log2E, cc = i & (E - 1);
+      const long r = r0 + rr;
+      float a = 0.0f, b = 0.0f;
+      if (r < r_end) {
+        const long node = r / nm;
+        const int mm = (int)(r - node * nm);
+        const size_t off = (((size_t)node * D + l * l + mm) << log2E) + cc;
+        a = dy[off];
+        b = x[off];
+      }
+      sdy[i] = a;
+      sx[i] = b;
+    }
+    __syncthreads();
+    if (active) {
+      for (int rr = 0; rr < WG_ROWS; ++rr) {
+        const float xv = sx[(rr << log2E) + c];
+        const float* dr = sdy + (rr << log2E) + d0;
+#pragma unroll
+        for (int q = 0; q < PT; ++q) acc[q] += dr[q * dstep] * xv;
+      }
+    }
+  }
+  if (active) {
+    float* out = partial + ((size_t)blockIdx.x * (lmax + 1) + l) * E * E;
+#pragma unroll
+    for (int q = 0; q < PT; ++q) out[((d0 + q * dstep) << log2E) + c] = acc[q];
+  }
+}
+
+#define WGRAD_MAX_CHUNKS 256
+size_t egnn_mix_wgrad_ws_bytes(const egnn_ctx* ctx) {
+  const size_t E = ctx->desc.channels;
+  return (size_t)WGRAD_MAX_CHUNKS * (ctx->desc.lmax + 1) * E * E * sizeof(float);
+}
+
+// dW[lmax+1][E][E] = sum_rows dy (x) x; `partial` must hold egnn_mix_wgrad_ws_bytes.
+int egnn_launch_mix_wgrad(egnn_ctx* ctx, const float* dy, const float* x, float* dW, float* partial, int n_nodes,
+                          hipStream_t stream) {
+  const int E = ctx->desc.channels, lmax = ctx->desc.lmax;
+  const long n_w = (long)(lmax + 1) * E * E;
+  if (n_nodes == 0) return egnn_launch_reduce_partials(ctx, partial, 0, n_w, dW, 1.0f, stream);
+  int chunks = n_nodes < WGRAD_MAX_CHUNKS ? n_nodes : WGRAD_MAX_CHUNKS;
+  const int per = (n_nodes + chunks - 1) / chunks;
+  chunks = (n_nodes + per - 1) / per;
+  const dim3 grid(chunks, lmax + 1), block(256);
+  const size_t shmem = 2 * WG_ROWS * E * sizeof(float);
+#define LAUNCH(PT)                                                                                             \
+  hipLaunchKernelGGL(mix_wgrad_kernel<PT>, grid, block, shmem, stream, dy, x, partial, n_nodes, lmax,          \
+                     ctx->log2_channels, per)
+  switch (E) {
+    case 8: case 16: LAUNCH(1); break;
+    case 32: LAUNCH(4); break;
+    case 64: LAUNCH(16); break;
+    case 128: LAUNCH(64); break;
+    default: return egnn_fail(ctx, EGNN_EINVAL, "mix_wgrad: unsupported channel count");
+  }
+#undef LAUNCH
+  EGNN_LAUNCH_CHECK(ctx, "mix_wgrad_kernel");
+  return egnn_launch_reduce_partials(ctx, partial, chunks, n_w, dW, 1.0f, stream);
 }
 
 __global__ void species_embed_kernel(const int* __restrict__ species, const float* __restrict__ table,

@@ -1,0 +1,105 @@
+// Reverse pass of S4 (tensor-product messages + segmented sum).
+//
+// Forward, per edge k = (i -> j):  o_k = D_k^T Mid(D_k h_i ; w_k),  a_j = scale * sum_k o_k, with D_k the rotation
+// into the bond frame.  Given da (gradient w.r.t. a):
+//     go_k = scale * da_j,   (gv', gw_k) = Mid^T(D_k h_i, w_k ; D_k go_k),   dh_i = sum_{k: src(k)=i} D_k^T gv'.
+// The sum over the outgoing edges of a source is what the forward pass does not have: edges are walked in
+// source-sorted order (col_ptr / perm from egnn_graph_transpose), one workgroup per source node, partial sums
+// in registers, slots added in fixed order -- the same shape as the forward kernel, no atomics.
+// dw_k is written per edge (it feeds the radial-MLP gradients).
+#include "egnn_internal.h"
+#include "bond_frame.h"
+
+template <int LMAX>
+__global__ __launch_bounds__(256) void tp_backward_kernel(const int* __restrict__ col_ptr, const int* __restrict__ perm,
+                                                          const int* __restrict__ dst,
+                                                          const float4* __restrict__ rhat_d,
+                                                          const float* __restrict__ h, const float* __restrict__ w,
+                                                          const float* __restrict__ da, float* __restrict__ dh,
+                                                          float* __restrict__ dw, int n_total, int log2E,
+                                                          int nodes_per_xcd, float scale) {
+  using Mid = typename LayerMid<LMAX>::T;
+  constexpr int D = (LMAX + 1) * (LMAX + 1);
+  constexpr int P = Mid::P;
+  __shared__ float red[256 * D];
+
+  const int i = (blockIdx.x & 7) * nodes_per_xcd + (blockIdx.x >> 3);
+  if (i >= n_total) return;
+  const int E = 1 << log2E;
+  const int tid = threadIdx.x;
+  const int c = tid & (E - 1);
+  const int slot = tid >> log2E;
+  const int n_slots = 256 >> log2E;
+  const int c0 = col_ptr[i], c1 = col_ptr[i + 1];
+
+  float v0[D], acc[D];
+  const float* hp = h + ((size_t)i * D << log2E) + c;
+#pragma unroll
+  for (int q = 0; q < D; ++q) {
+    v0[q] = hp[(size_t)q << log2E];
+    acc[q] = 0.0f;
+  }
+
+  for (int idx = c0 + slot; idx < c1; idx += n_slots) {
+    const int k = perm[idx];
+    const int j = dst[k];
+    const float4 g = rhat_d[k];
+    const float* gp = da + ((size_t)j * D << log2E) + c;
+    const float* wp = w + ((size_t)k * P << log2E) + c;
+    float* dwp = dw + ((size_t)k * P << log2E) + c;
+    float v[D], go[D], gv[D], wr[P], gw[P];
+#pragma unroll
+    for (int p = 0; p < P; ++p) wr[p] = wp[(size_t)p << log2E];
+#pragma unroll
+    for (int q = 0; q < D; ++q) {
+      v[q] = v0[q];
+      go[q] = scale * gp[(size_t)q << log2E];
+    }
+    BondTrig t;
+    egnn_bond_trig<LMAX>(g.x, g.y, g.z, t);
+    egnn_to_bond_frame<LMAX>(v, t);
+    egnn_to_bond_frame<LMAX>(go, t);
+    Mid::run_bwd(v, wr, go, gv, gw);
+    egnn_from_bond_frame<LMAX>(gv, t);
+#pragma unroll
+    for (int q = 0; q < D; ++q) acc[q] += gv[q];
+#pragma unroll
+    for (int p = 0; p < P; ++p) dwp[(size_t)p << log2E] = gw[p];
+  }
+
+#pragma unroll
+  for (int q = 0; q < D; ++q) red[((slot * D + q) << log2E) + c] = acc[q];
+  __syncthreads();
+  const int row = D << log2E;
+  float* out = dh + (size_t)i * row;
+  for (int idx = tid; idx < row; idx += 256) {
+    float sum = 0.0f;
+    for (int s = 0; s < n_slots; ++s) sum += red[s * row + idx];
+    out[idx] = sum;
+  }
+}
+
+int egnn_launch_tp_backward(egnn_ctx* ctx, const egnn_graph* g, const int* col_ptr, const int* perm,
+                            const float* rhat_d, const float* h, const float* w, const float* da, float* dh,
+                            float* dw, hipStream_t stream) {
+  const int n = g->n_total;
+  if (n == 0) return EGNN_OK;
+  const int per_xcd = (n + 7) / 8;
+  dim3 grid(per_xcd * 8), block(256);
+  const float scale = 1.0f / sqrtf(ctx->desc.agg_norm);
+  const float4* rd = reinterpret_cast<const float4*>(rhat_d);
+#define LAUNCH(L)                                                                                              \
+  hipLaunchKernelGGL(tp_backward_kernel<L>, grid, block, 0, stream, col_ptr, perm, g->dst, rd, h, w, da, dh, dw, \
+                     n, ctx->log2_channels, per_xcd, scale)
+  switch (ctx->desc.lmax) {
+    case 0: LAUNCH(0); break;
+    case 1: LAUNCH(1); break;
+    case 2: LAUNCH(2); break;
+    case 3: LAUNCH(3); break;
+    case 4: LAUNCH(4); break;
+    default: return egnn_fail(ctx, EGNN_EINVAL, "tp_backward: lmax out of range");
+  }
+#undef LAUNCH
+  EGNN_LAUNCH_CHECK(ctx, "tp_backward_kernel");
+  return EGNN_OK;
+}

@@ -74,3 +74,69 @@ def gpu_forward(w, wt, agg_norm, with_readout=True):
         H = m.egnn_readout_hij(graph, pos, w.box, xr, B.to_device(wt["readout"]), ws)
     torch.cuda.synchronize()
     return m, graph, xs, H
+
+
+def oracle_training_step(w, wt, g, agg, T):
+    """Forward, MSE loss and reverse pass on the oracle.  Gradients keyed 'x0', 'layer{t}.{name}', 'readout.{name}'."""
+    x = O.species_embed(wt["x0"], w.species, wt["table"])
+    xs = [x]
+    for t in range(w.n_layers):
+        y = O.layer_forward(g, w.pos, w.box, xs[-1], wt["layers"][t], w.lmax, w.lmax, w.channels, w.n_rbf, w.r_cut, agg)
+        nxt = np.concatenate([y, wt["halo"][(t + 1) % w.n_layers].astype(np.float64)], axis=0) \
+            if w.n_total > w.n_owned else y
+        xs.append(nxt)
+    H = O.readout_hij(g, w.pos, w.box, xs[-1], wt["readout"], w.lmax, w.lmax, w.channels, w.n_rbf, w.r_cut, w.orb_l)
+    loss = O.loss_mse(H, T)
+    dx, g_ro = O.readout_backward(g, w.pos, w.box, xs[-1], wt["readout"], w.lmax, w.lmax, w.channels, w.n_rbf,
+                                  w.r_cut, w.orb_l, O.loss_mse_backward(H, T))
+    grads = {f"readout.{k}": v for k, v in g_ro.items()}
+    for t in reversed(range(w.n_layers)):
+        dx, g_l = O.layer_backward(g, w.pos, w.box, xs[t], wt["layers"][t], w.lmax, w.lmax, w.channels, w.n_rbf,
+                                   w.r_cut, agg, dx[:w.n_owned])
+        grads.update({f"layer{t}.{k}": v for k, v in g_l.items()})
+    grads["x0"] = dx
+    return dict(loss=loss, grads=grads)
+
+
+def gpu_training_step(w, wt, agg, T, repeats=1, timing=None):
+    """The same step through the C ABI.  Layer inputs are kept; everything else is recomputed in the reverse pass."""
+    import torch
+    from paper_2507_03840_amd import binding as B
+    m = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, agg, n_layers=w.n_layers, orb_l=w.orb_l)
+    pos = B.to_device(w.pos)
+    graph = m.egnn_nlist(pos, w.n_owned, w.box, w.pbc)
+    ws = torch.empty(max(m.egnn_backward_workspace_bytes(graph.n_edges, graph.n_owned, graph.n_total),
+                         m.egnn_workspace_bytes(graph.n_edges, graph.n_owned, graph.n_total)),
+                     dtype=torch.uint8, device="cuda")
+    col_ptr, perm = m.egnn_graph_transpose(graph, ws)
+    layers = [B.to_device(l) for l in wt["layers"]]
+    ro = B.to_device(wt["readout"])
+    Td = B.to_device(T)
+    x = B.to_device(wt["x0"])
+    m.egnn_species_embed(B.to_device(w.species), B.to_device(wt["table"]), x)
+    out = None
+    for _ in range(repeats):
+        if timing is not None:
+            torch.cuda.synchronize()
+            t0 = __import__("time").perf_counter()
+        xs = [x]
+        for t in range(w.n_layers):
+            y = m.egnn_layer_forward(graph, pos, w.box, xs[-1], layers[t], ws)
+            nxt = torch.cat([y, B.to_device(wt["halo"][(t + 1) % w.n_layers])], dim=0).contiguous() \
+                if w.n_total > w.n_owned else y
+            xs.append(nxt)
+        H = m.egnn_readout_hij(graph, pos, w.box, xs[-1], ro, ws)
+        loss, dH = m.egnn_loss_mse(H, Td, ws)
+        dx, g_ro = m.egnn_readout_backward(graph, col_ptr, perm, pos, w.box, xs[-1], ro, dH, ws)
+        grads = {f"readout.{k}": v for k, v in g_ro.items()}
+        for t in reversed(range(w.n_layers)):
+            dx, g_l = m.egnn_layer_backward(graph, col_ptr, perm, pos, w.box, xs[t], layers[t],
+                                            dx[:w.n_owned].contiguous(), ws)
+            grads.update({f"layer{t}.{k}": v for k, v in g_l.items()})
+        grads["x0"] = dx
+        torch.cuda.synchronize()
+        if timing is not None:
+            timing.append(__import__("time").perf_counter() - t0)
+        out = dict(loss=float(loss.cpu()[0]), grads={k: v.cpu().numpy() for k, v in grads.items()},
+                   n_edges=graph.n_edges)
+    return out
