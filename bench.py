@@ -72,6 +72,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-nodes", type=int, default=1024)
+    ap.add_argument("--train-steps", type=int, default=3,
+                    help="training steps (forward + loss + reverse pass, config 5) timed after the main region; 0 = skip")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain 1 GiB -> 1 GiB elementwise copy 3 times (reference for rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -140,6 +142,42 @@ def main():
     ms, n_calls = m.egnn_timing_read()
     m.egnn_timing_enable(0)
 
+    # ---- S7: training step on the same graph and model (config 5 when the workload is config 3) ----
+    training = None
+    if w.readout and args.train_steps > 0:
+        bws = torch.empty(max(m.egnn_backward_workspace_bytes(n_edges, w.n_owned, w.n_total), ws.numel()),
+                          dtype=torch.uint8, device="cuda")
+        graph = m.egnn_nlist(pos, w.n_owned, w.box, w.pbc)
+        col_ptr, perm = m.egnn_graph_transpose(graph, bws)
+        target = B.to_device(synth.normal(np.random.default_rng([w.seed, 99]), (n_edges, w.n_orb, w.n_orb)))
+
+        def train_step():
+            x_full.copy_(x0)
+            m.egnn_species_embed(species, table, x_full)
+            xs = [x_full]
+            for t in range(w.n_layers):
+                xs.append(m.egnn_layer_forward(graph, pos, w.box, xs[-1], layers[t], bws))
+            Hh = m.egnn_readout_hij(graph, pos, w.box, xs[-1], ro, bws, out=H)
+            loss, dH = m.egnn_loss_mse(Hh, target, bws)
+            dx, g_ro = m.egnn_readout_backward(graph, col_ptr, perm, pos, w.box, xs[-1], ro, dH, bws)
+            for t in reversed(range(w.n_layers)):
+                dx, g_l = m.egnn_layer_backward(graph, col_ptr, perm, pos, w.box, xs[t], layers[t],
+                                                dx[:w.n_owned], bws)
+            return loss
+
+        if w.n_total == w.n_owned:
+            train_step()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(args.train_steps):
+                loss = train_step()
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t1) / args.train_steps
+            training = dict(ms_per_step=1e3 * dt, steps=args.train_steps, loss=float(loss.cpu()[0]),
+                            edge_layer_evaluations_per_s=n_edges * w.n_layers / dt,
+                            step="layers fwd + readout + MSE + readout bwd + layers bwd (forward recomputed inside bwd)")
+        del bws
+
     if args.copy_calibration:
         a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
         b = torch.empty_like(a)
@@ -179,6 +217,7 @@ def main():
                      "layer_total": sum(layer_ms.values()),
                      "layer_edges_per_s": n_edges / (sum(layer_ms.values()) * 1e-3)},
     }
+    out["training_step"] = training
     if not args.no_cpu_baseline:
         g = U.oracle_graph(w)
         out["cpu_baseline"] = cpu_baseline(w, wt, g, agg, min(args.cpu_nodes, w.n_owned))

@@ -112,9 +112,10 @@ int egnn_edge_geometry(egnn_ctx* ctx, const egnn_graph* g, const float* pos, con
 
 /* ---- S3  radial weights ----
  * w[k][p][c] = fc(d_k) * alpha_p * (W_r2 SiLU(W_r1 B(d_k)))[p*channels + c], alpha_p = 1/sqrt(#paths
- * with the same l3).  which = 0 (layer paths) or 1 (readout paths).  W_r1 [64][n_rbf], W_r2 [P*channels][64]. */
+ * with the same l3).  which = 0 (layer paths) or 1 (readout paths).  W_r1 [64][n_rbf], W_r2 [P*channels][64].
+ * ws: scratch of at least 384 * P * channels bytes, 256-byte aligned. */
 int egnn_radial_weights(egnn_ctx* ctx, int which, const float* rhat_d, int64_t n_edges,
-                        const float* W_r1, const float* W_r2, float* w, void* stream);
+                        const float* W_r1, const float* W_r2, float* w, void* ws, size_t ws_bytes, void* stream);
 
 /* ---- S4  tensor-product messages summed over incoming edges (Sec. 3 "Message passing";
  *          Sec. 2.1, 2.2, Eq. 1 for the coupling) ----
@@ -131,8 +132,8 @@ int egnn_node_mix(egnn_ctx* ctx, const float* x1, const float* W1, const float* 
 
 /* ---- one message-passing layer, forward: S2 (if needed) -> S3 -> S5(pre) -> S4 -> S5(post) ----
  * x_out[j] = W_post a_j + W_self x_in[j] for j < n_owned, with h = W_pre x_in.  x_in has n_total rows;
- * x_out has n_owned rows and must not alias x_in.  If w_edge != NULL it is used as the radial
- * weights (W_r1, W_r2 ignored).  ws: at least egnn_workspace_bytes(...) bytes, 256-byte aligned. */
+ * x_out has n_owned rows and must not alias x_in.  If w_edge != NULL ([n_edges][P][channels]) it is used as
+ * the radial weights (W_r1, W_r2 ignored).  ws: at least egnn_workspace_bytes(...) bytes, 256-byte aligned. */
 int egnn_layer_forward(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
                        const float* x_in, const float* W_pre, const float* W_post, const float* W_self,
                        const float* W_r1, const float* W_r2, const float* w_edge, float* x_out,

@@ -188,8 +188,9 @@ class Egnn:
         n = rhat_d.shape[0]
         P = self.n_paths if which == 0 else self.n_paths_readout
         w = out if out is not None else torch.empty((n, P, self.channels), dtype=torch.float32, device="cuda")
+        ws = torch.empty(384 * P * self.channels, dtype=torch.uint8, device="cuda")
         self._check(self.lib.egnn_radial_weights(self.ctx, which, _ptr(rhat_d), C.c_int64(n), _ptr(W_r1), _ptr(W_r2),
-                                                 _ptr(w), _stream()))
+                                                 _ptr(w), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
         return w
 
     # ---- S4

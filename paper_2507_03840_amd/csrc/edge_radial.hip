@@ -4,8 +4,8 @@
 //     unit vector and length; optionally the real spherical harmonics of the direction (Sec. 2.2), the
 //     Gaussian expansion of the length (Sec. 3 "Initialization") and the cosine cutoff.
 // S3: w[k][p][c] = fc(d_k) alpha_p (W_r2 SiLU(W_r1 B(d_k)))[p*E + c] -- a dense [n_edges x 64] x [64 x P*E]
-//     contraction, done on the fp32 matrix cores (v_mfma_f32_32x32x2_f32) with the 64-wide hidden
-//     activation of 64 edges per wavefront held in registers as the A operand for the whole row.
+//     contraction on the matrix cores, with the 64-wide hidden activation of 64 edges per wavefront held in
+//     registers as the A operand for the whole row.
 #include "egnn_internal.h"
 
 // ------------------------------------------------------------------------------------------------ S2
@@ -113,33 +113,113 @@ int egnn_launch_geometry(egnn_ctx* ctx, const egnn_graph* g, const float* pos, c
 }
 
 // ------------------------------------------------------------------------------------------------ S3
+// The contraction runs on the bf16 matrix cores with fp32-level accuracy: every fp32 operand x is cut into
+// three bf16 pieces of 8 mantissa bits each (x = hi + mid + lo exactly, by truncation and exact subtraction),
+// and the six piece products whose weight is at least 2^-16 are accumulated in fp32
+// (hi*hi, hi*mid, mid*hi, mid*mid, hi*lo, lo*hi); the three dropped ones are below 2^-24 of the product.
+// Six v_mfma_f32_32x32x16_bf16 replace eight v_mfma_f32_32x32x2_f32 at 1/16 of their cost each, which moves
+// the kernel from the fp32-MFMA roofline to the rate at which w can be written.
 typedef float float16v __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-// Workgroup = 4 wavefronts, each owning 64 consecutive edges (two 32-row MFMA blocks).  Lane l serves
-// matrix row/column (l & 31) and the half hh = l >> 5 of the 64-long contraction index: the k-th
-// MFMA of a block contracts hidden units {s, 32 + s}, so a lane reads 32 consecutive floats of a W_r2
-// row.  The output block of 32 columns is contiguous along the channel/path axis of w, i.e. each
-// accumulator register is stored as two full 128-byte lines.
-__global__ __launch_bounds__(256) void radial_weights_kernel(const float4* __restrict__ rhat_d, long n_edges,
+struct Split3 { uint32_t hi, mid, lo; };   // each: a bf16 in the upper 16 bits
+
+__device__ __forceinline__ Split3 split3(float x) {
+  Split3 r;
+  r.hi = __float_as_uint(x) & 0xffff0000u;
+  const float r1 = x - __uint_as_float(r.hi);
+  r.mid = __float_as_uint(r1) & 0xffff0000u;
+  const float r2 = r1 - __uint_as_float(r.mid);
+  r.lo = __float_as_uint(r2) & 0xffff0000u;
+  return r;
+}
+
+__device__ __forceinline__ uint32_t pack2(uint32_t even, uint32_t odd) { return (even >> 16) | odd; }
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// W_r2 (times alpha_p) cut into pieces once per call: out[n][piece][64] bf16.
+__global__ __launch_bounds__(256) void split_w2_kernel(const float* __restrict__ W_r2, uint16_t* __restrict__ out,
+                                                       int PE, int log2E, PathAlpha alpha) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= PE * EGNN_HIDDEN) return;
+  const int n = i >> 6, j = i & 63;
+  const Split3 s = split3(W_r2[i] * alpha.a[n >> log2E]);
+  uint16_t* o = out + (size_t)n * 3 * EGNN_HIDDEN + j;
+  o[0] = (uint16_t)(s.hi >> 16);
+  o[EGNN_HIDDEN] = (uint16_t)(s.mid >> 16);
+  o[2 * EGNN_HIDDEN] = (uint16_t)(s.lo >> 16);
+}
+
+// Workgroup = 8 wavefronts (one per register-file slot of a CU at this kernel's register count).  Waves 0-6 each
+// own 64 consecutive edges (two 32-row MFMA blocks): lane l serves
+// matrix row/column (l & 31) and the half hh = l >> 5 of the 64-long contraction index; MFMA step t contracts
+// hidden units 32*hh + 8*t .. +7 on both operands.  Wave 7 only moves data: it copies the pieces of the next
+// 32 rows of W_r2 (12 KB, contiguous) from global memory into one of two LDS buffers.
+// Why a separate loader: the memory counter of a wave retires loads and stores in issue order, so a wave that
+// both loads its next operand and stores its results has to sit out a full HBM write round trip per block.
+// The compute waves here never wait on global memory inside the loop -- their operand comes from LDS and their
+// stores are fire-and-forget -- and the barriers carry LDS-only fences.
+// The output block of 32 columns is contiguous along the channel/path axis of w, i.e. each accumulator
+// register is stored as two full 128-byte lines.
+#define RW_COMPUTE_WAVES 7
+#define RW_THREADS ((RW_COMPUTE_WAVES + 1) * 64)
+#define RW_BROW4 25   // uint4 per staged W_r2 row: 24 of data (3 pieces x 64 bf16) + 1 of padding (bank spread)
+
+__device__ __forceinline__ void lds_release_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+}
+__device__ __forceinline__ void lds_barrier_acquire() {
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+__global__ __launch_bounds__(RW_THREADS) void radial_weights_kernel(const float4* __restrict__ rhat_d, long n_edges,
                                                              const float* __restrict__ W_r1,
-                                                             const float* __restrict__ W_r2,
+                                                             const uint16_t* __restrict__ W2s,
                                                              float* __restrict__ w, int n_rbf, int PE,
-                                                             int log2E, float r_cut, PathAlpha alpha) {
+                                                             float r_cut) {
   __shared__ float sW1[32 * EGNN_HIDDEN];  // [b][j], n_rbf <= 32
+  __shared__ uint4 sB[2][32 * RW_BROW4];
   const int tid = threadIdx.x;
-  for (int i = tid; i < n_rbf * EGNN_HIDDEN; i += 256) {
+  for (int i = tid; i < n_rbf * EGNN_HIDDEN; i += RW_THREADS) {
     const int jj = i & (EGNN_HIDDEN - 1), b = i >> 6;
     sW1[i] = W_r1[jj * n_rbf + b];
   }
   __syncthreads();
 
   const int lane = tid & 63, wave = tid >> 6;
-  const int m = lane & 31, hh = lane >> 5;
-  const long e_base = ((long)blockIdx.x * 4 + wave) * 64;
-  if (e_base >= n_edges) return;
+  const int n_blocks = (PE + 31) >> 5;
 
-  // A operand: hidden activations (times the cutoff envelope) of 2 x 32 edges, this lane's 32 units
-  float a_frag[2][32];
+  if (wave == RW_COMPUTE_WAVES) {
+    // ---- loader: block nb -> sB[nb & 1]; rows past the end repeat row 0 (their columns are never stored)
+    const uint4* src = reinterpret_cast<const uint4*>(W2s);
+    for (int nb = 0; nb < n_blocks; ++nb) {
+      uint4 v[12];
+#pragma unroll
+      for (int i = 0; i < 12; ++i) {
+        const int u = i * 64 + lane, row = u / 24, c16 = u - row * 24;
+        const int n = nb * 32 + row;
+        v[i] = src[(size_t)(n < PE ? n : 0) * 24 + c16];
+      }
+#pragma unroll
+      for (int i = 0; i < 12; ++i) {
+        const int u = i * 64 + lane, row = u / 24, c16 = u - row * 24;
+        sB[nb & 1][row * RW_BROW4 + c16] = v[i];
+      }
+      lds_release_barrier();
+    }
+    return;
+  }
+
+  const int m = lane & 31, hh = lane >> 5;
+  const long e_base = ((long)blockIdx.x * RW_COMPUTE_WAVES + wave) * 64;
+  const bool any_row = e_base < n_edges;
+  const bool all_rows = e_base + 64 <= n_edges;
+
+  // A operand: hidden activations (times the cutoff envelope) of 2 x 32 edges, this lane's 32 units, in pieces
+  uint4 a_frag[2][3][4];
   const float step = r_cut / (float)(n_rbf - 1);
   const float inv2s2 = 0.5f / (step * step);
 #pragma unroll
@@ -159,57 +239,90 @@ __global__ __launch_bounds__(256) void radial_weights_kernel(const float4* __res
     }
     const float fc = 0.5f * (1.0f + cosf(3.14159265358979323846f * d / r_cut));
 #pragma unroll
-    for (int s = 0; s < 32; ++s) a_frag[mb][s] = fc * pre[s] / (1.0f + __expf(-pre[s]));
+    for (int t = 0; t < 4; ++t) {
+      uint32_t ph[4], pm[4], pl[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float x0 = pre[8 * t + 2 * q], x1 = pre[8 * t + 2 * q + 1];
+        const Split3 s0 = split3(fc * x0 / (1.0f + __expf(-x0)));
+        const Split3 s1 = split3(fc * x1 / (1.0f + __expf(-x1)));
+        ph[q] = pack2(s0.hi, s1.hi);
+        pm[q] = pack2(s0.mid, s1.mid);
+        pl[q] = pack2(s0.lo, s1.lo);
+      }
+      a_frag[mb][0][t] = make_uint4(ph[0], ph[1], ph[2], ph[3]);
+      a_frag[mb][1][t] = make_uint4(pm[0], pm[1], pm[2], pm[3]);
+      a_frag[mb][2][t] = make_uint4(pl[0], pl[1], pl[2], pl[3]);
+    }
   }
 
-  const int n_blocks = (PE + 31) >> 5;
+  float* const out_base = w + (size_t)(e_base + 4 * hh) * PE + m;
   for (int nb = 0; nb < n_blocks; ++nb) {
-    const int n = nb * 32 + m;
-    const bool col_ok = n < PE;
-    float b_frag[32];
-    if (col_ok) {
-      const float al = alpha.a[n >> log2E];
-      const float4* row = reinterpret_cast<const float4*>(W_r2 + (size_t)n * EGNN_HIDDEN + hh * 32);
+    lds_barrier_acquire();
+    uint4 b_frag[3][4];
+    {
+      const uint4* row = sB[nb & 1] + m * RW_BROW4 + hh * 4;
 #pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        const float4 t = row[q];
-        b_frag[4 * q + 0] = t.x * al;
-        b_frag[4 * q + 1] = t.y * al;
-        b_frag[4 * q + 2] = t.z * al;
-        b_frag[4 * q + 3] = t.w * al;
-      }
-    } else {
+      for (int p = 0; p < 3; ++p)
 #pragma unroll
-      for (int s = 0; s < 32; ++s) b_frag[s] = 0.0f;
+        for (int t = 0; t < 4; ++t) b_frag[p][t] = row[p * 8 + t];
     }
     float16v acc0 = {0}, acc1 = {0};
 #pragma unroll
-    for (int s = 0; s < 32; ++s) {
-      acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a_frag[0][s], b_frag[s], acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a_frag[1][s], b_frag[s], acc1, 0, 0, 0);
-    }
-    if (col_ok) {
+    for (int t = 0; t < 4; ++t) {
+      // smallest terms first: (lo,hi) (hi,lo) (mid,mid) (mid,hi) (hi,mid) (hi,hi)
+      const int pa[6] = {2, 0, 1, 1, 0, 0};
+      const int pb[6] = {0, 2, 1, 0, 1, 0};
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int r = 8 * (i >> 2) + 4 * hh + (i & 3);
-        const long e0 = e_base + r, e1 = e_base + 32 + r;
-        if (e0 < n_edges) w[(size_t)e0 * PE + n] = acc0[i];
-        if (e1 < n_edges) w[(size_t)e1 * PE + n] = acc1[i];
+      for (int q = 0; q < 6; ++q) {
+        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a_frag[0][pa[q]][t]), as_bf16x8(b_frag[pb[q]][t]),
+                                                       acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a_frag[1][pa[q]][t]), as_bf16x8(b_frag[pb[q]][t]),
+                                                       acc1, 0, 0, 0);
+      }
+    }
+    const int n = nb * 32 + m;
+    if (n < PE) {
+      float* out = out_base + nb * 32;
+      if (all_rows) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int r = 8 * (i >> 2) + (i & 3);            // row relative to e_base + 4*hh
+          out[(size_t)r * PE] = acc0[i];
+          out[(size_t)(32 + r) * PE] = acc1[i];
+        }
+      } else if (any_row) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int r = 8 * (i >> 2) + (i & 3);
+          if (e_base + 4 * hh + r < n_edges) out[(size_t)r * PE] = acc0[i];
+          if (e_base + 4 * hh + 32 + r < n_edges) out[(size_t)(32 + r) * PE] = acc1[i];
+        }
       }
     }
   }
 }
 
+size_t egnn_radial_ws_bytes(const egnn_ctx* ctx, int which) {
+  return (size_t)ctx->n_paths[which] * ctx->desc.channels * 3 * EGNN_HIDDEN * sizeof(uint16_t);
+}
+
+// `scratch` holds egnn_radial_ws_bytes: the pieces of W_r2.
 int egnn_launch_radial(egnn_ctx* ctx, int which, const float* rhat_d, int64_t n_edges, const float* W_r1,
-                       const float* W_r2, float* w, hipStream_t stream) {
+                       const float* W_r2, float* w, void* scratch, hipStream_t stream) {
   if (n_edges == 0) return EGNN_OK;
   const int P = ctx->n_paths[which];
   const int PE = P * ctx->desc.channels;
   PathAlpha al;
   for (int p = 0; p < EGNN_MAX_PATHS; ++p) al.a[p] = p < P ? ctx->alpha[which][p] : 0.0f;
-  dim3 grid((unsigned)((n_edges + 255) / 256)), block(256);
+  uint16_t* W2s = (uint16_t*)scratch;
+  hipLaunchKernelGGL(split_w2_kernel, dim3((PE * EGNN_HIDDEN + 255) / 256), dim3(256), 0, stream, W_r2, W2s, PE,
+                     ctx->log2_channels, al);
+  EGNN_LAUNCH_CHECK(ctx, "split_w2_kernel");
+  const long per_wg = 64L * RW_COMPUTE_WAVES;
+  dim3 grid((unsigned)((n_edges + per_wg - 1) / per_wg)), block(RW_THREADS);
   hipLaunchKernelGGL(radial_weights_kernel, grid, block, 0, stream, reinterpret_cast<const float4*>(rhat_d),
-                     (long)n_edges, W_r1, W_r2, w, ctx->desc.n_rbf, PE, ctx->log2_channels, ctx->desc.r_cut, al);
+                     (long)n_edges, W_r1, W2s, w, ctx->desc.n_rbf, PE, ctx->desc.r_cut);
   EGNN_LAUNCH_CHECK(ctx, "radial_weights_kernel");
   return EGNN_OK;
 }

@@ -202,6 +202,7 @@ static size_t layer_ws(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, in
   c.take((size_t)n_total * row);
   c.take((size_t)n_owned * row);
   if (with_w) c.take((size_t)n_edges * ctx->n_paths[0] * ctx->desc.channels * sizeof(float));
+  if (with_w) c.take(egnn_radial_ws_bytes(ctx, 0));
   return c.used;
 }
 
@@ -214,6 +215,7 @@ static size_t readout_ws(const egnn_ctx* ctx, int64_t n_edges, int32_t n_total) 
   c.take(readout_tab_ints(ctx) * sizeof(int));
   c.take(ctx->unc_c.size() * sizeof(float));
   c.take((size_t)n_edges * ctx->n_paths[1] * ctx->desc.channels * sizeof(float));
+  c.take(egnn_radial_ws_bytes(ctx, 1));
   return c.used;
 }
 
@@ -246,11 +248,14 @@ extern "C" int egnn_edge_geometry(egnn_ctx* ctx, const egnn_graph* g, const floa
 }
 
 extern "C" int egnn_radial_weights(egnn_ctx* ctx, int which, const float* rhat_d, int64_t n_edges,
-                                   const float* W_r1, const float* W_r2, float* w, void* stream) {
+                                   const float* W_r1, const float* W_r2, float* w, void* ws, size_t ws_bytes,
+                                   void* stream) {
   if (!ctx) return EGNN_EINVAL;
-  if (which < 0 || which > 1 || n_edges < 0 || !rhat_d || !W_r1 || !W_r2 || !w)
+  if (which < 0 || which > 1 || n_edges < 0 || !rhat_d || !W_r1 || !W_r2 || !w || !ws)
     return egnn_fail(ctx, EGNN_EINVAL, "radial_weights: bad argument");
-  return egnn_launch_radial(ctx, which, rhat_d, n_edges, W_r1, W_r2, w, (hipStream_t)stream);
+  if (((uintptr_t)ws & 255) != 0) return egnn_fail(ctx, EGNN_EINVAL, "radial_weights: workspace not 256-byte aligned");
+  if (ws_bytes < egnn_radial_ws_bytes(ctx, which)) return egnn_fail(ctx, EGNN_EWS, "radial_weights: workspace too small");
+  return egnn_launch_radial(ctx, which, rhat_d, n_edges, W_r1, W_r2, w, ws, (hipStream_t)stream);
 }
 
 extern "C" int egnn_tp_segsum(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, const float* h,
@@ -293,10 +298,11 @@ extern "C" int egnn_layer_forward(egnn_ctx* ctx, const egnn_graph* g, const floa
   float* a = (float*)c.take((size_t)g->n_owned * row);
   float* w = with_w ? (float*)c.take((size_t)g->n_edges * ctx->n_paths[0] * ctx->desc.channels * sizeof(float))
                     : nullptr;
+  void* w2s = with_w ? c.take(egnn_radial_ws_bytes(ctx, 0)) : nullptr;
   StageTimer tm(ctx, st, 0);
   if ((rc = egnn_launch_geometry(ctx, g, pos, box, rhat_d, nullptr, nullptr, nullptr, st))) return rc;
   tm.mark(0);
-  if (with_w && (rc = egnn_launch_radial(ctx, 0, rhat_d, g->n_edges, W_r1, W_r2, w, st))) return rc;
+  if (with_w && (rc = egnn_launch_radial(ctx, 0, rhat_d, g->n_edges, W_r1, W_r2, w, w2s, st))) return rc;
   tm.mark(1);
   if ((rc = egnn_launch_node_mix(ctx, x_in, W_pre, nullptr, nullptr, h, g->n_total, st))) return rc;
   tm.mark(2);
@@ -328,6 +334,7 @@ extern "C" int egnn_readout_hij(egnn_ctx* ctx, const egnn_graph* g, const float*
   int* tab_i = (int*)c.take(readout_tab_ints(ctx) * sizeof(int));
   float* tab_f = (float*)c.take(ctx->unc_c.size() * sizeof(float));
   float* w = (float*)c.take((size_t)g->n_edges * ctx->n_paths[1] * ctx->desc.channels * sizeof(float));
+  void* w2s = c.take(egnn_radial_ws_bytes(ctx, 1));
 
   // integer table: q_row[nq] q_vrow[nq] slot_L[n_slots] slot_qoff[n_slots] unc_ptr[nq+1] unc_q[nnz]
   const int nq = ctx->n_orb * ctx->n_orb;
@@ -355,7 +362,7 @@ extern "C" int egnn_readout_hij(egnn_ctx* ctx, const egnn_graph* g, const float*
   StageTimer tm(ctx, st, 1);
   if ((rc = egnn_launch_geometry(ctx, g, pos, box, rhat_d, nullptr, nullptr, nullptr, st))) return rc;
   tm.mark(0);
-  if ((rc = egnn_launch_radial(ctx, 1, rhat_d, g->n_edges, W_r1, W_r2, w, st))) return rc;
+  if ((rc = egnn_launch_radial(ctx, 1, rhat_d, g->n_edges, W_r1, W_r2, w, w2s, st))) return rc;
   tm.mark(1);
   if ((rc = egnn_launch_node_mix(ctx, x, W_s, nullptr, nullptr, zs, g->n_total, st))) return rc;
   tm.mark(2);

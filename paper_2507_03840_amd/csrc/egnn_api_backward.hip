@@ -28,7 +28,7 @@ static int vrows(const egnn_ctx* ctx) {
 
 struct LayerBwdBufs {
   float *rhat_d, *h, *a, *w, *da, *dh, *dw, *wgrad_partial;
-  void* radial;
+  void *radial, *w2s;
 };
 
 static size_t carve_layer_bwd(const egnn_ctx* ctx, const egnn_graph* g, char* base, LayerBwdBufs* b) {
@@ -44,13 +44,14 @@ static size_t carve_layer_bwd(const egnn_ctx* ctx, const egnn_graph* g, char* ba
   b->dw = (float*)c.take(wbytes);
   b->wgrad_partial = (float*)c.take(egnn_mix_wgrad_ws_bytes(ctx));
   b->radial = c.take(egnn_radial_backward_ws_bytes(ctx, 0, g->n_edges));
+  b->w2s = c.take(egnn_radial_ws_bytes(ctx, 0));
   return c.used;
 }
 
 struct ReadoutBwdBufs {
   float *rhat_d, *zs, *zt, *dzs, *dzt, *w, *dw, *dz, *wgrad_partial, *dV_partial, *tab_f;
   int* tab_i;
-  void* radial;
+  void *radial, *w2s;
 };
 
 static size_t readout_bwd_tab_ints(const egnn_ctx* ctx) {
@@ -75,6 +76,7 @@ static size_t carve_readout_bwd(const egnn_ctx* ctx, const egnn_graph* g, char* 
   b->tab_i = (int*)c.take(readout_bwd_tab_ints(ctx) * sizeof(int));
   b->tab_f = (float*)c.take(ctx->unc_c.size() * sizeof(float));
   b->radial = c.take(egnn_radial_backward_ws_bytes(ctx, 1, g->n_edges));
+  b->w2s = c.take(egnn_radial_ws_bytes(ctx, 1));
   return c.used;
 }
 
@@ -123,7 +125,7 @@ extern "C" int egnn_layer_backward(egnn_ctx* ctx, const egnn_graph* g, const int
 
   // forward quantities
   if ((rc = egnn_launch_geometry(ctx, g, pos, box, b.rhat_d, nullptr, nullptr, nullptr, st))) return rc;
-  if ((rc = egnn_launch_radial(ctx, 0, b.rhat_d, g->n_edges, W_r1, W_r2, b.w, st))) return rc;
+  if ((rc = egnn_launch_radial(ctx, 0, b.rhat_d, g->n_edges, W_r1, W_r2, b.w, b.w2s, st))) return rc;
   if ((rc = egnn_launch_node_mix(ctx, x_in, W_pre, nullptr, nullptr, b.h, n_t, st))) return rc;
   if ((rc = egnn_launch_tp_segsum(ctx, g, b.rhat_d, b.h, b.w, b.a, st))) return rc;
   // x_out = W_post a + W_self x_in[:n_owned]
@@ -193,7 +195,7 @@ extern "C" int egnn_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const i
   EGNN_HIP(ctx, hipStreamSynchronize(st));   // the tables live in pageable host memory of this frame
 
   if ((rc = egnn_launch_geometry(ctx, g, pos, box, b.rhat_d, nullptr, nullptr, nullptr, st))) return rc;
-  if ((rc = egnn_launch_radial(ctx, 1, b.rhat_d, g->n_edges, W_r1, W_r2, b.w, st))) return rc;
+  if ((rc = egnn_launch_radial(ctx, 1, b.rhat_d, g->n_edges, W_r1, W_r2, b.w, b.w2s, st))) return rc;
   if ((rc = egnn_launch_node_mix(ctx, x, W_s, nullptr, nullptr, b.zs, n_t, st))) return rc;
   if ((rc = egnn_launch_node_mix(ctx, x, W_t, nullptr, nullptr, b.zt, n_t, st))) return rc;
   if ((rc = egnn_launch_readout_backward(ctx, g, b.rhat_d, b.zs, b.zt, b.w, V, b.tab_i, b.tab_f, dH, b.dz, b.dw, dV,

@@ -82,7 +82,8 @@ int egnn_launch_readout_backward(egnn_ctx*, const egnn_graph*, const float* rhat
 int egnn_launch_tp_segsum(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* h, const float* w,
                           float* a, hipStream_t);
 int egnn_launch_radial(egnn_ctx*, int which, const float* rhat_d, int64_t n_edges, const float* W_r1,
-                       const float* W_r2, float* w, hipStream_t);
+                       const float* W_r2, float* w, void* scratch, hipStream_t);
+size_t egnn_radial_ws_bytes(const egnn_ctx*, int which);
 int egnn_launch_geometry(egnn_ctx*, const egnn_graph*, const float* pos, const float box[3], float* rhat_d,
                          float* Y, float* rbf, float* fc, hipStream_t);
 int egnn_launch_readout(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* zs, const float* zt,

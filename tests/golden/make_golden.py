@@ -7,7 +7,7 @@ fixed random set of owned nodes, the H_ij blocks at a fixed random set of edges,
 full tensor (the scale of the relative error).  The work is spread over processes by destination-node
 chunks; each chunk goes through the oracle's own functions unchanged.
 
-    python tests/golden/make_golden.py 3 4
+    python tests/golden/make_golden.py 3 4 5
 """
 import os
 import sys
@@ -93,7 +93,111 @@ def make(index, pool_size):
     print("wrote", path, f"{os.path.getsize(path) / 1e3:.0f} kB", flush=True)
 
 
+
+
+# ------------------------------------------------------------------------------------------------------------
+# training step (config 5): loss and every gradient.  The reverse pass of the oracle is spread over processes
+# by edge chunks; each chunk goes through the oracle's own adjoint functions, partial sums are added in order.
+# ------------------------------------------------------------------------------------------------------------
+EDGE_CHUNK = 8192
+
+
+def _layer_bwd_chunk(args):
+    k0, k1 = args
+    w, g, h, W, da, agg = (_state[k] for k in ("w", "g", "h", "W", "da", "agg"))
+    src, dst, shift, row_ptr = g
+    paths = O.tp_paths(w.lmax, w.lmax, w.lmax)
+    r = O.edge_vectors(w.pos, w.box, src[k0:k1], dst[k0:k1], shift[k0:k1])
+    d = np.sqrt(np.einsum("ka,ka->k", r, r))
+    Y = O.sph_harm_real(w.lmax, r / d[:, None])
+    wk = O.radial_weights(d, W["W_r1"], W["W_r2"], paths, w.channels, w.n_rbf, w.r_cut)
+    dh_k, dw_k = O.tensor_product_backward(h[src[k0:k1]], Y, wk, paths, da[dst[k0:k1]] / np.sqrt(agg))
+    dh = np.zeros_like(h)
+    np.add.at(dh, src[k0:k1], dh_k)
+    g1, g2 = O.radial_weights_backward(d, W["W_r1"], W["W_r2"], paths, w.channels, w.n_rbf, w.r_cut, dw_k)
+    return dh, g1, g2
+
+
+def layer_backward_parallel(pool_size, w, g, x, W, agg, dx_out):
+    """Same composition as oracle.layer_backward, the edge loop split over processes."""
+    h = O.mix_channels(x, W["W_pre"], w.lmax)
+    _state.update(w=w, g=g, h=h, W=W, agg=agg)
+    a = np.zeros((w.n_owned, (w.lmax + 1) ** 2, w.channels))
+    jobs = [(j0, min(w.n_owned, j0 + CHUNK)) for j0 in range(0, w.n_owned, CHUNK)]
+    with ProcessPoolExecutor(pool_size) as ex:
+        for j0, part in ex.map(_messages_chunk, jobs):
+            a[j0:j0 + part.shape[0]] = part
+    da, dW_post = O.mix_channels_backward(a, W["W_post"], dx_out, w.lmax)
+    dx_self, dW_self = O.mix_channels_backward(x[:w.n_owned], W["W_self"], dx_out, w.lmax)
+    _state.update(da=da)
+    dh = np.zeros_like(h)
+    dW_r1 = np.zeros(np.shape(W["W_r1"]))
+    dW_r2 = np.zeros(np.shape(W["W_r2"]))
+    n_e = len(g[0])
+    with ProcessPoolExecutor(pool_size) as ex:
+        for p_dh, g1, g2 in ex.map(_layer_bwd_chunk, [(k, min(n_e, k + EDGE_CHUNK)) for k in range(0, n_e, EDGE_CHUNK)]):
+            dh += p_dh
+            dW_r1 += g1
+            dW_r2 += g2
+    dx, dW_pre = O.mix_channels_backward(x, W["W_pre"], dh, w.lmax)
+    dx[:w.n_owned] += dx_self
+    return dx, dict(W_pre=dW_pre, W_post=dW_post, W_self=dW_self, W_r1=dW_r1, W_r2=dW_r2)
+
+
+def _readout_fwd_bwd_chunk(args):
+    """H of a chunk of edges, its contribution to the loss, and the chunk's share of every readout gradient."""
+    k0, k1 = args
+    w, g, x, Wr, T, n_values = (_state[k] for k in ("w", "g", "x", "Wr", "T", "n_values"))
+    src, dst, shift, row_ptr = g
+    H = O.readout_hij(g, w.pos, w.box, x, Wr, w.lmax, w.lmax, w.channels, w.n_rbf, w.r_cut, w.orb_l, k_range=(k0, k1))
+    diff = H - T[k0:k1]
+    dH = 2.0 * diff / n_values
+    sub = (src[k0:k1], dst[k0:k1], shift[k0:k1], None)
+    dx, gr = O.readout_backward(sub, w.pos, w.box, x, Wr, w.lmax, w.lmax, w.channels, w.n_rbf, w.r_cut, w.orb_l, dH)
+    return float(np.sum(diff * diff)), dx, gr, np.abs(H).max()
+
+
+def make_training(index, pool_size):
+    t0 = time.time()
+    w = synth.workload(index)
+    wt = U.model_weights(w)
+    g = U.oracle_graph(w)
+    agg = U.mean_degree(g, w.n_owned)
+    n_e = len(g[0])
+    T = synth.normal(np.random.default_rng([w.seed, 99]), (n_e, w.n_orb, w.n_orb))
+    xs = [O.species_embed(wt["x0"], w.species, wt["table"])]
+    for t in range(w.n_layers):
+        xs.append(layer_parallel(pool_size, w, g, xs[-1], wt["layers"][t], agg))
+        print(f"config {index}: forward layer {t} done, {time.time() - t0:.0f} s", flush=True)
+    _state.update(w=w, g=g, x=xs[-1], Wr=wt["readout"], T=T, n_values=float(T.size))
+    sq, dx, g_ro, hmax = 0.0, np.zeros_like(xs[-1]), None, 0.0
+    with ProcessPoolExecutor(pool_size) as ex:
+        for s_part, dx_part, gr, hm in ex.map(_readout_fwd_bwd_chunk,
+                                              [(k, min(n_e, k + EDGE_CHUNK)) for k in range(0, n_e, EDGE_CHUNK)]):
+            sq += s_part
+            dx += dx_part
+            hmax = max(hmax, hm)
+            g_ro = gr if g_ro is None else {k: g_ro[k] + gr[k] for k in gr}
+    out = dict(loss=sq / T.size, n_edges=n_e, agg=agg, H_maxabs=hmax)
+    out.update({f"readout.{k}": v for k, v in g_ro.items()})
+    print(f"config {index}: readout forward+backward done, loss {out['loss']:.6f}, {time.time() - t0:.0f} s", flush=True)
+    for t in reversed(range(w.n_layers)):
+        dx, g_l = layer_backward_parallel(pool_size, w, g, xs[t], wt["layers"][t], agg, dx[:w.n_owned])
+        out.update({f"layer{t}.{k}": v for k, v in g_l.items()})
+        print(f"config {index}: backward layer {t} done, {time.time() - t0:.0f} s", flush=True)
+    rng = np.random.default_rng([w.seed, 4242])
+    nodes = np.sort(rng.choice(w.n_total, N_NODE_SAMPLES, replace=False))
+    out.update(nodes=nodes, x0_rows=dx[nodes], x0_maxabs=np.abs(dx).max())
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"config{index}_training.npz")
+    np.savez_compressed(path, **out)
+    print("wrote", path, f"{os.path.getsize(path) / 1e3:.0f} kB", flush=True)
+
+
 if __name__ == "__main__":
-    which = [int(a) for a in sys.argv[1:]] or [3, 4]
+    which = [int(a) for a in sys.argv[1:]] or [3, 4, 5]
+    procs = int(os.environ.get("GOLDEN_PROCS", "6"))
     for idx in which:
-        make(idx, int(os.environ.get("GOLDEN_PROCS", "6")))
+        if idx in (1, 5):          # training step (1 = small self-check of this script against the oracle's own chain)
+            make_training(idx, procs)
+        else:
+            make(idx, procs)
