@@ -162,6 +162,8 @@ __global__ __launch_bounds__(256) void split_w2_kernel(const float* __restrict__
 // stores are fire-and-forget -- and the barriers carry LDS-only fences.
 // The output block of 32 columns is contiguous along the channel/path axis of w, i.e. each accumulator
 // register is stored as two full 128-byte lines.
+#define RW_MB 2                 // 32-row MFMA blocks per compute wave
+#define RW_ROWS (32 * RW_MB)
 #define RW_COMPUTE_WAVES 7
 #define RW_THREADS ((RW_COMPUTE_WAVES + 1) * 64)
 #define RW_BROW4 25   // uint4 per staged W_r2 row: 24 of data (3 pieces x 64 bf16) + 1 of padding (bank spread)
@@ -214,16 +216,16 @@ __global__ __launch_bounds__(RW_THREADS) void radial_weights_kernel(const float4
   }
 
   const int m = lane & 31, hh = lane >> 5;
-  const long e_base = ((long)blockIdx.x * RW_COMPUTE_WAVES + wave) * 64;
+  const long e_base = ((long)blockIdx.x * RW_COMPUTE_WAVES + wave) * RW_ROWS;
   const bool any_row = e_base < n_edges;
-  const bool all_rows = e_base + 64 <= n_edges;
+  const bool all_rows = e_base + RW_ROWS <= n_edges;
 
-  // A operand: hidden activations (times the cutoff envelope) of 2 x 32 edges, this lane's 32 units, in pieces
-  uint4 a_frag[2][3][4];
+  // A operand: hidden activations (times the cutoff envelope) of RW_MB x 32 edges, this lane's 32 units, in pieces
+  uint4 a_frag[RW_MB][3][4];
   const float step = r_cut / (float)(n_rbf - 1);
   const float inv2s2 = 0.5f / (step * step);
 #pragma unroll
-  for (int mb = 0; mb < 2; ++mb) {
+  for (int mb = 0; mb < RW_MB; ++mb) {
     long e = e_base + mb * 32 + m;
     if (e >= n_edges) e = n_edges - 1;
     const float d = rhat_d[e].w;
@@ -267,37 +269,39 @@ __global__ __launch_bounds__(RW_THREADS) void radial_weights_kernel(const float4
 #pragma unroll
         for (int t = 0; t < 4; ++t) b_frag[p][t] = row[p * 8 + t];
     }
-    float16v acc0 = {0}, acc1 = {0};
+    float16v acc[RW_MB];
+#pragma unroll
+    for (int mb = 0; mb < RW_MB; ++mb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[mb][i] = 0.0f;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       // smallest terms first: (lo,hi) (hi,lo) (mid,mid) (mid,hi) (hi,mid) (hi,hi)
       const int pa[6] = {2, 0, 1, 1, 0, 0};
       const int pb[6] = {0, 2, 1, 0, 1, 0};
 #pragma unroll
-      for (int q = 0; q < 6; ++q) {
-        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a_frag[0][pa[q]][t]), as_bf16x8(b_frag[pb[q]][t]),
-                                                       acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a_frag[1][pa[q]][t]), as_bf16x8(b_frag[pb[q]][t]),
-                                                       acc1, 0, 0, 0);
-      }
+      for (int q = 0; q < 6; ++q)
+#pragma unroll
+        for (int mb = 0; mb < RW_MB; ++mb)
+          acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a_frag[mb][pa[q]][t]),
+                                                            as_bf16x8(b_frag[pb[q]][t]), acc[mb], 0, 0, 0);
     }
     const int n = nb * 32 + m;
     if (n < PE) {
       float* out = out_base + nb * 32;
       if (all_rows) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int r = 8 * (i >> 2) + (i & 3);            // row relative to e_base + 4*hh
-          out[(size_t)r * PE] = acc0[i];
-          out[(size_t)(32 + r) * PE] = acc1[i];
-        }
+        for (int mb = 0; mb < RW_MB; ++mb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) out[(size_t)(32 * mb + 8 * (i >> 2) + (i & 3)) * PE] = acc[mb][i];
       } else if (any_row) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int r = 8 * (i >> 2) + (i & 3);
-          if (e_base + 4 * hh + r < n_edges) out[(size_t)r * PE] = acc0[i];
-          if (e_base + 4 * hh + 32 + r < n_edges) out[(size_t)(32 + r) * PE] = acc1[i];
-        }
+        for (int mb = 0; mb < RW_MB; ++mb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int r = 32 * mb + 8 * (i >> 2) + (i & 3);      // row relative to e_base + 4*hh
+            if (e_base + 4 * hh + r < n_edges) out[(size_t)r * PE] = acc[mb][i];
+          }
       }
     }
   }
@@ -319,7 +323,7 @@ int egnn_launch_radial(egnn_ctx* ctx, int which, const float* rhat_d, int64_t n_
   hipLaunchKernelGGL(split_w2_kernel, dim3((PE * EGNN_HIDDEN + 255) / 256), dim3(256), 0, stream, W_r2, W2s, PE,
                      ctx->log2_channels, al);
   EGNN_LAUNCH_CHECK(ctx, "split_w2_kernel");
-  const long per_wg = 64L * RW_COMPUTE_WAVES;
+  const long per_wg = (long)RW_ROWS * RW_COMPUTE_WAVES;
   dim3 grid((unsigned)((n_edges + per_wg - 1) / per_wg)), block(RW_THREADS);
   hipLaunchKernelGGL(radial_weights_kernel, grid, block, 0, stream, reinterpret_cast<const float4*>(rhat_d),
                      (long)n_edges, W_r1, W2s, w, ctx->desc.n_rbf, PE, ctx->desc.r_cut);
