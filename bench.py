@@ -23,16 +23,19 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 FP32_MFMA_PEAK_TFLOPS = 157.3  # dense fp32 matrix peak
 
 
-def stage_model(w, n_edges, n_paths):
-    """Algorithmic bytes / flops per launch of the two heavy kernels."""
+def stage_model(w, n_edges, n_paths, n_paths_ro):
+    """Algorithmic bytes per launch of the three heavy kernels (all HBM-bound by design)."""
     E, D = w.channels, (w.lmax + 1) ** 2
     # S4: per edge the weight row (P*E floats), the gathered source row (D*E floats), indices and unit vector
     # (24 bytes); per owned node one output row.
     s4_bytes = n_edges * (4 * (n_paths * E + D * E) + 24) + w.n_owned * 4 * D * E
-    # S3: [n_edges x 64] x [64 x P*E] contraction plus the 64 x n_rbf first layer
-    s3_flops = n_edges * 2.0 * (w.n_rbf * 64 + 64 * n_paths * E)
+    # S3: per edge one (r_hat, d) record read and the weight row written; the contraction itself
+    # (2*(n_rbf*64 + 64*P*E) flop per edge) runs on the bf16 matrix cores and is far from their roofline.
     s3_bytes = n_edges * (4 * n_paths * E + 16)
-    return s4_bytes, s3_flops, s3_bytes
+    s3_flops = n_edges * 2.0 * (w.n_rbf * 64 + 64 * n_paths * E)
+    # S6: weight row, two gathered rows, indices/unit vector, one n_orb x n_orb block written
+    s6_bytes = n_edges * (4 * (n_paths_ro * E + 2 * D * E) + 24 + 4 * w.n_orb ** 2)
+    return s4_bytes, s3_bytes, s3_flops, s6_bytes
 
 
 def read_traffic(kernel, workload):
@@ -191,17 +194,27 @@ def main():
     layer_ms = {n: ms[i] / max(1, n_calls[0]) for i, n in enumerate(B.LAYER_STAGES)}
     ro_ms = {n: ms[5 + i] / max(1, n_calls[1]) for i, n in enumerate(B.READOUT_STAGES)}
 
-    s4_bytes, s3_flops, s3_bytes = stage_model(w, n_edges, m.n_paths)
-    s4_t, s3_t = layer_ms["tp_segsum"] * 1e-3, layer_ms["radial_weights"] * 1e-3
-    roof_s4 = dict(kernel="tp_segsum_kernel", bound="hbm", achieved=s4_bytes / s4_t / 1e9, peak=HBM_PEAK_GBS,
-                   unit="GB/s", frac=s4_bytes / s4_t / 1e9 / HBM_PEAK_GBS,
-                   traffic=read_traffic("tp_segsum_kernel", w.name), avg_ms=layer_ms["tp_segsum"],
-                   algorithmic_bytes=s4_bytes, edges_per_s=n_edges / s4_t)
-    roof_s3 = dict(kernel="radial_weights_kernel", bound="mfma", achieved=s3_flops / s3_t / 1e12,
-                   peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=s3_flops / s3_t / 1e12 / FP32_MFMA_PEAK_TFLOPS,
-                   traffic=read_traffic("radial_weights_kernel", w.name), avg_ms=layer_ms["radial_weights"],
-                   algorithmic_flops=s3_flops, write_GBs=s3_bytes / s3_t / 1e9)
-    dominant, other = (roof_s4, roof_s3) if s4_t >= s3_t else (roof_s3, roof_s4)
+    s4_bytes, s3_bytes, s3_flops, s6_bytes = stage_model(w, n_edges, m.n_paths, m.n_paths_readout)
+
+    def hbm_roof(kernel, nbytes, avg_ms, calls_per_step, **extra):
+        t = avg_ms * 1e-3
+        d = dict(kernel=kernel, bound="hbm", achieved=nbytes / t / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
+                 frac=nbytes / t / 1e9 / HBM_PEAK_GBS, traffic=read_traffic(kernel, w.name), avg_ms=avg_ms,
+                 algorithmic_bytes=nbytes, launches_per_step=calls_per_step, ms_per_step=avg_ms * calls_per_step,
+                 edges_per_s=n_edges / t)
+        d.update(extra)
+        return d
+
+    n_ro = 1 if w.readout else 0
+    s3_ms = (layer_ms["radial_weights"] * n_calls[0] + ro_ms["radial_weights"] * n_calls[1]) / max(1, sum(n_calls))
+    roofs = [hbm_roof("tp_segsum_kernel", s4_bytes, layer_ms["tp_segsum"], w.n_layers),
+             hbm_roof("radial_weights_kernel", s3_bytes, s3_ms, w.n_layers + n_ro,
+                      mfma_TFLOPs=s3_flops / (s3_ms * 1e-3) / 1e12, mfma_peak_TFLOPs_bf16=2500.0,
+                      note="contraction on bf16 MFMA with 3-piece operand splitting (6 products per fp32 product)")]
+    if w.readout:
+        roofs.append(hbm_roof("readout_kernel", s6_bytes, ro_ms["readout"], 1))
+    roofs.sort(key=lambda r: -r["ms_per_step"])
+    dominant, other = roofs[0], roofs[1:]
 
     out = {
         "metric": "edges/sec per eGNN message-passing layer (fwd) + % of peak HBM GB/s on 1 GPU",
@@ -212,7 +225,7 @@ def main():
                    "n_edges": n_edges, "lmax": w.lmax, "channels": w.channels, "n_rbf": w.n_rbf,
                    "n_layers": w.n_layers, "readout": bool(w.readout), "r_cut": w.r_cut,
                    "step": "nlist + species embed + layers fwd + H_ij readout"},
-        "roofline": dominant, "roofline_other": other,
+        "roofline": dominant, "roofline_others": other,
         "stage_ms": {"layer": layer_ms, "readout": ro_ms if w.readout else None,
                      "layer_total": sum(layer_ms.values()),
                      "layer_edges_per_s": n_edges / (sum(layer_ms.values()) * 1e-3)},
