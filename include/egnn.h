@@ -130,7 +130,15 @@ int egnn_tp_segsum(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, cons
 int egnn_node_mix(egnn_ctx* ctx, const float* x1, const float* W1, const float* x2, const float* W2,
                   float* y, int32_t n_nodes, void* stream);
 
-/* ---- one message-passing layer, forward: S2 (if needed) -> S3 -> S5(pre) -> S4 -> S5(post) ----
+/* Options.  EGNN_OPT_FUSED (default 0): when 1, egnn_layer_forward with its own radial MLP and 16, 32 or 64
+ * channels produces and consumes the radial weights inside one kernel (they are never written to memory);
+ * when 0 it goes through the materialised weight tensor (S3 then S4), as it always does for caller-supplied
+ * weights and other channel counts.  Both routes compute the same function; the two-kernel route is the faster
+ * one at present. */
+#define EGNN_OPT_FUSED 1
+int egnn_set_option(egnn_ctx* ctx, int32_t option, int32_t value);
+
+/* ---- one message-passing layer, forward: S2 -> S5(pre) -> S3+S4 fused (or S3 -> S4) -> S5(post) ----
  * x_out[j] = W_post a_j + W_self x_in[j] for j < n_owned, with h = W_pre x_in.  x_in has n_total rows;
  * x_out has n_owned rows and must not alias x_in.  If w_edge != NULL ([n_edges][P][channels]) it is used as
  * the radial weights (W_r1, W_r2 ignored).  ws: at least egnn_workspace_bytes(...) bytes, 256-byte aligned. */

@@ -11,6 +11,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libegnn_hip.so")
 MAX_SHELLS = 8
+OPT_FUSED = 1
 
 SYMBOLS = [
     "egnn_create", "egnn_destroy", "egnn_last_error", "egnn_path_count", "egnn_readout_widths",
@@ -18,7 +19,7 @@ SYMBOLS = [
     "egnn_edge_geometry", "egnn_radial_weights", "egnn_tp_segsum", "egnn_node_mix",
     "egnn_layer_forward", "egnn_readout_hij", "egnn_timing_enable", "egnn_timing_read",
     "egnn_backward_workspace_bytes", "egnn_graph_transpose", "egnn_loss_mse", "egnn_layer_backward",
-    "egnn_readout_backward",
+    "egnn_readout_backward", "egnn_set_option",
 ]
 
 
@@ -125,6 +126,9 @@ class Egnn:
     def _check(self, rc):
         if rc:
             raise EgnnError(rc, self.lib.egnn_last_error(self.ctx).decode())
+
+    def egnn_set_option(self, option, value):
+        self._check(self.lib.egnn_set_option(self.ctx, int(option), int(value)))
 
     # ---- queries
     def egnn_path_count(self, which):

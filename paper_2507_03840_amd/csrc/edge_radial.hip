@@ -119,24 +119,7 @@ int egnn_launch_geometry(egnn_ctx* ctx, const egnn_graph* g, const float* pos, c
 // (hi*hi, hi*mid, mid*hi, mid*mid, hi*lo, lo*hi); the three dropped ones are below 2^-24 of the product.
 // Six v_mfma_f32_32x32x16_bf16 replace eight v_mfma_f32_32x32x2_f32 at 1/16 of their cost each, which moves
 // the kernel from the fp32-MFMA roofline to the rate at which w can be written.
-typedef float float16v __attribute__((ext_vector_type(16)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-
-struct Split3 { uint32_t hi, mid, lo; };   // each: a bf16 in the upper 16 bits
-
-__device__ __forceinline__ Split3 split3(float x) {
-  Split3 r;
-  r.hi = __float_as_uint(x) & 0xffff0000u;
-  const float r1 = x - __uint_as_float(r.hi);
-  r.mid = __float_as_uint(r1) & 0xffff0000u;
-  const float r2 = r1 - __uint_as_float(r.mid);
-  r.lo = __float_as_uint(r2) & 0xffff0000u;
-  return r;
-}
-
-__device__ __forceinline__ uint32_t pack2(uint32_t even, uint32_t odd) { return (even >> 16) | odd; }
-
-__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+#include "split_bf16.h"
 
 // W_r2 (times alpha_p) cut into pieces once per call: out[n][piece][64] bf16.
 __global__ __launch_bounds__(256) void split_w2_kernel(const float* __restrict__ W_r2, uint16_t* __restrict__ out,
@@ -311,18 +294,26 @@ size_t egnn_radial_ws_bytes(const egnn_ctx* ctx, int which) {
   return (size_t)ctx->n_paths[which] * ctx->desc.channels * 3 * EGNN_HIDDEN * sizeof(uint16_t);
 }
 
-// `scratch` holds egnn_radial_ws_bytes: the pieces of W_r2.
-int egnn_launch_radial(egnn_ctx* ctx, int which, const float* rhat_d, int64_t n_edges, const float* W_r1,
-                       const float* W_r2, float* w, void* scratch, hipStream_t stream) {
-  if (n_edges == 0) return EGNN_OK;
+// W_r2 * alpha_p -> bf16 pieces [n][3][64] in `scratch` (egnn_radial_ws_bytes).
+int egnn_launch_split_w2(egnn_ctx* ctx, int which, const float* W_r2, void* scratch, hipStream_t stream) {
   const int P = ctx->n_paths[which];
   const int PE = P * ctx->desc.channels;
   PathAlpha al;
   for (int p = 0; p < EGNN_MAX_PATHS; ++p) al.a[p] = p < P ? ctx->alpha[which][p] : 0.0f;
-  uint16_t* W2s = (uint16_t*)scratch;
-  hipLaunchKernelGGL(split_w2_kernel, dim3((PE * EGNN_HIDDEN + 255) / 256), dim3(256), 0, stream, W_r2, W2s, PE,
-                     ctx->log2_channels, al);
+  hipLaunchKernelGGL(split_w2_kernel, dim3((PE * EGNN_HIDDEN + 255) / 256), dim3(256), 0, stream, W_r2,
+                     (uint16_t*)scratch, PE, ctx->log2_channels, al);
   EGNN_LAUNCH_CHECK(ctx, "split_w2_kernel");
+  return EGNN_OK;
+}
+
+// `scratch` holds egnn_radial_ws_bytes: the pieces of W_r2.
+int egnn_launch_radial(egnn_ctx* ctx, int which, const float* rhat_d, int64_t n_edges, const float* W_r1,
+                       const float* W_r2, float* w, void* scratch, hipStream_t stream) {
+  if (n_edges == 0) return EGNN_OK;
+  const int PE = ctx->n_paths[which] * ctx->desc.channels;
+  int rc = egnn_launch_split_w2(ctx, which, W_r2, scratch, stream);
+  if (rc) return rc;
+  uint16_t* W2s = (uint16_t*)scratch;
   const long per_wg = (long)RW_ROWS * RW_COMPUTE_WAVES;
   dim3 grid((unsigned)((n_edges + per_wg - 1) / per_wg)), block(RW_THREADS);
   hipLaunchKernelGGL(radial_weights_kernel, grid, block, 0, stream, reinterpret_cast<const float4*>(rhat_d),

@@ -162,6 +162,15 @@ extern "C" int egnn_timing_read(egnn_ctx* ctx, float ms[2 * EGNN_STAGES], int32_
   return EGNN_OK;
 }
 
+extern "C" int egnn_set_option(egnn_ctx* ctx, int32_t option, int32_t value) {
+  if (!ctx) return EGNN_EINVAL;
+  if (option == EGNN_OPT_FUSED) {
+    ctx->use_fused = value != 0;
+    return EGNN_OK;
+  }
+  return egnn_fail(ctx, EGNN_EINVAL, "set_option: unknown option");
+}
+
 extern "C" const char* egnn_last_error(const egnn_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
 
 extern "C" int egnn_path_count(const egnn_ctx* ctx, int which, int32_t* n_paths, int32_t* paths) {
@@ -302,11 +311,22 @@ extern "C" int egnn_layer_forward(egnn_ctx* ctx, const egnn_graph* g, const floa
   StageTimer tm(ctx, st, 0);
   if ((rc = egnn_launch_geometry(ctx, g, pos, box, rhat_d, nullptr, nullptr, nullptr, st))) return rc;
   tm.mark(0);
-  if (with_w && (rc = egnn_launch_radial(ctx, 0, rhat_d, g->n_edges, W_r1, W_r2, w, w2s, st))) return rc;
+  // Default: S3 writes the weight tensor, S4 reads it.  Opt-in (EGNN_OPT_FUSED): the weights are produced and
+  // consumed inside one kernel and never leave the chip.
+  const bool fused = with_w && ctx->use_fused && egnn_fused_supported(ctx);
+  if (fused) {
+    if (g->n_edges > 0 && (rc = egnn_launch_split_w2(ctx, 0, W_r2, w2s, st))) return rc;
+  } else if (with_w) {
+    if ((rc = egnn_launch_radial(ctx, 0, rhat_d, g->n_edges, W_r1, W_r2, w, w2s, st))) return rc;
+  }
   tm.mark(1);
   if ((rc = egnn_launch_node_mix(ctx, x_in, W_pre, nullptr, nullptr, h, g->n_total, st))) return rc;
   tm.mark(2);
-  if ((rc = egnn_launch_tp_segsum(ctx, g, rhat_d, h, with_w ? w : w_edge, a, st))) return rc;
+  if (fused) {
+    if ((rc = egnn_launch_layer_fused(ctx, g, rhat_d, h, W_r1, w2s, a, st))) return rc;
+  } else {
+    if ((rc = egnn_launch_tp_segsum(ctx, g, rhat_d, h, with_w ? w : w_edge, a, st))) return rc;
+  }
   tm.mark(3);
   rc = egnn_launch_node_mix(ctx, a, W_post, x_in, W_self, x_out, g->n_owned, st);
   tm.mark(4);

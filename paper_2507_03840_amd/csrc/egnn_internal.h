@@ -27,6 +27,7 @@ struct egnn_ctx {
   std::vector<hipEvent_t> ev;
   std::vector<int> ev_kind;              // per recorded call: 0 = layer, 1 = readout
   int ev_max_calls = 0;
+  bool use_fused = false;                // egnn_set_option(EGNN_OPT_FUSED)
   std::string err;
 };
 
@@ -84,6 +85,10 @@ int egnn_launch_tp_segsum(egnn_ctx*, const egnn_graph*, const float* rhat_d, con
 int egnn_launch_radial(egnn_ctx*, int which, const float* rhat_d, int64_t n_edges, const float* W_r1,
                        const float* W_r2, float* w, void* scratch, hipStream_t);
 size_t egnn_radial_ws_bytes(const egnn_ctx*, int which);
+int egnn_launch_split_w2(egnn_ctx*, int which, const float* W_r2, void* scratch, hipStream_t);
+bool egnn_fused_supported(const egnn_ctx*);
+int egnn_launch_layer_fused(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* h, const float* W_r1,
+                            const void* W2s, float* a, hipStream_t);
 int egnn_launch_geometry(egnn_ctx*, const egnn_graph*, const float* pos, const float box[3], float* rhat_d,
                          float* Y, float* rbf, float* fc, hipStream_t);
 int egnn_launch_readout(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* zs, const float* zt,

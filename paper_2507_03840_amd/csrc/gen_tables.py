@@ -314,7 +314,29 @@ def emit_mid(l_in, l_sh, l_out, paths, groups):
     for p in range(len(paths)):
         if p not in tw:
             lines.append(f"    gw[{p}] = 0.0f;")
-    lines += ["  }", "};"]
+    lines.append("  }")
+    # the same product split by input degree l1 (paths are ordered l1-major, so each piece uses one contiguous run of
+    # weights): o is accumulated into, v is the degree-l1 block only, w the weights of that run
+    first = [min(p for p, t in enumerate(paths) if t[0] == l1) for l1 in range(l_in + 1)]
+    count = [sum(1 for t in paths if t[0] == l1) for l1 in range(l_in + 1)]
+    lines.append(f"  static constexpr int CHUNK_FIRST[{l_in + 1}] = {{{', '.join(map(str, first))}}};")
+    lines.append(f"  static constexpr int CHUNK_COUNT[{l_in + 1}] = {{{', '.join(map(str, count))}}};")
+    lines.append(f"  static constexpr int CHUNK_MAX = {max(count)};")
+    lines.append("  template <int L1> __device__ __forceinline__ static void run_l1(const float* v, const float* w, float* o);")
+    lines.append("};")
+    for l1 in range(l_in + 1):
+        lines.append(f"template <> __device__ __forceinline__ void TpMid_{tag}::run_l1<{l1}>(const float* v, const float* w, float* o) {{")
+        for (a, l3) in sorted(groups):
+            if a != l1:
+                continue
+            for m in sorted(groups[(a, l3)]):
+                terms = groups[(a, l3)][m]
+                g = " + ".join(f"{f32(k)} * w[{p - first[l1]}]" for p, k in terms)
+                lines.append(f"  {{ const float g = {g};")
+                for mm in ([m, -m] if m else [0]):
+                    lines.append(f"    o[{l3 * l3 + l3 + mm}] += g * v[{l1 + mm}];")
+                lines.append("  }")
+        lines.append("}")
     return "\n".join(lines)
 
 

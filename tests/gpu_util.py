@@ -52,11 +52,13 @@ def oracle_forward(w, wt, g, agg_norm, with_readout=True):
     return xs, H
 
 
-def gpu_forward(w, wt, agg_norm, with_readout=True):
+def gpu_forward(w, wt, agg_norm, with_readout=True, fused=False):
     """Same model through the C ABI.  Returns (model, graph, xs (device tensors), H)."""
     import torch
     from paper_2507_03840_amd import binding as B
     m = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, agg_norm, n_layers=w.n_layers, orb_l=w.orb_l)
+    if fused:
+        m.egnn_set_option(B.OPT_FUSED, 1)
     pos = B.to_device(w.pos)
     graph = m.egnn_nlist(pos, w.n_owned, w.box, w.pbc)
     ws = m.workspace(graph)

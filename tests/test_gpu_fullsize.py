@@ -15,8 +15,8 @@ pytestmark = pytest.mark.gpu
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
 
-@pytest.mark.parametrize("index", [3, 4])
-def test_fullsize_sampled_rows(index):
+@pytest.mark.parametrize("index,fused", [(3, False), (4, False), (3, True), (4, True)])
+def test_fullsize_sampled_rows(index, fused):
     import torch
     assert torch.cuda.is_available()
     path = os.path.join(GOLDEN, f"config{index}_samples.npz")
@@ -25,7 +25,7 @@ def test_fullsize_sampled_rows(index):
     print(f"config {index}: building inputs", flush=True)
     w = synth.workload(index)
     wt = U.model_weights(w)
-    m, graph, xs, H = U.gpu_forward(w, wt, float(gold["agg"]), with_readout=w.readout)
+    m, graph, xs, H = U.gpu_forward(w, wt, float(gold["agg"]), with_readout=w.readout, fused=fused)
     assert graph.n_edges == int(gold["n_edges"])
     rp = graph.row_ptr.cpu().numpy()
     assert rp[-1] == graph.n_edges and np.all(np.diff(rp) > 0)

@@ -166,14 +166,16 @@ def test_tp_segsum_edge_along_polar_axis(B):
 
 
 # ------------------------------------------------------------------------------------------ whole model
+@pytest.mark.parametrize("fused", [False, True])
 @pytest.mark.parametrize("index", [1, 2])
-def test_model_forward_configs_full(B, index):
-    """Configs 1 and 2 in full: species embedding, all layers, H_ij readout, every element."""
+def test_model_forward_configs_full(B, index, fused):
+    """Configs 1 and 2 in full: species embedding, all layers, H_ij readout, every element; once through the materialised weight tensor
+    (default) and once with the fused radial-weights + message kernel."""
     w = synth.workload(index)
     wt = U.model_weights(w)
     g = U.oracle_graph(w)
     agg = U.mean_degree(g, w.n_owned)
-    m, graph, xs, H = U.gpu_forward(w, wt, agg)
+    m, graph, xs, H = U.gpu_forward(w, wt, agg, fused=fused)
     assert np.array_equal(graph.src.cpu().numpy(), g[0]) and np.array_equal(graph.dst.cpu().numpy(), g[1])
     xs_ref, H_ref = U.oracle_forward(w, wt, g, agg)
     for t in range(w.n_layers):
@@ -187,15 +189,28 @@ def test_model_forward_configs_full(B, index):
 
 @pytest.mark.parametrize("lmax,E,periodic,n,n_owned", [(0, 8, False, 40, 40), (1, 16, True, 120, 120),
                                                         (2, 64, False, 100, 60), (3, 16, True, 150, 90),
-                                                        (4, 128, False, 60, 40), (4, 8, False, 70, 70)])
+                                                        (4, 128, False, 60, 40), (4, 8, False, 70, 70),
+                                                        (3, 32, True, 260, 200), (4, 32, False, 200, 150),
+                                                        (4, 64, True, 180, 120), (0, 16, False, 40, 30),
+                                                        (2, 32, False, 33, 33)])
 def test_model_forward_small_shapes(B, lmax, E, periodic, n, n_owned):
+    _model_forward_small(B, lmax, E, periodic, n, n_owned, False)
+
+
+@pytest.mark.parametrize("lmax,E,n,n_owned", [(1, 16, 120, 120), (2, 64, 100, 60), (3, 32, 150, 90), (4, 16, 70, 70),
+                                               (0, 32, 50, 50), (4, 64, 90, 70)])
+def test_model_forward_small_shapes_fused(B, lmax, E, n, n_owned):
+    _model_forward_small(B, lmax, E, False, n, n_owned, True)
+
+
+def _model_forward_small(B, lmax, E, periodic, n, n_owned, fused):
     """Small ragged cases over every supported degree and channel width, with halo rows, two layers, readout."""
     w = _cluster(n, n_owned, lmax, E, n_rbf=6, r_cut=4.0, seed=30 + lmax, periodic=periodic)
     w.n_layers = 2
     wt = U.model_weights(w)
     g = U.oracle_graph(w)
     agg = max(1.0, U.mean_degree(g, w.n_owned))
-    m, graph, xs, H = U.gpu_forward(w, wt, agg)
+    m, graph, xs, H = U.gpu_forward(w, wt, agg, fused=fused)
     xs_ref, H_ref = U.oracle_forward(w, wt, g, agg)
     for t in range(2):
         assert U.rel_err(xs[t].cpu().numpy(), xs_ref[t]) < TOL
