@@ -38,30 +38,28 @@ __device__ __forceinline__ void rotate_slot_back(float* q, const BondTrig& t) {
   for (int i = 0; i < 2 * L + 1; ++i) q[i] = v[i];
 }
 
-template <int LMAX>
+template <int LMAX, int log2E>
 __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ src, const int* __restrict__ dst,
                                                       const float4* __restrict__ rhat_d,
                                                       const float* __restrict__ zs, const float* __restrict__ zt,
                                                       const float* __restrict__ w, const float* __restrict__ V,
-                                                      ReadoutTabs tb, float* __restrict__ H, long n_edges,
-                                                      int log2E) {
+                                                      ReadoutTabs tb, float* __restrict__ H, long n_edges) {
   using Mid = typename ReadoutMid<LMAX>::T;
   constexpr int D = (LMAX + 1) * (LMAX + 1);
   constexpr int P = Mid::P;
   extern __shared__ float smem[];
-  const int E = 1 << log2E;
+  constexpr int E = 1 << log2E;
   const int tid = threadIdx.x;
   const int c = tid & (E - 1), slot = tid >> log2E;
-  const int n_slots = 256 >> log2E;
-  const int us = E + 1;                 // padded row of su
-  const int vs = tb.n_vrows | 1;        // odd row length of sVt
-  float* sVt = smem;                                    // [E][vs]
-  float* su = sVt + (size_t)E * vs + (size_t)slot * RO_D * us;            // this slot: [25][E+1]
-  float* sq = smem + (size_t)E * vs + (size_t)n_slots * RO_D * us + (size_t)slot * tb.nq;  // this slot: [nq]
+  constexpr int n_slots = 256 >> log2E;
+  constexpr int us = E + 4;             // padded row of su and sV: 16-byte aligned, rows 4 banks apart
+  float* sV = smem;                                      // [n_vrows][E+4]
+  float* su = sV + (size_t)tb.n_vrows * us + (size_t)slot * RO_D * us;    // this slot: [25][E+4]
+  float* sq = smem + (size_t)tb.n_vrows * us + (size_t)n_slots * RO_D * us + (size_t)slot * tb.nq;  // this slot: [nq]
 
   for (int i = tid; i < tb.n_vrows * E; i += 256) {
     const int r = i >> log2E, cc = i & (E - 1);
-    sVt[cc * vs + r] = V[i];
+    sV[r * us + cc] = V[i];
   }
 
   const long k_base = (long)blockIdx.x * n_slots * RO_ITERS;
@@ -89,11 +87,18 @@ __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ sr
     __syncthreads();
     if (live) {
       for (int q = c; q < tb.nq; q += E) {
-        const float* ur = su + tb.q_row[q] * us;
-        const float* vr = sVt + tb.q_vrow[q];
-        float sum = 0.0f;
-        for (int cc = 0; cc < E; ++cc) sum += vr[cc * vs] * ur[cc];
-        sq[q] = sum;
+        const float4* ur = reinterpret_cast<const float4*>(su + tb.q_row[q] * us);
+        const float4* vr = reinterpret_cast<const float4*>(sV + tb.q_vrow[q] * us);
+        float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+#pragma unroll
+        for (int cc = 0; cc < E / 4; ++cc) {
+          const float4 a = ur[cc], b = vr[cc];
+          s0 += a.x * b.x;
+          s1 += a.y * b.y;
+          s2 += a.z * b.z;
+          s3 += a.w * b.w;
+        }
+        sq[q] = (s0 + s1) + (s2 + s3);
       }
     }
     __syncthreads();
@@ -121,12 +126,30 @@ __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ sr
   }
 }
 
+template <int L, int LE>
+static int launch_readout(egnn_ctx* ctx, const egnn_graph* g, const float4* rd, const float* zs, const float* zt,
+                          const float* w, const float* V, const ReadoutTabs& tb, float* H, hipStream_t stream) {
+  constexpr int E = 1 << LE, n_slots = 256 / E;
+  const size_t shmem = ((size_t)tb.n_vrows * (E + 4) + (size_t)n_slots * RO_D * (E + 4) + (size_t)n_slots * tb.nq) *
+                       sizeof(float);
+  const long per_wg = (long)n_slots * RO_ITERS;
+  dim3 grid((unsigned)((g->n_edges + per_wg - 1) / per_wg)), block(256);
+  auto kern = readout_kernel<L, LE>;
+  if (shmem > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)shmem);
+    if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(readout_kernel)");
+  }
+  hipLaunchKernelGGL(kern, grid, block, shmem, stream, g->src, g->dst, rd, zs, zt, w, V, tb, H, (long)g->n_edges);
+  EGNN_LAUNCH_CHECK(ctx, "readout_kernel");
+  return EGNN_OK;
+}
+
 int egnn_launch_readout(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, const float* zs, const float* zt,
                         const float* w, const float* V, const int* tab_i, const float* tab_f, float* H,
                         hipStream_t stream) {
   const long n = g->n_edges;
   if (n == 0) return EGNN_OK;
-  const int E = ctx->desc.channels;
   const int nq = ctx->n_orb * ctx->n_orb;
   ReadoutTabs tb;
   tb.nq = nq;
@@ -141,31 +164,12 @@ int egnn_launch_readout(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d,
   tb.unc_ptr = tb.slot_qoff + ctx->n_slots;
   tb.unc_q = tb.unc_ptr + nq + 1;
   tb.unc_c = tab_f;
-  const int n_slots = 256 / E;
-  const int vs = tb.n_vrows | 1;
-  const size_t shmem = ((size_t)E * vs + (size_t)n_slots * RO_D * (E + 1) + (size_t)n_slots * nq) * sizeof(float);
-  const long per_wg = (long)n_slots * RO_ITERS;
-  dim3 grid((unsigned)((n + per_wg - 1) / per_wg)), block(256);
   const float4* rd = reinterpret_cast<const float4*>(rhat_d);
-#define LAUNCH(L)                                                                                             \
-  do {                                                                                                        \
-    if (shmem > 64 * 1024) {                                                                                  \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(readout_kernel<L>),                    \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);             \
-      if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(readout_kernel)");              \
-    }                                                                                                         \
-    hipLaunchKernelGGL(readout_kernel<L>, grid, block, shmem, stream, g->src, g->dst, rd, zs, zt, w, V, tb, H, \
-                       n, ctx->log2_channels);                                                                \
-  } while (0)
-  switch (ctx->desc.lmax) {
-    case 0: LAUNCH(0); break;
-    case 1: LAUNCH(1); break;
-    case 2: LAUNCH(2); break;
-    case 3: LAUNCH(3); break;
-    case 4: LAUNCH(4); break;
-    default: return egnn_fail(ctx, EGNN_EINVAL, "readout: lmax out of range");
-  }
-#undef LAUNCH
-  EGNN_LAUNCH_CHECK(ctx, "readout_kernel");
-  return EGNN_OK;
+#define CASE(L, LE) \
+  if (ctx->desc.lmax == L && ctx->log2_channels == LE) return launch_readout<L, LE>(ctx, g, rd, zs, zt, w, V, tb, H, stream);
+#define CASES(L) CASE(L, 3) CASE(L, 4) CASE(L, 5) CASE(L, 6) CASE(L, 7)
+  CASES(0) CASES(1) CASES(2) CASES(3) CASES(4)
+#undef CASES
+#undef CASE
+  return egnn_fail(ctx, EGNN_EINVAL, "readout: unsupported (lmax, channels)");
 }
