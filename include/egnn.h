@@ -90,13 +90,20 @@ int egnn_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, 
  * Two phases because n_edges depends on the data: count fills row_ptr and returns n_edges (host),
  * the caller allocates src/dst/shift (n_edges entries; may be NULL when n_edges == 0) and passes the
  * same n_edges back, fill writes them sorted by (dst, src).
- * box, pbc: host arrays of 3.  EGNN_EBOX if a periodic edge is shorter than 2*r_cut. */
+ * box, pbc: host arrays of 3.  EGNN_EBOX if a periodic edge is shorter than 2*r_cut.
+ * ws: with a workspace of egnn_nlist_workspace_bytes (256-byte aligned) and at most 262,144 atoms the search
+ * goes through a cell list (cells of edge >= r_cut, at most 64 per axis); count builds the cells, fill reuses
+ * them, so fill must follow count with the same atoms and the same, untouched workspace.  With ws == NULL
+ * every destination sweeps all atoms (O(n_owned * n_total), fine for a few thousand atoms).  Both give the
+ * same edge list.  count synchronises the stream (twice with a workspace: bounding box, edge count). */
+int egnn_nlist_workspace_bytes(const egnn_ctx* ctx, int32_t n_total, size_t* bytes);
 int egnn_nlist_count(egnn_ctx* ctx, const float* pos, int32_t n_owned, int32_t n_total,
                      const float box[3], const uint8_t pbc[3], int32_t* row_ptr, int64_t* n_edges,
-                     void* stream);
+                     void* ws, size_t ws_bytes, void* stream);
 int egnn_nlist_fill(egnn_ctx* ctx, const float* pos, int32_t n_owned, int32_t n_total,
                     const float box[3], const uint8_t pbc[3], const int32_t* row_ptr, int64_t n_edges,
-                    int32_t* src, int32_t* dst, int8_t* shift /* may be NULL */, void* stream);
+                    int32_t* src, int32_t* dst, int8_t* shift /* may be NULL */, void* ws, size_t ws_bytes,
+                    void* stream);
 
 /* ---- node initialisation (Sec. 3: the L=0 plane carries the atomic species) ----
  * x[i][0][c] += table[species[i]][c]. */

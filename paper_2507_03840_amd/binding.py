@@ -15,7 +15,7 @@ OPT_FUSED = 1
 
 SYMBOLS = [
     "egnn_create", "egnn_destroy", "egnn_last_error", "egnn_path_count", "egnn_readout_widths",
-    "egnn_workspace_bytes", "egnn_nlist_count", "egnn_nlist_fill", "egnn_species_embed",
+    "egnn_workspace_bytes", "egnn_nlist_workspace_bytes", "egnn_nlist_count", "egnn_nlist_fill", "egnn_species_embed",
     "egnn_edge_geometry", "egnn_radial_weights", "egnn_tp_segsum", "egnn_node_mix",
     "egnn_layer_forward", "egnn_readout_hij", "egnn_timing_enable", "egnn_timing_read",
     "egnn_backward_workspace_bytes", "egnn_graph_transpose", "egnn_loss_mse", "egnn_layer_backward",
@@ -154,20 +154,27 @@ class Egnn:
         return torch.empty(nbytes, dtype=torch.uint8, device="cuda")
 
     # ---- S1
-    def egnn_nlist(self, pos, n_owned, box, pbc, with_shift=True):
-        """count + allocate + fill; returns a Graph."""
+    def egnn_nlist_workspace_bytes(self, n_total):
+        out = C.c_size_t()
+        self._check(self.lib.egnn_nlist_workspace_bytes(self.ctx, int(n_total), C.byref(out)))
+        return out.value
+
+    def egnn_nlist(self, pos, n_owned, box, pbc, with_shift=True, cell_list=True):
+        """count + allocate + fill; returns a Graph.  cell_list=False: every destination sweeps all atoms."""
         n_total = pos.shape[0]
         pbc_c = (C.c_uint8 * 3)(*[int(v) for v in pbc])
         row_ptr = torch.empty(n_owned + 1, dtype=torch.int32, device="cuda")
         n_edges = C.c_int64()
+        ws = torch.empty(self.egnn_nlist_workspace_bytes(n_total), dtype=torch.uint8, device="cuda") if cell_list else None
+        ws_n = C.c_size_t(ws.numel() if ws is not None else 0)
         self._check(self.lib.egnn_nlist_count(self.ctx, _ptr(pos), n_owned, n_total, _f3(box), pbc_c, _ptr(row_ptr),
-                                              C.byref(n_edges), _stream()))
+                                              C.byref(n_edges), _ptr(ws), ws_n, _stream()))
         n = n_edges.value
         src = torch.empty(n, dtype=torch.int32, device="cuda")
         dst = torch.empty(n, dtype=torch.int32, device="cuda")
         shift = torch.empty((n, 3), dtype=torch.int8, device="cuda") if with_shift else None
         self._check(self.lib.egnn_nlist_fill(self.ctx, _ptr(pos), n_owned, n_total, _f3(box), pbc_c, _ptr(row_ptr),
-                                             C.c_int64(n), _ptr(src), _ptr(dst), _ptr(shift), _stream()))
+                                             C.c_int64(n), _ptr(src), _ptr(dst), _ptr(shift), _ptr(ws), ws_n, _stream()))
         return Graph(src, dst, row_ptr, shift, n_owned, n_total)
 
     # ---- node init

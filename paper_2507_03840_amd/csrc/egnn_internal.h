@@ -10,6 +10,13 @@
 #define EGNN_HIDDEN 64
 #define EGNN_L_READOUT 4
 
+// Cell grid of the neighbour search: periodic axes span the box, open axes the bounding box of the atoms.
+struct CellGrid {
+  double lo[3], inv_cell[3], box[3];
+  int n[3], pbc[3];
+  int n_cells;
+};
+
 struct egnn_ctx {
   egnn_model_desc desc;
   int n_paths[2];                        // 0: layers, 1: readout
@@ -27,6 +34,8 @@ struct egnn_ctx {
   std::vector<hipEvent_t> ev;
   std::vector<int> ev_kind;              // per recorded call: 0 = layer, 1 = readout
   int ev_max_calls = 0;
+  CellGrid nl_grid;                      // grid of the last egnn_nlist_count that used the cell list
+  int nl_grid_atoms = -1;                //   and the atom count it was built for
   bool use_fused = false;                // egnn_set_option(EGNN_OPT_FUSED)
   std::string err;
 };

@@ -33,8 +33,10 @@ def _graph_to_device(B, g, n_owned, n_total):
 
 
 # ------------------------------------------------------------------------------------------ S1
-@pytest.mark.parametrize("case", ["open", "periodic", "halo", "config1", "config2", "empty", "single"])
-def test_nlist_bit_exact(B, case):
+@pytest.mark.parametrize("cell_list", [True, False])
+@pytest.mark.parametrize("case", ["open", "periodic", "halo", "config1", "config2", "empty", "single", "slab", "line"])
+def test_nlist_bit_exact(B, case, cell_list):
+    """Edge list, CSR index and periodic shifts against the brute-force oracle, for both search strategies."""
     print("case", case, flush=True)
     if case == "config1":
         w = synth.workload(1)
@@ -44,10 +46,16 @@ def test_nlist_bit_exact(B, case):
         w = _cluster(5, 0, 1, 8, seed=3)
     elif case == "single":
         w = _cluster(1, 1, 1, 8, seed=3)
+    elif case == "slab":      # periodic in x, y only, many cells along x, halo atoms: the shape of config 4
+        w = _cluster(900, 600, 1, 8, r_cut=3.0, seed=6, periodic=True, density=0.05)
+        w.pbc = np.array([1, 1, 0], np.uint8)
+    elif case == "line":      # all atoms on a line: two axes with zero extent
+        w = _cluster(50, 50, 1, 8, r_cut=3.0, seed=7)
+        w.pos[:, 1:] = 0.25
     else:
         w = _cluster(333, 200 if case == "halo" else 333, 1, 8, r_cut=5.0, seed=4, periodic=(case == "periodic"))
     m = B.Egnn(1, 8, 8, w.r_cut, 1.0)
-    g = m.egnn_nlist(B.to_device(w.pos), w.n_owned, w.box, w.pbc)
+    g = m.egnn_nlist(B.to_device(w.pos), w.n_owned, w.box, w.pbc, cell_list=cell_list)
     src, dst, shift, row_ptr = U.oracle_graph(w)
     assert g.n_edges == len(src)
     assert np.array_equal(g.row_ptr.cpu().numpy(), row_ptr)
