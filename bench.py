@@ -77,8 +77,8 @@ def main():
     ap.add_argument("--cpu-nodes", type=int, default=1024)
     ap.add_argument("--train-steps", type=int, default=3,
                     help="training steps (forward + loss + reverse pass, config 5) timed after the main region; 0 = skip")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also launch a plain 1 GiB -> 1 GiB elementwise copy 3 times (reference for rocprofv3 --pmc)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also time one layer forward on growing prefixes of the destination nodes (saturation curve)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -181,13 +181,42 @@ def main():
                             step="layers fwd + readout + MSE + readout bwd + layers bwd (forward recomputed inside bwd)")
         del bws
 
-    if args.copy_calibration:
-        a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
-        b = torch.empty_like(a)
-        for _ in range(3):
-            torch.mul(a, 1.0, out=b)
+    # ---- what this GPU's memory system delivers to the simplest kernels: 1 GiB elementwise copy and 1 GiB fill ----
+    def timed(fn, reps):
+        fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ev[0].record()
+        for _ in range(reps):
+            fn()
+        ev[1].record()
         torch.cuda.synchronize()
-        del a, b
+        return ev[0].elapsed_time(ev[1]) / reps
+
+    a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+    b = torch.empty_like(a)
+    copy_ms = timed(lambda: torch.mul(a, 1.0, out=b), 3)      # the same launch the --pmc calibration reads
+    fill_ms = timed(lambda: b.zero_(), 3)
+    calibration = dict(copy_GBs=2 * a.numel() * 4 / copy_ms / 1e6, fill_GBs=a.numel() * 4 / fill_ms / 1e6,
+                       note="torch elementwise copy (1 GiB read + 1 GiB write) and fill (1 GiB write)")
+    del a, b
+
+    # ---- saturation curve: one layer forward into the first n destination nodes ----
+    sweep = None
+    if args.sweep:
+        graph = m.egnn_nlist(pos, w.n_owned, w.box, w.pbc)
+        row = graph.row_ptr.cpu().numpy()
+        x_full.copy_(x0)
+        sweep = []
+        n = max(1, w.n_owned // 256)
+        while True:
+            n = min(n, w.n_owned)
+            k = int(row[n])
+            sub = B.Graph(graph.src[:k], graph.dst[:k], graph.row_ptr[:n + 1], graph.shift[:3 * k], n, w.n_total)
+            t_ms = timed(lambda: m.egnn_layer_forward(sub, pos, w.box, x_full, layers[0], ws, out=x_out[0][:n]), 10)
+            sweep.append(dict(n_dst=n, n_edges=k, ms=t_ms, edges_per_s=k / t_ms * 1e3))
+            if n == w.n_owned:
+                break
+            n *= 2
 
     ms_per_step = 1e3 * elapsed / args.steps
     value = n_edges * w.n_layers / (elapsed / args.steps)
@@ -231,6 +260,9 @@ def main():
                      "layer_edges_per_s": n_edges / (sum(layer_ms.values()) * 1e-3)},
     }
     out["training_step"] = training
+    out["hbm_calibration"] = calibration
+    if sweep is not None:
+        out["saturation_sweep"] = sweep
     if not args.no_cpu_baseline:
         g = U.oracle_graph(w)
         out["cpu_baseline"] = cpu_baseline(w, wt, g, agg, min(args.cpu_nodes, w.n_owned))
