@@ -77,6 +77,8 @@ def main():
     ap.add_argument("--cpu-nodes", type=int, default=1024)
     ap.add_argument("--train-steps", type=int, default=3,
                     help="training steps (forward + loss + reverse pass, config 5) timed after the main region; 0 = skip")
+    ap.add_argument("--fused", type=int, default=0, choices=[0, 1],
+                    help="1: radial weights and messages in one kernel (weights never written to memory)")
     ap.add_argument("--sweep", action="store_true",
                     help="also time one layer forward on growing prefixes of the destination nodes (saturation curve)")
     args = ap.parse_args()
@@ -108,6 +110,7 @@ def main():
     n_edges = g0.n_edges
     agg = n_edges / max(1, w.n_owned)
     m = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, agg, n_layers=w.n_layers, orb_l=w.orb_l)
+    m.egnn_set_option(B.OPT_FUSED, args.fused)
     ws = m.workspace(g0)
     x_out = [torch.empty((w.n_owned, m.dim, w.channels), dtype=torch.float32, device="cuda") for _ in range(2)]
     H = torch.empty((n_edges, m.n_orb, m.n_orb), dtype=torch.float32, device="cuda") if w.readout else None

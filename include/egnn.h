@@ -137,11 +137,11 @@ int egnn_tp_segsum(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, cons
 int egnn_node_mix(egnn_ctx* ctx, const float* x1, const float* W1, const float* x2, const float* W2,
                   float* y, int32_t n_nodes, void* stream);
 
-/* Options.  EGNN_OPT_FUSED (default 0): when 1, egnn_layer_forward with its own radial MLP and 16, 32 or 64
- * channels produces and consumes the radial weights inside one kernel (they are never written to memory);
- * when 0 it goes through the materialised weight tensor (S3 then S4), as it always does for caller-supplied
- * weights and other channel counts.  Both routes compute the same function; the two-kernel route is the faster
- * one at present. */
+/* Options.  EGNN_OPT_FUSED (default 0): when 1, egnn_layer_forward with its own radial MLP, lmax >= 1, a power of
+ * two >= 8 channels and at most 32 radial bases produces and consumes the radial weights inside one kernel (they
+ * are never written to memory); when 0 it goes through the materialised weight tensor (S3 then S4), as it always
+ * does for caller-supplied weights and other shapes.  Both routes compute the same function; the two-kernel route
+ * is the faster one at present. */
 #define EGNN_OPT_FUSED 1
 int egnn_set_option(egnn_ctx* ctx, int32_t option, int32_t value);
 

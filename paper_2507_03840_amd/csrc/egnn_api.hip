@@ -204,13 +204,20 @@ static size_t readout_tab_ints(const egnn_ctx* ctx) {
   return (size_t)2 * nq + 2 * ctx->n_slots + nq + 1 + ctx->unc_q.size();
 }
 
+// the weight tensor of a layer, or the (much smaller, except for tiny models) scratch of the fused route in its place
+static size_t layer_w_bytes(const egnn_ctx* ctx, int64_t n_edges) {
+  const size_t w = (size_t)n_edges * ctx->n_paths[0] * ctx->desc.channels * sizeof(float);
+  const size_t f = egnn_fused_supported(ctx) ? egnn_fused_scratch_bytes(ctx, n_edges) : 0;
+  return w > f ? w : f;
+}
+
 static size_t layer_ws(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, int32_t n_total, int with_w) {
   const size_t row = (size_t)(ctx->desc.lmax + 1) * (ctx->desc.lmax + 1) * ctx->desc.channels * sizeof(float);
   Carver c{nullptr, 0};
   c.take((size_t)n_edges * 16);
   c.take((size_t)n_total * row);
   c.take((size_t)n_owned * row);
-  if (with_w) c.take((size_t)n_edges * ctx->n_paths[0] * ctx->desc.channels * sizeof(float));
+  if (with_w) c.take(layer_w_bytes(ctx, n_edges));
   if (with_w) c.take(egnn_radial_ws_bytes(ctx, 0));
   return c.used;
 }
@@ -305,14 +312,15 @@ extern "C" int egnn_layer_forward(egnn_ctx* ctx, const egnn_graph* g, const floa
   float* rhat_d = (float*)c.take((size_t)g->n_edges * 16);
   float* h = (float*)c.take((size_t)g->n_total * row);
   float* a = (float*)c.take((size_t)g->n_owned * row);
-  float* w = with_w ? (float*)c.take((size_t)g->n_edges * ctx->n_paths[0] * ctx->desc.channels * sizeof(float))
-                    : nullptr;
+  const size_t w_bytes = with_w ? layer_w_bytes(ctx, g->n_edges) : 0;
+  float* w = with_w ? (float*)c.take(w_bytes) : nullptr;
   void* w2s = with_w ? c.take(egnn_radial_ws_bytes(ctx, 0)) : nullptr;
   StageTimer tm(ctx, st, 0);
   if ((rc = egnn_launch_geometry(ctx, g, pos, box, rhat_d, nullptr, nullptr, nullptr, st))) return rc;
   tm.mark(0);
   // Default: S3 writes the weight tensor, S4 reads it.  Opt-in (EGNN_OPT_FUSED): the weights are produced and
   // consumed inside one kernel and never leave the chip.
+  // (the scratch of the fused route lives where the weight tensor would be)
   const bool fused = with_w && ctx->use_fused && egnn_fused_supported(ctx);
   if (fused) {
     if (g->n_edges > 0 && (rc = egnn_launch_split_w2(ctx, 0, W_r2, w2s, st))) return rc;
@@ -323,7 +331,7 @@ extern "C" int egnn_layer_forward(egnn_ctx* ctx, const egnn_graph* g, const floa
   if ((rc = egnn_launch_node_mix(ctx, x_in, W_pre, nullptr, nullptr, h, g->n_total, st))) return rc;
   tm.mark(2);
   if (fused) {
-    if ((rc = egnn_launch_layer_fused(ctx, g, rhat_d, h, W_r1, w2s, a, st))) return rc;
+    if ((rc = egnn_launch_layer_fused(ctx, g, rhat_d, h, W_r1, w2s, w, w_bytes, a, st))) return rc;
   } else {
     if ((rc = egnn_launch_tp_segsum(ctx, g, rhat_d, h, with_w ? w : w_edge, a, st))) return rc;
   }

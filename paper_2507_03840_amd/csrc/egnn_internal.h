@@ -96,8 +96,9 @@ int egnn_launch_radial(egnn_ctx*, int which, const float* rhat_d, int64_t n_edge
 size_t egnn_radial_ws_bytes(const egnn_ctx*, int which);
 int egnn_launch_split_w2(egnn_ctx*, int which, const float* W_r2, void* scratch, hipStream_t);
 bool egnn_fused_supported(const egnn_ctx*);
+size_t egnn_fused_scratch_bytes(const egnn_ctx*, int64_t n_edges);
 int egnn_launch_layer_fused(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* h, const float* W_r1,
-                            const void* W2s, float* a, hipStream_t);
+                            const void* W2s, void* scratch, size_t scratch_bytes, float* a, hipStream_t);
 int egnn_launch_geometry(egnn_ctx*, const egnn_graph*, const float* pos, const float box[3], float* rhat_d,
                          float* Y, float* rbf, float* fc, hipStream_t);
 int egnn_launch_readout(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* zs, const float* zt,

@@ -205,15 +205,18 @@ def test_model_forward_small_shapes(B, lmax, E, periodic, n, n_owned):
     _model_forward_small(B, lmax, E, periodic, n, n_owned, False)
 
 
-@pytest.mark.parametrize("lmax,E,n,n_owned", [(1, 16, 120, 120), (2, 64, 100, 60), (3, 32, 150, 90), (4, 16, 70, 70),
-                                               (0, 32, 50, 50), (4, 64, 90, 70)])
-def test_model_forward_small_shapes_fused(B, lmax, E, n, n_owned):
-    _model_forward_small(B, lmax, E, False, n, n_owned, True)
+@pytest.mark.parametrize("lmax,E,n,n_owned,r_cut", [(1, 16, 120, 120, 4.0), (2, 64, 100, 60, 4.0), (3, 32, 150, 90, 4.0),
+                                                     (4, 16, 70, 70, 4.0), (0, 32, 50, 50, 4.0), (4, 64, 90, 70, 4.0),
+                                                     (1, 8, 60, 60, 4.0), (4, 128, 60, 40, 4.0), (3, 8, 150, 90, 4.0),
+                                                     # up to ~300 incoming edges per node: several 128-edge tiles, ragged tails
+                                                     (2, 8, 330, 25, 9.5), (4, 16, 330, 12, 9.5)])
+def test_model_forward_small_shapes_fused(B, lmax, E, n, n_owned, r_cut):
+    _model_forward_small(B, lmax, E, False, n, n_owned, True, r_cut)
 
 
-def _model_forward_small(B, lmax, E, periodic, n, n_owned, fused):
+def _model_forward_small(B, lmax, E, periodic, n, n_owned, fused, r_cut=4.0):
     """Small ragged cases over every supported degree and channel width, with halo rows, two layers, readout."""
-    w = _cluster(n, n_owned, lmax, E, n_rbf=6, r_cut=4.0, seed=30 + lmax, periodic=periodic)
+    w = _cluster(n, n_owned, lmax, E, n_rbf=6, r_cut=r_cut, seed=30 + lmax, periodic=periodic)
     w.n_layers = 2
     wt = U.model_weights(w)
     g = U.oracle_graph(w)
