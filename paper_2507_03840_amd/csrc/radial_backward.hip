@@ -5,11 +5,12 @@
 //   dpre[k][j]  = S[k][j] * sum_n dw[k][n] alpha_n W_r2[n][j],     S = fc * SiLU'(pre)
 //   dW_r1[j][b] = sum_k dpre[k][j] B_b(d_k)
 //
-// The two large contractions run on the fp32 matrix cores like the forward one; sums over edges are split into
-// fixed chunks whose partial results are added in a second pass, so the result does not depend on scheduling.
+// The two large contractions run on the matrix cores with split-bf16 operands like the forward one; sums over edges
+// are split into fixed chunks whose partial results are added in a second pass, so the result does not depend on
+// scheduling.
 #include "egnn_internal.h"
+#include "split_bf16.h"
 
-typedef float float16v __attribute__((ext_vector_type(16)));
 #define RB_KCHUNK 4096   // edges per partial of dW_r2
 #define RB_R1CHUNK 1024  // edges per partial of dW_r1
 
@@ -40,18 +41,118 @@ __global__ __launch_bounds__(256) void radial_hidden_kernel(const float4* __rest
   S[k * EGNN_HIDDEN + j] = fc * sig * (1.0f + pre * (1.0f - sig));
 }
 
-// dpre[k][j] = S[k][j] * sum_n dw[k][n] alpha_n W_r2[n][j]  (in place over S).  One wavefront: 64 edges x 64 units.
-__global__ __launch_bounds__(256) void radial_dpre_kernel(const float* __restrict__ dw, long n_edges,
-                                                          const float* __restrict__ W_r2, float* __restrict__ S,
-                                                          int PE, int log2E, PathAlpha alpha) {
+// ---- the two large contractions ------------------------------------------------------------------------------
+// Both stream dw (the big operand, read once) against a small operand that every wave needs.  The small operand is
+// cut into bf16 pieces beforehand and stored transposed in blocks of 64 contraction indices,
+//   T[step][j][piece][64]  (step = contraction index / 64, j = hidden unit),
+// which is the order an MFMA B operand is read in; one wave of each workgroup copies the next 24 KB block into one of
+// two LDS buffers while the other seven contract (same scheme as the forward kernel: a wave that only computes never
+// waits on a store, and the barriers carry LDS-only fences).  dw is cut into pieces on the fly, in registers.
+// Six piece products per fp32 product, smallest first: fp32-level accuracy at 6/16 of the fp32-MFMA cost.
+#define RB_WAVES 7                    // compute waves per workgroup
+#define RB_THREADS ((RB_WAVES + 1) * 64)
+#define RB_BROW4 25                   // uint4 per staged row: 24 of data (3 pieces x 64 bf16) + 1 of padding
+
+// src[r][64] (r < n_rows, times scale[r >> log2E] if scale_on) -> T[r / 64][j][piece][r % 64]; rows past n_rows are 0.
+// One workgroup per block of 64 rows; the 64 x 64 tile is turned in LDS so that both sides are contiguous.
+__global__ __launch_bounds__(256) void rb_split_transpose_kernel(const float* __restrict__ src, long n_rows,
+                                                                 uint16_t* __restrict__ T, int log2E, PathAlpha alpha,
+                                                                 int scale_on) {
+  __shared__ float tile[64][65];
+  const long r0 = (long)blockIdx.x * 64;
+  for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+    const int rr = i >> 6, j = i & 63;
+    const long r = r0 + rr;
+    tile[rr][j] = r < n_rows ? src[r * EGNN_HIDDEN + j] * (scale_on ? alpha.a[r >> log2E] : 1.0f) : 0.0f;
+  }
+  __syncthreads();
+  uint32_t* out = reinterpret_cast<uint32_t*>(T + (size_t)blockIdx.x * 64 * 3 * 64);
+  // thread -> (j, pair of rows): three 4-byte stores, consecutive threads write consecutive words of a piece row
+  for (int i = threadIdx.x; i < 64 * 32; i += 256) {
+    const int j = i >> 5, rp = i & 31;
+    const Split3 s0 = split3(tile[2 * rp][j]), s1 = split3(tile[2 * rp + 1][j]);
+    uint32_t* o = out + j * 96 + rp;
+    o[0] = pack2(s0.hi, s1.hi);
+    o[32] = pack2(s0.mid, s1.mid);
+    o[64] = pack2(s0.lo, s1.lo);
+  }
+}
+
+__device__ __forceinline__ void rb_release_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+}
+__device__ __forceinline__ void rb_barrier_acquire() {
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// the loader wave: block `step` of T -> sB[step & 1], one barrier per block (the loads of block s + 1 overlap the
+// compute waves' work on block s)
+__device__ __forceinline__ void rb_loader(const uint16_t* __restrict__ T, long first_step, int n_steps, uint4* sB, int lane) {
+  const uint4* src = reinterpret_cast<const uint4*>(T) + first_step * (64 * 24);
+  for (int s = 0; s < n_steps; ++s) {
+    uint4 v[24];
+#pragma unroll
+    for (int i = 0; i < 24; ++i) v[i] = src[(size_t)s * (64 * 24) + i * 64 + lane];
+    uint4* dst = sB + (s & 1) * (64 * RB_BROW4);
+#pragma unroll
+    for (int i = 0; i < 24; ++i) {
+      const int u = i * 64 + lane, row = u / 24, c16 = u - row * 24;
+      dst[row * RB_BROW4 + c16] = v[i];
+    }
+    rb_release_barrier();
+  }
+}
+
+// eight fp32 values -> the three bf16 pieces of an MFMA operand register
+__device__ __forceinline__ void rb_split8(const float (&x)[8], uint4& hi, uint4& mid, uint4& lo) {
+  uint32_t h[4], m[4], l[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const Split3 s0 = split3(x[2 * q]), s1 = split3(x[2 * q + 1]);
+    h[q] = pack2(s0.hi, s1.hi);
+    m[q] = pack2(s0.mid, s1.mid);
+    l[q] = pack2(s0.lo, s1.lo);
+  }
+  hi = make_uint4(h[0], h[1], h[2], h[3]);
+  mid = make_uint4(m[0], m[1], m[2], m[3]);
+  lo = make_uint4(l[0], l[1], l[2], l[3]);
+}
+
+// acc += A (pieces ah, am, al) x B (pieces b[0..2]) for one 16-wide contraction step
+__device__ __forceinline__ float16v rb_mma6(uint4 ah, uint4 am, uint4 al, const uint4 (&b)[3], float16v acc) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(al), as_bf16x8(b[0]), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ah), as_bf16x8(b[2]), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(am), as_bf16x8(b[1]), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(am), as_bf16x8(b[0]), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ah), as_bf16x8(b[1]), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ah), as_bf16x8(b[0]), acc, 0, 0, 0);
+  return acc;
+}
+
+// dpre[k][j] = S[k][j] * sum_n dw[k][n] alpha_n W_r2[n][j]  (in place over S).  W2T = T of (alpha W_r2), contraction
+// index n.  A compute wave owns 64 edges (two 32-row blocks) and all 64 units; lane l serves row/column l & 31 and
+// the half hh = l >> 5 of each 64-wide step: MFMA step t contracts n = 64 s + 32 hh + 8 t .. + 7.
+__global__ __launch_bounds__(RB_THREADS) void radial_dpre_kernel(const float* __restrict__ dw, long n_edges,
+                                                                 const uint16_t* __restrict__ W2T,
+                                                                 float* __restrict__ S, int PE, int n_steps) {
+  __shared__ uint4 sB[2 * 64 * RB_BROW4];
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
+  if (wave == RB_WAVES) {
+    rb_loader(W2T, 0, n_steps, sB, lane);
+    return;
+  }
   const int m = lane & 31, hh = lane >> 5;
-  const long e_base = ((long)blockIdx.x * 4 + wave) * 64;
-  if (e_base >= n_edges) return;
-  long e_row[2];
-  e_row[0] = e_base + m < n_edges ? e_base + m : n_edges - 1;
-  e_row[1] = e_base + 32 + m < n_edges ? e_base + 32 + m : n_edges - 1;
+  const long e_base = ((long)blockIdx.x * RB_WAVES + wave) * 64;
+  const float* row[2];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    long e = e_base + rb * 32 + m;
+    if (e >= n_edges) e = n_edges - 1;
+    row[rb] = dw + (size_t)e * PE + hh * 32;
+  }
   float16v acc[2][2];
 #pragma unroll
   for (int a = 0; a < 2; ++a)
@@ -60,96 +161,124 @@ __global__ __launch_bounds__(256) void radial_dpre_kernel(const float* __restric
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
 
-  for (int n0 = 0; n0 < PE; n0 += 64) {
-    float a_frag[2][32], b_frag[2][32];
-    const int nl = n0 + 32 * hh;   // first contraction index of this lane half
+  // dw of the next step is in flight while this one is contracted
+  float4 nxt[2][8];
+  auto fetch = [&](int s) {
+    const int nl = s * 64 + hh * 32;
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
-      const float4* row = reinterpret_cast<const float4*>(dw + (size_t)e_row[mb] * PE + nl);
+    for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (nl + 4 * q < PE) t = row[q];
-        a_frag[mb][4 * q + 0] = t.x;
-        a_frag[mb][4 * q + 1] = t.y;
-        a_frag[mb][4 * q + 2] = t.z;
-        a_frag[mb][4 * q + 3] = t.w;
+      for (int q = 0; q < 8; ++q)
+        nxt[rb][q] = (nl + 4 * q < PE) ? *reinterpret_cast<const float4*>(row[rb] + s * 64 + 4 * q)
+                                       : make_float4(0.f, 0.f, 0.f, 0.f);
+  };
+  fetch(0);
+  for (int s = 0; s < n_steps; ++s) {
+    float4 cur[2][8];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int q = 0; q < 8; ++q) cur[rb][q] = nxt[rb][q];
+    if (s + 1 < n_steps) fetch(s + 1);
+    rb_barrier_acquire();
+    const uint4* bbase = sB + (s & 1) * (64 * RB_BROW4) + hh * 4;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      uint4 ah[2], am[2], al[2];
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) {
+        const float4 u = cur[rb][2 * t], v = cur[rb][2 * t + 1];
+        const float x[8] = {u.x, u.y, u.z, u.w, v.x, v.y, v.z, v.w};
+        rb_split8(x, ah[rb], am[rb], al[rb]);
       }
-    }
 #pragma unroll
-    for (int s = 0; s < 32; ++s) {
-      const int n = nl + s;
-      float b0 = 0.0f, b1 = 0.0f;
-      if (n < PE) {
-        const float al = alpha.a[n >> log2E];
-        b0 = al * W_r2[(size_t)n * EGNN_HIDDEN + m];
-        b1 = al * W_r2[(size_t)n * EGNN_HIDDEN + 32 + m];
+      for (int cb = 0; cb < 2; ++cb) {
+        const uint4* brow = bbase + (m + 32 * cb) * RB_BROW4 + t;
+        const uint4 b[3] = {brow[0], brow[8], brow[16]};
+        acc[0][cb] = rb_mma6(ah[0], am[0], al[0], b, acc[0][cb]);
+        acc[1][cb] = rb_mma6(ah[1], am[1], al[1], b, acc[1][cb]);
       }
-      b_frag[0][s] = b0;
-      b_frag[1][s] = b1;
-    }
-#pragma unroll
-    for (int s = 0; s < 32; ++s) {
-      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_frag[0][s], b_frag[0][s], acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_frag[0][s], b_frag[1][s], acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_frag[1][s], b_frag[0][s], acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_frag[1][s], b_frag[1][s], acc[1][1], 0, 0, 0);
     }
   }
 #pragma unroll
-  for (int mb = 0; mb < 2; ++mb)
+  for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
+    for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const long e = e_base + mb * 32 + 8 * (i >> 2) + 4 * hh + (i & 3);
+        const long e = e_base + rb * 32 + 8 * (i >> 2) + 4 * hh + (i & 3);
         if (e < n_edges) {
-          const size_t at = (size_t)e * EGNN_HIDDEN + nb * 32 + m;
-          S[at] = S[at] * acc[mb][nb][i];
+          const size_t at = (size_t)e * EGNN_HIDDEN + cb * 32 + m;
+          S[at] = S[at] * acc[rb][cb][i];
         }
       }
 }
 
-// Partial dW_r2 over one chunk of edges: grid = (edge chunks, tiles of 128 rows n); wave = 32 rows x 64 units.
-__global__ __launch_bounds__(256) void radial_dw2_kernel(const float* __restrict__ dw, long n_edges,
-                                                         const float* __restrict__ G, float* __restrict__ partial,
-                                                         int PE, int log2E, PathAlpha alpha) {
+// Partial dW_r2 over one chunk of RB_KCHUNK edges: partial[chunk][n][j] = alpha_n sum_{k in chunk} dw[k][n] G[k][j].
+// GT = T of G, contraction index k.  grid = (tiles of 32 * RB_WAVES rows n, edge chunks); a compute wave owns 32 rows n
+// and all 64 units; MFMA step t of a 64-edge step contracts k = 64 s + 32 hh + 8 t .. + 7.
+__global__ __launch_bounds__(RB_THREADS) void radial_dw2_kernel(const float* __restrict__ dw, long n_edges,
+                                                                const uint16_t* __restrict__ GT,
+                                                                float* __restrict__ partial, int PE, int log2E,
+                                                                PathAlpha alpha) {
+  __shared__ uint4 sB[2 * 64 * RB_BROW4];
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int m = lane & 31, hh = lane >> 5;
-  const int n_row = (blockIdx.y * 4 + wave) * 32 + m;     // row of dW_r2 this lane feeds as the A operand
-  if ((blockIdx.y * 4 + wave) * 32 >= PE) return;
-  const bool row_ok = n_row < PE;
-  const long k_begin = (long)blockIdx.x * RB_KCHUNK;
+  // blockIdx.x = tile of rows n (fastest: the workgroups that read the other columns of the same edges run at the
+  // same time, so the rows of dw are fetched whole), blockIdx.y = edge chunk
+  const long k_begin = (long)blockIdx.y * RB_KCHUNK;
   long k_end = k_begin + RB_KCHUNK;
   if (k_end > n_edges) k_end = n_edges;
-  float16v acc0, acc1;
+  const int n_steps = (int)((k_end - k_begin + 63) / 64);
+  if (wave == RB_WAVES) {
+    rb_loader(GT, k_begin / 64, n_steps, sB, lane);
+    return;
+  }
+  const int m = lane & 31, hh = lane >> 5;
+  const int n_tile = (blockIdx.x * RB_WAVES + wave) * 32;
+  const int n_row = n_tile + m;                       // row of dW_r2 this lane feeds as the A operand
+  const bool row_ok = n_row < PE;
+  const float* col = dw + (row_ok ? n_row : 0);
+  float16v acc[2];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) acc0[i] = acc1[i] = 0.0f;
-  for (long k0 = k_begin; k0 < k_end; k0 += 64) {
-    float a_frag[32], b0[32], b1[32];
+  for (int i = 0; i < 16; ++i) acc[0][i] = acc[1][i] = 0.0f;
+
+  float nxt[32];
+  auto fetch = [&](int s) {
+    const long kl = k_begin + (long)s * 64 + hh * 32;
 #pragma unroll
-    for (int s = 0; s < 32; ++s) {
-      const long k = k0 + 32 * hh + s;
-      const bool ok = k < k_end;
-      a_frag[s] = (ok && row_ok) ? dw[(size_t)k * PE + n_row] : 0.0f;
-      b0[s] = ok ? G[(size_t)k * EGNN_HIDDEN + m] : 0.0f;
-      b1[s] = ok ? G[(size_t)k * EGNN_HIDDEN + 32 + m] : 0.0f;
-    }
+    for (int q = 0; q < 32; ++q) nxt[q] = (row_ok && kl + q < k_end) ? col[(size_t)(kl + q) * PE] : 0.0f;
+  };
+  fetch(0);
+  for (int s = 0; s < n_steps; ++s) {
+    float cur[32];
 #pragma unroll
-    for (int s = 0; s < 32; ++s) {
-      acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a_frag[s], b0[s], acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a_frag[s], b1[s], acc1, 0, 0, 0);
+    for (int q = 0; q < 32; ++q) cur[q] = nxt[q];
+    if (s + 1 < n_steps) fetch(s + 1);
+    rb_barrier_acquire();
+    const uint4* bbase = sB + (s & 1) * (64 * RB_BROW4) + hh * 4;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const float x[8] = {cur[8 * t], cur[8 * t + 1], cur[8 * t + 2], cur[8 * t + 3],
+                          cur[8 * t + 4], cur[8 * t + 5], cur[8 * t + 6], cur[8 * t + 7]};
+      uint4 ah, am, al;
+      rb_split8(x, ah, am, al);
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) {
+        const uint4* brow = bbase + (m + 32 * cb) * RB_BROW4 + t;
+        const uint4 b[3] = {brow[0], brow[8], brow[16]};
+        acc[cb] = rb_mma6(ah, am, al, b, acc[cb]);
+      }
     }
   }
-  float* out = partial + (size_t)blockIdx.x * PE * EGNN_HIDDEN;
+  float* out = partial + (size_t)blockIdx.y * PE * EGNN_HIDDEN;
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
-    const int n = (blockIdx.y * 4 + wave) * 32 + 8 * (i >> 2) + 4 * hh + (i & 3);
+    const int n = n_tile + 8 * (i >> 2) + 4 * hh + (i & 3);
     if (n < PE) {
       const float al = alpha.a[n >> log2E];
-      out[(size_t)n * EGNN_HIDDEN + m] = al * acc0[i];
-      out[(size_t)n * EGNN_HIDDEN + 32 + m] = al * acc1[i];
+      out[(size_t)n * EGNN_HIDDEN + m] = al * acc[0][i];
+      out[(size_t)n * EGNN_HIDDEN + 32 + m] = al * acc[1][i];
     }
   }
 }
@@ -186,12 +315,14 @@ __global__ __launch_bounds__(256) void radial_dw1_kernel(const float4* __restric
 }
 
 static size_t a256(size_t n) { return (n + 255) & ~(size_t)255; }
+static size_t rb_pad64(size_t n) { return (n + 63) & ~(size_t)63; }
 
 size_t egnn_radial_backward_ws_bytes(const egnn_ctx* ctx, int which, int64_t n_edges) {
   const size_t PE = (size_t)ctx->n_paths[which] * ctx->desc.channels;
   const size_t kc = (size_t)((n_edges + RB_KCHUNK - 1) / RB_KCHUNK), rc = (size_t)((n_edges + RB_R1CHUNK - 1) / RB_R1CHUNK);
   return 2 * a256((size_t)n_edges * EGNN_HIDDEN * 4) + a256(kc * PE * EGNN_HIDDEN * 4) +
-         a256(rc * EGNN_HIDDEN * ctx->desc.n_rbf * 4);
+         a256(rc * EGNN_HIDDEN * ctx->desc.n_rbf * 4) + a256(rb_pad64(PE) * EGNN_HIDDEN * 6) +
+         a256(rb_pad64(n_edges) * EGNN_HIDDEN * 6);
 }
 
 int egnn_launch_radial_backward(egnn_ctx* ctx, int which, const float* rhat_d, int64_t n_edges, const float* W_r1,
@@ -212,16 +343,27 @@ int egnn_launch_radial_backward(egnn_ctx* ctx, int which, const float* rhat_d, i
   float* S = (float*)(base + a256((size_t)n_edges * EGNN_HIDDEN * 4));
   float* part2 = (float*)(base + 2 * a256((size_t)n_edges * EGNN_HIDDEN * 4));
   float* part1 = (float*)((char*)part2 + a256((size_t)kc * PE * EGNN_HIDDEN * 4));
+  uint16_t* W2T = (uint16_t*)((char*)part1 + a256((size_t)r1c * EGNN_HIDDEN * n_rbf * 4));
+  uint16_t* GT = (uint16_t*)((char*)W2T + a256(rb_pad64(PE) * EGNN_HIDDEN * 6));
+  const long pe_pad = (long)rb_pad64(PE), ne_pad = (long)rb_pad64(n_edges);
   const float4* rd = reinterpret_cast<const float4*>(rhat_d);
   hipLaunchKernelGGL(radial_hidden_kernel, dim3((unsigned)((n_edges + 3) / 4)), dim3(256), 0, st, rd, (long)n_edges,
                      W_r1, G, S, n_rbf, ctx->desc.r_cut);
   EGNN_LAUNCH_CHECK(ctx, "radial_hidden_kernel");
-  hipLaunchKernelGGL(radial_dw2_kernel, dim3(kc, (PE + 127) / 128), dim3(256), 0, st, dw, (long)n_edges, G, part2, PE,
-                     ctx->log2_channels, al);
+  hipLaunchKernelGGL(rb_split_transpose_kernel, dim3((unsigned)(ne_pad / 64)), dim3(256), 0, st, G, (long)n_edges, GT, 0,
+                     al, 0);
+  EGNN_LAUNCH_CHECK(ctx, "rb_split_transpose_kernel(G)");
+  hipLaunchKernelGGL(rb_split_transpose_kernel, dim3((unsigned)(pe_pad / 64)), dim3(256), 0, st, W_r2, (long)PE, W2T,
+                     ctx->log2_channels, al, 1);
+  EGNN_LAUNCH_CHECK(ctx, "rb_split_transpose_kernel(W_r2)");
+  const int n_tile = 32 * RB_WAVES;
+  hipLaunchKernelGGL(radial_dw2_kernel, dim3((PE + n_tile - 1) / n_tile, kc), dim3(RB_THREADS), 0, st, dw, (long)n_edges, GT,
+                     part2, PE, ctx->log2_channels, al);
   EGNN_LAUNCH_CHECK(ctx, "radial_dw2_kernel");
   if ((rc = egnn_launch_reduce_partials(ctx, part2, kc, (long)PE * EGNN_HIDDEN, dW_r2, 1.0f, st))) return rc;
-  hipLaunchKernelGGL(radial_dpre_kernel, dim3((unsigned)((n_edges + 255) / 256)), dim3(256), 0, st, dw, (long)n_edges,
-                     W_r2, S, PE, ctx->log2_channels, al);
+  const long per_wg = 64L * RB_WAVES;
+  hipLaunchKernelGGL(radial_dpre_kernel, dim3((unsigned)((n_edges + per_wg - 1) / per_wg)), dim3(RB_THREADS), 0, st, dw,
+                     (long)n_edges, W2T, S, PE, (int)(pe_pad / 64));
   EGNN_LAUNCH_CHECK(ctx, "radial_dpre_kernel");
   hipLaunchKernelGGL(radial_dw1_kernel, dim3(r1c), dim3(256), 0, st, rd, (long)n_edges, S, part1, n_rbf,
                      ctx->desc.r_cut);
