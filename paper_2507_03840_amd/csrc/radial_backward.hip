@@ -163,14 +163,18 @@ __global__ __launch_bounds__(RB_THREADS) void radial_dpre_kernel(const float* __
 
   // dw of the next step is in flight while this one is contracted
   float4 nxt[2][8];
+  // (no branch around a load: indices past the row are clamped, and the value is replaced by zero where it is used --
+  // not here, which would make the wave wait for the load it has just issued)
   auto fetch = [&](int s) {
     const int nl = s * 64 + hh * 32;
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-      for (int q = 0; q < 8; ++q)
-        nxt[rb][q] = (nl + 4 * q < PE) ? *reinterpret_cast<const float4*>(row[rb] + s * 64 + 4 * q)
-                                       : make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int q = 0; q < 8; ++q) {
+        const int n = nl + 4 * q;
+        const bool ok = n < PE;
+        nxt[rb][q] = *reinterpret_cast<const float4*>(row[rb] - hh * 32 + (ok ? n : PE - 4));
+      }
   };
   fetch(0);
   for (int s = 0; s < n_steps; ++s) {
@@ -187,7 +191,9 @@ __global__ __launch_bounds__(RB_THREADS) void radial_dpre_kernel(const float* __
       uint4 ah[2], am[2], al[2];
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb) {
-        const float4 u = cur[rb][2 * t], v = cur[rb][2 * t + 1];
+        const int n = s * 64 + hh * 32 + 8 * t;
+        const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+        const float4 u = n < PE ? cur[rb][2 * t] : zero, v = n + 4 < PE ? cur[rb][2 * t + 1] : zero;
         const float x[8] = {u.x, u.y, u.z, u.w, v.x, v.y, v.z, v.w};
         rb_split8(x, ah[rb], am[rb], al[rb]);
       }
@@ -244,10 +250,15 @@ __global__ __launch_bounds__(RB_THREADS) void radial_dw2_kernel(const float* __r
   for (int i = 0; i < 16; ++i) acc[0][i] = acc[1][i] = 0.0f;
 
   float nxt[32];
+  // (no branch around a load: edges past the chunk are clamped to its last edge; the value is replaced by zero where
+  // it is used)
   auto fetch = [&](int s) {
     const long kl = k_begin + (long)s * 64 + hh * 32;
+    const long kb = kl < k_end ? kl : k_end - 1;
+    const int qmax = (int)(k_end - 1 - kb < 31 ? k_end - 1 - kb : 31);
+    const float* p = col + (size_t)kb * PE;
 #pragma unroll
-    for (int q = 0; q < 32; ++q) nxt[q] = (row_ok && kl + q < k_end) ? col[(size_t)(kl + q) * PE] : 0.0f;
+    for (int q = 0; q < 32; ++q) nxt[q] = p[(q < qmax ? q : qmax) * PE];
   };
   fetch(0);
   for (int s = 0; s < n_steps; ++s) {
@@ -259,8 +270,10 @@ __global__ __launch_bounds__(RB_THREADS) void radial_dw2_kernel(const float* __r
     const uint4* bbase = sB + (s & 1) * (64 * RB_BROW4) + hh * 4;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      const float x[8] = {cur[8 * t], cur[8 * t + 1], cur[8 * t + 2], cur[8 * t + 3],
-                          cur[8 * t + 4], cur[8 * t + 5], cur[8 * t + 6], cur[8 * t + 7]};
+      const long kt = k_begin + (long)s * 64 + hh * 32 + 8 * t;
+      float x[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) x[q] = (row_ok && kt + q < k_end) ? cur[8 * t + q] : 0.0f;
       uint4 ah, am, al;
       rb_split8(x, ah, am, al);
 #pragma unroll
