@@ -310,34 +310,49 @@ __global__ __launch_bounds__(RB_THREADS) void radial_dw2_kernel(const float* __r
   }
 }
 
-// Partial dW_r1 over one chunk of edges: thread = (hidden unit j, group of 8 basis functions).
+// Partial dW_r1 over one chunk of edges.  Tiles of 64 edges: the basis values of the tile are computed once into LDS,
+// then thread (hidden unit j, wave w) takes the edges e = w mod 4 of the tile against all bases; the four waves'
+// sums are added in fixed order at the end.
 __global__ __launch_bounds__(256) void radial_dw1_kernel(const float4* __restrict__ rhat_d, long n_edges,
                                                          const float* __restrict__ dpre, float* __restrict__ partial,
                                                          int n_rbf, float r_cut) {
+  __shared__ float sBas[64][33];
+  __shared__ float red[4][EGNN_HIDDEN][33];
   const int tid = threadIdx.x;
-  const int j = tid & 63, bg = tid >> 6;
+  const int j = tid & 63, w = tid >> 6;
   const long k_begin = (long)blockIdx.x * RB_R1CHUNK;
   long k_end = k_begin + RB_R1CHUNK;
   if (k_end > n_edges) k_end = n_edges;
   const float step = r_cut / (float)(n_rbf - 1);
   const float inv2s2 = 0.5f / (step * step);
-  float acc[8];
+  float acc[32];
 #pragma unroll
-  for (int q = 0; q < 8; ++q) acc[q] = 0.0f;
-  for (long k = k_begin; k < k_end; ++k) {
-    const float d = rhat_d[k].w;
-    const float dp = dpre[k * EGNN_HIDDEN + j];
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const int b = bg * 8 + q;
-      if (b < n_rbf) acc[q] += dp * rb_basis(d, b, step, inv2s2);
+  for (int b = 0; b < 32; ++b) acc[b] = 0.0f;
+  for (long k0 = k_begin; k0 < k_end; k0 += 64) {
+    for (int i = tid; i < 64 * n_rbf; i += 256) {
+      const int e = i / n_rbf, b = i - e * n_rbf;
+      const long k = k0 + e;
+      sBas[e][b] = k < k_end ? rb_basis(rhat_d[k].w, b, step, inv2s2) : 0.0f;
     }
-  }
-  float* out = partial + (size_t)blockIdx.x * EGNN_HIDDEN * n_rbf;
+    __syncthreads();
+#pragma unroll 4
+    for (int ee = 0; ee < 16; ++ee) {
+      const int e = 4 * ee + w;
+      const long k = k0 + e;
+      const float dp = k < k_end ? dpre[k * EGNN_HIDDEN + j] : 0.0f;
 #pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    const int b = bg * 8 + q;
-    if (b < n_rbf) out[j * n_rbf + b] = acc[q];
+      for (int b = 0; b < 32; ++b)
+        if (b < n_rbf) acc[b] += dp * sBas[e][b];
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int b = 0; b < 32; ++b) red[w][j][b] = acc[b];
+  __syncthreads();
+  float* out = partial + (size_t)blockIdx.x * EGNN_HIDDEN * n_rbf;
+  for (int i = tid; i < EGNN_HIDDEN * n_rbf; i += 256) {
+    const int jj = i / n_rbf, b = i - jj * n_rbf;
+    out[i] = (red[0][jj][b] + red[1][jj][b]) + (red[2][jj][b] + red[3][jj][b]);
   }
 }
 
