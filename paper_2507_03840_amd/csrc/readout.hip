@@ -5,12 +5,13 @@
 // Clebsch-Gordan transform (Eq. 1 read backwards) from the coupled components q[o][M] to the orbital
 // block H[(a,m_a)][(b,m_b)].
 //
-// As in the message kernel the product is evaluated in the bond frame.  The collapse acts on the channel
-// axis only, so it commutes with the rotation: the E-channel result is collapsed while still in the bond
-// frame and only the n_orb^2 collapsed numbers are rotated back (one (2L+1)-vector per coupled slot).
+// As in the message kernel the product is evaluated in the bond frame and rotated back per lane (lane = channel:
+// all lanes run the same rotation code; rotating the collapsed numbers instead -- fewer of them, since the collapse
+// commutes with the rotation -- needs one rotation per coupled slot with the degree varying from lane to lane,
+// which a wavefront executes one degree after the other and which costs more than it saves).
 //
-// A group of E lanes (a "slot") works on one edge: lane = channel for the product, then the lanes share
-// the n_orb^2 collapsed outputs among themselves through LDS.
+// A group of E lanes works on one edge: lane = channel for the product, then the lanes share the n_orb^2 collapsed
+// outputs among themselves through LDS.  The small index tables of the collapse and of the uncoupling live in LDS.
 #include "egnn_internal.h"
 #include "bond_frame.h"
 
@@ -25,18 +26,8 @@ struct ReadoutTabs {
   const int* unc_ptr;   // [nq+1]
   const int* unc_q;     // [nnz]
   const float* unc_c;   // [nnz]
-  int nq, n_slots, n_vrows;
+  int nq, n_slots, n_vrows, nnz;
 };
-
-template <int L>
-__device__ __forceinline__ void rotate_slot_back(float* q, const BondTrig& t) {
-  float v[2 * L + 1];
-#pragma unroll
-  for (int i = 0; i < 2 * L + 1; ++i) v[i] = q[i];
-  egnn_from_bond_frame_l<L>(v, t);
-#pragma unroll
-  for (int i = 0; i < 2 * L + 1; ++i) q[i] = v[i];
-}
 
 template <int LMAX, int log2E>
 __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ src, const int* __restrict__ dst,
@@ -56,17 +47,31 @@ __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ sr
   float* sV = smem;                                      // [n_vrows][E+4]
   float* su = sV + (size_t)tb.n_vrows * us + (size_t)slot * RO_D * us;    // this slot: [25][E+4]
   float* sq = smem + (size_t)tb.n_vrows * us + (size_t)n_slots * RO_D * us + (size_t)slot * tb.nq;  // this slot: [nq]
+  // tables: offsets of the two rows of each collapsed value, CSR of the uncoupling
+  int* s_urow = reinterpret_cast<int*>(smem + (size_t)tb.n_vrows * us + (size_t)n_slots * RO_D * us + (size_t)n_slots * tb.nq);
+  int* s_vrow = s_urow + tb.nq;
+  int* s_ptr = s_vrow + tb.nq;          // [nq + 1]
+  int* s_uq = s_ptr + tb.nq + 1;        // [nnz]
+  float* s_uc = reinterpret_cast<float*>(s_uq + tb.nnz);   // [nnz]
 
   for (int i = tid; i < tb.n_vrows * E; i += 256) {
     const int r = i >> log2E, cc = i & (E - 1);
     sV[r * us + cc] = V[i];
+  }
+  for (int i = tid; i < tb.nq; i += 256) {
+    s_urow[i] = tb.q_row[i] * us;
+    s_vrow[i] = tb.q_vrow[i] * us;
+  }
+  for (int i = tid; i <= tb.nq; i += 256) s_ptr[i] = tb.unc_ptr[i];
+  for (int i = tid; i < tb.nnz; i += 256) {
+    s_uq[i] = tb.unc_q[i];
+    s_uc[i] = tb.unc_c[i];
   }
 
   const long k_base = (long)blockIdx.x * n_slots * RO_ITERS;
   for (int it = 0; it < RO_ITERS; ++it) {
     const long k = k_base + (long)it * n_slots + slot;
     const bool live = k < n_edges;
-    BondTrig t;
     if (live) {
       const int s = src[k], d = dst[k];
       const float4 g = rhat_d[k];
@@ -78,17 +83,19 @@ __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ sr
       for (int p = 0; p < P; ++p) wr[p] = __builtin_nontemporal_load(wp + ((size_t)p << log2E));
 #pragma unroll
       for (int i = 0; i < D; ++i) v[i] = zsp[(size_t)i << log2E] + ztp[(size_t)i << log2E];
+      BondTrig t;
       egnn_bond_trig<4>(g.x, g.y, g.z, t);
       egnn_to_bond_frame<LMAX>(v, t);
       Mid::run(v, wr, o);
+      egnn_from_bond_frame<4>(o, t);
 #pragma unroll
       for (int i = 0; i < RO_D; ++i) su[i * us + c] = o[i];
     }
-    __syncthreads();
+    __syncthreads();   // (also orders the table fill before the first use)
     if (live) {
       for (int q = c; q < tb.nq; q += E) {
-        const float4* ur = reinterpret_cast<const float4*>(su + tb.q_row[q] * us);
-        const float4* vr = reinterpret_cast<const float4*>(sV + tb.q_vrow[q] * us);
+        const float4* ur = reinterpret_cast<const float4*>(su + s_urow[q]);
+        const float4* vr = reinterpret_cast<const float4*>(sV + s_vrow[q]);
         float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
 #pragma unroll
         for (int cc = 0; cc < E / 4; ++cc) {
@@ -103,26 +110,15 @@ __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ sr
     }
     __syncthreads();
     if (live) {
-      for (int sl = c; sl < tb.n_slots; sl += E) {
-        float* q = sq + tb.slot_qoff[sl];
-        switch (tb.slot_L[sl]) {
-          case 1: rotate_slot_back<1>(q, t); break;
-          case 2: rotate_slot_back<2>(q, t); break;
-          case 3: rotate_slot_back<3>(q, t); break;
-          case 4: rotate_slot_back<4>(q, t); break;
-          default: break;
-        }
-      }
-    }
-    __syncthreads();
-    if (live) {
       float* out = H + (size_t)k * tb.nq;
       for (int q = c; q < tb.nq; q += E) {
         float sum = 0.0f;
-        for (int n = tb.unc_ptr[q]; n < tb.unc_ptr[q + 1]; ++n) sum += tb.unc_c[n] * sq[tb.unc_q[n]];
+        for (int n = s_ptr[q]; n < s_ptr[q + 1]; ++n) sum += s_uc[n] * sq[s_uq[n]];
         __builtin_nontemporal_store(sum, out + q);
       }
     }
+    // the next iteration overwrites su before its first barrier and sq after it: sq is safe (barrier in between),
+    // su needs the collapse of this iteration to be over -- it is, the barrier above
   }
 }
 
@@ -131,7 +127,8 @@ static int launch_readout(egnn_ctx* ctx, const egnn_graph* g, const float4* rd, 
                           const float* w, const float* V, const ReadoutTabs& tb, float* H, hipStream_t stream) {
   constexpr int E = 1 << LE, n_slots = 256 / E;
   const size_t shmem = ((size_t)tb.n_vrows * (E + 4) + (size_t)n_slots * RO_D * (E + 4) + (size_t)n_slots * tb.nq) *
-                       sizeof(float);
+                           sizeof(float) +
+                       ((size_t)3 * tb.nq + 1 + 2 * (size_t)tb.nnz) * sizeof(int);
   const long per_wg = (long)n_slots * RO_ITERS;
   dim3 grid((unsigned)((g->n_edges + per_wg - 1) / per_wg)), block(256);
   auto kern = readout_kernel<L, LE>;
@@ -164,6 +161,7 @@ int egnn_launch_readout(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d,
   tb.unc_ptr = tb.slot_qoff + ctx->n_slots;
   tb.unc_q = tb.unc_ptr + nq + 1;
   tb.unc_c = tab_f;
+  tb.nnz = (int)ctx->unc_c.size();
   const float4* rd = reinterpret_cast<const float4*>(rhat_d);
 #define CASE(L, LE) \
   if (ctx->desc.lmax == L && ctx->log2_channels == LE) return launch_readout<L, LE>(ctx, g, rd, zs, zt, w, V, tb, H, stream);
