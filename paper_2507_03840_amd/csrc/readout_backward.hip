@@ -1,13 +1,14 @@
 // Reverse pass of S6 (H_ij readout), per edge.
 //
-// Forward (bond frame, ' = rotated by D_k):  u' = Mid(D z ; w),  q'[o][M] = sum_c V[o][c] u'[(L,M)][c],
-// q = D^T q' per slot,  H = C q.  Given dH:
-//     dq = C^T dH,  dq' = D dq per slot,
-//     dV[o][c]  += sum_M dq'[o][M] u'[(L,M)][c]            (summed over all edges)
-//     du'[(L,M)][c] = sum_o V[o][c] dq'[o][M]
+// Forward (' = in the bond frame, rotated by D_k):  u = D^T Mid(D z ; w),  q[o][M] = sum_c V[o][c] u[(L,M)][c],
+// H = C q.  Given dH:
+//     dq = C^T dH,
+//     dV[o][c]  += sum_M dq[o][M] u[(L,M)][c]              (summed over all edges)
+//     du[(L,M)][c] = sum_o V[o][c] dq[o][M],   du' = D du
 //     (gv', gw) = Mid^T(D z, w ; du'),   dz = D^T gv'   (per edge row; summed by source and by destination later)
-// A group of E lanes works on one edge.  The collapsed quantities are shared through LDS; the loops over the
-// rows o of V run per coupled degree L with the (L, M) register index fixed at compile time.
+// A group of E lanes works on one edge, lane = channel: every rotation runs per lane on all lanes alike.  The
+// collapsed quantities are shared through LDS; the loops over the rows o of V run per coupled degree L with the
+// (L, M) register index fixed at compile time.
 #include "egnn_internal.h"
 #include "bond_frame.h"
 
@@ -21,26 +22,16 @@ struct ReadoutBwdTabs {
   const int* slot_L;     // [n_slots]
   const int* slot_qoff;  // [n_slots]
   const int* vrow_qoff;  // [n_vrows] offset of the (2L+1) values of the slot that uses row o of V
-  int nq, n_slots, n_vrows;
+  int nq, n_slots, n_vrows, nnz;
   int v_off[EGNN_L_READOUT + 2];
 };
 
 template <int L>
-__device__ __forceinline__ void rotate_slot_in(float* q, const BondTrig& t) {
-  float v[2 * L + 1];
-#pragma unroll
-  for (int i = 0; i < 2 * L + 1; ++i) v[i] = q[i];
-  egnn_to_bond_frame_l<L>(v, t);
-#pragma unroll
-  for (int i = 0; i < 2 * L + 1; ++i) q[i] = v[i];
-}
-
-template <int L>
 __device__ __forceinline__ void collapse_adjoint(const ReadoutBwdTabs& tb, const float* __restrict__ V,
-                                                 const float* sq, float* sdV, const float* u, float* du, int c,
-                                                 int log2E) {
+                                                 const float* sq, const int* s_vq, float* sdV, const float* u,
+                                                 float* du, int c, int log2E) {
   for (int o = tb.v_off[L]; o < tb.v_off[L + 1]; ++o) {
-    const float* q = sq + tb.vrow_qoff[o];
+    const float* q = sq + s_vq[o];
     const float vv = V[((size_t)o << log2E) + c];
     float dot = 0.0f;
 #pragma unroll
@@ -70,6 +61,18 @@ __global__ __launch_bounds__(256) void readout_backward_kernel(
   float* sq = smem + (size_t)slot * tb.nq;                                           // [nq] per slot
   float* sdV = smem + (size_t)n_slots * tb.nq + ((size_t)slot * tb.n_vrows << log2E);  // [n_vrows][E] per slot
   for (int o = 0; o < tb.n_vrows; ++o) sdV[(o << log2E) + c] = 0.0f;
+  // the index tables, once per workgroup
+  int* s_ptr = reinterpret_cast<int*>(smem + (size_t)n_slots * tb.nq + ((size_t)n_slots * tb.n_vrows << log2E));  // [nq + 1]
+  int* s_h = s_ptr + tb.nq + 1;                            // [nnz]
+  float* s_c = reinterpret_cast<float*>(s_h + tb.nnz);     // [nnz]
+  int* s_vq = reinterpret_cast<int*>(s_c + tb.nnz);        // [n_vrows]
+  for (int i = tid; i <= tb.nq; i += 256) s_ptr[i] = tb.uncT_ptr[i];
+  for (int i = tid; i < tb.nnz; i += 256) {
+    s_h[i] = tb.uncT_h[i];
+    s_c[i] = tb.uncT_c[i];
+  }
+  for (int i = tid; i < tb.n_vrows; i += 256) s_vq[i] = tb.vrow_qoff[i];
+  __syncthreads();
 
   const long k_base = (long)blockIdx.x * n_slots * iters;
   for (int it = 0; it < iters; ++it) {
@@ -83,21 +86,8 @@ __global__ __launch_bounds__(256) void readout_backward_kernel(
       const float* hrow = dH + (size_t)k * tb.nq;
       for (int q = c; q < tb.nq; q += E) {
         float sum = 0.0f;
-        for (int n = tb.uncT_ptr[q]; n < tb.uncT_ptr[q + 1]; ++n) sum += tb.uncT_c[n] * hrow[tb.uncT_h[n]];
+        for (int n = s_ptr[q]; n < s_ptr[q + 1]; ++n) sum += s_c[n] * hrow[s_h[n]];
         sq[q] = sum;
-      }
-    }
-    __syncthreads();
-    if (live) {
-      for (int sl = c; sl < tb.n_slots; sl += E) {
-        float* q = sq + tb.slot_qoff[sl];
-        switch (tb.slot_L[sl]) {
-          case 1: rotate_slot_in<1>(q, t); break;
-          case 2: rotate_slot_in<2>(q, t); break;
-          case 3: rotate_slot_in<3>(q, t); break;
-          case 4: rotate_slot_in<4>(q, t); break;
-          default: break;
-        }
       }
     }
     __syncthreads();
@@ -113,13 +103,15 @@ __global__ __launch_bounds__(256) void readout_backward_kernel(
       for (int i = 0; i < D; ++i) v[i] = zsp[(size_t)i << log2E] + ztp[(size_t)i << log2E];
       egnn_to_bond_frame<LMAX>(v, t);
       Mid::run(v, wr, u);
+      egnn_from_bond_frame<4>(u, t);
 #pragma unroll
       for (int i = 0; i < ROB_D; ++i) du[i] = 0.0f;
-      collapse_adjoint<0>(tb, V, sq, sdV, u, du, c, log2E);
-      collapse_adjoint<1>(tb, V, sq, sdV, u, du, c, log2E);
-      collapse_adjoint<2>(tb, V, sq, sdV, u, du, c, log2E);
-      collapse_adjoint<3>(tb, V, sq, sdV, u, du, c, log2E);
-      collapse_adjoint<4>(tb, V, sq, sdV, u, du, c, log2E);
+      collapse_adjoint<0>(tb, V, sq, s_vq, sdV, u, du, c, log2E);
+      collapse_adjoint<1>(tb, V, sq, s_vq, sdV, u, du, c, log2E);
+      collapse_adjoint<2>(tb, V, sq, s_vq, sdV, u, du, c, log2E);
+      collapse_adjoint<3>(tb, V, sq, s_vq, sdV, u, du, c, log2E);
+      collapse_adjoint<4>(tb, V, sq, s_vq, sdV, u, du, c, log2E);
+      egnn_to_bond_frame<4>(du, t);
       float gv[D], gw[P];
       Mid::run_bwd(v, wr, du, gv, gw);
       egnn_from_bond_frame<LMAX>(gv, t);
@@ -181,6 +173,7 @@ int egnn_launch_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const float
   tb.nq = nq;
   tb.n_slots = ctx->n_slots;
   tb.n_vrows = n_vrows;
+  tb.nnz = nnz;
   tb.v_off[0] = 0;
   for (int L = 0; L <= EGNN_L_READOUT; ++L) tb.v_off[L + 1] = tb.v_off[L] + ctx->n_out[L];
   tb.uncT_ptr = tab_i;
@@ -190,7 +183,8 @@ int egnn_launch_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const float
   tb.vrow_qoff = tb.slot_qoff + ctx->n_slots;
   tb.uncT_c = tab_f;
   const int n_slots = 256 / E;
-  const size_t shmem = ((size_t)n_slots * nq + (size_t)n_slots * n_vrows * E) * sizeof(float);
+  const size_t shmem = ((size_t)n_slots * nq + (size_t)n_slots * n_vrows * E) * sizeof(float) +
+                       ((size_t)nq + 1 + 2 * (size_t)nnz + n_vrows) * sizeof(int);
   const long grid_x = rob_grid(ctx, n);
   dim3 grid((unsigned)grid_x), block(256);
   const float4* rd = reinterpret_cast<const float4*>(rhat_d);
