@@ -7,12 +7,12 @@
 #include "egnn_internal.h"
 
 #define MIX_RPT 4      // rows per thread
-#define MIX_TILES 8    // row tiles per workgroup
+#define MIX_TILES 8    // row tiles per workgroup at most (fewer on small inputs, to have enough workgroups in flight)
 
 __global__ __launch_bounds__(256) void node_mix_kernel(const float* __restrict__ x1, const float* __restrict__ W1,
                                                        const float* __restrict__ x2, const float* __restrict__ W2,
                                                        float* __restrict__ y, int n_nodes, int lmax, int log2E,
-                                                       int transpose) {
+                                                       int transpose, int tiles) {
   extern __shared__ float smem[];
   const int E = 1 << log2E;
   const int l = blockIdx.y;
@@ -35,8 +35,8 @@ __global__ __launch_bounds__(256) void node_mix_kernel(const float* __restrict__
     if (W2) sWt[E * E + at] = W2[(size_t)l * E * E + i];
   }
 
-  for (int t = 0; t < MIX_TILES; ++t) {
-    const long r0 = ((long)blockIdx.x * MIX_TILES + t) * rows_per_tile;
+  for (int t = 0; t < tiles; ++t) {
+    const long r0 = ((long)blockIdx.x * tiles + t) * rows_per_tile;
     if (r0 >= n_rows) break;
     __syncthreads();
     for (int i = tid; i < rows_per_tile * E; i += 256) {
@@ -84,7 +84,11 @@ int egnn_launch_node_mix(egnn_ctx* ctx, const float* x1, const float* W1, const 
   const int E = ctx->desc.channels, lmax = ctx->desc.lmax;
   const int rows_per_tile = MIX_RPT * (256 / E);
   const long max_rows = (long)n_nodes * (2 * lmax + 1);
-  const long per_wg = (long)rows_per_tile * MIX_TILES;
+  // each workgroup loads W once: several tiles per workgroup amortise that, but only once the grid is large enough
+  const long n_tiles = (max_rows + rows_per_tile - 1) / rows_per_tile;
+  long tiles = n_tiles / 2048;
+  tiles = tiles < 1 ? 1 : (tiles > MIX_TILES ? MIX_TILES : tiles);
+  const long per_wg = (long)rows_per_tile * tiles;
   dim3 grid((unsigned)((max_rows + per_wg - 1) / per_wg), lmax + 1), block(256);
   const int n_in = W2 ? 2 : 1;
   const size_t shmem = ((size_t)n_in * E * E + (size_t)n_in * rows_per_tile * (E + 1)) * sizeof(float);
@@ -94,7 +98,7 @@ int egnn_launch_node_mix(egnn_ctx* ctx, const float* x1, const float* W1, const 
     if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(node_mix_kernel)");
   }
   hipLaunchKernelGGL(node_mix_kernel, grid, block, shmem, stream, x1, W1, x2, W2, y, n_nodes, lmax,
-                     ctx->log2_channels, transpose);
+                     ctx->log2_channels, transpose, (int)tiles);
   EGNN_LAUNCH_CHECK(ctx, "node_mix_kernel");
   return EGNN_OK;
 }
