@@ -1,0 +1,128 @@
+"""CPU oracle (fp64, numpy) for the bond-aligned SO(2) form of the message transform.  TEST INFRASTRUCTURE ONLY.
+
+Imported by tests/ only (and by nothing under paper_2507_03840_amd/); shares no code with the HIP path.
+
+What it follows (arXiv 2507.03840): Fig. 2(a) bottom (a message is the concatenation of the two node embeddings
+and the edge embedding), Fig. 2(d) and Sec. 3 "Message passing" (every message is rotated with the Wigner matrix of
+its bond so that the bond lies on a fixed axis, split into its m components, each |m| goes through its own linear
+layer that mixes the degrees l and takes 3E channels to E, and the result is rotated back), Sec. 2.1 end (this is
+what turns the tensor product into linear layers), Sec. 3 "Initialization" (the L = 0 plane of an edge embedding
+is the Gaussian expansion of the edge length) and the sum over incoming edges of Sec. 3.
+
+Choices where the paper is silent (its references define the layer):
+  * frame: any rotation R_k with R_k rhat_k = z; the result does not depend on which one (a linear layer of this
+    form commutes with rotations about z), which test_so2_gauge checks;
+  * components: with the real harmonics of egnn_oracle (m > 0 <-> cos, m < 0 <-> sin) a rotation about z by a turns
+    (x_{+m}, x_{-m}) by the angle m a, so the layer of order m > 0 is
+        y_{+m} = Wr_m x_{+m} - Wi_m x_{-m},   y_{-m} = Wi_m x_{+m} + Wr_m x_{-m}
+    and y_0 = W_0 x_0, where x_{+-m} stacks the degrees l >= m and the 3E channels, y the degrees l >= m and E channels;
+  * weights do not depend on the edge; the edge enters through its embedding e_k, whose L = 0 plane is W_e B(d_k)
+    (W_e [E][n_rbf], a learnable linear map of the Gaussian basis) and whose other planes are zero (edge embeddings
+    are not carried from layer to layer in this build);
+  * each message is multiplied by the cosine envelope f_c(d_k) and the sum over incoming edges by agg_norm^-1/2 (the
+    paper's attention weights are not part of this path).
+"""
+from math import sqrt
+import numpy as np
+from . import egnn_oracle as O
+
+F64 = np.float64
+
+
+def so2_shapes(lmax, E):
+    """[(rows, cols)] of W_0, then of Wr_m = Wi_m for m = 1..lmax: rows (l_out - m) E + c_out, cols (l_in - m) 3E + g E + c_in."""
+    return [((lmax + 1 - m) * E, (lmax + 1 - m) * 3 * E) for m in range(lmax + 1)]
+
+
+def so2_pack(W0, Wr, Wi):
+    """Flat fp32 layout of the C ABI: W_0, then Wr_1, Wi_1, Wr_2, Wi_2, ..., each row-major."""
+    parts = [np.asarray(W0, np.float32).ravel()]
+    for a, b in zip(Wr, Wi):
+        parts += [np.asarray(a, np.float32).ravel(), np.asarray(b, np.float32).ravel()]
+    return np.concatenate(parts)
+
+
+def bond_rotations(rhat, gauge=None):
+    """R [n][3][3] with R rhat = z (Rodrigues about rhat x z), optionally followed by a rotation about z by gauge[n]."""
+    rhat = np.asarray(rhat, F64)
+    n = len(rhat)
+    z = np.array([0.0, 0.0, 1.0])
+    R = np.zeros((n, 3, 3), F64)
+    for k in range(n):
+        v = np.cross(rhat[k], z)
+        s, c = np.linalg.norm(v), float(rhat[k] @ z)
+        if s < 1e-14:
+            Rk = np.eye(3) if c > 0 else np.diag([1.0, -1.0, -1.0])     # rhat = -z: half turn about x
+        else:
+            K = np.array([[0, -v[2], v[1]], [v[2], 0, -v[0]], [-v[1], v[0], 0]]) / s
+            Rk = np.eye(3) + s * K + (1 - c) * (K @ K)
+        if gauge is not None:
+            ca, sa = np.cos(gauge[k]), np.sin(gauge[k])
+            Rk = np.array([[ca, -sa, 0], [sa, ca, 0], [0, 0, 1.0]]) @ Rk
+        R[k] = Rk
+    return R
+
+
+def wigner_blocks(lmax, R):
+    """D [n][(lmax+1)^2][(lmax+1)^2], block diagonal, with Y(R_k r) = D_k Y(r): solved from the harmonics themselves at a
+    fixed set of sample directions (the same definition as egnn_oracle.wigner_d_real, batched over rotations)."""
+    rng = np.random.default_rng(4321)
+    n = len(R)
+    dim = (lmax + 1) ** 2
+    D = np.zeros((n, dim, dim), F64)
+    v = rng.standard_normal((8 * (2 * lmax + 1), 3))
+    v /= np.linalg.norm(v, axis=1, keepdims=True)
+    Yv = O.sph_harm_real(lmax, v)                                      # [s][dim]
+    rot = np.einsum("kab,sb->ksa", R, v)                               # R_k v_s
+    Yr = O.sph_harm_real(lmax, rot.reshape(-1, 3)).reshape(n, len(v), dim)
+    for l in range(lmax + 1):
+        pinv = np.linalg.pinv(Yv[:, O.sl(l)])                          # [2l+1][s]
+        D[:, O.sl(l), O.sl(l)] = np.einsum("as,ksb->kba", pinv, Yr[:, :, O.sl(l)])
+    return D
+
+
+def so2_linear(Xp, W0, Wr, Wi, lmax, E):
+    """The per-|m| linear layers on bond-frame messages Xp [n][(lmax+1)^2][3E] -> [n][(lmax+1)^2][E]."""
+    n = Xp.shape[0]
+    Yp = np.zeros((n, (lmax + 1) ** 2, E), F64)
+    ls0 = np.arange(lmax + 1)
+    x0 = Xp[:, ls0 * ls0 + ls0, :].reshape(n, -1)                      # (l, channel) stacked
+    Yp[:, ls0 * ls0 + ls0, :] = (x0 @ np.asarray(W0, F64).T).reshape(n, lmax + 1, E)
+    for m in range(1, lmax + 1):
+        ls = np.arange(m, lmax + 1)
+        xp = Xp[:, ls * ls + ls + m, :].reshape(n, -1)
+        xm = Xp[:, ls * ls + ls - m, :].reshape(n, -1)
+        A, B = np.asarray(Wr[m - 1], F64), np.asarray(Wi[m - 1], F64)
+        Yp[:, ls * ls + ls + m, :] = (xp @ A.T - xm @ B.T).reshape(n, len(ls), E)
+        Yp[:, ls * ls + ls - m, :] = (xp @ B.T + xm @ A.T).reshape(n, len(ls), E)
+    return Yp
+
+
+def so2_messages(src, dst, r, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut, gauge=None):
+    """One transformed message per edge, lab frame: f_c(d) D^T SO2Linear(D [x_src | x_dst | e])."""
+    x = np.asarray(x, F64)
+    d = np.sqrt(np.einsum("ka,ka->k", r, r))
+    D = wigner_blocks(lmax, bond_rotations(r / d[:, None], gauge))
+    n, dim = len(src), (lmax + 1) ** 2
+    M = np.zeros((n, dim, 3 * E), F64)
+    M[:, :, :E] = x[src]
+    M[:, :, E:2 * E] = x[dst]
+    M[:, 0, 2 * E:] = O.radial_basis(d, n_rbf, r_cut) @ np.asarray(W_e, F64).T
+    Xp = np.einsum("kab,kbc->kac", D, M)
+    Yp = so2_linear(Xp, W0, Wr, Wi, lmax, E)
+    Y = np.einsum("kba,kbc->kac", D, Yp)                               # D^T = D^-1
+    return Y * O.envelope(d, r_cut)[:, None, None]
+
+
+def so2_message_sum(graph, pos, box, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut, agg_norm, gauge=None, chunk=4096):
+    """a_j = agg_norm^-1/2 sum over the incoming edges of owned node j of the transformed messages."""
+    src, dst, shift, row_ptr = graph
+    n_owned = len(row_ptr) - 1
+    a = np.zeros((n_owned, (lmax + 1) ** 2, E), F64)
+    for k0 in range(0, len(src), chunk):
+        k1 = min(len(src), k0 + chunk)
+        r = O.edge_vectors(pos, box, src[k0:k1], dst[k0:k1], shift[k0:k1])
+        Y = so2_messages(src[k0:k1], dst[k0:k1], r, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut,
+                         None if gauge is None else gauge[k0:k1])
+        np.add.at(a, dst[k0:k1], Y)
+    return a / sqrt(agg_norm)
