@@ -201,6 +201,25 @@ int egnn_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col
                           const float* dH, float* dx, float* dW_s, float* dW_t, float* dW_r1, float* dW_r2,
                           float* dV, void* ws, size_t ws_bytes, void* stream);
 
+/* ---- the message transform in its bond-aligned SO(2) form (Fig. 2(a) bottom, Fig. 2(d); Sec. 3 "Message passing";
+ *      Sec. 2.1, last paragraph), summed over incoming edges ----
+ * Per directed edge k = (i -> j) the message is [x_i | x_j | e_k] along the channel axis (3 * channels), e_k zero
+ * except for its L = 0 plane W_e B(d_k) (B the Gaussian basis of S2).  It is rotated so that the bond lies on z,
+ * every order m goes through its own linear layer over (degree l >= |m|, channel), 3 * channels -> channels,
+ *     y_0 = W_0 x_0;   y_{+m} = Wr_m x_{+m} - Wi_m x_{-m},   y_{-m} = Wi_m x_{+m} + Wr_m x_{-m}   (m > 0 <-> cos, m < 0 <-> sin),
+ * rotated back, multiplied by the cutoff envelope f_c(d_k), and
+ *     a[j] = agg_norm^-1/2 sum_{k: dst(k) = j} y_k        for the owned nodes j.
+ * W_so2: W_0, then Wr_1, Wi_1, ..., Wr_lmax, Wi_lmax, each row-major [(lmax+1-m) * channels][(lmax+1-m) * 3 * channels]
+ * with row = (l_out - m) * channels + c_out and column = (l_in - m) * 3 * channels + g * channels + c_in, g = 0 source
+ * node, 1 destination node, 2 edge (egnn_so2_weight_count floats in all).  W_e [channels][n_rbf].
+ * x [n_total][(lmax+1)^2][channels], a [n_owned][(lmax+1)^2][channels] (a must not alias x).  Needs >= 8 channels.
+ * The same function as the tensor-product messages of S4 when the weights are the coupling coefficients of the
+ * bond direction (no channel mixing); in general a dense contraction shared by all edges. */
+int egnn_so2_weight_count(const egnn_ctx* ctx, int64_t* n_floats);
+int egnn_so2_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, size_t* bytes);
+int egnn_so2_message_sum(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3], const float* x,
+                         const float* W_e, const float* W_so2, float* a, void* ws, size_t ws_bytes, void* stream);
+
 /* ---- stage timing (measurement aid; follows the paper's protocol of timing the blocks of the forward
  *      pass separately, Sec. 4.4 / Fig. 6(c)) ----
  * egnn_timing_enable(ctx, max_calls > 0) creates HIP events; from then on every egnn_layer_forward /

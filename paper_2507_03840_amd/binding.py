@@ -19,7 +19,8 @@ SYMBOLS = [
     "egnn_edge_geometry", "egnn_radial_weights", "egnn_tp_segsum", "egnn_node_mix",
     "egnn_layer_forward", "egnn_readout_hij", "egnn_timing_enable", "egnn_timing_read",
     "egnn_backward_workspace_bytes", "egnn_graph_transpose", "egnn_loss_mse", "egnn_layer_backward",
-    "egnn_readout_backward", "egnn_set_option",
+    "egnn_readout_backward", "egnn_set_option", "egnn_so2_weight_count", "egnn_so2_workspace_bytes",
+    "egnn_so2_message_sum",
 ]
 
 
@@ -218,6 +219,25 @@ class Egnn:
         self._check(self.lib.egnn_node_mix(self.ctx, _ptr(x1), _ptr(W1), _ptr(x2), _ptr(W2), _ptr(y), x1.shape[0],
                                            _stream()))
         return y
+
+    # ---- SO(2) form of the message transform
+    def egnn_so2_weight_count(self):
+        out = C.c_int64()
+        self._check(self.lib.egnn_so2_weight_count(self.ctx, C.byref(out)))
+        return out.value
+
+    def egnn_so2_workspace_bytes(self, n_edges):
+        out = C.c_size_t()
+        self._check(self.lib.egnn_so2_workspace_bytes(self.ctx, C.c_int64(n_edges), C.byref(out)))
+        return out.value
+
+    def egnn_so2_message_sum(self, graph, pos, box, x, W_e, W_so2, ws, out=None):
+        a = out if out is not None else torch.empty((graph.n_owned, self.dim, self.channels), dtype=torch.float32,
+                                                    device="cuda")
+        g = graph.desc()
+        self._check(self.lib.egnn_so2_message_sum(self.ctx, C.byref(g), _ptr(pos), _f3(box), _ptr(x), _ptr(W_e),
+                                                  _ptr(W_so2), _ptr(a), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+        return a
 
     # ---- layer / readout
     def egnn_layer_forward(self, graph, pos, box, x_in, W, ws, w_edge=None, out=None):
