@@ -114,10 +114,21 @@ def so2_messages(src, dst, r, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut, gauge=N
     return Y * O.envelope(d, r_cut)[:, None, None]
 
 
-def so2_message_sum(graph, pos, box, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut, agg_norm, gauge=None, chunk=4096):
-    """a_j = agg_norm^-1/2 sum over the incoming edges of owned node j of the transformed messages."""
+def so2_message_sum(graph, pos, box, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut, agg_norm, gauge=None, chunk=4096,
+                    nodes=None):
+    """a_j = agg_norm^-1/2 sum over the incoming edges of owned node j of the transformed messages.
+    nodes: if given, only these destination nodes are evaluated and only their rows returned (same arithmetic)."""
     src, dst, shift, row_ptr = graph
     n_owned = len(row_ptr) - 1
+    if nodes is not None:
+        out = np.zeros((len(nodes), (lmax + 1) ** 2, E), F64)
+        for i, j in enumerate(nodes):
+            k0, k1 = int(row_ptr[j]), int(row_ptr[j + 1])
+            if k1 > k0:
+                r = O.edge_vectors(pos, box, src[k0:k1], dst[k0:k1], shift[k0:k1])
+                out[i] = so2_messages(src[k0:k1], dst[k0:k1], r, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut,
+                                      None if gauge is None else gauge[k0:k1]).sum(axis=0)
+        return out / sqrt(agg_norm)
     a = np.zeros((n_owned, (lmax + 1) ** 2, E), F64)
     for k0 in range(0, len(src), chunk):
         k1 = min(len(src), k0 + chunk)

@@ -214,5 +214,17 @@ def node_features(rng, n_rows, lmax, channels):
     return normal(rng, (n_rows, (lmax + 1) ** 2, channels))
 
 
+def so2_weights(rng, lmax, channels, n_rbf):
+    """Random weights of the SO(2) message transform: W_e [E][n_rbf], W_0, and (Wr_m, Wi_m) for m = 1..lmax with
+    (lmax+1-m) E rows and (lmax+1-m) 3E columns; every matrix ~ N(0, 1/fan_in), two blocks feeding each output for m > 0."""
+    E = channels
+    shapes = [((lmax + 1 - m) * E, (lmax + 1 - m) * 3 * E) for m in range(lmax + 1)]
+    W0 = normal(rng, shapes[0], shapes[0][1] ** -0.5)
+    Wr = [normal(rng, s, (2 * s[1]) ** -0.5) for s in shapes[1:]]
+    Wi = [normal(rng, s, (2 * s[1]) ** -0.5) for s in shapes[1:]]
+    W_e = normal(rng, (E, n_rbf), n_rbf ** -0.5)
+    return W_e, W0, Wr, Wi
+
+
 def species_table(rng, n_species, channels):
     return normal(rng, (n_species, channels))

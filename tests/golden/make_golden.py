@@ -8,6 +8,7 @@ full tensor (the scale of the relative error).  The work is spread over processe
 chunks; each chunk goes through the oracle's own functions unchanged.
 
     python tests/golden/make_golden.py 3 4 5
+    python tests/golden/make_golden.py so2:3 so2:4      (SO(2) message sums at sampled nodes)
 """
 import os
 import sys
@@ -56,6 +57,36 @@ def layer_parallel(pool_size, w, g, x, W, agg):
         for j0, part in ex.map(_messages_chunk, jobs):
             a[j0:j0 + part.shape[0]] = part
     return O.mix_channels(a, W["W_post"], w.lmax) + O.mix_channels(x[:w.n_owned], W["W_self"], w.lmax)
+
+
+def _so2_chunk(nodes):
+    from oracle import so2_oracle as S
+    w, g, x, Wso2, agg = _state["w"], _state["g"], _state["x"], _state["Wso2"], _state["agg"]
+    W_e, W0, Wr, Wi = Wso2
+    return S.so2_message_sum(g, w.pos, w.box, x, W_e, W0, Wr, Wi, w.lmax, w.channels, w.n_rbf, w.r_cut, agg, nodes=nodes)
+
+
+def make_so2(index, pool_size):
+    """SO(2) message sums of the full-size configuration at sampled destination nodes -> config{index}_so2_samples.npz.
+    Inputs: the model's layer-0 features (species embedded) and synth.so2_weights with seed [w.seed, 777]."""
+    t0 = time.time()
+    w = synth.workload(index)
+    wt = U.model_weights(w)
+    g = U.oracle_graph(w)
+    agg = U.mean_degree(g, w.n_owned)
+    rng = np.random.default_rng([w.seed, 4243])
+    nodes = np.sort(rng.choice(w.n_owned, N_NODE_SAMPLES, replace=False))
+    x = O.species_embed(wt["x0"], w.species, wt["table"])
+    Wso2 = synth.so2_weights(np.random.default_rng([w.seed, 777]), w.lmax, w.channels, w.n_rbf)
+    _state.update(w=w, g=g, x=x, Wso2=Wso2, agg=agg)
+    parts = [nodes[i::pool_size] for i in range(pool_size)]
+    rows = np.zeros((N_NODE_SAMPLES, (w.lmax + 1) ** 2, w.channels))
+    with ProcessPoolExecutor(pool_size) as ex:
+        for i, part in enumerate(ex.map(_so2_chunk, parts)):
+            rows[i::pool_size] = part
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"config{index}_so2_samples.npz")
+    np.savez_compressed(path, nodes=nodes, rows=rows, agg=agg, n_edges=len(g[0]))
+    print(f"config {index} so2: wrote {path}, max|a| over samples {np.abs(rows).max():.4f}, {time.time() - t0:.0f} s", flush=True)
 
 
 def make(index, pool_size):
@@ -194,8 +225,11 @@ def make_training(index, pool_size):
 
 
 if __name__ == "__main__":
-    which = [int(a) for a in sys.argv[1:]] or [3, 4, 5]
+    which = [int(a) for a in sys.argv[1:] if not a.startswith("so2")] or ([] if len(sys.argv) > 1 else [3, 4, 5])
     procs = int(os.environ.get("GOLDEN_PROCS", "6"))
+    for a in sys.argv[1:]:
+        if a.startswith("so2:"):   # e.g. so2:3 so2:4
+            make_so2(int(a[4:]), procs)
     for idx in which:
         if idx in (1, 5):          # training step (1 = small self-check of this script against the oracle's own chain)
             make_training(idx, procs)

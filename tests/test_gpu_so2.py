@@ -18,22 +18,12 @@ def B():
     return binding
 
 
-def so2_weights(rng, lmax, E, n_rbf):
-    """Every matrix ~ N(0, 1/fan_in) (fan_in doubled for m > 0, where two blocks feed each output)."""
-    shapes = S.so2_shapes(lmax, E)
-    W0 = synth.normal(rng, shapes[0], shapes[0][1] ** -0.5)
-    Wr = [synth.normal(rng, s, (2 * s[1]) ** -0.5) for s in shapes[1:]]
-    Wi = [synth.normal(rng, s, (2 * s[1]) ** -0.5) for s in shapes[1:]]
-    W_e = synth.normal(rng, (E, n_rbf), n_rbf ** -0.5)
-    return W_e, W0, Wr, Wi
-
-
 def run_case(B, w, seed=0):
     g = U.oracle_graph(w)
     agg = max(1.0, U.mean_degree(g, w.n_owned))
     rng = np.random.default_rng([w.seed if hasattr(w, "seed") and w.seed else 0, 7, seed])
     x = synth.node_features(rng, w.n_total, w.lmax, w.channels)
-    W_e, W0, Wr, Wi = so2_weights(rng, w.lmax, w.channels, w.n_rbf)
+    W_e, W0, Wr, Wi = synth.so2_weights(rng, w.lmax, w.channels, w.n_rbf)
     ref = S.so2_message_sum(g, w.pos, w.box, x, W_e, W0, Wr, Wi, w.lmax, w.channels, w.n_rbf, w.r_cut, agg)
     m = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, agg)
     flat = S.so2_pack(W0, Wr, Wi)
@@ -86,3 +76,40 @@ def test_so2_message_sum_empty_graph_and_errors(B):
     with pytest.raises(B.EgnnError) as err:
         m.egnn_so2_message_sum(graph, B.to_device(w2.pos), w2.box, x, We, Wf, small)
     assert err.value.code == -3        # workspace too small
+
+
+@pytest.mark.parametrize("index", [3, 4])
+def test_so2_fullsize_sampled_rows(B, index):
+    """Configs 3 and 4 in full (625,262 and 2,350,179 edges), against oracle rows stored by tests/golden/make_golden.py
+    (so2:3 so2:4) at sampled destination nodes; the scale of the relative error is the largest sampled entry."""
+    import os
+    import time
+    import torch
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", f"config{index}_so2_samples.npz")
+    assert os.path.exists(path), "run tests/golden/make_golden.py so2:3 so2:4"
+    gold = np.load(path)
+    w = synth.workload(index)
+    wt = U.model_weights(w)
+    agg = float(gold["agg"])
+    m = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, agg)
+    pos = B.to_device(w.pos)
+    graph = m.egnn_nlist(pos, w.n_owned, w.box, w.pbc)
+    assert graph.n_edges == int(gold["n_edges"])
+    x = B.to_device(wt["x0"]).clone()
+    m.egnn_species_embed(B.to_device(w.species), B.to_device(wt["table"]), x)
+    W_e, W0, Wr, Wi = synth.so2_weights(np.random.default_rng([w.seed, 777]), w.lmax, w.channels, w.n_rbf)
+    flat = B.to_device(S.so2_pack(W0, Wr, Wi))
+    ws = torch.empty(m.egnn_so2_workspace_bytes(graph.n_edges), dtype=torch.uint8, device="cuda")
+    print(f"config {index}: workspace {ws.numel() / 1e9:.2f} GB", flush=True)
+    a = m.egnn_so2_message_sum(graph, pos, w.box, x, B.to_device(W_e), flat, ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(3):
+        m.egnn_so2_message_sum(graph, pos, w.box, x, B.to_device(W_e), flat, ws, out=a)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / 3
+    got = a[torch.from_numpy(gold["nodes"]).cuda()].cpu().numpy().astype(np.float64)
+    err = np.abs(got - gold["rows"]).max() / np.abs(gold["rows"]).max()
+    print(f"config {index}: SO(2) message sum {dt * 1e3:.2f} ms ({graph.n_edges / dt:.3e} edges/s), sampled rel err {err:.2e}",
+          flush=True)
+    assert err < TOL
