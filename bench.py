@@ -79,6 +79,8 @@ def main():
                     help="training steps (forward + loss + reverse pass, config 5) timed after the main region; 0 = skip")
     ap.add_argument("--fused", type=int, default=0, choices=[0, 1],
                     help="1: radial weights and messages in one kernel (weights never written to memory)")
+    ap.add_argument("--no-so2", action="store_true",
+                    help="skip the extra timing of the SO(2) form of the message transform (egnn_so2_message_sum)")
     ap.add_argument("--sweep", action="store_true",
                     help="also time one layer forward on growing prefixes of the destination nodes (saturation curve)")
     args = ap.parse_args()
@@ -203,6 +205,25 @@ def main():
                        note="torch elementwise copy (1 GiB read + 1 GiB write) and fill (1 GiB write)")
     del a, b
 
+    # ---- the message transform in its SO(2) form (dense per-m linear layers, 3E -> E), same graph and features ----
+    so2 = None
+    if not args.no_so2 and w.channels >= 8:
+        graph = m.egnn_nlist(pos, w.n_owned, w.box, w.pbc)
+        W_e, W0, Wr, Wi = synth.so2_weights(np.random.default_rng([w.seed, 777]), w.lmax, w.channels, w.n_rbf)
+        flat = B.to_device(np.concatenate([W0.ravel()] + [a.ravel() for pair in zip(Wr, Wi) for a in pair]))
+        assert flat.numel() == m.egnn_so2_weight_count()
+        We = B.to_device(W_e)
+        ws2 = torch.empty(m.egnn_so2_workspace_bytes(n_edges), dtype=torch.uint8, device="cuda")
+        so2_ms = timed(lambda: m.egnn_so2_message_sum(graph, pos, w.box, x0, We, flat, ws2, out=x_out[0]), 5)
+        E_, L_ = w.channels, w.lmax
+        macs = sum((1 if q == 0 else 4) * ((L_ + 1 - q) * E_) * ((L_ + 1 - q) * 2 * E_) for q in range(L_ + 1)) + (L_ + 1) * E_ * E_
+        so2 = dict(ms=so2_ms, edges_per_s=n_edges / so2_ms * 1e3, flop_per_edge=2 * macs,
+                   TFLOPs_fp32_equivalent=2 * macs * n_edges / so2_ms / 1e9,
+                   bf16_mfma_TFLOPs=6 * 2 * macs * n_edges / so2_ms / 1e9, bf16_mfma_peak_TFLOPs=2500.0,
+                   workspace_GB=ws2.numel() / 1e9,
+                   note="gather+rotate, five split-bf16 GEMMs (six bf16 products per fp32 product), rotate back + segmented sum")
+        del ws2
+
     # ---- saturation curve: one layer forward into the first n destination nodes ----
     sweep = None
     if args.sweep:
@@ -264,6 +285,8 @@ def main():
     }
     out["training_step"] = training
     out["hbm_calibration"] = calibration
+    if so2 is not None:
+        out["so2_message_sum"] = so2
     if sweep is not None:
         out["saturation_sweep"] = sweep
     if not args.no_cpu_baseline:

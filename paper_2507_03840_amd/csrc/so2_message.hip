@@ -139,24 +139,30 @@ __global__ __launch_bounds__(256) void so2_pack_kernel(const float* __restrict__
 }
 
 // ---------------------------------------------------------------------------------------------- 3. GEMM
-// C[e][ct*64 + j] = sum_k A[e][k] B[k][ct*64 + j].  blockIdx.x = 64-column tile (fastest: the tiles of one block of
-// rows run at the same time and share its rows of A in L2), blockIdx.y = block of 64 * RB_WAVES rows.  A compute wave
-// owns 64 rows; its 64 x 64 tile of A is fetched in memory order and turned to operand order through a private LDS tile.
+// C[e][ct*64 + j] = sum_k A[e][k] B[k][ct*64 + j].  A workgroup = (block of 64 * RB_WAVES rows, 64-column tile ct).
+// Workgroup ids go round-robin over the 8 XCDs, each with its own L2, so the id is decoded such that the column tiles
+// of one block of rows sit on the same XCD with consecutive dispatch slots: they read the same rows of A, once from
+// HBM and then from that L2.  A compute wave owns 64 rows; its 64 x 64 tile of A is fetched in memory order and turned
+// to operand order through a private LDS tile.
 #define SO2_AROW 68
 __global__ __launch_bounds__(RB_THREADS) void so2_gemm_kernel(const float* __restrict__ A, long M, int K, const uint16_t* __restrict__ T,
-                                                              int n_steps, float* __restrict__ C, int N) {
+                                                              int n_steps, float* __restrict__ C, int N, int n_ct,
+                                                              int n_row_blocks) {
   extern __shared__ uint4 so2_smem[];
   uint4* sB = so2_smem;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int ct = blockIdx.x;
+  const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+  const int ct = idx % n_ct;
+  const int row_block = (idx / n_ct) * 8 + xcd;
+  if (row_block >= n_row_blocks) return;   // (whole workgroup: the grid is rounded up to a multiple of 8 row blocks)
   if (wave == RB_WAVES) {
     rb_loader(T, (long)ct * n_steps, n_steps, sB, lane);
     return;
   }
   float* sA = reinterpret_cast<float*>(sB + 2 * 64 * RB_BROW4) + (size_t)wave * 32 * SO2_AROW;
   const int m = lane & 31, hh = lane >> 5;
-  const long e_base = ((long)blockIdx.y * RB_WAVES + wave) * 64;
+  const long e_base = ((long)row_block * RB_WAVES + wave) * 64;
   const int frow = lane >> 4, fcol = (lane & 15) * 4;
   const float* fptr[2][8];
 #pragma unroll
@@ -372,8 +378,10 @@ extern "C" int egnn_so2_message_sum(egnn_ctx* ctx, const egnn_graph* g, const fl
                          W_so2 + so2_w_offset(lmax, E, m), T[m], m, lmax, E, K, N, n_steps, n_ct);
       EGNN_LAUNCH_CHECK(ctx, "so2_pack_kernel");
       const long rows_per_wg = 64L * RB_WAVES;
-      hipLaunchKernelGGL(so2_gemm_kernel, dim3(n_ct, (unsigned)((n + rows_per_wg - 1) / rows_per_wg)), dim3(RB_THREADS), lds,
-                         st, b.A[m], n, K, T[m], n_steps, b.Y[m], N);
+      const int n_row_blocks = (int)((n + rows_per_wg - 1) / rows_per_wg);
+      const unsigned grid_x = (unsigned)(((n_row_blocks + 7) / 8) * 8 * n_ct);
+      hipLaunchKernelGGL(so2_gemm_kernel, dim3(grid_x), dim3(RB_THREADS), lds, st, b.A[m], n, K, T[m], n_steps, b.Y[m], N,
+                         n_ct, n_row_blocks);
       EGNN_LAUNCH_CHECK(ctx, "so2_gemm_kernel");
     }
   }
