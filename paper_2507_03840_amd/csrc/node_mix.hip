@@ -1,9 +1,10 @@
 // S5: per-degree channel mix  y[n][(l,m)][:] = W1[l] x1[n][(l,m)][:] (+ W2[l] x2[n][(l,m)][:])
 // (the linear layer of Fig. 2(d), one E x E matrix per degree l), and the species embedding of Sec. 3.
 //
-// Workgroup = (one degree l, a run of rows (node, m)).  W^T sits in LDS so that lanes of consecutive
-// output channels read consecutive words; a thread produces ROWS_PER_THREAD rows of one output channel
-// and reads the inputs of its rows as LDS broadcasts.
+// Two implementations.  32 and 64 channels: fp32 MFMA (node_mix_mfma_kernel below).  Other channel counts: a vector
+// kernel -- workgroup = (one degree l, a run of rows (node, m)), W^T in LDS so that lanes of consecutive output channels
+// read consecutive words; a thread produces ROWS_PER_THREAD rows of one output channel and reads the inputs of its
+// rows as LDS broadcasts.
 #include "egnn_internal.h"
 
 #define MIX_RPT 4      // rows per thread
@@ -78,9 +79,97 @@ __global__ __launch_bounds__(256) void node_mix_kernel(const float* __restrict__
   }
 }
 
+// The same mix on the matrix cores, for 32 and 64 channels (a 32 x 32 MFMA block is one block of output channels):
+// workgroup = (degree l, run of 32-row tiles), W^T in LDS, one tile per wave at a time.  v_mfma_f32_32x32x2_f32 takes
+// plain fp32 operands, so the products are exact fp32 as in the vector version.  Lane l serves row / output channel
+// l & 31; the contraction index of MFMA step s on lane half hh is c' = hh * E/2 + s (any order will do as long as
+// both operands use it; this one lets a lane fetch its half row as contiguous 16-byte loads).
+typedef float mix_float16v __attribute__((ext_vector_type(16)));
+
+template <int LOG2E>
+__global__ __launch_bounds__(256) void node_mix_mfma_kernel(const float* __restrict__ x1, const float* __restrict__ W1,
+                                                            const float* __restrict__ x2, const float* __restrict__ W2,
+                                                            float* __restrict__ y, int n_nodes, int lmax, int transpose,
+                                                            int tiles) {
+  constexpr int E = 1 << LOG2E, KH = E / 2, NCB = E / 32;
+  extern __shared__ float smem[];   // [n_in][c'][c]
+  const int l = blockIdx.y;
+  const int D = (lmax + 1) * (lmax + 1);
+  const int nm = 2 * l + 1;
+  const long n_rows = (long)n_nodes * nm;
+  const int n_in = W2 ? 2 : 1;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int m = lane & 31, hh = lane >> 5;
+  for (int i = tid; i < E * E; i += 256) {
+    // forward: y[co] = sum_ci W[l][co][ci] x[ci]; transposed (reverse pass): y[co] = sum_ci W[l][ci][co] x[ci]
+    const int r = i >> LOG2E, q = i & (E - 1);
+    const int at = transpose ? i : q * E + r;
+    smem[at] = W1[(size_t)l * E * E + i];
+    if (W2) smem[E * E + at] = W2[(size_t)l * E * E + i];
+  }
+  __syncthreads();
+  for (int t = 0; t < tiles; ++t) {
+    const long r0 = (((long)blockIdx.x * tiles + t) * 4 + wave) * 32;
+    if (r0 >= n_rows) break;
+    mix_float16v acc[NCB];
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[cb][i] = 0.0f;
+    long r = r0 + m;
+    if (r >= n_rows) r = n_rows - 1;
+    const long node = r / nm;
+    const size_t off = (((size_t)node * D + l * l + (int)(r - node * nm)) << LOG2E) + hh * KH;
+    for (int in = 0; in < n_in; ++in) {
+      const float4* xr = reinterpret_cast<const float4*>((in ? x2 : x1) + off);
+      float a[KH];
+#pragma unroll
+      for (int q = 0; q < KH / 4; ++q) {
+        const float4 v = xr[q];
+        a[4 * q] = v.x; a[4 * q + 1] = v.y; a[4 * q + 2] = v.z; a[4 * q + 3] = v.w;
+      }
+      const float* wt = smem + (size_t)in * E * E + (size_t)(hh * KH) * E + m;
+#pragma unroll
+      for (int s = 0; s < KH; ++s)
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+          acc[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s], wt[s * E + 32 * cb], acc[cb], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const long ro = r0 + 8 * (i >> 2) + 4 * hh + (i & 3);
+      if (ro < n_rows) {
+        const long no = ro / nm;
+        float* out = y + (((size_t)no * D + l * l + (int)(ro - no * nm)) << LOG2E) + m;
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) out[32 * cb] = acc[cb][i];
+      }
+    }
+  }
+}
+
+template <int LOG2E>
+static int launch_node_mix_mfma(egnn_ctx* ctx, const float* x1, const float* W1, const float* x2, const float* W2,
+                                float* y, int n_nodes, hipStream_t stream, int transpose) {
+  constexpr int E = 1 << LOG2E;
+  const int lmax = ctx->desc.lmax;
+  const long max_rows = (long)n_nodes * (2 * lmax + 1);
+  const long n_tiles = (max_rows + 127) / 128;                 // 4 waves x 32 rows
+  long tiles = n_tiles / 2048;
+  tiles = tiles < 1 ? 1 : (tiles > 8 ? 8 : tiles);
+  dim3 grid((unsigned)((n_tiles + tiles - 1) / tiles), lmax + 1), block(256);
+  const size_t shmem = (size_t)(W2 ? 2 : 1) * E * E * sizeof(float);
+  hipLaunchKernelGGL(node_mix_mfma_kernel<LOG2E>, grid, block, shmem, stream, x1, W1, x2, W2, y, n_nodes, lmax, transpose,
+                     (int)tiles);
+  EGNN_LAUNCH_CHECK(ctx, "node_mix_mfma_kernel");
+  return EGNN_OK;
+}
+
 int egnn_launch_node_mix(egnn_ctx* ctx, const float* x1, const float* W1, const float* x2, const float* W2,
                          float* y, int n_nodes, hipStream_t stream, int transpose) {
   if (n_nodes == 0) return EGNN_OK;
+  if (ctx->desc.channels == 32) return launch_node_mix_mfma<5>(ctx, x1, W1, x2, W2, y, n_nodes, stream, transpose);
+  if (ctx->desc.channels == 64) return launch_node_mix_mfma<6>(ctx, x1, W1, x2, W2, y, n_nodes, stream, transpose);
   const int E = ctx->desc.channels, lmax = ctx->desc.lmax;
   const int rows_per_tile = MIX_RPT * (256 / E);
   const long max_rows = (long)n_nodes * (2 * lmax + 1);
