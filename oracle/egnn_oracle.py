@@ -216,12 +216,16 @@ def silu(t):
     return t / (1.0 + np.exp(-t))
 
 
-def radial_weights(d, W_r1, W_r2, paths, channels, n_rbf, r_cut):
-    """w[k, p, c] = f_c(d_k) alpha_p (W_r2 SiLU(W_r1 B(d_k)))[p*E + c]; no biases."""
+def radial_weights(d, W_r1, W_r2, paths, channels, n_rbf, r_cut, w_dtype=None):
+    """w[k, p, c] = f_c(d_k) alpha_p (W_r2 SiLU(W_r1 B(d_k)))[p*E + c]; no biases.
+
+    w_dtype=np.float16 models the mixed-precision mode (Sec. 4.1: half-precision values, fp32 sums): the weights are
+    rounded to half precision (round to nearest even) where they are stored; everything else stays as it is."""
     B = radial_basis(d, n_rbf, r_cut)
     g = silu(B @ np.asarray(W_r1, F64).T)
     w = (g @ np.asarray(W_r2, F64).T).reshape(len(d), len(paths), channels)
-    return w * envelope(d, r_cut)[:, None, None] * path_norm(paths)[None, :, None]
+    w = w * envelope(d, r_cut)[:, None, None] * path_norm(paths)[None, :, None]
+    return w if w_dtype is None else w.astype(w_dtype).astype(F64)
 
 
 # --------------------------------------------------------------------------------------
@@ -275,7 +279,7 @@ def edge_messages_sum(graph, pos, box, h, weights_fn, lmax, l_sh, agg_norm, chun
     return a / sqrt(agg_norm)
 
 
-def layer_forward(graph, pos, box, x_in, W, lmax, l_sh, channels, n_rbf, r_cut, agg_norm, w_edge=None):
+def layer_forward(graph, pos, box, x_in, W, lmax, l_sh, channels, n_rbf, r_cut, agg_norm, w_edge=None, w_dtype=None):
     """One message-passing layer.  x_in has n_total rows (owned first), returns the n_owned new rows.
 
     h = W_pre x (all nodes);  a_j as in edge_messages_sum;  x'_j = W_post a_j + W_self x_j.
@@ -285,7 +289,7 @@ def layer_forward(graph, pos, box, x_in, W, lmax, l_sh, channels, n_rbf, r_cut, 
     x = np.asarray(x_in, F64)
     h = mix_channels(x, W["W_pre"], lmax)
     if w_edge is None:
-        fn = lambda d, k0, k1, paths: radial_weights(d, W["W_r1"], W["W_r2"], paths, channels, n_rbf, r_cut)
+        fn = lambda d, k0, k1, paths: radial_weights(d, W["W_r1"], W["W_r2"], paths, channels, n_rbf, r_cut, w_dtype)
     else:
         fn = lambda d, k0, k1, paths: np.asarray(w_edge[k0:k1], F64)
     a = edge_messages_sum(graph, pos, box, h, fn, lmax, l_sh, agg_norm)
@@ -314,7 +318,7 @@ def readout_slots(orb_l):
     return slots, n_out
 
 
-def readout_hij(graph, pos, box, x, W, lmax, l_sh, channels, n_rbf, r_cut, orb_l, k_range=None):
+def readout_hij(graph, pos, box, x, W, lmax, l_sh, channels, n_rbf, r_cut, orb_l, k_range=None, w_dtype=None):
     """H_k[(alpha, m_a), (beta, m_b)] for edges k (rows: source-atom orbitals, cols: destination's).
 
     z_k = (W_s x)_src + (W_t x)_dst;  u_k = TP(z_k, Yhat_k; w_k) for L <= 4;
@@ -338,7 +342,7 @@ def readout_hij(graph, pos, box, x, W, lmax, l_sh, channels, n_rbf, r_cut, orb_l
         r = edge_vectors(pos, box, src[c0:c1], dst[c0:c1], shift[c0:c1])
         d = np.sqrt(np.einsum("ka,ka->k", r, r))
         Y = sph_harm_real(l_sh, r / d[:, None])
-        w = radial_weights(d, W["W_r1"], W["W_r2"], paths, channels, n_rbf, r_cut)
+        w = radial_weights(d, W["W_r1"], W["W_r2"], paths, channels, n_rbf, r_cut, w_dtype)
         z = xs[src[c0:c1]] + xt[dst[c0:c1]]
         u = tensor_product(z, Y, w, paths, L_READOUT)
         for (a, b, L, o) in slots:

@@ -445,3 +445,27 @@ def test_readout_ss_block_is_the_collapsed_scalar():
 def test_mse_loss_value():
     H = np.arange(8.0).reshape(2, 2, 2)
     assert np.isclose(O.loss_mse(H, H + 2.0), 4.0) and np.isclose(O.loss_mse(H, 0 * H), np.mean(np.arange(8.0) ** 2))
+
+
+def test_half_precision_weight_mode_rounds_only_the_weights():
+    """w_dtype=float16: every stored weight is the nearest half-precision number (error <= 2^-11 relative for normal
+    numbers), nothing else changes -- a layer run with pre-rounded explicit weights gives the same result."""
+    rng = np.random.default_rng(21)
+    lmax, E, n_rbf, r_cut = 2, 4, 6, 4.0
+    paths = O.tp_paths(lmax, lmax, lmax)
+    W = synth.layer_weights(rng, lmax, E, n_rbf, 64, len(paths))
+    d = rng.uniform(0.5, 3.9, 200)
+    w = O.radial_weights(d, W["W_r1"], W["W_r2"], paths, E, n_rbf, r_cut)
+    wh = O.radial_weights(d, W["W_r1"], W["W_r2"], paths, E, n_rbf, r_cut, np.float16)
+    big = np.abs(w) > 1e-3
+    assert np.all(np.abs(wh - w)[big] <= 2.0 ** -11 * np.abs(w)[big] * (1 + 1e-12))
+    assert np.abs(wh - w).max() > 0 and np.all(wh.astype(np.float16).astype(np.float64) == wh)
+    cl = synth.small_cluster(12, 12, lmax, E, n_rbf, r_cut, 2)
+    g = O.neighbour_list(cl.pos, 12, cl.box, cl.pbc, r_cut)
+    x = rng.standard_normal((12, 9, E))
+    y_mode = O.layer_forward(g, cl.pos, cl.box, x, W, lmax, lmax, E, n_rbf, r_cut, 5.0, w_dtype=np.float16)
+    r = O.edge_vectors(cl.pos, cl.box, g[0], g[1], g[2])
+    dd = np.sqrt((r * r).sum(axis=1))
+    w_edge = O.radial_weights(dd, W["W_r1"], W["W_r2"], paths, E, n_rbf, r_cut).astype(np.float16).astype(np.float64)
+    y_explicit = O.layer_forward(g, cl.pos, cl.box, x, W, lmax, lmax, E, n_rbf, r_cut, 5.0, w_edge=w_edge)
+    assert np.array_equal(y_mode, y_explicit)
