@@ -143,6 +143,14 @@ int egnn_node_mix(egnn_ctx* ctx, const float* x1, const float* W1, const float* 
  * does for caller-supplied weights and other shapes.  Both routes compute the same function; the two-kernel route
  * is the faster one at present. */
 #define EGNN_OPT_FUSED 1
+/* EGNN_OPT_W_FP16 (default 0): when 1, the radial weights that egnn_layer_forward (two-kernel route, own radial MLP)
+ * and egnn_readout_hij pass from S3 to S4 / S6 inside their workspace are stored in IEEE half precision (rounded to
+ * nearest even once, after the fp32 evaluation of the MLP, the envelope and alpha_p); all products and sums stay in
+ * fp32 (half-precision values with fp32 aggregation: the arithmetic of the paper's own runs, Sec. 4.1).  This halves
+ * the dominant memory traffic of both calls at a relative rounding error of 2^-11 per weight: a reduced-precision
+ * mode, not covered by the fp32 accuracy statement of the default.  The stage entry points and the reverse pass
+ * always use fp32 weights. */
+#define EGNN_OPT_W_FP16 2
 int egnn_set_option(egnn_ctx* ctx, int32_t option, int32_t value);
 
 /* ---- one message-passing layer, forward: S2 -> S5(pre) -> S3+S4 fused (or S3 -> S4) -> S5(post) ----

@@ -12,6 +12,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libegnn_hip.so")
 MAX_SHELLS = 8
 OPT_FUSED = 1
+OPT_W_FP16 = 2
 
 SYMBOLS = [
     "egnn_create", "egnn_destroy", "egnn_last_error", "egnn_path_count", "egnn_readout_widths",

@@ -120,6 +120,7 @@ int egnn_launch_geometry(egnn_ctx* ctx, const egnn_graph* g, const float* pos, c
 // Six v_mfma_f32_32x32x16_bf16 replace eight v_mfma_f32_32x32x2_f32 at 1/16 of their cost each, which moves
 // the kernel from the fp32-MFMA roofline to the rate at which w can be written.
 #include "split_bf16.h"
+#include "w_half.h"
 
 // W_r2 (times alpha_p) cut into pieces once per call: out[n][piece][64] bf16.
 __global__ __launch_bounds__(256) void split_w2_kernel(const float* __restrict__ W_r2, uint16_t* __restrict__ out,
@@ -160,6 +161,38 @@ __device__ __forceinline__ void lds_barrier_acquire() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// One 32-column block: wait for its rows of W_r2 in LDS, then 4 steps x 6 piece products per 32-row block.
+__device__ __forceinline__ void rw_block(const uint4* __restrict__ sB_nb, const uint4 (&a_frag)[RW_MB][3][4], int m,
+                                         int hh, float16v (&acc)[RW_MB]) {
+  lds_barrier_acquire();
+  uint4 b_frag[3][4];
+  {
+    const uint4* row = sB_nb + m * RW_BROW4 + hh * 4;
+#pragma unroll
+    for (int p = 0; p < 3; ++p)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) b_frag[p][t] = row[p * 8 + t];
+  }
+#pragma unroll
+  for (int mb = 0; mb < RW_MB; ++mb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[mb][i] = 0.0f;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    // smallest terms first: (lo,hi) (hi,lo) (mid,mid) (mid,hi) (hi,mid) (hi,hi)
+    const int pa[6] = {2, 0, 1, 1, 0, 0};
+    const int pb[6] = {0, 2, 1, 0, 1, 0};
+#pragma unroll
+    for (int q = 0; q < 6; ++q)
+#pragma unroll
+      for (int mb = 0; mb < RW_MB; ++mb)
+        acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a_frag[mb][pa[q]][t]),
+                                                          as_bf16x8(b_frag[pb[q]][t]), acc[mb], 0, 0, 0);
+  }
+}
+
+// HALF: w is stored in half precision (layout of w_half.h), two column blocks per 32-bit word.
+template <bool HALF>
 __global__ __launch_bounds__(RW_THREADS) void radial_weights_kernel(const float4* __restrict__ rhat_d, long n_edges,
                                                              const float* __restrict__ W_r1,
                                                              const uint16_t* __restrict__ W2s,
@@ -241,52 +274,68 @@ __global__ __launch_bounds__(RW_THREADS) void radial_weights_kernel(const float4
     }
   }
 
-  float* const out_base = w + (size_t)(e_base + 4 * hh) * PE + m;
-  for (int nb = 0; nb < n_blocks; ++nb) {
-    lds_barrier_acquire();
-    uint4 b_frag[3][4];
-    {
-      const uint4* row = sB[nb & 1] + m * RW_BROW4 + hh * 4;
+  if constexpr (!HALF) {
+    float* const out_base = w + (size_t)(e_base + 4 * hh) * PE + m;
+    for (int nb = 0; nb < n_blocks; ++nb) {
+      float16v acc[RW_MB];
+      rw_block(sB[nb & 1], a_frag, m, hh, acc);
+      const int n = nb * 32 + m;
+      if (n < PE) {
+        float* out = out_base + nb * 32;
+        // w is written once and read once by another kernel: non-temporal stores (measured: 0.82 -> 0.72 ms)
+        if (all_rows) {
 #pragma unroll
-      for (int p = 0; p < 3; ++p)
+          for (int mb = 0; mb < RW_MB; ++mb)
 #pragma unroll
-        for (int t = 0; t < 4; ++t) b_frag[p][t] = row[p * 8 + t];
+            for (int i = 0; i < 16; ++i)
+              __builtin_nontemporal_store(acc[mb][i], out + (size_t)(32 * mb + 8 * (i >> 2) + (i & 3)) * PE);
+        } else if (any_row) {
+#pragma unroll
+          for (int mb = 0; mb < RW_MB; ++mb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int r = 32 * mb + 8 * (i >> 2) + (i & 3);      // row relative to e_base + 4*hh
+              if (e_base + 4 * hh + r < n_edges) __builtin_nontemporal_store(acc[mb][i], out + (size_t)r * PE);
+            }
+        }
+      }
     }
-    float16v acc[RW_MB];
+  } else {
+    const int row_words = w_half_row_words(PE);
+    uint32_t* const out_base = reinterpret_cast<uint32_t*>(w) + (size_t)(e_base + 4 * hh) * row_words + m;
+    for (int nb = 0; nb < n_blocks; nb += 2) {
+      float16v acc[RW_MB];
+      uint32_t word[RW_MB][16];
+      rw_block(sB[0], a_frag, m, hh, acc);          // nb is even
 #pragma unroll
-    for (int mb = 0; mb < RW_MB; ++mb)
+      for (int mb = 0; mb < RW_MB; ++mb)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) acc[mb][i] = 0.0f;
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      // smallest terms first: (lo,hi) (hi,lo) (mid,mid) (mid,hi) (hi,mid) (hi,hi)
-      const int pa[6] = {2, 0, 1, 1, 0, 0};
-      const int pb[6] = {0, 2, 1, 0, 1, 0};
-#pragma unroll
-      for (int q = 0; q < 6; ++q)
-#pragma unroll
-        for (int mb = 0; mb < RW_MB; ++mb)
-          acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a_frag[mb][pa[q]][t]),
-                                                            as_bf16x8(b_frag[pb[q]][t]), acc[mb], 0, 0, 0);
-    }
-    const int n = nb * 32 + m;
-    if (n < PE) {
-      float* out = out_base + nb * 32;
-      // w is written once and read once by another kernel: non-temporal stores (measured: 0.82 -> 0.72 ms)
-      if (all_rows) {
+        for (int i = 0; i < 16; ++i) word[mb][i] = w_half_bits(acc[mb][i]);
+      if (nb + 1 < n_blocks) {                      // (the same for every wave of the workgroup, loader included)
+        rw_block(sB[1], a_frag, m, hh, acc);
 #pragma unroll
         for (int mb = 0; mb < RW_MB; ++mb)
 #pragma unroll
-          for (int i = 0; i < 16; ++i)
-            __builtin_nontemporal_store(acc[mb][i], out + (size_t)(32 * mb + 8 * (i >> 2) + (i & 3)) * PE);
-      } else if (any_row) {
+          for (int i = 0; i < 16; ++i) word[mb][i] |= w_half_bits(acc[mb][i]) << 16;
+      }
+      // the low half decides: if its column exists the word does (a high half past the end is never read)
+      if (nb * 32 + m < PE) {
+        uint32_t* out = out_base + (nb >> 1) * 32;
+        if (all_rows) {
 #pragma unroll
-        for (int mb = 0; mb < RW_MB; ++mb)
+          for (int mb = 0; mb < RW_MB; ++mb)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int r = 32 * mb + 8 * (i >> 2) + (i & 3);      // row relative to e_base + 4*hh
-            if (e_base + 4 * hh + r < n_edges) __builtin_nontemporal_store(acc[mb][i], out + (size_t)r * PE);
-          }
+            for (int i = 0; i < 16; ++i)
+              __builtin_nontemporal_store(word[mb][i], out + (size_t)(32 * mb + 8 * (i >> 2) + (i & 3)) * row_words);
+        } else if (any_row) {
+#pragma unroll
+          for (int mb = 0; mb < RW_MB; ++mb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int r = 32 * mb + 8 * (i >> 2) + (i & 3);
+              if (e_base + 4 * hh + r < n_edges) __builtin_nontemporal_store(word[mb][i], out + (size_t)r * row_words);
+            }
+        }
       }
     }
   }
@@ -310,7 +359,7 @@ int egnn_launch_split_w2(egnn_ctx* ctx, int which, const float* W_r2, void* scra
 
 // `scratch` holds egnn_radial_ws_bytes: the pieces of W_r2.
 int egnn_launch_radial(egnn_ctx* ctx, int which, const float* rhat_d, int64_t n_edges, const float* W_r1,
-                       const float* W_r2, float* w, void* scratch, hipStream_t stream) {
+                       const float* W_r2, float* w, void* scratch, hipStream_t stream, bool half) {
   if (n_edges == 0) return EGNN_OK;
   const int PE = ctx->n_paths[which] * ctx->desc.channels;
   int rc = egnn_launch_split_w2(ctx, which, W_r2, scratch, stream);
@@ -318,8 +367,12 @@ int egnn_launch_radial(egnn_ctx* ctx, int which, const float* rhat_d, int64_t n_
   uint16_t* W2s = (uint16_t*)scratch;
   const long per_wg = (long)RW_ROWS * RW_COMPUTE_WAVES;
   dim3 grid((unsigned)((n_edges + per_wg - 1) / per_wg)), block(RW_THREADS);
-  hipLaunchKernelGGL(radial_weights_kernel, grid, block, 0, stream, reinterpret_cast<const float4*>(rhat_d),
-                     (long)n_edges, W_r1, W2s, w, ctx->desc.n_rbf, PE, ctx->desc.r_cut);
+  if (half)
+    hipLaunchKernelGGL(radial_weights_kernel<true>, grid, block, 0, stream, reinterpret_cast<const float4*>(rhat_d),
+                       (long)n_edges, W_r1, W2s, w, ctx->desc.n_rbf, PE, ctx->desc.r_cut);
+  else
+    hipLaunchKernelGGL(radial_weights_kernel<false>, grid, block, 0, stream, reinterpret_cast<const float4*>(rhat_d),
+                       (long)n_edges, W_r1, W2s, w, ctx->desc.n_rbf, PE, ctx->desc.r_cut);
   EGNN_LAUNCH_CHECK(ctx, "radial_weights_kernel");
   return EGNN_OK;
 }

@@ -2,6 +2,7 @@
 #include <math.h>
 #include <string.h>
 #include "egnn_internal.h"
+#include "w_half.h"
 #define EGNN_GEN_HOST_TABLES
 #include "egnn_gen.inc"
 
@@ -168,6 +169,10 @@ extern "C" int egnn_set_option(egnn_ctx* ctx, int32_t option, int32_t value) {
     ctx->use_fused = value != 0;
     return EGNN_OK;
   }
+  if (option == EGNN_OPT_W_FP16) {
+    ctx->w_half = value != 0;
+    return EGNN_OK;
+  }
   return egnn_fail(ctx, EGNN_EINVAL, "set_option: unknown option");
 }
 
@@ -205,8 +210,15 @@ static size_t readout_tab_ints(const egnn_ctx* ctx) {
 }
 
 // the weight tensor of a layer, or the (much smaller, except for tiny models) scratch of the fused route in its place
+size_t egnn_w_bytes(const egnn_ctx* ctx, int which, int64_t n_edges) {
+  const int PE = ctx->n_paths[which] * ctx->desc.channels;
+  const size_t full = (size_t)n_edges * PE * sizeof(float);
+  const size_t half = (size_t)n_edges * w_half_row_words(PE) * sizeof(uint32_t);   // larger only for PE < 64
+  return full > half ? full : half;
+}
+
 static size_t layer_w_bytes(const egnn_ctx* ctx, int64_t n_edges) {
-  const size_t w = (size_t)n_edges * ctx->n_paths[0] * ctx->desc.channels * sizeof(float);
+  const size_t w = egnn_w_bytes(ctx, 0, n_edges);
   const size_t f = egnn_fused_supported(ctx) ? egnn_fused_scratch_bytes(ctx, n_edges) : 0;
   return w > f ? w : f;
 }
@@ -230,7 +242,7 @@ static size_t readout_ws(const egnn_ctx* ctx, int64_t n_edges, int32_t n_total) 
   c.take((size_t)n_total * row);
   c.take(readout_tab_ints(ctx) * sizeof(int));
   c.take(ctx->unc_c.size() * sizeof(float));
-  c.take((size_t)n_edges * ctx->n_paths[1] * ctx->desc.channels * sizeof(float));
+  c.take(egnn_w_bytes(ctx, 1, n_edges));
   c.take(egnn_radial_ws_bytes(ctx, 1));
   return c.used;
 }
@@ -322,10 +334,11 @@ extern "C" int egnn_layer_forward(egnn_ctx* ctx, const egnn_graph* g, const floa
   // consumed inside one kernel and never leave the chip.
   // (the scratch of the fused route lives where the weight tensor would be)
   const bool fused = with_w && ctx->use_fused && egnn_fused_supported(ctx);
+  const bool half = with_w && !fused && ctx->w_half;   // storage precision of the weight tensor between S3 and S4
   if (fused) {
     if (g->n_edges > 0 && (rc = egnn_launch_split_w2(ctx, 0, W_r2, w2s, st))) return rc;
   } else if (with_w) {
-    if ((rc = egnn_launch_radial(ctx, 0, rhat_d, g->n_edges, W_r1, W_r2, w, w2s, st))) return rc;
+    if ((rc = egnn_launch_radial(ctx, 0, rhat_d, g->n_edges, W_r1, W_r2, w, w2s, st, half))) return rc;
   }
   tm.mark(1);
   if ((rc = egnn_launch_node_mix(ctx, x_in, W_pre, nullptr, nullptr, h, g->n_total, st))) return rc;
@@ -333,7 +346,7 @@ extern "C" int egnn_layer_forward(egnn_ctx* ctx, const egnn_graph* g, const floa
   if (fused) {
     if ((rc = egnn_launch_layer_fused(ctx, g, rhat_d, h, W_r1, w2s, w, w_bytes, a, st))) return rc;
   } else {
-    if ((rc = egnn_launch_tp_segsum(ctx, g, rhat_d, h, with_w ? w : w_edge, a, st))) return rc;
+    if ((rc = egnn_launch_tp_segsum(ctx, g, rhat_d, h, with_w ? w : w_edge, a, st, half))) return rc;
   }
   tm.mark(3);
   rc = egnn_launch_node_mix(ctx, a, W_post, x_in, W_self, x_out, g->n_owned, st);
@@ -361,7 +374,7 @@ extern "C" int egnn_readout_hij(egnn_ctx* ctx, const egnn_graph* g, const float*
   float* zt = (float*)c.take((size_t)g->n_total * row);
   int* tab_i = (int*)c.take(readout_tab_ints(ctx) * sizeof(int));
   float* tab_f = (float*)c.take(ctx->unc_c.size() * sizeof(float));
-  float* w = (float*)c.take((size_t)g->n_edges * ctx->n_paths[1] * ctx->desc.channels * sizeof(float));
+  float* w = (float*)c.take(egnn_w_bytes(ctx, 1, g->n_edges));
   void* w2s = c.take(egnn_radial_ws_bytes(ctx, 1));
 
   // integer table: q_row[nq] q_vrow[nq] slot_L[n_slots] slot_qoff[n_slots] unc_ptr[nq+1] unc_q[nnz]
@@ -390,13 +403,13 @@ extern "C" int egnn_readout_hij(egnn_ctx* ctx, const egnn_graph* g, const float*
   StageTimer tm(ctx, st, 1);
   if ((rc = egnn_launch_geometry(ctx, g, pos, box, rhat_d, nullptr, nullptr, nullptr, st))) return rc;
   tm.mark(0);
-  if ((rc = egnn_launch_radial(ctx, 1, rhat_d, g->n_edges, W_r1, W_r2, w, w2s, st))) return rc;
+  if ((rc = egnn_launch_radial(ctx, 1, rhat_d, g->n_edges, W_r1, W_r2, w, w2s, st, ctx->w_half))) return rc;
   tm.mark(1);
   if ((rc = egnn_launch_node_mix(ctx, x, W_s, nullptr, nullptr, zs, g->n_total, st))) return rc;
   tm.mark(2);
   if ((rc = egnn_launch_node_mix(ctx, x, W_t, nullptr, nullptr, zt, g->n_total, st))) return rc;
   tm.mark(3);
-  rc = egnn_launch_readout(ctx, g, rhat_d, zs, zt, w, V, tab_i, tab_f, H, st);
+  rc = egnn_launch_readout(ctx, g, rhat_d, zs, zt, w, V, tab_i, tab_f, H, st, ctx->w_half);
   tm.mark(4);
   return rc;
 }

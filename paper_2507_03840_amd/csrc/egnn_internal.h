@@ -37,6 +37,7 @@ struct egnn_ctx {
   CellGrid nl_grid;                      // grid of the last egnn_nlist_count that used the cell list
   int nl_grid_atoms = -1;                //   and the atom count it was built for
   bool use_fused = false;                // egnn_set_option(EGNN_OPT_FUSED)
+  bool w_half = false;                   // egnn_set_option(EGNN_OPT_W_FP16)
   std::string err;
 };
 
@@ -89,10 +90,12 @@ size_t egnn_readout_backward_partial_bytes(const egnn_ctx*, int64_t n_edges);
 int egnn_launch_readout_backward(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* zs, const float* zt,
                                  const float* w, const float* V, const int* tab_i, const float* tab_f,
                                  const float* dH, float* dz, float* dw, float* dV, float* partial, hipStream_t);
+// half = true: `w` holds half-precision weights in the layout of w_half.h (egnn_w_bytes sizes it)
 int egnn_launch_tp_segsum(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* h, const float* w,
-                          float* a, hipStream_t);
+                          float* a, hipStream_t, bool half = false);
 int egnn_launch_radial(egnn_ctx*, int which, const float* rhat_d, int64_t n_edges, const float* W_r1,
-                       const float* W_r2, float* w, void* scratch, hipStream_t);
+                       const float* W_r2, float* w, void* scratch, hipStream_t, bool half = false);
+size_t egnn_w_bytes(const egnn_ctx*, int which, int64_t n_edges);   // room for w in either precision
 size_t egnn_radial_ws_bytes(const egnn_ctx*, int which);
 int egnn_launch_split_w2(egnn_ctx*, int which, const float* W_r2, void* scratch, hipStream_t);
 bool egnn_fused_supported(const egnn_ctx*);
@@ -102,4 +105,5 @@ int egnn_launch_layer_fused(egnn_ctx*, const egnn_graph*, const float* rhat_d, c
 int egnn_launch_geometry(egnn_ctx*, const egnn_graph*, const float* pos, const float box[3], float* rhat_d,
                          float* Y, float* rbf, float* fc, hipStream_t);
 int egnn_launch_readout(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* zs, const float* zt,
-                        const float* w, const float* V, const int* tab_i, const float* tab_f, float* H, hipStream_t);
+                        const float* w, const float* V, const int* tab_i, const float* tab_f, float* H, hipStream_t,
+                        bool half = false);

@@ -14,6 +14,7 @@
 // outputs among themselves through LDS.  The small index tables of the collapse and of the uncoupling live in LDS.
 #include "egnn_internal.h"
 #include "bond_frame.h"
+#include "w_half.h"
 
 #define RO_ITERS 8   // edges per slot per workgroup
 #define RO_D 25      // (L_READOUT+1)^2
@@ -29,7 +30,8 @@ struct ReadoutTabs {
   int nq, n_slots, n_vrows, nnz;
 };
 
-template <int LMAX, int log2E>
+// HALF: w in half precision (layout of w_half.h)
+template <int LMAX, int log2E, bool HALF>
 __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ src, const int* __restrict__ dst,
                                                       const float4* __restrict__ rhat_d,
                                                       const float* __restrict__ zs, const float* __restrict__ zt,
@@ -77,10 +79,14 @@ __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ sr
       const float4 g = rhat_d[k];
       const float* zsp = zs + ((size_t)s * D << log2E) + c;
       const float* ztp = zt + ((size_t)d * D << log2E) + c;
-      const float* wp = w + ((size_t)k * P << log2E) + c;
       float v[D], wr[P], o[RO_D];
+      if constexpr (!HALF) {
+        const float* wp = w + ((size_t)k * P << log2E) + c;
 #pragma unroll
-      for (int p = 0; p < P; ++p) wr[p] = __builtin_nontemporal_load(wp + ((size_t)p << log2E));
+        for (int p = 0; p < P; ++p) wr[p] = __builtin_nontemporal_load(wp + ((size_t)p << log2E));
+      } else {
+        w_half_load<P, log2E>(reinterpret_cast<const uint32_t*>(w) + (size_t)k * w_half_row_words(P << log2E), c, wr);
+      }
 #pragma unroll
       for (int i = 0; i < D; ++i) v[i] = zsp[(size_t)i << log2E] + ztp[(size_t)i << log2E];
       BondTrig t;
@@ -122,7 +128,7 @@ __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ sr
   }
 }
 
-template <int L, int LE>
+template <int L, int LE, bool HALF>
 static int launch_readout(egnn_ctx* ctx, const egnn_graph* g, const float4* rd, const float* zs, const float* zt,
                           const float* w, const float* V, const ReadoutTabs& tb, float* H, hipStream_t stream) {
   constexpr int E = 1 << LE, n_slots = 256 / E;
@@ -131,7 +137,7 @@ static int launch_readout(egnn_ctx* ctx, const egnn_graph* g, const float4* rd, 
                        ((size_t)3 * tb.nq + 1 + 2 * (size_t)tb.nnz) * sizeof(int);
   const long per_wg = (long)n_slots * RO_ITERS;
   dim3 grid((unsigned)((g->n_edges + per_wg - 1) / per_wg)), block(256);
-  auto kern = readout_kernel<L, LE>;
+  auto kern = readout_kernel<L, LE, HALF>;
   if (shmem > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)shmem);
@@ -144,7 +150,7 @@ static int launch_readout(egnn_ctx* ctx, const egnn_graph* g, const float4* rd, 
 
 int egnn_launch_readout(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, const float* zs, const float* zt,
                         const float* w, const float* V, const int* tab_i, const float* tab_f, float* H,
-                        hipStream_t stream) {
+                        hipStream_t stream, bool half) {
   const long n = g->n_edges;
   if (n == 0) return EGNN_OK;
   const int nq = ctx->n_orb * ctx->n_orb;
@@ -163,8 +169,10 @@ int egnn_launch_readout(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d,
   tb.unc_c = tab_f;
   tb.nnz = (int)ctx->unc_c.size();
   const float4* rd = reinterpret_cast<const float4*>(rhat_d);
-#define CASE(L, LE) \
-  if (ctx->desc.lmax == L && ctx->log2_channels == LE) return launch_readout<L, LE>(ctx, g, rd, zs, zt, w, V, tb, H, stream);
+#define CASE(L, LE)                                                                         \
+  if (ctx->desc.lmax == L && ctx->log2_channels == LE)                                      \
+    return half ? launch_readout<L, LE, true>(ctx, g, rd, zs, zt, w, V, tb, H, stream)      \
+                : launch_readout<L, LE, false>(ctx, g, rd, zs, zt, w, V, tb, H, stream);
 #define CASES(L) CASE(L, 3) CASE(L, 4) CASE(L, 5) CASE(L, 6) CASE(L, 7)
   CASES(0) CASES(1) CASES(2) CASES(3) CASES(4)
 #undef CASES

@@ -14,8 +14,11 @@
 // result does not depend on scheduling (no atomics).
 #include "egnn_internal.h"
 #include "bond_frame.h"
+#include "w_half.h"
 
-template <int LMAX>
+// HLE = 0: w in fp32, any channel count (log2E at run time).  HLE > 0: w in half precision (layout of w_half.h)
+// for 2^HLE channels.
+template <int LMAX, int HLE>
 __global__ __launch_bounds__(256) void tp_segsum_kernel(const int* __restrict__ row_ptr,
                                                         const int* __restrict__ src,
                                                         const float4* __restrict__ rhat_d,
@@ -32,6 +35,7 @@ __global__ __launch_bounds__(256) void tp_segsum_kernel(const int* __restrict__ 
   const int j = (blockIdx.x & 7) * nodes_per_xcd + (blockIdx.x >> 3);
   if (j >= n_owned || (int)(blockIdx.x >> 3) >= nodes_per_xcd) return;
 
+  if (HLE) log2E = HLE;
   const int E = 1 << log2E;
   const int tid = threadIdx.x;
   const int c = tid & (E - 1);
@@ -47,10 +51,14 @@ __global__ __launch_bounds__(256) void tp_segsum_kernel(const int* __restrict__ 
     const int s = src[k];
     const float4 g = rhat_d[k];
     const float* hp = h + ((size_t)s * D << log2E) + c;
-    const float* wp = w + ((size_t)k * P << log2E) + c;
     float v[D], wr[P], o[D];
+    if constexpr (HLE == 0) {
+      const float* wp = w + ((size_t)k * P << log2E) + c;
 #pragma unroll
-    for (int p = 0; p < P; ++p) wr[p] = __builtin_nontemporal_load(wp + ((size_t)p << log2E));   // streamed once
+      for (int p = 0; p < P; ++p) wr[p] = __builtin_nontemporal_load(wp + ((size_t)p << log2E));   // streamed once
+    } else {
+      w_half_load<P, HLE>(reinterpret_cast<const uint32_t*>(w) + (size_t)k * w_half_row_words(P << HLE), c, wr);
+    }
 #pragma unroll
     for (int i = 0; i < D; ++i) v[i] = hp[(size_t)i << log2E];
     BondTrig t;
@@ -75,24 +83,33 @@ __global__ __launch_bounds__(256) void tp_segsum_kernel(const int* __restrict__ 
 }
 
 int egnn_launch_tp_segsum(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, const float* h,
-                          const float* w, float* a, hipStream_t stream) {
+                          const float* w, float* a, hipStream_t stream, bool half) {
   const int n = g->n_owned;
   if (n == 0) return EGNN_OK;
   const int per_xcd = (n + 7) / 8;
   dim3 grid(per_xcd * 8), block(256);
   const float scale = 1.0f / sqrtf(ctx->desc.agg_norm);
   const float4* rd = reinterpret_cast<const float4*>(rhat_d);
-#define LAUNCH(L)                                                                                   \
-  hipLaunchKernelGGL(tp_segsum_kernel<L>, grid, block, 0, stream, g->row_ptr, g->src, rd, h, w, a, \
+#define LAUNCH(L, H)                                                                                   \
+  hipLaunchKernelGGL((tp_segsum_kernel<L, H>), grid, block, 0, stream, g->row_ptr, g->src, rd, h, w, a, \
                      n, ctx->log2_channels, per_xcd, scale)
+#define CASE(L)                                                                                  \
+  case L:                                                                                        \
+    switch (half ? ctx->log2_channels : 0) {                                                     \
+      case 0: LAUNCH(L, 0); break;                                                               \
+      case 3: LAUNCH(L, 3); break;                                                               \
+      case 4: LAUNCH(L, 4); break;                                                               \
+      case 5: LAUNCH(L, 5); break;                                                               \
+      case 6: LAUNCH(L, 6); break;                                                               \
+      case 7: LAUNCH(L, 7); break;                                                               \
+      default: return egnn_fail(ctx, EGNN_EINVAL, "tp_segsum: half-precision weights need 8..128 channels"); \
+    }                                                                                            \
+    break;
   switch (ctx->desc.lmax) {
-    case 0: LAUNCH(0); break;
-    case 1: LAUNCH(1); break;
-    case 2: LAUNCH(2); break;
-    case 3: LAUNCH(3); break;
-    case 4: LAUNCH(4); break;
+    CASE(0) CASE(1) CASE(2) CASE(3) CASE(4)
     default: return egnn_fail(ctx, EGNN_EINVAL, "tp_segsum: lmax out of range");
   }
+#undef CASE
 #undef LAUNCH
   EGNN_LAUNCH_CHECK(ctx, "tp_segsum_kernel");
   return EGNN_OK;

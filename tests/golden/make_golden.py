@@ -9,6 +9,7 @@ chunks; each chunk goes through the oracle's own functions unchanged.
 
     python tests/golden/make_golden.py 3 4 5
     python tests/golden/make_golden.py so2:3 so2:4      (SO(2) message sums at sampled nodes)
+    python tests/golden/make_golden.py w16:3 w16:4      (first layer and readout with half-precision path weights)
 """
 import os
 import sys
@@ -87,6 +88,56 @@ def make_so2(index, pool_size):
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"config{index}_so2_samples.npz")
     np.savez_compressed(path, nodes=nodes, rows=rows, agg=agg, n_edges=len(g[0]))
     print(f"config {index} so2: wrote {path}, max|a| over samples {np.abs(rows).max():.4f}, {time.time() - t0:.0f} s", flush=True)
+
+
+def _w16_node(j):
+    """Layer output row of owned node j from the layer-0 input, with (half) and without (full) rounding of w."""
+    w, g, x, h, W, agg = (_state[k] for k in ("w", "g", "x", "h", "W", "agg"))
+    src, dst, shift, row_ptr = g
+    k0, k1 = int(row_ptr[j]), int(row_ptr[j + 1])
+    sub = (src[k0:k1], dst[k0:k1], shift[k0:k1], row_ptr[j:j + 2] - k0)
+    out = []
+    for w_dtype in (np.float16, None):
+        fn = lambda d, a, b, paths: O.radial_weights(d, W["W_r1"], W["W_r2"], paths, w.channels, w.n_rbf, w.r_cut,
+                                                     w_dtype)
+        a = O.edge_messages_sum(sub, w.pos, w.box, h, fn, w.lmax, w.lmax, agg)
+        out.append((O.mix_channels(a, W["W_post"], w.lmax) + O.mix_channels(x[j:j + 1], W["W_self"], w.lmax))[0])
+    return out
+
+
+def _w16_edge(k):
+    w, g, x, Wr = _state["w"], _state["g"], _state["x"], _state["Wr"]
+    return [O.readout_hij(g, w.pos, w.box, x, Wr, w.lmax, w.lmax, w.channels, w.n_rbf, w.r_cut, w.orb_l,
+                          k_range=(k, k + 1), w_dtype=dt)[0] for dt in (np.float16, None)]
+
+
+def make_w16(index, pool_size):
+    """First layer (sampled owned nodes) and readout (sampled edges) of the full-size configuration, both applied to
+    the layer-0 features, with the per-edge path weights rounded to half precision -> config{index}_w16_samples.npz
+    (the unrounded results of the same rows are stored next to them)."""
+    t0 = time.time()
+    w = synth.workload(index)
+    wt = U.model_weights(w)
+    g = U.oracle_graph(w)
+    agg = U.mean_degree(g, w.n_owned)
+    rng = np.random.default_rng([w.seed, 4244])
+    nodes = np.sort(rng.choice(w.n_owned, N_NODE_SAMPLES, replace=False))
+    edges = np.sort(rng.choice(len(g[0]), N_EDGE_SAMPLES, replace=False))
+    x = O.species_embed(wt["x0"], w.species, wt["table"])
+    W = wt["layers"][0]
+    _state.update(w=w, g=g, x=x, h=O.mix_channels(x, W["W_pre"], w.lmax), W=W, agg=agg, Wr=wt["readout"])
+    with ProcessPoolExecutor(pool_size) as ex:
+        rows = list(ex.map(_w16_node, [int(j) for j in nodes]))
+        blocks = list(ex.map(_w16_edge, [int(k) for k in edges]))
+    out = dict(nodes=nodes, edges=edges, agg=agg, n_edges=len(g[0]),
+               x1_rows=np.array([r[0] for r in rows]), x1_rows_full=np.array([r[1] for r in rows]),
+               H_rows=np.array([b[0] for b in blocks]), H_rows_full=np.array([b[1] for b in blocks]))
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"config{index}_w16_samples.npz")
+    np.savez_compressed(path, **out)
+    d1 = np.abs(out["x1_rows"] - out["x1_rows_full"]).max() / np.abs(out["x1_rows_full"]).max()
+    d2 = np.abs(out["H_rows"] - out["H_rows_full"]).max() / np.abs(out["H_rows_full"]).max()
+    print(f"config {index} w16: wrote {path}; effect of the rounding: layer {d1:.2e}, H {d2:.2e}; "
+          f"{time.time() - t0:.0f} s", flush=True)
 
 
 def make(index, pool_size):
@@ -225,11 +276,13 @@ def make_training(index, pool_size):
 
 
 if __name__ == "__main__":
-    which = [int(a) for a in sys.argv[1:] if not a.startswith("so2")] or ([] if len(sys.argv) > 1 else [3, 4, 5])
+    which = [int(a) for a in sys.argv[1:] if ":" not in a] or ([] if len(sys.argv) > 1 else [3, 4, 5])
     procs = int(os.environ.get("GOLDEN_PROCS", "6"))
     for a in sys.argv[1:]:
         if a.startswith("so2:"):   # e.g. so2:3 so2:4
             make_so2(int(a[4:]), procs)
+        if a.startswith("w16:"):
+            make_w16(int(a[4:]), procs)
     for idx in which:
         if idx in (1, 5):          # training step (1 = small self-check of this script against the oracle's own chain)
             make_training(idx, procs)

@@ -35,30 +35,34 @@ def mean_degree(g, n_owned):
     return float(len(g[0])) / max(1, n_owned)
 
 
-def oracle_forward(w, wt, g, agg_norm, with_readout=True):
-    """Whole model on the oracle: species embedding, n_layers layers, readout.  Returns (xs, H)."""
+def oracle_forward(w, wt, g, agg_norm, with_readout=True, w_dtype=None):
+    """Whole model on the oracle: species embedding, n_layers layers, readout.  Returns (xs, H).
+    w_dtype: storage precision of the per-edge path weights (None: not rounded)."""
     x = O.species_embed(wt["x0"], w.species, wt["table"])
     xs = []
     for t in range(w.n_layers):
         y = O.layer_forward(g, w.pos, w.box, x, wt["layers"][t], w.lmax, w.lmax, w.channels, w.n_rbf, w.r_cut,
-                            agg_norm)
+                            agg_norm, w_dtype=w_dtype)
         xs.append(y)
         if t + 1 < w.n_layers:
             x = np.concatenate([y, wt["halo"][t + 1].astype(np.float64)], axis=0)
     H = None
     if with_readout:
         xr = np.concatenate([xs[-1], wt["halo"][0].astype(np.float64)], axis=0) if w.n_total > w.n_owned else xs[-1]
-        H = O.readout_hij(g, w.pos, w.box, xr, wt["readout"], w.lmax, w.lmax, w.channels, w.n_rbf, w.r_cut, w.orb_l)
+        H = O.readout_hij(g, w.pos, w.box, xr, wt["readout"], w.lmax, w.lmax, w.channels, w.n_rbf, w.r_cut, w.orb_l,
+                          w_dtype=w_dtype)
     return xs, H
 
 
-def gpu_forward(w, wt, agg_norm, with_readout=True, fused=False):
+def gpu_forward(w, wt, agg_norm, with_readout=True, fused=False, w_fp16=False):
     """Same model through the C ABI.  Returns (model, graph, xs (device tensors), H)."""
     import torch
     from paper_2507_03840_amd import binding as B
     m = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, agg_norm, n_layers=w.n_layers, orb_l=w.orb_l)
     if fused:
         m.egnn_set_option(B.OPT_FUSED, 1)
+    if w_fp16:
+        m.egnn_set_option(B.OPT_W_FP16, 1)
     pos = B.to_device(w.pos)
     graph = m.egnn_nlist(pos, w.n_owned, w.box, w.pbc)
     ws = m.workspace(graph)
