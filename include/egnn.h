@@ -132,6 +132,18 @@ int egnn_radial_weights(egnn_ctx* ctx, int which, const float* rhat_d, int64_t n
 int egnn_tp_segsum(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, const float* h,
                    const float* w, float* a, void* stream);
 
+/* ---- S3 / S4 with the weights stored in half precision (storage only: the weights are evaluated in fp32 as in
+ *      egnn_radial_weights, rounded to nearest even once, and converted back to fp32 before use; half-precision
+ *      values with fp32 sums are the arithmetic of the paper's own runs, Sec. 4.1) ----
+ * w16 [n_edges][row_words] 32-bit words, row_words = 32 * ceil(P * channels / 64): word m (0..31) of group j of a
+ * row holds column n = 64 j + m in its low 16 bits and column n + 32 in its high 16 bits, n = p * channels + c
+ * (halves whose column is >= P * channels are unspecified).  Other arguments as in the fp32 calls. */
+int egnn_radial_weights_f16(egnn_ctx* ctx, int which, const float* rhat_d, int64_t n_edges,
+                            const float* W_r1, const float* W_r2, uint32_t* w16, void* ws, size_t ws_bytes,
+                            void* stream);
+int egnn_tp_segsum_f16(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, const float* h,
+                       const uint32_t* w16, float* a, void* stream);
+
 /* ---- S5  per-degree channel mix (the per-l linear of Fig. 2(d)) ----
  * y[n][(l,m)][c] = sum_c' W1[l][c][c'] x1[n][(l,m)][c'] (+ sum_c' W2[l][c][c'] x2[n][(l,m)][c'] if W2 != NULL). */
 int egnn_node_mix(egnn_ctx* ctx, const float* x1, const float* W1, const float* x2, const float* W2,
@@ -144,12 +156,10 @@ int egnn_node_mix(egnn_ctx* ctx, const float* x1, const float* W1, const float* 
  * is the faster one at present. */
 #define EGNN_OPT_FUSED 1
 /* EGNN_OPT_W_FP16 (default 0): when 1, the radial weights that egnn_layer_forward (two-kernel route, own radial MLP)
- * and egnn_readout_hij pass from S3 to S4 / S6 inside their workspace are stored in IEEE half precision (rounded to
- * nearest even once, after the fp32 evaluation of the MLP, the envelope and alpha_p); all products and sums stay in
- * fp32 (half-precision values with fp32 aggregation: the arithmetic of the paper's own runs, Sec. 4.1).  This halves
- * the dominant memory traffic of both calls at a relative rounding error of 2^-11 per weight: a reduced-precision
- * mode, not covered by the fp32 accuracy statement of the default.  The stage entry points and the reverse pass
- * always use fp32 weights. */
+ * and egnn_readout_hij pass from S3 to S4 / S6 inside their workspace are stored in half precision, as by
+ * egnn_radial_weights_f16; all products and sums stay in fp32.  This halves the dominant memory traffic of both
+ * calls at a relative rounding error of 2^-12 per weight: a reduced-precision mode, not covered by the fp32 accuracy
+ * statement of the default.  Caller-supplied w_edge and the reverse pass always use fp32 weights. */
 #define EGNN_OPT_W_FP16 2
 int egnn_set_option(egnn_ctx* ctx, int32_t option, int32_t value);
 

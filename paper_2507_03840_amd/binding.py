@@ -20,7 +20,7 @@ SYMBOLS = [
     "egnn_edge_geometry", "egnn_radial_weights", "egnn_tp_segsum", "egnn_node_mix",
     "egnn_layer_forward", "egnn_readout_hij", "egnn_timing_enable", "egnn_timing_read",
     "egnn_backward_workspace_bytes", "egnn_graph_transpose", "egnn_loss_mse", "egnn_layer_backward",
-    "egnn_readout_backward", "egnn_set_option", "egnn_so2_weight_count", "egnn_so2_workspace_bytes",
+    "egnn_readout_backward", "egnn_set_option", "egnn_radial_weights_f16", "egnn_tp_segsum_f16", "egnn_so2_weight_count", "egnn_so2_workspace_bytes",
     "egnn_so2_message_sum",
 ]
 
@@ -205,6 +205,25 @@ class Egnn:
         self._check(self.lib.egnn_radial_weights(self.ctx, which, _ptr(rhat_d), C.c_int64(n), _ptr(W_r1), _ptr(W_r2),
                                                  _ptr(w), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
         return w
+
+    def egnn_radial_weights_f16(self, which, rhat_d, W_r1, W_r2):
+        """Half-precision weights, packed: int32 tensor [n_edges][32 * ceil(P * channels / 64)]."""
+        n = rhat_d.shape[0]
+        P = self.n_paths if which == 0 else self.n_paths_readout
+        w16 = torch.empty((n, 32 * ((P * self.channels + 63) // 64)), dtype=torch.int32, device="cuda")
+        ws = torch.empty(384 * P * self.channels, dtype=torch.uint8, device="cuda")
+        self._check(self.lib.egnn_radial_weights_f16(self.ctx, which, _ptr(rhat_d), C.c_int64(n), _ptr(W_r1),
+                                                     _ptr(W_r2), _ptr(w16), _ptr(ws), C.c_size_t(ws.numel()),
+                                                     _stream()))
+        return w16
+
+    def egnn_tp_segsum_f16(self, graph, rhat_d, h, w16, out=None):
+        a = out if out is not None else torch.empty((graph.n_owned, self.dim, self.channels), dtype=torch.float32,
+                                                    device="cuda")
+        g = graph.desc()
+        self._check(self.lib.egnn_tp_segsum_f16(self.ctx, C.byref(g), _ptr(rhat_d), _ptr(h), _ptr(w16), _ptr(a),
+                                                _stream()))
+        return a
 
     # ---- S4
     def egnn_tp_segsum(self, graph, rhat_d, h, w, out=None):

@@ -295,6 +295,28 @@ extern "C" int egnn_tp_segsum(egnn_ctx* ctx, const egnn_graph* g, const float* r
   return egnn_launch_tp_segsum(ctx, g, rhat_d, h, w, a, (hipStream_t)stream);
 }
 
+// the same two stages with w in half precision
+extern "C" int egnn_radial_weights_f16(egnn_ctx* ctx, int which, const float* rhat_d, int64_t n_edges,
+                                       const float* W_r1, const float* W_r2, uint32_t* w16, void* ws, size_t ws_bytes,
+                                       void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  if (which < 0 || which > 1 || n_edges < 0 || !rhat_d || !W_r1 || !W_r2 || !w16 || !ws)
+    return egnn_fail(ctx, EGNN_EINVAL, "radial_weights_f16: bad argument");
+  if (((uintptr_t)ws & 255) != 0) return egnn_fail(ctx, EGNN_EINVAL, "radial_weights_f16: workspace not 256-byte aligned");
+  if (ws_bytes < egnn_radial_ws_bytes(ctx, which)) return egnn_fail(ctx, EGNN_EWS, "radial_weights_f16: workspace too small");
+  return egnn_launch_radial(ctx, which, rhat_d, n_edges, W_r1, W_r2, reinterpret_cast<float*>(w16), ws,
+                            (hipStream_t)stream, true);
+}
+
+extern "C" int egnn_tp_segsum_f16(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, const float* h,
+                                  const uint32_t* w16, float* a, void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  int rc = check_graph(ctx, g, "tp_segsum_f16");
+  if (rc) return rc;
+  if (!rhat_d || !h || !w16 || !a) return egnn_fail(ctx, EGNN_EINVAL, "tp_segsum_f16: null pointer");
+  return egnn_launch_tp_segsum(ctx, g, rhat_d, h, reinterpret_cast<const float*>(w16), a, (hipStream_t)stream, true);
+}
+
 extern "C" int egnn_node_mix(egnn_ctx* ctx, const float* x1, const float* W1, const float* x2, const float* W2,
                              float* y, int32_t n_nodes, void* stream) {
   if (!ctx) return EGNN_EINVAL;

@@ -1,10 +1,16 @@
-"""GPU parity of the half-precision weight-storage option (EGNN_OPT_W_FP16) against the oracle run with its weights
-rounded the same way (w_dtype=float16): same 1e-4 bar as the fp32 path, on small ragged shapes of every channel
-width and degree, on configs 1 and 2 in full, and on sampled rows of the full-size configs 3 and 4.
+"""GPU parity of the half-precision storage of the per-edge path weights (egnn_radial_weights_f16,
+egnn_tp_segsum_f16, EGNN_OPT_W_FP16) against the oracle run with its weights rounded the same way (w_dtype=float16).
 
-Both sides round w to half precision after evaluating it in their own working precision (fp32 on the GPU, fp64 in
-the oracle), so a weight that lies within ~1e-6 relative of a rounding boundary may land on the neighbouring half
-value; that moves one of the thousands of terms of an output by 2^-11 of itself, far below the bar.
+Rounding w to half precision is a quantisation decided by floating point: the GPU takes it on its fp32 value of w,
+the oracle on its fp64 value, and a weight within the fp32 evaluation error of a rounding boundary lands on the
+neighbouring code (a step of 2^-11 of that weight instead of an error of ~1e-6 of it).  The tests therefore split the
+path where the decision is taken:
+  * the codes themselves: equal to the oracle's, except where the oracle's value lies within the fp32 stage tolerance
+    of the boundary between the two codes (and then only the neighbouring code is accepted);
+  * the consumer (S4) fed with codes made by the oracle, so that both sides use identical weights: fp32 bar;
+  * the composite calls: layer outputs (sums over ~10^2 edges x paths average the few flipped codes out) at the 1e-4
+    bar; H_ij blocks (one edge each, nothing averages) within the size of the rounding itself in the max norm and
+    far below it in the root-mean-square, where the rare flips do not dominate.
 """
 import os
 import numpy as np
@@ -26,6 +32,99 @@ def B():
     return binding
 
 
+def unpack_w16(words, n_cols):
+    """int32 [n][32 * groups] -> float64 [n][n_cols] (layout of egnn_radial_weights_f16)."""
+    u = np.ascontiguousarray(words).view(np.uint32)
+    n, rw = u.shape
+    lo = (u & 0xffff).astype(np.uint16).view(np.float16).reshape(n, rw // 32, 1, 32)
+    hi = (u >> 16).astype(np.uint16).view(np.float16).reshape(n, rw // 32, 1, 32)
+    return np.concatenate([lo, hi], axis=2).reshape(n, rw * 2)[:, :n_cols].astype(np.float64)
+
+
+def pack_w16(w, fill=0.0):
+    """float [n][n_cols] -> int32 words in the same layout (values rounded to half precision, nearest even)."""
+    n, nc = w.shape
+    groups = (nc + 63) // 64
+    full = np.full((n, groups * 64), fill, np.float64)
+    full[:, :nc] = w
+    codes = full.astype(np.float16).view(np.uint16).astype(np.uint32).reshape(n, groups, 2, 32)
+    return (codes[:, :, 0, :] | (codes[:, :, 1, :] << 16)).reshape(n, groups * 32).view(np.int32)
+
+
+def test_pack_unpack_roundtrip_host():
+    rng = np.random.default_rng(0)
+    for nc in (8, 24, 64, 96, 1344):
+        w = rng.standard_normal((5, nc))
+        assert np.array_equal(unpack_w16(pack_w16(w), nc), w.astype(np.float16).astype(np.float64))
+
+
+def _edge_setup(B, lmax, E, n, n_owned, n_rbf, r_cut, seed, which):
+    from oracle import egnn_oracle as O
+    w = synth.small_cluster(n, n_owned, lmax, E, n_rbf, r_cut, seed)
+    g = U.oracle_graph(w)
+    paths = O.tp_paths(lmax, lmax, lmax if which == 0 else O.L_READOUT)
+    rng = np.random.default_rng([seed, 5])
+    W = synth.layer_weights(rng, lmax, E, n_rbf, 64, len(paths))
+    m = B.Egnn(lmax, E, n_rbf, r_cut, 4.0, orb_l=w.orb_l)
+    pos = B.to_device(w.pos)
+    gd = m.egnn_nlist(pos, n_owned, w.box, w.pbc)
+    rhat_d = m.egnn_edge_geometry(gd, pos, w.box)[0]
+    r = O.edge_vectors(w.pos, w.box, g[0], g[1], g[2])
+    d = np.sqrt((r * r).sum(axis=1))
+    w64 = O.radial_weights(d, W["W_r1"], W["W_r2"], paths, E, n_rbf, r_cut).reshape(len(d), -1)
+    return w, g, m, gd, pos, rhat_d, W, w64, paths
+
+
+@pytest.mark.parametrize("lmax,E,n,which", [(2, 8, 70, 0), (1, 8, 50, 0), (2, 16, 90, 1), (3, 32, 150, 0),
+                                            (4, 32, 120, 1), (4, 64, 100, 0), (2, 128, 60, 0), (0, 8, 40, 0)])
+def test_radial_weights_f16_codes(B, lmax, E, n, which):
+    """Every stored code is the oracle's, or its neighbour where the oracle's value sits on a rounding boundary."""
+    w, g, m, gd, pos, rhat_d, W, w64, paths = _edge_setup(B, lmax, E, n, n, 8, 4.0, 70 + lmax, which)
+    words = m.egnn_radial_weights_f16(which, rhat_d, B.to_device(W["W_r1"]), B.to_device(W["W_r2"])).cpu().numpy()
+    assert words.shape == (len(g[0]), 32 * ((w64.shape[1] + 63) // 64))
+    got = unpack_w16(words, w64.shape[1])
+    want = w64.astype(np.float16).astype(np.float64)
+    same = got == want
+    delta = 2e-5 * np.abs(w64).max()          # tolerance of the fp32 evaluation of w (the S3 stage test's bar)
+    # a differing code must be the neighbour on the side of w64, and w64 within delta of the midpoint of the two
+    mid = 0.5 * (got + want)
+    ok = same | ((np.abs(w64 - mid) <= delta) & (np.abs(got - want) <= np.spacing(np.abs(want).astype(np.float16)).astype(np.float64) * 1.0001))
+    frac = 1.0 - same.mean()
+    print(f"lmax {lmax} E {E} which {which}: {same.size} codes, {frac:.2e} differ from the fp64 decision", flush=True)
+    assert ok.all() and frac < 0.02
+
+
+@pytest.mark.parametrize("lmax,E,n,n_owned", [(2, 8, 70, 50), (1, 16, 60, 60), (3, 32, 150, 100), (4, 32, 100, 100),
+                                              (4, 64, 100, 80), (2, 128, 60, 60), (0, 16, 40, 40)])
+def test_tp_segsum_f16_with_oracle_made_codes(B, lmax, E, n, n_owned):
+    """S4 on half-precision weights packed on the host from the oracle's rounded values: identical weights on both
+    sides, fp32 bar.  Unused halves of the last group hold NaN to show that they are not read."""
+    from oracle import egnn_oracle as O
+    w, g, m, gd, pos, rhat_d, W, w64, paths = _edge_setup(B, lmax, E, n, n_owned, 8, 4.0, 80 + lmax, 0)
+    wr = w64.astype(np.float16).astype(np.float64)
+    rng = np.random.default_rng(9)
+    h = synth.node_features(rng, n, lmax, E)
+    a = m.egnn_tp_segsum_f16(gd, rhat_d, B.to_device(h), B.to_device(pack_w16(wr, fill=np.nan)))
+    ref = O.edge_messages_sum(g, w.pos, w.box, h.astype(np.float64),
+                              lambda d, k0, k1, p: wr[k0:k1].reshape(k1 - k0, len(paths), E), lmax, lmax, 4.0)
+    assert U.rel_err(a.cpu().numpy(), ref) < 2e-5
+
+
+def _rms(a):
+    return float(np.sqrt(np.mean(np.square(a))))
+
+
+def _check_composite_H(got, H_half, H_full, label):
+    """Max norm: within the size of the rounding itself; rms: far below it."""
+    scale = np.abs(H_full).max()
+    e_half, e_full = np.abs(got - H_half).max() / scale, np.abs(got - H_full).max() / scale
+    r_half, r_round = _rms(got - H_half), _rms(H_half - H_full)
+    print(f"{label}: H max err vs rounded-weight oracle {e_half:.2e} (vs unrounded {e_full:.2e}); "
+          f"rms {r_half / scale:.2e} vs rms of the rounding effect {r_round / scale:.2e}", flush=True)
+    assert e_half < 2.0 ** -11 and e_half <= e_full
+    assert r_half < 0.25 * r_round
+
+
 @pytest.mark.parametrize("lmax,E,periodic,n,n_owned", [(0, 8, False, 40, 40), (1, 16, True, 120, 120),
                                                         (2, 64, False, 100, 60), (3, 16, True, 150, 90),
                                                         (4, 128, False, 60, 40), (4, 8, False, 70, 70),
@@ -43,11 +142,7 @@ def test_w_fp16_small_shapes(B, lmax, E, periodic, n, n_owned):
     xs_full, H_full = U.oracle_forward(w, wt, g, agg)
     for t in range(2):
         assert U.rel_err(xs[t].cpu().numpy(), xs_ref[t]) < U.TOL
-    e_half, e_full = U.rel_err(H.cpu().numpy(), H_ref), U.rel_err(H.cpu().numpy(), H_full)
-    print(f"lmax {lmax} E {E}: H vs half-weight oracle {e_half:.2e}, vs unrounded oracle {e_full:.2e}", flush=True)
-    assert e_half < U.TOL
-    # the option is really on: the result is closer to the rounded-weight oracle than to the unrounded one
-    assert e_half < 0.5 * e_full
+    _check_composite_H(H.cpu().numpy().astype(np.float64), H_ref, H_full, f"lmax {lmax} E {E}")
 
 
 @pytest.mark.parametrize("index", [1, 2])
@@ -58,13 +153,12 @@ def test_w_fp16_configs_full(B, index):
     agg = U.mean_degree(g, w.n_owned)
     m, graph, xs, H = U.gpu_forward(w, wt, agg, w_fp16=True)
     xs_ref, H_ref = U.oracle_forward(w, wt, g, agg, w_dtype=np.float16)
+    xs_full, H_full = U.oracle_forward(w, wt, g, agg)
     for t in range(w.n_layers):
         e = U.rel_err(xs[t].cpu().numpy(), xs_ref[t])
         print(f"config {index} layer {t} (half-precision w): rel err {e:.2e}", flush=True)
         assert e < U.TOL
-    e = U.rel_err(H.cpu().numpy(), H_ref)
-    print(f"config {index} H_ij (half-precision w): rel err {e:.2e}", flush=True)
-    assert e < U.TOL
+    _check_composite_H(H.cpu().numpy().astype(np.float64), H_ref, H_full, f"config {index}")
 
 
 @pytest.mark.parametrize("index", [3, 4])
@@ -91,15 +185,10 @@ def test_w_fp16_fullsize_sampled_rows(B, index):
     e_full = np.abs(got - gold["x1_rows_full"]).max() / scale
     print(f"config {index} layer (half-precision w): vs rounded-weight oracle {e_half:.2e}, vs unrounded {e_full:.2e}",
           flush=True)
-    assert e_half < U.TOL and e_half < 0.5 * e_full
+    assert e_half < U.TOL and e_half < e_full
     H = m.egnn_readout_hij(graph, pos, w.box, x, B.to_device(wt["readout"]), ws)
     got = H[torch.from_numpy(gold["edges"]).cuda()].cpu().numpy().astype(np.float64)
-    scale = np.abs(gold["H_rows"]).max()
-    e_half = np.abs(got - gold["H_rows"]).max() / scale
-    e_full = np.abs(got - gold["H_rows_full"]).max() / scale
-    print(f"config {index} H_ij (half-precision w): vs rounded-weight oracle {e_half:.2e}, vs unrounded {e_full:.2e}",
-          flush=True)
-    assert e_half < U.TOL and e_half < 0.5 * e_full
+    _check_composite_H(got, gold["H_rows"], gold["H_rows_full"], f"config {index}")
 
 
 def test_w_fp16_leaves_given_weights_and_stage_calls_alone(B):
