@@ -150,6 +150,27 @@ def main():
     ms, n_calls = m.egnn_timing_read()
     m.egnn_timing_enable(0)
 
+    # ---- the same step with the radial weights stored in half precision between S3 and S4 / S6 (a reduced-precision
+    #      option; reported next to `value`, never as `value`) ----
+    m.egnn_set_option(B.OPT_W_FP16, 1)
+    for _ in range(2):
+        step()
+    torch.cuda.synchronize()
+    n16 = max(3, args.steps // 2)
+    m.egnn_timing_enable(n16 * (w.n_layers + 1))
+    t1 = time.perf_counter()
+    for _ in range(n16):
+        step()
+    torch.cuda.synchronize()
+    dt16 = (time.perf_counter() - t1) / n16
+    ms16, calls16 = m.egnn_timing_read()
+    m.egnn_timing_enable(0)
+    m.egnn_set_option(B.OPT_W_FP16, 0)
+    w_fp16 = dict(ms_per_step=1e3 * dt16, steps=n16, edge_layer_evaluations_per_s=n_edges * w.n_layers / dt16,
+                  layer_ms={n: ms16[i] / max(1, calls16[0]) for i, n in enumerate(B.LAYER_STAGES)},
+                  readout_ms={n: ms16[5 + i] / max(1, calls16[1]) for i, n in enumerate(B.READOUT_STAGES)} if w.readout else None,
+                  note="EGNN_OPT_W_FP16: w rounded to half precision once, fp32 products and sums; not the fp32 figure")
+
     # ---- S7: training step on the same graph and model (config 5 when the workload is config 3) ----
     training = None
     if w.readout and args.train_steps > 0:
@@ -284,6 +305,7 @@ def main():
                      "layer_edges_per_s": n_edges / (sum(layer_ms.values()) * 1e-3)},
     }
     out["training_step"] = training
+    out["w_fp16_storage"] = w_fp16
     out["hbm_calibration"] = calibration
     if so2 is not None:
         out["so2_message_sum"] = so2
