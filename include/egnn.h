@@ -8,8 +8,9 @@
  *   - Every pointer is a DEVICE pointer unless its comment says "host".  The caller owns every
  *     buffer, including the workspace; the library allocates no device memory, keeps no pointer
  *     after a call returns, and enqueues all work on the stream passed in (a hipStream_t, passed
- *     as void*; NULL = the default stream).  egnn_nlist_count (edge count read-back) and
- *     egnn_readout_hij (upload of its small index tables) synchronise the stream; nothing else does.
+ *     as void*; NULL = the default stream).  egnn_nlist_count (edge count read-back),
+ *     egnn_readout_hij, egnn_readout_backward and egnn_onsite_hii (upload of their small index tables) and
+ *     egnn_hamiltonian_structure (size read-back) synchronise the stream; nothing else does.
  *   - Node tensors: float [n_nodes][(lmax+1)^2][channels], channel fastest; the (l, m) axis is
  *     flattened as l*l + l + m, m = -l..l  (Sec. 3 "Initialization": T^node of shape
  *     (l_max+1)^2 x E per atom).
@@ -237,6 +238,47 @@ int egnn_so2_weight_count(const egnn_ctx* ctx, int64_t* n_floats);
 int egnn_so2_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, size_t* bytes);
 int egnn_so2_message_sum(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3], const float* x,
                          const float* W_e, const float* W_so2, float* a, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- assembly of the predicted Hamiltonian (Sec. 3, end of "Message passing": nodes give the diagonal blocks, edges the
+ *      off-diagonal ones; Fig. 2(e): collapse E -> 1, padded outputs; Sec. 2.2 / Eq. 1: the coupled basis and its
+ *      inverse; Sec. 6: combined L1 + L2 loss over the elements of H) ----
+ * Orbital sets: the model's shell list (egnn_model_desc.orb_l) is the global one; species s owns the orbitals whose
+ * bit is set in orb_bits[s] (bit o = o-th orbital of the global list; device array of n_species words).  species is a
+ * device array over all n_total atoms (values clamped to 0 .. n_species-1).  An entry of a block whose row orbital is
+ * absent on the row atom or whose column orbital is absent on the column atom is padding.
+ * Blocks: float [n_blocks][n_orb][n_orb]; row_atom / col_atom [n_blocks] give the atoms of a block's rows and
+ * columns (for edge blocks g->src and g->dst; NULL = the block index itself, i.e. on-site blocks).
+ *
+ * egnn_onsite_hii: H_ii[i][(a,m_a)][(b,m_b)] = sum_{L <= lmax, M} C^{(L,M)}_{(l_a m_a)(l_b m_b)} q_i[o(a,b,L)][M],
+ *   q_i[o][M] = sum_c V_node[L][o][c] x[i][(L,M)][c]; V_node packed like V of egnn_readout_hij (rows of degrees above
+ *   lmax are not read).  x [n_nodes][(lmax+1)^2][channels].  Synchronises the stream once (table upload).
+ * egnn_apply_padding: sets the padding entries of H to zero in place.
+ * egnn_loss_l1l2: loss[0] = mean |H - T| + mean (H - T)^2 over the entries that are not padding, loss[1], loss[2] the
+ *   two terms (device, 3 floats); if dH != NULL, dH = (sign(H - T) + 2 (H - T)) / (number of such entries), 0 on padding.
+ * egnn_hamiltonian_structure / egnn_hamiltonian_fill: the matrix with columns = orbitals of the owned atoms and rows =
+ *   orbitals of all atoms (atom-major, each atom's own orbitals in the order of the global list), column-compressed:
+ *   orb_off [n_total+1] first row/column of every atom; col_ptr [n_cols+1] (the caller provides n_owned * n_orb + 1
+ *   entries); per column the rows ascend: the blocks of the sources of the atom's incoming edges and its own on-site
+ *   block, every entry of a block stored.  structure computes orb_off, col_ptr and the placement of every block
+ *   (kept in `plan`, an opaque device buffer of plan_bytes from egnn_hamiltonian_workspace_bytes) and returns
+ *   n_cols and nnz (host; synchronises the stream); fill writes values [nnz] and, if not NULL, row_idx [nnz] from
+ *   H_edge [n_edges][n_orb][n_orb] (rows = source orbitals) and H_node [>= n_owned][n_orb][n_orb].
+ * ws / plan: 256-byte aligned, sizes from egnn_hamiltonian_workspace_bytes. */
+int egnn_hamiltonian_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, int32_t n_total,
+                                     size_t* ws_bytes, size_t* plan_bytes);
+int egnn_onsite_hii(egnn_ctx* ctx, const float* x, const float* V_node, float* H_ii, int32_t n_nodes,
+                    void* ws, size_t ws_bytes, void* stream);
+int egnn_apply_padding(egnn_ctx* ctx, float* H, int64_t n_blocks, const int32_t* row_atom, const int32_t* col_atom,
+                       const int32_t* species, const uint32_t* orb_bits, int32_t n_species, void* stream);
+int egnn_loss_l1l2(egnn_ctx* ctx, const float* H, const float* T, int64_t n_blocks, const int32_t* row_atom,
+                   const int32_t* col_atom, const int32_t* species, const uint32_t* orb_bits, int32_t n_species,
+                   float* loss, float* dH, void* ws, size_t ws_bytes, void* stream);
+int egnn_hamiltonian_structure(egnn_ctx* ctx, const egnn_graph* g, const int32_t* species, const uint32_t* orb_bits,
+                               int32_t n_species, int32_t* orb_off, int64_t* col_ptr, void* plan, size_t plan_bytes,
+                               int64_t* n_cols, int64_t* nnz, void* stream);
+int egnn_hamiltonian_fill(egnn_ctx* ctx, const egnn_graph* g, const int32_t* species, const uint32_t* orb_bits,
+                          int32_t n_species, const int32_t* orb_off, const void* plan, size_t plan_bytes,
+                          const float* H_edge, const float* H_node, int32_t* row_idx, float* values, void* stream);
 
 /* ---- stage timing (measurement aid; follows the paper's protocol of timing the blocks of the forward
  *      pass separately, Sec. 4.4 / Fig. 6(c)) ----

@@ -21,7 +21,8 @@ SYMBOLS = [
     "egnn_layer_forward", "egnn_readout_hij", "egnn_timing_enable", "egnn_timing_read",
     "egnn_backward_workspace_bytes", "egnn_graph_transpose", "egnn_loss_mse", "egnn_layer_backward",
     "egnn_readout_backward", "egnn_set_option", "egnn_radial_weights_f16", "egnn_tp_segsum_f16", "egnn_so2_weight_count", "egnn_so2_workspace_bytes",
-    "egnn_so2_message_sum",
+    "egnn_so2_message_sum", "egnn_hamiltonian_workspace_bytes", "egnn_onsite_hii", "egnn_apply_padding", "egnn_loss_l1l2",
+    "egnn_hamiltonian_structure", "egnn_hamiltonian_fill",
 ]
 
 
@@ -279,6 +280,63 @@ class Egnn:
             _ptr(W["W_r2"]), _ptr(W["V"]), _ptr(H), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
         return H
 
+
+    # ---- assembly of the predicted Hamiltonian
+    def egnn_hamiltonian_workspace_bytes(self, n_edges, n_owned, n_total):
+        ws, plan = C.c_size_t(), C.c_size_t()
+        self._check(self.lib.egnn_hamiltonian_workspace_bytes(self.ctx, C.c_int64(n_edges), n_owned, n_total,
+                                                              C.byref(ws), C.byref(plan)))
+        return ws.value, plan.value
+
+    def hamiltonian_workspace(self, graph):
+        ws, plan = self.egnn_hamiltonian_workspace_bytes(graph.n_edges, graph.n_owned, graph.n_total)
+        return (torch.empty(ws, dtype=torch.uint8, device="cuda"), torch.empty(plan, dtype=torch.uint8, device="cuda"))
+
+    def egnn_onsite_hii(self, x, V_node, ws, out=None):
+        n = x.shape[0]
+        H = out if out is not None else torch.empty((n, self.n_orb, self.n_orb), dtype=torch.float32, device="cuda")
+        self._check(self.lib.egnn_onsite_hii(self.ctx, _ptr(x), _ptr(V_node), _ptr(H), n, _ptr(ws),
+                                             C.c_size_t(ws.numel()), _stream()))
+        return H
+
+    def egnn_apply_padding(self, H, row_atom, col_atom, species, orb_bits):
+        self._check(self.lib.egnn_apply_padding(self.ctx, _ptr(H), C.c_int64(H.shape[0]), _ptr(row_atom), _ptr(col_atom),
+                                                _ptr(species), _ptr(orb_bits), int(orb_bits.numel()), _stream()))
+        return H
+
+    def egnn_loss_l1l2(self, H, T, row_atom, col_atom, species, orb_bits, ws, want_grad=True):
+        """Returns (loss [3]: total, L1 term, L2 term; device), dH or None."""
+        loss = torch.empty(3, dtype=torch.float32, device="cuda")
+        dH = torch.empty_like(H) if want_grad else None
+        self._check(self.lib.egnn_loss_l1l2(self.ctx, _ptr(H), _ptr(T), C.c_int64(H.shape[0]), _ptr(row_atom),
+                                            _ptr(col_atom), _ptr(species), _ptr(orb_bits), int(orb_bits.numel()),
+                                            _ptr(loss), _ptr(dH), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+        return loss, dH
+
+    def egnn_hamiltonian_structure(self, graph, species, orb_bits, plan):
+        """Returns (orb_off [n_total+1] int32, col_ptr [n_cols+1] int64, nnz)."""
+        orb_off = torch.empty(graph.n_total + 1, dtype=torch.int32, device="cuda")
+        col_ptr = torch.empty(graph.n_owned * self.n_orb + 1, dtype=torch.int64, device="cuda")
+        n_cols, nnz = C.c_int64(), C.c_int64()
+        g = graph.desc()
+        self._check(self.lib.egnn_hamiltonian_structure(self.ctx, C.byref(g), _ptr(species), _ptr(orb_bits),
+                                                        int(orb_bits.numel()), _ptr(orb_off), _ptr(col_ptr), _ptr(plan),
+                                                        C.c_size_t(plan.numel()), C.byref(n_cols), C.byref(nnz),
+                                                        _stream()))
+        return orb_off, col_ptr[:n_cols.value + 1], nnz.value
+
+    def egnn_hamiltonian_fill(self, graph, species, orb_bits, orb_off, plan, H_edge, H_node, nnz, want_rows=True,
+                              values=None, row_idx=None):
+        if values is None:
+            values = torch.empty(nnz, dtype=torch.float32, device="cuda")
+        if row_idx is None and want_rows:
+            row_idx = torch.empty(nnz, dtype=torch.int32, device="cuda")
+        g = graph.desc()
+        self._check(self.lib.egnn_hamiltonian_fill(self.ctx, C.byref(g), _ptr(species), _ptr(orb_bits),
+                                                   int(orb_bits.numel()), _ptr(orb_off), _ptr(plan),
+                                                   C.c_size_t(plan.numel()), _ptr(H_edge), _ptr(H_node), _ptr(row_idx),
+                                                   _ptr(values), _stream()))
+        return row_idx, values
 
     # ---- S7: loss and reverse pass
     def egnn_backward_workspace_bytes(self, n_edges, n_owned, n_total):

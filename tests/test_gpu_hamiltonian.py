@@ -1,0 +1,155 @@
+"""GPU parity of the Hamiltonian assembly (on-site blocks, padding, L1+L2 loss, column-compressed matrix) against
+oracle/hamiltonian_oracle.py.  Index arrays and the placement of every value are compared exactly (the assembly copies
+fp32 numbers); floating-point results at the bar of the fp32 path."""
+import numpy as np
+import pytest
+
+from oracle import egnn_oracle as O
+from oracle import hamiltonian_oracle as Hm
+from paper_2507_03840_amd import synth
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+ORB_L = (0, 0, 1, 1, 2)
+SHELLS3 = [[0, 1, 2, 3, 4], [0, 1, 2, 4], [0, 2]]        # 13, 10 and 4 orbitals
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2507_03840_amd import binding
+    binding.load_library()
+    return binding
+
+
+def _dev_bits(B, bits):
+    return B.to_device(np.asarray(bits, np.uint32).view(np.int32))
+
+
+@pytest.mark.parametrize("lmax,E,n,orb_l", [(0, 8, 5, ORB_L), (1, 16, 40, ORB_L), (2, 32, 33, ORB_L), (3, 64, 20, ORB_L),
+                                            (4, 128, 9, ORB_L), (4, 32, 300, ORB_L), (2, 8, 17, (0,)), (4, 16, 12, (0, 1, 2, 2))])
+def test_onsite_blocks(B, lmax, E, n, orb_l):
+    rng = np.random.default_rng([11, lmax, E])
+    x = synth.node_features(rng, n, lmax, E)
+    _, n_out = O.readout_slots(orb_l)
+    V = (synth.normal(rng, (sum(n_out), E)) / np.sqrt(E)).astype(np.float32)
+    m = B.Egnn(lmax, E, 8, 4.0, 1.0, orb_l=orb_l)
+    ws = B.torch.empty(m.egnn_hamiltonian_workspace_bytes(0, n, n)[0], dtype=B.torch.uint8, device="cuda")
+    H = m.egnn_onsite_hii(B.to_device(x), B.to_device(V), ws).cpu().numpy()
+    ref = Hm.onsite_hii(x, V, lmax, orb_l)
+    assert H.shape == ref.shape and U.rel_err(H, ref) < 1e-5
+
+
+def _blocks_case(B, n, n_owned, periodic, seed, shells=SHELLS3, r_cut=3.0):
+    rng = np.random.default_rng([12, seed])
+    w = synth.small_cluster(n, n_owned, 1, 8, 4, r_cut, seed, periodic=periodic)
+    g = O.neighbour_list(w.pos, n_owned, w.box, w.pbc, w.r_cut)
+    species = rng.integers(0, len(shells), n).astype(np.int32)
+    bits = Hm.species_orbital_bits(ORB_L, shells)
+    H_edge = synth.normal(rng, (len(g[0]), 13, 13)).astype(np.float32)
+    H_node = synth.normal(rng, (n, 13, 13)).astype(np.float32)
+    m = B.Egnn(1, 8, 4, r_cut, 1.0, orb_l=ORB_L)
+    gd = B.Graph(B.to_device(g[0]), B.to_device(g[1]), B.to_device(g[3]), B.to_device(g[2]), n_owned, n)
+    return w, g, species, bits, H_edge, H_node, m, gd
+
+
+@pytest.mark.parametrize("n,n_owned,periodic", [(40, 40, False), (60, 35, False), (90, 90, True)])
+def test_padding_and_loss(B, n, n_owned, periodic):
+    w, g, species, bits, H_edge, H_node, m, gd = _blocks_case(B, n, n_owned, periodic, 3)
+    rng = np.random.default_rng(5)
+    sp_d, bits_d = B.to_device(species), _dev_bits(B, bits)
+    ws, plan = m.hamiltonian_workspace(gd)
+    for H, rows, cols, ra, ca in ((H_edge, g[0], g[1], gd.src, gd.dst), (H_node, np.arange(n), np.arange(n), None, None)):
+        T = synth.normal(rng, H.shape).astype(np.float32)
+        rb, cb = bits[species[rows]], bits[species[cols]]
+        Hd = B.to_device(H.copy())
+        m.egnn_apply_padding(Hd, ra, ca, sp_d, bits_d)
+        assert np.array_equal(Hd.cpu().numpy().astype(np.float64), Hm.apply_padding(H, rb, cb))
+        loss, dH = m.egnn_loss_l1l2(B.to_device(H), B.to_device(T), ra, ca, sp_d, bits_d, ws)
+        ref_loss, ref_g = Hm.loss_l1l2(H, T, rb, cb)
+        d = H.astype(np.float64) - T
+        msk = Hm.block_mask(rb, cb, 13)
+        got = loss.cpu().numpy()
+        assert abs(got[0] / ref_loss - 1) < 1e-6
+        assert abs(got[1] / (np.abs(d[msk]).mean()) - 1) < 1e-6 and abs(got[2] / (np.square(d[msk]).mean()) - 1) < 1e-6
+        assert U.rel_err(dH.cpu().numpy(), ref_g) < 1e-6
+        assert np.all(dH.cpu().numpy()[~msk] == 0)
+
+
+@pytest.mark.parametrize("n,n_owned,periodic,shells,r_cut", [(40, 40, False, SHELLS3, 3.0), (60, 35, False, SHELLS3, 3.0),
+                                                           (90, 90, True, SHELLS3, 3.0), (50, 50, False, [[0, 1, 2, 3, 4]], 3.0),
+                                                           (45, 30, False, [[0, 1, 2, 3, 4], []], 3.0),      # a species without orbitals
+                                                           (30, 30, False, SHELLS3, 0.5),                    # no edges: on-site blocks only
+                                                           (300, 20, False, SHELLS3, 12.0)])                 # > 128 blocks per column: several tiles
+def test_assembly_exact(B, n, n_owned, periodic, shells, r_cut):
+    w, g, species, bits, H_edge, H_node, m, gd = _blocks_case(B, n, n_owned, periodic, 7, shells, r_cut)
+    if r_cut == 12.0:
+        assert np.diff(g[3]).max() > 130
+    sp_d, bits_d = B.to_device(species), _dev_bits(B, bits)
+    ws, plan = m.hamiltonian_workspace(gd)
+    orb_off, col_ptr, nnz = m.egnn_hamiltonian_structure(gd, sp_d, bits_d, plan)
+    He = B.to_device(H_edge) if len(g[0]) else None
+    row_idx, values = m.egnn_hamiltonian_fill(gd, sp_d, bits_d, orb_off, plan, He, B.to_device(H_node), nnz)
+    r_off, r_ptr, r_rows, r_vals = Hm.assemble_csc(g, species, bits, H_edge, H_node[:n_owned], n_owned, n)
+    assert np.array_equal(orb_off.cpu().numpy(), r_off)
+    assert np.array_equal(col_ptr.cpu().numpy(), r_ptr) and nnz == len(r_vals)
+    assert np.array_equal(row_idx.cpu().numpy(), r_rows)
+    assert np.array_equal(values.cpu().numpy().astype(np.float64), r_vals)
+    # values only (structure known): same numbers
+    _, v2 = m.egnn_hamiltonian_fill(gd, sp_d, bits_d, orb_off, plan, He, B.to_device(H_node), nnz, want_rows=False)
+    assert np.array_equal(v2.cpu().numpy(), values.cpu().numpy())
+
+
+def test_assembly_fullsize_config3(B):
+    """Config 3's graph (3,000 atoms, all edges of the seeded structure), two species with 10 and 4 orbitals
+    (the counts of Sec. 4.4): offsets and column pointers against closed-form counts, sampled columns entry by entry."""
+    import torch
+    w = synth.workload(3)
+    rng = np.random.default_rng([w.seed, 31])
+    bits = Hm.species_orbital_bits(ORB_L, [[0, 1, 2, 4], [0, 2]])
+    counts = np.array([10, 4])[w.species]
+    m = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, 150.0, orb_l=ORB_L)
+    pos = B.to_device(w.pos)
+    gd = m.egnn_nlist(pos, w.n_owned, w.box, w.pbc)
+    src, row_ptr = gd.src.cpu().numpy(), gd.row_ptr.cpu().numpy()
+    H_edge = torch.from_numpy(synth.normal(rng, (gd.n_edges, 13, 13)).astype(np.float32))
+    H_node = torch.from_numpy(synth.normal(rng, (w.n_total, 13, 13)).astype(np.float32))
+    sp_d, bits_d = B.to_device(w.species), _dev_bits(B, bits)
+    ws, plan = m.hamiltonian_workspace(gd)
+    orb_off, col_ptr, nnz = m.egnn_hamiltonian_structure(gd, sp_d, bits_d, plan)
+    row_idx, values = m.egnn_hamiltonian_fill(gd, sp_d, bits_d, orb_off, plan, H_edge.cuda(), H_node.cuda(), nnz)
+    off = np.concatenate([[0], np.cumsum(counts)])
+    assert np.array_equal(orb_off.cpu().numpy(), off)
+    # length of the columns of atom j = its own orbitals + those of its sources
+    seg = np.add.reduceat(counts[src], row_ptr[:-1]) + counts[:w.n_owned]
+    want_ptr = np.concatenate([[0], np.cumsum(np.repeat(seg, counts[:w.n_owned]))])
+    assert np.array_equal(col_ptr.cpu().numpy(), want_ptr) and nnz == want_ptr[-1]
+    print(f"config 3 assembly: {off[-1]} x {off[w.n_owned]} matrix, {nnz} stored entries", flush=True)
+    rows_h, vals_h, ptr_h = row_idx.cpu().numpy(), values.cpu().numpy(), want_ptr
+    present = Hm.bits_to_bool(bits[w.species], 13)
+    for j in rng.choice(w.n_owned, 40, replace=False):
+        k0, k1 = row_ptr[j], row_ptr[j + 1]
+        blocks = {int(src[k]): H_edge[k].numpy() for k in range(k0, k1)}
+        blocks[int(j)] = H_node[j].numpy()
+        for bp, b in enumerate(np.nonzero(present[j])[0]):
+            c = off[j] + bp
+            want_r = np.concatenate([off[i] + np.arange(counts[i]) for i in sorted(blocks)])
+            want_v = np.concatenate([blocks[i][np.nonzero(present[i])[0], b] for i in sorted(blocks)])
+            assert np.array_equal(rows_h[ptr_h[c]:ptr_h[c + 1]], want_r)
+            assert np.array_equal(vals_h[ptr_h[c]:ptr_h[c + 1]], want_v)
+
+
+def test_hamiltonian_errors(B):
+    import torch
+    w, g, species, bits, H_edge, H_node, m, gd = _blocks_case(B, 40, 40, False, 3)
+    sp_d, bits_d = B.to_device(species), _dev_bits(B, bits)
+    ws, plan = m.hamiltonian_workspace(gd)
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.EgnnError):
+        m.egnn_hamiltonian_structure(gd, sp_d, bits_d, small)
+    with pytest.raises(B.EgnnError):
+        m.egnn_loss_l1l2(B.to_device(H_edge), B.to_device(H_edge), gd.src, gd.dst, sp_d, bits_d, small)
+    with pytest.raises(B.EgnnError):
+        m.egnn_onsite_hii(B.to_device(synth.node_features(np.random.default_rng(0), 4, 1, 8)),
+                          B.to_device(np.zeros((50, 8), np.float32)), small[:16])
