@@ -79,6 +79,8 @@ def main():
                     help="training steps (forward + loss + reverse pass, config 5) timed after the main region; 0 = skip")
     ap.add_argument("--fused", type=int, default=0, choices=[0, 1],
                     help="1: radial weights and messages in one kernel (weights never written to memory)")
+    ap.add_argument("--no-hamiltonian", action="store_true",
+                    help="skip the extra timing of the Hamiltonian assembly (on-site blocks, padding, L1+L2 loss, CSC matrix)")
     ap.add_argument("--no-so2", action="store_true",
                     help="skip the extra timing of the SO(2) form of the message transform (egnn_so2_message_sum)")
     ap.add_argument("--sweep", action="store_true",
@@ -245,6 +247,48 @@ def main():
                    note="gather+rotate, five split-bf16 GEMMs (six bf16 products per fp32 product), rotate back + segmented sum")
         del ws2
 
+    # ---- assembly of the predicted Hamiltonian from the blocks of this step: on-site blocks, padding for two species
+    #      with 10 and 4 of the 13 orbitals, L1+L2 loss, column-compressed matrix ----
+    ham = None
+    if w.readout and not args.no_hamiltonian:
+        graph = m.egnn_nlist(pos, w.n_owned, w.box, w.pbc)
+        off = np.concatenate([[0], np.cumsum([2 * l + 1 for l in w.orb_l])])
+        def bits_of(shells):
+            return sum(1 << o for s in shells for o in range(off[s], off[s + 1]))
+        orb_bits = B.to_device(np.array([bits_of([0, 1, 2, 4]), bits_of([0, 2])], np.uint32).view(np.int32))
+        n_out = m.egnn_readout_widths()
+        V_node = B.to_device((synth.normal(np.random.default_rng([w.seed, 555]), (sum(n_out), w.channels)) /
+                              np.sqrt(w.channels)).astype(np.float32))
+        hws, plan = m.hamiltonian_workspace(graph)
+        target = B.to_device(synth.normal(np.random.default_rng([w.seed, 99]), (n_edges, w.n_orb, w.n_orb)))
+        H_node = m.egnn_onsite_hii(x_full, V_node, hws)
+        orb_off, col_ptr, nnz = m.egnn_hamiltonian_structure(graph, species, orb_bits, plan)
+        vals = torch.empty(nnz, dtype=torch.float32, device="cuda")
+        rows = torch.empty(nnz, dtype=torch.int32, device="cuda")
+        t_on = timed(lambda: m.egnn_onsite_hii(x_full, V_node, hws, out=H_node), 5)
+        t_pad = timed(lambda: m.egnn_apply_padding(H, graph.src, graph.dst, species, orb_bits), 5)
+        t_loss = timed(lambda: m.egnn_loss_l1l2(H, target, graph.src, graph.dst, species, orb_bits, hws), 5)
+        t_struct = timed(lambda: m.egnn_hamiltonian_structure(graph, species, orb_bits, plan), 5)
+        t_fill = timed(lambda: m.egnn_hamiltonian_fill(graph, species, orb_bits, orb_off, plan, H, H_node, nnz,
+                                                       values=vals, row_idx=rows), 5)
+        t_vals = timed(lambda: m.egnn_hamiltonian_fill(graph, species, orb_bits, orb_off, plan, H, H_node, nnz,
+                                                       want_rows=False, values=vals), 5)
+        nq = w.n_orb * w.n_orb
+        cnt = torch.tensor([10, 4], device="cuda")[species.long()]
+        n_present = int((cnt[graph.src.long()] * cnt[graph.dst.long()]).sum())
+        blocks_bytes = (n_edges + w.n_owned) * nq * 4
+        ham = dict(matrix=[int(orb_off[-1]), int(col_ptr.numel() - 1)], stored_entries=int(nnz),
+                   onsite_ms=t_on, padding_ms=t_pad, loss_l1l2_ms=t_loss, structure_ms=t_struct,
+                   fill_ms=t_fill, fill_values_only_ms=t_vals,
+                   padding_GBs=(n_edges * nq - n_present) * 4 / t_pad / 1e6,
+                   loss_GBs=n_edges * nq * 4 * 3 / t_loss / 1e6,
+                   fill_GBs=(blocks_bytes + 8 * nnz) / t_fill / 1e6,
+                   fill_values_only_GBs=(blocks_bytes + 4 * nnz) / t_vals / 1e6,
+                   edge_entries_not_padding=n_present,
+                   note="species 0 / 1 own 10 / 4 of the 13 orbitals; GB/s = algorithmic bytes over time (padding: "
+                        "the zeros written; loss: H, T read, dH written; fill: blocks read once, outputs written once)")
+        del vals, rows, target, H_node, hws, plan
+
     # ---- saturation curve: one layer forward into the first n destination nodes ----
     sweep = None
     if args.sweep:
@@ -309,6 +353,8 @@ def main():
     out["hbm_calibration"] = calibration
     if so2 is not None:
         out["so2_message_sum"] = so2
+    if ham is not None:
+        out["hamiltonian_assembly"] = ham
     if sweep is not None:
         out["saturation_sweep"] = sweep
     if not args.no_cpu_baseline:

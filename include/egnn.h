@@ -268,6 +268,12 @@ int egnn_hamiltonian_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, int32
                                      size_t* ws_bytes, size_t* plan_bytes);
 int egnn_onsite_hii(egnn_ctx* ctx, const float* x, const float* V_node, float* H_ii, int32_t n_nodes,
                     void* ws, size_t ws_bytes, void* stream);
+/* Adjoint of egnn_onsite_hii: dx [n_nodes][(lmax+1)^2][channels] and dV_node (packed like V_node; rows of degrees
+ * above lmax are set to zero) from dH_ii; both overwritten.  Nodes are added in a fixed order.  Synchronises the
+ * stream once (table upload).  ws: egnn_onsite_backward_workspace_bytes, 256-byte aligned. */
+int egnn_onsite_backward_workspace_bytes(const egnn_ctx* ctx, int32_t n_nodes, size_t* bytes);
+int egnn_onsite_backward(egnn_ctx* ctx, const float* x, const float* V_node, const float* dH_ii, float* dx,
+                         float* dV_node, int32_t n_nodes, void* ws, size_t ws_bytes, void* stream);
 int egnn_apply_padding(egnn_ctx* ctx, float* H, int64_t n_blocks, const int32_t* row_atom, const int32_t* col_atom,
                        const int32_t* species, const uint32_t* orb_bits, int32_t n_species, void* stream);
 int egnn_loss_l1l2(egnn_ctx* ctx, const float* H, const float* T, int64_t n_blocks, const int32_t* row_atom,

@@ -74,6 +74,26 @@ def onsite_hii(x, V_node, lmax, orb_l):
     return H
 
 
+def onsite_backward(x, V_node, lmax, orb_l, dH):
+    """Adjoint of onsite_hii: returns (dx, dV_node) for a gradient dH w.r.t. the blocks (training needs the
+    gradients of the forward pass, Sec. 4.1)."""
+    x = np.asarray(x, F64)
+    V = np.asarray(V_node, F64)
+    dH = np.asarray(dH, F64)
+    slots, n_out = O.readout_slots(orb_l)
+    v_off = np.concatenate([[0], np.cumsum(n_out)])
+    off, n_orb = shell_orbitals(orb_l)
+    dx, dV = np.zeros_like(x), np.zeros_like(V)
+    for (a, b, L, o) in slots:
+        if L > lmax:
+            continue
+        C = O.cg_real(orb_l[a], orb_l[b], L)
+        dq = np.einsum("abm,nab->nm", C, dH[:, off[a]:off[a + 1], off[b]:off[b + 1]])
+        dV[v_off[L] + o] += np.einsum("nm,nmc->c", dq, x[:, O.sl(L), :])
+        dx[:, O.sl(L), :] += dq[:, :, None] * V[v_off[L] + o][None, None, :]
+    return dx, dV
+
+
 def block_mask(row_bits, col_bits, n_orb):
     """[n][n_orb][n_orb] bool: entry present (not padding)."""
     return bits_to_bool(row_bits, n_orb)[:, :, None] & bits_to_bool(col_bits, n_orb)[:, None, :]

@@ -22,7 +22,7 @@ SYMBOLS = [
     "egnn_backward_workspace_bytes", "egnn_graph_transpose", "egnn_loss_mse", "egnn_layer_backward",
     "egnn_readout_backward", "egnn_set_option", "egnn_radial_weights_f16", "egnn_tp_segsum_f16", "egnn_so2_weight_count", "egnn_so2_workspace_bytes",
     "egnn_so2_message_sum", "egnn_hamiltonian_workspace_bytes", "egnn_onsite_hii", "egnn_apply_padding", "egnn_loss_l1l2",
-    "egnn_hamiltonian_structure", "egnn_hamiltonian_fill",
+    "egnn_hamiltonian_structure", "egnn_hamiltonian_fill", "egnn_onsite_backward_workspace_bytes", "egnn_onsite_backward",
 ]
 
 
@@ -298,6 +298,16 @@ class Egnn:
         self._check(self.lib.egnn_onsite_hii(self.ctx, _ptr(x), _ptr(V_node), _ptr(H), n, _ptr(ws),
                                              C.c_size_t(ws.numel()), _stream()))
         return H
+
+    def egnn_onsite_backward(self, x, V_node, dH):
+        n = x.shape[0]
+        nb = C.c_size_t()
+        self._check(self.lib.egnn_onsite_backward_workspace_bytes(self.ctx, n, C.byref(nb)))
+        ws = torch.empty(nb.value, dtype=torch.uint8, device="cuda")
+        dx, dV = torch.empty_like(x), torch.empty_like(V_node)
+        self._check(self.lib.egnn_onsite_backward(self.ctx, _ptr(x), _ptr(V_node), _ptr(dH), _ptr(dx), _ptr(dV), n,
+                                                  _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+        return dx, dV
 
     def egnn_apply_padding(self, H, row_atom, col_atom, species, orb_bits):
         self._check(self.lib.egnn_apply_padding(self.ctx, _ptr(H), C.c_int64(H.shape[0]), _ptr(row_atom), _ptr(col_atom),

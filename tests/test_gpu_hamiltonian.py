@@ -41,6 +41,22 @@ def test_onsite_blocks(B, lmax, E, n, orb_l):
     assert H.shape == ref.shape and U.rel_err(H, ref) < 1e-5
 
 
+@pytest.mark.parametrize("lmax,E,n,orb_l", [(0, 8, 5, ORB_L), (1, 16, 40, ORB_L), (2, 32, 333, ORB_L), (3, 64, 20, ORB_L),
+                                            (4, 128, 9, ORB_L), (4, 32, 3000, ORB_L), (4, 16, 12, (0, 1, 2, 2))])
+def test_onsite_backward(B, lmax, E, n, orb_l):
+    rng = np.random.default_rng([13, lmax, E])
+    x = synth.node_features(rng, n, lmax, E)
+    _, n_out = O.readout_slots(orb_l)
+    V = (synth.normal(rng, (sum(n_out), E)) / np.sqrt(E)).astype(np.float32)
+    n_orb = sum(2 * l + 1 for l in orb_l)
+    dH = synth.normal(rng, (n, n_orb, n_orb)).astype(np.float32)
+    m = B.Egnn(lmax, E, 8, 4.0, 1.0, orb_l=orb_l)
+    dx, dV = m.egnn_onsite_backward(B.to_device(x), B.to_device(V), B.to_device(dH))
+    rx, rV = Hm.onsite_backward(x, V, lmax, orb_l, dH)
+    assert U.rel_err(dx.cpu().numpy(), rx) < 1e-5 and U.rel_err(dV.cpu().numpy(), rV) < 1e-5
+    assert np.all(dV.cpu().numpy()[sum(n_out[:lmax + 1]):] == 0)
+
+
 def _blocks_case(B, n, n_owned, periodic, seed, shells=SHELLS3, r_cut=3.0):
     rng = np.random.default_rng([12, seed])
     w = synth.small_cluster(n, n_owned, 1, 8, 4, r_cut, seed, periodic=periodic)
@@ -153,3 +169,69 @@ def test_hamiltonian_errors(B):
     with pytest.raises(B.EgnnError):
         m.egnn_onsite_hii(B.to_device(synth.node_features(np.random.default_rng(0), 4, 1, 8)),
                           B.to_device(np.zeros((50, 8), np.float32)), small[:16])
+
+
+@pytest.mark.parametrize("index", [0, 1])
+def test_training_chain_with_onsite_blocks_padding_and_l1l2_loss(B, index):
+    """Model forward -> H_ij and H_ii -> padding -> L1+L2 loss over both -> gradients w.r.t. the readout input,
+    through egnn_readout_backward and egnn_onsite_backward, against the same chain on the oracle."""
+    import torch
+    if index == 0:
+        w = synth.small_cluster(70, 50, 2, 16, 6, 4.0, 91)
+        w.n_layers = 1
+    else:
+        w = synth.workload(1)
+    rng = np.random.default_rng([14, index])
+    wt = U.model_weights(w)
+    g = U.oracle_graph(w)
+    agg = max(1.0, U.mean_degree(g, w.n_owned))
+    n_e, n = len(g[0]), w.n_total
+    species = rng.integers(0, 3, n).astype(np.int32)
+    bits = Hm.species_orbital_bits(ORB_L, SHELLS3)
+    _, n_out = O.readout_slots(ORB_L)
+    Vn = (synth.normal(rng, (sum(n_out), w.channels)) / np.sqrt(w.channels)).astype(np.float32)
+    T_e = synth.normal(rng, (n_e, 13, 13)).astype(np.float32)
+    T_n = synth.normal(rng, (n, 13, 13)).astype(np.float32)
+    # ---- oracle
+    xs_ref, H_ref = U.oracle_forward(w, wt, g, agg)
+    xr = np.concatenate([xs_ref[-1], wt["halo"][0].astype(np.float64)], axis=0) if n > w.n_owned else xs_ref[-1]
+    Hn_ref = Hm.onsite_hii(xr, Vn, w.lmax, ORB_L)
+    rb_e, cb_e = bits[species[g[0]]], bits[species[g[1]]]
+    rb_n = bits[species]
+    le, ge = Hm.loss_l1l2(H_ref, T_e, rb_e, cb_e)
+    ln, gn = Hm.loss_l1l2(Hn_ref, T_n, rb_n, rb_n)
+    dx_e, g_ro = O.readout_backward(g, w.pos, w.box, xr, wt["readout"], w.lmax, w.lmax, w.channels, w.n_rbf, w.r_cut,
+                                    ORB_L, ge)
+    dx_n, dVn = Hm.onsite_backward(xr, Vn, w.lmax, ORB_L, gn)
+    # ---- GPU
+    m, graph, xs, H = U.gpu_forward(w, wt, agg)
+    xd = torch.cat([xs[-1], B.to_device(wt["halo"][0])], dim=0).contiguous() if n > w.n_owned else xs[-1]
+    sp_d, bits_d = B.to_device(species), _dev_bits(B, bits)
+    hws, plan = m.hamiltonian_workspace(graph)
+    Vd = B.to_device(Vn)
+    Hn = m.egnn_onsite_hii(xd, Vd, hws)
+    m.egnn_apply_padding(H, graph.src, graph.dst, sp_d, bits_d)
+    m.egnn_apply_padding(Hn, None, None, sp_d, bits_d)
+    assert U.rel_err(H.cpu().numpy(), Hm.apply_padding(H_ref, rb_e, cb_e)) < U.TOL
+    assert U.rel_err(Hn.cpu().numpy(), Hm.apply_padding(Hn_ref, rb_n, rb_n)) < U.TOL
+    loss_e, dH_e = m.egnn_loss_l1l2(H, B.to_device(T_e), graph.src, graph.dst, sp_d, bits_d, hws)
+    loss_e = float(loss_e.cpu()[0])
+    loss_n, dH_n = m.egnn_loss_l1l2(Hn, B.to_device(T_n), None, None, sp_d, bits_d, hws)
+    loss_n = float(loss_n.cpu()[0])
+    assert abs(loss_e / le - 1) < 1e-5 and abs(loss_n / ln - 1) < 1e-5
+    # |H - T| has a kink at zero: where the oracle's difference is within 1e-4 of it the two signs may differ
+    far = np.abs(H_ref - T_e) > 1e-4
+    assert np.abs((dH_e.cpu().numpy() - ge))[far].max() / np.abs(ge).max() < U.TOL and far.mean() > 0.999
+    bws = torch.empty(m.egnn_backward_workspace_bytes(graph.n_edges, graph.n_owned, graph.n_total), dtype=torch.uint8,
+                      device="cuda")
+    col_ptr, perm = m.egnn_graph_transpose(graph, bws)
+    ro = B.to_device(wt["readout"])
+    # gradients are linear in dH: feed the oracle's dH so that a flipped sign cannot enter the comparison
+    dxe_gpu, g_gpu = m.egnn_readout_backward(graph, col_ptr, perm, B.to_device(w.pos), w.box, xd, ro,
+                                             B.to_device(ge.astype(np.float32)), bws)
+    dxn_gpu, dVn_gpu = m.egnn_onsite_backward(xd, Vd, B.to_device(gn.astype(np.float32)))
+    dx_ref = dx_e + dx_n
+    assert U.rel_err((dxe_gpu + dxn_gpu).cpu().numpy(), dx_ref) < U.TOL
+    assert U.rel_err(dVn_gpu.cpu().numpy(), dVn) < U.TOL
+    for k in ("V", "W_s", "W_t", "W_r1", "W_r2"):
+        assert U.rel_err(g_gpu[k].cpu().numpy(), g_ro[k]) < U.TOL, k

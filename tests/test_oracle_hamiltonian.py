@@ -159,3 +159,27 @@ def test_padding_zeroes_exactly_the_absent_orbitals():
     keep = [0, 2, 3, 4]
     assert np.count_nonzero(P[0]) == 13 * 4 and np.count_nonzero(P[1]) == 16
     assert np.array_equal(P[1][np.ix_(keep, keep)], H[1][np.ix_(keep, keep)])
+
+
+def test_onsite_backward_by_central_differences():
+    """f = sum(G * onsite_hii(x, V)) is bilinear in (x, V): central differences are exact up to rounding."""
+    rng = np.random.default_rng(6)
+    E, lmax, n = 4, 3, 3
+    x = rng.standard_normal((n, (lmax + 1) ** 2, E))
+    V = _V(rng, ORB_L, E)
+    G = rng.standard_normal((n, 13, 13))
+    dx, dV = Hm.onsite_backward(x, V, lmax, ORB_L, G)
+    f = lambda xx, vv: float(np.sum(G * Hm.onsite_hii(xx, vv, lmax, ORB_L)))
+    eps = 1e-4
+    for _ in range(30):
+        i, q, c = rng.integers(0, n), rng.integers(0, (lmax + 1) ** 2), rng.integers(0, E)
+        xp, xn = x.copy(), x.copy()
+        xp[i, q, c] += eps; xn[i, q, c] -= eps
+        assert (f(xp, V) - f(xn, V)) / (2 * eps) == pytest.approx(dx[i, q, c], abs=1e-9)
+        r = rng.integers(0, V.shape[0])
+        Vp, Vn = V.copy(), V.copy()
+        Vp[r, c] += eps; Vn[r, c] -= eps
+        assert (f(x, Vp) - f(x, Vn)) / (2 * eps) == pytest.approx(dV[r, c], abs=1e-9)
+    # rows of V for degrees above l_max get no gradient
+    _, n_out = O.readout_slots(ORB_L)
+    assert np.all(dV[sum(n_out[:lmax + 1]):] == 0) and np.abs(dV[:sum(n_out[:lmax + 1])]).min() > 0
