@@ -98,8 +98,10 @@ def so2_linear(Xp, W0, Wr, Wi, lmax, E):
     return Yp
 
 
-def so2_messages(src, dst, r, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut, gauge=None):
-    """One transformed message per edge, lab frame: f_c(d) D^T SO2Linear(D [x_src | x_dst | e])."""
+def so2_messages(src, dst, r, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut, gauge=None, T_edge=None, envelope=True):
+    """One transformed message per edge, lab frame: f_c(d) D^T SO2Linear(D [x_src | x_dst | e]).
+    T_edge [n][(lmax+1)^2][E]: full edge embeddings of these edges (W_e is then not used); envelope=False leaves
+    the factor f_c(d) out."""
     x = np.asarray(x, F64)
     d = np.sqrt(np.einsum("ka,ka->k", r, r))
     D = wigner_blocks(lmax, bond_rotations(r / d[:, None], gauge))
@@ -107,11 +109,14 @@ def so2_messages(src, dst, r, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut, gauge=N
     M = np.zeros((n, dim, 3 * E), F64)
     M[:, :, :E] = x[src]
     M[:, :, E:2 * E] = x[dst]
-    M[:, 0, 2 * E:] = O.radial_basis(d, n_rbf, r_cut) @ np.asarray(W_e, F64).T
+    if T_edge is None:
+        M[:, 0, 2 * E:] = O.radial_basis(d, n_rbf, r_cut) @ np.asarray(W_e, F64).T
+    else:
+        M[:, :, 2 * E:] = np.asarray(T_edge, F64)
     Xp = np.einsum("kab,kbc->kac", D, M)
     Yp = so2_linear(Xp, W0, Wr, Wi, lmax, E)
     Y = np.einsum("kba,kbc->kac", D, Yp)                               # D^T = D^-1
-    return Y * O.envelope(d, r_cut)[:, None, None]
+    return Y * O.envelope(d, r_cut)[:, None, None] if envelope else Y
 
 
 def so2_message_sum(graph, pos, box, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut, agg_norm, gauge=None, chunk=4096,
@@ -137,3 +142,80 @@ def so2_message_sum(graph, pos, box, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut, 
                          None if gauge is None else gauge[k0:k1])
         np.add.at(a, dst[k0:k1], Y)
     return a / sqrt(agg_norm)
+
+
+# --------------------------------------------------------------------------------------
+# The two blocks of a layer with the full message content (Sec. 3 "Message passing", Fig. 2(b), 2(c)): persistent edge
+# embeddings, a node block that ends in an attention-weighted sum over incoming edges, an edge block without the sum.
+#
+# Choices where the paper is silent (it names the steps and leaves the formulas to its references):
+#   * edge embeddings start with the L = 0 plane W_e B(d_k) and zeros elsewhere (Sec. 3 "Initialization") and are then
+#     full tensors [(lmax+1)^2][E] that rotate like node embeddings;
+#   * attention: one head; the score of an edge is s_k = w_att . LeakyReLU_0.2(y_k[L = 0]) from the rotation-invariant
+#     plane of its transformed message (before the envelope), the weights are the softmax of the scores over the
+#     incoming edges of the destination node, and a_j = sum_k alpha_k f_c(d_k) y_k;
+#   * edge block: T'_k = T_k + f_c(d_k) y_k with its own SO(2) weights, no sum;
+#   * gate: the L = 0 plane goes through SiLU; the plane of degree l >= 1 is multiplied, channel by channel, by
+#     sigmoid(W_g[l-1] x[L = 0]) (scalars computed from the input's L = 0 plane gate the higher degrees).
+# --------------------------------------------------------------------------------------
+def edge_embedding_init(d, W_e, lmax, E, n_rbf, r_cut):
+    T = np.zeros((len(d), (lmax + 1) ** 2, E), F64)
+    T[:, 0, :] = O.radial_basis(np.asarray(d, F64), n_rbf, r_cut) @ np.asarray(W_e, F64).T
+    return T
+
+
+def attention_weights(y0, w_att, row_ptr, slope=0.2):
+    """alpha [n_edges]: softmax over each destination segment of w_att . LeakyReLU(y0[k]);  y0 [n_edges][E]."""
+    y0 = np.asarray(y0, F64)
+    s = np.where(y0 > 0, y0, slope * y0) @ np.asarray(w_att, F64)
+    alpha = np.zeros(len(s), F64)
+    for j in range(len(row_ptr) - 1):
+        k0, k1 = int(row_ptr[j]), int(row_ptr[j + 1])
+        if k1 > k0:
+            e = np.exp(s[k0:k1] - s[k0:k1].max())
+            alpha[k0:k1] = e / e.sum()
+    return alpha
+
+
+def so2_node_block(graph, pos, box, x, T_edge, W0, Wr, Wi, w_att, lmax, E, r_cut, nodes=None):
+    """a_j = sum over incoming edges of alpha_k f_c(d_k) y_k (owned nodes; `nodes`: only these rows)."""
+    src, dst, shift, row_ptr = graph
+    n_owned = len(row_ptr) - 1
+    todo = range(n_owned) if nodes is None else nodes
+    out = np.zeros((len(todo), (lmax + 1) ** 2, E), F64)
+    for i, j in enumerate(todo):
+        k0, k1 = int(row_ptr[j]), int(row_ptr[j + 1])
+        if k1 == k0:
+            continue
+        r = O.edge_vectors(pos, box, src[k0:k1], dst[k0:k1], shift[k0:k1])
+        Y = so2_messages(src[k0:k1], dst[k0:k1], r, x, None, W0, Wr, Wi, lmax, E, 0, r_cut, T_edge=T_edge[k0:k1],
+                         envelope=False)
+        alpha = attention_weights(Y[:, 0, :], w_att, np.array([0, k1 - k0]))
+        fc = O.envelope(np.sqrt(np.einsum("ka,ka->k", r, r)), r_cut)
+        out[i] = np.einsum("k,kac->ac", alpha * fc, Y)
+    return out
+
+
+def so2_edge_block(graph, pos, box, x, T_edge, W0, Wr, Wi, lmax, E, r_cut, k_range=None, chunk=4096):
+    """T'_k = T_k + f_c(d_k) y_k for every edge (or those of k_range)."""
+    src, dst, shift, row_ptr = graph
+    a, b = (0, len(src)) if k_range is None else k_range
+    out = np.zeros((b - a, (lmax + 1) ** 2, E), F64)
+    for k0 in range(a, b, chunk):
+        k1 = min(b, k0 + chunk)
+        r = O.edge_vectors(pos, box, src[k0:k1], dst[k0:k1], shift[k0:k1])
+        out[k0 - a:k1 - a] = np.asarray(T_edge[k0:k1], F64) + so2_messages(
+            src[k0:k1], dst[k0:k1], r, x, None, W0, Wr, Wi, lmax, E, 0, r_cut, T_edge=T_edge[k0:k1])
+    return out
+
+
+def gate(x, W_g, lmax):
+    """x [n][(lmax+1)^2][E], W_g [lmax][E][E]."""
+    x = np.asarray(x, F64)
+    out = np.zeros_like(x)
+    x0 = x[:, 0, :]
+    out[:, 0, :] = O.silu(x0)
+    for l in range(1, lmax + 1):
+        g = 1.0 / (1.0 + np.exp(-(x0 @ np.asarray(W_g[l - 1], F64).T)))
+        out[:, O.sl(l), :] = x[:, O.sl(l), :] * g[:, None, :]
+    return out

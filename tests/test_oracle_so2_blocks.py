@@ -1,0 +1,118 @@
+"""Pins of the node block, edge block, attention and gate of oracle/so2_oracle.py."""
+import numpy as np
+import pytest
+
+from oracle import egnn_oracle as O
+from oracle import so2_oracle as S
+from tests.test_oracle_so2 import _rot, _setup
+
+
+def _edge_lengths(w, g):
+    r = O.edge_vectors(w.pos, w.box, g[0], g[1], g[2])
+    return r, np.sqrt((r * r).sum(axis=1))
+
+
+def test_initial_edge_embedding_reproduces_the_message_sum():
+    """With T_edge = its initial value (L = 0 plane W_e B(d), zeros elsewhere) the full-content messages are the ones
+    of so2_message_sum (which is pinned to the Clebsch-Gordan product)."""
+    lmax, E, n_rbf, r_cut = 3, 4, 6, 4.0
+    w, g, x, W_e, W0, Wr, Wi = _setup(lmax, E)
+    r, d = _edge_lengths(w, g)
+    T = S.edge_embedding_init(d, W_e, lmax, E, n_rbf, r_cut)
+    assert np.all(T[:, 1:, :] == 0) and np.allclose(T[:, 0, :], O.radial_basis(d, n_rbf, r_cut) @ W_e.T)
+    Y_old = S.so2_messages(g[0], g[1], r, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut)
+    Y_new = S.so2_messages(g[0], g[1], r, x, None, W0, Wr, Wi, lmax, E, 0, r_cut, T_edge=T)
+    assert np.allclose(Y_old, Y_new, atol=1e-13)
+    # uniform attention (w_att = 0): the node block is the plain mean, i.e. the message sum rescaled per node
+    a_sum = S.so2_message_sum(g, w.pos, w.box, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut, 1.0)
+    a_att = S.so2_node_block(g, w.pos, w.box, x, T, W0, Wr, Wi, np.zeros(E), lmax, E, r_cut)
+    deg = np.diff(g[3]).astype(float)
+    assert deg.min() > 0 and np.allclose(a_att * deg[:, None, None], a_sum, atol=1e-12)
+
+
+def test_attention_weights_closed_forms():
+    rng = np.random.default_rng(3)
+    E = 5
+    w_att = rng.standard_normal(E)
+    y0 = rng.standard_normal((7, E))
+    row_ptr = np.array([0, 2, 2, 7])
+    al = S.attention_weights(y0, w_att, row_ptr)
+    lrelu = lambda t: np.where(t > 0, t, 0.2 * t)
+    s = lrelu(y0) @ w_att
+    # two edges: a logistic function of the score difference
+    assert al[0] == pytest.approx(1.0 / (1.0 + np.exp(s[1] - s[0])), abs=1e-14) and al[0] + al[1] == pytest.approx(1.0)
+    assert al[2:].sum() == pytest.approx(1.0) and np.all(al > 0)
+    assert np.allclose(al[2:] / al[2], np.exp(s[2:] - s[2]), atol=1e-13)
+    # adding a constant to all scores of a node changes nothing; very large scores do not overflow
+    big = S.attention_weights(y0 * 1e4, w_att, row_ptr)
+    assert np.all(np.isfinite(big)) and big[:2].sum() == pytest.approx(1.0)
+    # negative inputs are scaled by 0.2
+    one = S.attention_weights(np.array([[-1.0], [0.0]]), np.array([1.0]), np.array([0, 2]))
+    assert one[0] == pytest.approx(1.0 / (1.0 + np.exp(0.2)))
+
+
+@pytest.mark.parametrize("lmax", [1, 3])
+def test_blocks_are_equivariant(lmax):
+    """Rotating positions, node embeddings and edge embeddings rotates the outputs of both blocks; the attention
+    weights are invariant."""
+    E, r_cut = 4, 4.0
+    w, g, x, W_e, W0, Wr, Wi = _setup(lmax, E, seed=2)
+    rng = np.random.default_rng(7)
+    T = rng.standard_normal((len(g[0]), (lmax + 1) ** 2, E))
+    w_att = rng.standard_normal(E)
+    R = _rot(rng)
+    Dm = O.wigner_d_block(lmax, R)
+    c = w.pos.astype(np.float64).mean(axis=0)
+    pos2 = ((w.pos.astype(np.float64) - c) @ R.T + c).astype(np.float32)
+    x2 = np.einsum("ab,nbc->nac", Dm, x)
+    T2 = np.einsum("ab,nbc->nac", Dm, T)
+    g2 = O.neighbour_list(pos2, w.n_owned, w.box, w.pbc, r_cut)
+    if not (np.array_equal(g2[0], g[0]) and np.array_equal(g2[1], g[1])):
+        pytest.skip("rounding of the rotated positions moved a pair across the cutoff")
+    a1 = S.so2_node_block(g, w.pos, w.box, x, T, W0, Wr, Wi, w_att, lmax, E, r_cut)
+    a2 = S.so2_node_block(g2, pos2, w.box, x2, T2, W0, Wr, Wi, w_att, lmax, E, r_cut)
+    assert np.allclose(a2, np.einsum("ab,nbc->nac", Dm, a1), atol=2e-6 * np.abs(a1).max())
+    t1 = S.so2_edge_block(g, w.pos, w.box, x, T, W0, Wr, Wi, lmax, E, r_cut)
+    t2 = S.so2_edge_block(g2, pos2, w.box, x2, T2, W0, Wr, Wi, lmax, E, r_cut)
+    assert np.allclose(t2, np.einsum("ab,nbc->nac", Dm, t1), atol=2e-6 * np.abs(t1).max())
+    assert np.abs(a1).max() > 1e-2 and np.abs(t1 - T).max() > 1e-2
+
+
+def test_edge_embedding_enters_every_degree():
+    """A change of T_edge in degree l changes the message: the edge slot of the weights is read for every l."""
+    lmax, E, r_cut = 2, 4, 4.0
+    w, g, x, W_e, W0, Wr, Wi = _setup(lmax, E, seed=4)
+    rng = np.random.default_rng(8)
+    T = rng.standard_normal((len(g[0]), 9, E))
+    base = S.so2_edge_block(g, w.pos, w.box, x, T, W0, Wr, Wi, lmax, E, r_cut)
+    for l in range(lmax + 1):
+        T2 = T.copy()
+        T2[:, O.sl(l), :] += 1.0
+        assert np.abs(S.so2_edge_block(g, w.pos, w.box, x, T2, W0, Wr, Wi, lmax, E, r_cut) - base - (T2 - T)).max() > 1e-3
+    # zero weights: the block is the identity; k_range gives the same rows
+    Z0, Zr, Zi = np.zeros_like(W0), [np.zeros_like(a) for a in Wr], [np.zeros_like(a) for a in Wi]
+    assert np.array_equal(S.so2_edge_block(g, w.pos, w.box, x, T, Z0, Zr, Zi, lmax, E, r_cut), T)
+    assert np.array_equal(S.so2_edge_block(g, w.pos, w.box, x, T, W0, Wr, Wi, lmax, E, r_cut, k_range=(3, 9)), base[3:9])
+    # nodes= gives the same rows of the node block
+    w_att = rng.standard_normal(E)
+    a = S.so2_node_block(g, w.pos, w.box, x, T, W0, Wr, Wi, w_att, lmax, E, r_cut)
+    assert np.array_equal(S.so2_node_block(g, w.pos, w.box, x, T, W0, Wr, Wi, w_att, lmax, E, r_cut, nodes=[5, 1]), a[[5, 1]])
+
+
+def test_gate_closed_forms_and_equivariance():
+    rng = np.random.default_rng(9)
+    lmax, E = 3, 5
+    x = rng.standard_normal((6, 16, E))
+    W_g = rng.standard_normal((lmax, E, E))
+    y = S.gate(x, W_g, lmax)
+    assert np.allclose(y[:, 0, :], x[:, 0, :] / (1 + np.exp(-x[:, 0, :])))
+    # zero scalars: every higher degree is halved, the scalar plane stays zero
+    x0 = x.copy(); x0[:, 0, :] = 0
+    y0 = S.gate(x0, W_g, lmax)
+    assert np.allclose(y0[:, 1:, :], 0.5 * x0[:, 1:, :]) and np.all(y0[:, 0, :] == 0)
+    # the gate of (degree l, channel c) is sigmoid(sum_c' W_g[l-1][c][c'] x[0][c'])
+    n, l, c = 2, 2, 3
+    gate = 1 / (1 + np.exp(-(W_g[l - 1][c] @ x[n, 0, :])))
+    assert np.allclose(y[n, O.sl(l), c], x[n, O.sl(l), c] * gate)
+    Dm = O.wigner_d_block(lmax, _rot(rng))
+    assert np.allclose(S.gate(np.einsum("ab,nbc->nac", Dm, x), W_g, lmax), np.einsum("ab,nbc->nac", Dm, y), atol=1e-12)
