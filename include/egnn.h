@@ -239,6 +239,29 @@ int egnn_so2_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, size_t* bytes
 int egnn_so2_message_sum(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3], const float* x,
                          const float* W_e, const float* W_so2, float* a, void* ws, size_t ws_bytes, void* stream);
 
+/* ---- the two blocks of a layer with the full message content (Sec. 3 "Message passing"; Fig. 2(b), 2(c)) ----
+ * Edge embeddings T_edge [n_edges][(lmax+1)^2][channels] are persistent tensors that rotate like node embeddings;
+ * the message of edge k is [x_src | x_dst | T_edge_k] in every degree (3 * channels), transformed as in
+ * egnn_so2_message_sum (W_so2 in the same layout; all of its columns are used now).
+ * egnn_edge_embed_init: the initial embeddings (Sec. 3 "Initialization"): L = 0 plane W_e B(d_k), zeros elsewhere.
+ * egnn_so2_node_block (Fig. 2(b)): a[j] = sum_{k: dst(k) = j} alpha_k f_c(d_k) y_k for owned j, with the attention
+ *   weights alpha = softmax over the incoming edges of j of s_k = sum_c w_att[c] LeakyReLU_0.2(y_k[L = 0][c]) (one
+ *   head; the score uses the rotation-invariant plane of the transformed message before the envelope).
+ * egnn_so2_edge_block (Fig. 2(c)): T_edge_out[k] = T_edge_in[k] + f_c(d_k) y_k, no sum; T_edge_out may alias T_edge_in.
+ * egnn_gate: y[n][L = 0][c] = SiLU(x[n][L = 0][c]); for l >= 1, y[n][(l,m)][c] = x[n][(l,m)][c] *
+ *   sigmoid(sum_c' W_g[l-1][c][c'] x[n][L = 0][c']);  W_g [lmax][channels][channels]; y may alias x.
+ * ws: egnn_so2_blocks_workspace_bytes, 256-byte aligned. */
+int egnn_so2_blocks_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, size_t* bytes);
+int egnn_edge_embed_init(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3], const float* W_e,
+                         float* T_edge, void* ws, size_t ws_bytes, void* stream);
+int egnn_so2_node_block(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3], const float* x,
+                        const float* T_edge, const float* W_so2, const float* w_att, float* a, void* ws,
+                        size_t ws_bytes, void* stream);
+int egnn_so2_edge_block(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3], const float* x,
+                        const float* T_edge_in, const float* W_so2, float* T_edge_out, void* ws, size_t ws_bytes,
+                        void* stream);
+int egnn_gate(egnn_ctx* ctx, const float* x, const float* W_g, float* y, int32_t n_nodes, void* stream);
+
 /* ---- assembly of the predicted Hamiltonian (Sec. 3, end of "Message passing": nodes give the diagonal blocks, edges the
  *      off-diagonal ones; Fig. 2(e): collapse E -> 1, padded outputs; Sec. 2.2 / Eq. 1: the coupled basis and its
  *      inverse; Sec. 6: combined L1 + L2 loss over the elements of H) ----

@@ -21,7 +21,8 @@ SYMBOLS = [
     "egnn_layer_forward", "egnn_readout_hij", "egnn_timing_enable", "egnn_timing_read",
     "egnn_backward_workspace_bytes", "egnn_graph_transpose", "egnn_loss_mse", "egnn_layer_backward",
     "egnn_readout_backward", "egnn_set_option", "egnn_radial_weights_f16", "egnn_tp_segsum_f16", "egnn_so2_weight_count", "egnn_so2_workspace_bytes",
-    "egnn_so2_message_sum", "egnn_hamiltonian_workspace_bytes", "egnn_onsite_hii", "egnn_apply_padding", "egnn_loss_l1l2",
+    "egnn_so2_message_sum", "egnn_so2_blocks_workspace_bytes", "egnn_edge_embed_init", "egnn_so2_node_block",
+    "egnn_so2_edge_block", "egnn_gate", "egnn_hamiltonian_workspace_bytes", "egnn_onsite_hii", "egnn_apply_padding", "egnn_loss_l1l2",
     "egnn_hamiltonian_structure", "egnn_hamiltonian_fill", "egnn_onsite_backward_workspace_bytes", "egnn_onsite_backward",
 ]
 
@@ -259,6 +260,40 @@ class Egnn:
         self._check(self.lib.egnn_so2_message_sum(self.ctx, C.byref(g), _ptr(pos), _f3(box), _ptr(x), _ptr(W_e),
                                                   _ptr(W_so2), _ptr(a), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
         return a
+
+    def egnn_so2_blocks_workspace_bytes(self, n_edges):
+        out = C.c_size_t()
+        self._check(self.lib.egnn_so2_blocks_workspace_bytes(self.ctx, C.c_int64(n_edges), C.byref(out)))
+        return out.value
+
+    def egnn_edge_embed_init(self, graph, pos, box, W_e, ws, out=None):
+        T = out if out is not None else torch.empty((graph.n_edges, self.dim, self.channels), dtype=torch.float32,
+                                                    device="cuda")
+        g = graph.desc()
+        self._check(self.lib.egnn_edge_embed_init(self.ctx, C.byref(g), _ptr(pos), _f3(box), _ptr(W_e), _ptr(T), _ptr(ws),
+                                                  C.c_size_t(ws.numel()), _stream()))
+        return T
+
+    def egnn_so2_node_block(self, graph, pos, box, x, T_edge, W_so2, w_att, ws, out=None):
+        a = out if out is not None else torch.empty((graph.n_owned, self.dim, self.channels), dtype=torch.float32,
+                                                    device="cuda")
+        g = graph.desc()
+        self._check(self.lib.egnn_so2_node_block(self.ctx, C.byref(g), _ptr(pos), _f3(box), _ptr(x), _ptr(T_edge),
+                                                 _ptr(W_so2), _ptr(w_att), _ptr(a), _ptr(ws), C.c_size_t(ws.numel()),
+                                                 _stream()))
+        return a
+
+    def egnn_so2_edge_block(self, graph, pos, box, x, T_edge, W_so2, ws, out=None):
+        T = out if out is not None else torch.empty_like(T_edge)
+        g = graph.desc()
+        self._check(self.lib.egnn_so2_edge_block(self.ctx, C.byref(g), _ptr(pos), _f3(box), _ptr(x), _ptr(T_edge),
+                                                 _ptr(W_so2), _ptr(T), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+        return T
+
+    def egnn_gate(self, x, W_g, out=None):
+        y = out if out is not None else torch.empty_like(x)
+        self._check(self.lib.egnn_gate(self.ctx, _ptr(x), _ptr(W_g), _ptr(y), x.shape[0], _stream()))
+        return y
 
     # ---- layer / readout
     def egnn_layer_forward(self, graph, pos, box, x_in, W, ws, w_edge=None, out=None):

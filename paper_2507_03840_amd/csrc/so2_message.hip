@@ -26,7 +26,12 @@ struct So2Bufs {
   int K[5], N[5];   // columns of A_m and of Y_m
 };
 
-__host__ __device__ inline int so2_K(int lmax, int E, int m) { return m == 0 ? (lmax + 1) * 2 * E + E : 2 * (lmax + 1 - m) * 2 * E; }
+// columns of A_m: without persistent edge embeddings the edge slot exists only for l = 0 (its other planes are zero);
+// with them (full) every degree carries [source | destination | edge]
+__host__ __device__ inline int so2_K(int lmax, int E, int m, bool full = false) {
+  if (full) return (m == 0 ? 1 : 2) * (lmax + 1 - m) * 3 * E;
+  return m == 0 ? (lmax + 1) * 2 * E + E : 2 * (lmax + 1 - m) * 2 * E;
+}
 __host__ __device__ inline int so2_N(int lmax, int E, int m) { return m == 0 ? (lmax + 1) * E : 2 * (lmax + 1 - m) * E; }
 // first float of order m in the packed weights: W_0, then (Wr_m, Wi_m) for m = 1..lmax
 static size_t so2_w_offset(int lmax, int E, int m) {
@@ -39,10 +44,11 @@ static size_t so2_w_offset(int lmax, int E, int m) {
 }
 
 // ---------------------------------------------------------------------------------------------- 1. gather
-template <int LMAX>
+// FULL: edge_in is the edge embedding tensor [n_edges][(LMAX+1)^2][E]; otherwise it is W_e [E][n_rbf]
+template <int LMAX, bool FULL>
 __global__ __launch_bounds__(256) void so2_gather_kernel(const int* __restrict__ src, const int* __restrict__ dst,
                                                          const float4* __restrict__ rhat_d, const float* __restrict__ x,
-                                                         const float* __restrict__ W_e, So2Bufs b, long n_edges,
+                                                         const float* __restrict__ edge_in, So2Bufs b, long n_edges,
                                                          int log2E, int n_rbf, float r_cut) {
   constexpr int D = (LMAX + 1) * (LMAX + 1);
   const int E = 1 << log2E;
@@ -62,42 +68,103 @@ __global__ __launch_bounds__(256) void so2_gather_kernel(const int* __restrict__
   egnn_bond_trig<LMAX>(g.x, g.y, g.z, t);
   egnn_to_bond_frame<LMAX>(vs, t);
   egnn_to_bond_frame<LMAX>(vd, t);
-  // L = 0 plane of the edge embedding: a linear map of the Gaussian expansion of the length
-  const float step = r_cut / (float)(n_rbf - 1);
-  const float inv2s2 = 0.5f / (step * step);
-  float e0 = 0.0f;
-  for (int q = 0; q < n_rbf; ++q) {
-    const float u = g.w - (float)q * step;
-    e0 += W_e[c * n_rbf + q] * __expf(-u * u * inv2s2);
-  }
-  float* a0 = b.A[0] + (size_t)k * b.K[0] + c;
+  if constexpr (FULL) {
+    float ve[D];
+    const float* te = edge_in + (((size_t)k * D) << log2E) + c;
 #pragma unroll
-  for (int l = 0; l <= LMAX; ++l) {
-    __builtin_nontemporal_store(vs[l * l + l], a0 + ((2 * l) << log2E));
-    __builtin_nontemporal_store(vd[l * l + l], a0 + ((2 * l + 1) << log2E));
-  }
-  __builtin_nontemporal_store(e0, a0 + ((2 * (LMAX + 1)) << log2E));
+    for (int i = 0; i < D; ++i) ve[i] = __builtin_nontemporal_load(te + ((size_t)i << log2E));
+    egnn_to_bond_frame<LMAX>(ve, t);
+    float* a0 = b.A[0] + (size_t)k * b.K[0] + c;
 #pragma unroll
-  for (int m = 1; m <= LMAX; ++m) {
-    constexpr int dummy = 0;
-    (void)dummy;
-    const int nl = LMAX + 1 - m;
-    float* am = b.A[m] + (size_t)k * b.K[m] + c;
+    for (int l = 0; l <= LMAX; ++l) {
+      __builtin_nontemporal_store(vs[l * l + l], a0 + ((3 * l) << log2E));
+      __builtin_nontemporal_store(vd[l * l + l], a0 + ((3 * l + 1) << log2E));
+      __builtin_nontemporal_store(ve[l * l + l], a0 + ((3 * l + 2) << log2E));
+    }
 #pragma unroll
-    for (int l = m; l <= LMAX; ++l) {
-      const int col = (2 * (l - m)) << log2E;
-      __builtin_nontemporal_store(vs[l * l + l + m], am + col);
-      __builtin_nontemporal_store(vd[l * l + l + m], am + col + E);
-      __builtin_nontemporal_store(vs[l * l + l - m], am + ((2 * nl) << log2E) + col);
-      __builtin_nontemporal_store(vd[l * l + l - m], am + ((2 * nl) << log2E) + col + E);
+    for (int m = 1; m <= LMAX; ++m) {
+      const int nl = LMAX + 1 - m;
+      float* am = b.A[m] + (size_t)k * b.K[m] + c;
+#pragma unroll
+      for (int l = m; l <= LMAX; ++l) {
+        const int col = (3 * (l - m)) << log2E, neg = (3 * nl) << log2E;
+        __builtin_nontemporal_store(vs[l * l + l + m], am + col);
+        __builtin_nontemporal_store(vd[l * l + l + m], am + col + E);
+        __builtin_nontemporal_store(ve[l * l + l + m], am + col + 2 * E);
+        __builtin_nontemporal_store(vs[l * l + l - m], am + neg + col);
+        __builtin_nontemporal_store(vd[l * l + l - m], am + neg + col + E);
+        __builtin_nontemporal_store(ve[l * l + l - m], am + neg + col + 2 * E);
+      }
+    }
+  } else {
+    // L = 0 plane of the edge embedding: a linear map of the Gaussian expansion of the length
+    const float step = r_cut / (float)(n_rbf - 1);
+    const float inv2s2 = 0.5f / (step * step);
+    float e0 = 0.0f;
+    for (int q = 0; q < n_rbf; ++q) {
+      const float u = g.w - (float)q * step;
+      e0 += edge_in[c * n_rbf + q] * __expf(-u * u * inv2s2);
+    }
+    float* a0 = b.A[0] + (size_t)k * b.K[0] + c;
+#pragma unroll
+    for (int l = 0; l <= LMAX; ++l) {
+      __builtin_nontemporal_store(vs[l * l + l], a0 + ((2 * l) << log2E));
+      __builtin_nontemporal_store(vd[l * l + l], a0 + ((2 * l + 1) << log2E));
+    }
+    __builtin_nontemporal_store(e0, a0 + ((2 * (LMAX + 1)) << log2E));
+#pragma unroll
+    for (int m = 1; m <= LMAX; ++m) {
+      const int nl = LMAX + 1 - m;
+      float* am = b.A[m] + (size_t)k * b.K[m] + c;
+#pragma unroll
+      for (int l = m; l <= LMAX; ++l) {
+        const int col = (2 * (l - m)) << log2E;
+        __builtin_nontemporal_store(vs[l * l + l + m], am + col);
+        __builtin_nontemporal_store(vd[l * l + l + m], am + col + E);
+        __builtin_nontemporal_store(vs[l * l + l - m], am + ((2 * nl) << log2E) + col);
+        __builtin_nontemporal_store(vd[l * l + l - m], am + ((2 * nl) << log2E) + col + E);
+      }
     }
   }
 }
 
+// The initial edge embedding (Sec. 3 "Initialization"): L = 0 plane = W_e B(d_k), zeros elsewhere.
+__global__ __launch_bounds__(256) void so2_edge_init_kernel(const float4* __restrict__ rhat_d, const float* __restrict__ W_e,
+                                                            float* __restrict__ T_edge, long n_edges, int D, int log2E,
+                                                            int n_rbf, float r_cut) {
+  const int E = 1 << log2E;
+  const int c = threadIdx.x & (E - 1);
+  const long k = (long)blockIdx.x * (256 >> log2E) + (threadIdx.x >> log2E);
+  if (k >= n_edges) return;
+  const float d = rhat_d[k].w;
+  const float step = r_cut / (float)(n_rbf - 1);
+  const float inv2s2 = 0.5f / (step * step);
+  float e0 = 0.0f;
+  for (int q = 0; q < n_rbf; ++q) {
+    const float u = d - (float)q * step;
+    e0 += W_e[c * n_rbf + q] * __expf(-u * u * inv2s2);
+  }
+  float* te = T_edge + (((size_t)k * D) << log2E) + c;
+  te[0] = e0;
+  for (int i = 1; i < D; ++i) te[(size_t)i << log2E] = 0.0f;
+}
+
 // ---------------------------------------------------------------------------------------------- 2. weights
 // B_m[k][n] for the column order of A_m (k) and of Y_m (n); W points at W_0 (m = 0) or at Wr_m (Wi_m follows it)
-__device__ __forceinline__ float so2_b_value(const float* __restrict__ W, int m, int lmax, int E, int k, int n, int K, int N) {
+__device__ __forceinline__ float so2_b_value(const float* __restrict__ W, int m, int lmax, int E, int k, int n, int K, int N,
+                                             bool full) {
   if (k >= K || n >= N) return 0.0f;
+  if (full) {
+    // the columns of A_m are in the column order of the weights: (l_in - m) 3E + g E + c, +m half then -m half
+    const int nl = lmax + 1 - m;
+    const int half_k = nl * 3 * E, half_n = nl * E;
+    if (m == 0) return W[(size_t)n * half_k + k];
+    const int s_in = k / half_k, col = k - s_in * half_k;
+    const int s_out = n / half_n, row = n - s_out * half_n;
+    const size_t at = (size_t)row * half_k + col, sz = (size_t)half_n * half_k;
+    if (s_in == s_out) return W[at];
+    return s_in == 0 ? W[sz + at] : -W[sz + at];
+  }
   if (m == 0) {
     const int edge0 = (lmax + 1) * 2 * E;
     int col;
@@ -123,7 +190,7 @@ __device__ __forceinline__ float so2_b_value(const float* __restrict__ W, int m,
 
 // T[ct][step][j][piece][64]: thread -> (ct, step, j, pair of contraction indices)
 __global__ __launch_bounds__(256) void so2_pack_kernel(const float* __restrict__ W, uint16_t* __restrict__ T, int m, int lmax,
-                                                       int E, int K, int N, int n_steps, int n_ct) {
+                                                       int E, int K, int N, int n_steps, int n_ct, bool full) {
   const long i = (long)blockIdx.x * 256 + threadIdx.x;
   const long total = (long)n_ct * n_steps * 64 * 32;
   if (i >= total) return;
@@ -131,7 +198,7 @@ __global__ __launch_bounds__(256) void so2_pack_kernel(const float* __restrict__
   const long blk = i >> 11;                    // ct * n_steps + step
   const int step = (int)(blk % n_steps), ct = (int)(blk / n_steps);
   const int n = ct * 64 + j, k = step * 64 + 2 * rp;
-  const Split3 s0 = split3(so2_b_value(W, m, lmax, E, k, n, K, N)), s1 = split3(so2_b_value(W, m, lmax, E, k + 1, n, K, N));
+  const Split3 s0 = split3(so2_b_value(W, m, lmax, E, k, n, K, N, full)), s1 = split3(so2_b_value(W, m, lmax, E, k + 1, n, K, N, full));
   uint32_t* o = reinterpret_cast<uint32_t*>(T) + blk * (64 * 96) + j * 96 + rp;
   o[0] = pack2(s0.hi, s1.hi);
   o[32] = pack2(s0.mid, s1.mid);
@@ -243,9 +310,32 @@ __global__ __launch_bounds__(RB_THREADS) void so2_gemm_kernel(const float* __res
 }
 
 // ---------------------------------------------------------------------------------------------- 4. scatter
+// bond-frame rows of Y (m-major) of edge k, channel c -> o[(l, m)] in the lab frame
+template <int LMAX>
+__device__ __forceinline__ void so2_load_rotate_back(const So2Bufs& b, long k, int c, int log2E, const float4& g, float* o) {
+  const float* y0 = b.Y[0] + (size_t)k * b.N[0] + c;
+#pragma unroll
+  for (int l = 0; l <= LMAX; ++l) o[l * l + l] = __builtin_nontemporal_load(y0 + (l << log2E));
+#pragma unroll
+  for (int m = 1; m <= LMAX; ++m) {
+    const int nl = LMAX + 1 - m;
+    const float* ym = b.Y[m] + (size_t)k * b.N[m] + c;
+#pragma unroll
+    for (int l = m; l <= LMAX; ++l) {
+      o[l * l + l + m] = __builtin_nontemporal_load(ym + ((l - m) << log2E));
+      o[l * l + l - m] = __builtin_nontemporal_load(ym + ((nl + l - m) << log2E));
+    }
+  }
+  BondTrig t;
+  egnn_bond_trig<LMAX>(g.x, g.y, g.z, t);
+  egnn_from_bond_frame<LMAX>(o, t);
+}
+
+// alpha != NULL: every message is weighted by its attention weight as well
 template <int LMAX>
 __global__ __launch_bounds__(256) void so2_scatter_kernel(const int* __restrict__ row_ptr, const float4* __restrict__ rhat_d,
-                                                          So2Bufs b, float* __restrict__ a, int n_owned, int log2E,
+                                                          So2Bufs b, const float* __restrict__ alpha,
+                                                          float* __restrict__ a, int n_owned, int log2E,
                                                           int nodes_per_xcd, float scale, float r_cut) {
   constexpr int D = (LMAX + 1) * (LMAX + 1);
   __shared__ float red[256 * D];
@@ -261,23 +351,9 @@ __global__ __launch_bounds__(256) void so2_scatter_kernel(const int* __restrict_
   for (int k = k0 + slot; k < k1; k += n_slots) {
     const float4 g = rhat_d[k];
     float o[D];
-    const float* y0 = b.Y[0] + (size_t)k * b.N[0] + c;
-#pragma unroll
-    for (int l = 0; l <= LMAX; ++l) o[l * l + l] = __builtin_nontemporal_load(y0 + (l << log2E));
-#pragma unroll
-    for (int m = 1; m <= LMAX; ++m) {
-      const int nl = LMAX + 1 - m;
-      const float* ym = b.Y[m] + (size_t)k * b.N[m] + c;
-#pragma unroll
-      for (int l = m; l <= LMAX; ++l) {
-        o[l * l + l + m] = __builtin_nontemporal_load(ym + ((l - m) << log2E));
-        o[l * l + l - m] = __builtin_nontemporal_load(ym + ((nl + l - m) << log2E));
-      }
-    }
-    BondTrig t;
-    egnn_bond_trig<LMAX>(g.x, g.y, g.z, t);
-    egnn_from_bond_frame<LMAX>(o, t);
-    const float fc = 0.5f * (1.0f + cosf(3.14159265358979323846f * g.w / r_cut));
+    so2_load_rotate_back<LMAX>(b, k, c, log2E, g, o);
+    float fc = 0.5f * (1.0f + cosf(3.14159265358979323846f * g.w / r_cut));
+    if (alpha) fc *= alpha[k];
 #pragma unroll
     for (int i = 0; i < D; ++i) acc[i] += fc * o[i];
   }
@@ -293,6 +369,92 @@ __global__ __launch_bounds__(256) void so2_scatter_kernel(const int* __restrict_
   }
 }
 
+// ---------------------------------------------------------------------------------------------- 5. attention
+// One wavefront per destination node: score of an incoming edge from the L = 0 plane of its transformed message (the
+// first E columns of Y_0; that plane is the same in the bond frame and in the lab frame), softmax over the node's edges.
+__global__ __launch_bounds__(256) void so2_attention_kernel(const int* __restrict__ row_ptr, const float* __restrict__ Y0,
+                                                            int N0, const float* __restrict__ w_att,
+                                                            float* __restrict__ alpha, int n_owned, int E) {
+  const int lane = threadIdx.x & 63;
+  const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (j >= n_owned) return;
+  const int k0 = row_ptr[j], k1 = row_ptr[j + 1];
+  float mx = -3.0e38f;
+  for (int k = k0 + lane; k < k1; k += 64) {
+    const float* y = Y0 + (size_t)k * N0;
+    float sc = 0.0f;
+    for (int c = 0; c < E; ++c) {
+      const float v = y[c];
+      sc += w_att[c] * (v > 0.0f ? v : 0.2f * v);
+    }
+    alpha[k] = sc;
+    mx = fmaxf(mx, sc);
+  }
+  for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+  float sum = 0.0f;
+  for (int k = k0 + lane; k < k1; k += 64) {
+    const float e = __expf(alpha[k] - mx);     // written by this lane above
+    alpha[k] = e;
+    sum += e;
+  }
+  for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+  const float inv = 1.0f / sum;
+  for (int k = k0 + lane; k < k1; k += 64) alpha[k] *= inv;
+}
+
+// ---------------------------------------------------------------------------------------------- 6. edge update
+// lane = (edge, channel): T_out = T_in + f_c(d) * (transformed message, rotated back); no sum over edges.
+template <int LMAX>
+__global__ __launch_bounds__(256) void so2_edge_update_kernel(const float4* __restrict__ rhat_d, So2Bufs b,
+                                                              const float* __restrict__ T_in, float* __restrict__ T_out,
+                                                              long n_edges, int log2E, float r_cut) {
+  constexpr int D = (LMAX + 1) * (LMAX + 1);
+  const int E = 1 << log2E;
+  const int c = threadIdx.x & (E - 1);
+  const long k = (long)blockIdx.x * (256 >> log2E) + (threadIdx.x >> log2E);
+  if (k >= n_edges) return;
+  const float4 g = rhat_d[k];
+  float o[D];
+  so2_load_rotate_back<LMAX>(b, k, c, log2E, g, o);
+  const float fc = 0.5f * (1.0f + cosf(3.14159265358979323846f * g.w / r_cut));
+  const float* ti = T_in + (((size_t)k * D) << log2E) + c;
+  float* to = T_out + (((size_t)k * D) << log2E) + c;
+#pragma unroll
+  for (int i = 0; i < D; ++i)
+    __builtin_nontemporal_store(__builtin_nontemporal_load(ti + ((size_t)i << log2E)) + fc * o[i], to + ((size_t)i << log2E));
+}
+
+// ---------------------------------------------------------------------------------------------- 7. gate
+// One workgroup per node: y[L=0] = SiLU(x[L=0]); y[(l,m)][c] = x[(l,m)][c] * sigmoid(sum_c' W_g[l-1][c][c'] x[L=0][c']).
+__global__ __launch_bounds__(256) void so2_gate_kernel(const float* __restrict__ x, const float* __restrict__ W_g,
+                                                       float* __restrict__ y, int lmax, int log2E) {
+  __shared__ float s_x0[128];
+  __shared__ float s_gate[4 * 128];
+  const int E = 1 << log2E, D = (lmax + 1) * (lmax + 1), tid = threadIdx.x;
+  const float* xi = x + (((size_t)blockIdx.x * D) << log2E);
+  float* yi = y + (((size_t)blockIdx.x * D) << log2E);
+  if (tid < E) s_x0[tid] = xi[tid];
+  __syncthreads();
+  for (int t = tid; t < (lmax << log2E); t += 256) {
+    const float* wrow = W_g + ((size_t)t << log2E);     // row (l-1) * E + c
+    float sc = 0.0f;
+    for (int cc = 0; cc < E; ++cc) sc += wrow[cc] * s_x0[cc];
+    s_gate[t] = 1.0f / (1.0f + __expf(-sc));
+  }
+  __syncthreads();
+  for (int idx = tid; idx < (D << log2E); idx += 256) {
+    const int q = idx >> log2E, c = idx & (E - 1);
+    const float v = xi[idx];
+    if (q == 0) {
+      yi[idx] = v / (1.0f + __expf(-v));
+    } else {
+      int l = 1;
+      while ((l + 1) * (l + 1) <= q) ++l;
+      yi[idx] = v * s_gate[((l - 1) << log2E) + c];
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------------------------- host side
 static size_t so2_a256(size_t n) { return (n + 255) & ~(size_t)255; }
 static int so2_steps(int K) { return (K + 63) / 64; }
@@ -304,26 +466,130 @@ extern "C" int egnn_so2_weight_count(const egnn_ctx* ctx, int64_t* n_floats) {
   return EGNN_OK;
 }
 
-static size_t so2_ws(const egnn_ctx* ctx, int64_t n_edges, bool carve, char* base, float** rhat_d, So2Bufs* b, uint16_t** T) {
+// rhat_d, the operands A_m, the results Y_m, the packed weights, and (blocks only) one float per edge
+static size_t so2_ws(const egnn_ctx* ctx, int64_t n_edges, bool full, bool carve, char* base, float** rhat_d, So2Bufs* b,
+                     uint16_t** T, float** alpha) {
   const int lmax = ctx->desc.lmax, E = ctx->desc.channels;
   size_t used = 0;
   auto take = [&](size_t bytes) { char* p = carve ? base + used : nullptr; used += so2_a256(bytes); return p; };
   float* rd = (float*)take((size_t)n_edges * 16);
   if (rhat_d) *rhat_d = rd;
   for (int m = 0; m <= lmax; ++m) {
-    const int K = so2_K(lmax, E, m), N = so2_N(lmax, E, m);
+    const int K = so2_K(lmax, E, m, full), N = so2_N(lmax, E, m);
     float* A = (float*)take((size_t)n_edges * K * sizeof(float));
     float* Y = (float*)take((size_t)n_edges * N * sizeof(float));
     uint16_t* t = (uint16_t*)take((size_t)so2_tiles(N) * so2_steps(K) * 64 * 3 * 64 * sizeof(uint16_t));
     if (b) { b->A[m] = A; b->Y[m] = Y; b->K[m] = K; b->N[m] = N; }
     if (T) T[m] = t;
   }
+  if (full) {
+    float* al = (float*)take((size_t)n_edges * sizeof(float));
+    if (alpha) *alpha = al;
+  }
   return used;
 }
 
 extern "C" int egnn_so2_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, size_t* bytes) {
   if (!ctx || !bytes || n_edges < 0) return EGNN_EINVAL;
-  *bytes = so2_ws(ctx, n_edges, false, nullptr, nullptr, nullptr, nullptr) + 256;
+  *bytes = so2_ws(ctx, n_edges, false, false, nullptr, nullptr, nullptr, nullptr, nullptr) + 256;
+  return EGNN_OK;
+}
+
+extern "C" int egnn_so2_blocks_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, size_t* bytes) {
+  if (!ctx || !bytes || n_edges < 0) return EGNN_EINVAL;
+  *bytes = so2_ws(ctx, n_edges, true, false, nullptr, nullptr, nullptr, nullptr, nullptr) + 256;
+  return EGNN_OK;
+}
+
+struct So2Call {
+  float* rhat_d;
+  float* alpha;
+  So2Bufs b;
+  uint16_t* T[5];
+};
+
+static int so2_check(egnn_ctx* ctx, const egnn_graph* g, const void* ws, size_t ws_bytes, bool full, const char* who) {
+  if (!g || g->n_edges < 0 || g->n_edges > 2147483647LL || g->n_owned < 0 || g->n_total < g->n_owned || !g->row_ptr ||
+      (g->n_edges > 0 && (!g->src || !g->dst)))
+    return egnn_fail(ctx, EGNN_EINVAL, std::string(who) + ": bad graph");
+  if (!ws || ((uintptr_t)ws & 255) != 0) return egnn_fail(ctx, EGNN_EINVAL, std::string(who) + ": workspace missing or not 256-byte aligned");
+  if (ctx->desc.channels < 8 || ctx->desc.n_rbf < 2)
+    return egnn_fail(ctx, EGNN_EINVAL, std::string(who) + ": needs >= 8 channels and >= 2 radial bases");
+  if (ctx->desc.lmax < 0 || ctx->desc.lmax > 4) return egnn_fail(ctx, EGNN_EINVAL, std::string(who) + ": lmax out of range");
+  if (ws_bytes < so2_ws(ctx, g->n_edges, full, false, nullptr, nullptr, nullptr, nullptr, nullptr))
+    return egnn_fail(ctx, EGNN_EWS, std::string(who) + ": workspace too small");
+  return EGNN_OK;
+}
+
+// geometry, gather into the m-major operands, weight packing and the GEMMs: Y_m of every edge in the workspace
+static int so2_transform(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3], const float* x,
+                         const float* edge_in, bool full, const float* W_so2, void* ws, So2Call* call, hipStream_t st) {
+  const int lmax = ctx->desc.lmax, E = ctx->desc.channels;
+  for (int m = 0; m < 5; ++m) { call->b.A[m] = call->b.Y[m] = nullptr; call->b.K[m] = call->b.N[m] = 0; call->T[m] = nullptr; }
+  call->alpha = nullptr;
+  so2_ws(ctx, g->n_edges, full, true, (char*)ws, &call->rhat_d, &call->b, call->T, &call->alpha);
+  const long n = g->n_edges;
+  if (n == 0) return EGNN_OK;
+  int rc;
+  if ((rc = egnn_launch_geometry(ctx, g, pos, box, call->rhat_d, nullptr, nullptr, nullptr, st))) return rc;
+  const float4* rd = reinterpret_cast<const float4*>(call->rhat_d);
+  const int per_wg = 256 / E;
+  dim3 grid((unsigned)((n + per_wg - 1) / per_wg)), block(256);
+#define GATHER(L)                                                                                                      \
+  do {                                                                                                                 \
+    if (full)                                                                                                          \
+      hipLaunchKernelGGL((so2_gather_kernel<L, true>), grid, block, 0, st, g->src, g->dst, rd, x, edge_in, call->b, n, \
+                         ctx->log2_channels, ctx->desc.n_rbf, ctx->desc.r_cut);                                        \
+    else                                                                                                               \
+      hipLaunchKernelGGL((so2_gather_kernel<L, false>), grid, block, 0, st, g->src, g->dst, rd, x, edge_in, call->b, n, \
+                         ctx->log2_channels, ctx->desc.n_rbf, ctx->desc.r_cut);                                        \
+  } while (0)
+  switch (lmax) {
+    case 0: GATHER(0); break;
+    case 1: GATHER(1); break;
+    case 2: GATHER(2); break;
+    case 3: GATHER(3); break;
+    default: GATHER(4); break;
+  }
+#undef GATHER
+  EGNN_LAUNCH_CHECK(ctx, "so2_gather_kernel");
+  const size_t lds = (size_t)2 * 64 * RB_BROW4 * sizeof(uint4) + (size_t)RB_WAVES * 32 * SO2_AROW * sizeof(float);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(so2_gemm_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(so2_gemm_kernel)");
+  for (int m = 0; m <= lmax; ++m) {
+    const int K = call->b.K[m], N = call->b.N[m], n_steps = so2_steps(K), n_ct = so2_tiles(N);
+    const long total = (long)n_ct * n_steps * 64 * 32;
+    hipLaunchKernelGGL(so2_pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       W_so2 + so2_w_offset(lmax, E, m), call->T[m], m, lmax, E, K, N, n_steps, n_ct, full);
+    EGNN_LAUNCH_CHECK(ctx, "so2_pack_kernel");
+    const long rows_per_wg = 64L * RB_WAVES;
+    const int n_row_blocks = (int)((n + rows_per_wg - 1) / rows_per_wg);
+    const unsigned grid_x = (unsigned)(((n_row_blocks + 7) / 8) * 8 * n_ct);
+    hipLaunchKernelGGL(so2_gemm_kernel, dim3(grid_x), dim3(RB_THREADS), lds, st, call->b.A[m], n, K, call->T[m], n_steps,
+                       call->b.Y[m], N, n_ct, n_row_blocks);
+    EGNN_LAUNCH_CHECK(ctx, "so2_gemm_kernel");
+  }
+  return EGNN_OK;
+}
+
+static int so2_scatter(egnn_ctx* ctx, const egnn_graph* g, const So2Call& call, const float* alpha, float scale, float* a,
+                       hipStream_t st) {
+  if (g->n_owned == 0) return EGNN_OK;
+  const int per_xcd = (g->n_owned + 7) / 8;
+  const float4* rd = reinterpret_cast<const float4*>(call.rhat_d);
+#define SCATTER(L)                                                                                                  \
+  hipLaunchKernelGGL(so2_scatter_kernel<L>, dim3(per_xcd * 8), dim3(256), 0, st, g->row_ptr, rd, call.b, alpha, a,    \
+                     g->n_owned, ctx->log2_channels, per_xcd, scale, ctx->desc.r_cut)
+  switch (ctx->desc.lmax) {
+    case 0: SCATTER(0); break;
+    case 1: SCATTER(1); break;
+    case 2: SCATTER(2); break;
+    case 3: SCATTER(3); break;
+    default: SCATTER(4); break;
+  }
+#undef SCATTER
+  EGNN_LAUNCH_CHECK(ctx, "so2_scatter_kernel");
   return EGNN_OK;
 }
 
@@ -331,76 +597,94 @@ extern "C" int egnn_so2_message_sum(egnn_ctx* ctx, const egnn_graph* g, const fl
                                     const float* x, const float* W_e, const float* W_so2, float* a, void* ws,
                                     size_t ws_bytes, void* stream) {
   if (!ctx) return EGNN_EINVAL;
-  if (!g || !pos || !box || !x || !W_e || !W_so2 || !a || !ws)
-    return egnn_fail(ctx, EGNN_EINVAL, "so2_message_sum: null pointer");
-  if (g->n_edges < 0 || g->n_edges > 2147483647LL || g->n_owned < 0 || g->n_total < g->n_owned || !g->row_ptr ||
-      (g->n_edges > 0 && (!g->src || !g->dst)))
-    return egnn_fail(ctx, EGNN_EINVAL, "so2_message_sum: bad graph");
-  if (((uintptr_t)ws & 255) != 0) return egnn_fail(ctx, EGNN_EINVAL, "so2_message_sum: workspace not 256-byte aligned");
-  const int lmax = ctx->desc.lmax, E = ctx->desc.channels;
-  if (E < 8 || ctx->desc.n_rbf < 2) return egnn_fail(ctx, EGNN_EINVAL, "so2_message_sum: needs >= 8 channels and >= 2 radial bases");
-  if (ws_bytes < so2_ws(ctx, g->n_edges, false, nullptr, nullptr, nullptr, nullptr))
-    return egnn_fail(ctx, EGNN_EWS, "so2_message_sum: workspace too small");
+  if (!pos || !box || !x || !W_e || !W_so2 || !a) return egnn_fail(ctx, EGNN_EINVAL, "so2_message_sum: null pointer");
+  int rc = so2_check(ctx, g, ws, ws_bytes, false, "so2_message_sum");
+  if (rc) return rc;
   hipStream_t st = (hipStream_t)stream;
-  float* rhat_d;
-  So2Bufs b;
-  uint16_t* T[5];
-  for (int m = 0; m < 5; ++m) { b.A[m] = b.Y[m] = nullptr; b.K[m] = b.N[m] = 0; T[m] = nullptr; }
-  so2_ws(ctx, g->n_edges, true, (char*)ws, &rhat_d, &b, T);
+  So2Call call;
+  if ((rc = so2_transform(ctx, g, pos, box, x, W_e, false, W_so2, ws, &call, st))) return rc;
+  return so2_scatter(ctx, g, call, nullptr, 1.0f / sqrtf(ctx->desc.agg_norm), a, st);
+}
+
+extern "C" int egnn_edge_embed_init(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
+                                    const float* W_e, float* T_edge, void* ws, size_t ws_bytes, void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  if (!pos || !box || !W_e) return egnn_fail(ctx, EGNN_EINVAL, "edge_embed_init: null pointer");
+  int rc = so2_check(ctx, g, ws, ws_bytes, true, "edge_embed_init");
+  if (rc) return rc;
   const long n = g->n_edges;
-  int rc;
-  if (n > 0) {
-    if ((rc = egnn_launch_geometry(ctx, g, pos, box, rhat_d, nullptr, nullptr, nullptr, st))) return rc;
-    const float4* rd = reinterpret_cast<const float4*>(rhat_d);
-    const int per_wg = 256 / E;
-    dim3 grid((unsigned)((n + per_wg - 1) / per_wg)), block(256);
-#define GATHER(L)                                                                                                    \
-  hipLaunchKernelGGL(so2_gather_kernel<L>, grid, block, 0, st, g->src, g->dst, rd, x, W_e, b, n, ctx->log2_channels, \
-                     ctx->desc.n_rbf, ctx->desc.r_cut)
-    switch (lmax) {
-      case 0: GATHER(0); break;
-      case 1: GATHER(1); break;
-      case 2: GATHER(2); break;
-      case 3: GATHER(3); break;
-      case 4: GATHER(4); break;
-      default: return egnn_fail(ctx, EGNN_EINVAL, "so2_message_sum: lmax out of range");
-    }
-#undef GATHER
-    EGNN_LAUNCH_CHECK(ctx, "so2_gather_kernel");
-    const size_t lds = (size_t)2 * 64 * RB_BROW4 * sizeof(uint4) + (size_t)RB_WAVES * 32 * SO2_AROW * sizeof(float);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(so2_gemm_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(so2_gemm_kernel)");
-    for (int m = 0; m <= lmax; ++m) {
-      const int K = b.K[m], N = b.N[m], n_steps = so2_steps(K), n_ct = so2_tiles(N);
-      const long total = (long)n_ct * n_steps * 64 * 32;
-      hipLaunchKernelGGL(so2_pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                         W_so2 + so2_w_offset(lmax, E, m), T[m], m, lmax, E, K, N, n_steps, n_ct);
-      EGNN_LAUNCH_CHECK(ctx, "so2_pack_kernel");
-      const long rows_per_wg = 64L * RB_WAVES;
-      const int n_row_blocks = (int)((n + rows_per_wg - 1) / rows_per_wg);
-      const unsigned grid_x = (unsigned)(((n_row_blocks + 7) / 8) * 8 * n_ct);
-      hipLaunchKernelGGL(so2_gemm_kernel, dim3(grid_x), dim3(RB_THREADS), lds, st, b.A[m], n, K, T[m], n_steps, b.Y[m], N,
-                         n_ct, n_row_blocks);
-      EGNN_LAUNCH_CHECK(ctx, "so2_gemm_kernel");
-    }
-  }
+  if (n == 0) return EGNN_OK;
+  if (!T_edge) return egnn_fail(ctx, EGNN_EINVAL, "edge_embed_init: null pointer");
+  hipStream_t st = (hipStream_t)stream;
+  float* rhat_d = (float*)ws;
+  if ((rc = egnn_launch_geometry(ctx, g, pos, box, rhat_d, nullptr, nullptr, nullptr, st))) return rc;
+  const int E = ctx->desc.channels, per_wg = 256 / E, D = (ctx->desc.lmax + 1) * (ctx->desc.lmax + 1);
+  hipLaunchKernelGGL(so2_edge_init_kernel, dim3((unsigned)((n + per_wg - 1) / per_wg)), dim3(256), 0, st,
+                     reinterpret_cast<const float4*>(rhat_d), W_e, T_edge, n, D, ctx->log2_channels, ctx->desc.n_rbf,
+                     ctx->desc.r_cut);
+  EGNN_LAUNCH_CHECK(ctx, "so2_edge_init_kernel");
+  return EGNN_OK;
+}
+
+extern "C" int egnn_so2_node_block(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
+                                   const float* x, const float* T_edge, const float* W_so2, const float* w_att, float* a,
+                                   void* ws, size_t ws_bytes, void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  if (!pos || !box || !x || !W_so2 || !w_att || !a) return egnn_fail(ctx, EGNN_EINVAL, "so2_node_block: null pointer");
+  int rc = so2_check(ctx, g, ws, ws_bytes, true, "so2_node_block");
+  if (rc) return rc;
+  if (g->n_edges > 0 && !T_edge) return egnn_fail(ctx, EGNN_EINVAL, "so2_node_block: null edge embeddings");
+  hipStream_t st = (hipStream_t)stream;
+  So2Call call;
+  if ((rc = so2_transform(ctx, g, pos, box, x, T_edge, true, W_so2, ws, &call, st))) return rc;
   if (g->n_owned == 0) return EGNN_OK;
-  const int per_xcd = (g->n_owned + 7) / 8;
-  const float scale = 1.0f / sqrtf(ctx->desc.agg_norm);
-  const float4* rd = reinterpret_cast<const float4*>(rhat_d);
-#define SCATTER(L)                                                                                               \
-  hipLaunchKernelGGL(so2_scatter_kernel<L>, dim3(per_xcd * 8), dim3(256), 0, st, g->row_ptr, rd, b, a, g->n_owned, \
-                     ctx->log2_channels, per_xcd, scale, ctx->desc.r_cut)
-  switch (lmax) {
-    case 0: SCATTER(0); break;
-    case 1: SCATTER(1); break;
-    case 2: SCATTER(2); break;
-    case 3: SCATTER(3); break;
-    case 4: SCATTER(4); break;
-    default: return egnn_fail(ctx, EGNN_EINVAL, "so2_message_sum: lmax out of range");
+  if (g->n_edges > 0) {
+    hipLaunchKernelGGL(so2_attention_kernel, dim3((g->n_owned + 3) / 4), dim3(256), 0, st, g->row_ptr, call.b.Y[0],
+                       call.b.N[0], w_att, call.alpha, g->n_owned, ctx->desc.channels);
+    EGNN_LAUNCH_CHECK(ctx, "so2_attention_kernel");
   }
-#undef SCATTER
-  EGNN_LAUNCH_CHECK(ctx, "so2_scatter_kernel");
+  return so2_scatter(ctx, g, call, call.alpha, 1.0f, a, st);
+}
+
+extern "C" int egnn_so2_edge_block(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
+                                   const float* x, const float* T_edge_in, const float* W_so2, float* T_edge_out,
+                                   void* ws, size_t ws_bytes, void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  if (!pos || !box || !x || !W_so2) return egnn_fail(ctx, EGNN_EINVAL, "so2_edge_block: null pointer");
+  int rc = so2_check(ctx, g, ws, ws_bytes, true, "so2_edge_block");
+  if (rc) return rc;
+  const long n = g->n_edges;
+  if (n == 0) return EGNN_OK;
+  if (!T_edge_in || !T_edge_out) return egnn_fail(ctx, EGNN_EINVAL, "so2_edge_block: null edge embeddings");
+  hipStream_t st = (hipStream_t)stream;
+  So2Call call;
+  if ((rc = so2_transform(ctx, g, pos, box, x, T_edge_in, true, W_so2, ws, &call, st))) return rc;
+  const float4* rd = reinterpret_cast<const float4*>(call.rhat_d);
+  const int per_wg = 256 / ctx->desc.channels;
+  dim3 grid((unsigned)((n + per_wg - 1) / per_wg)), block(256);
+#define UPDATE(L)                                                                                              \
+  hipLaunchKernelGGL(so2_edge_update_kernel<L>, grid, block, 0, st, rd, call.b, T_edge_in, T_edge_out, n,        \
+                     ctx->log2_channels, ctx->desc.r_cut)
+  switch (ctx->desc.lmax) {
+    case 0: UPDATE(0); break;
+    case 1: UPDATE(1); break;
+    case 2: UPDATE(2); break;
+    case 3: UPDATE(3); break;
+    default: UPDATE(4); break;
+  }
+#undef UPDATE
+  EGNN_LAUNCH_CHECK(ctx, "so2_edge_update_kernel");
+  return EGNN_OK;
+}
+
+extern "C" int egnn_gate(egnn_ctx* ctx, const float* x, const float* W_g, float* y, int32_t n_nodes, void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  if (n_nodes < 0 || (n_nodes > 0 && (!x || !y || (ctx->desc.lmax > 0 && !W_g))))
+    return egnn_fail(ctx, EGNN_EINVAL, "gate: bad argument");
+  if (ctx->desc.channels > 128 || ctx->desc.lmax > 4) return egnn_fail(ctx, EGNN_EINVAL, "gate: unsupported shape");
+  if (n_nodes == 0) return EGNN_OK;
+  hipLaunchKernelGGL(so2_gate_kernel, dim3(n_nodes), dim3(256), 0, (hipStream_t)stream, x, W_g, y, ctx->desc.lmax,
+                     ctx->log2_channels);
+  EGNN_LAUNCH_CHECK(ctx, "so2_gate_kernel");
   return EGNN_OK;
 }

@@ -10,6 +10,7 @@ chunks; each chunk goes through the oracle's own functions unchanged.
     python tests/golden/make_golden.py 3 4 5
     python tests/golden/make_golden.py so2:3 so2:4      (SO(2) message sums at sampled nodes)
     python tests/golden/make_golden.py w16:3 w16:4      (first layer and readout with half-precision path weights)
+    python tests/golden/make_golden.py blocks:3 blocks:4  (node block and edge block with full message content)
 """
 import os
 import sys
@@ -88,6 +89,43 @@ def make_so2(index, pool_size):
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"config{index}_so2_samples.npz")
     np.savez_compressed(path, nodes=nodes, rows=rows, agg=agg, n_edges=len(g[0]))
     print(f"config {index} so2: wrote {path}, max|a| over samples {np.abs(rows).max():.4f}, {time.time() - t0:.0f} s", flush=True)
+
+
+def _blocks_nodes(nodes):
+    from oracle import so2_oracle as S
+    w, g, x, T, Wn, w_att = (_state[k] for k in ("w", "g", "x", "T", "Wn", "w_att"))
+    return S.so2_node_block(g, w.pos, w.box, x, T, Wn[1], Wn[2], Wn[3], w_att, w.lmax, w.channels, w.r_cut, nodes=nodes)
+
+
+def _blocks_edges(edges):
+    from oracle import so2_oracle as S
+    w, g, x, T, We = (_state[k] for k in ("w", "g", "x", "T", "We"))
+    return np.concatenate([S.so2_edge_block(g, w.pos, w.box, x, T, We[1], We[2], We[3], w.lmax, w.channels, w.r_cut,
+                                            k_range=(int(k), int(k) + 1)) for k in edges])
+
+
+def make_blocks(index, pool_size):
+    """Node block at sampled owned nodes and edge block at sampled edges of the full-size configuration, inputs from
+    tests/test_gpu_so2_blocks.block_inputs -> config{index}_so2_blocks_samples.npz."""
+    from tests.test_gpu_so2_blocks import block_inputs
+    t0 = time.time()
+    w = synth.workload(index)
+    g, x, T, Wn, We, w_att = block_inputs(w)
+    rng = np.random.default_rng([w.seed, 4245])
+    nodes = np.sort(rng.choice(w.n_owned, N_NODE_SAMPLES, replace=False))
+    edges = np.sort(rng.choice(len(g[0]), N_EDGE_SAMPLES, replace=False))
+    _state.update(w=w, g=g, x=x, T=T, Wn=Wn, We=We, w_att=w_att)
+    with ProcessPoolExecutor(pool_size) as ex:
+        a_parts = list(ex.map(_blocks_nodes, [nodes[i::pool_size] for i in range(pool_size)]))
+        t_parts = list(ex.map(_blocks_edges, [edges[i::pool_size] for i in range(pool_size)]))
+    a_rows = np.zeros((N_NODE_SAMPLES,) + a_parts[0].shape[1:])
+    T_rows = np.zeros((N_EDGE_SAMPLES,) + t_parts[0].shape[1:])
+    for i in range(pool_size):
+        a_rows[i::pool_size] = a_parts[i]
+        T_rows[i::pool_size] = t_parts[i]
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"config{index}_so2_blocks_samples.npz")
+    np.savez_compressed(path, nodes=nodes, edges=edges, a_rows=a_rows, T_rows=T_rows, n_edges=len(g[0]))
+    print(f"config {index} blocks: wrote {path}, max|a| {np.abs(a_rows).max():.4f}, {time.time() - t0:.0f} s", flush=True)
 
 
 def _w16_node(j):
@@ -283,6 +321,8 @@ if __name__ == "__main__":
             make_so2(int(a[4:]), procs)
         if a.startswith("w16:"):
             make_w16(int(a[4:]), procs)
+        if a.startswith("blocks:"):
+            make_blocks(int(a[7:]), procs)
     for idx in which:
         if idx in (1, 5):          # training step (1 = small self-check of this script against the oracle's own chain)
             make_training(idx, procs)

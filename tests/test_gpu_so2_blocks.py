@@ -1,0 +1,142 @@
+"""GPU parity of the node block, the edge block, the initial edge embeddings and the gate (full message content:
+persistent edge embeddings, attention-weighted sum) against oracle/so2_oracle.py."""
+import os
+import numpy as np
+import pytest
+
+from oracle import egnn_oracle as O
+from oracle import so2_oracle as S
+from paper_2507_03840_amd import synth
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+TOL = U.TOL
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2507_03840_amd import binding
+    binding.load_library()
+    return binding
+
+
+def block_inputs(w, seed=0):
+    """Seeded inputs of both sides: node features, edge embeddings with every plane filled, SO(2) weights of the node
+    and of the edge block, attention vector."""
+    g = U.oracle_graph(w)
+    rng = np.random.default_rng([w.seed if getattr(w, "seed", 0) else 0, 17, seed])
+    x = synth.node_features(rng, w.n_total, w.lmax, w.channels)
+    # (drawn in fp32 directly: at config 4 this tensor has 3.8e9 entries)
+    T = rng.standard_normal(size=(len(g[0]), (w.lmax + 1) ** 2, w.channels), dtype=np.float32)
+    Wn = synth.so2_weights(rng, w.lmax, w.channels, w.n_rbf)
+    We = synth.so2_weights(rng, w.lmax, w.channels, w.n_rbf)
+    w_att = synth.normal(rng, (w.channels,), 2.0 / np.sqrt(w.channels))
+    return g, x, T, Wn, We, w_att
+
+
+def run_blocks(B, w, seed=0):
+    import torch
+    g, x, T, Wn, We, w_att = block_inputs(w, seed)
+    m = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, 1.0)
+    pos = B.to_device(w.pos)
+    graph = m.egnn_nlist(pos, w.n_owned, w.box, w.pbc)
+    assert np.array_equal(graph.src.cpu().numpy(), g[0])
+    ws = torch.empty(m.egnn_so2_blocks_workspace_bytes(graph.n_edges), dtype=torch.uint8, device="cuda")
+    xd, Td = B.to_device(x), B.to_device(T)
+    a = m.egnn_so2_node_block(graph, pos, w.box, xd, Td, B.to_device(S.so2_pack(*Wn[1:])), B.to_device(w_att), ws)
+    T2 = m.egnn_so2_edge_block(graph, pos, w.box, xd, Td, B.to_device(S.so2_pack(*We[1:])), ws)
+    return g, x, T, Wn, We, w_att, a.cpu().numpy(), T2.cpu().numpy()
+
+
+@pytest.mark.parametrize("lmax,E,periodic,n,n_owned,r_cut", [
+    (0, 8, False, 40, 40, 4.0), (1, 16, True, 120, 120, 4.0), (2, 32, False, 100, 60, 4.0), (3, 8, True, 150, 90, 4.0),
+    (4, 16, False, 70, 70, 4.0), (4, 32, False, 90, 50, 4.0), (2, 64, False, 60, 40, 4.0),
+    (3, 16, False, 330, 12, 9.5), (1, 128, False, 40, 25, 4.0)])
+def test_node_and_edge_block_small(B, lmax, E, periodic, n, n_owned, r_cut):
+    print("case", lmax, E, periodic, n, n_owned, r_cut, flush=True)
+    w = synth.small_cluster(n, n_owned, lmax, E, 6, r_cut, 150 + lmax, periodic)
+    g, x, T, Wn, We, w_att, a, T2 = run_blocks(B, w)
+    ref_a = S.so2_node_block(g, w.pos, w.box, x, T, Wn[1], Wn[2], Wn[3], w_att, lmax, E, r_cut)
+    ref_T = S.so2_edge_block(g, w.pos, w.box, x, T, We[1], We[2], We[3], lmax, E, r_cut)
+    ea, eT = U.rel_err(a, ref_a), U.rel_err(T2, ref_T)
+    # the update itself (T' - T), not hidden behind the size of T
+    eU = np.abs((T2 - T) - (ref_T - T)).max() / np.abs(ref_T - T).max()
+    print(f"  {len(g[0])} edges: node block {ea:.2e}, edge block {eT:.2e} (update alone {eU:.2e})", flush=True)
+    assert np.abs(ref_a).max() > 1e-2 and ea < TOL and eT < TOL and eU < TOL
+
+
+def test_blocks_config1_and_attention_is_not_uniform(B):
+    w = synth.workload(1)
+    g, x, T, Wn, We, w_att, a, T2 = run_blocks(B, w)
+    ref_a = S.so2_node_block(g, w.pos, w.box, x, T, Wn[1], Wn[2], Wn[3], w_att, w.lmax, w.channels, w.r_cut)
+    uni = S.so2_node_block(g, w.pos, w.box, x, T, Wn[1], Wn[2], Wn[3], 0 * w_att, w.lmax, w.channels, w.r_cut)
+    assert U.rel_err(a, ref_a) < TOL
+    assert U.rel_err(uni, ref_a) > 0.05          # the weights matter: a kernel that ignored them would fail above
+    ref_T = S.so2_edge_block(g, w.pos, w.box, x, T, We[1], We[2], We[3], w.lmax, w.channels, w.r_cut)
+    assert U.rel_err(T2, ref_T) < TOL
+
+
+@pytest.mark.parametrize("lmax,E,n", [(2, 16, 80), (4, 32, 60), (0, 8, 30)])
+def test_edge_embed_init(B, lmax, E, n):
+    import torch
+    w = synth.small_cluster(n, n, lmax, E, 7, 4.0, 160 + lmax)
+    g = U.oracle_graph(w)
+    rng = np.random.default_rng(5)
+    W_e = synth.normal(rng, (E, 7), 7 ** -0.5)
+    m = B.Egnn(lmax, E, 7, 4.0, 1.0)
+    pos = B.to_device(w.pos)
+    graph = m.egnn_nlist(pos, n, w.box, w.pbc)
+    ws = torch.empty(m.egnn_so2_blocks_workspace_bytes(graph.n_edges), dtype=torch.uint8, device="cuda")
+    T = m.egnn_edge_embed_init(graph, pos, w.box, B.to_device(W_e), ws).cpu().numpy()
+    r = O.edge_vectors(w.pos, w.box, g[0], g[1], g[2])
+    ref = S.edge_embedding_init(np.sqrt((r * r).sum(axis=1)), W_e, lmax, E, 7, 4.0)
+    assert np.all(T[:, 1:, :] == 0) and U.rel_err(T, ref) < 1e-5
+
+
+@pytest.mark.parametrize("lmax,E,n", [(0, 8, 10), (1, 16, 33), (3, 32, 200), (4, 64, 50), (4, 128, 7)])
+def test_gate(B, lmax, E, n):
+    rng = np.random.default_rng([6, lmax, E])
+    x = synth.node_features(rng, n, lmax, E)
+    W_g = synth.normal(rng, (max(lmax, 1), E, E), E ** -0.5)
+    m = B.Egnn(lmax, E, 6, 4.0, 1.0)
+    y = m.egnn_gate(B.to_device(x), B.to_device(W_g)).cpu().numpy()
+    assert U.rel_err(y, S.gate(x, W_g, lmax)) < 1e-5
+
+
+def test_blocks_empty_graph_and_errors(B):
+    import torch
+    w = synth.small_cluster(5, 5, 2, 8, 6, 0.5, 3)
+    g, x, T, Wn, We, w_att, a, T2 = run_blocks(B, w)
+    assert len(g[0]) == 0 and a.shape == (5, 9, 8) and np.all(a == 0) and T2.shape == (0, 9, 8)
+    m = B.Egnn(2, 8, 6, 4.0, 1.0)
+    w2 = synth.small_cluster(30, 30, 2, 8, 6, 4.0, 4)
+    pos = B.to_device(w2.pos)
+    graph = m.egnn_nlist(pos, 30, w2.box, w2.pbc)
+    x = torch.zeros((30, 9, 8), device="cuda")
+    Td = torch.zeros((graph.n_edges, 9, 8), device="cuda")
+    Wf = torch.zeros(m.egnn_so2_weight_count(), device="cuda")
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.EgnnError) as err:
+        m.egnn_so2_node_block(graph, pos, w2.box, x, Td, Wf, torch.zeros(8, device="cuda"), small)
+    assert err.value.code == -3
+    with pytest.raises(B.EgnnError):
+        m.egnn_so2_edge_block(graph, pos, w2.box, x, Td, Wf, small)
+
+
+@pytest.mark.parametrize("index", [3, 4])
+def test_blocks_fullsize_sampled(B, index):
+    """Full-size configurations against stored oracle rows (tests/golden/make_golden.py blocks:N)."""
+    import torch
+    path = os.path.join(GOLDEN, f"config{index}_so2_blocks_samples.npz")
+    assert os.path.exists(path), f"run tests/golden/make_golden.py blocks:{index}"
+    gold = np.load(path)
+    w = synth.workload(index)
+    g, x, T, Wn, We, w_att, a, T2 = run_blocks(B, w)
+    assert len(g[0]) == int(gold["n_edges"])
+    ea = np.abs(a[gold["nodes"]] - gold["a_rows"]).max() / np.abs(gold["a_rows"]).max()
+    upd = T2[gold["edges"]] - T[gold["edges"]]
+    ref_upd = gold["T_rows"] - T[gold["edges"]]
+    eT = np.abs(upd - ref_upd).max() / np.abs(ref_upd).max()
+    print(f"config {index}: node block {ea:.2e}, edge update {eT:.2e}", flush=True)
+    assert ea < TOL and eT < TOL
