@@ -67,6 +67,12 @@ def cpu_baseline(w, wt, g, agg, n_nodes):
                        f"workload, {dt:.1f} s, numpy fp64, 1 thread")
 
 
+def _so2_flat(ws):
+    """(W_e, W0, Wr, Wi) -> [W0, Wr_1, Wi_1, ...] in the order of the C ABI."""
+    W_e, W0, Wr, Wi = ws
+    return [W0] + [a for pair in zip(Wr, Wi) for a in pair]
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -246,6 +252,30 @@ def main():
                    workspace_GB=ws2.numel() / 1e9,
                    note="gather+rotate, five split-bf16 GEMMs (six bf16 products per fp32 product), rotate back + segmented sum")
         del ws2
+        # the same transform with the full message content: persistent edge embeddings, attention-weighted node block,
+        # gate, edge block (one layer in the shape the paper describes)
+        ws3 = torch.empty(m.egnn_so2_blocks_workspace_bytes(n_edges), dtype=torch.uint8, device="cuda")
+        rng_b = np.random.default_rng([w.seed, 778])
+        Wn = B.to_device(np.concatenate([a.ravel() for a in _so2_flat(synth.so2_weights(rng_b, w.lmax, w.channels, w.n_rbf))]))
+        Wed = B.to_device(np.concatenate([a.ravel() for a in _so2_flat(synth.so2_weights(rng_b, w.lmax, w.channels, w.n_rbf))]))
+        w_att = B.to_device(synth.normal(rng_b, (w.channels,), 2.0 / np.sqrt(w.channels)))
+        W_g = B.to_device(synth.normal(rng_b, (max(1, w.lmax), w.channels, w.channels), w.channels ** -0.5))
+        T_edge = m.egnn_edge_embed_init(graph, pos, w.box, We, ws3)
+        xb = x0.clone()
+        t_node = timed(lambda: m.egnn_so2_node_block(graph, pos, w.box, xb, T_edge, Wn, w_att, ws3, out=x_out[0]), 3)
+        t_gate = timed(lambda: m.egnn_gate(x_out[0], W_g, out=x_out[1]), 3)
+        t_edge = timed(lambda: m.egnn_so2_edge_block(graph, pos, w.box, xb, T_edge, Wed, ws3, out=T_edge), 3)
+        macs_full = sum((1 if q == 0 else 4) * ((L_ + 1 - q) * E_) * ((L_ + 1 - q) * 3 * E_) for q in range(L_ + 1))
+        so2["full_content"] = dict(node_block_ms=t_node, gate_ms=t_gate, edge_block_ms=t_edge,
+                                   layer_ms=t_node + t_gate + t_edge,
+                                   messages_per_s=2 * n_edges / (t_node + t_edge) * 1e3,
+                                   floats_per_message=3 * (L_ + 1) ** 2 * E_, flop_per_message=2 * macs_full,
+                                   bf16_mfma_TFLOPs=6 * 2 * macs_full * n_edges * 2 / (t_node + t_edge) / 1e9,
+                                   workspace_GB=ws3.numel() / 1e9, edge_embeddings_GB=T_edge.numel() * 4 / 1e9,
+                                   note="node block = gather (3 x 25 x E floats per message) + GEMMs + attention + "
+                                        "weighted segmented sum; edge block = the same transform with its own weights, "
+                                        "then T_edge += f_c y")
+        del ws3, T_edge, xb
 
     # ---- assembly of the predicted Hamiltonian from the blocks of this step: on-site blocks, padding for two species
     #      with 10 and 4 of the 13 orbitals, L1+L2 loss, column-compressed matrix ----
