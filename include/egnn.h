@@ -309,6 +309,30 @@ int egnn_hamiltonian_fill(egnn_ctx* ctx, const egnn_graph* g, const int32_t* spe
                           int32_t n_species, const int32_t* orb_off, const void* plan, size_t plan_bytes,
                           const float* H_edge, const float* H_node, int32_t* row_idx, float* values, void* stream);
 
+/* ---- Low-NN partitioner (Sec. 4.4; Appendix A, Algorithm 1) and pack / unpack of halo rows (Sec. 4.3, Fig. 4(b)) ----
+ * egnn_partition_low_nn: HOST function, all pointers are host pointers; needs no context and no GPU.  Recursive
+ *   bisection of n_atoms atoms into 2^levels parts: a dimension that has no cut yet is first "opened" at its balanced
+ *   position (one cut through a periodic ring divides nothing, it fixes the origin; non-periodic dimensions start
+ *   opened at their smallest coordinate); then, at every level, NN[d] = 1 for a dimension with one cut and
+ *   ceil(2 r_cut / L[d]) otherwise (L = extent of the sub-domain), the dimension with the lowest NN is cut (the highest
+ *   index among equals) at the position that splits the atoms, ordered along it, into the two groups whose summed
+ *   degree differs least (fewest atoms on the left among equals; atoms at equal coordinate keep their order of
+ *   arrival), and both halves are cut further with their own copy of the cut counts.
+ *   pos [n_atoms][3], degree [n_atoms] (edges of each atom), box / pbc [3], part [n_atoms] out: 0 .. 2^levels - 1 in
+ *   the order the parts are finished (left before right).  cut_log (may be NULL): [2^levels - 1][4] = (level,
+ *   dimension, atoms in the sub-domain, atoms on the left) for every bisection in depth-first order; n_cuts (may be
+ *   NULL): how many were made (empty sub-domains make none).  levels <= 20.
+ * egnn_pack_rows: out[r] = x[idx[r]] for r < n_idx (rows of (lmax+1)^2 * channels floats; idx clamped to
+ *   0 .. n_rows_x - 1); half != 0: the buffer holds IEEE half precision (round to nearest even), else fp32.
+ * egnn_unpack_rows: x_full[first_row + r] = buf[r] for r < n_rows (converted back to fp32 if half != 0). */
+int egnn_partition_low_nn(const float* pos, const int32_t* degree, int32_t n_atoms, const float box[3],
+                          const uint8_t pbc[3], double r_cut, int32_t levels, int32_t* part, int32_t* cut_log,
+                          int32_t* n_cuts);
+int egnn_pack_rows(egnn_ctx* ctx, const float* x, int32_t n_rows_x, const int32_t* idx, int32_t n_idx, int32_t half,
+                   void* out, void* stream);
+int egnn_unpack_rows(egnn_ctx* ctx, const void* buf, int32_t n_rows, int32_t half, float* x_full, int32_t first_row,
+                     void* stream);
+
 /* ---- stage timing (measurement aid; follows the paper's protocol of timing the blocks of the forward
  *      pass separately, Sec. 4.4 / Fig. 6(c)) ----
  * egnn_timing_enable(ctx, max_calls > 0) creates HIP events; from then on every egnn_layer_forward /

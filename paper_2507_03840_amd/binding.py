@@ -24,6 +24,7 @@ SYMBOLS = [
     "egnn_so2_message_sum", "egnn_so2_blocks_workspace_bytes", "egnn_edge_embed_init", "egnn_so2_node_block",
     "egnn_so2_edge_block", "egnn_gate", "egnn_hamiltonian_workspace_bytes", "egnn_onsite_hii", "egnn_apply_padding", "egnn_loss_l1l2",
     "egnn_hamiltonian_structure", "egnn_hamiltonian_fill", "egnn_onsite_backward_workspace_bytes", "egnn_onsite_backward",
+    "egnn_partition_low_nn", "egnn_pack_rows", "egnn_unpack_rows",
 ]
 
 
@@ -93,6 +94,25 @@ class Graph:
 
 LAYER_STAGES = ["geometry", "radial_weights", "mix_pre", "tp_segsum", "mix_post"]
 READOUT_STAGES = ["geometry", "radial_weights", "mix_src", "mix_dst", "readout"]
+
+
+def egnn_partition_low_nn(pos, degree, box, pbc, r_cut, levels):
+    """Host call (numpy in, numpy out; no GPU needed): returns (part [n], cut_log [n_cuts][4])."""
+    lib = load_library()
+    pos = np.ascontiguousarray(pos, np.float32)
+    degree = np.ascontiguousarray(degree, np.int32)
+    n = pos.shape[0]
+    part = np.full(n, -1, np.int32)
+    log = np.zeros((max(1, (1 << levels) - 1), 4), np.int32)
+    n_cuts = C.c_int32()
+    pbc3 = (C.c_uint8 * 3)(*[int(v) for v in pbc])
+    lib.egnn_partition_low_nn.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_double,
+                                          C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+    rc = lib.egnn_partition_low_nn(pos.ctypes.data, degree.ctypes.data, n, _f3(box), pbc3, float(r_cut), int(levels),
+                                   part.ctypes.data, log.ctypes.data, C.byref(n_cuts))
+    if rc:
+        raise EgnnError(rc, "egnn_partition_low_nn: bad argument")
+    return part, log[:min(n_cuts.value, log.shape[0])]
 
 
 class Egnn:
@@ -315,6 +335,19 @@ class Egnn:
             _ptr(W["W_r2"]), _ptr(W["V"]), _ptr(H), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
         return H
 
+
+    # ---- halo rows
+    def egnn_pack_rows(self, x, idx, half=False):
+        out = torch.empty((idx.numel(),) + tuple(x.shape[1:]), dtype=torch.float16 if half else torch.float32,
+                          device="cuda")
+        self._check(self.lib.egnn_pack_rows(self.ctx, _ptr(x), x.shape[0], _ptr(idx), idx.numel(), int(half), _ptr(out),
+                                            _stream()))
+        return out
+
+    def egnn_unpack_rows(self, buf, x_full, first_row):
+        self._check(self.lib.egnn_unpack_rows(self.ctx, _ptr(buf), buf.shape[0], int(buf.dtype == torch.float16),
+                                              _ptr(x_full), int(first_row), _stream()))
+        return x_full
 
     # ---- assembly of the predicted Hamiltonian
     def egnn_hamiltonian_workspace_bytes(self, n_edges, n_owned, n_total):
