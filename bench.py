@@ -85,6 +85,8 @@ def main():
                     help="training steps (forward + loss + reverse pass, config 5) timed after the main region; 0 = skip")
     ap.add_argument("--fused", type=int, default=0, choices=[0, 1],
                     help="1: radial weights and messages in one kernel (weights never written to memory)")
+    ap.add_argument("--no-partition", action="store_true",
+                    help="skip the extra timing of the Low-NN partitioner and of the halo pack / unpack")
     ap.add_argument("--no-hamiltonian", action="store_true",
                     help="skip the extra timing of the Hamiltonian assembly (on-site blocks, padding, L1+L2 loss, CSC matrix)")
     ap.add_argument("--no-so2", action="store_true",
@@ -319,6 +321,43 @@ def main():
                         "the zeros written; loss: H, T read, dH written; fill: blocks read once, outputs written once)")
         del vals, rows, target, H_node, hws, plan
 
+    # ---- Low-NN partitioner on the structure tiled 2 x 2 x 2 (the shape of the paper's partitioning example: 24,000
+    #      atoms into 64 parts), and pack / unpack of the halo rows of one part ----
+    lownn = None
+    if not args.no_partition and all(w.pbc):
+        shifts = np.array([[i, j, k] for i in range(2) for j in range(2) for k in range(2)], np.float32)
+        big_pos = np.concatenate([w.pos + sft * w.box for sft in shifts]).astype(np.float32)
+        big_box = (2 * w.box).astype(np.float32)
+        mb = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, 1.0)
+        gb = mb.egnn_nlist(B.to_device(big_pos), len(big_pos), big_box, w.pbc)
+        deg = torch.diff(gb.row_ptr).cpu().numpy().astype(np.int32)
+        t0p = time.perf_counter()
+        part, cut_log = B.egnn_partition_low_nn(big_pos, deg, big_box, w.pbc, w.r_cut, 6)
+        t_part = time.perf_counter() - t0p
+        pt = torch.from_numpy(part.astype(np.int64)).cuda()
+        ps, pd = pt[gb.src.long()], pt[gb.dst.long()]
+        cross = ps != pd
+        pairs = torch.unique(ps[cross] * 64 + pd[cross])
+        n_nb = torch.bincount(pairs % 64, minlength=64).cpu().numpy()
+        dsum = np.bincount(part, weights=deg, minlength=64)
+        # halo of part 0: distinct sources of its incoming edges that it does not own
+        halo_idx = torch.unique(gb.src[(pd == 0) & cross]).to(torch.int32)
+        xb = torch.randn((len(big_pos), m.dim, w.channels), device="cuda")
+        xf = torch.empty((int((pt == 0).sum()) + halo_idx.numel(), m.dim, w.channels), device="cuda")
+        t_pack = timed(lambda: m.egnn_pack_rows(xb, halo_idx, half=True), 5)
+        buf = m.egnn_pack_rows(xb, halo_idx, half=True)
+        t_unpack = timed(lambda: m.egnn_unpack_rows(buf, xf, int((pt == 0).sum())), 5)
+        lownn = dict(atoms=int(len(big_pos)), edges=int(gb.n_edges), parts=64, host_ms=1e3 * t_part,
+                     cut_dimensions_by_level={int(l): sorted({int(e[1]) for e in cut_log if e[0] == l}) for l in range(6, 0, -1)},
+                     degree_sum_max_over_mean=float(dsum.max() / dsum.mean()),
+                     neighbour_parts_min_mean_max=[int(n_nb.min()), float(n_nb.mean()), int(n_nb.max())],
+                     part0_owned=int((pt == 0).sum()), part0_halo_rows=int(halo_idx.numel()),
+                     pack_f16_ms=t_pack, unpack_f16_ms=t_unpack,
+                     pack_GBs=halo_idx.numel() * m.dim * w.channels * 6 / t_pack / 1e6,
+                     note="host code, one core; the paper quotes 1.41 s for 64 parts of its 24,000-atom structure (another "
+                          "machine and implementation: context only)")
+        del xb, xf, buf, gb
+
     # ---- saturation curve: one layer forward into the first n destination nodes ----
     sweep = None
     if args.sweep:
@@ -385,6 +424,8 @@ def main():
         out["so2_message_sum"] = so2
     if ham is not None:
         out["hamiltonian_assembly"] = ham
+    if lownn is not None:
+        out["low_nn_partition"] = lownn
     if sweep is not None:
         out["saturation_sweep"] = sweep
     if not args.no_cpu_baseline:
