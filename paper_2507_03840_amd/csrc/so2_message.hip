@@ -212,6 +212,15 @@ __global__ __launch_bounds__(256) void so2_pack_kernel(const float* __restrict__
 // HBM and then from that L2.  A compute wave owns 64 rows; its 64 x 64 tile of A is fetched in memory order and turned
 // to operand order through a private LDS tile.
 #define SO2_AROW 68
+typedef float so2_f4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void so2_fetch8(so2_f4 (&dst)[8], const float* const (&row)[8], int col) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) dst[i] = *reinterpret_cast<const so2_f4*>(row[i] + col);
+}
+__device__ __forceinline__ void so2_store8(float* tile, const so2_f4 (&v)[8]) {   // rows 4 apart
+#pragma unroll
+  for (int i = 0; i < 8; ++i) *reinterpret_cast<so2_f4*>(tile + 4 * i * SO2_AROW) = v[i];
+}
 __global__ __launch_bounds__(RB_THREADS) void so2_gemm_kernel(const float* __restrict__ A, long M, int K, const uint16_t* __restrict__ T,
                                                               int n_steps, float* __restrict__ C, int N, int n_ct,
                                                               int n_row_blocks) {
@@ -231,15 +240,17 @@ __global__ __launch_bounds__(RB_THREADS) void so2_gemm_kernel(const float* __res
   const int m = lane & 31, hh = lane >> 5;
   const long e_base = ((long)row_block * RB_WAVES + wave) * 64;
   const int frow = lane >> 4, fcol = (lane & 15) * 4;
-  const float* fptr[2][8];
+  // row pointers of the two 32-row blocks (rows past the end repeat the last row; their results are not stored)
+  const float* fptr0[8];
+  const float* fptr1[8];
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      long e = e_base + rb * 32 + 4 * i + frow;
-      if (e >= M) e = M - 1;
-      fptr[rb][i] = A + (size_t)e * K;
-    }
+  for (int i = 0; i < 8; ++i) {
+    long e0 = e_base + 4 * i + frow, e1 = e0 + 32;
+    if (e0 >= M) e0 = M - 1;
+    if (e1 >= M) e1 = M - 1;
+    fptr0[i] = A + (size_t)e0 * K;
+    fptr1[i] = A + (size_t)e1 * K;
+  }
   float16v acc[2][2];
 #pragma unroll
   for (int a = 0; a < 2; ++a)
@@ -247,53 +258,50 @@ __global__ __launch_bounds__(RB_THREADS) void so2_gemm_kernel(const float* __res
     for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
-  // rows of the next step in flight while this one is contracted; columns past the row are clamped here and
-  // zeroed where the value is used (touching it here would make the wave wait for the load it has just issued)
-  float4 nxt[2][8];
-  auto fetch = [&](int s) {
-    const int n = s * 64 + fcol;
-    const int nc = n < K ? n : K - 4;
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-      for (int i = 0; i < 8; ++i) nxt[rb][i] = *reinterpret_cast<const float4*>(fptr[rb][i] + nc);
-  };
-  fetch(0);
+  // The rows of step s + 1 are fetched into the registers of step s as soon as those have been copied to the LDS tile
+  // (row block by row block), so the data is never moved between registers.  Columns past the end of a row are
+  // clamped to the row's last four: the packed weights are zero for contraction indices >= K, and what is read in
+  // their place is finite, so those products vanish.
+  so2_f4 nxt0[8], nxt1[8];
+#define SO2_FETCH(S, NXT, FPTR)                                 \
+  {                                                             \
+    const int n_ = (S) * 64 + fcol;                             \
+    so2_fetch8(NXT, FPTR, n_ < K ? n_ : K - 4);                 \
+  }
+#define SO2_ROW_BLOCK(NXT, FPTR, ACC0, ACC1)                                                                       \
+  {                                                                                                                \
+    so2_store8(sA + frow * SO2_AROW + fcol, NXT);                                                                  \
+    SO2_FETCH(s_next, NXT, FPTR)   /* (the last step fetches itself again: no branch around the loads) */          \
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");                                                \
+    __builtin_amdgcn_wave_barrier();                                                                               \
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");                                                \
+    const float4* arow = reinterpret_cast<const float4*>(sA + m * SO2_AROW + hh * 32);                             \
+    _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                                                \
+      /* both column blocks' pieces of B first: their LDS latency passes while A is cut into pieces */             \
+      const uint4* brow0 = bbase + m * RB_BROW4 + t;                                                               \
+      const uint4* brow1 = brow0 + 32 * RB_BROW4;                                                                  \
+      const uint4 b0[3] = {brow0[0], brow0[8], brow0[16]};                                                         \
+      const uint4 b1[3] = {brow1[0], brow1[8], brow1[16]};                                                         \
+      const float4 u = arow[2 * t], v = arow[2 * t + 1];                                                           \
+      const float xv[8] = {u.x, u.y, u.z, u.w, v.x, v.y, v.z, v.w};                                                \
+      uint4 ah, am, al;                                                                                            \
+      rb_split8(xv, ah, am, al);                                                                                   \
+      rb_mma6x2(ah, am, al, b0, b1, ACC0, ACC1);                                                                   \
+    }                                                                                                              \
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");                                                \
+    __builtin_amdgcn_wave_barrier();                                                                               \
+  }
+  SO2_FETCH(0, nxt0, fptr0)
+  SO2_FETCH(0, nxt1, fptr1)
   for (int s = 0; s < n_steps; ++s) {
-    float4 cur[2][8];
-    const bool col_ok = s * 64 + fcol < K;
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-      for (int i = 0; i < 8; ++i) cur[rb][i] = col_ok ? nxt[rb][i] : make_float4(0.f, 0.f, 0.f, 0.f);
-    if (s + 1 < n_steps) fetch(s + 1);
     rb_barrier_acquire();
     const uint4* bbase = sB + (s & 1) * (64 * RB_BROW4) + hh * 4;
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) *reinterpret_cast<float4*>(sA + (4 * i + frow) * SO2_AROW + fcol) = cur[rb][i];
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
-      const float4* arow = reinterpret_cast<const float4*>(sA + m * SO2_AROW + hh * 32);
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const float4 u = arow[2 * t], v = arow[2 * t + 1];
-        const float xv[8] = {u.x, u.y, u.z, u.w, v.x, v.y, v.z, v.w};
-        uint4 ah, am, al;
-        rb_split8(xv, ah, am, al);
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-          const uint4* brow = bbase + (m + 32 * cb) * RB_BROW4 + t;
-          const uint4 bq[3] = {brow[0], brow[8], brow[16]};
-          acc[rb][cb] = rb_mma6(ah, am, al, bq, acc[rb][cb]);
-        }
-      }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-      __builtin_amdgcn_wave_barrier();
-    }
+    const int s_next = s + 1 < n_steps ? s + 1 : s;
+    SO2_ROW_BLOCK(nxt0, fptr0, acc[0][0], acc[0][1])
+    SO2_ROW_BLOCK(nxt1, fptr1, acc[1][0], acc[1][1])
   }
+#undef SO2_ROW_BLOCK
+#undef SO2_FETCH
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb)
 #pragma unroll

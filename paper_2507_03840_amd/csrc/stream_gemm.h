@@ -67,3 +67,14 @@ __device__ __forceinline__ float16v rb_mma6(uint4 ah, uint4 am, uint4 al, const 
   return acc;
 }
 
+
+// the same for two independent column blocks, the two accumulation chains interleaved (a matrix-core instruction that
+// continues the chain of the one before it has to wait for its result)
+__device__ __forceinline__ void rb_mma6x2(uint4 ah, uint4 am, uint4 al, const uint4 (&b0)[3], const uint4 (&b1)[3],
+                                          float16v& acc0, float16v& acc1) {
+#define RB_STEP(A, P)                                                                                  \
+  acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(A), as_bf16x8(b0[P]), acc0, 0, 0, 0);       \
+  acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(A), as_bf16x8(b1[P]), acc1, 0, 0, 0);
+  RB_STEP(al, 0) RB_STEP(ah, 2) RB_STEP(am, 1) RB_STEP(am, 0) RB_STEP(ah, 1) RB_STEP(ah, 0)
+#undef RB_STEP
+}
