@@ -206,13 +206,16 @@ __global__ __launch_bounds__(256) void so2_pack_kernel(const float* __restrict__
 }
 
 // ---------------------------------------------------------------------------------------------- 3. GEMM
-// C[e][ct*64 + j] = sum_k A[e][k] B[k][ct*64 + j].  A workgroup = (block of 64 * RB_WAVES rows, 64-column tile ct).
+// C[e][ct*64 + j] = sum_k A[e][k] B[k][ct*64 + j].  A workgroup = (block of 64 * SO2_WAVES rows, 64-column tile ct);
+// eight waves that all do the same (two per SIMD: the matrix cores of the four SIMDs carry equal loads).
 // Workgroup ids go round-robin over the 8 XCDs, each with its own L2, so the id is decoded such that the column tiles
 // of one block of rows sit on the same XCD with consecutive dispatch slots: they read the same rows of A, once from
 // HBM and then from that L2.  A compute wave owns 64 rows; its 64 x 64 tile of A is fetched in memory order and turned
 // to operand order through a private LDS tile.
 #define SO2_AROW 68
 typedef float so2_f4 __attribute__((ext_vector_type(4)));
+typedef unsigned int so2_u4 __attribute__((ext_vector_type(4)));
+#define SO2_WAVES 8   // waves per workgroup of the GEMM (RB_THREADS = 512 threads), all alike
 __device__ __forceinline__ void so2_fetch8(so2_f4 (&dst)[8], const float* const (&row)[8], int col) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) dst[i] = *reinterpret_cast<const so2_f4*>(row[i] + col);
@@ -232,13 +235,9 @@ __global__ __launch_bounds__(RB_THREADS) void so2_gemm_kernel(const float* __res
   const int ct = idx % n_ct;
   const int row_block = (idx / n_ct) * 8 + xcd;
   if (row_block >= n_row_blocks) return;   // (whole workgroup: the grid is rounded up to a multiple of 8 row blocks)
-  if (wave == RB_WAVES) {
-    rb_loader(T, (long)ct * n_steps, n_steps, sB, lane);
-    return;
-  }
   float* sA = reinterpret_cast<float*>(sB + 2 * 64 * RB_BROW4) + (size_t)wave * 32 * SO2_AROW;
   const int m = lane & 31, hh = lane >> 5;
-  const long e_base = ((long)row_block * RB_WAVES + wave) * 64;
+  const long e_base = ((long)row_block * SO2_WAVES + wave) * 64;
   const int frow = lane >> 4, fcol = (lane & 15) * 4;
   // row pointers of the two 32-row blocks (rows past the end repeat the last row; their results are not stored)
   const float* fptr0[8];
@@ -291,14 +290,37 @@ __global__ __launch_bounds__(RB_THREADS) void so2_gemm_kernel(const float* __res
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");                                                \
     __builtin_amdgcn_wave_barrier();                                                                               \
   }
+  // The 24 KB block of B of a step is brought in by all eight waves together, three 16-byte pieces per thread: loaded
+  // into registers at the top of step s, written to the other LDS buffer after the step's arithmetic, published by the
+  // barrier that opens step s + 1.  (No wave stores to global memory inside the loop, so these loads cost no waiting.)
+  const uint4* tsrc = reinterpret_cast<const uint4*>(T) + (long)ct * n_steps * (64 * 24);
+  so2_u4 bnext[3];
+#pragma unroll
+  for (int i = 0; i < 3; ++i) bnext[i] = *reinterpret_cast<const so2_u4*>(tsrc + i * RB_THREADS + tid);
+#pragma unroll
+  for (int i = 0; i < 3; ++i) {
+    const int u = i * RB_THREADS + tid, row = u / 24, c16 = u - row * 24;
+    *reinterpret_cast<so2_u4*>(sB + row * RB_BROW4 + c16) = bnext[i];
+  }
   SO2_FETCH(0, nxt0, fptr0)
   SO2_FETCH(0, nxt1, fptr1)
   for (int s = 0; s < n_steps; ++s) {
-    rb_barrier_acquire();
+    rb_release_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
     const uint4* bbase = sB + (s & 1) * (64 * RB_BROW4) + hh * 4;
     const int s_next = s + 1 < n_steps ? s + 1 : s;
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+      bnext[i] = *reinterpret_cast<const so2_u4*>(tsrc + (size_t)s_next * (64 * 24) + i * RB_THREADS + tid);
     SO2_ROW_BLOCK(nxt0, fptr0, acc[0][0], acc[0][1])
     SO2_ROW_BLOCK(nxt1, fptr1, acc[1][0], acc[1][1])
+    // (after the last step this rewrites a buffer that nobody reads any more)
+    uint4* bdst = sB + ((s + 1) & 1) * (64 * RB_BROW4);
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+      const int u = i * RB_THREADS + tid, row = u / 24, c16 = u - row * 24;
+      *reinterpret_cast<so2_u4*>(bdst + row * RB_BROW4 + c16) = bnext[i];
+    }
   }
 #undef SO2_ROW_BLOCK
 #undef SO2_FETCH
@@ -561,7 +583,7 @@ static int so2_transform(egnn_ctx* ctx, const egnn_graph* g, const float* pos, c
   }
 #undef GATHER
   EGNN_LAUNCH_CHECK(ctx, "so2_gather_kernel");
-  const size_t lds = (size_t)2 * 64 * RB_BROW4 * sizeof(uint4) + (size_t)RB_WAVES * 32 * SO2_AROW * sizeof(float);
+  const size_t lds = (size_t)2 * 64 * RB_BROW4 * sizeof(uint4) + (size_t)SO2_WAVES * 32 * SO2_AROW * sizeof(float);
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(so2_gemm_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(so2_gemm_kernel)");
@@ -571,7 +593,7 @@ static int so2_transform(egnn_ctx* ctx, const egnn_graph* g, const float* pos, c
     hipLaunchKernelGGL(so2_pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                        W_so2 + so2_w_offset(lmax, E, m), call->T[m], m, lmax, E, K, N, n_steps, n_ct, full);
     EGNN_LAUNCH_CHECK(ctx, "so2_pack_kernel");
-    const long rows_per_wg = 64L * RB_WAVES;
+    const long rows_per_wg = 64L * SO2_WAVES;
     const int n_row_blocks = (int)((n + rows_per_wg - 1) / rows_per_wg);
     const unsigned grid_x = (unsigned)(((n_row_blocks + 7) / 8) * 8 * n_ct);
     hipLaunchKernelGGL(so2_gemm_kernel, dim3(grid_x), dim3(RB_THREADS), lds, st, call->b.A[m], n, K, call->T[m], n_steps,
