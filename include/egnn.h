@@ -8,9 +8,10 @@
  *   - Every pointer is a DEVICE pointer unless its comment says "host".  The caller owns every
  *     buffer, including the workspace; the library allocates no device memory, keeps no pointer
  *     after a call returns, and enqueues all work on the stream passed in (a hipStream_t, passed
- *     as void*; NULL = the default stream).  egnn_nlist_count (edge count read-back),
- *     egnn_readout_hij, egnn_readout_backward and egnn_onsite_hii (upload of their small index tables) and
- *     egnn_hamiltonian_structure (size read-back) synchronise the stream; nothing else does.
+ *     as void*; NULL = the default stream).  egnn_nlist_count (edge count read-back) and
+ *     egnn_hamiltonian_structure (size read-back) synchronise the stream; nothing else does.  The readout and
+ *     on-site calls upload small index tables from memory owned by the context; egnn_destroy therefore waits for
+ *     the device if such a call has been made.
  *   - Node tensors: float [n_nodes][(lmax+1)^2][channels], channel fastest; the (l, m) axis is
  *     flattened as l*l + l + m, m = -l..l  (Sec. 3 "Initialization": T^node of shape
  *     (l_max+1)^2 x E per atom).
@@ -213,7 +214,7 @@ int egnn_layer_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_p
                         float* dW_r1, float* dW_r2, void* ws, size_t ws_bytes, void* stream);
 
 /* Adjoint of egnn_readout_hij.  dH [n_edges][n_orb][n_orb]; dx [n_total][...]; dV packed like V.
- * Synchronises the stream once (upload of its index tables). */
+ */
 int egnn_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm,
                           const float* pos, const float box[3], const float* x, const float* W_s,
                           const float* W_t, const float* W_r1, const float* W_r2, const float* V,
@@ -274,7 +275,7 @@ int egnn_gate(egnn_ctx* ctx, const float* x, const float* W_g, float* y, int32_t
  *
  * egnn_onsite_hii: H_ii[i][(a,m_a)][(b,m_b)] = sum_{L <= lmax, M} C^{(L,M)}_{(l_a m_a)(l_b m_b)} q_i[o(a,b,L)][M],
  *   q_i[o][M] = sum_c V_node[L][o][c] x[i][(L,M)][c]; V_node packed like V of egnn_readout_hij (rows of degrees above
- *   lmax are not read).  x [n_nodes][(lmax+1)^2][channels].  Synchronises the stream once (table upload).
+ *   lmax are not read).  x [n_nodes][(lmax+1)^2][channels].
  * egnn_apply_padding: sets the padding entries of H to zero in place.
  * egnn_loss_l1l2: loss[0] = mean |H - T| + mean (H - T)^2 over the entries that are not padding, loss[1], loss[2] the
  *   two terms (device, 3 floats); if dH != NULL, dH = (sign(H - T) + 2 (H - T)) / (number of such entries), 0 on padding.
@@ -292,8 +293,7 @@ int egnn_hamiltonian_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, int32
 int egnn_onsite_hii(egnn_ctx* ctx, const float* x, const float* V_node, float* H_ii, int32_t n_nodes,
                     void* ws, size_t ws_bytes, void* stream);
 /* Adjoint of egnn_onsite_hii: dx [n_nodes][(lmax+1)^2][channels] and dV_node (packed like V_node; rows of degrees
- * above lmax are set to zero) from dH_ii; both overwritten.  Nodes are added in a fixed order.  Synchronises the
- * stream once (table upload).  ws: egnn_onsite_backward_workspace_bytes, 256-byte aligned. */
+ * above lmax are set to zero) from dH_ii; both overwritten.  Nodes are added in a fixed order.  ws: egnn_onsite_backward_workspace_bytes, 256-byte aligned. */
 int egnn_onsite_backward_workspace_bytes(const egnn_ctx* ctx, int32_t n_nodes, size_t* bytes);
 int egnn_onsite_backward(egnn_ctx* ctx, const float* x, const float* V_node, const float* dH_ii, float* dx,
                          float* dV_node, int32_t n_nodes, void* ws, size_t ws_bytes, void* stream);

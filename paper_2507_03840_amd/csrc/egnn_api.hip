@@ -112,6 +112,9 @@ extern "C" int egnn_create(const egnn_model_desc* d, egnn_ctx** out) {
 
 extern "C" void egnn_destroy(egnn_ctx* ctx) {
   if (!ctx) return;
+  // uploads of the context's index tables may still be queued: they read host memory that is freed below
+  if (!ctx->tab_ro_i.empty() || !ctx->tab_rob_i.empty() || !ctx->tab_on_i.empty() || !ctx->tab_onb_i.empty())
+    (void)hipDeviceSynchronize();
   for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
   delete ctx;
 }
@@ -401,26 +404,27 @@ extern "C" int egnn_readout_hij(egnn_ctx* ctx, const egnn_graph* g, const float*
 
   // integer table: q_row[nq] q_vrow[nq] slot_L[n_slots] slot_qoff[n_slots] unc_ptr[nq+1] unc_q[nnz]
   const int nq = ctx->n_orb * ctx->n_orb;
-  std::vector<int> ti;
-  ti.reserve(readout_tab_ints(ctx));
-  std::vector<int> q_row(nq), q_vrow(nq);
-  for (int s = 0; s < ctx->n_slots; ++s) {
-    const int L = ctx->slot_L[s];
-    for (int M = 0; M < 2 * L + 1; ++M) {
-      q_row[ctx->slot_qoff[s] + M] = L * L + M;
-      q_vrow[ctx->slot_qoff[s] + M] = ctx->slot_vrow[s];
+  std::vector<int>& ti = ctx->tab_ro_i;
+  if (ti.empty()) {
+    ti.reserve(readout_tab_ints(ctx));
+    std::vector<int> q_row(nq), q_vrow(nq);
+    for (int s = 0; s < ctx->n_slots; ++s) {
+      const int L = ctx->slot_L[s];
+      for (int M = 0; M < 2 * L + 1; ++M) {
+        q_row[ctx->slot_qoff[s] + M] = L * L + M;
+        q_vrow[ctx->slot_qoff[s] + M] = ctx->slot_vrow[s];
+      }
     }
+    ti.insert(ti.end(), q_row.begin(), q_row.end());
+    ti.insert(ti.end(), q_vrow.begin(), q_vrow.end());
+    ti.insert(ti.end(), ctx->slot_L.begin(), ctx->slot_L.end());
+    ti.insert(ti.end(), ctx->slot_qoff.begin(), ctx->slot_qoff.end());
+    ti.insert(ti.end(), ctx->unc_ptr.begin(), ctx->unc_ptr.end());
+    ti.insert(ti.end(), ctx->unc_q.begin(), ctx->unc_q.end());
   }
-  ti.insert(ti.end(), q_row.begin(), q_row.end());
-  ti.insert(ti.end(), q_vrow.begin(), q_vrow.end());
-  ti.insert(ti.end(), ctx->slot_L.begin(), ctx->slot_L.end());
-  ti.insert(ti.end(), ctx->slot_qoff.begin(), ctx->slot_qoff.end());
-  ti.insert(ti.end(), ctx->unc_ptr.begin(), ctx->unc_ptr.end());
-  ti.insert(ti.end(), ctx->unc_q.begin(), ctx->unc_q.end());
+  // (sources owned by the context: no need to wait for the copies)
   EGNN_HIP(ctx, hipMemcpyAsync(tab_i, ti.data(), ti.size() * sizeof(int), hipMemcpyHostToDevice, st));
   EGNN_HIP(ctx, hipMemcpyAsync(tab_f, ctx->unc_c.data(), ctx->unc_c.size() * sizeof(float), hipMemcpyHostToDevice, st));
-  // the table copies read pageable host memory that dies with this frame
-  EGNN_HIP(ctx, hipStreamSynchronize(st));
 
   StageTimer tm(ctx, st, 1);
   if ((rc = egnn_launch_geometry(ctx, g, pos, box, rhat_d, nullptr, nullptr, nullptr, st))) return rc;

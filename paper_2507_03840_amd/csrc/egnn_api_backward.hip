@@ -169,30 +169,32 @@ extern "C" int egnn_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const i
   const int row_len = (int)(row_bytes(ctx) / sizeof(float));
 
   // tables: transposed uncoupling (q <- H), slots, and the q offset of every row of V
-  std::vector<std::vector<std::pair<int, float>>> byq(nq);
-  for (int hidx = 0; hidx < nq; ++hidx)
-    for (int n = ctx->unc_ptr[hidx]; n < ctx->unc_ptr[hidx + 1]; ++n) byq[ctx->unc_q[n]].push_back({hidx, ctx->unc_c[n]});
-  std::vector<int> ti;
-  std::vector<float> tf;
-  int run = 0;
-  ti.push_back(0);
-  for (int q = 0; q < nq; ++q) {
-    run += (int)byq[q].size();
-    ti.push_back(run);
-  }
-  for (int q = 0; q < nq; ++q)
-    for (auto& e : byq[q]) {
-      ti.push_back(e.first);
-      tf.push_back(e.second);
+  std::vector<int>& ti = ctx->tab_rob_i;
+  std::vector<float>& tf = ctx->tab_rob_f;
+  if (ti.empty()) {
+    std::vector<std::vector<std::pair<int, float>>> byq(nq);
+    for (int hidx = 0; hidx < nq; ++hidx)
+      for (int n = ctx->unc_ptr[hidx]; n < ctx->unc_ptr[hidx + 1]; ++n) byq[ctx->unc_q[n]].push_back({hidx, ctx->unc_c[n]});
+    int run = 0;
+    ti.push_back(0);
+    for (int q = 0; q < nq; ++q) {
+      run += (int)byq[q].size();
+      ti.push_back(run);
     }
-  ti.insert(ti.end(), ctx->slot_L.begin(), ctx->slot_L.end());
-  ti.insert(ti.end(), ctx->slot_qoff.begin(), ctx->slot_qoff.end());
-  std::vector<int> vq(nv, 0);
-  for (int s = 0; s < ctx->n_slots; ++s) vq[ctx->slot_vrow[s]] = ctx->slot_qoff[s];
-  ti.insert(ti.end(), vq.begin(), vq.end());
+    for (int q = 0; q < nq; ++q)
+      for (auto& e : byq[q]) {
+        ti.push_back(e.first);
+        tf.push_back(e.second);
+      }
+    ti.insert(ti.end(), ctx->slot_L.begin(), ctx->slot_L.end());
+    ti.insert(ti.end(), ctx->slot_qoff.begin(), ctx->slot_qoff.end());
+    std::vector<int> vq(nv, 0);
+    for (int s = 0; s < ctx->n_slots; ++s) vq[ctx->slot_vrow[s]] = ctx->slot_qoff[s];
+    ti.insert(ti.end(), vq.begin(), vq.end());
+  }
+  // (sources owned by the context: no need to wait for the copies)
   EGNN_HIP(ctx, hipMemcpyAsync(b.tab_i, ti.data(), ti.size() * sizeof(int), hipMemcpyHostToDevice, st));
   EGNN_HIP(ctx, hipMemcpyAsync(b.tab_f, tf.data(), tf.size() * sizeof(float), hipMemcpyHostToDevice, st));
-  EGNN_HIP(ctx, hipStreamSynchronize(st));   // the tables live in pageable host memory of this frame
 
   if ((rc = egnn_launch_geometry(ctx, g, pos, box, b.rhat_d, nullptr, nullptr, nullptr, st))) return rc;
   if ((rc = egnn_launch_radial(ctx, 1, b.rhat_d, g->n_edges, W_r1, W_r2, b.w, b.w2s, st))) return rc;

@@ -38,6 +38,10 @@ struct egnn_ctx {
   int nl_grid_atoms = -1;                //   and the atom count it was built for
   bool use_fused = false;                // egnn_set_option(EGNN_OPT_FUSED)
   bool w_half = false;                   // egnn_set_option(EGNN_OPT_W_FP16)
+  // index tables of the readout / on-site kernels in the order the kernels read them, built on first use and kept:
+  // the asynchronous uploads into the caller's workspace read this memory, which lives as long as the context
+  std::vector<int> tab_ro_i, tab_rob_i, tab_on_i, tab_onb_i;
+  std::vector<float> tab_rob_f, tab_onb_f;
   std::string err;
 };
 

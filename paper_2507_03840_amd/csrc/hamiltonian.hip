@@ -528,21 +528,24 @@ extern "C" int egnn_onsite_hii(egnn_ctx* ctx, const float* x, const float* V_nod
   hipStream_t st = (hipStream_t)stream;
   const int nq = ctx->n_orb * ctx->n_orb;
   // integer table: q_row[nq] q_vrow[nq] unc_ptr[nq+1] unc_q[nnz]
-  std::vector<int> ti(ni);
-  for (int s = 0; s < ctx->n_slots; ++s) {
-    const int L = ctx->slot_L[s];
-    for (int M = 0; M < 2 * L + 1; ++M) {
-      ti[ctx->slot_qoff[s] + M] = L * L + M;
-      ti[nq + ctx->slot_qoff[s] + M] = ctx->slot_vrow[s];
+  std::vector<int>& ti = ctx->tab_on_i;
+  if (ti.empty()) {
+    ti.resize(ni);
+    for (int s = 0; s < ctx->n_slots; ++s) {
+      const int L = ctx->slot_L[s];
+      for (int M = 0; M < 2 * L + 1; ++M) {
+        ti[ctx->slot_qoff[s] + M] = L * L + M;
+        ti[nq + ctx->slot_qoff[s] + M] = ctx->slot_vrow[s];
+      }
     }
+    std::copy(ctx->unc_ptr.begin(), ctx->unc_ptr.end(), ti.begin() + 2 * nq);
+    std::copy(ctx->unc_q.begin(), ctx->unc_q.end(), ti.begin() + 3 * nq + 1);
   }
-  std::copy(ctx->unc_ptr.begin(), ctx->unc_ptr.end(), ti.begin() + 2 * nq);
-  std::copy(ctx->unc_q.begin(), ctx->unc_q.end(), ti.begin() + 3 * nq + 1);
   int* tab_i = (int*)ws;
   float* tab_f = (float*)((char*)ws + h256(ni * sizeof(int)));
+  // (sources owned by the context: no need to wait for the copies)
   EGNN_HIP(ctx, hipMemcpyAsync(tab_i, ti.data(), ni * sizeof(int), hipMemcpyHostToDevice, st));
   EGNN_HIP(ctx, hipMemcpyAsync(tab_f, ctx->unc_c.data(), nf * sizeof(float), hipMemcpyHostToDevice, st));
-  EGNN_HIP(ctx, hipStreamSynchronize(st));   // the copies read host memory that dies with this frame
   const int D = (ctx->desc.lmax + 1) * (ctx->desc.lmax + 1);
   const size_t shmem = ((size_t)D * ctx->desc.channels + nq) * sizeof(float);
   hipLaunchKernelGGL(onsite_kernel, dim3(n_nodes), dim3(256), shmem, st, x, V_node, tab_i, tab_i + nq, tab_i + 2 * nq,
@@ -584,54 +587,54 @@ extern "C" int egnn_onsite_backward(egnn_ctx* ctx, const float* x, const float* 
   const int D = (ctx->desc.lmax + 1) * (ctx->desc.lmax + 1);
   int nv = 0;
   for (int L = 0; L <= EGNN_L_READOUT; ++L) nv += ctx->n_out[L];
-  // host tables: transposed uncoupling (q <- H), the collapsed components that read each feature row, rows of V
-  std::vector<std::vector<std::pair<int, float>>> byq(nq);
-  for (int e = 0; e < nq; ++e)
-    for (int n = ctx->unc_ptr[e]; n < ctx->unc_ptr[e + 1]; ++n) byq[ctx->unc_q[n]].push_back({e, ctx->unc_c[n]});
-  std::vector<int> q_row(nq), q_vrow(nq), vrow_L(nv, 0), vrow_qoff(nv, 0);
-  for (int s = 0; s < ctx->n_slots; ++s) {
-    const int L = ctx->slot_L[s];
-    vrow_L[ctx->slot_vrow[s]] = L;
-    vrow_qoff[ctx->slot_vrow[s]] = ctx->slot_qoff[s];
-    for (int M = 0; M < 2 * L + 1; ++M) {
-      q_row[ctx->slot_qoff[s] + M] = L * L + M;
-      q_vrow[ctx->slot_qoff[s] + M] = ctx->slot_vrow[s];
+  // host tables (built once, kept in the context): transposed uncoupling (q <- H), the collapsed components that
+  // read each feature row, rows of V
+  const size_t o_rowptr = (size_t)(nq + 1) + nf, o_rowt = o_rowptr + D + 1, o_vrow = o_rowt + nq, o_vL = o_vrow + nq,
+               o_vq = o_vL + nv;
+  std::vector<int>& ti = ctx->tab_onb_i;
+  std::vector<float>& tf = ctx->tab_onb_f;
+  if (ti.empty()) {
+    std::vector<std::vector<std::pair<int, float>>> byq(nq);
+    for (int e = 0; e < nq; ++e)
+      for (int n = ctx->unc_ptr[e]; n < ctx->unc_ptr[e + 1]; ++n) byq[ctx->unc_q[n]].push_back({e, ctx->unc_c[n]});
+    std::vector<int> q_row(nq), q_vrow(nq), vrow_L(nv, 0), vrow_qoff(nv, 0);
+    for (int s = 0; s < ctx->n_slots; ++s) {
+      const int L = ctx->slot_L[s];
+      vrow_L[ctx->slot_vrow[s]] = L;
+      vrow_qoff[ctx->slot_vrow[s]] = ctx->slot_qoff[s];
+      for (int M = 0; M < 2 * L + 1; ++M) {
+        q_row[ctx->slot_qoff[s] + M] = L * L + M;
+        q_vrow[ctx->slot_qoff[s] + M] = ctx->slot_vrow[s];
+      }
     }
+    ti.reserve(ni);
+    int run = 0;
+    ti.push_back(0);
+    for (int q = 0; q < nq; ++q) ti.push_back(run += (int)byq[q].size());
+    for (int q = 0; q < nq; ++q)
+      for (auto& e : byq[q]) {
+        ti.push_back(e.first);
+        tf.push_back(e.second);
+      }
+    std::vector<std::vector<int>> byrow(D);
+    for (int t = 0; t < nq; ++t)
+      if (q_row[t] < D) byrow[q_row[t]].push_back(t);
+    run = 0;
+    ti.push_back(0);
+    for (int r = 0; r < D; ++r) ti.push_back(run += (int)byrow[r].size());
+    for (int r = 0; r < D; ++r) ti.insert(ti.end(), byrow[r].begin(), byrow[r].end());
+    ti.resize(o_rowt + nq, 0);
+    ti.insert(ti.end(), q_vrow.begin(), q_vrow.end());
+    ti.insert(ti.end(), vrow_L.begin(), vrow_L.end());
+    ti.insert(ti.end(), vrow_qoff.begin(), vrow_qoff.end());
   }
-  std::vector<int> ti;
-  std::vector<float> tf;
-  ti.reserve(ni);
-  int run = 0;
-  ti.push_back(0);
-  for (int q = 0; q < nq; ++q) ti.push_back(run += (int)byq[q].size());
-  for (int q = 0; q < nq; ++q)
-    for (auto& e : byq[q]) {
-      ti.push_back(e.first);
-      tf.push_back(e.second);
-    }
-  const size_t o_rowptr = ti.size();
-  std::vector<std::vector<int>> byrow(D);
-  for (int t = 0; t < nq; ++t)
-    if (q_row[t] < D) byrow[q_row[t]].push_back(t);
-  run = 0;
-  ti.push_back(0);
-  for (int r = 0; r < D; ++r) ti.push_back(run += (int)byrow[r].size());
-  const size_t o_rowt = ti.size();
-  for (int r = 0; r < D; ++r) ti.insert(ti.end(), byrow[r].begin(), byrow[r].end());
-  ti.resize(o_rowt + nq, 0);
-  const size_t o_vrow = ti.size();
-  ti.insert(ti.end(), q_vrow.begin(), q_vrow.end());
-  const size_t o_vL = ti.size();
-  ti.insert(ti.end(), vrow_L.begin(), vrow_L.end());
-  const size_t o_vq = ti.size();
-  ti.insert(ti.end(), vrow_qoff.begin(), vrow_qoff.end());
   if (ti.size() != ni || tf.size() != nf) return egnn_fail(ctx, EGNN_EINVAL, "onsite_backward: table size mismatch");
   int* tab_i = (int*)ws;
   float* tab_f = (float*)((char*)ws + h256(ni * sizeof(int)));
   float* dq_all = (float*)((char*)tab_f + h256(nf * sizeof(float)));
+  // (sources owned by the context: no need to wait for the copies)
   EGNN_HIP(ctx, hipMemcpyAsync(tab_i, ti.data(), ni * sizeof(int), hipMemcpyHostToDevice, st));
   EGNN_HIP(ctx, hipMemcpyAsync(tab_f, tf.data(), nf * sizeof(float), hipMemcpyHostToDevice, st));
-  EGNN_HIP(ctx, hipStreamSynchronize(st));   // the copies read host memory that dies with this frame
   hipLaunchKernelGGL(onsite_bwd_node_kernel, dim3(n_nodes), dim3(256), 2 * (size_t)nq * sizeof(float), st, V_node, dH_ii,
                      tab_i, tab_i + nq + 1, tab_f, tab_i + o_rowptr, tab_i + o_rowt, tab_i + o_vrow, dx, dq_all, D,
                      ctx->log2_channels, nq);
