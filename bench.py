@@ -190,18 +190,33 @@ def main():
         col_ptr, perm = m.egnn_graph_transpose(graph, bws)
         target = B.to_device(synth.normal(np.random.default_rng([w.seed, 99]), (n_edges, w.n_orb, w.n_orb)))
 
-        def train_step():
+        def train_step(keep=False):
             x_full.copy_(x0)
             m.egnn_species_embed(species, table, x_full)
-            xs = [x_full]
+            xs, kept = [x_full], []
             for t in range(w.n_layers):
-                xs.append(m.egnn_layer_forward(graph, pos, w.box, xs[-1], layers[t], bws))
-            Hh = m.egnn_readout_hij(graph, pos, w.box, xs[-1], ro, bws, out=H)
+                if keep:
+                    y, sv = m.egnn_layer_forward_save(graph, pos, w.box, xs[-1], layers[t], bws)
+                    kept.append(sv)
+                    xs.append(y)
+                else:
+                    xs.append(m.egnn_layer_forward(graph, pos, w.box, xs[-1], layers[t], bws))
+            if keep:
+                Hh, w_ro = m.egnn_readout_hij_save(graph, pos, w.box, xs[-1], ro, bws, out=H)
+            else:
+                Hh = m.egnn_readout_hij(graph, pos, w.box, xs[-1], ro, bws, out=H)
             loss, dH = m.egnn_loss_mse(Hh, target, bws)
-            dx, g_ro = m.egnn_readout_backward(graph, col_ptr, perm, pos, w.box, xs[-1], ro, dH, bws)
+            if keep:
+                dx, g_ro = m.egnn_readout_backward_saved(graph, col_ptr, perm, pos, w.box, xs[-1], ro, w_ro, dH, bws)
+            else:
+                dx, g_ro = m.egnn_readout_backward(graph, col_ptr, perm, pos, w.box, xs[-1], ro, dH, bws)
             for t in reversed(range(w.n_layers)):
-                dx, g_l = m.egnn_layer_backward(graph, col_ptr, perm, pos, w.box, xs[t], layers[t],
-                                                dx[:w.n_owned], bws)
+                if keep:
+                    dx, g_l = m.egnn_layer_backward_saved(graph, col_ptr, perm, pos, w.box, xs[t], layers[t], kept[t],
+                                                          dx[:w.n_owned], bws)
+                else:
+                    dx, g_l = m.egnn_layer_backward(graph, col_ptr, perm, pos, w.box, xs[t], layers[t],
+                                                    dx[:w.n_owned], bws)
             return loss
 
         if w.n_total == w.n_owned:
@@ -212,9 +227,21 @@ def main():
                 loss = train_step()
             torch.cuda.synchronize()
             dt = (time.perf_counter() - t1) / args.train_steps
+            train_step(keep=True)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(args.train_steps):
+                loss_k = train_step(keep=True)
+            torch.cuda.synchronize()
+            dt_k = (time.perf_counter() - t1) / args.train_steps
             training = dict(ms_per_step=1e3 * dt, steps=args.train_steps, loss=float(loss.cpu()[0]),
                             edge_layer_evaluations_per_s=n_edges * w.n_layers / dt,
-                            step="layers fwd + readout + MSE + readout bwd + layers bwd (forward recomputed inside bwd)")
+                            step="layers fwd + readout + MSE + readout bwd + layers bwd (forward recomputed inside bwd)",
+                            keeping_forward_quantities=dict(
+                                ms_per_step=1e3 * dt_k, loss=float(loss_k.cpu()[0]),
+                                kept_GB=4 * n_edges * w.channels * (w.n_layers * m.n_paths + m.n_paths_readout) / 1e9,
+                                note="radial weights of every layer and of the readout and the summed messages kept "
+                                     "by the caller (egnn_*_save / egnn_*_backward_saved); gradients bit-identical"))
         del bws
 
     # ---- what this GPU's memory system delivers to the simplest kernels: 1 GiB elementwise copy and 1 GiB fill ----

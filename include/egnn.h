@@ -213,6 +213,33 @@ int egnn_layer_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_p
                         const float* dx_out, float* dx_in, float* dW_pre, float* dW_post, float* dW_self,
                         float* dW_r1, float* dW_r2, void* ws, size_t ws_bytes, void* stream);
 
+/* Keeping forward quantities instead of recomputing them (a trade of memory for time: at 3,000 atoms the weight
+ * tensors of three layers and the readout are 13.5 GB, a few per cent of this GPU's memory; the paper reports 115 GB
+ * of saved activations for its training runs at that size, Sec. 4).  egnn_layer_forward_save / egnn_readout_hij_save
+ * compute exactly what egnn_layer_forward (own radial MLP, route through the materialised fp32 weight tensor) /
+ * egnn_readout_hij compute and leave the radial weights w_save [n_edges][P][channels] and, for the layer, the summed
+ * messages a_save [n_owned][(lmax+1)^2][channels] in caller buffers; egnn_layer_backward_saved /
+ * egnn_readout_backward_saved take them back (either may be NULL: then it is recomputed) and give bit-identical
+ * gradients to the recomputing calls.  Workspaces as for the recomputing calls. */
+int egnn_layer_forward_save(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
+                            const float* x_in, const float* W_pre, const float* W_post, const float* W_self,
+                            const float* W_r1, const float* W_r2, float* x_out, float* w_save, float* a_save,
+                            void* ws, size_t ws_bytes, void* stream);
+int egnn_readout_hij_save(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3], const float* x,
+                          const float* W_s, const float* W_t, const float* W_r1, const float* W_r2, const float* V,
+                          float* H, float* w_save, void* ws, size_t ws_bytes, void* stream);
+int egnn_layer_backward_saved(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm,
+                              const float* pos, const float box[3], const float* x_in, const float* W_pre,
+                              const float* W_post, const float* W_self, const float* W_r1, const float* W_r2,
+                              const float* w_saved, const float* a_saved, const float* dx_out, float* dx_in,
+                              float* dW_pre, float* dW_post, float* dW_self, float* dW_r1, float* dW_r2, void* ws,
+                              size_t ws_bytes, void* stream);
+int egnn_readout_backward_saved(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm,
+                                const float* pos, const float box[3], const float* x, const float* W_s,
+                                const float* W_t, const float* W_r1, const float* W_r2, const float* V,
+                                const float* w_saved, const float* dH, float* dx, float* dW_s, float* dW_t,
+                                float* dW_r1, float* dW_r2, float* dV, void* ws, size_t ws_bytes, void* stream);
+
 /* Adjoint of egnn_readout_hij.  dH [n_edges][n_orb][n_orb]; dx [n_total][...]; dV packed like V.
  */
 int egnn_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm,

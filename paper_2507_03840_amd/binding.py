@@ -25,6 +25,7 @@ SYMBOLS = [
     "egnn_so2_edge_block", "egnn_gate", "egnn_hamiltonian_workspace_bytes", "egnn_onsite_hii", "egnn_apply_padding", "egnn_loss_l1l2",
     "egnn_hamiltonian_structure", "egnn_hamiltonian_fill", "egnn_onsite_backward_workspace_bytes", "egnn_onsite_backward",
     "egnn_partition_low_nn", "egnn_pack_rows", "egnn_unpack_rows",
+    "egnn_layer_forward_save", "egnn_readout_hij_save", "egnn_layer_backward_saved", "egnn_readout_backward_saved",
 ]
 
 
@@ -415,6 +416,53 @@ class Egnn:
                                                    C.c_size_t(plan.numel()), _ptr(H_edge), _ptr(H_node), _ptr(row_idx),
                                                    _ptr(values), _stream()))
         return row_idx, values
+
+    # ---- forward calls that leave w (and a) with the caller, reverse calls that take them back
+    def egnn_layer_forward_save(self, graph, pos, box, x_in, W, ws, out=None):
+        """Returns (x_out, saved) with saved = (w [n_edges][P][E], a [n_owned][dim][E])."""
+        x_out = out if out is not None else torch.empty((graph.n_owned, self.dim, self.channels),
+                                                        dtype=torch.float32, device="cuda")
+        w = torch.empty((graph.n_edges, self.n_paths, self.channels), dtype=torch.float32, device="cuda")
+        a = torch.empty((graph.n_owned, self.dim, self.channels), dtype=torch.float32, device="cuda")
+        g = graph.desc()
+        self._check(self.lib.egnn_layer_forward_save(
+            self.ctx, C.byref(g), _ptr(pos), _f3(box), _ptr(x_in), _ptr(W["W_pre"]), _ptr(W["W_post"]),
+            _ptr(W["W_self"]), _ptr(W["W_r1"]), _ptr(W["W_r2"]), _ptr(x_out), _ptr(w), _ptr(a), _ptr(ws),
+            C.c_size_t(ws.numel()), _stream()))
+        return x_out, (w, a)
+
+    def egnn_readout_hij_save(self, graph, pos, box, x, W, ws, out=None):
+        H = out if out is not None else torch.empty((graph.n_edges, self.n_orb, self.n_orb), dtype=torch.float32,
+                                                    device="cuda")
+        w = torch.empty((graph.n_edges, self.n_paths_readout, self.channels), dtype=torch.float32, device="cuda")
+        g = graph.desc()
+        self._check(self.lib.egnn_readout_hij_save(
+            self.ctx, C.byref(g), _ptr(pos), _f3(box), _ptr(x), _ptr(W["W_s"]), _ptr(W["W_t"]), _ptr(W["W_r1"]),
+            _ptr(W["W_r2"]), _ptr(W["V"]), _ptr(H), _ptr(w), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+        return H, w
+
+    def egnn_layer_backward_saved(self, graph, col_ptr, perm, pos, box, x_in, W, saved, dx_out, ws):
+        w, a = saved
+        dx_in = torch.empty((graph.n_total, self.dim, self.channels), dtype=torch.float32, device="cuda")
+        grads = {k: torch.empty_like(W[k]) for k in ("W_pre", "W_post", "W_self", "W_r1", "W_r2")}
+        g = graph.desc()
+        self._check(self.lib.egnn_layer_backward_saved(
+            self.ctx, C.byref(g), _ptr(col_ptr), _ptr(perm), _ptr(pos), _f3(box), _ptr(x_in), _ptr(W["W_pre"]),
+            _ptr(W["W_post"]), _ptr(W["W_self"]), _ptr(W["W_r1"]), _ptr(W["W_r2"]), _ptr(w), _ptr(a), _ptr(dx_out),
+            _ptr(dx_in), _ptr(grads["W_pre"]), _ptr(grads["W_post"]), _ptr(grads["W_self"]), _ptr(grads["W_r1"]),
+            _ptr(grads["W_r2"]), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+        return dx_in, grads
+
+    def egnn_readout_backward_saved(self, graph, col_ptr, perm, pos, box, x, W, w_saved, dH, ws):
+        dx = torch.empty((graph.n_total, self.dim, self.channels), dtype=torch.float32, device="cuda")
+        grads = {k: torch.empty_like(W[k]) for k in ("W_s", "W_t", "W_r1", "W_r2", "V")}
+        g = graph.desc()
+        self._check(self.lib.egnn_readout_backward_saved(
+            self.ctx, C.byref(g), _ptr(col_ptr), _ptr(perm), _ptr(pos), _f3(box), _ptr(x), _ptr(W["W_s"]),
+            _ptr(W["W_t"]), _ptr(W["W_r1"]), _ptr(W["W_r2"]), _ptr(W["V"]), _ptr(w_saved), _ptr(dH), _ptr(dx),
+            _ptr(grads["W_s"]), _ptr(grads["W_t"]), _ptr(grads["W_r1"]), _ptr(grads["W_r2"]), _ptr(grads["V"]), _ptr(ws),
+            C.c_size_t(ws.numel()), _stream()))
+        return dx, grads
 
     # ---- S7: loss and reverse pass
     def egnn_backward_workspace_bytes(self, n_edges, n_owned, n_total):

@@ -329,10 +329,12 @@ extern "C" int egnn_node_mix(egnn_ctx* ctx, const float* x1, const float* W1, co
 }
 
 // ---- composite entry points ----------------------------------------------------------------------
-extern "C" int egnn_layer_forward(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
-                                  const float* x_in, const float* W_pre, const float* W_post, const float* W_self,
-                                  const float* W_r1, const float* W_r2, const float* w_edge, float* x_out,
-                                  void* ws, size_t ws_bytes, void* stream) {
+// w_save / a_save (may be NULL): caller buffers that receive the weight tensor and the summed messages instead of the
+// workspace (then the route through the materialised fp32 weights is taken whatever the options say)
+static int layer_forward_impl(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
+                              const float* x_in, const float* W_pre, const float* W_post, const float* W_self,
+                              const float* W_r1, const float* W_r2, const float* w_edge, float* x_out, float* w_save,
+                              float* a_save, void* ws, size_t ws_bytes, void* stream) {
   if (!ctx) return EGNN_EINVAL;
   int rc = check_graph(ctx, g, "layer_forward");
   if (rc) return rc;
@@ -351,6 +353,9 @@ extern "C" int egnn_layer_forward(egnn_ctx* ctx, const egnn_graph* g, const floa
   float* a = (float*)c.take((size_t)g->n_owned * row);
   const size_t w_bytes = with_w ? layer_w_bytes(ctx, g->n_edges) : 0;
   float* w = with_w ? (float*)c.take(w_bytes) : nullptr;
+  const bool saving = w_save || a_save;
+  if (w_save && with_w) w = w_save;
+  if (a_save) a = a_save;
   void* w2s = with_w ? c.take(egnn_radial_ws_bytes(ctx, 0)) : nullptr;
   StageTimer tm(ctx, st, 0);
   if ((rc = egnn_launch_geometry(ctx, g, pos, box, rhat_d, nullptr, nullptr, nullptr, st))) return rc;
@@ -358,8 +363,8 @@ extern "C" int egnn_layer_forward(egnn_ctx* ctx, const egnn_graph* g, const floa
   // Default: S3 writes the weight tensor, S4 reads it.  Opt-in (EGNN_OPT_FUSED): the weights are produced and
   // consumed inside one kernel and never leave the chip.
   // (the scratch of the fused route lives where the weight tensor would be)
-  const bool fused = with_w && ctx->use_fused && egnn_fused_supported(ctx);
-  const bool half = with_w && !fused && ctx->w_half;   // storage precision of the weight tensor between S3 and S4
+  const bool fused = with_w && !saving && ctx->use_fused && egnn_fused_supported(ctx);
+  const bool half = with_w && !saving && !fused && ctx->w_half;   // storage precision of the weight tensor between S3 and S4
   if (fused) {
     if (g->n_edges > 0 && (rc = egnn_launch_split_w2(ctx, 0, W_r2, w2s, st))) return rc;
   } else if (with_w) {
@@ -379,10 +384,28 @@ extern "C" int egnn_layer_forward(egnn_ctx* ctx, const egnn_graph* g, const floa
   return rc;
 }
 
-extern "C" int egnn_readout_hij(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
-                                const float* x, const float* W_s, const float* W_t, const float* W_r1,
-                                const float* W_r2, const float* V, float* H, void* ws, size_t ws_bytes,
-                                void* stream) {
+extern "C" int egnn_layer_forward(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
+                                  const float* x_in, const float* W_pre, const float* W_post, const float* W_self,
+                                  const float* W_r1, const float* W_r2, const float* w_edge, float* x_out,
+                                  void* ws, size_t ws_bytes, void* stream) {
+  return layer_forward_impl(ctx, g, pos, box, x_in, W_pre, W_post, W_self, W_r1, W_r2, w_edge, x_out, nullptr, nullptr,
+                            ws, ws_bytes, stream);
+}
+
+extern "C" int egnn_layer_forward_save(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
+                                       const float* x_in, const float* W_pre, const float* W_post, const float* W_self,
+                                       const float* W_r1, const float* W_r2, float* x_out, float* w_save, float* a_save,
+                                       void* ws, size_t ws_bytes, void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  if (!w_save || !a_save || !W_r1 || !W_r2) return egnn_fail(ctx, EGNN_EINVAL, "layer_forward_save: null pointer");
+  return layer_forward_impl(ctx, g, pos, box, x_in, W_pre, W_post, W_self, W_r1, W_r2, nullptr, x_out, w_save, a_save, ws,
+                            ws_bytes, stream);
+}
+
+static int readout_hij_impl(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
+                            const float* x, const float* W_s, const float* W_t, const float* W_r1,
+                            const float* W_r2, const float* V, float* H, float* w_save, void* ws, size_t ws_bytes,
+                            void* stream) {
   if (!ctx) return EGNN_EINVAL;
   int rc = check_graph(ctx, g, "readout_hij");
   if (rc) return rc;
@@ -401,6 +424,8 @@ extern "C" int egnn_readout_hij(egnn_ctx* ctx, const egnn_graph* g, const float*
   float* tab_f = (float*)c.take(ctx->unc_c.size() * sizeof(float));
   float* w = (float*)c.take(egnn_w_bytes(ctx, 1, g->n_edges));
   void* w2s = c.take(egnn_radial_ws_bytes(ctx, 1));
+  const bool half = ctx->w_half && !w_save;
+  if (w_save) w = w_save;
 
   // integer table: q_row[nq] q_vrow[nq] slot_L[n_slots] slot_qoff[n_slots] unc_ptr[nq+1] unc_q[nnz]
   const int nq = ctx->n_orb * ctx->n_orb;
@@ -429,13 +454,29 @@ extern "C" int egnn_readout_hij(egnn_ctx* ctx, const egnn_graph* g, const float*
   StageTimer tm(ctx, st, 1);
   if ((rc = egnn_launch_geometry(ctx, g, pos, box, rhat_d, nullptr, nullptr, nullptr, st))) return rc;
   tm.mark(0);
-  if ((rc = egnn_launch_radial(ctx, 1, rhat_d, g->n_edges, W_r1, W_r2, w, w2s, st, ctx->w_half))) return rc;
+  if ((rc = egnn_launch_radial(ctx, 1, rhat_d, g->n_edges, W_r1, W_r2, w, w2s, st, half))) return rc;
   tm.mark(1);
   if ((rc = egnn_launch_node_mix(ctx, x, W_s, nullptr, nullptr, zs, g->n_total, st))) return rc;
   tm.mark(2);
   if ((rc = egnn_launch_node_mix(ctx, x, W_t, nullptr, nullptr, zt, g->n_total, st))) return rc;
   tm.mark(3);
-  rc = egnn_launch_readout(ctx, g, rhat_d, zs, zt, w, V, tab_i, tab_f, H, st, ctx->w_half);
+  rc = egnn_launch_readout(ctx, g, rhat_d, zs, zt, w, V, tab_i, tab_f, H, st, half);
   tm.mark(4);
   return rc;
+}
+
+extern "C" int egnn_readout_hij(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
+                                const float* x, const float* W_s, const float* W_t, const float* W_r1,
+                                const float* W_r2, const float* V, float* H, void* ws, size_t ws_bytes,
+                                void* stream) {
+  return readout_hij_impl(ctx, g, pos, box, x, W_s, W_t, W_r1, W_r2, V, H, nullptr, ws, ws_bytes, stream);
+}
+
+extern "C" int egnn_readout_hij_save(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
+                                     const float* x, const float* W_s, const float* W_t, const float* W_r1,
+                                     const float* W_r2, const float* V, float* H, float* w_save, void* ws,
+                                     size_t ws_bytes, void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  if (!w_save) return egnn_fail(ctx, EGNN_EINVAL, "readout_hij_save: null pointer");
+  return readout_hij_impl(ctx, g, pos, box, x, W_s, W_t, W_r1, W_r2, V, H, w_save, ws, ws_bytes, stream);
 }

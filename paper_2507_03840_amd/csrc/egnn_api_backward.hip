@@ -104,11 +104,14 @@ static int check_bwd_graph(egnn_ctx* ctx, const egnn_graph* g, const int32_t* co
   return EGNN_OK;
 }
 
-extern "C" int egnn_layer_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm,
-                                   const float* pos, const float box[3], const float* x_in, const float* W_pre,
-                                   const float* W_post, const float* W_self, const float* W_r1, const float* W_r2,
-                                   const float* dx_out, float* dx_in, float* dW_pre, float* dW_post, float* dW_self,
-                                   float* dW_r1, float* dW_r2, void* ws, size_t ws_bytes, void* stream) {
+// w_saved / a_saved (may be NULL): the weight tensor and the summed messages of the forward pass, if the caller kept
+// them (egnn_layer_forward_save); what is missing is recomputed
+static int layer_backward_impl(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm,
+                               const float* pos, const float box[3], const float* x_in, const float* W_pre,
+                               const float* W_post, const float* W_self, const float* W_r1, const float* W_r2,
+                               const float* w_saved, const float* a_saved, const float* dx_out, float* dx_in,
+                               float* dW_pre, float* dW_post, float* dW_self, float* dW_r1, float* dW_r2, void* ws,
+                               size_t ws_bytes, void* stream) {
   if (!ctx) return EGNN_EINVAL;
   int rc = check_bwd_graph(ctx, g, col_ptr, perm, "layer_backward");
   if (rc) return rc;
@@ -125,15 +128,17 @@ extern "C" int egnn_layer_backward(egnn_ctx* ctx, const egnn_graph* g, const int
 
   // forward quantities
   if ((rc = egnn_launch_geometry(ctx, g, pos, box, b.rhat_d, nullptr, nullptr, nullptr, st))) return rc;
-  if ((rc = egnn_launch_radial(ctx, 0, b.rhat_d, g->n_edges, W_r1, W_r2, b.w, b.w2s, st))) return rc;
+  const float* w = w_saved ? w_saved : b.w;
+  const float* a = a_saved ? a_saved : b.a;
+  if (!w_saved && (rc = egnn_launch_radial(ctx, 0, b.rhat_d, g->n_edges, W_r1, W_r2, b.w, b.w2s, st))) return rc;
   if ((rc = egnn_launch_node_mix(ctx, x_in, W_pre, nullptr, nullptr, b.h, n_t, st))) return rc;
-  if ((rc = egnn_launch_tp_segsum(ctx, g, b.rhat_d, b.h, b.w, b.a, st))) return rc;
+  if (!a_saved && (rc = egnn_launch_tp_segsum(ctx, g, b.rhat_d, b.h, w, b.a, st))) return rc;
   // x_out = W_post a + W_self x_in[:n_owned]
   if ((rc = egnn_launch_node_mix(ctx, dx_out, W_post, nullptr, nullptr, b.da, n_o, st, 1))) return rc;
-  if ((rc = egnn_launch_mix_wgrad(ctx, dx_out, b.a, dW_post, b.wgrad_partial, n_o, st))) return rc;
+  if ((rc = egnn_launch_mix_wgrad(ctx, dx_out, a, dW_post, b.wgrad_partial, n_o, st))) return rc;
   if ((rc = egnn_launch_mix_wgrad(ctx, dx_out, x_in, dW_self, b.wgrad_partial, n_o, st))) return rc;
   // messages
-  if ((rc = egnn_launch_tp_backward(ctx, g, col_ptr, perm, b.rhat_d, b.h, b.w, b.da, b.dh, b.dw, st))) return rc;
+  if ((rc = egnn_launch_tp_backward(ctx, g, col_ptr, perm, b.rhat_d, b.h, w, b.da, b.dh, b.dw, st))) return rc;
   // h = W_pre x_in ; owned rows also receive the self term
   if ((rc = egnn_launch_node_mix(ctx, b.dh, W_pre, dx_out, W_self, dx_in, n_o, st, 1))) return rc;
   if (n_t > n_o &&
@@ -145,11 +150,31 @@ extern "C" int egnn_layer_backward(egnn_ctx* ctx, const egnn_graph* g, const int
   return egnn_launch_radial_backward(ctx, 0, b.rhat_d, g->n_edges, W_r1, W_r2, b.dw, dW_r1, dW_r2, b.radial, st);
 }
 
-extern "C" int egnn_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm,
-                                     const float* pos, const float box[3], const float* x, const float* W_s,
-                                     const float* W_t, const float* W_r1, const float* W_r2, const float* V,
-                                     const float* dH, float* dx, float* dW_s, float* dW_t, float* dW_r1,
-                                     float* dW_r2, float* dV, void* ws, size_t ws_bytes, void* stream) {
+extern "C" int egnn_layer_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm,
+                                   const float* pos, const float box[3], const float* x_in, const float* W_pre,
+                                   const float* W_post, const float* W_self, const float* W_r1, const float* W_r2,
+                                   const float* dx_out, float* dx_in, float* dW_pre, float* dW_post, float* dW_self,
+                                   float* dW_r1, float* dW_r2, void* ws, size_t ws_bytes, void* stream) {
+  return layer_backward_impl(ctx, g, col_ptr, perm, pos, box, x_in, W_pre, W_post, W_self, W_r1, W_r2, nullptr, nullptr,
+                             dx_out, dx_in, dW_pre, dW_post, dW_self, dW_r1, dW_r2, ws, ws_bytes, stream);
+}
+
+extern "C" int egnn_layer_backward_saved(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr,
+                                         const int32_t* perm, const float* pos, const float box[3], const float* x_in,
+                                         const float* W_pre, const float* W_post, const float* W_self,
+                                         const float* W_r1, const float* W_r2, const float* w_saved,
+                                         const float* a_saved, const float* dx_out, float* dx_in, float* dW_pre,
+                                         float* dW_post, float* dW_self, float* dW_r1, float* dW_r2, void* ws,
+                                         size_t ws_bytes, void* stream) {
+  return layer_backward_impl(ctx, g, col_ptr, perm, pos, box, x_in, W_pre, W_post, W_self, W_r1, W_r2, w_saved, a_saved,
+                             dx_out, dx_in, dW_pre, dW_post, dW_self, dW_r1, dW_r2, ws, ws_bytes, stream);
+}
+
+static int readout_backward_impl(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm,
+                                 const float* pos, const float box[3], const float* x, const float* W_s,
+                                 const float* W_t, const float* W_r1, const float* W_r2, const float* V,
+                                 const float* w_saved, const float* dH, float* dx, float* dW_s, float* dW_t,
+                                 float* dW_r1, float* dW_r2, float* dV, void* ws, size_t ws_bytes, void* stream) {
   if (!ctx) return EGNN_EINVAL;
   int rc = check_bwd_graph(ctx, g, col_ptr, perm, "readout_backward");
   if (rc) return rc;
@@ -197,10 +222,11 @@ extern "C" int egnn_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const i
   EGNN_HIP(ctx, hipMemcpyAsync(b.tab_f, tf.data(), tf.size() * sizeof(float), hipMemcpyHostToDevice, st));
 
   if ((rc = egnn_launch_geometry(ctx, g, pos, box, b.rhat_d, nullptr, nullptr, nullptr, st))) return rc;
-  if ((rc = egnn_launch_radial(ctx, 1, b.rhat_d, g->n_edges, W_r1, W_r2, b.w, b.w2s, st))) return rc;
+  const float* w = w_saved ? w_saved : b.w;
+  if (!w_saved && (rc = egnn_launch_radial(ctx, 1, b.rhat_d, g->n_edges, W_r1, W_r2, b.w, b.w2s, st))) return rc;
   if ((rc = egnn_launch_node_mix(ctx, x, W_s, nullptr, nullptr, b.zs, n_t, st))) return rc;
   if ((rc = egnn_launch_node_mix(ctx, x, W_t, nullptr, nullptr, b.zt, n_t, st))) return rc;
-  if ((rc = egnn_launch_readout_backward(ctx, g, b.rhat_d, b.zs, b.zt, b.w, V, b.tab_i, b.tab_f, dH, b.dz, b.dw, dV,
+  if ((rc = egnn_launch_readout_backward(ctx, g, b.rhat_d, b.zs, b.zt, w, V, b.tab_i, b.tab_f, dH, b.dz, b.dw, dV,
                                          b.dV_partial, st)))
     return rc;
   // dz_k feeds the source row (zs) and the destination row (zt, owned nodes only)
@@ -215,4 +241,23 @@ extern "C" int egnn_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const i
   if ((rc = egnn_launch_mix_wgrad(ctx, b.dzs, x, dW_s, b.wgrad_partial, n_t, st))) return rc;
   if ((rc = egnn_launch_mix_wgrad(ctx, b.dzt, x, dW_t, b.wgrad_partial, n_t, st))) return rc;
   return egnn_launch_radial_backward(ctx, 1, b.rhat_d, g->n_edges, W_r1, W_r2, b.dw, dW_r1, dW_r2, b.radial, st);
+}
+
+extern "C" int egnn_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm,
+                                     const float* pos, const float box[3], const float* x, const float* W_s,
+                                     const float* W_t, const float* W_r1, const float* W_r2, const float* V,
+                                     const float* dH, float* dx, float* dW_s, float* dW_t, float* dW_r1,
+                                     float* dW_r2, float* dV, void* ws, size_t ws_bytes, void* stream) {
+  return readout_backward_impl(ctx, g, col_ptr, perm, pos, box, x, W_s, W_t, W_r1, W_r2, V, nullptr, dH, dx, dW_s, dW_t,
+                               dW_r1, dW_r2, dV, ws, ws_bytes, stream);
+}
+
+extern "C" int egnn_readout_backward_saved(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr,
+                                           const int32_t* perm, const float* pos, const float box[3], const float* x,
+                                           const float* W_s, const float* W_t, const float* W_r1, const float* W_r2,
+                                           const float* V, const float* w_saved, const float* dH, float* dx,
+                                           float* dW_s, float* dW_t, float* dW_r1, float* dW_r2, float* dV, void* ws,
+                                           size_t ws_bytes, void* stream) {
+  return readout_backward_impl(ctx, g, col_ptr, perm, pos, box, x, W_s, W_t, W_r1, W_r2, V, w_saved, dH, dx, dW_s, dW_t,
+                               dW_r1, dW_r2, dV, ws, ws_bytes, stream);
 }

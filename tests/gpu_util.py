@@ -104,8 +104,9 @@ def oracle_training_step(w, wt, g, agg, T):
     return dict(loss=loss, grads=grads)
 
 
-def gpu_training_step(w, wt, agg, T, repeats=1, timing=None):
-    """The same step through the C ABI.  Layer inputs are kept; everything else is recomputed in the reverse pass."""
+def gpu_training_step(w, wt, agg, T, repeats=1, timing=None, keep=False):
+    """The same step through the C ABI.  Layer inputs are kept; everything else is recomputed in the reverse pass, or
+    (keep=True) the radial weights and summed messages of the forward pass are kept and handed back."""
     import torch
     from paper_2507_03840_amd import binding as B
     m = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, agg, n_layers=w.n_layers, orb_l=w.orb_l)
@@ -126,18 +127,33 @@ def gpu_training_step(w, wt, agg, T, repeats=1, timing=None):
             torch.cuda.synchronize()
             t0 = __import__("time").perf_counter()
         xs = [x]
+        kept = []
         for t in range(w.n_layers):
-            y = m.egnn_layer_forward(graph, pos, w.box, xs[-1], layers[t], ws)
+            if keep:
+                y, sv = m.egnn_layer_forward_save(graph, pos, w.box, xs[-1], layers[t], ws)
+                kept.append(sv)
+            else:
+                y = m.egnn_layer_forward(graph, pos, w.box, xs[-1], layers[t], ws)
             nxt = torch.cat([y, B.to_device(wt["halo"][(t + 1) % w.n_layers])], dim=0).contiguous() \
                 if w.n_total > w.n_owned else y
             xs.append(nxt)
-        H = m.egnn_readout_hij(graph, pos, w.box, xs[-1], ro, ws)
+        if keep:
+            H, w_ro = m.egnn_readout_hij_save(graph, pos, w.box, xs[-1], ro, ws)
+        else:
+            H = m.egnn_readout_hij(graph, pos, w.box, xs[-1], ro, ws)
         loss, dH = m.egnn_loss_mse(H, Td, ws)
-        dx, g_ro = m.egnn_readout_backward(graph, col_ptr, perm, pos, w.box, xs[-1], ro, dH, ws)
+        if keep:
+            dx, g_ro = m.egnn_readout_backward_saved(graph, col_ptr, perm, pos, w.box, xs[-1], ro, w_ro, dH, ws)
+        else:
+            dx, g_ro = m.egnn_readout_backward(graph, col_ptr, perm, pos, w.box, xs[-1], ro, dH, ws)
         grads = {f"readout.{k}": v for k, v in g_ro.items()}
         for t in reversed(range(w.n_layers)):
-            dx, g_l = m.egnn_layer_backward(graph, col_ptr, perm, pos, w.box, xs[t], layers[t],
-                                            dx[:w.n_owned].contiguous(), ws)
+            if keep:
+                dx, g_l = m.egnn_layer_backward_saved(graph, col_ptr, perm, pos, w.box, xs[t], layers[t], kept[t],
+                                                      dx[:w.n_owned].contiguous(), ws)
+            else:
+                dx, g_l = m.egnn_layer_backward(graph, col_ptr, perm, pos, w.box, xs[t], layers[t],
+                                                dx[:w.n_owned].contiguous(), ws)
             grads.update({f"layer{t}.{k}": v for k, v in g_l.items()})
         grads["x0"] = dx
         torch.cuda.synchronize()

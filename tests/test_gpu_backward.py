@@ -121,3 +121,23 @@ def test_training_step_config(B, index):
         e = U.rel_err(res["grads"][k], ref["grads"][k])
         print(f"{k}: {e:.2e}", flush=True)
         assert e < TOL, k
+
+
+@pytest.mark.parametrize("index", [0, 1, 2])
+def test_training_step_with_kept_forward_quantities_is_bit_identical(B, index):
+    """egnn_*_save / egnn_*_backward_saved: the same kernels run on the same numbers, so loss and every gradient must
+    equal those of the recomputing calls bit for bit."""
+    if index == 0:
+        w = synth.small_cluster(90, 60, 3, 16, 6, 4.0, 77)
+        w.n_layers = 2
+    else:
+        w = synth.workload(index)
+    wt = U.model_weights(w)
+    g = U.oracle_graph(w)
+    agg = max(1.0, U.mean_degree(g, w.n_owned))
+    T = synth.normal(np.random.default_rng([3, index]), (len(g[0]), w.n_orb, w.n_orb))
+    r0 = U.gpu_training_step(w, wt, agg, T)
+    r1 = U.gpu_training_step(w, wt, agg, T, keep=True)
+    assert r0["loss"] == r1["loss"]
+    for k in r0["grads"]:
+        assert np.array_equal(r0["grads"][k], r1["grads"][k]), k

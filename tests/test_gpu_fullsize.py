@@ -66,7 +66,8 @@ def test_stage_timing_records_every_stage():
     m.egnn_timing_enable(0)
 
 
-def test_fullsize_training_step_config5():
+@pytest.mark.parametrize("keep", [False, True])
+def test_fullsize_training_step_config5(keep):
     """Config 5: forward + MSE + reverse pass on the 3,000-atom graph; loss and every gradient against the stored
     fp64 oracle results (weight gradients in full, input-feature gradient at sampled rows)."""
     import torch
@@ -77,7 +78,7 @@ def test_fullsize_training_step_config5():
     w = synth.workload(5)
     wt = U.model_weights(w)
     T = synth.normal(np.random.default_rng([w.seed, 99]), (int(gold["n_edges"]), w.n_orb, w.n_orb))
-    res = U.gpu_training_step(w, wt, float(gold["agg"]), T)
+    res = U.gpu_training_step(w, wt, float(gold["agg"]), T, keep=keep)
     assert res["n_edges"] == int(gold["n_edges"])
     print(f"loss gpu {res['loss']:.8f} oracle {float(gold['loss']):.8f}", flush=True)
     assert abs(res["loss"] / float(gold["loss"]) - 1) < 1e-5
