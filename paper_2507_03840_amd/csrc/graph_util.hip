@@ -46,24 +46,45 @@ __global__ __launch_bounds__(256) void edge_rows_segsum_kernel(const float* __re
                                                                int row_len) {
   const int i = blockIdx.x;
   const int p0 = ptr[i], p1 = ptr[i + 1];
+  // four interleaved running sums (position in the segment mod 4): four row loads in flight per thread, fixed order
   for (int q = threadIdx.x; q < row_len; q += 256) {
-    float acc = 0.0f;
-    for (int idx = p0; idx < p1; ++idx) {
-      const long k = perm ? perm[idx] : idx;
-      acc += rows[k * row_len + q];
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    int idx = p0;
+    for (; idx + 4 <= p1; idx += 4) {
+      float v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const long k = perm ? perm[idx + u] : idx + u;
+        v[u] = __builtin_nontemporal_load(rows + k * row_len + q);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) acc[u] += v[u];
     }
-    out[(long)i * row_len + q] = acc;
+    for (int u = 0; idx < p1; ++idx, ++u) {
+      const long k = perm ? perm[idx] : idx;
+      acc[u] += rows[k * row_len + q];
+    }
+    out[(long)i * row_len + q] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
   }
 }
 
-// out[i] = scale * sum_b partial[b][i], b ascending.
+// out[i] = scale * sum_b partial[b][i] in a fixed order: eight interleaved running sums (b mod 8), so that eight
+// loads are in flight per thread, combined pairwise at the end.
 __global__ void reduce_partials_kernel(const float* __restrict__ partial, int n_partials, long n,
                                        float* __restrict__ out, float scale) {
   const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
-  float acc = 0.0f;
-  for (int b = 0; b < n_partials; ++b) acc += partial[(long)b * n + i];
-  out[i] = acc * scale;
+  float acc[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+  int b = 0;
+  for (; b + 8 <= n_partials; b += 8) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(partial + (long)(b + u) * n + i);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc[u] += v[u];
+  }
+  for (int u = 0; b < n_partials; ++b, ++u) acc[u] += partial[(long)b * n + i];
+  out[i] = (((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]))) * scale;
 }
 
 #define LOSS_PER_BLOCK 4096
