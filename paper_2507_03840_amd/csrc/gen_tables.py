@@ -323,6 +323,8 @@ def emit_mid(l_in, l_sh, l_out, paths, groups):
     lines.append(f"  static constexpr int CHUNK_COUNT[{l_in + 1}] = {{{', '.join(map(str, count))}}};")
     lines.append(f"  static constexpr int CHUNK_MAX = {max(count)};")
     lines.append("  template <int L1> __device__ __forceinline__ static void run_l1(const float* v, const float* w, float* o);")
+    lines.append("  template <int L1> __device__ __forceinline__ static void run_bwd_l1(const float* v, const float* w, const float* go,")
+    lines.append("                                                                       float* gv, float* gw);")
     lines.append("};")
     for l1 in range(l_in + 1):
         lines.append(f"template <> __device__ __forceinline__ void TpMid_{tag}::run_l1<{l1}>(const float* v, const float* w, float* o) {{")
@@ -336,6 +338,37 @@ def emit_mid(l_in, l_sh, l_out, paths, groups):
                 for mm in ([m, -m] if m else [0]):
                     lines.append(f"    o[{l3 * l3 + l3 + mm}] += g * v[{l1 + mm}];")
                 lines.append("  }")
+        lines.append("}")
+    # the adjoint split the same way: v and gv are the degree-l1 block only (gv overwritten), w and gw the run of
+    # weights of that degree (gw overwritten), go the whole output gradient
+    for l1 in range(l_in + 1):
+        lines.append(f"template <> __device__ __forceinline__ void TpMid_{tag}::run_bwd_l1<{l1}>(const float* v, const float* w, const float* go,")
+        lines.append("                                                                          float* gv, float* gw) {")
+        tv, tw = set(), set()
+        for (a, l3) in sorted(groups):
+            if a != l1:
+                continue
+            for m in sorted(groups[(a, l3)]):
+                terms = groups[(a, l3)][m]
+                g = " + ".join(f"{f32(k)} * w[{p - first[l1]}]" for p, k in terms)
+                pairs = [(l3 * l3 + l3 + mm, l1 + mm) for mm in ([m, -m] if m else [0])]
+                dg = " + ".join(f"go[{oi}] * v[{vi}]" for oi, vi in pairs)
+                lines.append(f"  {{ const float g = {g};")
+                lines.append(f"    const float dg = {dg};")
+                for oi, vi in pairs:
+                    lines.append(f"    gv[{vi}] {'+=' if vi in tv else '='} g * go[{oi}];")
+                    tv.add(vi)
+                for p, k in terms:
+                    q = p - first[l1]
+                    lines.append(f"    gw[{q}] {'+=' if q in tw else '='} {f32(k)} * dg;")
+                    tw.add(q)
+                lines.append("  }")
+        for vi in range(2 * l1 + 1):
+            if vi not in tv:
+                lines.append(f"  gv[{vi}] = 0.0f;")
+        for q in range(count[l1]):
+            if q not in tw:
+                lines.append(f"  gw[{q}] = 0.0f;")
         lines.append("}")
     return "\n".join(lines)
 

@@ -10,14 +10,34 @@
 #include "egnn_internal.h"
 #include "bond_frame.h"
 
+// The adjoint of the bond-frame product, one input degree l1 at a time: the paths of a degree use one contiguous
+// run of weights, so a run is loaded, turned into its part of the feature gradient and its own gradient, and stored
+// before the next one is touched -- at most ten weights and ten weight gradients are live at once instead of 42 + 42,
+// which is what lets two waves share a SIMD.
+template <int LMAX, int L1>
+struct TpBwdDegree {
+  using Mid = typename LayerMid<LMAX>::T;
+  __device__ __forceinline__ static void run(const float* v, const float* go, float* gv, const float* __restrict__ wp,
+                                             float* __restrict__ dwp, int log2E) {
+    constexpr int first = Mid::CHUNK_FIRST[L1], count = Mid::CHUNK_COUNT[L1];
+    float wr[count], gw[count];
+#pragma unroll
+    for (int p = 0; p < count; ++p) wr[p] = __builtin_nontemporal_load(wp + ((size_t)(first + p) << log2E));
+    Mid::template run_bwd_l1<L1>(v + L1 * L1, wr, go, gv + L1 * L1, gw);
+#pragma unroll
+    for (int p = 0; p < count; ++p) __builtin_nontemporal_store(gw[p], dwp + ((size_t)(first + p) << log2E));
+    if constexpr (L1 < LMAX) TpBwdDegree<LMAX, L1 + 1>::run(v, go, gv, wp, dwp, log2E);
+  }
+};
+
 template <int LMAX>
-__global__ __launch_bounds__(256) void tp_backward_kernel(const int* __restrict__ col_ptr, const int* __restrict__ perm,
-                                                          const int* __restrict__ dst,
-                                                          const float4* __restrict__ rhat_d,
-                                                          const float* __restrict__ h, const float* __restrict__ w,
-                                                          const float* __restrict__ da, float* __restrict__ dh,
-                                                          float* __restrict__ dw, int n_total, int log2E,
-                                                          int nodes_per_xcd, float scale) {
+__global__ __launch_bounds__(256, 2) void tp_backward_kernel(const int* __restrict__ col_ptr, const int* __restrict__ perm,
+                                                             const int* __restrict__ dst,
+                                                             const float4* __restrict__ rhat_d,
+                                                             const float* __restrict__ h, const float* __restrict__ w,
+                                                             const float* __restrict__ da, float* __restrict__ dh,
+                                                             float* __restrict__ dw, int n_total, int log2E,
+                                                             int nodes_per_xcd, float scale) {
   using Mid = typename LayerMid<LMAX>::T;
   constexpr int D = (LMAX + 1) * (LMAX + 1);
   constexpr int P = Mid::P;
@@ -47,9 +67,7 @@ __global__ __launch_bounds__(256) void tp_backward_kernel(const int* __restrict_
     const float* gp = da + ((size_t)j * D << log2E) + c;
     const float* wp = w + ((size_t)k * P << log2E) + c;
     float* dwp = dw + ((size_t)k * P << log2E) + c;
-    float v[D], go[D], gv[D], wr[P], gw[P];
-#pragma unroll
-    for (int p = 0; p < P; ++p) wr[p] = wp[(size_t)p << log2E];
+    float v[D], go[D], gv[D];
 #pragma unroll
     for (int q = 0; q < D; ++q) {
       v[q] = v0[q];
@@ -59,12 +77,10 @@ __global__ __launch_bounds__(256) void tp_backward_kernel(const int* __restrict_
     egnn_bond_trig<LMAX>(g.x, g.y, g.z, t);
     egnn_to_bond_frame<LMAX>(v, t);
     egnn_to_bond_frame<LMAX>(go, t);
-    Mid::run_bwd(v, wr, go, gv, gw);
+    TpBwdDegree<LMAX, 0>::run(v, go, gv, wp, dwp, log2E);
     egnn_from_bond_frame<LMAX>(gv, t);
 #pragma unroll
     for (int q = 0; q < D; ++q) acc[q] += gv[q];
-#pragma unroll
-    for (int p = 0; p < P; ++p) __builtin_nontemporal_store(gw[p], dwp + ((size_t)p << log2E));
   }
 
 #pragma unroll
