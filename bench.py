@@ -67,6 +67,18 @@ def cpu_baseline(w, wt, g, agg, n_nodes):
                        f"workload, {dt:.1f} s, numpy fp64, 1 thread")
 
 
+def model_weights(w, synth, n_paths, n_paths_readout, n_vrows):
+    """Random weights of every layer and of the readout of workload w, drawn in the order the parity tests draw them."""
+    import numpy as np
+    rng = np.random.default_rng([w.seed, 1000])
+    layers = [synth.layer_weights(rng, w.lmax, w.channels, w.n_rbf, w.n_hidden, n_paths) for _ in range(w.n_layers)]
+    ro = synth.readout_weights(rng, w.lmax, w.channels, w.n_rbf, w.n_hidden, n_paths_readout, n_vrows)
+    x0 = synth.node_features(rng, w.n_total, w.lmax, w.channels)
+    table = synth.species_table(rng, w.n_species, w.channels)
+    halo = [synth.node_features(rng, w.n_total - w.n_owned, w.lmax, w.channels) for _ in range(w.n_layers)]
+    return dict(layers=layers, readout=ro, x0=x0, table=table, halo=halo)
+
+
 def _so2_flat(ws):
     """(W_e, W0, Wr, Wi) -> [W0, Wr_1, Wi_1, ...] in the order of the C ABI."""
     W_e, W0, Wr, Wi = ws
@@ -102,12 +114,14 @@ def main():
     import torch
     from paper_2507_03840_amd import binding as B
     from paper_2507_03840_amd import synth
-    from tests import gpu_util as U
 
     assert torch.cuda.is_available(), "bench.py needs an MI355X"
     B.load_library()
     w = synth.workload(args.config, check_cutoff=False)
-    wt = U.model_weights(w)
+    # weights sized from the library's own path and readout-slot counts (nothing of the oracle runs in this leg)
+    sizes = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, 1.0, orb_l=w.orb_l)
+    wt = model_weights(w, synth, sizes.n_paths, sizes.n_paths_readout, sum(sizes.egnn_readout_widths()))
+    del sizes
     pos = B.to_device(w.pos)
     species = B.to_device(w.species)
     table = B.to_device(wt["table"])
@@ -456,6 +470,7 @@ def main():
     if sweep is not None:
         out["saturation_sweep"] = sweep
     if not args.no_cpu_baseline:
+        from tests import gpu_util as U                      # (the oracle and its helpers: this leg only)
         g = U.oracle_graph(w)
         out["cpu_baseline"] = cpu_baseline(w, wt, g, agg, min(args.cpu_nodes, w.n_owned))
     print(json.dumps(out))
