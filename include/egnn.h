@@ -27,7 +27,8 @@
  *     halo nodes (read-only sources) follow.
  *   - Return value: 0 on success, a negative EGNN_E* code otherwise; egnn_last_error() gives text.
  *     Nothing throws or aborts across this boundary.  Identical inputs give bit-identical
- *     outputs (no floating-point atomics anywhere).
+ *     outputs (no floating-point atomics anywhere).  A context keeps the last error text and a few
+ *     lazily built tables: use it from one thread at a time.
  */
 #ifndef EGNN_H
 #define EGNN_H
