@@ -147,3 +147,40 @@ def test_axis_aligned_bonds_model(B, fused):
     for t in range(2):
         assert U.rel_err(xs[t].cpu().numpy(), xs_ref[t]) < TOL
     assert U.rel_err(H.cpu().numpy(), H_ref) < TOL
+
+
+@pytest.mark.parametrize("lmax,E,n", [(2, 8, 60), (4, 16, 80), (3, 32, 70)])
+def test_two_gpu_routes_agree_when_so2_weights_are_the_coupling_coefficients(B, lmax, E, n):
+    """The statement of the C ABI: egnn_so2_message_sum is egnn_tp_segsum when its weights are read off the coupling
+    with the harmonics of the bond direction.  Both sides here are GPU kernels of different design (vector ALU with
+    generated sparse constants vs split-bf16 MFMA GEMMs); the oracle only supplies the coupling coefficients."""
+    import torch
+    w = synth.small_cluster(n, n, lmax, E, 6, 4.0, 300 + lmax)
+    g = U.oracle_graph(w)
+    rng = np.random.default_rng([31, lmax])
+    x = synth.node_features(rng, n, lmax, E)
+    paths = O.tp_paths(lmax, lmax, lmax)
+    wp = synth.normal(rng, (len(paths), E))
+    shapes = S.so2_shapes(lmax, E)
+    W0 = np.zeros(shapes[0])
+    Wr = [np.zeros(s) for s in shapes[1:]]
+    Wi = [np.zeros(s) for s in shapes[1:]]
+    for p, (l1, l2, l3) in enumerate(paths):
+        T = O.cg_real(l1, l2, l3)[:, l2, :] * np.sqrt(2 * l2 + 1)
+        for c in range(E):
+            W0[l3 * E + c, l1 * 3 * E + c] += wp[p, c] * T[l1, l3]
+            for m in range(1, min(l1, l3) + 1):
+                Wr[m - 1][(l3 - m) * E + c, (l1 - m) * 3 * E + c] += wp[p, c] * T[l1 + m, l3 + m]
+                Wi[m - 1][(l3 - m) * E + c, (l1 - m) * 3 * E + c] += wp[p, c] * T[l1 + m, l3 - m]
+    m = B.Egnn(lmax, E, 6, 4.0, 4.0)
+    pos = B.to_device(w.pos)
+    graph = m.egnn_nlist(pos, n, w.box, w.pbc)
+    ws = torch.empty(m.egnn_so2_workspace_bytes(graph.n_edges), dtype=torch.uint8, device="cuda")
+    a_so2 = m.egnn_so2_message_sum(graph, pos, w.box, B.to_device(x), torch.zeros((E, 6), device="cuda"),
+                                   B.to_device(S.so2_pack(W0, Wr, Wi)), ws).cpu().numpy()
+    rhat_d, _, _, fc = m.egnn_edge_geometry(graph, pos, w.box, want_fc=True)
+    w_edge = (fc[:, None, None] * B.to_device(wp)[None]).contiguous()
+    a_tp = m.egnn_tp_segsum(graph, rhat_d, B.to_device(x), w_edge).cpu().numpy()
+    e = np.abs(a_so2 - a_tp).max() / np.abs(a_tp).max()
+    print(f"lmax {lmax} E {E}: the two GPU routes differ by {e:.2e}", flush=True)
+    assert np.abs(a_tp).max() > 0.05 and e < 2e-5
