@@ -76,94 +76,16 @@ __global__ __launch_bounds__(256) void rb_split_transpose_kernel(const float* __
 }
 
 // dpre[k][j] = S[k][j] * sum_n dw[k][n] alpha_n W_r2[n][j]  (in place over S).  W2T = T of (alpha W_r2), contraction
-// index n.  A compute wave owns 64 edges (two 32-row blocks) and all 64 units; lane l serves row/column l & 31 and
-// the half hh = l >> 5 of each 64-wide step: MFMA step t contracts n = 64 s + 32 hh + 8 t .. + 7.
-// The wave's 64 x 64 tile of dw is fetched in the order memory likes (16 lanes per 256-byte row segment, four rows per
-// load instruction) and turned into the operand order (one row per lane) through a private LDS tile; fetching it in
-// operand order would touch 64 cache lines per load instruction and leave the kernel bound by address processing.
-#define RB_AROW 68   // floats per row of the private tile: 64 + 4 (16-byte aligned, rows 4 banks apart)
-__global__ __launch_bounds__(RB_THREADS) void radial_dpre_kernel(const float* __restrict__ dw, long n_edges,
+// index n; the contraction is sg_contract of stream_gemm.h (rows = edges, one 64-column tile = the 64 hidden units).
+__global__ __launch_bounds__(SG_THREADS) void radial_dpre_kernel(const float* __restrict__ dw, long n_edges,
                                                                  const uint16_t* __restrict__ W2T,
                                                                  float* __restrict__ S, int PE, int n_steps) {
   extern __shared__ uint4 rb_smem[];
-  uint4* sB = rb_smem;                                                     // [2][64][RB_BROW4]
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
-  if (wave == RB_WAVES) {
-    rb_loader(W2T, 0, n_steps, sB, lane);
-    return;
-  }
-  float* sA = reinterpret_cast<float*>(sB + 2 * 64 * RB_BROW4) + (size_t)wave * 32 * RB_AROW;   // this wave: [32][RB_AROW]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int m = lane & 31, hh = lane >> 5;
-  const long e_base = ((long)blockIdx.x * RB_WAVES + wave) * 64;
-  // fetch order: load i of a row block covers rows 4 i .. 4 i + 3, lane -> (row 4 i + lane / 16, floats 4 (lane & 15) ..)
-  const int frow = lane >> 4, fcol = (lane & 15) * 4;
-  const float* fptr[2][8];
-#pragma unroll
-  for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      long e = e_base + rb * 32 + 4 * i + frow;
-      if (e >= n_edges) e = n_edges - 1;
-      fptr[rb][i] = dw + (size_t)e * PE;
-    }
+  const long e_base = ((long)blockIdx.x * SG_WAVES + wave) * 64;
   float16v acc[2][2];
-#pragma unroll
-  for (int a = 0; a < 2; ++a)
-#pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
-
-  // dw of the next step is in flight while this one is contracted.  No branch around a load: columns past the row
-  // are clamped, and the value is replaced by zero where it is used -- not here, which would make the wave wait
-  // for the load it has just issued.
-  float4 nxt[2][8];
-  auto fetch = [&](int s) {
-    const int n = s * 64 + fcol;
-    const int nc = n < PE ? n : PE - 4;
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-      for (int i = 0; i < 8; ++i) nxt[rb][i] = *reinterpret_cast<const float4*>(fptr[rb][i] + nc);
-  };
-  fetch(0);
-  for (int s = 0; s < n_steps; ++s) {
-    float4 cur[2][8];
-    const bool col_ok = s * 64 + fcol < PE;
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-      for (int i = 0; i < 8; ++i) cur[rb][i] = col_ok ? nxt[rb][i] : make_float4(0.f, 0.f, 0.f, 0.f);
-    if (s + 1 < n_steps) fetch(s + 1);
-    rb_barrier_acquire();
-    const uint4* bbase = sB + (s & 1) * (64 * RB_BROW4) + hh * 4;
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-      // the private tile: written in fetch order, read in operand order; the wave's own LDS accesses stay in order
-#pragma unroll
-      for (int i = 0; i < 8; ++i) *reinterpret_cast<float4*>(sA + (4 * i + frow) * RB_AROW + fcol) = cur[rb][i];
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
-      const float4* arow = reinterpret_cast<const float4*>(sA + m * RB_AROW + hh * 32);
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const float4 u = arow[2 * t], v = arow[2 * t + 1];
-        const float x[8] = {u.x, u.y, u.z, u.w, v.x, v.y, v.z, v.w};
-        uint4 ah, am, al;
-        rb_split8(x, ah, am, al);
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-          const uint4* brow = bbase + (m + 32 * cb) * RB_BROW4 + t;
-          const uint4 b[3] = {brow[0], brow[8], brow[16]};
-          acc[rb][cb] = rb_mma6(ah, am, al, b, acc[rb][cb]);
-        }
-      }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-      __builtin_amdgcn_wave_barrier();   // reads of the tile are done before the next block overwrites it
-    }
-  }
+  sg_contract(dw, n_edges, PE, reinterpret_cast<const uint4*>(W2T), n_steps, rb_smem, e_base, acc);
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
@@ -347,14 +269,14 @@ int egnn_launch_radial_backward(egnn_ctx* ctx, int which, const float* rhat_d, i
                      part2, PE, ctx->log2_channels, al);
   EGNN_LAUNCH_CHECK(ctx, "radial_dw2_kernel");
   if ((rc = egnn_launch_reduce_partials(ctx, part2, kc, (long)PE * EGNN_HIDDEN, dW_r2, 1.0f, st))) return rc;
-  const long per_wg = 64L * RB_WAVES;
-  const size_t dpre_lds = (size_t)2 * 64 * RB_BROW4 * sizeof(uint4) + (size_t)RB_WAVES * 32 * RB_AROW * sizeof(float);
+  const long per_wg = 64L * SG_WAVES;
+  const size_t dpre_lds = SG_LDS_BYTES;
   {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(radial_dpre_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)dpre_lds);
     if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(radial_dpre_kernel)");
   }
-  hipLaunchKernelGGL(radial_dpre_kernel, dim3((unsigned)((n_edges + per_wg - 1) / per_wg)), dim3(RB_THREADS), dpre_lds, st,
+  hipLaunchKernelGGL(radial_dpre_kernel, dim3((unsigned)((n_edges + per_wg - 1) / per_wg)), dim3(SG_THREADS), dpre_lds, st,
                      dw, (long)n_edges, W2T, S, PE, (int)(pe_pad / 64));
   EGNN_LAUNCH_CHECK(ctx, "radial_dpre_kernel");
   hipLaunchKernelGGL(radial_dw1_kernel, dim3(r1c), dim3(256), 0, st, rd, (long)n_edges, S, part1, n_rbf,

@@ -206,124 +206,25 @@ __global__ __launch_bounds__(256) void so2_pack_kernel(const float* __restrict__
 }
 
 // ---------------------------------------------------------------------------------------------- 3. GEMM
-// C[e][ct*64 + j] = sum_k A[e][k] B[k][ct*64 + j].  A workgroup = (block of 64 * SO2_WAVES rows, 64-column tile ct);
-// eight waves that all do the same (two per SIMD: the matrix cores of the four SIMDs carry equal loads).
+// C[e][ct*64 + j] = sum_k A[e][k] B[k][ct*64 + j].  A workgroup = (block of 64 * SG_WAVES rows, 64-column tile ct);
+// the contraction itself is sg_contract of stream_gemm.h.
 // Workgroup ids go round-robin over the 8 XCDs, each with its own L2, so the id is decoded such that the column tiles
 // of one block of rows sit on the same XCD with consecutive dispatch slots: they read the same rows of A, once from
 // HBM and then from that L2.  A compute wave owns 64 rows; its 64 x 64 tile of A is fetched in memory order and turned
 // to operand order through a private LDS tile.
-#define SO2_AROW 68
-typedef float so2_f4 __attribute__((ext_vector_type(4)));
-typedef unsigned int so2_u4 __attribute__((ext_vector_type(4)));
-#define SO2_WAVES 8   // waves per workgroup of the GEMM (RB_THREADS = 512 threads), all alike
-__device__ __forceinline__ void so2_fetch8(so2_f4 (&dst)[8], const float* const (&row)[8], int col) {
-#pragma unroll
-  for (int i = 0; i < 8; ++i) dst[i] = *reinterpret_cast<const so2_f4*>(row[i] + col);
-}
-__device__ __forceinline__ void so2_store8(float* tile, const so2_f4 (&v)[8]) {   // rows 4 apart
-#pragma unroll
-  for (int i = 0; i < 8; ++i) *reinterpret_cast<so2_f4*>(tile + 4 * i * SO2_AROW) = v[i];
-}
-__global__ __launch_bounds__(RB_THREADS) void so2_gemm_kernel(const float* __restrict__ A, long M, int K, const uint16_t* __restrict__ T,
+__global__ __launch_bounds__(SG_THREADS) void so2_gemm_kernel(const float* __restrict__ A, long M, int K, const uint16_t* __restrict__ T,
                                                               int n_steps, float* __restrict__ C, int N, int n_ct,
                                                               int n_row_blocks) {
   extern __shared__ uint4 so2_smem[];
-  uint4* sB = so2_smem;
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
   const int ct = idx % n_ct;
   const int row_block = (idx / n_ct) * 8 + xcd;
   if (row_block >= n_row_blocks) return;   // (whole workgroup: the grid is rounded up to a multiple of 8 row blocks)
-  float* sA = reinterpret_cast<float*>(sB + 2 * 64 * RB_BROW4) + (size_t)wave * 32 * SO2_AROW;
-  const int m = lane & 31, hh = lane >> 5;
-  const long e_base = ((long)row_block * SO2_WAVES + wave) * 64;
-  const int frow = lane >> 4, fcol = (lane & 15) * 4;
-  // row pointers of the two 32-row blocks (rows past the end repeat the last row; their results are not stored)
-  const float* fptr0[8];
-  const float* fptr1[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    long e0 = e_base + 4 * i + frow, e1 = e0 + 32;
-    if (e0 >= M) e0 = M - 1;
-    if (e1 >= M) e1 = M - 1;
-    fptr0[i] = A + (size_t)e0 * K;
-    fptr1[i] = A + (size_t)e1 * K;
-  }
+  const long e_base = ((long)row_block * SG_WAVES + wave) * 64;
   float16v acc[2][2];
-#pragma unroll
-  for (int a = 0; a < 2; ++a)
-#pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
-  // The rows of step s + 1 are fetched into the registers of step s as soon as those have been copied to the LDS tile
-  // (row block by row block), so the data is never moved between registers.  Columns past the end of a row are
-  // clamped to the row's last four: the packed weights are zero for contraction indices >= K, and what is read in
-  // their place is finite, so those products vanish.
-  so2_f4 nxt0[8], nxt1[8];
-#define SO2_FETCH(S, NXT, FPTR)                                 \
-  {                                                             \
-    const int n_ = (S) * 64 + fcol;                             \
-    so2_fetch8(NXT, FPTR, n_ < K ? n_ : K - 4);                 \
-  }
-#define SO2_ROW_BLOCK(NXT, FPTR, ACC0, ACC1)                                                                       \
-  {                                                                                                                \
-    so2_store8(sA + frow * SO2_AROW + fcol, NXT);                                                                  \
-    SO2_FETCH(s_next, NXT, FPTR)   /* (the last step fetches itself again: no branch around the loads) */          \
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");                                                \
-    __builtin_amdgcn_wave_barrier();                                                                               \
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");                                                \
-    const float4* arow = reinterpret_cast<const float4*>(sA + m * SO2_AROW + hh * 32);                             \
-    _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                                                \
-      /* both column blocks' pieces of B first: their LDS latency passes while A is cut into pieces */             \
-      const uint4* brow0 = bbase + m * RB_BROW4 + t;                                                               \
-      const uint4* brow1 = brow0 + 32 * RB_BROW4;                                                                  \
-      const uint4 b0[3] = {brow0[0], brow0[8], brow0[16]};                                                         \
-      const uint4 b1[3] = {brow1[0], brow1[8], brow1[16]};                                                         \
-      const float4 u = arow[2 * t], v = arow[2 * t + 1];                                                           \
-      const float xv[8] = {u.x, u.y, u.z, u.w, v.x, v.y, v.z, v.w};                                                \
-      uint4 ah, am, al;                                                                                            \
-      rb_split8(xv, ah, am, al);                                                                                   \
-      rb_mma6x2(ah, am, al, b0, b1, ACC0, ACC1);                                                                   \
-    }                                                                                                              \
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");                                                \
-    __builtin_amdgcn_wave_barrier();                                                                               \
-  }
-  // The 24 KB block of B of a step is brought in by all eight waves together, three 16-byte pieces per thread: loaded
-  // into registers at the top of step s, written to the other LDS buffer after the step's arithmetic, published by the
-  // barrier that opens step s + 1.  (No wave stores to global memory inside the loop, so these loads cost no waiting.)
-  const uint4* tsrc = reinterpret_cast<const uint4*>(T) + (long)ct * n_steps * (64 * 24);
-  so2_u4 bnext[3];
-#pragma unroll
-  for (int i = 0; i < 3; ++i) bnext[i] = *reinterpret_cast<const so2_u4*>(tsrc + i * RB_THREADS + tid);
-#pragma unroll
-  for (int i = 0; i < 3; ++i) {
-    const int u = i * RB_THREADS + tid, row = u / 24, c16 = u - row * 24;
-    *reinterpret_cast<so2_u4*>(sB + row * RB_BROW4 + c16) = bnext[i];
-  }
-  SO2_FETCH(0, nxt0, fptr0)
-  SO2_FETCH(0, nxt1, fptr1)
-  for (int s = 0; s < n_steps; ++s) {
-    rb_release_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-    const uint4* bbase = sB + (s & 1) * (64 * RB_BROW4) + hh * 4;
-    const int s_next = s + 1 < n_steps ? s + 1 : s;
-#pragma unroll
-    for (int i = 0; i < 3; ++i)
-      bnext[i] = *reinterpret_cast<const so2_u4*>(tsrc + (size_t)s_next * (64 * 24) + i * RB_THREADS + tid);
-    SO2_ROW_BLOCK(nxt0, fptr0, acc[0][0], acc[0][1])
-    SO2_ROW_BLOCK(nxt1, fptr1, acc[1][0], acc[1][1])
-    // (after the last step this rewrites a buffer that nobody reads any more)
-    uint4* bdst = sB + ((s + 1) & 1) * (64 * RB_BROW4);
-#pragma unroll
-    for (int i = 0; i < 3; ++i) {
-      const int u = i * RB_THREADS + tid, row = u / 24, c16 = u - row * 24;
-      *reinterpret_cast<so2_u4*>(bdst + row * RB_BROW4 + c16) = bnext[i];
-    }
-  }
-#undef SO2_ROW_BLOCK
-#undef SO2_FETCH
+  sg_contract(A, M, K, reinterpret_cast<const uint4*>(T) + (long)ct * n_steps * (64 * 24), n_steps, so2_smem, e_base, acc);
+  const int m = lane & 31, hh = lane >> 5;
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
@@ -583,7 +484,7 @@ static int so2_transform(egnn_ctx* ctx, const egnn_graph* g, const float* pos, c
   }
 #undef GATHER
   EGNN_LAUNCH_CHECK(ctx, "so2_gather_kernel");
-  const size_t lds = (size_t)2 * 64 * RB_BROW4 * sizeof(uint4) + (size_t)SO2_WAVES * 32 * SO2_AROW * sizeof(float);
+  const size_t lds = SG_LDS_BYTES;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(so2_gemm_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(so2_gemm_kernel)");
@@ -593,10 +494,10 @@ static int so2_transform(egnn_ctx* ctx, const egnn_graph* g, const float* pos, c
     hipLaunchKernelGGL(so2_pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                        W_so2 + so2_w_offset(lmax, E, m), call->T[m], m, lmax, E, K, N, n_steps, n_ct, full);
     EGNN_LAUNCH_CHECK(ctx, "so2_pack_kernel");
-    const long rows_per_wg = 64L * SO2_WAVES;
+    const long rows_per_wg = 64L * SG_WAVES;
     const int n_row_blocks = (int)((n + rows_per_wg - 1) / rows_per_wg);
     const unsigned grid_x = (unsigned)(((n_row_blocks + 7) / 8) * 8 * n_ct);
-    hipLaunchKernelGGL(so2_gemm_kernel, dim3(grid_x), dim3(RB_THREADS), lds, st, call->b.A[m], n, K, call->T[m], n_steps,
+    hipLaunchKernelGGL(so2_gemm_kernel, dim3(grid_x), dim3(SG_THREADS), lds, st, call->b.A[m], n, K, call->T[m], n_steps,
                        call->b.Y[m], N, n_ct, n_row_blocks);
     EGNN_LAUNCH_CHECK(ctx, "so2_gemm_kernel");
   }

@@ -78,3 +78,116 @@ __device__ __forceinline__ void rb_mma6x2(uint4 ah, uint4 am, uint4 al, const ui
   RB_STEP(al, 0) RB_STEP(ah, 2) RB_STEP(am, 1) RB_STEP(am, 0) RB_STEP(ah, 1) RB_STEP(ah, 0)
 #undef RB_STEP
 }
+
+// ---------------------------------------------------------------------------------------------------------------
+// The streaming contraction as a whole: acc[rb][cb] = rows (e_base + 32 rb ..+31) of A [M][K] times the 64-column
+// tile of the small operand whose packed blocks start at `tsrc` (n_steps blocks of 64 contraction indices).
+// A workgroup is SG_WAVES = 8 identical waves of 64 rows each (two per SIMD: the matrix cores of the four SIMDs carry
+// equal loads).  The wave's 64 x 64 tile of A is fetched in memory order, one step ahead (the registers of step s are
+// refilled with step s + 1 as soon as they have been copied to LDS, row block by row block: no register copies), and
+// turned to operand order through a private LDS tile.  The 24 KB block of the small operand of a step is brought in
+// by all waves together, three 16-byte pieces per thread: loaded into registers at the top of step s, written to the
+// other LDS buffer after the step's arithmetic, published by the barrier that opens step s + 1 (no wave stores to
+// global memory inside the loop, so these loads cost no waiting).  Columns past the end of a row of A are clamped to
+// the row's last four: the packed operand is zero for contraction indices >= K and what is read in their place is
+// finite, so those products vanish.  Rows past M repeat row M - 1; the caller does not store them.
+// Dynamic LDS: SG_LDS_BYTES.
+#define SG_WAVES 8
+#define SG_THREADS (SG_WAVES * 64)
+#define SG_AROW 68   // floats per row of the private tile: 64 + 4 (16-byte aligned, rows 4 banks apart)
+#define SG_LDS_BYTES ((size_t)2 * 64 * RB_BROW4 * sizeof(uint4) + (size_t)SG_WAVES * 32 * SG_AROW * sizeof(float))
+typedef float sg_f4 __attribute__((ext_vector_type(4)));
+typedef unsigned int sg_u4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void sg_fetch8(sg_f4 (&dst)[8], const float* const (&row)[8], int col) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) dst[i] = *reinterpret_cast<const sg_f4*>(row[i] + col);
+}
+__device__ __forceinline__ void sg_store8(float* tile, const sg_f4 (&v)[8]) {   // rows 4 apart
+#pragma unroll
+  for (int i = 0; i < 8; ++i) *reinterpret_cast<sg_f4*>(tile + 4 * i * SG_AROW) = v[i];
+}
+
+// one 32-row block of a step: registers -> private tile, refill, tile -> operand order, 4 x (cut, 12 products)
+__device__ __forceinline__ void sg_row_block(float* sA, const uint4* bbase, sg_f4 (&nxt)[8], const float* const (&fptr)[8],
+                                             int next_col, int frow, int fcol, int m, int hh, float16v& acc0,
+                                             float16v& acc1) {
+  sg_store8(sA + frow * SG_AROW + fcol, nxt);
+  sg_fetch8(nxt, fptr, next_col);
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+  const float4* arow = reinterpret_cast<const float4*>(sA + m * SG_AROW + hh * 32);
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    // both column blocks' pieces of the small operand first: their LDS latency passes while A is cut into pieces
+    const uint4* brow0 = bbase + m * RB_BROW4 + t;
+    const uint4* brow1 = brow0 + 32 * RB_BROW4;
+    const uint4 b0[3] = {brow0[0], brow0[8], brow0[16]};
+    const uint4 b1[3] = {brow1[0], brow1[8], brow1[16]};
+    const float4 u = arow[2 * t], v = arow[2 * t + 1];
+    const float xv[8] = {u.x, u.y, u.z, u.w, v.x, v.y, v.z, v.w};
+    uint4 ah, am, al;
+    rb_split8(xv, ah, am, al);
+    rb_mma6x2(ah, am, al, b0, b1, acc0, acc1);
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+  __builtin_amdgcn_wave_barrier();   // reads of the tile are done before the next block overwrites it
+}
+
+__device__ __forceinline__ void sg_contract(const float* __restrict__ A, long M, int K, const uint4* __restrict__ tsrc,
+                                            int n_steps, uint4* smem, long e_base, float16v (&acc)[2][2]) {
+  uint4* sB = smem;                                  // [2][64][RB_BROW4]
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  float* sA = reinterpret_cast<float*>(sB + 2 * 64 * RB_BROW4) + (size_t)wave * 32 * SG_AROW;
+  const int m = lane & 31, hh = lane >> 5;
+  const int frow = lane >> 4, fcol = (lane & 15) * 4;
+  const float* fptr0[8];
+  const float* fptr1[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    long e0 = e_base + 4 * i + frow, e1 = e0 + 32;
+    if (e0 >= M) e0 = M - 1;
+    if (e1 >= M) e1 = M - 1;
+    fptr0[i] = A + (size_t)e0 * K;
+    fptr1[i] = A + (size_t)e1 * K;
+  }
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
+  sg_u4 bnext[3];
+#pragma unroll
+  for (int i = 0; i < 3; ++i) bnext[i] = *reinterpret_cast<const sg_u4*>(tsrc + i * SG_THREADS + tid);
+#pragma unroll
+  for (int i = 0; i < 3; ++i) {
+    const int u = i * SG_THREADS + tid, row = u / 24, c16 = u - row * 24;
+    *reinterpret_cast<sg_u4*>(sB + row * RB_BROW4 + c16) = bnext[i];
+  }
+  sg_f4 nxt0[8], nxt1[8];
+  sg_fetch8(nxt0, fptr0, fcol < K ? fcol : K - 4);
+  sg_fetch8(nxt1, fptr1, fcol < K ? fcol : K - 4);
+  for (int s = 0; s < n_steps; ++s) {
+    rb_release_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    const uint4* bbase = sB + (s & 1) * (64 * RB_BROW4) + hh * 4;
+    const int s_next = s + 1 < n_steps ? s + 1 : s;   // (the last step fetches itself again: no branch around loads)
+    const int n_next = s_next * 64 + fcol;
+    const int next_col = n_next < K ? n_next : K - 4;
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+      bnext[i] = *reinterpret_cast<const sg_u4*>(tsrc + (size_t)s_next * (64 * 24) + i * SG_THREADS + tid);
+    sg_row_block(sA, bbase, nxt0, fptr0, next_col, frow, fcol, m, hh, acc[0][0], acc[0][1]);
+    sg_row_block(sA, bbase, nxt1, fptr1, next_col, frow, fcol, m, hh, acc[1][0], acc[1][1]);
+    // (after the last step this rewrites a buffer that nobody reads any more)
+    uint4* bdst = sB + ((s + 1) & 1) * (64 * RB_BROW4);
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+      const int u = i * SG_THREADS + tid, row = u / 24, c16 = u - row * 24;
+      *reinterpret_cast<sg_u4*>(bdst + row * RB_BROW4 + c16) = bnext[i];
+    }
+  }
+}
