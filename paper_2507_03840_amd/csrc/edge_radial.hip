@@ -162,8 +162,13 @@ __device__ __forceinline__ void lds_barrier_acquire() {
 }
 
 // One 32-column block: wait for its rows of W_r2 in LDS, then 4 steps x 6 piece products per 32-row block.
+// STORE: after each step a quarter of the previous block's results (prev) goes to memory: out_prev is the wave's
+// first row at the block's first column (the same for all lanes), lane_off the lane's own offset, ld the row stride
+// (w is written once and read once by another kernel: non-temporal stores).
+template <bool STORE>
 __device__ __forceinline__ void rw_block(const uint4* __restrict__ sB_nb, const uint4 (&a_frag)[RW_MB][3][4], int m,
-                                         int hh, float16v (&acc)[RW_MB]) {
+                                         int hh, float16v (&acc)[RW_MB], const float16v (&prev)[RW_MB],
+                                         float* __restrict__ out_prev, unsigned lane_off, size_t ld) {
   lds_barrier_acquire();
   uint4 b_frag[3][4];
   {
@@ -188,6 +193,23 @@ __device__ __forceinline__ void rw_block(const uint4* __restrict__ sB_nb, const 
       for (int mb = 0; mb < RW_MB; ++mb)
         acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a_frag[mb][pa[q]][t]),
                                                           as_bf16x8(b_frag[pb[q]][t]), acc[mb], 0, 0, 0);
+    if constexpr (STORE) {
+      static_assert(RW_MB == 2, "a quarter of the previous block per contraction step");
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int idx = 8 * t + j, mb = idx >> 4, i = idx & 15;
+        float* rowp = out_prev + (size_t)(32 * mb + 8 * (i >> 2) + (i & 3)) * ld;   // the same for all lanes
+        __builtin_nontemporal_store(prev[mb][i], rowp + lane_off);
+      }
+    }
+  }
+  if constexpr (STORE) {
+    // keep the stores spread between the matrix-core instructions (the scheduler would otherwise bunch them up)
+#pragma unroll
+    for (int g = 0; g < 16; ++g) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);   // 3 MFMA
+      __builtin_amdgcn_sched_group_barrier(0x040, 2, 0);   // 2 global stores
+    }
   }
 }
 
@@ -207,7 +229,7 @@ __global__ __launch_bounds__(RW_THREADS) void radial_weights_kernel(const float4
   }
   __syncthreads();
 
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n_blocks = (PE + 31) >> 5;
 
   if (wave == RW_COMPUTE_WAVES) {
@@ -275,30 +297,46 @@ __global__ __launch_bounds__(RW_THREADS) void radial_weights_kernel(const float4
   }
 
   if constexpr (!HALF) {
-    float* const out_base = w + (size_t)(e_base + 4 * hh) * PE + m;
-    for (int nb = 0; nb < n_blocks; ++nb) {
-      float16v acc[RW_MB];
-      rw_block(sB[nb & 1], a_frag, m, hh, acc);
-      const int n = nb * 32 + m;
-      if (n < PE) {
-        float* out = out_base + nb * 32;
-        // w is written once and read once by another kernel: non-temporal stores (measured: 0.82 -> 0.72 ms)
-        if (all_rows) {
+    // Software-pipelined over column blocks: while the matrix cores work on block nb, the wave stores block nb - 1
+    // from a second set of accumulators, a quarter of it after each of the four contraction steps.  Without this all
+    // waves of the workgroup (kept in step by the barriers) store at the same time and compute at the same time, and
+    // neither the matrix pipes nor the memory pipeline are fed evenly.
+    float* const wave_base = w + (size_t)e_base * PE;                    // the same for all lanes
+    const unsigned lane_off = (unsigned)(4 * hh * PE + m);
+    float* const out_base = wave_base + lane_off;
+    auto store_block = [&](const float16v (&acc)[RW_MB], int nb) {      // general case: ragged rows / last columns
+      if (nb * 32 + m >= PE || !any_row) return;
+      float* out = out_base + nb * 32;
 #pragma unroll
-          for (int mb = 0; mb < RW_MB; ++mb)
+      for (int mb = 0; mb < RW_MB; ++mb)
 #pragma unroll
-            for (int i = 0; i < 16; ++i)
-              __builtin_nontemporal_store(acc[mb][i], out + (size_t)(32 * mb + 8 * (i >> 2) + (i & 3)) * PE);
-        } else if (any_row) {
-#pragma unroll
-          for (int mb = 0; mb < RW_MB; ++mb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const int r = 32 * mb + 8 * (i >> 2) + (i & 3);      // row relative to e_base + 4*hh
-              if (e_base + 4 * hh + r < n_edges) __builtin_nontemporal_store(acc[mb][i], out + (size_t)r * PE);
-            }
+        for (int i = 0; i < 16; ++i) {
+          const int r = 32 * mb + 8 * (i >> 2) + (i & 3);               // row relative to e_base + 4*hh
+          if (all_rows || e_base + 4 * hh + r < n_edges) __builtin_nontemporal_store(acc[mb][i], out + (size_t)r * PE);
         }
+    };
+    // block nb -> acc, block nb - 1 (in prev) -> memory
+    auto step = [&](float16v (&acc)[RW_MB], const float16v (&prev)[RW_MB], int nb) {
+      const bool fast = all_rows && nb * 32 <= PE;                      // block nb - 1 lies wholly inside the row
+      if (fast)
+        rw_block<true>(sB[nb & 1], a_frag, m, hh, acc, prev, wave_base + (nb - 1) * 32, lane_off, (size_t)PE);
+      else {
+        rw_block<false>(sB[nb & 1], a_frag, m, hh, acc, prev, nullptr, 0, 0);
+        store_block(prev, nb - 1);
       }
+    };
+    float16v acc0[RW_MB], acc1[RW_MB];
+    rw_block<false>(sB[0], a_frag, m, hh, acc0, acc0, nullptr, 0, 0);
+    int nb = 1;
+    for (; nb + 1 < n_blocks; nb += 2) {
+      step(acc1, acc0, nb);
+      step(acc0, acc1, nb + 1);
+    }
+    if (nb < n_blocks) {
+      step(acc1, acc0, nb);
+      store_block(acc1, nb);
+    } else {
+      store_block(acc0, n_blocks - 1);
     }
   } else {
     const int row_words = w_half_row_words(PE);
@@ -306,13 +344,13 @@ __global__ __launch_bounds__(RW_THREADS) void radial_weights_kernel(const float4
     for (int nb = 0; nb < n_blocks; nb += 2) {
       float16v acc[RW_MB];
       uint32_t word[RW_MB][16];
-      rw_block(sB[0], a_frag, m, hh, acc);          // nb is even
+      rw_block<false>(sB[0], a_frag, m, hh, acc, acc, nullptr, 0, 0);          // nb is even
 #pragma unroll
       for (int mb = 0; mb < RW_MB; ++mb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) word[mb][i] = w_half_bits(acc[mb][i]);
       if (nb + 1 < n_blocks) {                      // (the same for every wave of the workgroup, loader included)
-        rw_block(sB[1], a_frag, m, hh, acc);
+        rw_block<false>(sB[1], a_frag, m, hh, acc, acc, nullptr, 0, 0);
 #pragma unroll
         for (int mb = 0; mb < RW_MB; ++mb)
 #pragma unroll
