@@ -30,6 +30,21 @@ struct ReadoutTabs {
   int nq, n_slots, n_vrows, nnz;
 };
 
+// The lanes of a slot exchange data through LDS.  Up to 64 channels a slot lies inside one wavefront, whose LDS
+// accesses execute in program order: a wave-level fence is all the synchronisation needed, and the waves of the
+// workgroup run free of each other (their memory phases and their arithmetic phases overlap).  Wider slots span
+// wavefronts and need the workgroup barrier.
+template <int log2E>
+__device__ __forceinline__ void readout_slot_sync() {
+  if constexpr (log2E <= 6) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+  } else {
+    __syncthreads();
+  }
+}
+
 // HALF: w in half precision (layout of w_half.h)
 template <int LMAX, int log2E, bool HALF>
 __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ src, const int* __restrict__ dst,
@@ -69,6 +84,7 @@ __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ sr
     s_uq[i] = tb.unc_q[i];
     s_uc[i] = tb.unc_c[i];
   }
+  __syncthreads();
 
   const long k_base = (long)blockIdx.x * n_slots * RO_ITERS;
   for (int it = 0; it < RO_ITERS; ++it) {
@@ -97,7 +113,7 @@ __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ sr
 #pragma unroll
       for (int i = 0; i < RO_D; ++i) su[i * us + c] = o[i];
     }
-    __syncthreads();   // (also orders the table fill before the first use)
+    readout_slot_sync<log2E>();
     if (live) {
       for (int q = c; q < tb.nq; q += E) {
         const float4* ur = reinterpret_cast<const float4*>(su + s_urow[q]);
@@ -114,7 +130,7 @@ __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ sr
         sq[q] = (s0 + s1) + (s2 + s3);
       }
     }
-    __syncthreads();
+    readout_slot_sync<log2E>();
     if (live) {
       float* out = H + (size_t)k * tb.nq;
       for (int q = c; q < tb.nq; q += E) {
@@ -123,8 +139,8 @@ __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ sr
         __builtin_nontemporal_store(sum, out + q);
       }
     }
-    // the next iteration overwrites su before its first barrier and sq after it: sq is safe (barrier in between),
-    // su needs the collapse of this iteration to be over -- it is, the barrier above
+    // the next iteration overwrites su before its first synchronisation and sq after it: sq is safe (a
+    // synchronisation in between), su needs the collapse of this iteration to be over -- it is, by the one above
   }
 }
 

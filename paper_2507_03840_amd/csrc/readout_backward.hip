@@ -26,6 +26,18 @@ struct ReadoutBwdTabs {
   int v_off[EGNN_L_READOUT + 2];
 };
 
+// Synchronisation among the lanes of a slot: up to 64 channels the slot lies inside one wavefront, whose LDS accesses
+// execute in program order, so a wave-level fence suffices and the waves of the workgroup run free of each other.
+__device__ __forceinline__ void rob_slot_sync(int log2E) {
+  if (log2E <= 6) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+  } else {
+    __syncthreads();
+  }
+}
+
 template <int L>
 __device__ __forceinline__ void collapse_adjoint(const ReadoutBwdTabs& tb, const float* __restrict__ V,
                                                  const float* sq, const int* s_vq, float* sdV, const float* u,
@@ -90,7 +102,7 @@ __global__ __launch_bounds__(256) void readout_backward_kernel(
         sq[q] = sum;
       }
     }
-    __syncthreads();
+    rob_slot_sync(log2E);
     if (live) {
       const int s = src[k], d = dst[k];
       const float* zsp = zs + ((size_t)s * D << log2E) + c;
