@@ -81,7 +81,7 @@ int egnn_launch_row_scan(egnn_ctx*, int* row_ptr, int n, hipStream_t);
 int egnn_launch_fill_int(egnn_ctx*, int* p, long n, int v, hipStream_t);
 int egnn_launch_segsum_rows(egnn_ctx*, const float* rows, const int* ptr, const int* perm, float* out, int n_segments,
                             int row_len, hipStream_t);
-int egnn_launch_reduce_partials(egnn_ctx*, const float* partial, int n_partials, long n, float* out, float scale,
+int egnn_launch_reduce_partials(egnn_ctx*, float* partial /* scratch, may be overwritten */, int n_partials, long n, float* out, float scale,
                                 hipStream_t);
 size_t egnn_transpose_ws_bytes(int64_t n_edges, int32_t n_total);
 int egnn_launch_tp_backward(egnn_ctx*, const egnn_graph*, const int* col_ptr, const int* perm, const float* rhat_d,

@@ -68,23 +68,46 @@ __global__ __launch_bounds__(256) void edge_rows_segsum_kernel(const float* __re
   }
 }
 
-// out[i] = scale * sum_b partial[b][i] in a fixed order: eight interleaved running sums (b mod 8), so that eight
-// loads are in flight per thread, combined pairwise at the end.
-__global__ void reduce_partials_kernel(const float* __restrict__ partial, int n_partials, long n,
+// out[i] = scale * sum_b partial[b * stride][i] in a fixed order: eight interleaved running sums (b mod 8), so that
+// eight loads are in flight per thread, combined pairwise at the end.
+__global__ void reduce_partials_kernel(const float* __restrict__ partial, int n_partials, long stride, long n,
                                        float* __restrict__ out, float scale) {
   const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
   float acc[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+  const long step = stride * n;
   int b = 0;
   for (; b + 8 <= n_partials; b += 8) {
     float v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(partial + (long)(b + u) * n + i);
+    for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(partial + (long)(b + u) * step + i);
 #pragma unroll
     for (int u = 0; u < 8; ++u) acc[u] += v[u];
   }
-  for (int u = 0; b < n_partials; ++b, ++u) acc[u] += partial[(long)b * n + i];
+  for (int u = 0; b < n_partials; ++b, ++u) acc[u] += partial[(long)b * step + i];
   out[i] = (((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]))) * scale;
+}
+
+// First level for long lists of partials: blockIdx.y takes RP_CHUNK consecutive rows and leaves their sum in the
+// first of them (every element of the buffer is read and written by one thread only).
+#define RP_CHUNK 32
+__global__ void reduce_partials_chunk_kernel(float* __restrict__ partial, int n_partials, long n) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int b0 = blockIdx.y * RP_CHUNK;
+  const int cnt = n_partials - b0 < RP_CHUNK ? n_partials - b0 : RP_CHUNK;
+  float* base = partial + (long)b0 * n + i;
+  float acc[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+  int b = 0;
+  for (; b + 8 <= cnt; b += 8) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = base[(long)(b + u) * n];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc[u] += v[u];
+  }
+  for (int u = 0; b < cnt; ++b, ++u) acc[u] += base[(long)b * n];
+  base[0] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
 }
 
 #define LOSS_PER_BLOCK 4096
@@ -140,11 +163,21 @@ int egnn_launch_segsum_rows(egnn_ctx* ctx, const float* rows, const int* ptr, co
   return EGNN_OK;
 }
 
-int egnn_launch_reduce_partials(egnn_ctx* ctx, const float* partial, int n_partials, long n, float* out,
-                                float scale, hipStream_t st) {
+// `partial` is scratch: long lists are summed in two levels, the first one in place.
+int egnn_launch_reduce_partials(egnn_ctx* ctx, float* partial, int n_partials, long n, float* out, float scale,
+                                hipStream_t st) {
   if (n <= 0) return EGNN_OK;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, partial,
-                     n_partials, n, out, scale);
+  const unsigned gx = (unsigned)((n + 255) / 256);
+  long stride = 1;
+  if (n_partials > 8 * RP_CHUNK) {
+    const int n_chunks = (n_partials + RP_CHUNK - 1) / RP_CHUNK;
+    hipLaunchKernelGGL(reduce_partials_chunk_kernel, dim3(gx, (unsigned)n_chunks), dim3(256), 0, st, partial,
+                       n_partials, n);
+    EGNN_LAUNCH_CHECK(ctx, "reduce_partials_chunk_kernel");
+    n_partials = n_chunks;
+    stride = RP_CHUNK;
+  }
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(gx), dim3(256), 0, st, partial, n_partials, stride, n, out, scale);
   EGNN_LAUNCH_CHECK(ctx, "reduce_partials_kernel");
   return EGNN_OK;
 }

@@ -6,13 +6,14 @@
 //     dV[o][c]  += sum_M dq[o][M] u[(L,M)][c]              (summed over all edges)
 //     du[(L,M)][c] = sum_o V[o][c] dq[o][M],   du' = D du
 //     (gv', gw) = Mid^T(D z, w ; du'),   dz = D^T gv'   (per edge row; summed by source and by destination later)
-// A group of E lanes works on one edge, lane = channel: every rotation runs per lane on all lanes alike.  The
-// collapsed quantities are shared through LDS; the loops over the rows o of V run per coupled degree L with the
-// (L, M) register index fixed at compile time.
+// A group of E lanes (a slot) works on one edge, lane = channel: every rotation runs per lane on all lanes alike.
+// The edge's block of dH is staged in LDS (coalesced), dq is shared through LDS; the loops over the rows o of V run
+// per coupled degree L with the (L, M) register index fixed at compile time.
 #include "egnn_internal.h"
 #include "bond_frame.h"
 
-#define ROB_MAX_WG 1024   // workgroups (= partial results of dV)
+#define ROB_MAX_WG 8192   // workgroups (= partial results of dV): many short ones, so that the last round of
+                          // resident workgroups is nearly as full as the others
 #define ROB_D 25
 
 struct ReadoutBwdTabs {
@@ -38,10 +39,17 @@ __device__ __forceinline__ void rob_slot_sync(int log2E) {
   }
 }
 
+// Adjoint of the collapse for the rows o of V that belong to coupled degree L.  The partial dV of the wavefront is
+// kept in LDS, one value per (row, channel): the slots of a wavefront (same channel, different edges) add their
+// contributions with a fixed-order butterfly first, then the first slot updates the sum.
 template <int L>
 __device__ __forceinline__ void collapse_adjoint(const ReadoutBwdTabs& tb, const float* __restrict__ V,
-                                                 const float* sq, const int* s_vq, float* sdV, const float* u,
-                                                 float* du, int c, int log2E) {
+                                                 const float* __restrict__ sq, const int* __restrict__ s_vq,
+                                                 float* __restrict__ sdVw, const float* u, float* du, int c, int wl,
+                                                 int log2E) {
+  const int E = 1 << log2E;
+  const int log2Ew = log2E < 6 ? log2E : 6;
+  const bool writer = wl < (1 << log2Ew);
   for (int o = tb.v_off[L]; o < tb.v_off[L + 1]; ++o) {
     const float* q = sq + s_vq[o];
     const float vv = V[((size_t)o << log2E) + c];
@@ -52,16 +60,66 @@ __device__ __forceinline__ void collapse_adjoint(const ReadoutBwdTabs& tb, const
       dot += qv * u[L * L + M];
       du[L * L + M] += vv * qv;
     }
-    sdV[(o << log2E) + c] += dot;
+    for (int off = E; off < 64; off <<= 1) dot += __shfl_xor(dot, off);
+    if (writer) sdVw[(o << log2Ew) + wl] += dot;
   }
 }
 
-template <int LMAX>
-__global__ __launch_bounds__(256) void readout_backward_kernel(
+// The bond-frame product and its adjoint, one input degree at a time.  The rows of z of a degree, of the rotated
+// input and of the input gradient are its own, and its weight gradients are one contiguous run, so a degree is
+// loaded, rotated, used and (in the adjoint) rotated back and stored before the next one is touched: the weights
+// stay in registers throughout (a second read would come from HBM), but at most two nine-component rows and ten
+// weight gradients are live next to them instead of everything at once.  The price is a second read of z (from
+// cache) and a second rotation; the gain is that three waves share a SIMD and hide each other's latency.
+template <int L1>
+__device__ __forceinline__ void rob_load_rotate(const float* __restrict__ zsp, const float* __restrict__ ztp,
+                                                const BondTrig& t, float* vl, int log2E) {
+#pragma unroll
+  for (int i = 0; i < 2 * L1 + 1; ++i)
+    vl[i] = zsp[(size_t)(L1 * L1 + i) << log2E] + ztp[(size_t)(L1 * L1 + i) << log2E];
+  egnn_to_bond_frame_l<L1>(vl, t);
+}
+template <int LMAX, int L1>
+struct RobFwdDegree {
+  using Mid = typename ReadoutMid<LMAX>::T;
+  __device__ __forceinline__ static void run(const float* __restrict__ zsp, const float* __restrict__ ztp,
+                                             const BondTrig& t, float* u, const float* wr, int log2E) {
+    constexpr int first = Mid::CHUNK_FIRST[L1];
+    float vl[2 * L1 + 1];
+    rob_load_rotate<L1>(zsp, ztp, t, vl, log2E);
+    Mid::template run_l1<L1>(vl, wr + first, u);
+    if constexpr (L1 < LMAX) RobFwdDegree<LMAX, L1 + 1>::run(zsp, ztp, t, u, wr, log2E);
+  }
+};
+template <int LMAX, int L1>
+struct RobBwdDegree {
+  using Mid = typename ReadoutMid<LMAX>::T;
+  __device__ __forceinline__ static void run(const float* __restrict__ zsp, const float* __restrict__ ztp,
+                                             const BondTrig& t, const float* du, const float* wr,
+                                             float* __restrict__ dwp, float* __restrict__ dzp, bool live, int log2E) {
+    constexpr int first = Mid::CHUNK_FIRST[L1], count = Mid::CHUNK_COUNT[L1];
+    float vl[2 * L1 + 1], gvl[2 * L1 + 1], gw[count];
+    rob_load_rotate<L1>(zsp, ztp, t, vl, log2E);
+    Mid::template run_bwd_l1<L1>(vl, wr + first, du, gvl, gw);
+    egnn_from_bond_frame_l<L1>(gvl, t);
+    if (live) {
+#pragma unroll
+      for (int p = 0; p < count; ++p) __builtin_nontemporal_store(gw[p], dwp + ((size_t)(first + p) << log2E));
+#pragma unroll
+      for (int i = 0; i < 2 * L1 + 1; ++i) __builtin_nontemporal_store(gvl[i], dzp + ((size_t)(L1 * L1 + i) << log2E));
+    }
+    if constexpr (L1 < LMAX) RobBwdDegree<LMAX, L1 + 1>::run(zsp, ztp, t, du, wr, dwp, dzp, live, log2E);
+  }
+};
+
+// LE = log2(channels): a template parameter so that the row offsets of w, z, dw and dz are immediates.
+template <int LMAX, int LE>
+__global__ __launch_bounds__(256, 3) void readout_backward_kernel(
     const int* __restrict__ src, const int* __restrict__ dst, const float4* __restrict__ rhat_d,
     const float* __restrict__ zs, const float* __restrict__ zt, const float* __restrict__ w,
     const float* __restrict__ V, ReadoutBwdTabs tb, const float* __restrict__ dH, float* __restrict__ dz,
-    float* __restrict__ dw, float* __restrict__ dV_partial, long n_edges, int log2E, int iters) {
+    float* __restrict__ dw, float* __restrict__ dV_partial, long n_edges, int iters) {
+  constexpr int log2E = LE;
   using Mid = typename ReadoutMid<LMAX>::T;
   constexpr int D = (LMAX + 1) * (LMAX + 1);
   constexpr int P = Mid::P;
@@ -69,12 +127,17 @@ __global__ __launch_bounds__(256) void readout_backward_kernel(
   const int E = 1 << log2E;
   const int tid = threadIdx.x;
   const int c = tid & (E - 1), slot = tid >> log2E;
+  const int wl = tid & 63, wave = tid >> 6;
   const int n_slots = 256 >> log2E;
-  float* sq = smem + (size_t)slot * tb.nq;                                           // [nq] per slot
-  float* sdV = smem + (size_t)n_slots * tb.nq + ((size_t)slot * tb.n_vrows << log2E);  // [n_vrows][E] per slot
-  for (int o = 0; o < tb.n_vrows; ++o) sdV[(o << log2E) + c] = 0.0f;
+  const int log2Ew = log2E < 6 ? log2E : 6;                  // channels of a slot that one wavefront covers
+  const int nvw = tb.n_vrows << log2Ew;
+  float* sq = smem + (size_t)slot * tb.nq;                   // [nq] per slot: dq
+  float* sh = smem + (size_t)(n_slots + slot) * tb.nq;       // [nq] per slot: the edge's block of dH
+  float* sdV_all = smem + (size_t)2 * n_slots * tb.nq;       // [4 waves][n_vrows][2^log2Ew]
+  float* sdVw = sdV_all + (size_t)wave * nvw;
+  for (int i = wl; i < nvw; i += 64) sdVw[i] = 0.0f;
   // the index tables, once per workgroup
-  int* s_ptr = reinterpret_cast<int*>(smem + (size_t)n_slots * tb.nq + ((size_t)n_slots * tb.n_vrows << log2E));  // [nq + 1]
+  int* s_ptr = reinterpret_cast<int*>(sdV_all + (size_t)4 * nvw);  // [nq + 1]
   int* s_h = s_ptr + tb.nq + 1;                            // [nnz]
   float* s_c = reinterpret_cast<float*>(s_h + tb.nnz);     // [nnz]
   int* s_vq = reinterpret_cast<int*>(s_c + tb.nnz);        // [n_vrows]
@@ -88,61 +151,65 @@ __global__ __launch_bounds__(256) void readout_backward_kernel(
 
   const long k_base = (long)blockIdx.x * n_slots * iters;
   for (int it = 0; it < iters; ++it) {
-    const long k = k_base + (long)it * n_slots + slot;
-    const bool live = k < n_edges;
-    BondTrig t;
-    float4 g = make_float4(0.f, 0.f, 1.f, 1.f);
-    if (live) {
-      g = rhat_d[k];
-      egnn_bond_trig<4>(g.x, g.y, g.z, t);
+    // A slot past the end works on the last edge with dH = 0 (every lane takes part in the butterflies) and
+    // stores nothing.
+    const long k_own = k_base + (long)it * n_slots + slot;
+    const bool live = k_own < n_edges;
+    const long k = live ? k_own : n_edges - 1;
+    // Every load of the edge that comes from HBM is issued here, ahead of the first wait: a wave's memory counter
+    // retires loads and stores in issue order, so that wait also sits out the stores of the previous edge -- one
+    // round trip per edge instead of one for dH and another for the weights.
+    const float4 g = rhat_d[k];
+    const int s = src[k], d = dst[k];
+    const float* wp = w + ((size_t)k * P << log2E) + c;
+    float wr[P];
+#pragma unroll
+    for (int p = 0; p < P; ++p) wr[p] = __builtin_nontemporal_load(wp + ((size_t)p << log2E));
+    {
       const float* hrow = dH + (size_t)k * tb.nq;
-      for (int q = c; q < tb.nq; q += E) {
-        float sum = 0.0f;
-        for (int n = s_ptr[q]; n < s_ptr[q + 1]; ++n) sum += s_c[n] * hrow[s_h[n]];
-        sq[q] = sum;
-      }
+      for (int q = c; q < tb.nq; q += E) sh[q] = live ? hrow[q] : 0.0f;
     }
     rob_slot_sync(log2E);
-    if (live) {
-      const int s = src[k], d = dst[k];
+    for (int q = c; q < tb.nq; q += E) {
+      float sum = 0.0f;
+      for (int n = s_ptr[q]; n < s_ptr[q + 1]; ++n) sum += s_c[n] * sh[s_h[n]];
+      sq[q] = sum;
+    }
+    rob_slot_sync(log2E);
+    {
+      BondTrig t;
+      egnn_bond_trig<4>(g.x, g.y, g.z, t);
       const float* zsp = zs + ((size_t)s * D << log2E) + c;
       const float* ztp = zt + ((size_t)d * D << log2E) + c;
-      const float* wp = w + ((size_t)k * P << log2E) + c;
-      float v[D], wr[P], u[ROB_D], du[ROB_D];
+      float u[ROB_D], du[ROB_D];
 #pragma unroll
-      for (int p = 0; p < P; ++p) wr[p] = wp[(size_t)p << log2E];
-#pragma unroll
-      for (int i = 0; i < D; ++i) v[i] = zsp[(size_t)i << log2E] + ztp[(size_t)i << log2E];
-      egnn_to_bond_frame<LMAX>(v, t);
-      Mid::run(v, wr, u);
+      for (int i = 0; i < ROB_D; ++i) u[i] = 0.0f;
+      RobFwdDegree<LMAX, 0>::run(zsp, ztp, t, u, wr, log2E);
       egnn_from_bond_frame<4>(u, t);
 #pragma unroll
       for (int i = 0; i < ROB_D; ++i) du[i] = 0.0f;
-      collapse_adjoint<0>(tb, V, sq, s_vq, sdV, u, du, c, log2E);
-      collapse_adjoint<1>(tb, V, sq, s_vq, sdV, u, du, c, log2E);
-      collapse_adjoint<2>(tb, V, sq, s_vq, sdV, u, du, c, log2E);
-      collapse_adjoint<3>(tb, V, sq, s_vq, sdV, u, du, c, log2E);
-      collapse_adjoint<4>(tb, V, sq, s_vq, sdV, u, du, c, log2E);
+      collapse_adjoint<0>(tb, V, sq, s_vq, sdVw, u, du, c, wl, log2E);
+      collapse_adjoint<1>(tb, V, sq, s_vq, sdVw, u, du, c, wl, log2E);
+      collapse_adjoint<2>(tb, V, sq, s_vq, sdVw, u, du, c, wl, log2E);
+      collapse_adjoint<3>(tb, V, sq, s_vq, sdVw, u, du, c, wl, log2E);
+      collapse_adjoint<4>(tb, V, sq, s_vq, sdVw, u, du, c, wl, log2E);
       egnn_to_bond_frame<4>(du, t);
-      float gv[D], gw[P];
-      Mid::run_bwd(v, wr, du, gv, gw);
-      egnn_from_bond_frame<LMAX>(gv, t);
-      float* dzp = dz + ((size_t)k * D << log2E) + c;
-      float* dwp = dw + ((size_t)k * P << log2E) + c;
-#pragma unroll
-      for (int i = 0; i < D; ++i) __builtin_nontemporal_store(gv[i], dzp + ((size_t)i << log2E));
-#pragma unroll
-      for (int p = 0; p < P; ++p) __builtin_nontemporal_store(gw[p], dwp + ((size_t)p << log2E));
+      RobBwdDegree<LMAX, 0>::run(zsp, ztp, t, du, wr, dw + ((size_t)k * P << log2E) + c,
+                                 dz + ((size_t)k * D << log2E) + c, live, log2E);
     }
-    __syncthreads();
+    rob_slot_sync(log2E);   // sq and sh are rewritten by the next edge
   }
-  // one partial [n_vrows][E] per workgroup: its slots added in fixed order
+  __syncthreads();
+  // one partial [n_vrows][E] per workgroup: the wavefronts that cover a channel added in fixed order
   const int nv = tb.n_vrows << log2E;
-  const float* all = smem + (size_t)n_slots * tb.nq;
+  const int waves_per_slot = E > 64 ? E >> 6 : 1;
   float* out = dV_partial + (size_t)blockIdx.x * nv;
   for (int idx = tid; idx < nv; idx += 256) {
+    const int o = idx >> log2E, cc = idx & (E - 1);
+    const int part = cc >> 6, cl = cc & ((1 << log2Ew) - 1);
     float sum = 0.0f;
-    for (int sidx = 0; sidx < n_slots; ++sidx) sum += all[(size_t)sidx * nv + idx];
+    for (int wv = 0; wv < 4; ++wv)
+      if ((wv & (waves_per_slot - 1)) == part) sum += sdV_all[(size_t)wv * nvw + (o << log2Ew) + cl];
     out[idx] = sum;
   }
 }
@@ -195,29 +262,41 @@ int egnn_launch_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const float
   tb.vrow_qoff = tb.slot_qoff + ctx->n_slots;
   tb.uncT_c = tab_f;
   const int n_slots = 256 / E;
-  const size_t shmem = ((size_t)n_slots * nq + (size_t)n_slots * n_vrows * E) * sizeof(float) +
+  const int Ew = E < 64 ? E : 64;
+  const size_t shmem = ((size_t)2 * n_slots * nq + (size_t)4 * n_vrows * Ew) * sizeof(float) +
                        ((size_t)nq + 1 + 2 * (size_t)nnz + n_vrows) * sizeof(int);
   const long grid_x = rob_grid(ctx, n);
   dim3 grid((unsigned)grid_x), block(256);
   const float4* rd = reinterpret_cast<const float4*>(rhat_d);
-#define LAUNCH(L)                                                                                                 \
+#define LAUNCH(L, LE_)                                                                                            \
   do {                                                                                                            \
+    auto kern = readout_backward_kernel<L, LE_>;                                                                  \
     if (shmem > 64 * 1024) {                                                                                      \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(readout_backward_kernel<L>),               \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                     \
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);                 \
       if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(readout_backward_kernel)");         \
     }                                                                                                             \
-    hipLaunchKernelGGL(readout_backward_kernel<L>, grid, block, shmem, stream, g->src, g->dst, rd, zs, zt, w, V, \
-                       tb, dH, dz, dw, partial, n, ctx->log2_channels, rob_iters(ctx, n));                        \
+    hipLaunchKernelGGL(kern, grid, block, shmem, stream, g->src, g->dst, rd, zs, zt, w, V, tb, dH, dz, dw,        \
+                       partial, n, rob_iters(ctx, n));                                                            \
   } while (0)
+#define CASES(L)                                                                \
+  switch (ctx->log2_channels) {                                                 \
+    case 3: LAUNCH(L, 3); break;                                                \
+    case 4: LAUNCH(L, 4); break;                                                \
+    case 5: LAUNCH(L, 5); break;                                                \
+    case 6: LAUNCH(L, 6); break;                                                \
+    case 7: LAUNCH(L, 7); break;                                                \
+    default: return egnn_fail(ctx, EGNN_EINVAL, "readout_backward: channels out of range"); \
+  }
   switch (ctx->desc.lmax) {
-    case 0: LAUNCH(0); break;
-    case 1: LAUNCH(1); break;
-    case 2: LAUNCH(2); break;
-    case 3: LAUNCH(3); break;
-    case 4: LAUNCH(4); break;
+    case 0: CASES(0); break;
+    case 1: CASES(1); break;
+    case 2: CASES(2); break;
+    case 3: CASES(3); break;
+    case 4: CASES(4); break;
     default: return egnn_fail(ctx, EGNN_EINVAL, "readout_backward: lmax out of range");
   }
+#undef CASES
 #undef LAUNCH
   EGNN_LAUNCH_CHECK(ctx, "readout_backward_kernel");
   return egnn_launch_reduce_partials(ctx, partial, (int)grid_x, (long)n_vrows * E, dV, 1.0f, stream);
