@@ -17,27 +17,27 @@
 template <int LMAX, int L1>
 struct TpBwdDegree {
   using Mid = typename LayerMid<LMAX>::T;
-  __device__ __forceinline__ static void run(const float* v, const float* go, float* gv, const float* __restrict__ wp,
+  __device__ __forceinline__ static void run(const float* v, const float* go, float* gv, const float* wr,
                                              float* __restrict__ dwp, int log2E) {
     constexpr int first = Mid::CHUNK_FIRST[L1], count = Mid::CHUNK_COUNT[L1];
-    float wr[count], gw[count];
-#pragma unroll
-    for (int p = 0; p < count; ++p) wr[p] = __builtin_nontemporal_load(wp + ((size_t)(first + p) << log2E));
-    Mid::template run_bwd_l1<L1>(v + L1 * L1, wr, go, gv + L1 * L1, gw);
+    float gw[count];
+    Mid::template run_bwd_l1<L1>(v + L1 * L1, wr + first, go, gv + L1 * L1, gw);
 #pragma unroll
     for (int p = 0; p < count; ++p) __builtin_nontemporal_store(gw[p], dwp + ((size_t)(first + p) << log2E));
-    if constexpr (L1 < LMAX) TpBwdDegree<LMAX, L1 + 1>::run(v, go, gv, wp, dwp, log2E);
+    if constexpr (L1 < LMAX) TpBwdDegree<LMAX, L1 + 1>::run(v, go, gv, wr, dwp, log2E);
   }
 };
 
-template <int LMAX>
+// LE = log2(channels): a template parameter so that the row offsets of w, dw, h and da are immediates.
+template <int LMAX, int LE>
 __global__ __launch_bounds__(256, 2) void tp_backward_kernel(const int* __restrict__ col_ptr, const int* __restrict__ perm,
                                                              const int* __restrict__ dst,
                                                              const float4* __restrict__ rhat_d,
                                                              const float* __restrict__ h, const float* __restrict__ w,
                                                              const float* __restrict__ da, float* __restrict__ dh,
-                                                             float* __restrict__ dw, int n_total, int log2E,
+                                                             float* __restrict__ dw, int n_total,
                                                              int nodes_per_xcd, float scale) {
+  constexpr int log2E = LE;
   using Mid = typename LayerMid<LMAX>::T;
   constexpr int D = (LMAX + 1) * (LMAX + 1);
   constexpr int P = Mid::P;
@@ -67,7 +67,9 @@ __global__ __launch_bounds__(256, 2) void tp_backward_kernel(const int* __restri
     const float* gp = da + ((size_t)j * D << log2E) + c;
     const float* wp = w + ((size_t)k * P << log2E) + c;
     float* dwp = dw + ((size_t)k * P << log2E) + c;
-    float v[D], go[D], gv[D];
+    float v[D], go[D], gv[D], wr[P];
+#pragma unroll
+    for (int p = 0; p < P; ++p) wr[p] = __builtin_nontemporal_load(wp + ((size_t)p << log2E));
 #pragma unroll
     for (int q = 0; q < D; ++q) {
       v[q] = v0[q];
@@ -77,7 +79,7 @@ __global__ __launch_bounds__(256, 2) void tp_backward_kernel(const int* __restri
     egnn_bond_trig<LMAX>(g.x, g.y, g.z, t);
     egnn_to_bond_frame<LMAX>(v, t);
     egnn_to_bond_frame<LMAX>(go, t);
-    TpBwdDegree<LMAX, 0>::run(v, go, gv, wp, dwp, log2E);
+    TpBwdDegree<LMAX, 0>::run(v, go, gv, wr, dwp, log2E);
     egnn_from_bond_frame<LMAX>(gv, t);
 #pragma unroll
     for (int q = 0; q < D; ++q) acc[q] += gv[q];
@@ -104,17 +106,27 @@ int egnn_launch_tp_backward(egnn_ctx* ctx, const egnn_graph* g, const int* col_p
   dim3 grid(per_xcd * 8), block(256);
   const float scale = 1.0f / sqrtf(ctx->desc.agg_norm);
   const float4* rd = reinterpret_cast<const float4*>(rhat_d);
-#define LAUNCH(L)                                                                                              \
-  hipLaunchKernelGGL(tp_backward_kernel<L>, grid, block, 0, stream, col_ptr, perm, g->dst, rd, h, w, da, dh, dw, \
-                     n, ctx->log2_channels, per_xcd, scale)
+#define LAUNCH(L, LE_)                                                                                          \
+  hipLaunchKernelGGL((tp_backward_kernel<L, LE_>), grid, block, 0, stream, col_ptr, perm, g->dst, rd, h, w, da, dh, \
+                     dw, n, per_xcd, scale)
+#define CASES(L)                                                                        \
+  switch (ctx->log2_channels) {                                                         \
+    case 3: LAUNCH(L, 3); break;                                                        \
+    case 4: LAUNCH(L, 4); break;                                                        \
+    case 5: LAUNCH(L, 5); break;                                                        \
+    case 6: LAUNCH(L, 6); break;                                                        \
+    case 7: LAUNCH(L, 7); break;                                                        \
+    default: return egnn_fail(ctx, EGNN_EINVAL, "tp_backward: channels out of range"); \
+  }
   switch (ctx->desc.lmax) {
-    case 0: LAUNCH(0); break;
-    case 1: LAUNCH(1); break;
-    case 2: LAUNCH(2); break;
-    case 3: LAUNCH(3); break;
-    case 4: LAUNCH(4); break;
+    case 0: CASES(0); break;
+    case 1: CASES(1); break;
+    case 2: CASES(2); break;
+    case 3: CASES(3); break;
+    case 4: CASES(4); break;
     default: return egnn_fail(ctx, EGNN_EINVAL, "tp_backward: lmax out of range");
   }
+#undef CASES
 #undef LAUNCH
   EGNN_LAUNCH_CHECK(ctx, "tp_backward_kernel");
   return EGNN_OK;
