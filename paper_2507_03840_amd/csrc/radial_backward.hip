@@ -13,33 +13,57 @@
 #include "stream_gemm.h"
 
 #define RB_KCHUNK 4096   // edges per partial of dW_r2
-#define RB_R1CHUNK 1024  // edges per partial of dW_r1
+#define RB_R1CHUNK 256   // edges per partial of dW_r1 (many short workgroups; the partials are summed in two levels)
 
 __device__ __forceinline__ float rb_basis(float d, int b, float step, float inv2s2) {
   const float u = d - (float)b * step;
   return __expf(-u * u * inv2s2);
 }
 
-// G[k][j], S[k][j] for all edges: 4 edges per workgroup, one hidden unit per lane.
+// G[k][j], S[k][j] for all edges.  Tiles of 64 edges per workgroup: the basis values and the envelope of the tile
+// are computed once into LDS, lane j keeps column j of W_r1 in registers and each wave takes 16 of the edges.
+// NB8 = number of bases rounded up to a multiple of 8, in eighths: the loops over the bases have compile-time bounds
+// (columns past n_rbf hold zeros), so that no branch sits between the LDS reads.
+#define RH_EDGES 64
+template <int NB8>
 __global__ __launch_bounds__(256) void radial_hidden_kernel(const float4* __restrict__ rhat_d, long n_edges,
                                                             const float* __restrict__ W_r1, float* __restrict__ G,
                                                             float* __restrict__ S, int n_rbf, float r_cut) {
-  __shared__ float sW1[32 * EGNN_HIDDEN];
+  __shared__ float sBas[RH_EDGES][33];
+  __shared__ float sFc[RH_EDGES];
   const int tid = threadIdx.x;
-  for (int i = tid; i < n_rbf * EGNN_HIDDEN; i += 256) sW1[(i % n_rbf) * EGNN_HIDDEN + i / n_rbf] = W_r1[i];
-  __syncthreads();
-  const long k = (long)blockIdx.x * 4 + (tid >> 6);
-  if (k >= n_edges) return;
-  const int j = tid & 63;
-  const float d = rhat_d[k].w;
+  const int j = tid & 63, w = tid >> 6;
+  const long k0 = (long)blockIdx.x * RH_EDGES;
   const float step = r_cut / (float)(n_rbf - 1);
   const float inv2s2 = 0.5f / (step * step);
-  float pre = 0.0f;
-  for (int b = 0; b < n_rbf; ++b) pre += sW1[b * EGNN_HIDDEN + j] * rb_basis(d, b, step, inv2s2);
-  const float fc = 0.5f * (1.0f + cosf(3.14159265358979323846f * d / r_cut));
-  const float sig = 1.0f / (1.0f + __expf(-pre));
-  G[k * EGNN_HIDDEN + j] = fc * pre * sig;
-  S[k * EGNN_HIDDEN + j] = fc * sig * (1.0f + pre * (1.0f - sig));
+  constexpr int NB = 8 * NB8;
+  for (int i = tid; i < RH_EDGES * NB; i += 256) {
+    const int e = i / NB, b = i - e * NB;
+    const long k = k0 + e < n_edges ? k0 + e : n_edges - 1;
+    sBas[e][b] = b < n_rbf ? rb_basis(rhat_d[k].w, b, step, inv2s2) : 0.0f;
+  }
+  if (tid < RH_EDGES) {
+    const long k = k0 + tid < n_edges ? k0 + tid : n_edges - 1;
+    sFc[tid] = 0.5f * (1.0f + cosf(3.14159265358979323846f * rhat_d[k].w / r_cut));
+  }
+  float w1[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) w1[b] = b < n_rbf ? W_r1[j * n_rbf + b] : 0.0f;
+  __syncthreads();
+#pragma unroll 4
+  for (int ee = 0; ee < RH_EDGES / 4; ++ee) {
+    const int e = 4 * ee + w;
+    const long k = k0 + e;
+    float pre = 0.0f;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) pre += w1[b] * sBas[e][b];
+    const float fc = sFc[e];
+    const float sig = 1.0f / (1.0f + __expf(-pre));
+    if (k < n_edges) {
+      G[k * EGNN_HIDDEN + j] = fc * pre * sig;
+      S[k * EGNN_HIDDEN + j] = fc * sig * (1.0f + pre * (1.0f - sig));
+    }
+  }
 }
 
 // ---- the two large contractions ------------------------------------------------------------------------------
@@ -176,50 +200,59 @@ __global__ __launch_bounds__(RB_THREADS) void radial_dw2_kernel(const float* __r
   }
 }
 
-// Partial dW_r1 over one chunk of edges.  Tiles of 64 edges: the basis values of the tile are computed once into LDS,
-// then thread (hidden unit j, wave w) takes the edges e = w mod 4 of the tile against all bases; the four waves'
-// sums are added in fixed order at the end.
+// Partial dW_r1: one partial per wavefront and chunk of RB_R1CHUNK edges, the waves of a workgroup independent of
+// each other (no workgroup barrier).  Tiles of 32 edges: the basis values of the tile are computed once into the
+// wave's own LDS tile (two lanes per edge, half of the bases each), then lane j accumulates hidden unit j against all
+// bases, its 32 values of dpre loaded ahead.
+#define RB_R1TILE 32
+template <int NB8>
 __global__ __launch_bounds__(256) void radial_dw1_kernel(const float4* __restrict__ rhat_d, long n_edges,
                                                          const float* __restrict__ dpre, float* __restrict__ partial,
                                                          int n_rbf, float r_cut) {
-  __shared__ float sBas[64][33];
-  __shared__ float red[4][EGNN_HIDDEN][33];
+  __shared__ float sBas_all[4][RB_R1TILE][33];
   const int tid = threadIdx.x;
   const int j = tid & 63, w = tid >> 6;
-  const long k_begin = (long)blockIdx.x * RB_R1CHUNK;
+  float (*sBas)[33] = sBas_all[w];
+  const long chunk = (long)blockIdx.x * 4 + w;
+  const long k_begin = chunk * RB_R1CHUNK;
+  if (k_begin >= n_edges) return;                    // (whole wave; no workgroup barrier below)
   long k_end = k_begin + RB_R1CHUNK;
   if (k_end > n_edges) k_end = n_edges;
   const float step = r_cut / (float)(n_rbf - 1);
   const float inv2s2 = 0.5f / (step * step);
-  float acc[32];
+  constexpr int NB = 8 * NB8;
+  const int be = j & 31, bhalf = j >> 5;
+  float acc[NB];
 #pragma unroll
-  for (int b = 0; b < 32; ++b) acc[b] = 0.0f;
-  for (long k0 = k_begin; k0 < k_end; k0 += 64) {
-    for (int i = tid; i < 64 * n_rbf; i += 256) {
-      const int e = i / n_rbf, b = i - e * n_rbf;
-      const long k = k0 + e;
-      sBas[e][b] = k < k_end ? rb_basis(rhat_d[k].w, b, step, inv2s2) : 0.0f;
+  for (int b = 0; b < NB; ++b) acc[b] = 0.0f;
+  for (long k0 = k_begin; k0 < k_end; k0 += RB_R1TILE) {
+    float dp[RB_R1TILE];
+#pragma unroll
+    for (int e = 0; e < RB_R1TILE; ++e) dp[e] = k0 + e < k_end ? dpre[(k0 + e) * EGNN_HIDDEN + j] : 0.0f;
+    {
+      const long k = k0 + be;
+      const float d = rhat_d[k < k_end ? k : k_end - 1].w;
+#pragma unroll
+      for (int bb = 0; bb < NB / 2; ++bb) {
+        const int b = bhalf * (NB / 2) + bb;
+        sBas[be][b] = (k < k_end && b < n_rbf) ? rb_basis(d, b, step, inv2s2) : 0.0f;
+      }
     }
-    __syncthreads();
-#pragma unroll 4
-    for (int ee = 0; ee < 16; ++ee) {
-      const int e = 4 * ee + w;
-      const long k = k0 + e;
-      const float dp = k < k_end ? dpre[k * EGNN_HIDDEN + j] : 0.0f;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
 #pragma unroll
-      for (int b = 0; b < 32; ++b)
-        if (b < n_rbf) acc[b] += dp * sBas[e][b];
+    for (int e = 0; e < RB_R1TILE; ++e) {
+#pragma unroll
+      for (int b = 0; b < NB; ++b) acc[b] += dp[e] * sBas[e][b];
     }
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_wave_barrier();                 // reads of the tile are over before the next one is written
   }
+  float* out = partial + (size_t)chunk * EGNN_HIDDEN * n_rbf + (size_t)j * n_rbf;
 #pragma unroll
-  for (int b = 0; b < 32; ++b) red[w][j][b] = acc[b];
-  __syncthreads();
-  float* out = partial + (size_t)blockIdx.x * EGNN_HIDDEN * n_rbf;
-  for (int i = tid; i < EGNN_HIDDEN * n_rbf; i += 256) {
-    const int jj = i / n_rbf, b = i - jj * n_rbf;
-    out[i] = (red[0][jj][b] + red[1][jj][b]) + (red[2][jj][b] + red[3][jj][b]);
-  }
+  for (int b = 0; b < NB; ++b)
+    if (b < n_rbf) out[b] = acc[b];
 }
 
 static size_t a256(size_t n) { return (n + 255) & ~(size_t)255; }
@@ -255,8 +288,16 @@ int egnn_launch_radial_backward(egnn_ctx* ctx, int which, const float* rhat_d, i
   uint16_t* GT = (uint16_t*)((char*)W2T + a256(rb_pad64(PE) * EGNN_HIDDEN * 6));
   const long pe_pad = (long)rb_pad64(PE), ne_pad = (long)rb_pad64(n_edges);
   const float4* rd = reinterpret_cast<const float4*>(rhat_d);
-  hipLaunchKernelGGL(radial_hidden_kernel, dim3((unsigned)((n_edges + 3) / 4)), dim3(256), 0, st, rd, (long)n_edges,
-                     W_r1, G, S, n_rbf, ctx->desc.r_cut);
+  const int nb8 = (n_rbf + 7) / 8;   // 1 .. 4 (n_rbf <= 32)
+#define RB_BY_NB8(KERNEL, GRID, ...)                                                                 \
+  switch (nb8) {                                                                                     \
+    case 1: hipLaunchKernelGGL(KERNEL<1>, GRID, dim3(256), 0, st, __VA_ARGS__); break;               \
+    case 2: hipLaunchKernelGGL(KERNEL<2>, GRID, dim3(256), 0, st, __VA_ARGS__); break;               \
+    case 3: hipLaunchKernelGGL(KERNEL<3>, GRID, dim3(256), 0, st, __VA_ARGS__); break;               \
+    default: hipLaunchKernelGGL(KERNEL<4>, GRID, dim3(256), 0, st, __VA_ARGS__); break;              \
+  }
+  RB_BY_NB8(radial_hidden_kernel, dim3((unsigned)((n_edges + RH_EDGES - 1) / RH_EDGES)), rd, (long)n_edges, W_r1, G, S,
+            n_rbf, ctx->desc.r_cut);
   EGNN_LAUNCH_CHECK(ctx, "radial_hidden_kernel");
   hipLaunchKernelGGL(rb_split_transpose_kernel, dim3((unsigned)(ne_pad / 64)), dim3(256), 0, st, G, (long)n_edges, GT, 0,
                      al, 0);
@@ -279,8 +320,8 @@ int egnn_launch_radial_backward(egnn_ctx* ctx, int which, const float* rhat_d, i
   hipLaunchKernelGGL(radial_dpre_kernel, dim3((unsigned)((n_edges + per_wg - 1) / per_wg)), dim3(SG_THREADS), dpre_lds, st,
                      dw, (long)n_edges, W2T, S, PE, (int)(pe_pad / 64));
   EGNN_LAUNCH_CHECK(ctx, "radial_dpre_kernel");
-  hipLaunchKernelGGL(radial_dw1_kernel, dim3(r1c), dim3(256), 0, st, rd, (long)n_edges, S, part1, n_rbf,
-                     ctx->desc.r_cut);
+  RB_BY_NB8(radial_dw1_kernel, dim3((r1c + 3) / 4), rd, (long)n_edges, S, part1, n_rbf, ctx->desc.r_cut);
+#undef RB_BY_NB8
   EGNN_LAUNCH_CHECK(ctx, "radial_dw1_kernel");
   return egnn_launch_reduce_partials(ctx, part1, r1c, (long)EGNN_HIDDEN * n_rbf, dW_r1, 1.0f, st);
 }
