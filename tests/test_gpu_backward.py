@@ -87,7 +87,8 @@ def test_layer_backward(B, lmax, E, n, n_owned, periodic):
 
 @pytest.mark.parametrize("lmax,E,n,n_owned,periodic", [(0, 8, 40, 40, False), (2, 16, 90, 60, True),
                                                        (3, 32, 70, 70, False), (4, 32, 100, 70, False),
-                                                       (4, 64, 50, 50, True)])
+                                                       (4, 64, 50, 50, True), (4, 8, 45, 45, True),
+                                                       (1, 128, 40, 30, False)])
 def test_readout_backward(B, lmax, E, n, n_owned, periodic):
     w, g, agg, m, pos, graph, ws, col_ptr, perm = _setup(B, lmax, E, n, n_owned, periodic, 60 + lmax)
     rng = np.random.default_rng(10 + lmax)
