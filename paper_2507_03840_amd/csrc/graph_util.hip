@@ -171,6 +171,7 @@ int egnn_launch_reduce_partials(egnn_ctx* ctx, float* partial, int n_partials, l
   long stride = 1;
   if (n_partials > 8 * RP_CHUNK) {
     const int n_chunks = (n_partials + RP_CHUNK - 1) / RP_CHUNK;
+    if (n_chunks > 65535) return egnn_fail(ctx, EGNN_EINVAL, "reduce_partials: too many partial results");
     hipLaunchKernelGGL(reduce_partials_chunk_kernel, dim3(gx, (unsigned)n_chunks), dim3(256), 0, st, partial,
                        n_partials, n);
     EGNN_LAUNCH_CHECK(ctx, "reduce_partials_chunk_kernel");
