@@ -50,18 +50,35 @@ __device__ __forceinline__ void collapse_adjoint(const ReadoutBwdTabs& tb, const
   const int E = 1 << log2E;
   const int log2Ew = log2E < 6 ? log2E : 6;
   const bool writer = wl < (1 << log2Ew);
-  for (int o = tb.v_off[L]; o < tb.v_off[L + 1]; ++o) {
-    const float* q = sq + s_vq[o];
-    const float vv = V[((size_t)o << log2E) + c];
-    float dot = 0.0f;
+  // four rows at a time, so that four butterflies and four LDS updates are in flight (rows past the end of the
+  // degree repeat its last row with weight zero and are not written)
+  const int o_end = tb.v_off[L + 1];
+  for (int o0 = tb.v_off[L]; o0 < o_end; o0 += 4) {
+    float dot[4];
 #pragma unroll
-    for (int M = 0; M < 2 * L + 1; ++M) {
-      const float qv = q[M];
-      dot += qv * u[L * L + M];
-      du[L * L + M] += vv * qv;
+    for (int r = 0; r < 4; ++r) {
+      const bool ok = o0 + r < o_end;
+      const int o = ok ? o0 + r : o_end - 1;
+      const float* q = sq + s_vq[o];
+      const float vv = ok ? V[((size_t)o << log2E) + c] : 0.0f;
+      float dsum = 0.0f;
+#pragma unroll
+      for (int M = 0; M < 2 * L + 1; ++M) {
+        const float qv = q[M];
+        dsum += qv * u[L * L + M];
+        du[L * L + M] += vv * qv;
+      }
+      dot[r] = dsum;
     }
-    for (int off = E; off < 64; off <<= 1) dot += __shfl_xor(dot, off);
-    if (writer) sdVw[(o << log2Ew) + wl] += dot;
+    for (int off = E; off < 64; off <<= 1) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) dot[r] += __shfl_xor(dot[r], off);
+    }
+    if (writer) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        if (o0 + r < o_end) sdVw[((o0 + r) << log2Ew) + wl] += dot[r];
+    }
   }
 }
 
