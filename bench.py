@@ -243,16 +243,35 @@ def main():
             dt = (time.perf_counter() - t1) / args.train_steps
             train_step(keep=True)
             torch.cuda.synchronize()
+            m.egnn_timing_enable(2 * args.train_steps * (w.n_layers + 1))
             t1 = time.perf_counter()
             for _ in range(args.train_steps):
                 loss_k = train_step(keep=True)
             torch.cuda.synchronize()
             dt_k = (time.perf_counter() - t1) / args.train_steps
+            ms_k, calls_k = m.egnn_timing_read()
+            m.egnn_timing_enable(0)
+            # stages of the reverse pass (HIP events of the library on the launch stream) with the bytes each one
+            # has to move at least: tp_backward reads w and writes dw; the readout adjoint reads w and dH and writes
+            # dw and dz; the radial MLP's reverse pass reads dw twice
+            wbytes = 4 * n_edges * m.n_paths * w.channels
+            wbytes_ro = 4 * n_edges * m.n_paths_readout * w.channels
+            row = 4 * m.dim * w.channels
+            adj = {n: ms_k[10 + i] / max(1, calls_k[2]) for i, n in enumerate(B.LAYER_ADJOINT_STAGES)}
+            adj_ro = {n: ms_k[15 + i] / max(1, calls_k[3]) for i, n in enumerate(B.READOUT_ADJOINT_STAGES)}
+            stage_bytes = dict(tp_backward=2 * wbytes, radial_backward=2 * wbytes,
+                               readout_backward=2 * wbytes_ro + n_edges * (row + 4 * w.n_orb * w.n_orb))
+            reverse = dict(layer_ms=adj, readout_ms=adj_ro,
+                           tp_backward_GBs=stage_bytes["tp_backward"] / adj["tp_backward"] / 1e6,
+                           radial_backward_GBs=stage_bytes["radial_backward"] / adj["radial_backward"] / 1e6,
+                           readout_backward_GBs=stage_bytes["readout_backward"] / adj_ro["readout_backward"] / 1e6,
+                           note="per call, forward quantities kept; GB/s = the bytes the stage has to move at least "
+                                "(w, dw, dz, dH) over its time, against 8,000 GB/s")
             training = dict(ms_per_step=1e3 * dt, steps=args.train_steps, loss=float(loss.cpu()[0]),
                             edge_layer_evaluations_per_s=n_edges * w.n_layers / dt,
                             step="layers fwd + readout + MSE + readout bwd + layers bwd (forward recomputed inside bwd)",
                             keeping_forward_quantities=dict(
-                                ms_per_step=1e3 * dt_k, loss=float(loss_k.cpu()[0]),
+                                ms_per_step=1e3 * dt_k, loss=float(loss_k.cpu()[0]), reverse_pass_stages=reverse,
                                 kept_GB=4 * n_edges * w.channels * (w.n_layers * m.n_paths + m.n_paths_readout) / 1e9,
                                 note="radial weights of every layer and of the readout and the summed messages kept "
                                      "by the caller (egnn_*_save / egnn_*_backward_saved); gradients bit-identical"))

@@ -364,14 +364,20 @@ int egnn_unpack_rows(egnn_ctx* ctx, const void* buf, int32_t n_rows, int32_t hal
 /* ---- stage timing (measurement aid; follows the paper's protocol of timing the blocks of the forward
  *      pass separately, Sec. 4.4 / Fig. 6(c)) ----
  * egnn_timing_enable(ctx, max_calls > 0) creates HIP events; from then on every egnn_layer_forward /
- * egnn_readout_hij records one event per stage on the caller's stream, for at most max_calls calls
- * (further calls are not recorded).  max_calls = 0 turns it off.  egnn_timing_read waits for the recorded
- * calls, sums the elapsed milliseconds per stage and clears the record:
- *   ms[0..4]  layer:   geometry, radial weights, pre mix, tensor-product + segmented sum, post mix
- *   ms[5..9]  readout: geometry, radial weights, source mix, destination mix, product + collapse + uncoupling
- *   n_calls[0], n_calls[1]: recorded layer / readout calls (host arrays). */
+ * egnn_readout_hij / egnn_layer_backward / egnn_readout_backward (and their _save / _saved forms) records one event
+ * per stage on the caller's stream, for at most max_calls calls (further calls are not recorded).  max_calls = 0
+ * turns it off.  egnn_timing_read waits for the recorded calls, sums the elapsed milliseconds per stage and clears
+ * the record:
+ *   ms[0..4]    layer:           geometry, radial weights, pre mix, tensor-product + segmented sum, post mix
+ *   ms[5..9]    readout:         geometry, radial weights, source mix, destination mix, product + collapse + uncoupling
+ *   ms[10..14]  layer adjoint:   forward quantities (what is not supplied), adjoint of the post mix + weight
+ *                                gradients, adjoint of the messages, adjoint of the pre mix + weight gradient,
+ *                                radial MLP
+ *   ms[15..19]  readout adjoint: forward quantities, adjoint of uncoupling + collapse + product, row sums + adjoints
+ *                                of the two mixes + weight gradients, radial MLP, (unused)
+ *   n_calls[0..3]: recorded calls of each kind (host arrays). */
 int egnn_timing_enable(egnn_ctx* ctx, int32_t max_calls);
-int egnn_timing_read(egnn_ctx* ctx, float ms[10], int32_t n_calls[2]);
+int egnn_timing_read(egnn_ctx* ctx, float ms[20], int32_t n_calls[4]);
 
 #ifdef __cplusplus
 }

@@ -95,6 +95,8 @@ class Graph:
 
 LAYER_STAGES = ["geometry", "radial_weights", "mix_pre", "tp_segsum", "mix_post"]
 READOUT_STAGES = ["geometry", "radial_weights", "mix_src", "mix_dst", "readout"]
+LAYER_ADJOINT_STAGES = ["forward_quantities", "mix_post_adjoint", "tp_backward", "mix_pre_adjoint", "radial_backward"]
+READOUT_ADJOINT_STAGES = ["forward_quantities", "readout_backward", "row_sums_and_mix_adjoints", "radial_backward"]
 
 
 def egnn_partition_low_nn(pos, degree, box, pbc, r_cut, levels):
@@ -517,8 +519,8 @@ class Egnn:
         self._check(self.lib.egnn_timing_enable(self.ctx, int(max_calls)))
 
     def egnn_timing_read(self):
-        ms = (C.c_float * 10)()
-        n = (C.c_int32 * 2)()
+        ms = (C.c_float * 20)()
+        n = (C.c_int32 * 4)()
         self._check(self.lib.egnn_timing_read(self.ctx, ms, n))
         return list(ms), list(n)
 

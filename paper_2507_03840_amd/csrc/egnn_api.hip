@@ -147,10 +147,11 @@ extern "C" int egnn_timing_enable(egnn_ctx* ctx, int32_t max_calls) {
   return EGNN_OK;
 }
 
-extern "C" int egnn_timing_read(egnn_ctx* ctx, float ms[2 * EGNN_STAGES], int32_t n_calls[2]) {
+extern "C" int egnn_timing_read(egnn_ctx* ctx, float ms[EGNN_TIMED_KINDS * EGNN_STAGES],
+                                int32_t n_calls[EGNN_TIMED_KINDS]) {
   if (!ctx || !ms || !n_calls) return EGNN_EINVAL;
-  for (int i = 0; i < 2 * EGNN_STAGES; ++i) ms[i] = 0.0f;
-  n_calls[0] = n_calls[1] = 0;
+  for (int i = 0; i < EGNN_TIMED_KINDS * EGNN_STAGES; ++i) ms[i] = 0.0f;
+  for (int i = 0; i < EGNN_TIMED_KINDS; ++i) n_calls[i] = 0;
   for (size_t c = 0; c < ctx->ev_kind.size(); ++c) {
     const int kind = ctx->ev_kind[c];
     hipEvent_t* e = &ctx->ev[c * (EGNN_STAGES + 1)];

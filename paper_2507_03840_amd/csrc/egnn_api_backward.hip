@@ -127,18 +127,22 @@ static int layer_backward_impl(egnn_ctx* ctx, const egnn_graph* g, const int32_t
   const int n_o = g->n_owned, n_t = g->n_total;
 
   // forward quantities
+  StageTimer tm(ctx, st, 2);
   if ((rc = egnn_launch_geometry(ctx, g, pos, box, b.rhat_d, nullptr, nullptr, nullptr, st))) return rc;
   const float* w = w_saved ? w_saved : b.w;
   const float* a = a_saved ? a_saved : b.a;
   if (!w_saved && (rc = egnn_launch_radial(ctx, 0, b.rhat_d, g->n_edges, W_r1, W_r2, b.w, b.w2s, st))) return rc;
   if ((rc = egnn_launch_node_mix(ctx, x_in, W_pre, nullptr, nullptr, b.h, n_t, st))) return rc;
   if (!a_saved && (rc = egnn_launch_tp_segsum(ctx, g, b.rhat_d, b.h, w, b.a, st))) return rc;
+  tm.mark(0);
   // x_out = W_post a + W_self x_in[:n_owned]
   if ((rc = egnn_launch_node_mix(ctx, dx_out, W_post, nullptr, nullptr, b.da, n_o, st, 1))) return rc;
   if ((rc = egnn_launch_mix_wgrad(ctx, dx_out, a, dW_post, b.wgrad_partial, n_o, st))) return rc;
   if ((rc = egnn_launch_mix_wgrad(ctx, dx_out, x_in, dW_self, b.wgrad_partial, n_o, st))) return rc;
+  tm.mark(1);
   // messages
   if ((rc = egnn_launch_tp_backward(ctx, g, col_ptr, perm, b.rhat_d, b.h, w, b.da, b.dh, b.dw, st))) return rc;
+  tm.mark(2);
   // h = W_pre x_in ; owned rows also receive the self term
   if ((rc = egnn_launch_node_mix(ctx, b.dh, W_pre, dx_out, W_self, dx_in, n_o, st, 1))) return rc;
   if (n_t > n_o &&
@@ -146,8 +150,11 @@ static int layer_backward_impl(egnn_ctx* ctx, const egnn_graph* g, const int32_t
                                  n_t - n_o, st, 1)))
     return rc;
   if ((rc = egnn_launch_mix_wgrad(ctx, b.dh, x_in, dW_pre, b.wgrad_partial, n_t, st))) return rc;
+  tm.mark(3);
   // radial MLP
-  return egnn_launch_radial_backward(ctx, 0, b.rhat_d, g->n_edges, W_r1, W_r2, b.dw, dW_r1, dW_r2, b.radial, st);
+  rc = egnn_launch_radial_backward(ctx, 0, b.rhat_d, g->n_edges, W_r1, W_r2, b.dw, dW_r1, dW_r2, b.radial, st);
+  tm.mark(4);
+  return rc;
 }
 
 extern "C" int egnn_layer_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm,
@@ -183,8 +190,8 @@ static int readout_backward_impl(egnn_ctx* ctx, const egnn_graph* g, const int32
       !dV || !ws)
     return egnn_fail(ctx, EGNN_EINVAL, "readout_backward: null pointer");
   if (((uintptr_t)ws & 255) != 0) return egnn_fail(ctx, EGNN_EINVAL, "readout_backward: workspace not 256-byte aligned");
-  const int nq = ctx->n_orb * ctx->n_orb, nv = vrows(ctx), E = ctx->desc.channels;
-  if (((size_t)(256 / E) * nq + (size_t)(256 / E) * nv * E) * sizeof(float) > 160 * 1024)
+  const int nq = ctx->n_orb * ctx->n_orb, nv = vrows(ctx);
+  if (egnn_readout_backward_lds_bytes(ctx) > 160 * 1024)
     return egnn_fail(ctx, EGNN_EINVAL, "readout_backward: orbital basis too large for the LDS tiles");
   ReadoutBwdBufs b;
   if (ws_bytes < carve_readout_bwd(ctx, g, nullptr, &b)) return egnn_fail(ctx, EGNN_EWS, "readout_backward: workspace too small");
@@ -221,14 +228,17 @@ static int readout_backward_impl(egnn_ctx* ctx, const egnn_graph* g, const int32
   EGNN_HIP(ctx, hipMemcpyAsync(b.tab_i, ti.data(), ti.size() * sizeof(int), hipMemcpyHostToDevice, st));
   EGNN_HIP(ctx, hipMemcpyAsync(b.tab_f, tf.data(), tf.size() * sizeof(float), hipMemcpyHostToDevice, st));
 
+  StageTimer tm(ctx, st, 3);
   if ((rc = egnn_launch_geometry(ctx, g, pos, box, b.rhat_d, nullptr, nullptr, nullptr, st))) return rc;
   const float* w = w_saved ? w_saved : b.w;
   if (!w_saved && (rc = egnn_launch_radial(ctx, 1, b.rhat_d, g->n_edges, W_r1, W_r2, b.w, b.w2s, st))) return rc;
   if ((rc = egnn_launch_node_mix(ctx, x, W_s, nullptr, nullptr, b.zs, n_t, st))) return rc;
   if ((rc = egnn_launch_node_mix(ctx, x, W_t, nullptr, nullptr, b.zt, n_t, st))) return rc;
+  tm.mark(0);
   if ((rc = egnn_launch_readout_backward(ctx, g, b.rhat_d, b.zs, b.zt, w, V, b.tab_i, b.tab_f, dH, b.dz, b.dw, dV,
                                          b.dV_partial, st)))
     return rc;
+  tm.mark(1);
   // dz_k feeds the source row (zs) and the destination row (zt, owned nodes only)
   if ((rc = egnn_launch_segsum_rows(ctx, b.dz, col_ptr, perm, b.dzs, n_t, row_len, st))) return rc;
   if ((rc = egnn_launch_segsum_rows(ctx, b.dz, g->row_ptr, nullptr, b.dzt, g->n_owned, row_len, st))) return rc;
@@ -240,7 +250,11 @@ static int readout_backward_impl(egnn_ctx* ctx, const egnn_graph* g, const int32
   if ((rc = egnn_launch_node_mix(ctx, b.dzs, W_s, b.dzt, W_t, dx, n_t, st, 1))) return rc;
   if ((rc = egnn_launch_mix_wgrad(ctx, b.dzs, x, dW_s, b.wgrad_partial, n_t, st))) return rc;
   if ((rc = egnn_launch_mix_wgrad(ctx, b.dzt, x, dW_t, b.wgrad_partial, n_t, st))) return rc;
-  return egnn_launch_radial_backward(ctx, 1, b.rhat_d, g->n_edges, W_r1, W_r2, b.dw, dW_r1, dW_r2, b.radial, st);
+  tm.mark(2);
+  rc = egnn_launch_radial_backward(ctx, 1, b.rhat_d, g->n_edges, W_r1, W_r2, b.dw, dW_r1, dW_r2, b.radial, st);
+  tm.mark(3);
+  tm.mark(4);
+  return rc;
 }
 
 extern "C" int egnn_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm,

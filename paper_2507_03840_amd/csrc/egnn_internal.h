@@ -32,7 +32,7 @@ struct egnn_ctx {
   std::vector<float> unc_c;              //   and coupling coefficients
   // optional stage timing (egnn_timing_enable): EGNN_STAGES+1 events per recorded composite call
   std::vector<hipEvent_t> ev;
-  std::vector<int> ev_kind;              // per recorded call: 0 = layer, 1 = readout
+  std::vector<int> ev_kind;              // per recorded call: 0 = layer, 1 = readout, 2 = layer adjoint, 3 = readout adjoint
   int ev_max_calls = 0;
   CellGrid nl_grid;                      // grid of the last egnn_nlist_count that used the cell list
   int nl_grid_atoms = -1;                //   and the atom count it was built for
@@ -46,6 +46,7 @@ struct egnn_ctx {
 };
 
 #define EGNN_STAGES 5   // stages per composite call
+#define EGNN_TIMED_KINDS 4
 
 // Records the event that closes stage `stage` (or opens the call for stage = -1) if timing is on.
 struct StageTimer {
@@ -91,6 +92,7 @@ int egnn_launch_radial_backward(egnn_ctx*, int which, const float* rhat_d, int64
                                 const float* W_r2, const float* dw, float* dW_r1, float* dW_r2, void* ws,
                                 hipStream_t);
 size_t egnn_readout_backward_partial_bytes(const egnn_ctx*, int64_t n_edges);
+size_t egnn_readout_backward_lds_bytes(const egnn_ctx*);
 int egnn_launch_readout_backward(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* zs, const float* zt,
                                  const float* w, const float* V, const int* tab_i, const float* tab_f,
                                  const float* dH, float* dz, float* dw, float* dV, float* partial, hipStream_t);

@@ -250,6 +250,13 @@ static int rob_vrows(const egnn_ctx* ctx) {
   return n;
 }
 
+// dynamic LDS of the kernel: dq and the block of dH per slot, one partial dV per wavefront, the index tables
+size_t egnn_readout_backward_lds_bytes(const egnn_ctx* ctx) {
+  const int E = ctx->desc.channels, n_slots = 256 / E, Ew = E < 64 ? E : 64;
+  const size_t nq = (size_t)ctx->n_orb * ctx->n_orb, nnz = ctx->unc_q.size(), n_vrows = (size_t)rob_vrows(ctx);
+  return (2 * n_slots * nq + 4 * n_vrows * Ew) * sizeof(float) + (nq + 1 + 2 * nnz + n_vrows) * sizeof(int);
+}
+
 size_t egnn_readout_backward_partial_bytes(const egnn_ctx* ctx, int64_t n_edges) {
   return (size_t)rob_grid(ctx, n_edges) * rob_vrows(ctx) * ctx->desc.channels * sizeof(float);
 }
@@ -278,10 +285,7 @@ int egnn_launch_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const float
   tb.slot_qoff = tb.slot_L + ctx->n_slots;
   tb.vrow_qoff = tb.slot_qoff + ctx->n_slots;
   tb.uncT_c = tab_f;
-  const int n_slots = 256 / E;
-  const int Ew = E < 64 ? E : 64;
-  const size_t shmem = ((size_t)2 * n_slots * nq + (size_t)4 * n_vrows * Ew) * sizeof(float) +
-                       ((size_t)nq + 1 + 2 * (size_t)nnz + n_vrows) * sizeof(int);
+  const size_t shmem = egnn_readout_backward_lds_bytes(ctx);
   const long grid_x = rob_grid(ctx, n);
   dim3 grid((unsigned)grid_x), block(256);
   const float4* rd = reinterpret_cast<const float4*>(rhat_d);
