@@ -85,6 +85,24 @@ def test_layer_backward(B, lmax, E, n, n_owned, periodic):
     assert all(np.array_equal(grads[k].cpu().numpy(), grads2[k].cpu().numpy()) for k in grads)
 
 
+@pytest.mark.parametrize("n_rbf", [2, 9, 20, 32])
+def test_layer_backward_basis_counts(B, n_rbf):
+    """The reverse pass of the radial MLP pads the number of radial bases to a multiple of 8 at compile time."""
+    lmax, E, n = 2, 16, 60
+    w, g, agg, m, pos, graph, ws, col_ptr, perm = _setup(B, lmax, E, n, n, False, 70 + n_rbf, n_rbf=n_rbf)
+    rng = np.random.default_rng(n_rbf)
+    W = synth.layer_weights(rng, lmax, E, n_rbf, 64, m.n_paths)
+    x = synth.node_features(rng, n, lmax, E)
+    dy = synth.node_features(rng, n, lmax, E)
+    dx, grads = m.egnn_layer_backward(graph, col_ptr, perm, pos, w.box, B.to_device(x), B.to_device(W),
+                                      B.to_device(dy), ws)
+    dx_ref, g_ref = O.layer_backward(g, w.pos, w.box, x, W, lmax, lmax, E, n_rbf, w.r_cut, agg, dy.astype(np.float64))
+    errs = {"dx": U.rel_err(dx.cpu().numpy(), dx_ref)}
+    errs.update({k: U.rel_err(grads[k].cpu().numpy(), g_ref[k]) for k in g_ref})
+    print(errs, flush=True)
+    assert all(e < TOL for e in errs.values()), errs
+
+
 @pytest.mark.parametrize("lmax,E,n,n_owned,periodic", [(0, 8, 40, 40, False), (2, 16, 90, 60, True),
                                                        (3, 32, 70, 70, False), (4, 32, 100, 70, False),
                                                        (4, 64, 50, 50, True), (4, 8, 45, 45, True),
