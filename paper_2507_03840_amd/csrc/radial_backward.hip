@@ -148,44 +148,51 @@ __global__ __launch_bounds__(RB_THREADS) void radial_dw2_kernel(const float* __r
   const int n_tile = (blockIdx.x * RB_WAVES + wave) * 32;
   const int n_row = n_tile + m;                       // row of dW_r2 this lane feeds as the A operand
   const bool row_ok = n_row < PE;
-  const float* col = dw + (row_ok ? n_row : 0);
   float16v acc[2];
 #pragma unroll
   for (int i = 0; i < 16; ++i) acc[0][i] = acc[1][i] = 0.0f;
 
+  // The 32 values a lane needs for a step (its half of the 64 edges, one per load) are requested one step ahead
+  // into the registers the step before has just cut into pieces: no copy, nothing touched in the step that issues
+  // the load.  Row addresses are a uniform part (edge * PE, scalar arithmetic) plus a per-lane offset that never
+  // changes.  No masks: rows past the last edge are clamped to it and meet zero rows of GT, rows n >= PE read
+  // column 0 and are not stored.
+  const unsigned lane_off = (unsigned)(hh * 32) * (unsigned)PE + (unsigned)(row_ok ? n_row : 0);
+  const long k_last = n_edges - 1;
   float nxt[32];
-  // (no branch around a load: edges past the chunk are clamped to its last edge; the value is replaced by zero where
-  // it is used)
-  auto fetch = [&](int s) {
-    const long kl = k_begin + (long)s * 64 + hh * 32;
-    const long kb = kl < k_end ? kl : k_end - 1;
-    const int qmax = (int)(k_end - 1 - kb < 31 ? k_end - 1 - kb : 31);
-    const float* p = col + (size_t)kb * PE;
+  auto fetch8 = [&](int s, int t) {
+    const long k0 = k_begin + (long)s * 64 + 8 * t;          // (+ 32 hh through lane_off)
+    if (k0 + 32 + 7 <= k_last) {                             // the same for all lanes
+      const float* base = dw + (size_t)k0 * PE;
 #pragma unroll
-    for (int q = 0; q < 32; ++q) nxt[q] = p[(q < qmax ? q : qmax) * PE];
+      for (int q = 0; q < 8; ++q) nxt[8 * t + q] = (base + (size_t)q * PE)[lane_off];
+    } else {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const long k = k0 + hh * 32 + q;
+        nxt[8 * t + q] = dw[(size_t)(k < k_last ? k : k_last) * PE + (row_ok ? n_row : 0)];
+      }
+    }
   };
-  fetch(0);
-  for (int s = 0; s < n_steps; ++s) {
-    float cur[32];
 #pragma unroll
-    for (int q = 0; q < 32; ++q) cur[q] = nxt[q];
-    if (s + 1 < n_steps) fetch(s + 1);
+  for (int t = 0; t < 4; ++t) fetch8(0, t);
+  for (int s = 0; s < n_steps; ++s) {
+    const int s_next = s + 1 < n_steps ? s + 1 : s;          // (the last step fetches itself again: no branch)
     rb_barrier_acquire();
     const uint4* bbase = sB + (s & 1) * (64 * RB_BROW4) + hh * 4;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      const long kt = k_begin + (long)s * 64 + hh * 32 + 8 * t;
       float x[8];
 #pragma unroll
-      for (int q = 0; q < 8; ++q) x[q] = (row_ok && kt + q < k_end) ? cur[8 * t + q] : 0.0f;
+      for (int q = 0; q < 8; ++q) x[q] = nxt[8 * t + q];
       uint4 ah, am, al;
       rb_split8(x, ah, am, al);
-#pragma unroll
-      for (int cb = 0; cb < 2; ++cb) {
-        const uint4* brow = bbase + (m + 32 * cb) * RB_BROW4 + t;
-        const uint4 b[3] = {brow[0], brow[8], brow[16]};
-        acc[cb] = rb_mma6(ah, am, al, b, acc[cb]);
-      }
+      fetch8(s_next, t);
+      const uint4* brow0 = bbase + m * RB_BROW4 + t;
+      const uint4* brow1 = brow0 + 32 * RB_BROW4;
+      const uint4 b0[3] = {brow0[0], brow0[8], brow0[16]};
+      const uint4 b1[3] = {brow1[0], brow1[8], brow1[16]};
+      rb_mma6x2(ah, am, al, b0, b1, acc[0], acc[1]);
     }
   }
   float* out = partial + (size_t)blockIdx.y * PE * EGNN_HIDDEN;
