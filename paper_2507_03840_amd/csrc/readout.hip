@@ -51,7 +51,8 @@ __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ sr
                                                       const float4* __restrict__ rhat_d,
                                                       const float* __restrict__ zs, const float* __restrict__ zt,
                                                       const float* __restrict__ w, const float* __restrict__ V,
-                                                      ReadoutTabs tb, float* __restrict__ H, long n_edges) {
+                                                      ReadoutTabs tb, float* __restrict__ H, long n_edges,
+                                                      int tiles_per_xcd) {
   using Mid = typename ReadoutMid<LMAX>::T;
   constexpr int D = (LMAX + 1) * (LMAX + 1);
   constexpr int P = Mid::P;
@@ -86,7 +87,10 @@ __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ sr
   }
   __syncthreads();
 
-  const long k_base = (long)blockIdx.x * n_slots * RO_ITERS;
+  // consecutive groups of edges (the same destinations, neighbouring sources) go to the same XCD, so that its L2
+  // serves their rows of zs and zt
+  const long tile = (long)(blockIdx.x & 7) * tiles_per_xcd + (blockIdx.x >> 3);
+  const long k_base = tile * n_slots * RO_ITERS;
   for (int it = 0; it < RO_ITERS; ++it) {
     const long k = k_base + (long)it * n_slots + slot;
     const bool live = k < n_edges;
@@ -152,14 +156,16 @@ static int launch_readout(egnn_ctx* ctx, const egnn_graph* g, const float4* rd, 
                            sizeof(float) +
                        ((size_t)3 * tb.nq + 1 + 2 * (size_t)tb.nnz) * sizeof(int);
   const long per_wg = (long)n_slots * RO_ITERS;
-  dim3 grid((unsigned)((g->n_edges + per_wg - 1) / per_wg)), block(256);
+  const int tiles_per_xcd = (int)(((g->n_edges + per_wg - 1) / per_wg + 7) / 8);
+  dim3 grid((unsigned)(8 * tiles_per_xcd)), block(256);   // (a tile past the end finds no live edge)
   auto kern = readout_kernel<L, LE, HALF>;
   if (shmem > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)shmem);
     if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(readout_kernel)");
   }
-  hipLaunchKernelGGL(kern, grid, block, shmem, stream, g->src, g->dst, rd, zs, zt, w, V, tb, H, (long)g->n_edges);
+  hipLaunchKernelGGL(kern, grid, block, shmem, stream, g->src, g->dst, rd, zs, zt, w, V, tb, H, (long)g->n_edges,
+                     tiles_per_xcd);
   EGNN_LAUNCH_CHECK(ctx, "readout_kernel");
   return EGNN_OK;
 }
