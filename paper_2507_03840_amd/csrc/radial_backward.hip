@@ -159,13 +159,20 @@ __global__ __launch_bounds__(RB_THREADS) void radial_dw2_kernel(const float* __r
   // column 0 and are not stored.
   const unsigned lane_off = (unsigned)(hh * 32) * (unsigned)PE + (unsigned)(row_ok ? n_row : 0);
   const long k_last = n_edges - 1;
+  // (a chunk is at most RB_KCHUNK rows of PE floats: far below the 4 GB a descriptor spans)
+  const __amdgpu_buffer_rsrc_t chunk_rows = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(dw + (size_t)k_begin * PE), 0, (int)((k_end - k_begin) * PE * 4), 0x00020000);
   float nxt[32];
   auto fetch8 = [&](int s, int t) {
     const long k0 = k_begin + (long)s * 64 + 8 * t;          // (+ 32 hh through lane_off)
     if (k0 + 32 + 7 <= k_last) {                             // the same for all lanes
-      const float* base = dw + (size_t)k0 * PE;
+      // buffer loads: descriptor (the chunk's rows of dw) and row offset in scalar registers, the lane's own
+      // offset in one vector register -- no vector arithmetic per load
+      const int row0 = s * 64 + 8 * t;
 #pragma unroll
-      for (int q = 0; q < 8; ++q) nxt[8 * t + q] = (base + (size_t)q * PE)[lane_off];
+      for (int q = 0; q < 8; ++q)
+        nxt[8 * t + q] = __builtin_bit_cast(
+            float, __builtin_amdgcn_raw_buffer_load_b32(chunk_rows, (int)(lane_off * 4u), (row0 + q) * PE * 4, 0));
     } else {
 #pragma unroll
       for (int q = 0; q < 8; ++q) {
