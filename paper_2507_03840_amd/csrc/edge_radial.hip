@@ -162,13 +162,13 @@ __device__ __forceinline__ void lds_barrier_acquire() {
 }
 
 // One 32-column block: wait for its rows of W_r2 in LDS, then 4 steps x 6 piece products per 32-row block.
-// STORE: after each step a quarter of the previous block's results (prev) goes to memory: out_prev is the wave's
-// first row at the block's first column (the same for all lanes), lane_off the lane's own offset, ld the row stride
+// STORE: after each step a quarter of the previous block's results (prev) goes to memory: out_prev describes the
+// wave's rows of w, col_prev is the block's first column, lane_off the lane's own offset, ld the row stride
 // (w is written once and read once by another kernel: non-temporal stores).
 template <bool STORE>
 __device__ __forceinline__ void rw_block(const uint4* __restrict__ sB_nb, const uint4 (&a_frag)[RW_MB][3][4], int m,
                                          int hh, float16v (&acc)[RW_MB], const float16v (&prev)[RW_MB],
-                                         float* __restrict__ out_prev, unsigned lane_off, size_t ld) {
+                                         __amdgpu_buffer_rsrc_t out_prev, int col_prev, unsigned lane_off, size_t ld) {
   lds_barrier_acquire();
   uint4 b_frag[3][4];
   {
@@ -198,8 +198,10 @@ __device__ __forceinline__ void rw_block(const uint4* __restrict__ sB_nb, const 
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const int idx = 8 * t + j, mb = idx >> 4, i = idx & 15;
-        float* rowp = out_prev + (size_t)(32 * mb + 8 * (i >> 2) + (i & 3)) * ld;   // the same for all lanes
-        __builtin_nontemporal_store(prev[mb][i], rowp + lane_off);
+        // row and block offset in a scalar register, the lane's own offset in one vector register
+        const int row_off = ((32 * mb + 8 * (i >> 2) + (i & 3)) * (int)ld + col_prev) * 4;
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, (float)prev[mb][i]), out_prev,
+                                              (int)(lane_off * 4u), row_off, 2 /* non-temporal */);
       }
     }
   }
@@ -303,6 +305,10 @@ __global__ __launch_bounds__(RW_THREADS) void radial_weights_kernel(const float4
     // neither the matrix pipes nor the memory pipeline are fed evenly.
     float* const wave_base = w + (size_t)e_base * PE;                    // the same for all lanes
     const unsigned lane_off = (unsigned)(4 * hh * PE + m);
+    // the wave's RW_ROWS rows of w as a buffer (used on the path where all of them exist)
+    const __amdgpu_buffer_rsrc_t wave_rows =
+        __builtin_amdgcn_make_buffer_rsrc((void*)wave_base, 0, all_rows ? RW_ROWS * PE * 4 : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t no_rows = wave_rows;
     float* const out_base = wave_base + lane_off;
     auto store_block = [&](const float16v (&acc)[RW_MB], int nb) {      // general case: ragged rows / last columns
       if (nb * 32 + m >= PE || !any_row) return;
@@ -319,14 +325,14 @@ __global__ __launch_bounds__(RW_THREADS) void radial_weights_kernel(const float4
     auto step = [&](float16v (&acc)[RW_MB], const float16v (&prev)[RW_MB], int nb) {
       const bool fast = all_rows && nb * 32 <= PE;                      // block nb - 1 lies wholly inside the row
       if (fast)
-        rw_block<true>(sB[nb & 1], a_frag, m, hh, acc, prev, wave_base + (nb - 1) * 32, lane_off, (size_t)PE);
+        rw_block<true>(sB[nb & 1], a_frag, m, hh, acc, prev, wave_rows, (nb - 1) * 32, lane_off, (size_t)PE);
       else {
-        rw_block<false>(sB[nb & 1], a_frag, m, hh, acc, prev, nullptr, 0, 0);
+        rw_block<false>(sB[nb & 1], a_frag, m, hh, acc, prev, no_rows, 0, 0, 0);
         store_block(prev, nb - 1);
       }
     };
     float16v acc0[RW_MB], acc1[RW_MB];
-    rw_block<false>(sB[0], a_frag, m, hh, acc0, acc0, nullptr, 0, 0);
+    rw_block<false>(sB[0], a_frag, m, hh, acc0, acc0, no_rows, 0, 0, 0);
     int nb = 1;
     for (; nb + 1 < n_blocks; nb += 2) {
       step(acc1, acc0, nb);
@@ -339,18 +345,19 @@ __global__ __launch_bounds__(RW_THREADS) void radial_weights_kernel(const float4
       store_block(acc0, n_blocks - 1);
     }
   } else {
+    const __amdgpu_buffer_rsrc_t no_rows = __builtin_amdgcn_make_buffer_rsrc((void*)w, 0, 0, 0x00020000);
     const int row_words = w_half_row_words(PE);
     uint32_t* const out_base = reinterpret_cast<uint32_t*>(w) + (size_t)(e_base + 4 * hh) * row_words + m;
     for (int nb = 0; nb < n_blocks; nb += 2) {
       float16v acc[RW_MB];
       uint32_t word[RW_MB][16];
-      rw_block<false>(sB[0], a_frag, m, hh, acc, acc, nullptr, 0, 0);          // nb is even
+      rw_block<false>(sB[0], a_frag, m, hh, acc, acc, no_rows, 0, 0, 0);          // nb is even
 #pragma unroll
       for (int mb = 0; mb < RW_MB; ++mb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) word[mb][i] = w_half_bits(acc[mb][i]);
       if (nb + 1 < n_blocks) {                      // (the same for every wave of the workgroup, loader included)
-        rw_block<false>(sB[1], a_frag, m, hh, acc, acc, nullptr, 0, 0);
+        rw_block<false>(sB[1], a_frag, m, hh, acc, acc, no_rows, 0, 0, 0);
 #pragma unroll
         for (int mb = 0; mb < RW_MB; ++mb)
 #pragma unroll
