@@ -148,7 +148,15 @@ __global__ __launch_bounds__(256) void split_w2_kernel(const float* __restrict__
 // register is stored as two full 128-byte lines.
 #define RW_MB 2                 // 32-row MFMA blocks per compute wave
 #define RW_ROWS (32 * RW_MB)
+#ifndef RW_COMPUTE_WAVES
 #define RW_COMPUTE_WAVES 7
+#endif
+#ifndef RW_PIPELINE
+#define RW_PIPELINE 1
+#endif
+#ifndef RW_MIN_WG
+#define RW_MIN_WG 1
+#endif
 #define RW_THREADS ((RW_COMPUTE_WAVES + 1) * 64)
 #define RW_BROW4 25   // uint4 per staged W_r2 row: 24 of data (3 pieces x 64 bf16) + 1 of padding (bank spread)
 
@@ -170,20 +178,15 @@ __device__ __forceinline__ void rw_block(const uint4* __restrict__ sB_nb, const 
                                          int hh, float16v (&acc)[RW_MB], const float16v (&prev)[RW_MB],
                                          __amdgpu_buffer_rsrc_t out_prev, int col_prev, unsigned lane_off, size_t ld) {
   lds_barrier_acquire();
-  uint4 b_frag[3][4];
-  {
-    const uint4* row = sB_nb + m * RW_BROW4 + hh * 4;
-#pragma unroll
-    for (int p = 0; p < 3; ++p)
-#pragma unroll
-      for (int t = 0; t < 4; ++t) b_frag[p][t] = row[p * 8 + t];
-  }
+  const uint4* row = sB_nb + m * RW_BROW4 + hh * 4;
 #pragma unroll
   for (int mb = 0; mb < RW_MB; ++mb)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[mb][i] = 0.0f;
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
+    // the pieces of W_r2 of this step only (12 registers; the next step's are read while these are multiplied)
+    const uint4 b_frag[3] = {row[t], row[8 + t], row[16 + t]};
     // smallest terms first: (lo,hi) (hi,lo) (mid,mid) (mid,hi) (hi,mid) (hi,hi)
     const int pa[6] = {2, 0, 1, 1, 0, 0};
     const int pb[6] = {0, 2, 1, 0, 1, 0};
@@ -192,7 +195,7 @@ __device__ __forceinline__ void rw_block(const uint4* __restrict__ sB_nb, const 
 #pragma unroll
       for (int mb = 0; mb < RW_MB; ++mb)
         acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a_frag[mb][pa[q]][t]),
-                                                          as_bf16x8(b_frag[pb[q]][t]), acc[mb], 0, 0, 0);
+                                                          as_bf16x8(b_frag[pb[q]]), acc[mb], 0, 0, 0);
     if constexpr (STORE) {
       static_assert(RW_MB == 2, "a quarter of the previous block per contraction step");
 #pragma unroll
@@ -217,7 +220,7 @@ __device__ __forceinline__ void rw_block(const uint4* __restrict__ sB_nb, const 
 
 // HALF: w is stored in half precision (layout of w_half.h), two column blocks per 32-bit word.
 template <bool HALF>
-__global__ __launch_bounds__(RW_THREADS) void radial_weights_kernel(const float4* __restrict__ rhat_d, long n_edges,
+__global__ __launch_bounds__(RW_THREADS, RW_MIN_WG) void radial_weights_kernel(const float4* __restrict__ rhat_d, long n_edges,
                                                              const float* __restrict__ W_r1,
                                                              const uint16_t* __restrict__ W2s,
                                                              float* __restrict__ w, int n_rbf, int PE,
@@ -305,20 +308,22 @@ __global__ __launch_bounds__(RW_THREADS) void radial_weights_kernel(const float4
     // neither the matrix pipes nor the memory pipeline are fed evenly.
     float* const wave_base = w + (size_t)e_base * PE;                    // the same for all lanes
     const unsigned lane_off = (unsigned)(4 * hh * PE + m);
-    // the wave's RW_ROWS rows of w as a buffer (used on the path where all of them exist)
+    // The wave's rows of w as a buffer that ends with the last existing edge: a store to a row past it is out of
+    // range and discarded by the hardware's range check, so the ragged tile needs no per-row test.
+    const long rows_here = n_edges - e_base < 0 ? 0 : (n_edges - e_base < RW_ROWS ? n_edges - e_base : RW_ROWS);
     const __amdgpu_buffer_rsrc_t wave_rows =
-        __builtin_amdgcn_make_buffer_rsrc((void*)wave_base, 0, all_rows ? RW_ROWS * PE * 4 : 0, 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc((void*)wave_base, 0, (int)(rows_here * PE * 4), 0x00020000);
     const __amdgpu_buffer_rsrc_t no_rows = wave_rows;
-    float* const out_base = wave_base + lane_off;
     auto store_block = [&](const float16v (&acc)[RW_MB], int nb) {      // general case: ragged rows / last columns
-      if (nb * 32 + m >= PE || !any_row) return;
-      float* out = out_base + nb * 32;
+      if (nb * 32 + m >= PE) return;
 #pragma unroll
       for (int mb = 0; mb < RW_MB; ++mb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int r = 32 * mb + 8 * (i >> 2) + (i & 3);               // row relative to e_base + 4*hh
-          if (all_rows || e_base + 4 * hh + r < n_edges) __builtin_nontemporal_store(acc[mb][i], out + (size_t)r * PE);
+          // (the whole offset in the vector register: that is the part the range check looks at)
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, (float)acc[mb][i]), wave_rows,
+                                                (int)((lane_off + (unsigned)(r * PE + nb * 32)) * 4u), 0, 2);
         }
     };
     // block nb -> acc, block nb - 1 (in prev) -> memory
@@ -331,6 +336,7 @@ __global__ __launch_bounds__(RW_THREADS) void radial_weights_kernel(const float4
         store_block(prev, nb - 1);
       }
     };
+#if RW_PIPELINE
     float16v acc0[RW_MB], acc1[RW_MB];
     rw_block<false>(sB[0], a_frag, m, hh, acc0, acc0, no_rows, 0, 0, 0);
     int nb = 1;
@@ -344,6 +350,25 @@ __global__ __launch_bounds__(RW_THREADS) void radial_weights_kernel(const float4
     } else {
       store_block(acc0, n_blocks - 1);
     }
+#else
+    (void)step;
+    for (int nb = 0; nb < n_blocks; ++nb) {
+      float16v acc[RW_MB];
+      rw_block<false>(sB[nb & 1], a_frag, m, hh, acc, acc, no_rows, 0, 0, 0);
+      if (all_rows && (nb + 1) * 32 <= PE) {
+#pragma unroll
+        for (int mb = 0; mb < RW_MB; ++mb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int row_off = ((32 * mb + 8 * (i >> 2) + (i & 3)) * PE + nb * 32) * 4;
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, (float)acc[mb][i]), wave_rows,
+                                                  (int)(lane_off * 4u), row_off, 2);
+          }
+      } else {
+        store_block(acc, nb);
+      }
+    }
+#endif
   } else {
     const __amdgpu_buffer_rsrc_t no_rows = __builtin_amdgcn_make_buffer_rsrc((void*)w, 0, 0, 0x00020000);
     const int row_words = w_half_row_words(PE);
