@@ -211,9 +211,13 @@ __device__ __forceinline__ void rw_block(const uint4* __restrict__ sB_nb, const 
   if constexpr (STORE) {
     // keep the stores spread between the matrix-core instructions (the scheduler would otherwise bunch them up)
 #pragma unroll
-    for (int g = 0; g < 16; ++g) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);   // 3 MFMA
-      __builtin_amdgcn_sched_group_barrier(0x040, 2, 0);   // 2 global stores
+#ifndef RW_SG_M
+#define RW_SG_M 3
+#define RW_SG_S 2
+#endif
+    for (int g = 0; g < 48 / RW_SG_M; ++g) {
+      __builtin_amdgcn_sched_group_barrier(0x008, RW_SG_M, 0);   // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x040, RW_SG_S, 0);   // global stores
     }
   }
 }
