@@ -201,10 +201,11 @@ __device__ __forceinline__ void rw_block(const uint4* __restrict__ sB_nb, const 
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const int idx = 8 * t + j, mb = idx >> 4, i = idx & 15;
-        // row and block offset in a scalar register, the lane's own offset in one vector register
+        // row and block offset (the same for all lanes) added to the lane's own offset: one vector add per store, and
+        // the whole offset is what the range check of the buffer sees (rows the wave does not own are discarded)
         const int row_off = ((32 * mb + 8 * (i >> 2) + (i & 3)) * (int)ld + col_prev) * 4;
         __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, (float)prev[mb][i]), out_prev,
-                                              (int)(lane_off * 4u), row_off, 2 /* non-temporal */);
+                                              (int)(lane_off * 4u) + row_off, 0, 2 /* non-temporal */);
       }
     }
   }
@@ -228,7 +229,7 @@ __global__ __launch_bounds__(RW_THREADS, RW_MIN_WG) void radial_weights_kernel(c
                                                              const float* __restrict__ W_r1,
                                                              const uint16_t* __restrict__ W2s,
                                                              float* __restrict__ w, int n_rbf, int PE,
-                                                             float r_cut) {
+                                                             float r_cut, int rows_per_wave) {
   __shared__ float sW1[32 * EGNN_HIDDEN];  // [b][j], n_rbf <= 32
   __shared__ uint4 sB[2][32 * RW_BROW4];
   const int tid = threadIdx.x;
@@ -263,9 +264,13 @@ __global__ __launch_bounds__(RW_THREADS, RW_MIN_WG) void radial_weights_kernel(c
   }
 
   const int m = lane & 31, hh = lane >> 5;
-  const long e_base = ((long)blockIdx.x * RW_COMPUTE_WAVES + wave) * RW_ROWS;
-  const bool any_row = e_base < n_edges;
-  const bool all_rows = e_base + RW_ROWS <= n_edges;
+  // a wave owns rows_per_wave <= RW_ROWS consecutive edges (the launch spreads the edges evenly over a whole number
+  // of rounds of workgroups); it computes RW_ROWS rows, the surplus ones are its neighbour's and are not stored
+  const long e_base = ((long)blockIdx.x * RW_COMPUTE_WAVES + wave) * rows_per_wave;
+  const long rows_left = n_edges - e_base;
+  const int rows_here = rows_left <= 0 ? 0 : (rows_left < rows_per_wave ? (int)rows_left : rows_per_wave);
+  const bool any_row = rows_here > 0;
+  const bool all_rows = rows_here == RW_ROWS;
 
   // A operand: hidden activations (times the cutoff envelope) of RW_MB x 32 edges, this lane's 32 units, in pieces
   uint4 a_frag[RW_MB][3][4];
@@ -312,11 +317,10 @@ __global__ __launch_bounds__(RW_THREADS, RW_MIN_WG) void radial_weights_kernel(c
     // neither the matrix pipes nor the memory pipeline are fed evenly.
     float* const wave_base = w + (size_t)e_base * PE;                    // the same for all lanes
     const unsigned lane_off = (unsigned)(4 * hh * PE + m);
-    // The wave's rows of w as a buffer that ends with the last existing edge: a store to a row past it is out of
-    // range and discarded by the hardware's range check, so the ragged tile needs no per-row test.
-    const long rows_here = n_edges - e_base < 0 ? 0 : (n_edges - e_base < RW_ROWS ? n_edges - e_base : RW_ROWS);
+    // The wave's own rows of w as a buffer: a store to a row past them is out of range and discarded by the
+    // hardware's range check, so no store needs a per-row test.
     const __amdgpu_buffer_rsrc_t wave_rows =
-        __builtin_amdgcn_make_buffer_rsrc((void*)wave_base, 0, (int)(rows_here * PE * 4), 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc((void*)wave_base, 0, rows_here * PE * 4, 0x00020000);
     const __amdgpu_buffer_rsrc_t no_rows = wave_rows;
     auto store_block = [&](const float16v (&acc)[RW_MB], int nb) {      // general case: ragged rows / last columns
       if (nb * 32 + m >= PE) return;
@@ -332,7 +336,7 @@ __global__ __launch_bounds__(RW_THREADS, RW_MIN_WG) void radial_weights_kernel(c
     };
     // block nb -> acc, block nb - 1 (in prev) -> memory
     auto step = [&](float16v (&acc)[RW_MB], const float16v (&prev)[RW_MB], int nb) {
-      const bool fast = all_rows && nb * 32 <= PE;                      // block nb - 1 lies wholly inside the row
+      const bool fast = nb * 32 <= PE;                                  // block nb - 1 lies wholly inside the row
       if (fast)
         rw_block<true>(sB[nb & 1], a_frag, m, hh, acc, prev, wave_rows, (nb - 1) * 32, lane_off, (size_t)PE);
       else {
@@ -359,14 +363,14 @@ __global__ __launch_bounds__(RW_THREADS, RW_MIN_WG) void radial_weights_kernel(c
     for (int nb = 0; nb < n_blocks; ++nb) {
       float16v acc[RW_MB];
       rw_block<false>(sB[nb & 1], a_frag, m, hh, acc, acc, no_rows, 0, 0, 0);
-      if (all_rows && (nb + 1) * 32 <= PE) {
+      if ((nb + 1) * 32 <= PE) {
 #pragma unroll
         for (int mb = 0; mb < RW_MB; ++mb)
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
             const int row_off = ((32 * mb + 8 * (i >> 2) + (i & 3)) * PE + nb * 32) * 4;
             __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, (float)acc[mb][i]), wave_rows,
-                                                  (int)(lane_off * 4u), row_off, 2);
+                                                  (int)(lane_off * 4u) + row_off, 0, 2);
           }
       } else {
         store_block(acc, nb);
@@ -439,14 +443,22 @@ int egnn_launch_radial(egnn_ctx* ctx, int which, const float* rhat_d, int64_t n_
   int rc = egnn_launch_split_w2(ctx, which, W_r2, scratch, stream);
   if (rc) return rc;
   uint16_t* W2s = (uint16_t*)scratch;
+  // Workgroups: enough for RW_ROWS rows per wave; beyond one round of the 256 CUs their number is rounded up to whole
+  // rounds and the edges are spread evenly, so that the last round is as full as the others.
   const long per_wg = (long)RW_ROWS * RW_COMPUTE_WAVES;
-  dim3 grid((unsigned)((n_edges + per_wg - 1) / per_wg)), block(RW_THREADS);
+  long n_wg = (n_edges + per_wg - 1) / per_wg;
+  int rows_per_wave = RW_ROWS;
+  if (!half && n_wg > EGNN_CUS) {
+    n_wg = (n_wg + EGNN_CUS - 1) / EGNN_CUS * EGNN_CUS;
+    rows_per_wave = (int)((n_edges + n_wg * RW_COMPUTE_WAVES - 1) / (n_wg * RW_COMPUTE_WAVES));
+  }
+  dim3 grid((unsigned)n_wg), block(RW_THREADS);
   if (half)
     hipLaunchKernelGGL(radial_weights_kernel<true>, grid, block, 0, stream, reinterpret_cast<const float4*>(rhat_d),
-                       (long)n_edges, W_r1, W2s, w, ctx->desc.n_rbf, PE, ctx->desc.r_cut);
+                       (long)n_edges, W_r1, W2s, w, ctx->desc.n_rbf, PE, ctx->desc.r_cut, rows_per_wave);
   else
     hipLaunchKernelGGL(radial_weights_kernel<false>, grid, block, 0, stream, reinterpret_cast<const float4*>(rhat_d),
-                       (long)n_edges, W_r1, W2s, w, ctx->desc.n_rbf, PE, ctx->desc.r_cut);
+                       (long)n_edges, W_r1, W2s, w, ctx->desc.n_rbf, PE, ctx->desc.r_cut, rows_per_wave);
   EGNN_LAUNCH_CHECK(ctx, "radial_weights_kernel");
   return EGNN_OK;
 }

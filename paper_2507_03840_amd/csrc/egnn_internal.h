@@ -45,6 +45,7 @@ struct egnn_ctx {
   std::string err;
 };
 
+#define EGNN_CUS 256    // compute units of the GPU this library is written for
 #define EGNN_STAGES 5   // stages per composite call
 #define EGNN_TIMED_KINDS 4
 
