@@ -95,7 +95,7 @@ def main():
     ap.add_argument("--cpu-nodes", type=int, default=1024)
     ap.add_argument("--train-steps", type=int, default=3,
                     help="training steps (forward + loss + reverse pass, config 5) timed after the main region; 0 = skip")
-    ap.add_argument("--fused", type=int, default=0, choices=[0, 1],
+    ap.add_argument("--fused", type=int, default=0, choices=[0, 1, 2],
                     help="1: radial weights and messages in one kernel (weights never written to memory)")
     ap.add_argument("--no-partition", action="store_true",
                     help="skip the extra timing of the Low-NN partitioner and of the halo pack / unpack")

@@ -170,7 +170,8 @@ extern "C" int egnn_timing_read(egnn_ctx* ctx, float ms[EGNN_TIMED_KINDS * EGNN_
 extern "C" int egnn_set_option(egnn_ctx* ctx, int32_t option, int32_t value) {
   if (!ctx) return EGNN_EINVAL;
   if (option == EGNN_OPT_FUSED) {
-    ctx->use_fused = value != 0;
+    if (value < 0 || value > 2) return egnn_fail(ctx, EGNN_EINVAL, "set_option: EGNN_OPT_FUSED takes 0, 1 or 2");
+    ctx->use_fused = value;
     return EGNN_OK;
   }
   if (option == EGNN_OPT_W_FP16) {
@@ -221,10 +222,12 @@ size_t egnn_w_bytes(const egnn_ctx* ctx, int which, int64_t n_edges) {
   return full > half ? full : half;
 }
 
-static size_t layer_w_bytes(const egnn_ctx* ctx, int64_t n_edges) {
+static size_t layer_w_bytes(const egnn_ctx* ctx, int64_t n_edges, int32_t n_total) {
   const size_t w = egnn_w_bytes(ctx, 0, n_edges);
   const size_t f = egnn_fused_supported(ctx) ? egnn_fused_scratch_bytes(ctx, n_edges) : 0;
-  return w > f ? w : f;
+  const size_t f2 = egnn_fused_lane_supported(ctx) ? egnn_fused_lane_scratch_bytes(ctx, n_total) : 0;
+  const size_t m = w > f ? w : f;
+  return m > f2 ? m : f2;
 }
 
 static size_t layer_ws(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, int32_t n_total, int with_w) {
@@ -233,7 +236,7 @@ static size_t layer_ws(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, in
   c.take((size_t)n_edges * 16);
   c.take((size_t)n_total * row);
   c.take((size_t)n_owned * row);
-  if (with_w) c.take(layer_w_bytes(ctx, n_edges));
+  if (with_w) c.take(layer_w_bytes(ctx, n_edges, n_total));
   if (with_w) c.take(egnn_radial_ws_bytes(ctx, 0));
   return c.used;
 }
@@ -352,7 +355,7 @@ static int layer_forward_impl(egnn_ctx* ctx, const egnn_graph* g, const float* p
   float* rhat_d = (float*)c.take((size_t)g->n_edges * 16);
   float* h = (float*)c.take((size_t)g->n_total * row);
   float* a = (float*)c.take((size_t)g->n_owned * row);
-  const size_t w_bytes = with_w ? layer_w_bytes(ctx, g->n_edges) : 0;
+  const size_t w_bytes = with_w ? layer_w_bytes(ctx, g->n_edges, g->n_total) : 0;
   float* w = with_w ? (float*)c.take(w_bytes) : nullptr;
   const bool saving = w_save || a_save;
   if (w_save && with_w) w = w_save;
@@ -364,7 +367,8 @@ static int layer_forward_impl(egnn_ctx* ctx, const egnn_graph* g, const float* p
   // Default: S3 writes the weight tensor, S4 reads it.  Opt-in (EGNN_OPT_FUSED): the weights are produced and
   // consumed inside one kernel and never leave the chip.
   // (the scratch of the fused route lives where the weight tensor would be)
-  const bool fused = with_w && !saving && ctx->use_fused && egnn_fused_supported(ctx);
+  const bool fused_lane = with_w && !saving && ctx->use_fused == 2 && egnn_fused_lane_supported(ctx);
+  const bool fused = fused_lane || (with_w && !saving && ctx->use_fused == 1 && egnn_fused_supported(ctx));
   const bool half = with_w && !saving && !fused && ctx->w_half;   // storage precision of the weight tensor between S3 and S4
   if (fused) {
     if (g->n_edges > 0 && (rc = egnn_launch_split_w2(ctx, 0, W_r2, w2s, st))) return rc;
@@ -374,7 +378,9 @@ static int layer_forward_impl(egnn_ctx* ctx, const egnn_graph* g, const float* p
   tm.mark(1);
   if ((rc = egnn_launch_node_mix(ctx, x_in, W_pre, nullptr, nullptr, h, g->n_total, st))) return rc;
   tm.mark(2);
-  if (fused) {
+  if (fused_lane) {
+    if ((rc = egnn_launch_layer_fused_lane(ctx, g, rhat_d, h, W_r1, w2s, w, w_bytes, a, st))) return rc;
+  } else if (fused) {
     if ((rc = egnn_launch_layer_fused(ctx, g, rhat_d, h, W_r1, w2s, w, w_bytes, a, st))) return rc;
   } else {
     if ((rc = egnn_launch_tp_segsum(ctx, g, rhat_d, h, with_w ? w : w_edge, a, st, half))) return rc;

@@ -36,7 +36,7 @@ struct egnn_ctx {
   int ev_max_calls = 0;
   CellGrid nl_grid;                      // grid of the last egnn_nlist_count that used the cell list
   int nl_grid_atoms = -1;                //   and the atom count it was built for
-  bool use_fused = false;                // egnn_set_option(EGNN_OPT_FUSED)
+  int use_fused = 0;                     // egnn_set_option(EGNN_OPT_FUSED): 0 two kernels, 1 / 2 the fused designs
   bool w_half = false;                   // egnn_set_option(EGNN_OPT_W_FP16)
   // index tables of the readout / on-site kernels in the order the kernels read them, built on first use and kept:
   // the asynchronous uploads into the caller's workspace read this memory, which lives as long as the context
@@ -106,6 +106,10 @@ size_t egnn_w_bytes(const egnn_ctx*, int which, int64_t n_edges);   // room for 
 size_t egnn_radial_ws_bytes(const egnn_ctx*, int which);
 int egnn_launch_split_w2(egnn_ctx*, int which, const float* W_r2, void* scratch, hipStream_t);
 bool egnn_fused_supported(const egnn_ctx*);
+bool egnn_fused_lane_supported(const egnn_ctx*);
+size_t egnn_fused_lane_scratch_bytes(const egnn_ctx*, int32_t n_total);
+int egnn_launch_layer_fused_lane(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* h, const float* W_r1,
+                                 const void* W2s, void* scratch, size_t scratch_bytes, float* a, hipStream_t);
 size_t egnn_fused_scratch_bytes(const egnn_ctx*, int64_t n_edges);
 int egnn_launch_layer_fused(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* h, const float* W_r1,
                             const void* W2s, void* scratch, size_t scratch_bytes, float* a, hipStream_t);

@@ -60,7 +60,7 @@ def gpu_forward(w, wt, agg_norm, with_readout=True, fused=False, w_fp16=False):
     from paper_2507_03840_amd import binding as B
     m = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, agg_norm, n_layers=w.n_layers, orb_l=w.orb_l)
     if fused:
-        m.egnn_set_option(B.OPT_FUSED, 1)
+        m.egnn_set_option(B.OPT_FUSED, int(fused))   # True / 1: first fused design, 2: second
     if w_fp16:
         m.egnn_set_option(B.OPT_W_FP16, 1)
     pos = B.to_device(w.pos)

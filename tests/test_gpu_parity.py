@@ -174,7 +174,7 @@ def test_tp_segsum_edge_along_polar_axis(B):
 
 
 # ------------------------------------------------------------------------------------------ whole model
-@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("fused", [False, True, 2])
 @pytest.mark.parametrize("index", [1, 2])
 def test_model_forward_configs_full(B, index, fused):
     """Configs 1 and 2 in full: species embedding, all layers, H_ij readout, every element; once through the materialised weight tensor
@@ -212,6 +212,16 @@ def test_model_forward_small_shapes(B, lmax, E, periodic, n, n_owned):
                                                      (2, 8, 330, 25, 9.5), (4, 16, 330, 12, 9.5)])
 def test_model_forward_small_shapes_fused(B, lmax, E, n, n_owned, r_cut):
     _model_forward_small(B, lmax, E, False, n, n_owned, True, r_cut)
+
+
+@pytest.mark.parametrize("lmax,E,n,n_owned,r_cut", [(1, 16, 120, 120, 4.0), (2, 64, 100, 60, 4.0), (3, 32, 150, 90, 4.0),
+                                                     (4, 16, 70, 70, 4.0), (0, 32, 50, 50, 4.0), (4, 64, 90, 70, 4.0),
+                                                     (1, 8, 60, 60, 4.0), (4, 128, 60, 40, 4.0), (3, 8, 150, 90, 4.0),
+                                                     # up to ~300 incoming edges per node: more than one round of 224
+                                                     (2, 8, 330, 25, 9.5), (4, 16, 330, 12, 9.5)])
+def test_model_forward_small_shapes_fused_lane(B, lmax, E, n, n_owned, r_cut):
+    """The second fused design (weights produced on the matrix cores in the registers of the consuming lane)."""
+    _model_forward_small(B, lmax, E, False, n, n_owned, 2, r_cut)
 
 
 def _model_forward_small(B, lmax, E, periodic, n, n_owned, fused, r_cut=4.0):
