@@ -68,8 +68,8 @@ __global__ __launch_bounds__(256) void f2_pair_kernel(const float* __restrict__ 
 }
 
 // Sum over the 32 lanes of a half wavefront with data-parallel-primitive moves (vector ALU only, no LDS): four steps
-// inside the rows of 16 lanes, then lane 15 of rows 0 and 2 is added into rows 1 and 3, whose lanes hold the sum of
-// their half.  Each step is applied to all N values before the next one, so that no instruction waits for its
+// inside the rows of 16 lanes, then lane 15 of every row is added into the row after it: the lanes of rows 1 and 3
+// hold the sum of their half (rows 0 and 2 hold other things and are not read).  Each step is applied to all N values before the next one, so that no instruction waits for its
 // predecessor.
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ float f2_dpp(float x) {
@@ -87,7 +87,7 @@ __device__ __forceinline__ void f2_sum32(float (&x)[N]) {
 #pragma unroll
   for (int i = 0; i < N; ++i) x[i] += f2_dpp<0x140, 0xF>(x[i]);   // row_mirror: the other group of 8 of the row
 #pragma unroll
-  for (int i = 0; i < N; ++i) x[i] += f2_dpp<0x142, 0xA>(x[i]);   // row_bcast 15 into rows 1 and 3 (0 elsewhere)
+  for (int i = 0; i < N; ++i) x[i] += f2_dpp<0x142, 0xF>(x[i]);   // row_bcast 15: every row adds the row before it
 }
 
 template <int LMAX>
@@ -173,7 +173,8 @@ __global__ __launch_bounds__(F2_THREADS) void f2_kernel(const int* __restrict__ 
 #pragma unroll
           for (int s = 0; s < 32; ++s) pre[s] += wrow[s] * Bv;
         }
-        const float fc = 0.5f * (1.0f + cosf(3.14159265358979323846f * g.w / r_cut));
+        // (a lane past the node's last edge gets a zero envelope: zero weights, a zero message, nothing to mask later)
+        const float fc = valid ? 0.5f * (1.0f + cosf(3.14159265358979323846f * g.w / r_cut)) : 0.0f;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           uint32_t ph[4], pm[4], pl[4];
@@ -253,17 +254,14 @@ __global__ __launch_bounds__(F2_THREADS) void f2_kernel(const int* __restrict__ 
         egnn_from_bond_frame<LMAX>(o, trig);
         // ---- sum over the 32 edges of the wave (fixed order), one partial row per channel
         float* prow = sPw + (size_t)(cp * 2 + hh) * D;
-        float x[D];
-#pragma unroll
-        for (int i = 0; i < D; ++i) x[i] = valid ? o[i] : 0.0f;
-        f2_sum32<D>(x);
+        f2_sum32<D>(o);
         if (m == 16) {
           if (r == 0) {
 #pragma unroll
-            for (int i = 0; i < D; ++i) prow[i] = x[i];
+            for (int i = 0; i < D; ++i) prow[i] = o[i];
           } else {
 #pragma unroll
-            for (int i = 0; i < D; ++i) prow[i] += x[i];
+            for (int i = 0; i < D; ++i) prow[i] += o[i];
           }
         }
       }

@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
 
-@pytest.mark.parametrize("index,fused", [(3, False), (4, False), (3, True), (4, True)])
+@pytest.mark.parametrize("index,fused", [(3, False), (4, False), (3, True), (4, True), (3, 2), (4, 2)])
 def test_fullsize_sampled_rows(index, fused):
     import torch
     assert torch.cuda.is_available()
