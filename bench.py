@@ -96,7 +96,7 @@ def main():
     ap.add_argument("--train-steps", type=int, default=3,
                     help="training steps (forward + loss + reverse pass, config 5) timed after the main region; 0 = skip")
     ap.add_argument("--fused", type=int, default=0, choices=[0, 1, 2],
-                    help="1: radial weights and messages in one kernel (weights never written to memory)")
+                    help="1 / 2: radial weights and messages in one kernel (weights never written to memory), first / second design")
     ap.add_argument("--no-partition", action="store_true",
                     help="skip the extra timing of the Low-NN partitioner and of the halo pack / unpack")
     ap.add_argument("--no-hamiltonian", action="store_true",
@@ -194,6 +194,34 @@ def main():
                   layer_ms={n: ms16[i] / max(1, calls16[0]) for i, n in enumerate(B.LAYER_STAGES)},
                   readout_ms={n: ms16[5 + i] / max(1, calls16[1]) for i, n in enumerate(B.READOUT_STAGES)} if w.readout else None,
                   note="EGNN_OPT_W_FP16: w rounded to half precision once, fp32 products and sums; not the fp32 figure")
+
+    # ---- the same fp32 step with S3 and S4 as one kernel whose radial weights never leave the registers
+    #      (EGNN_OPT_FUSED = 2); reported next to the main figure unless --fused already selected a fused route ----
+    fused_lane = None
+    if args.fused == 0:
+        m.egnn_set_option(B.OPT_FUSED, 2)
+        for _ in range(2):
+            step()
+        torch.cuda.synchronize()
+        nfl = max(3, args.steps // 2)
+        m.egnn_timing_enable(nfl * (w.n_layers + 1))
+        t1 = time.perf_counter()
+        for _ in range(nfl):
+            step()
+        torch.cuda.synchronize()
+        dtfl = (time.perf_counter() - t1) / nfl
+        msfl, callsfl = m.egnn_timing_read()
+        m.egnn_timing_enable(0)
+        m.egnn_set_option(B.OPT_FUSED, 0)
+        layer_fl = msfl[3] / max(1, callsfl[0])
+        # bf16 matrix-core work of the radial contraction: six piece products per fp32 product
+        mfma_flop = 6.0 * 2.0 * 64 * m.n_paths * w.channels * n_edges
+        fused_lane = dict(ms_per_step=1e3 * dtfl, steps=nfl, edge_layer_evaluations_per_s=n_edges * w.n_layers / dtfl,
+                          s3_s4_kernel_ms=layer_fl, edges_per_s=n_edges / (layer_fl * 1e-3),
+                          bf16_mfma_TFLOPs=mfma_flop / (layer_fl * 1e-3) / 1e12, bf16_mfma_peak_TFLOPs=2500.0,
+                          note="EGNN_OPT_FUSED = 2: radial weights produced on the matrix cores in the registers of the "
+                               "lane that consumes them, no weight tensor in memory; bound by matrix-core plus vector "
+                               "work of the same SIMD, not by HBM")
 
     # ---- S7: training step on the same graph and model (config 5 when the workload is config 3) ----
     training = None
@@ -479,6 +507,7 @@ def main():
     }
     out["training_step"] = training
     out["w_fp16_storage"] = w_fp16
+    out["s3_s4_fused_in_registers"] = fused_lane
     out["hbm_calibration"] = calibration
     if so2 is not None:
         out["so2_message_sum"] = so2

@@ -152,11 +152,14 @@ int egnn_tp_segsum_f16(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, 
 int egnn_node_mix(egnn_ctx* ctx, const float* x1, const float* W1, const float* x2, const float* W2,
                   float* y, int32_t n_nodes, void* stream);
 
-/* Options.  EGNN_OPT_FUSED (default 0): when 1, egnn_layer_forward with its own radial MLP, lmax >= 1, a power of
- * two >= 8 channels and at most 32 radial bases produces and consumes the radial weights inside one kernel (they
- * are never written to memory); when 0 it goes through the materialised weight tensor (S3 then S4), as it always
- * does for caller-supplied weights and other shapes.  Both routes compute the same function; the two-kernel route
- * is the faster one at present. */
+/* Options.  EGNN_OPT_FUSED (default 0): when 1 or 2, egnn_layer_forward with its own radial MLP, a power of two >= 8
+ * channels and at most 32 radial bases produces and consumes the radial weights inside one kernel (they are never
+ * written to memory); when 0 it goes through the materialised weight tensor (S3 then S4), as it always does for
+ * caller-supplied weights, for the _save calls and for shapes the chosen kernel does not support.  All routes compute
+ * the same function.  1: producer and consumer waves hand the weights over through LDS (needs lmax >= 1).
+ * 2: transposed matrix-core tiles put the weights of one (edge, channel) into the registers of the lane that consumes
+ * them (needs its LDS tiles to fit: up to 64 channels at lmax 4).  At 32 channels route 2 runs about as fast as the
+ * two-kernel route, at 64 channels about 10 % faster; route 1 is slower than both. */
 #define EGNN_OPT_FUSED 1
 /* EGNN_OPT_W_FP16 (default 0): when 1, the radial weights that egnn_layer_forward (two-kernel route, own radial MLP)
  * and egnn_readout_hij pass from S3 to S4 / S6 inside their workspace are stored in half precision, as by
