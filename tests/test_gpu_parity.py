@@ -224,6 +224,13 @@ def test_model_forward_small_shapes_fused_lane(B, lmax, E, n, n_owned, r_cut):
     _model_forward_small(B, lmax, E, False, n, n_owned, 2, r_cut)
 
 
+@pytest.mark.parametrize("fused", [1, 2])
+@pytest.mark.parametrize("r_cut", [2.0, 2.6])
+def test_fused_sparse_graph(B, r_cut, fused):
+    """Few edges per node, and nodes without any."""
+    _model_forward_small(B, 2, 16, False, 200, 150, fused, r_cut)
+
+
 def _model_forward_small(B, lmax, E, periodic, n, n_owned, fused, r_cut=4.0):
     """Small ragged cases over every supported degree and channel width, with halo rows, two layers, readout."""
     w = _cluster(n, n_owned, lmax, E, n_rbf=6, r_cut=r_cut, seed=30 + lmax, periodic=periodic)
@@ -266,7 +273,8 @@ def test_layer_forward_with_given_edge_weights_and_errors(B):
     assert e.value.code == -1
 
 
-def test_empty_graph_layer(B):
+@pytest.mark.parametrize("fused", [0, 1, 2])
+def test_empty_graph_layer(B, fused):
     """No edges at all: the layer reduces to the self term."""
     w = _cluster(6, 6, 2, 16, r_cut=0.5, seed=2, density=0.001)
     g = U.oracle_graph(w)
@@ -275,6 +283,7 @@ def test_empty_graph_layer(B):
     W = synth.layer_weights(rng, 2, 16, 8, 64, len(O.tp_paths(2, 2, 2)))
     x = synth.node_features(rng, 6, 2, 16)
     m = B.Egnn(2, 16, 8, w.r_cut, 1.0)
+    m.egnn_set_option(B.OPT_FUSED, fused)
     graph = m.egnn_nlist(B.to_device(w.pos), 6, w.box, w.pbc)
     assert graph.n_edges == 0
     y = m.egnn_layer_forward(graph, B.to_device(w.pos), w.box, B.to_device(x), B.to_device(W), m.workspace(graph))
