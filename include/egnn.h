@@ -187,7 +187,7 @@ int egnn_layer_forward(egnn_ctx* ctx, const egnn_graph* g, const float* pos, con
  * H_k[(a,m_a)][(b,m_b)] = sum_{L,M} C^{(L,M)}_{(l_a m_a)(l_b m_b)} q_k[o(a,b,L)][M], rows = source-atom
  * orbitals, columns = destination-atom orbitals, o(a,b,L) counting ordered shell pairs in row-major
  * shell order with L ascending, separately per L.  V packs V_0 .. V_4, each [n_out(L)][channels].
- * H [n_edges][n_orb][n_orb]. */
+ * H [n_edges][n_orb][n_orb] (may be NULL for a graph without edges). */
 int egnn_readout_hij(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
                      const float* x, const float* W_s, const float* W_t, const float* W_r1,
                      const float* W_r2, const float* V, float* H, void* ws, size_t ws_bytes, void* stream);

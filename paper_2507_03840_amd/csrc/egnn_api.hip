@@ -417,7 +417,8 @@ static int readout_hij_impl(egnn_ctx* ctx, const egnn_graph* g, const float* pos
   int rc = check_graph(ctx, g, "readout_hij");
   if (rc) return rc;
   if (ctx->n_orb <= 0 || ctx->n_orb > 32) return egnn_fail(ctx, EGNN_EINVAL, "readout_hij: need 1..32 orbitals per atom");
-  if (!pos || !box || !x || !W_s || !W_t || !W_r1 || !W_r2 || !V || !H || !ws)
+  // (a graph without edges has no blocks: H may then be NULL)
+  if (!pos || !box || !x || !W_s || !W_t || !W_r1 || !W_r2 || !V || (!H && g->n_edges > 0) || !ws)
     return egnn_fail(ctx, EGNN_EINVAL, "readout_hij: null pointer");
   if (((uintptr_t)ws & 255) != 0) return egnn_fail(ctx, EGNN_EINVAL, "readout_hij: workspace not 256-byte aligned");
   if (ws_bytes < readout_ws(ctx, g->n_edges, g->n_total)) return egnn_fail(ctx, EGNN_EWS, "readout_hij: workspace too small");
@@ -484,6 +485,6 @@ extern "C" int egnn_readout_hij_save(egnn_ctx* ctx, const egnn_graph* g, const f
                                      const float* W_r2, const float* V, float* H, float* w_save, void* ws,
                                      size_t ws_bytes, void* stream) {
   if (!ctx) return EGNN_EINVAL;
-  if (!w_save) return egnn_fail(ctx, EGNN_EINVAL, "readout_hij_save: null pointer");
+  if (!w_save && g && g->n_edges > 0) return egnn_fail(ctx, EGNN_EINVAL, "readout_hij_save: null pointer");
   return readout_hij_impl(ctx, g, pos, box, x, W_s, W_t, W_r1, W_r2, V, H, w_save, ws, ws_bytes, stream);
 }

@@ -186,8 +186,9 @@ static int readout_backward_impl(egnn_ctx* ctx, const egnn_graph* g, const int32
   int rc = check_bwd_graph(ctx, g, col_ptr, perm, "readout_backward");
   if (rc) return rc;
   if (ctx->n_orb <= 0 || ctx->n_orb > 32) return egnn_fail(ctx, EGNN_EINVAL, "readout_backward: need 1..32 orbitals per atom");
-  if (!pos || !box || !x || !W_s || !W_t || !W_r1 || !W_r2 || !V || !dH || !dx || !dW_s || !dW_t || !dW_r1 || !dW_r2 ||
-      !dV || !ws)
+  // (a graph without edges has no blocks: dH may then be NULL; every gradient is zero)
+  if (!pos || !box || !x || !W_s || !W_t || !W_r1 || !W_r2 || !V || (!dH && g->n_edges > 0) || !dx || !dW_s || !dW_t ||
+      !dW_r1 || !dW_r2 || !dV || !ws)
     return egnn_fail(ctx, EGNN_EINVAL, "readout_backward: null pointer");
   if (((uintptr_t)ws & 255) != 0) return egnn_fail(ctx, EGNN_EINVAL, "readout_backward: workspace not 256-byte aligned");
   const int nq = ctx->n_orb * ctx->n_orb, nv = vrows(ctx);

@@ -123,6 +123,34 @@ def test_readout_backward(B, lmax, E, n, n_owned, periodic):
     assert all(e < TOL for e in errs.values()), errs
 
 
+def test_graph_without_edges(B):
+    """No edges at all: no blocks (the block buffers may be NULL), the readout has zero gradients, and the layer and
+    its adjoint reduce to the self term."""
+    lmax, E, n = 2, 16, 6
+    w, g, agg, m, pos, graph, ws, col_ptr, perm = _setup(B, lmax, E, n, n, False, 2, r_cut=0.3)
+    assert graph.n_edges == 0 and len(g[0]) == 0
+    rng = np.random.default_rng(3)
+    x = synth.node_features(rng, n, lmax, E)
+    Wr = synth.readout_weights(rng, lmax, E, w.n_rbf, 64, m.n_paths_readout, sum(m.n_out))
+    H = m.egnn_readout_hij(graph, pos, w.box, B.to_device(x), B.to_device(Wr), ws)
+    assert tuple(H.shape) == (0, 13, 13)
+    dH = synth.normal(rng, (0, 13, 13))
+    dx, grads = m.egnn_readout_backward(graph, col_ptr, perm, pos, w.box, B.to_device(x), B.to_device(Wr),
+                                        B.to_device(dH), ws)
+    assert np.all(dx.cpu().numpy() == 0)
+    assert all(np.all(v.cpu().numpy() == 0) for v in grads.values())
+    W = synth.layer_weights(rng, lmax, E, w.n_rbf, 64, m.n_paths)
+    dy = synth.node_features(rng, n, lmax, E)
+    dx, grads = m.egnn_layer_backward(graph, col_ptr, perm, pos, w.box, B.to_device(x), B.to_device(W),
+                                      B.to_device(dy), ws)
+    # x_out = W_self x: dx = W_self^T dy per degree, dW_self[l] = sum over nodes and m of dy x^T, everything else zero
+    dx_ref, dWs_ref = O.mix_channels_backward(x, W["W_self"], dy.astype(np.float64), lmax)
+    assert U.rel_err(dx.cpu().numpy(), dx_ref) < 1e-5
+    assert U.rel_err(grads["W_self"].cpu().numpy(), dWs_ref) < 1e-5
+    for k in ("W_pre", "W_post", "W_r1", "W_r2"):
+        assert np.all(grads[k].cpu().numpy() == 0), k
+
+
 @pytest.mark.parametrize("index", [1])
 def test_training_step_config(B, index):
     """Whole training step on config 1: forward, MSE against random targets, reverse pass through the readout
