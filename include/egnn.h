@@ -171,7 +171,7 @@ int egnn_set_option(egnn_ctx* ctx, int32_t option, int32_t value);
 
 /* ---- one message-passing layer, forward: S2 -> S5(pre) -> S3+S4 fused (or S3 -> S4) -> S5(post) ----
  * x_out[j] = W_post a_j + W_self x_in[j] for j < n_owned, with h = W_pre x_in.  x_in has n_total rows;
- * x_out has n_owned rows and must not alias x_in.  If w_edge != NULL ([n_edges][P][channels]) it is used as
+ * x_out has n_owned rows (may be NULL if n_owned is 0) and must not alias x_in.  If w_edge != NULL ([n_edges][P][channels]) it is used as
  * the radial weights (W_r1, W_r2 ignored).  ws: at least egnn_workspace_bytes(...) bytes, 256-byte aligned.
  * The call enqueues kernels only (no copies, no memsets, no host synchronisation; box is read on the host at call
  * time), so a stack of layers may be recorded into a graph by stream capture and replayed (tested); egnn_readout_hij

@@ -342,7 +342,9 @@ static int layer_forward_impl(egnn_ctx* ctx, const egnn_graph* g, const float* p
   if (!ctx) return EGNN_EINVAL;
   int rc = check_graph(ctx, g, "layer_forward");
   if (rc) return rc;
-  if (!pos || !box || !x_in || !W_pre || !W_post || !W_self || !x_out || !ws || (!w_edge && (!W_r1 || !W_r2)))
+  // (without owned nodes there is no output row: x_out may then be NULL)
+  if (!pos || !box || !x_in || !W_pre || !W_post || !W_self || (!x_out && g->n_owned > 0) || !ws ||
+      (!w_edge && (!W_r1 || !W_r2)))
     return egnn_fail(ctx, EGNN_EINVAL, "layer_forward: null pointer");
   if (x_in == x_out) return egnn_fail(ctx, EGNN_EINVAL, "layer_forward: x_out must not alias x_in");
   if (((uintptr_t)ws & 255) != 0) return egnn_fail(ctx, EGNN_EINVAL, "layer_forward: workspace not 256-byte aligned");

@@ -115,8 +115,9 @@ static int layer_backward_impl(egnn_ctx* ctx, const egnn_graph* g, const int32_t
   if (!ctx) return EGNN_EINVAL;
   int rc = check_bwd_graph(ctx, g, col_ptr, perm, "layer_backward");
   if (rc) return rc;
-  if (!pos || !box || !x_in || !W_pre || !W_post || !W_self || !W_r1 || !W_r2 || !dx_out || !dx_in || !dW_pre ||
-      !dW_post || !dW_self || !dW_r1 || !dW_r2 || !ws)
+  // (without owned nodes there is no output row: dx_out may then be NULL)
+  if (!pos || !box || !x_in || !W_pre || !W_post || !W_self || !W_r1 || !W_r2 || (!dx_out && g->n_owned > 0) || !dx_in ||
+      !dW_pre || !dW_post || !dW_self || !dW_r1 || !dW_r2 || !ws)
     return egnn_fail(ctx, EGNN_EINVAL, "layer_backward: null pointer");
   if (((uintptr_t)ws & 255) != 0) return egnn_fail(ctx, EGNN_EINVAL, "layer_backward: workspace not 256-byte aligned");
   LayerBwdBufs b;

@@ -151,6 +151,33 @@ def test_graph_without_edges(B):
         assert np.all(grads[k].cpu().numpy() == 0), k
 
 
+def test_no_owned_nodes(B):
+    """A rank that owns nothing (halo atoms only): no edges, no output rows, zero gradients, no error."""
+    import torch
+    lmax, E, n = 2, 16, 5
+    w, g, agg, m, pos, graph, ws, col_ptr, perm = _setup(B, lmax, E, n, 0, False, 3)
+    assert graph.n_edges == 0
+    rng = np.random.default_rng(0)
+    W = synth.layer_weights(rng, lmax, E, w.n_rbf, 64, m.n_paths)
+    Wr = synth.readout_weights(rng, lmax, E, w.n_rbf, 64, m.n_paths_readout, sum(m.n_out))
+    x = synth.node_features(rng, n, lmax, E)
+    for fused in (0, 1, 2):
+        m.egnn_set_option(B.OPT_FUSED, fused)
+        y = m.egnn_layer_forward(graph, pos, w.box, B.to_device(x), B.to_device(W), ws)
+        assert tuple(y.shape) == (0, 9, E)
+    m.egnn_set_option(B.OPT_FUSED, 0)
+    H = m.egnn_readout_hij(graph, pos, w.box, B.to_device(x), B.to_device(Wr), ws)
+    assert tuple(H.shape) == (0, 13, 13)
+    dx, grads = m.egnn_layer_backward(graph, col_ptr, perm, pos, w.box, B.to_device(x), B.to_device(W),
+                                      B.to_device(synth.node_features(rng, 0, lmax, E)), ws)
+    torch.cuda.synchronize()
+    assert np.all(dx.cpu().numpy() == 0) and all(np.all(v.cpu().numpy() == 0) for v in grads.values())
+    dx, grads = m.egnn_readout_backward(graph, col_ptr, perm, pos, w.box, B.to_device(x), B.to_device(Wr),
+                                        B.to_device(synth.normal(rng, (0, 13, 13))), ws)
+    torch.cuda.synchronize()
+    assert np.all(dx.cpu().numpy() == 0) and all(np.all(v.cpu().numpy() == 0) for v in grads.values())
+
+
 @pytest.mark.parametrize("index", [1])
 def test_training_step_config(B, index):
     """Whole training step on config 1: forward, MSE against random targets, reverse pass through the readout
