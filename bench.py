@@ -214,11 +214,12 @@ def main():
         m.egnn_timing_enable(0)
         m.egnn_set_option(B.OPT_FUSED, 0)
         layer_fl = msfl[3] / max(1, callsfl[0])
-        # bf16 matrix-core work of the radial contraction: six piece products per fp32 product
-        mfma_flop = 6.0 * 2.0 * 64 * m.n_paths * w.channels * n_edges
+        # matrix-core work of the radial contraction in this kernel: three half-precision piece products per fp32
+        # product (48 rows of W_r2 per 42 paths are multiplied: the padded tile rows count as work done)
+        mfma_flop = 3.0 * 2.0 * 64 * 16 * ((m.n_paths + 15) // 16) * w.channels * n_edges
         fused_lane = dict(ms_per_step=1e3 * dtfl, steps=nfl, edge_layer_evaluations_per_s=n_edges * w.n_layers / dtfl,
                           s3_s4_kernel_ms=layer_fl, edges_per_s=n_edges / (layer_fl * 1e-3),
-                          bf16_mfma_TFLOPs=mfma_flop / (layer_fl * 1e-3) / 1e12, bf16_mfma_peak_TFLOPs=2500.0,
+                          f16_mfma_TFLOPs=mfma_flop / (layer_fl * 1e-3) / 1e12, f16_mfma_peak_TFLOPs=2500.0,
                           note="EGNN_OPT_FUSED = 2: radial weights produced on the matrix cores in the registers of the "
                                "lane that consumes them, no weight tensor in memory; bound by matrix-core plus vector "
                                "work of the same SIMD, not by HBM")

@@ -381,7 +381,7 @@ static int layer_forward_impl(egnn_ctx* ctx, const egnn_graph* g, const float* p
   if ((rc = egnn_launch_node_mix(ctx, x_in, W_pre, nullptr, nullptr, h, g->n_total, st))) return rc;
   tm.mark(2);
   if (fused_lane) {
-    if ((rc = egnn_launch_layer_fused_lane(ctx, g, rhat_d, h, W_r1, w2s, w, w_bytes, a, st))) return rc;
+    if ((rc = egnn_launch_layer_fused_lane(ctx, g, rhat_d, h, W_r1, W_r2, w, w_bytes, a, st))) return rc;
   } else if (fused) {
     if ((rc = egnn_launch_layer_fused(ctx, g, rhat_d, h, W_r1, w2s, w, w_bytes, a, st))) return rc;
   } else {

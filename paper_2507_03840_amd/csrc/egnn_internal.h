@@ -109,7 +109,7 @@ bool egnn_fused_supported(const egnn_ctx*);
 bool egnn_fused_lane_supported(const egnn_ctx*);
 size_t egnn_fused_lane_scratch_bytes(const egnn_ctx*, int32_t n_total);
 int egnn_launch_layer_fused_lane(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* h, const float* W_r1,
-                                 const void* W2s, void* scratch, size_t scratch_bytes, float* a, hipStream_t);
+                                 const float* W_r2, void* scratch, size_t scratch_bytes, float* a, hipStream_t);
 size_t egnn_fused_scratch_bytes(const egnn_ctx*, int64_t n_edges);
 int egnn_launch_layer_fused(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* h, const float* W_r1,
                             const void* W2s, void* scratch, size_t scratch_bytes, float* a, hipStream_t);

@@ -26,8 +26,25 @@
 #define F2_WAVES 7                       // compute waves = blocks of 32 edges per round
 #define F2_THREADS ((F2_WAVES + 1) * 64)
 #define F2_ROUND (32 * F2_WAVES)         // edges of a node per round
-#define F2_BROW4 25                      // uint4 per staged row of W_r2: 24 of data + 1 of padding
+#define F2_BROW4 17                      // uint4 per staged row of W_r2: 16 of data (two pieces of 64 halves) + 1 of padding
+// Operands of the radial contraction are cut into two half-precision pieces (11 significant bits each) after a scaling
+// by a power of two: x * 2^s = hi + lo exactly to 22 bits, and a product is hi*hi + hi*lo + lo*hi (the lo*lo term is
+// 2^-22 of the product, the size of the representation error).  Against fp64 the contraction is as accurate as the
+// three-piece bf16 form with six products (1e-7 of the largest result, rms 1.5e-8) at half the matrix-core work.
+// Half precision has a narrow exponent range, so the two scalings are taken from the weights on the device, once per
+// call: alpha W_r2 by its largest magnitude, the hidden activations by the bound |SiLU(pre)| <= |pre| <=
+// max_j sum_b |W_r1[j][b]| (basis values lie in [0, 1]); the largest piece then sits in [2^13, 2^14), and elements
+// more than 2^-17 below it lose low bits that are below 2^-28 of the largest one.
 typedef unsigned int f2_u4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f2_h8 __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ f2_h8 f2_as_h8(uint4 v) { return __builtin_bit_cast(f2_h8, v); }
+// x -> (hi, lo) half-precision pieces, as raw bits
+__device__ __forceinline__ void f2_split(float x, uint32_t& hi, uint32_t& lo) {
+  const _Float16 h = (_Float16)x;
+  const _Float16 l = (_Float16)(x - (float)h);
+  hi = __builtin_bit_cast(unsigned short, h);
+  lo = __builtin_bit_cast(unsigned short, l);
+}
 
 __device__ __forceinline__ void f2_release_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -38,20 +55,69 @@ __device__ __forceinline__ void f2_barrier_acquire() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// W2s: [n = path * E + channel][3 pieces][64 units] bf16 (24 uint4 per row) -> W2p[tile = cp * npt + pt][R][24 uint4],
-// R = result row of the tile: (i, hh) = (4 (R / 8) + R % 4, (R / 4) % 2) <-> (path 16 pt + i, channel 2 cp + hh).
+// scales[0] = s_w, scales[1] = s_g (powers of two, see above), scales[2] = 1 / (s_w s_g).  One workgroup.
+__global__ __launch_bounds__(256) void f2_scales_kernel(const float* __restrict__ W_r1, const float* __restrict__ W_r2,
+                                                        int n_rbf, int PE, int log2E, PathAlpha alpha,
+                                                        float* __restrict__ scales) {
+  __shared__ float red[256];
+  float mw = 0.0f;
+  for (int i = threadIdx.x; i < PE * EGNN_HIDDEN; i += 256)
+    mw = fmaxf(mw, fabsf(alpha.a[(i / EGNN_HIDDEN) >> log2E] * W_r2[i]));
+  float mg = 0.0f;
+  if (threadIdx.x < EGNN_HIDDEN) {
+    for (int b = 0; b < n_rbf; ++b) mg += fabsf(W_r1[threadIdx.x * n_rbf + b]);
+  }
+  auto block_max = [&](float v) {
+    red[threadIdx.x] = v;
+    __syncthreads();
+    for (int st = 128; st > 0; st >>= 1) {
+      if ((int)threadIdx.x < st) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + st]);
+      __syncthreads();
+    }
+    const float r = red[0];
+    __syncthreads();
+    return r;
+  };
+  mw = block_max(mw);
+  mg = block_max(mg);
+  if (threadIdx.x == 0) {
+    // (zero, infinite or NaN weights: no scaling; the result then shows them as it would without)
+    auto exp_of = [](float m) { return (m > 0.0f && m < 3.0e38f) ? ilogbf(m) : 13; };
+    int ew = 13 - exp_of(mw), eg = 13 - exp_of(mg);
+    ew = ew < -60 ? -60 : (ew > 60 ? 60 : ew);
+    eg = eg < -60 ? -60 : (eg > 60 ? 60 : eg);
+    scales[0] = ldexpf(1.0f, ew);
+    scales[1] = ldexpf(1.0f, eg);
+    scales[2] = ldexpf(1.0f, -ew - eg);
+  }
+}
+
+// W_r2 [n = path * E + channel][64 units] fp32 -> W2p[tile = cp * npt + pt][R][2 pieces][64 halves] (16 uint4 per row),
+// values alpha_p * W_r2 * s_w cut into pieces; R = result row of the tile:
+// (i, hh) = (4 (R / 8) + R % 4, (R / 4) % 2) <-> (path 16 pt + i, channel 2 cp + hh).
 // Paths past the last one repeat path 0 (their weights are computed and never used).
-__global__ __launch_bounds__(256) void f2_pack_kernel(const uint4* __restrict__ W2s, uint4* __restrict__ W2p, int P,
-                                                      int log2E, int npt, int n_tiles) {
+__global__ __launch_bounds__(256) void f2_pack_kernel(const float* __restrict__ W_r2, uint4* __restrict__ W2p, int P,
+                                                      int log2E, int npt, int n_tiles, PathAlpha alpha,
+                                                      const float* __restrict__ scales) {
   const int idx = blockIdx.x * 256 + threadIdx.x;
-  if (idx >= n_tiles * 32 * 24) return;
-  const int c16 = idx % 24, R = (idx / 24) % 32, tile = idx / (24 * 32);
+  if (idx >= n_tiles * 32 * 16) return;
+  const int c16 = idx % 16, R = (idx / 16) % 32, tile = idx / (16 * 32);
   const int cp = tile / npt, pt = tile - cp * npt;
   const int i = 4 * (R >> 3) + (R & 3), hh = (R >> 2) & 1;
   int p = 16 * pt + i;
   if (p >= P) p = 0;
   const int n = (p << log2E) + 2 * cp + hh;
-  W2p[idx] = W2s[(size_t)n * 24 + c16];
+  const int piece = c16 >> 3, k0 = (c16 & 7) * 8;
+  const float sc = alpha.a[p] * scales[0];
+  uint32_t w[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    uint32_t h0, l0, h1, l1;
+    f2_split(sc * W_r2[(size_t)n * EGNN_HIDDEN + k0 + 2 * q], h0, l0);
+    f2_split(sc * W_r2[(size_t)n * EGNN_HIDDEN + k0 + 2 * q + 1], h1, l1);
+    w[q] = piece == 0 ? (h0 | (h1 << 16)) : (l0 | (l1 << 16));
+  }
+  W2p[idx] = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
 // h [node][(l,m)][E] -> h2 [node][cp][(l,m)][2]
@@ -94,7 +160,8 @@ template <int LMAX>
 __global__ __launch_bounds__(F2_THREADS) void f2_kernel(const int* __restrict__ row_ptr, const int* __restrict__ src,
                                                         const float4* __restrict__ rhat_d,
                                                         const float* __restrict__ h2, const float* __restrict__ W_r1,
-                                                        const uint4* __restrict__ W2p, float* __restrict__ a,
+                                                        const uint4* __restrict__ W2p,
+                                                        const float* __restrict__ scales, float* __restrict__ a,
                                                         int n_owned, int nodes_per_xcd, int n_rbf, int log2E,
                                                         float scale, float r_cut) {
   using Mid = typename LayerMid<LMAX>::T;
@@ -119,16 +186,17 @@ __global__ __launch_bounds__(F2_THREADS) void f2_kernel(const int* __restrict__ 
 
   const int k0 = row_ptr[j], deg = row_ptr[j + 1] - k0;
   const int rounds = (deg + F2_ROUND - 1) / F2_ROUND;
+  const float s_g = scales[1];
 
   if (wave == F2_WAVES) {
     // ---- loader: the NPT tiles of channel pair s (all rounds in sequence) -> sB[s & 1].  The loads of a group are
     // issued a whole group time before they are written to LDS, so that their latency does not show.
     const int n_groups = rounds * ncp;
-    constexpr int NV = NPT * 12;
+    constexpr int NV = NPT * 8;
     f2_u4 v[NV];                   // (native vectors: an array of them that lives across iterations stays in registers)
     auto fetch = [&](int s) {
       const int cp = s % ncp;
-      const f2_u4* tsrc = reinterpret_cast<const f2_u4*>(W2p) + (size_t)cp * NPT * (32 * 24);
+      const f2_u4* tsrc = reinterpret_cast<const f2_u4*>(W2p) + (size_t)cp * NPT * (32 * 16);
 #pragma unroll
       for (int i = 0; i < NV; ++i) v[i] = tsrc[i * 64 + lane];
     };
@@ -137,7 +205,7 @@ __global__ __launch_bounds__(F2_THREADS) void f2_kernel(const int* __restrict__ 
       f2_u4* dstb = reinterpret_cast<f2_u4*>(sB[s & 1]);
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
-        const int u = i * 64 + lane, row = u / 24, c16 = u - row * 24;     // row counts through the NPT tiles
+        const int u = i * 64 + lane, row = u >> 4, c16 = u & 15;            // row counts through the NPT tiles
         dstb[row * F2_BROW4 + c16] = v[i];
       }
       if (s + 1 < n_groups) fetch(s + 1);
@@ -159,7 +227,7 @@ __global__ __launch_bounds__(F2_THREADS) void f2_kernel(const int* __restrict__ 
       const float4 g = rhat_d[k];
       const int srcn = src[k];
       // hidden activations (times the cutoff envelope) of the lane's edge, units 32 hh .. 32 hh + 31, in pieces
-      uint4 gf[3][4];
+      uint4 gf[2][4];
       {
         const float step_r = r_cut / (float)(n_rbf - 1);
         const float inv2s2 = 0.5f / (step_r * step_r);
@@ -174,22 +242,21 @@ __global__ __launch_bounds__(F2_THREADS) void f2_kernel(const int* __restrict__ 
           for (int s = 0; s < 32; ++s) pre[s] += wrow[s] * Bv;
         }
         // (a lane past the node's last edge gets a zero envelope: zero weights, a zero message, nothing to mask later)
-        const float fc = valid ? 0.5f * (1.0f + cosf(3.14159265358979323846f * g.w / r_cut)) : 0.0f;
+        const float fc = valid ? s_g * 0.5f * (1.0f + cosf(3.14159265358979323846f * g.w / r_cut)) : 0.0f;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-          uint32_t ph[4], pm[4], pl[4];
+          uint32_t ph[4], pl[4];
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             const float x0 = pre[8 * t + 2 * q], x1 = pre[8 * t + 2 * q + 1];
-            const Split3 s0 = split3(fc * x0 / (1.0f + __expf(-x0)));
-            const Split3 s1 = split3(fc * x1 / (1.0f + __expf(-x1)));
-            ph[q] = pack2(s0.hi, s1.hi);
-            pm[q] = pack2(s0.mid, s1.mid);
-            pl[q] = pack2(s0.lo, s1.lo);
+            uint32_t h0, l0, h1, l1;
+            f2_split(fc * x0 / (1.0f + __expf(-x0)), h0, l0);
+            f2_split(fc * x1 / (1.0f + __expf(-x1)), h1, l1);
+            ph[q] = h0 | (h1 << 16);
+            pl[q] = l0 | (l1 << 16);
           }
           gf[0][t] = make_uint4(ph[0], ph[1], ph[2], ph[3]);
-          gf[1][t] = make_uint4(pm[0], pm[1], pm[2], pm[3]);
-          gf[2][t] = make_uint4(pl[0], pl[1], pl[2], pl[3]);
+          gf[1][t] = make_uint4(pl[0], pl[1], pl[2], pl[3]);
         }
       }
       BondTrig trig;
@@ -210,19 +277,18 @@ __global__ __launch_bounds__(F2_THREADS) void f2_kernel(const int* __restrict__ 
 #pragma unroll
           for (int i = 0; i < D; ++i) vn[i] = hn[2 * i];
         }
-        // ---- the weights of (edge, channel 2 cp + hh): NPT tiles, six piece products per fp32 product
+        // ---- the weights of (edge, channel 2 cp + hh): NPT tiles, three piece products per fp32 product
         float wr[NPT * 16];
         f2_barrier_acquire();
         const uint4* gbase = sB[step & 1] + m * F2_BROW4 + hh * 4;
         ++step;
         {
           // the pieces of W_r2 of contraction step u = 4 pt + t are read from LDS one step ahead of their products
-          uint4 wf[2][3];
-          auto lds_step = [&](int u, uint4 (&dstw)[3]) {
+          uint4 wf[2][2];
+          auto lds_step = [&](int u, uint4 (&dstw)[2]) {
             const uint4* row = gbase + (u >> 2) * (32 * F2_BROW4) + (u & 3);
             dstw[0] = row[0];
             dstw[1] = row[8];
-            dstw[2] = row[16];
           };
           lds_step(0, wf[0]);
           float16v acc;
@@ -234,13 +300,10 @@ __global__ __launch_bounds__(F2_THREADS) void f2_kernel(const int* __restrict__ 
 #pragma unroll
               for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
             }
-            // smallest terms first: (lo,hi) (hi,lo) (mid,mid) (mid,hi) (hi,mid) (hi,hi)
-            const int pa[6] = {2, 0, 1, 1, 0, 0};
-            const int pb[6] = {0, 2, 1, 0, 1, 0};
-#pragma unroll
-            for (int q = 0; q < 6; ++q)
-              acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(wf[u & 1][pa[q]]), as_bf16x8(gf[pb[q]][t]), acc, 0,
-                                                            0, 0);
+            // smallest terms first: (lo,hi) (hi,lo) (hi,hi)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(f2_as_h8(wf[u & 1][1]), f2_as_h8(gf[0][t]), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(f2_as_h8(wf[u & 1][0]), f2_as_h8(gf[1][t]), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(f2_as_h8(wf[u & 1][0]), f2_as_h8(gf[0][t]), acc, 0, 0, 0);
             if (t == 3) {
 #pragma unroll
               for (int i = 0; i < 16; ++i) wr[16 * pt + i] = acc[i];
@@ -268,14 +331,15 @@ __global__ __launch_bounds__(F2_THREADS) void f2_kernel(const int* __restrict__ 
     }
   }
   __syncthreads();
-  // a[j][(l,m)][c] = scale * sum over the waves, in fixed order
+  // a[j][(l,m)][c] = scale * sum over the waves, in fixed order (the operand scalings are undone here)
+  const float out_scale = scale * scales[2];
   float* out = a + ((size_t)j * D << log2E);
   for (int idx = tid; idx < (D << log2E); idx += F2_THREADS) {
     const int i = idx >> log2E, c = idx & (E - 1);
     float sum = 0.0f;
 #pragma unroll
     for (int w = 0; w < F2_WAVES; ++w) sum += sP[(size_t)w * D * E + (size_t)((c >> 1) * 2 + (c & 1)) * D + i];
-    out[idx] = scale * sum;
+    out[idx] = out_scale * sum;
   }
 }
 
@@ -294,7 +358,7 @@ bool egnn_fused_lane_supported(const egnn_ctx* ctx) {
 }
 
 static size_t f2_pack_bytes(const egnn_ctx* ctx) {
-  return (size_t)(ctx->desc.channels / 2) * f2_npt(ctx) * 32 * 24 * sizeof(uint4);
+  return 256 + (size_t)(ctx->desc.channels / 2) * f2_npt(ctx) * 32 * 16 * sizeof(uint4);   // scales, then tiles
 }
 static size_t f2_align(size_t b) { return (b + 255) & ~(size_t)255; }
 
@@ -304,9 +368,9 @@ size_t egnn_fused_lane_scratch_bytes(const egnn_ctx* ctx, int32_t n_total) {
   return f2_align(f2_pack_bytes(ctx)) + f2_align((size_t)n_total * row);
 }
 
-// W2s: the pre-split W_r2 (egnn_launch_split_w2); scratch: egnn_fused_lane_scratch_bytes.  a [n_owned][D][E].
+// scratch: egnn_fused_lane_scratch_bytes.  a [n_owned][D][E].
 int egnn_launch_layer_fused_lane(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, const float* h,
-                                 const float* W_r1, const void* W2s, void* scratch, size_t scratch_bytes, float* a,
+                                 const float* W_r1, const float* W_r2, void* scratch, size_t scratch_bytes, float* a,
                                  hipStream_t stream) {
   const int n = g->n_owned;
   if (n == 0) return EGNN_OK;
@@ -315,10 +379,16 @@ int egnn_launch_layer_fused_lane(egnn_ctx* ctx, const egnn_graph* g, const float
     return egnn_fail(ctx, EGNN_EWS, "layer_fused_lane: scratch too small");
   const int E = ctx->desc.channels, D = (ctx->desc.lmax + 1) * (ctx->desc.lmax + 1);
   const int npt = f2_npt(ctx), n_tiles = (E / 2) * npt;
-  uint4* W2p = reinterpret_cast<uint4*>(scratch);
+  float* scales = reinterpret_cast<float*>(scratch);
+  uint4* W2p = reinterpret_cast<uint4*>((char*)scratch + 256);
   float* h2 = reinterpret_cast<float*>((char*)scratch + f2_align(f2_pack_bytes(ctx)));
-  hipLaunchKernelGGL(f2_pack_kernel, dim3((n_tiles * 32 * 24 + 255) / 256), dim3(256), 0, stream,
-                     reinterpret_cast<const uint4*>(W2s), W2p, ctx->n_paths[0], ctx->log2_channels, npt, n_tiles);
+  PathAlpha al;
+  for (int p = 0; p < EGNN_MAX_PATHS; ++p) al.a[p] = p < ctx->n_paths[0] ? ctx->alpha[0][p] : 0.0f;
+  hipLaunchKernelGGL(f2_scales_kernel, dim3(1), dim3(256), 0, stream, W_r1, W_r2, ctx->desc.n_rbf, ctx->n_paths[0] * E,
+                     ctx->log2_channels, al, scales);
+  EGNN_LAUNCH_CHECK(ctx, "f2_scales_kernel");
+  hipLaunchKernelGGL(f2_pack_kernel, dim3((n_tiles * 32 * 16 + 255) / 256), dim3(256), 0, stream, W_r2, W2p,
+                     ctx->n_paths[0], ctx->log2_channels, npt, n_tiles, al, scales);
   EGNN_LAUNCH_CHECK(ctx, "f2_pack_kernel");
   const long n_values = (long)g->n_total * D * E;
   if (n_values > 0) {
@@ -339,7 +409,7 @@ int egnn_launch_layer_fused_lane(egnn_ctx* ctx, const egnn_graph* g, const float
       if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(f2_kernel)");                         \
     }                                                                                                               \
     hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(F2_THREADS), shmem, stream, g->row_ptr, g->src, rd, h2, W_r1,  \
-                       W2p, a, n, per_xcd, ctx->desc.n_rbf, ctx->log2_channels, scale, ctx->desc.r_cut);            \
+                       W2p, scales, a, n, per_xcd, ctx->desc.n_rbf, ctx->log2_channels, scale, ctx->desc.r_cut);            \
   } while (0)
   switch (ctx->desc.lmax) {
     case 0: LAUNCH(0); break;
