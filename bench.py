@@ -30,7 +30,7 @@ def stage_model(w, n_edges, n_paths, n_paths_ro):
     # (24 bytes); per owned node one output row.
     s4_bytes = n_edges * (4 * (n_paths * E + D * E) + 24) + w.n_owned * 4 * D * E
     # S3: per edge one (r_hat, d) record read and the weight row written; the contraction itself
-    # (2*(n_rbf*64 + 64*P*E) flop per edge) runs on the bf16 matrix cores and is far from their roofline.
+    # (2*(n_rbf*64 + 64*P*E) flop per edge) runs on the half-precision matrix cores and is far from their roofline.
     s3_bytes = n_edges * (4 * n_paths * E + 16)
     s3_flops = n_edges * 2.0 * (w.n_rbf * 64 + 64 * n_paths * E)
     # S6: weight row, two gathered rows, indices/unit vector, one n_orb x n_orb block written
@@ -485,8 +485,9 @@ def main():
     s3_ms = (layer_ms["radial_weights"] * n_calls[0] + ro_ms["radial_weights"] * n_calls[1]) / max(1, sum(n_calls))
     roofs = [hbm_roof("tp_segsum_kernel", s4_bytes, layer_ms["tp_segsum"], w.n_layers),
              hbm_roof("radial_weights_kernel", s3_bytes, s3_ms, w.n_layers + n_ro,
-                      mfma_TFLOPs=s3_flops / (s3_ms * 1e-3) / 1e12, mfma_peak_TFLOPs_bf16=2500.0,
-                      note="contraction on bf16 MFMA with 3-piece operand splitting (6 products per fp32 product)")]
+                      mfma_TFLOPs=s3_flops / (s3_ms * 1e-3) / 1e12, mfma_peak_TFLOPs_f16=2500.0,
+                      note="fp32-equivalent rate; the contraction runs on the f16 matrix cores with both operands "
+                           "cut into two half-precision pieces (3 products per fp32 product, 3 x this rate in f16 work)")]
     if w.readout:
         roofs.append(hbm_roof("readout_kernel", s6_bytes, ro_ms["readout"], 1))
     roofs.sort(key=lambda r: -r["ms_per_step"])

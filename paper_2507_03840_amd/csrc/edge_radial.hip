@@ -113,16 +113,84 @@ int egnn_launch_geometry(egnn_ctx* ctx, const egnn_graph* g, const float* pos, c
 }
 
 // ------------------------------------------------------------------------------------------------ S3
-// The contraction runs on the bf16 matrix cores with fp32-level accuracy: every fp32 operand x is cut into
-// three bf16 pieces of 8 mantissa bits each (x = hi + mid + lo exactly, by truncation and exact subtraction),
-// and the six piece products whose weight is at least 2^-16 are accumulated in fp32
-// (hi*hi, hi*mid, mid*hi, mid*mid, hi*lo, lo*hi); the three dropped ones are below 2^-24 of the product.
-// Six v_mfma_f32_32x32x16_bf16 replace eight v_mfma_f32_32x32x2_f32 at 1/16 of their cost each, which moves
-// the kernel from the fp32-MFMA roofline to the rate at which w can be written.
+// The contraction runs on the half-precision matrix cores with fp32-level accuracy.  Both operands are scaled by a
+// power of two and cut into two half-precision pieces of 11 significant bits each (x 2^s = hi + lo to 22 bits, by
+// rounding and exact subtraction); a product is hi*hi + hi*lo + lo*hi, accumulated in fp32 -- the dropped lo*lo term
+// is 2^-22 of the product, the size of the representation error.  Against fp64 this is as accurate as three bf16
+// pieces with six products (largest error 1e-7 of the largest result) and better than a plain fp32 dot product, at
+// half the matrix-core work of the former: three v_mfma_f32_32x32x16_f16 replace eight v_mfma_f32_32x32x2_f32 at 1/16
+// of their cost each.  Half precision has a narrow exponent range, so the scalings are taken from the weights, on
+// the device, once per call (egnn_launch_half_scales): alpha W_r2 by its largest magnitude, the hidden activations by
+// the bound |fc SiLU(pre)| <= |pre| <= max_j sum_b |W_r1[j][b]| (basis values and envelope lie in [0, 1]); the
+// largest piece then sits in [2^13, 2^14), and the scalings are undone exactly when the result is stored.
 #include "split_bf16.h"
 #include "w_half.h"
 
-// W_r2 (times alpha_p) cut into pieces once per call: out[n][piece][64] bf16.
+typedef _Float16 rw_h8 __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ rw_h8 rw_as_h8(uint4 v) { return __builtin_bit_cast(rw_h8, v); }
+// x -> (hi, lo) half-precision pieces, as raw bits
+__device__ __forceinline__ void rw_split(float x, uint32_t& hi, uint32_t& lo) {
+  const _Float16 h = (_Float16)x;
+  const _Float16 l = (_Float16)(x - (float)h);
+  hi = __builtin_bit_cast(unsigned short, h);
+  lo = __builtin_bit_cast(unsigned short, l);
+}
+
+// scales[0] = s_w, scales[1] = s_g (powers of two, see above), scales[2] = 1 / (s_w s_g).  One workgroup of 1,024
+// threads, 16-byte loads: a few microseconds for the 10^5 values of W_r2.
+#define HS_THREADS 1024
+__global__ __launch_bounds__(HS_THREADS) void half_scales_kernel(const float* __restrict__ W_r1,
+                                                                 const float* __restrict__ W_r2, int n_rbf, int PE,
+                                                                 int log2E, PathAlpha alpha, float* __restrict__ scales) {
+  __shared__ float red[HS_THREADS];
+  float mw = 0.0f;
+  const float4* W4 = reinterpret_cast<const float4*>(W_r2);
+  for (int i = threadIdx.x; i < PE * (EGNN_HIDDEN / 4); i += HS_THREADS) {
+    const float4 v = W4[i];
+    const float al = fabsf(alpha.a[(i / (EGNN_HIDDEN / 4)) >> log2E]);
+    mw = fmaxf(mw, al * fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+  }
+  float mg = 0.0f;
+  if (threadIdx.x < EGNN_HIDDEN) {
+    for (int b = 0; b < n_rbf; ++b) mg += fabsf(W_r1[threadIdx.x * n_rbf + b]);
+  }
+  auto block_max = [&](float v) {
+    red[threadIdx.x] = v;
+    __syncthreads();
+    for (int st = HS_THREADS / 2; st > 0; st >>= 1) {
+      if ((int)threadIdx.x < st) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + st]);
+      __syncthreads();
+    }
+    const float r = red[0];
+    __syncthreads();
+    return r;
+  };
+  mw = block_max(mw);
+  mg = block_max(mg);
+  if (threadIdx.x == 0) {
+    // (zero, infinite or NaN weights: no scaling; the result then shows them as it would without)
+    auto exp_of = [](float m) { return (m > 0.0f && m < 3.0e38f) ? ilogbf(m) : 13; };
+    int ew = 13 - exp_of(mw), eg = 13 - exp_of(mg);
+    ew = ew < -60 ? -60 : (ew > 60 ? 60 : ew);
+    eg = eg < -60 ? -60 : (eg > 60 ? 60 : eg);
+    scales[0] = ldexpf(1.0f, ew);
+    scales[1] = ldexpf(1.0f, eg);
+    scales[2] = ldexpf(1.0f, -ew - eg);
+  }
+}
+
+int egnn_launch_half_scales(egnn_ctx* ctx, int which, const float* W_r1, const float* W_r2, float* scales,
+                            hipStream_t stream) {
+  const int P = ctx->n_paths[which];
+  PathAlpha al;
+  for (int p = 0; p < EGNN_MAX_PATHS; ++p) al.a[p] = p < P ? ctx->alpha[which][p] : 0.0f;
+  hipLaunchKernelGGL(half_scales_kernel, dim3(1), dim3(HS_THREADS), 0, stream, W_r1, W_r2, ctx->desc.n_rbf,
+                     P * ctx->desc.channels, ctx->log2_channels, al, scales);
+  EGNN_LAUNCH_CHECK(ctx, "half_scales_kernel");
+  return EGNN_OK;
+}
+
+// W_r2 (times alpha_p) cut into three bf16 pieces once per call: out[n][piece][64] (operand of the first fused design).
 __global__ __launch_bounds__(256) void split_w2_kernel(const float* __restrict__ W_r2, uint16_t* __restrict__ out,
                                                        int PE, int log2E, PathAlpha alpha) {
   const int i = blockIdx.x * 256 + threadIdx.x;
@@ -135,11 +203,25 @@ __global__ __launch_bounds__(256) void split_w2_kernel(const float* __restrict__
   o[2 * EGNN_HIDDEN] = (uint16_t)(s.lo >> 16);
 }
 
+// W_r2 times alpha_p times s_w cut into two half-precision pieces: out[n][piece][64].
+__global__ __launch_bounds__(256) void split_w2_half_kernel(const float* __restrict__ W_r2, uint16_t* __restrict__ out,
+                                                            int PE, int log2E, PathAlpha alpha,
+                                                            const float* __restrict__ scales) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= PE * EGNN_HIDDEN) return;
+  const int n = i >> 6, j = i & 63;
+  uint32_t hi, lo;
+  rw_split(W_r2[i] * alpha.a[n >> log2E] * scales[0], hi, lo);
+  uint16_t* o = out + (size_t)n * 2 * EGNN_HIDDEN + j;
+  o[0] = (uint16_t)hi;
+  o[EGNN_HIDDEN] = (uint16_t)lo;
+}
+
 // Workgroup = 8 wavefronts (one per register-file slot of a CU at this kernel's register count).  Waves 0-6 each
 // own 64 consecutive edges (two 32-row MFMA blocks): lane l serves
 // matrix row/column (l & 31) and the half hh = l >> 5 of the 64-long contraction index; MFMA step t contracts
 // hidden units 32*hh + 8*t .. +7 on both operands.  Wave 7 only moves data: it copies the pieces of the next
-// 32 rows of W_r2 (12 KB, contiguous) from global memory into one of two LDS buffers.
+// 32 rows of W_r2 (8 KB, contiguous) from global memory into one of two LDS buffers.
 // Why a separate loader: the memory counter of a wave retires loads and stores in issue order, so a wave that
 // both loads its next operand and stores its results has to sit out a full HBM write round trip per block.
 // The compute waves here never wait on global memory inside the loop -- their operand comes from LDS and their
@@ -158,7 +240,7 @@ __global__ __launch_bounds__(256) void split_w2_kernel(const float* __restrict__
 #define RW_MIN_WG 1
 #endif
 #define RW_THREADS ((RW_COMPUTE_WAVES + 1) * 64)
-#define RW_BROW4 25   // uint4 per staged W_r2 row: 24 of data (3 pieces x 64 bf16) + 1 of padding (bank spread)
+#define RW_BROW4 17   // uint4 per staged W_r2 row: 16 of data (2 pieces x 64 halves) + 1 of padding (bank spread)
 
 __device__ __forceinline__ void lds_release_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -169,14 +251,15 @@ __device__ __forceinline__ void lds_barrier_acquire() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// One 32-column block: wait for its rows of W_r2 in LDS, then 4 steps x 6 piece products per 32-row block.
-// STORE: after each step a quarter of the previous block's results (prev) goes to memory: out_prev describes the
-// wave's rows of w, col_prev is the block's first column, lane_off the lane's own offset, ld the row stride
-// (w is written once and read once by another kernel: non-temporal stores).
+// One 32-column block: wait for its rows of W_r2 in LDS, then 4 steps x 3 piece products per 32-row block.
+// STORE: after each step a quarter of the previous block's results (prev, times `unscale`) goes to memory: out_prev
+// describes the wave's rows of w, col_prev is the block's first column, lane_off the lane's own offset, ld the row
+// stride (w is written once and read once by another kernel: non-temporal stores).
 template <bool STORE>
-__device__ __forceinline__ void rw_block(const uint4* __restrict__ sB_nb, const uint4 (&a_frag)[RW_MB][3][4], int m,
+__device__ __forceinline__ void rw_block(const uint4* __restrict__ sB_nb, const uint4 (&a_frag)[RW_MB][2][4], int m,
                                          int hh, float16v (&acc)[RW_MB], const float16v (&prev)[RW_MB],
-                                         __amdgpu_buffer_rsrc_t out_prev, int col_prev, unsigned lane_off, size_t ld) {
+                                         __amdgpu_buffer_rsrc_t out_prev, int col_prev, unsigned lane_off, size_t ld,
+                                         float unscale) {
   lds_barrier_acquire();
   const uint4* row = sB_nb + m * RW_BROW4 + hh * 4;
 #pragma unroll
@@ -185,17 +268,17 @@ __device__ __forceinline__ void rw_block(const uint4* __restrict__ sB_nb, const 
     for (int i = 0; i < 16; ++i) acc[mb][i] = 0.0f;
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
-    // the pieces of W_r2 of this step only (12 registers; the next step's are read while these are multiplied)
-    const uint4 b_frag[3] = {row[t], row[8 + t], row[16 + t]};
-    // smallest terms first: (lo,hi) (hi,lo) (mid,mid) (mid,hi) (hi,mid) (hi,hi)
-    const int pa[6] = {2, 0, 1, 1, 0, 0};
-    const int pb[6] = {0, 2, 1, 0, 1, 0};
+    // the pieces of W_r2 of this step only (8 registers; the next step's are read while these are multiplied)
+    const uint4 b_frag[2] = {row[t], row[8 + t]};
+    // smallest terms first: (lo,hi) (hi,lo) (hi,hi)
+    const int pa[3] = {1, 0, 0};
+    const int pb[3] = {0, 1, 0};
 #pragma unroll
-    for (int q = 0; q < 6; ++q)
+    for (int q = 0; q < 3; ++q)
 #pragma unroll
       for (int mb = 0; mb < RW_MB; ++mb)
-        acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a_frag[mb][pa[q]][t]),
-                                                          as_bf16x8(b_frag[pb[q]]), acc[mb], 0, 0, 0);
+        acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(rw_as_h8(a_frag[mb][pa[q]][t]), rw_as_h8(b_frag[pb[q]]),
+                                                         acc[mb], 0, 0, 0);
     if constexpr (STORE) {
       static_assert(RW_MB == 2, "a quarter of the previous block per contraction step");
 #pragma unroll
@@ -204,19 +287,19 @@ __device__ __forceinline__ void rw_block(const uint4* __restrict__ sB_nb, const 
         // row and block offset (the same for all lanes) added to the lane's own offset: one vector add per store, and
         // the whole offset is what the range check of the buffer sees (rows the wave does not own are discarded)
         const int row_off = ((32 * mb + 8 * (i >> 2) + (i & 3)) * (int)ld + col_prev) * 4;
-        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, (float)prev[mb][i]), out_prev,
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, unscale * (float)prev[mb][i]), out_prev,
                                               (int)(lane_off * 4u) + row_off, 0, 2 /* non-temporal */);
       }
     }
   }
   if constexpr (STORE) {
     // keep the stores spread between the matrix-core instructions (the scheduler would otherwise bunch them up)
-#pragma unroll
 #ifndef RW_SG_M
 #define RW_SG_M 3
-#define RW_SG_S 2
+#define RW_SG_S 4
 #endif
-    for (int g = 0; g < 48 / RW_SG_M; ++g) {
+#pragma unroll
+    for (int g = 0; g < 24 / RW_SG_M; ++g) {
       __builtin_amdgcn_sched_group_barrier(0x008, RW_SG_M, 0);   // MFMA
       __builtin_amdgcn_sched_group_barrier(0x040, RW_SG_S, 0);   // global stores
     }
@@ -228,6 +311,7 @@ template <bool HALF>
 __global__ __launch_bounds__(RW_THREADS, RW_MIN_WG) void radial_weights_kernel(const float4* __restrict__ rhat_d, long n_edges,
                                                              const float* __restrict__ W_r1,
                                                              const uint16_t* __restrict__ W2s,
+                                                             const float* __restrict__ scales,
                                                              float* __restrict__ w, int n_rbf, int PE,
                                                              float r_cut, int rows_per_wave) {
   __shared__ float sW1[32 * EGNN_HIDDEN];  // [b][j], n_rbf <= 32
@@ -246,16 +330,16 @@ __global__ __launch_bounds__(RW_THREADS, RW_MIN_WG) void radial_weights_kernel(c
     // ---- loader: block nb -> sB[nb & 1]; rows past the end repeat row 0 (their columns are never stored)
     const uint4* src = reinterpret_cast<const uint4*>(W2s);
     for (int nb = 0; nb < n_blocks; ++nb) {
-      uint4 v[12];
+      uint4 v[8];
 #pragma unroll
-      for (int i = 0; i < 12; ++i) {
-        const int u = i * 64 + lane, row = u / 24, c16 = u - row * 24;
+      for (int i = 0; i < 8; ++i) {
+        const int u = i * 64 + lane, row = u >> 4, c16 = u & 15;
         const int n = nb * 32 + row;
-        v[i] = src[(size_t)(n < PE ? n : 0) * 24 + c16];
+        v[i] = src[(size_t)(n < PE ? n : 0) * 16 + c16];
       }
 #pragma unroll
-      for (int i = 0; i < 12; ++i) {
-        const int u = i * 64 + lane, row = u / 24, c16 = u - row * 24;
+      for (int i = 0; i < 8; ++i) {
+        const int u = i * 64 + lane, row = u >> 4, c16 = u & 15;
         sB[nb & 1][row * RW_BROW4 + c16] = v[i];
       }
       lds_release_barrier();
@@ -272,10 +356,12 @@ __global__ __launch_bounds__(RW_THREADS, RW_MIN_WG) void radial_weights_kernel(c
   const bool any_row = rows_here > 0;
   const bool all_rows = rows_here == RW_ROWS;
 
-  // A operand: hidden activations (times the cutoff envelope) of RW_MB x 32 edges, this lane's 32 units, in pieces
-  uint4 a_frag[RW_MB][3][4];
+  // A operand: hidden activations (times the cutoff envelope and s_g) of RW_MB x 32 edges, this lane's 32 units, in
+  // pieces
+  uint4 a_frag[RW_MB][2][4];
   const float step = r_cut / (float)(n_rbf - 1);
   const float inv2s2 = 0.5f / (step * step);
+  const float s_g = scales[1], unscale = scales[2];
 #pragma unroll
   for (int mb = 0; mb < RW_MB; ++mb) {
     long e = e_base + mb * 32 + m;
@@ -291,22 +377,21 @@ __global__ __launch_bounds__(RW_THREADS, RW_MIN_WG) void radial_weights_kernel(c
 #pragma unroll
       for (int s = 0; s < 32; ++s) pre[s] += wrow[s] * B;
     }
-    const float fc = 0.5f * (1.0f + cosf(3.14159265358979323846f * d / r_cut));
+    const float fc = s_g * 0.5f * (1.0f + cosf(3.14159265358979323846f * d / r_cut));
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      uint32_t ph[4], pm[4], pl[4];
+      uint32_t ph[4], pl[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const float x0 = pre[8 * t + 2 * q], x1 = pre[8 * t + 2 * q + 1];
-        const Split3 s0 = split3(fc * x0 / (1.0f + __expf(-x0)));
-        const Split3 s1 = split3(fc * x1 / (1.0f + __expf(-x1)));
-        ph[q] = pack2(s0.hi, s1.hi);
-        pm[q] = pack2(s0.mid, s1.mid);
-        pl[q] = pack2(s0.lo, s1.lo);
+        uint32_t h0, l0, h1, l1;
+        rw_split(fc * x0 / (1.0f + __expf(-x0)), h0, l0);
+        rw_split(fc * x1 / (1.0f + __expf(-x1)), h1, l1);
+        ph[q] = h0 | (h1 << 16);
+        pl[q] = l0 | (l1 << 16);
       }
       a_frag[mb][0][t] = make_uint4(ph[0], ph[1], ph[2], ph[3]);
-      a_frag[mb][1][t] = make_uint4(pm[0], pm[1], pm[2], pm[3]);
-      a_frag[mb][2][t] = make_uint4(pl[0], pl[1], pl[2], pl[3]);
+      a_frag[mb][1][t] = make_uint4(pl[0], pl[1], pl[2], pl[3]);
     }
   }
 
@@ -330,7 +415,7 @@ __global__ __launch_bounds__(RW_THREADS, RW_MIN_WG) void radial_weights_kernel(c
         for (int i = 0; i < 16; ++i) {
           const int r = 32 * mb + 8 * (i >> 2) + (i & 3);               // row relative to e_base + 4*hh
           // (the whole offset in the vector register: that is the part the range check looks at)
-          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, (float)acc[mb][i]), wave_rows,
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, unscale * (float)acc[mb][i]), wave_rows,
                                                 (int)((lane_off + (unsigned)(r * PE + nb * 32)) * 4u), 0, 2);
         }
     };
@@ -338,15 +423,15 @@ __global__ __launch_bounds__(RW_THREADS, RW_MIN_WG) void radial_weights_kernel(c
     auto step = [&](float16v (&acc)[RW_MB], const float16v (&prev)[RW_MB], int nb) {
       const bool fast = nb * 32 <= PE;                                  // block nb - 1 lies wholly inside the row
       if (fast)
-        rw_block<true>(sB[nb & 1], a_frag, m, hh, acc, prev, wave_rows, (nb - 1) * 32, lane_off, (size_t)PE);
+        rw_block<true>(sB[nb & 1], a_frag, m, hh, acc, prev, wave_rows, (nb - 1) * 32, lane_off, (size_t)PE, unscale);
       else {
-        rw_block<false>(sB[nb & 1], a_frag, m, hh, acc, prev, no_rows, 0, 0, 0);
+        rw_block<false>(sB[nb & 1], a_frag, m, hh, acc, prev, no_rows, 0, 0, 0, unscale);
         store_block(prev, nb - 1);
       }
     };
 #if RW_PIPELINE
     float16v acc0[RW_MB], acc1[RW_MB];
-    rw_block<false>(sB[0], a_frag, m, hh, acc0, acc0, no_rows, 0, 0, 0);
+    rw_block<false>(sB[0], a_frag, m, hh, acc0, acc0, no_rows, 0, 0, 0, unscale);
     int nb = 1;
     for (; nb + 1 < n_blocks; nb += 2) {
       step(acc1, acc0, nb);
@@ -362,14 +447,14 @@ __global__ __launch_bounds__(RW_THREADS, RW_MIN_WG) void radial_weights_kernel(c
     (void)step;
     for (int nb = 0; nb < n_blocks; ++nb) {
       float16v acc[RW_MB];
-      rw_block<false>(sB[nb & 1], a_frag, m, hh, acc, acc, no_rows, 0, 0, 0);
+      rw_block<false>(sB[nb & 1], a_frag, m, hh, acc, acc, no_rows, 0, 0, 0, unscale);
       if ((nb + 1) * 32 <= PE) {
 #pragma unroll
         for (int mb = 0; mb < RW_MB; ++mb)
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
             const int row_off = ((32 * mb + 8 * (i >> 2) + (i & 3)) * PE + nb * 32) * 4;
-            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, (float)acc[mb][i]), wave_rows,
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, unscale * (float)acc[mb][i]), wave_rows,
                                                   (int)(lane_off * 4u) + row_off, 0, 2);
           }
       } else {
@@ -384,17 +469,17 @@ __global__ __launch_bounds__(RW_THREADS, RW_MIN_WG) void radial_weights_kernel(c
     for (int nb = 0; nb < n_blocks; nb += 2) {
       float16v acc[RW_MB];
       uint32_t word[RW_MB][16];
-      rw_block<false>(sB[0], a_frag, m, hh, acc, acc, no_rows, 0, 0, 0);          // nb is even
+      rw_block<false>(sB[0], a_frag, m, hh, acc, acc, no_rows, 0, 0, 0, unscale);   // nb is even
 #pragma unroll
       for (int mb = 0; mb < RW_MB; ++mb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) word[mb][i] = w_half_bits(acc[mb][i]);
+        for (int i = 0; i < 16; ++i) word[mb][i] = w_half_bits(unscale * acc[mb][i]);
       if (nb + 1 < n_blocks) {                      // (the same for every wave of the workgroup, loader included)
-        rw_block<false>(sB[1], a_frag, m, hh, acc, acc, no_rows, 0, 0, 0);
+        rw_block<false>(sB[1], a_frag, m, hh, acc, acc, no_rows, 0, 0, 0, unscale);
 #pragma unroll
         for (int mb = 0; mb < RW_MB; ++mb)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) word[mb][i] |= w_half_bits(acc[mb][i]) << 16;
+          for (int i = 0; i < 16; ++i) word[mb][i] |= w_half_bits(unscale * acc[mb][i]) << 16;
       }
       // the low half decides: if its column exists the word does (a high half past the end is never read)
       if (nb * 32 + m < PE) {
@@ -419,6 +504,8 @@ __global__ __launch_bounds__(RW_THREADS, RW_MIN_WG) void radial_weights_kernel(c
   }
 }
 
+// room for the pieces of W_r2 in either form: three bf16 pieces per value (384 bytes per row), or 256 bytes of
+// scalings and two half-precision pieces (256 bytes per row; P * channels is at least 2)
 size_t egnn_radial_ws_bytes(const egnn_ctx* ctx, int which) {
   return (size_t)ctx->n_paths[which] * ctx->desc.channels * 3 * EGNN_HIDDEN * sizeof(uint16_t);
 }
@@ -435,14 +522,23 @@ int egnn_launch_split_w2(egnn_ctx* ctx, int which, const float* W_r2, void* scra
   return EGNN_OK;
 }
 
-// `scratch` holds egnn_radial_ws_bytes: the pieces of W_r2.
+// `scratch` holds egnn_radial_ws_bytes: the three scalings (256 bytes), then the half-precision pieces of W_r2.
 int egnn_launch_radial(egnn_ctx* ctx, int which, const float* rhat_d, int64_t n_edges, const float* W_r1,
                        const float* W_r2, float* w, void* scratch, hipStream_t stream, bool half) {
   if (n_edges == 0) return EGNN_OK;
-  const int PE = ctx->n_paths[which] * ctx->desc.channels;
-  int rc = egnn_launch_split_w2(ctx, which, W_r2, scratch, stream);
+  const int P = ctx->n_paths[which];
+  const int PE = P * ctx->desc.channels;
+  float* scales = (float*)scratch;
+  uint16_t* W2s = (uint16_t*)((char*)scratch + 256);
+  int rc = egnn_launch_half_scales(ctx, which, W_r1, W_r2, scales, stream);
   if (rc) return rc;
-  uint16_t* W2s = (uint16_t*)scratch;
+  {
+    PathAlpha al;
+    for (int p = 0; p < EGNN_MAX_PATHS; ++p) al.a[p] = p < P ? ctx->alpha[which][p] : 0.0f;
+    hipLaunchKernelGGL(split_w2_half_kernel, dim3((PE * EGNN_HIDDEN + 255) / 256), dim3(256), 0, stream, W_r2, W2s, PE,
+                       ctx->log2_channels, al, scales);
+    EGNN_LAUNCH_CHECK(ctx, "split_w2_half_kernel");
+  }
   // Workgroups: enough for RW_ROWS rows per wave; beyond one round of the 256 CUs their number is rounded up to whole
   // rounds and the edges are spread evenly, so that the last round is as full as the others.
   const long per_wg = (long)RW_ROWS * RW_COMPUTE_WAVES;
@@ -455,10 +551,10 @@ int egnn_launch_radial(egnn_ctx* ctx, int which, const float* rhat_d, int64_t n_
   dim3 grid((unsigned)n_wg), block(RW_THREADS);
   if (half)
     hipLaunchKernelGGL(radial_weights_kernel<true>, grid, block, 0, stream, reinterpret_cast<const float4*>(rhat_d),
-                       (long)n_edges, W_r1, W2s, w, ctx->desc.n_rbf, PE, ctx->desc.r_cut, rows_per_wave);
+                       (long)n_edges, W_r1, W2s, scales, w, ctx->desc.n_rbf, PE, ctx->desc.r_cut, rows_per_wave);
   else
     hipLaunchKernelGGL(radial_weights_kernel<false>, grid, block, 0, stream, reinterpret_cast<const float4*>(rhat_d),
-                       (long)n_edges, W_r1, W2s, w, ctx->desc.n_rbf, PE, ctx->desc.r_cut, rows_per_wave);
+                       (long)n_edges, W_r1, W2s, scales, w, ctx->desc.n_rbf, PE, ctx->desc.r_cut, rows_per_wave);
   EGNN_LAUNCH_CHECK(ctx, "radial_weights_kernel");
   return EGNN_OK;
 }

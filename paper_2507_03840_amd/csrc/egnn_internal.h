@@ -105,6 +105,8 @@ int egnn_launch_radial(egnn_ctx*, int which, const float* rhat_d, int64_t n_edge
 size_t egnn_w_bytes(const egnn_ctx*, int which, int64_t n_edges);   // room for w in either precision
 size_t egnn_radial_ws_bytes(const egnn_ctx*, int which);
 int egnn_launch_split_w2(egnn_ctx*, int which, const float* W_r2, void* scratch, hipStream_t);
+// scales[0..2] = s_w, s_g, 1 / (s_w s_g): the power-of-two scalings of the half-precision operand pieces
+int egnn_launch_half_scales(egnn_ctx*, int which, const float* W_r1, const float* W_r2, float* scales, hipStream_t);
 bool egnn_fused_supported(const egnn_ctx*);
 bool egnn_fused_lane_supported(const egnn_ctx*);
 size_t egnn_fused_lane_scratch_bytes(const egnn_ctx*, int32_t n_total);

@@ -55,43 +55,6 @@ __device__ __forceinline__ void f2_barrier_acquire() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// scales[0] = s_w, scales[1] = s_g (powers of two, see above), scales[2] = 1 / (s_w s_g).  One workgroup.
-__global__ __launch_bounds__(256) void f2_scales_kernel(const float* __restrict__ W_r1, const float* __restrict__ W_r2,
-                                                        int n_rbf, int PE, int log2E, PathAlpha alpha,
-                                                        float* __restrict__ scales) {
-  __shared__ float red[256];
-  float mw = 0.0f;
-  for (int i = threadIdx.x; i < PE * EGNN_HIDDEN; i += 256)
-    mw = fmaxf(mw, fabsf(alpha.a[(i / EGNN_HIDDEN) >> log2E] * W_r2[i]));
-  float mg = 0.0f;
-  if (threadIdx.x < EGNN_HIDDEN) {
-    for (int b = 0; b < n_rbf; ++b) mg += fabsf(W_r1[threadIdx.x * n_rbf + b]);
-  }
-  auto block_max = [&](float v) {
-    red[threadIdx.x] = v;
-    __syncthreads();
-    for (int st = 128; st > 0; st >>= 1) {
-      if ((int)threadIdx.x < st) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + st]);
-      __syncthreads();
-    }
-    const float r = red[0];
-    __syncthreads();
-    return r;
-  };
-  mw = block_max(mw);
-  mg = block_max(mg);
-  if (threadIdx.x == 0) {
-    // (zero, infinite or NaN weights: no scaling; the result then shows them as it would without)
-    auto exp_of = [](float m) { return (m > 0.0f && m < 3.0e38f) ? ilogbf(m) : 13; };
-    int ew = 13 - exp_of(mw), eg = 13 - exp_of(mg);
-    ew = ew < -60 ? -60 : (ew > 60 ? 60 : ew);
-    eg = eg < -60 ? -60 : (eg > 60 ? 60 : eg);
-    scales[0] = ldexpf(1.0f, ew);
-    scales[1] = ldexpf(1.0f, eg);
-    scales[2] = ldexpf(1.0f, -ew - eg);
-  }
-}
-
 // W_r2 [n = path * E + channel][64 units] fp32 -> W2p[tile = cp * npt + pt][R][2 pieces][64 halves] (16 uint4 per row),
 // values alpha_p * W_r2 * s_w cut into pieces; R = result row of the tile:
 // (i, hh) = (4 (R / 8) + R % 4, (R / 4) % 2) <-> (path 16 pt + i, channel 2 cp + hh).
@@ -384,9 +347,10 @@ int egnn_launch_layer_fused_lane(egnn_ctx* ctx, const egnn_graph* g, const float
   float* h2 = reinterpret_cast<float*>((char*)scratch + f2_align(f2_pack_bytes(ctx)));
   PathAlpha al;
   for (int p = 0; p < EGNN_MAX_PATHS; ++p) al.a[p] = p < ctx->n_paths[0] ? ctx->alpha[0][p] : 0.0f;
-  hipLaunchKernelGGL(f2_scales_kernel, dim3(1), dim3(256), 0, stream, W_r1, W_r2, ctx->desc.n_rbf, ctx->n_paths[0] * E,
-                     ctx->log2_channels, al, scales);
-  EGNN_LAUNCH_CHECK(ctx, "f2_scales_kernel");
+  {
+    const int rc = egnn_launch_half_scales(ctx, 0, W_r1, W_r2, scales, stream);
+    if (rc) return rc;
+  }
   hipLaunchKernelGGL(f2_pack_kernel, dim3((n_tiles * 32 * 16 + 255) / 256), dim3(256), 0, stream, W_r2, W2p,
                      ctx->n_paths[0], ctx->log2_channels, npt, n_tiles, al, scales);
   EGNN_LAUNCH_CHECK(ctx, "f2_pack_kernel");

@@ -232,9 +232,9 @@ def test_fused_sparse_graph(B, r_cut, fused):
 
 
 @pytest.mark.parametrize("s1,s2", [(1e-4, 1e-6), (30.0, 1e5), (1.0, 3e-9), (2e-3, 4e7)])
-def test_fused_lane_weight_scales(B, s1, s2):
-    """The second fused design cuts its matrix-core operands into half-precision pieces; their scalings come from the
-    weights, so tiny and huge radial weights keep the accuracy of the default route."""
+def test_radial_weight_scales(B, s1, s2):
+    """The radial contraction (S3, and the second fused design) cuts its matrix-core operands into half-precision
+    pieces; their scalings come from the weights, so tiny and huge radial weights keep fp32-level accuracy."""
     w = _cluster(120, 90, 3, 16, n_rbf=6, r_cut=4.0, seed=77)
     w.n_layers = 1
     wt = U.model_weights(w)
@@ -243,14 +243,18 @@ def test_fused_lane_weight_scales(B, s1, s2):
     wt["layers"][0]["W_self"] = np.zeros_like(wt["layers"][0]["W_self"])     # the output is the message term alone
     g = U.oracle_graph(w)
     agg = max(1.0, U.mean_degree(g, w.n_owned))
-    xs_ref, _ = U.oracle_forward(w, wt, g, agg, with_readout=False)
-    assert np.abs(xs_ref[0]).max() > 0
+    wt["readout"]["W_r1"] = (wt["readout"]["W_r1"] * np.float32(s1)).astype(np.float32)
+    wt["readout"]["W_r2"] = (wt["readout"]["W_r2"] * np.float32(s2)).astype(np.float32)
+    xs_ref, H_ref = U.oracle_forward(w, wt, g, agg)
+    assert np.abs(xs_ref[0]).max() > 0 and np.abs(H_ref).max() > 0
     errs = []
     for fused in (0, 2):
-        m, graph, xs, H = U.gpu_forward(w, wt, agg, with_readout=False, fused=fused)
+        m, graph, xs, H = U.gpu_forward(w, wt, agg, fused=fused)
         errs.append(U.rel_err(xs[0].cpu().numpy(), xs_ref[0]))
-    print("rel err two-kernel %.2e, fused %.2e" % tuple(errs), flush=True)
-    assert errs[0] < 1e-5 and errs[1] < 1e-5
+        if fused == 0:
+            errs.append(U.rel_err(H.cpu().numpy(), H_ref))
+    print("rel err two-kernel %.2e (H_ij %.2e), fused %.2e" % tuple(errs), flush=True)
+    assert max(errs) < 1e-5
 
 
 def _model_forward_small(B, lmax, E, periodic, n, n_owned, fused, r_cut=4.0):
