@@ -339,9 +339,9 @@ def main():
         macs = sum((1 if q == 0 else 4) * ((L_ + 1 - q) * E_) * ((L_ + 1 - q) * 2 * E_) for q in range(L_ + 1)) + (L_ + 1) * E_ * E_
         so2 = dict(ms=so2_ms, edges_per_s=n_edges / so2_ms * 1e3, flop_per_edge=2 * macs,
                    TFLOPs_fp32_equivalent=2 * macs * n_edges / so2_ms / 1e9,
-                   bf16_mfma_TFLOPs=6 * 2 * macs * n_edges / so2_ms / 1e9, bf16_mfma_peak_TFLOPs=2500.0,
+                   f16_mfma_TFLOPs=3 * 2 * macs * n_edges / so2_ms / 1e9, f16_mfma_peak_TFLOPs=2500.0,
                    workspace_GB=ws2.numel() / 1e9,
-                   note="gather+rotate, five split-bf16 GEMMs (six bf16 products per fp32 product), rotate back + segmented sum")
+                   note="gather+rotate, five GEMMs on half-precision pieces of the fp32 operands (three products per fp32 product), rotate back + segmented sum")
         del ws2
         # the same transform with the full message content: persistent edge embeddings, attention-weighted node block,
         # gate, edge block (one layer in the shape the paper describes)
@@ -361,7 +361,7 @@ def main():
                                    layer_ms=t_node + t_gate + t_edge,
                                    messages_per_s=2 * n_edges / (t_node + t_edge) * 1e3,
                                    floats_per_message=3 * (L_ + 1) ** 2 * E_, flop_per_message=2 * macs_full,
-                                   bf16_mfma_TFLOPs=6 * 2 * macs_full * n_edges * 2 / (t_node + t_edge) / 1e9,
+                                   f16_mfma_TFLOPs=3 * 2 * macs_full * n_edges * 2 / (t_node + t_edge) / 1e9,
                                    workspace_GB=ws3.numel() / 1e9, edge_embeddings_GB=T_edge.numel() * 4 / 1e9,
                                    note="node block = gather (3 x 25 x E floats per message) + GEMMs + attention + "
                                         "weighted segmented sum; edge block = the same transform with its own weights, "

@@ -43,18 +43,27 @@ static size_t so2_w_offset(int lmax, int E, int m) {
   return off;
 }
 
+__device__ __forceinline__ void so2_raise_max(unsigned* target, float v) {
+  const unsigned bits = __float_as_uint(v);
+  if (bits > __atomic_load_n(target, __ATOMIC_RELAXED)) atomicMax(target, bits);
+}
+
 // ---------------------------------------------------------------------------------------------- 1. gather
 // FULL: edge_in is the edge embedding tensor [n_edges][(LMAX+1)^2][E]; otherwise it is W_e [E][n_rbf]
 template <int LMAX, bool FULL>
 __global__ __launch_bounds__(256) void so2_gather_kernel(const int* __restrict__ src, const int* __restrict__ dst,
                                                          const float4* __restrict__ rhat_d, const float* __restrict__ x,
                                                          const float* __restrict__ edge_in, So2Bufs b, long n_edges,
-                                                         int log2E, int n_rbf, float r_cut) {
+                                                         int log2E, int n_rbf, float r_cut,
+                                                         unsigned* __restrict__ a_max) {
   constexpr int D = (LMAX + 1) * (LMAX + 1);
   const int E = 1 << log2E;
   const int c = threadIdx.x & (E - 1);
-  const long k = (long)blockIdx.x * (256 >> log2E) + (threadIdx.x >> log2E);
-  if (k >= n_edges) return;
+  const long k_own = (long)blockIdx.x * (256 >> log2E) + (threadIdx.x >> log2E);
+  // (threads past the last edge repeat it and store nothing: every lane takes part in the reduction at the end)
+  const bool live = k_own < n_edges;
+  const long k = live ? k_own : n_edges - 1;
+  float amax = 0.0f;     // largest magnitude this thread writes into the operands A_m (scaling of the GEMMs)
   const float4 g = rhat_d[k];
   const float* xs = x + (((size_t)src[k] * D) << log2E) + c;
   const float* xd = x + (((size_t)dst[k] * D) << log2E) + c;
@@ -68,32 +77,38 @@ __global__ __launch_bounds__(256) void so2_gather_kernel(const int* __restrict__
   egnn_bond_trig<LMAX>(g.x, g.y, g.z, t);
   egnn_to_bond_frame<LMAX>(vs, t);
   egnn_to_bond_frame<LMAX>(vd, t);
+#pragma unroll
+  for (int i = 0; i < D; ++i) amax = fmaxf(amax, fmaxf(fabsf(vs[i]), fabsf(vd[i])));
   if constexpr (FULL) {
     float ve[D];
     const float* te = edge_in + (((size_t)k * D) << log2E) + c;
 #pragma unroll
     for (int i = 0; i < D; ++i) ve[i] = __builtin_nontemporal_load(te + ((size_t)i << log2E));
     egnn_to_bond_frame<LMAX>(ve, t);
-    float* a0 = b.A[0] + (size_t)k * b.K[0] + c;
 #pragma unroll
-    for (int l = 0; l <= LMAX; ++l) {
-      __builtin_nontemporal_store(vs[l * l + l], a0 + ((3 * l) << log2E));
-      __builtin_nontemporal_store(vd[l * l + l], a0 + ((3 * l + 1) << log2E));
-      __builtin_nontemporal_store(ve[l * l + l], a0 + ((3 * l + 2) << log2E));
-    }
+    for (int i = 0; i < D; ++i) amax = fmaxf(amax, fabsf(ve[i]));
+    if (live) {
+      float* a0 = b.A[0] + (size_t)k * b.K[0] + c;
 #pragma unroll
-    for (int m = 1; m <= LMAX; ++m) {
-      const int nl = LMAX + 1 - m;
-      float* am = b.A[m] + (size_t)k * b.K[m] + c;
+      for (int l = 0; l <= LMAX; ++l) {
+        __builtin_nontemporal_store(vs[l * l + l], a0 + ((3 * l) << log2E));
+        __builtin_nontemporal_store(vd[l * l + l], a0 + ((3 * l + 1) << log2E));
+        __builtin_nontemporal_store(ve[l * l + l], a0 + ((3 * l + 2) << log2E));
+      }
 #pragma unroll
-      for (int l = m; l <= LMAX; ++l) {
-        const int col = (3 * (l - m)) << log2E, neg = (3 * nl) << log2E;
-        __builtin_nontemporal_store(vs[l * l + l + m], am + col);
-        __builtin_nontemporal_store(vd[l * l + l + m], am + col + E);
-        __builtin_nontemporal_store(ve[l * l + l + m], am + col + 2 * E);
-        __builtin_nontemporal_store(vs[l * l + l - m], am + neg + col);
-        __builtin_nontemporal_store(vd[l * l + l - m], am + neg + col + E);
-        __builtin_nontemporal_store(ve[l * l + l - m], am + neg + col + 2 * E);
+      for (int m = 1; m <= LMAX; ++m) {
+        const int nl = LMAX + 1 - m;
+        float* am = b.A[m] + (size_t)k * b.K[m] + c;
+#pragma unroll
+        for (int l = m; l <= LMAX; ++l) {
+          const int col = (3 * (l - m)) << log2E, neg = (3 * nl) << log2E;
+          __builtin_nontemporal_store(vs[l * l + l + m], am + col);
+          __builtin_nontemporal_store(vd[l * l + l + m], am + col + E);
+          __builtin_nontemporal_store(ve[l * l + l + m], am + col + 2 * E);
+          __builtin_nontemporal_store(vs[l * l + l - m], am + neg + col);
+          __builtin_nontemporal_store(vd[l * l + l - m], am + neg + col + E);
+          __builtin_nontemporal_store(ve[l * l + l - m], am + neg + col + 2 * E);
+        }
       }
     }
   } else {
@@ -105,27 +120,45 @@ __global__ __launch_bounds__(256) void so2_gather_kernel(const int* __restrict__
       const float u = g.w - (float)q * step;
       e0 += edge_in[c * n_rbf + q] * __expf(-u * u * inv2s2);
     }
-    float* a0 = b.A[0] + (size_t)k * b.K[0] + c;
+    amax = fmaxf(amax, fabsf(e0));
+    if (live) {
+      float* a0 = b.A[0] + (size_t)k * b.K[0] + c;
 #pragma unroll
-    for (int l = 0; l <= LMAX; ++l) {
-      __builtin_nontemporal_store(vs[l * l + l], a0 + ((2 * l) << log2E));
-      __builtin_nontemporal_store(vd[l * l + l], a0 + ((2 * l + 1) << log2E));
-    }
-    __builtin_nontemporal_store(e0, a0 + ((2 * (LMAX + 1)) << log2E));
+      for (int l = 0; l <= LMAX; ++l) {
+        __builtin_nontemporal_store(vs[l * l + l], a0 + ((2 * l) << log2E));
+        __builtin_nontemporal_store(vd[l * l + l], a0 + ((2 * l + 1) << log2E));
+      }
+      __builtin_nontemporal_store(e0, a0 + ((2 * (LMAX + 1)) << log2E));
 #pragma unroll
-    for (int m = 1; m <= LMAX; ++m) {
-      const int nl = LMAX + 1 - m;
-      float* am = b.A[m] + (size_t)k * b.K[m] + c;
+      for (int m = 1; m <= LMAX; ++m) {
+        const int nl = LMAX + 1 - m;
+        float* am = b.A[m] + (size_t)k * b.K[m] + c;
 #pragma unroll
-      for (int l = m; l <= LMAX; ++l) {
-        const int col = (2 * (l - m)) << log2E;
-        __builtin_nontemporal_store(vs[l * l + l + m], am + col);
-        __builtin_nontemporal_store(vd[l * l + l + m], am + col + E);
-        __builtin_nontemporal_store(vs[l * l + l - m], am + ((2 * nl) << log2E) + col);
-        __builtin_nontemporal_store(vd[l * l + l - m], am + ((2 * nl) << log2E) + col + E);
+        for (int l = m; l <= LMAX; ++l) {
+          const int col = (2 * (l - m)) << log2E;
+          __builtin_nontemporal_store(vs[l * l + l + m], am + col);
+          __builtin_nontemporal_store(vd[l * l + l + m], am + col + E);
+          __builtin_nontemporal_store(vs[l * l + l - m], am + ((2 * nl) << log2E) + col);
+          __builtin_nontemporal_store(vd[l * l + l - m], am + ((2 * nl) << log2E) + col + E);
+        }
       }
     }
   }
+  // the wavefront's largest value raises the global one with an integer atomic (non-negative floats order like their
+  // bit patterns) -- only if it is larger than what is there already, which after the first few thousand wavefronts
+  // it almost never is: atomics on one address run one after the other
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+  if ((threadIdx.x & 63) == 0) so2_raise_max(a_max, amax);
+}
+
+// largest magnitude of the weights of all orders (they share one scaling), by integer atomics as above
+__global__ __launch_bounds__(256) void so2_wmax_kernel(const float* __restrict__ W, long n_w, unsigned* __restrict__ w_max) {
+  float mx = 0.0f;
+  for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n_w; i += (long)gridDim.x * 256) mx = fmaxf(mx, fabsf(W[i]));
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+  if ((threadIdx.x & 63) == 0) so2_raise_max(w_max, mx);
 }
 
 // The initial edge embedding (Sec. 3 "Initialization"): L = 0 plane = W_e B(d_k), zeros elsewhere.
@@ -188,9 +221,10 @@ __device__ __forceinline__ float so2_b_value(const float* __restrict__ W, int m,
   return s_in == 0 ? W[sz + at] : -W[sz + at];         // x_{+m} -> y_{-m}: +Wi;  x_{-m} -> y_{+m}: -Wi
 }
 
-// T[ct][step][j][piece][64]: thread -> (ct, step, j, pair of contraction indices)
+// T[ct][step][j][piece][64] halves (two pieces: see stream_gemm.h): thread -> (ct, step, j, pair of contraction indices)
 __global__ __launch_bounds__(256) void so2_pack_kernel(const float* __restrict__ W, uint16_t* __restrict__ T, int m, int lmax,
-                                                       int E, int K, int N, int n_steps, int n_ct, bool full) {
+                                                       int E, int K, int N, int n_steps, int n_ct, bool full,
+                                                       const unsigned* __restrict__ w_max) {
   const long i = (long)blockIdx.x * 256 + threadIdx.x;
   const long total = (long)n_ct * n_steps * 64 * 32;
   if (i >= total) return;
@@ -198,11 +232,14 @@ __global__ __launch_bounds__(256) void so2_pack_kernel(const float* __restrict__
   const long blk = i >> 11;                    // ct * n_steps + step
   const int step = (int)(blk % n_steps), ct = (int)(blk / n_steps);
   const int n = ct * 64 + j, k = step * 64 + 2 * rp;
-  const Split3 s0 = split3(so2_b_value(W, m, lmax, E, k, n, K, N, full)), s1 = split3(so2_b_value(W, m, lmax, E, k + 1, n, K, N, full));
-  uint32_t* o = reinterpret_cast<uint32_t*>(T) + blk * (64 * 96) + j * 96 + rp;
-  o[0] = pack2(s0.hi, s1.hi);
-  o[32] = pack2(s0.mid, s1.mid);
-  o[64] = pack2(s0.lo, s1.lo);
+  const float sc = ldexpf(1.0f, sgh_scale_exp(*w_max));
+  const float xv[8] = {so2_b_value(W, m, lmax, E, k, n, K, N, full), so2_b_value(W, m, lmax, E, k + 1, n, K, N, full),
+                       0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+  uint4 hi, lo;
+  sgh_split8(xv, sc, hi, lo);
+  uint32_t* o = reinterpret_cast<uint32_t*>(T) + blk * (64 * 64) + j * 64 + rp;
+  o[0] = hi.x;
+  o[32] = lo.x;
 }
 
 // ---------------------------------------------------------------------------------------------- 3. GEMM
@@ -214,7 +251,7 @@ __global__ __launch_bounds__(256) void so2_pack_kernel(const float* __restrict__
 // to operand order through a private LDS tile.
 __global__ __launch_bounds__(SG_THREADS) void so2_gemm_kernel(const float* __restrict__ A, long M, int K, const uint16_t* __restrict__ T,
                                                               int n_steps, float* __restrict__ C, int N, int n_ct,
-                                                              int n_row_blocks) {
+                                                              int n_row_blocks, const unsigned* __restrict__ maxima) {
   extern __shared__ uint4 so2_smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
@@ -222,8 +259,12 @@ __global__ __launch_bounds__(SG_THREADS) void so2_gemm_kernel(const float* __res
   const int row_block = (idx / n_ct) * 8 + xcd;
   if (row_block >= n_row_blocks) return;   // (whole workgroup: the grid is rounded up to a multiple of 8 row blocks)
   const long e_base = ((long)row_block * SG_WAVES + wave) * 64;
+  // scalings of the two operands (maxima[0]: largest |A| written by the gather kernel, maxima[1]: largest weight)
+  const int ea = sgh_scale_exp(maxima[0]), eb = sgh_scale_exp(maxima[1]);
+  const float a_scale = ldexpf(1.0f, ea), unscale = ldexpf(1.0f, -ea - eb);
   float16v acc[2][2];
-  sg_contract(A, M, K, reinterpret_cast<const uint4*>(T) + (long)ct * n_steps * (64 * 24), n_steps, so2_smem, e_base, acc);
+  sgh_contract(A, M, K, reinterpret_cast<const uint4*>(T) + (long)ct * n_steps * (64 * 16), n_steps, so2_smem, e_base,
+               a_scale, acc);
   const int m = lane & 31, hh = lane >> 5;
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb)
@@ -234,7 +275,7 @@ __global__ __launch_bounds__(SG_THREADS) void so2_gemm_kernel(const float* __res
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const long e = e_base + rb * 32 + 8 * (i >> 2) + 4 * hh + (i & 3);
-          if (e < M) C[(size_t)e * N + col] = acc[rb][cb][i];
+          if (e < M) C[(size_t)e * N + col] = unscale * acc[rb][cb][i];
         }
       }
     }
@@ -399,12 +440,14 @@ extern "C" int egnn_so2_weight_count(const egnn_ctx* ctx, int64_t* n_floats) {
 
 // rhat_d, the operands A_m, the results Y_m, the packed weights, and (blocks only) one float per edge
 static size_t so2_ws(const egnn_ctx* ctx, int64_t n_edges, bool full, bool carve, char* base, float** rhat_d, So2Bufs* b,
-                     uint16_t** T, float** alpha) {
+                     uint16_t** T, float** alpha, unsigned** maxima = nullptr) {
   const int lmax = ctx->desc.lmax, E = ctx->desc.channels;
   size_t used = 0;
   auto take = [&](size_t bytes) { char* p = carve ? base + used : nullptr; used += so2_a256(bytes); return p; };
   float* rd = (float*)take((size_t)n_edges * 16);
   if (rhat_d) *rhat_d = rd;
+  unsigned* mx = (unsigned*)take(256);     // largest magnitudes of the GEMM operands (bit patterns), see so2_transform
+  if (maxima) *maxima = mx;
   for (int m = 0; m <= lmax; ++m) {
     const int K = so2_K(lmax, E, m, full), N = so2_N(lmax, E, m);
     float* A = (float*)take((size_t)n_edges * K * sizeof(float));
@@ -435,6 +478,7 @@ extern "C" int egnn_so2_blocks_workspace_bytes(const egnn_ctx* ctx, int64_t n_ed
 struct So2Call {
   float* rhat_d;
   float* alpha;
+  unsigned* maxima;
   So2Bufs b;
   uint16_t* T[5];
 };
@@ -458,10 +502,12 @@ static int so2_transform(egnn_ctx* ctx, const egnn_graph* g, const float* pos, c
   const int lmax = ctx->desc.lmax, E = ctx->desc.channels;
   for (int m = 0; m < 5; ++m) { call->b.A[m] = call->b.Y[m] = nullptr; call->b.K[m] = call->b.N[m] = 0; call->T[m] = nullptr; }
   call->alpha = nullptr;
-  so2_ws(ctx, g->n_edges, full, true, (char*)ws, &call->rhat_d, &call->b, call->T, &call->alpha);
+  so2_ws(ctx, g->n_edges, full, true, (char*)ws, &call->rhat_d, &call->b, call->T, &call->alpha, &call->maxima);
   const long n = g->n_edges;
   if (n == 0) return EGNN_OK;
   int rc;
+  // the two largest magnitudes start at zero; the gather kernel and so2_wmax_kernel raise them
+  if ((rc = egnn_launch_fill_int(ctx, (int*)call->maxima, 64, 0, st))) return rc;
   if ((rc = egnn_launch_geometry(ctx, g, pos, box, call->rhat_d, nullptr, nullptr, nullptr, st))) return rc;
   const float4* rd = reinterpret_cast<const float4*>(call->rhat_d);
   const int per_wg = 256 / E;
@@ -470,10 +516,10 @@ static int so2_transform(egnn_ctx* ctx, const egnn_graph* g, const float* pos, c
   do {                                                                                                                 \
     if (full)                                                                                                          \
       hipLaunchKernelGGL((so2_gather_kernel<L, true>), grid, block, 0, st, g->src, g->dst, rd, x, edge_in, call->b, n, \
-                         ctx->log2_channels, ctx->desc.n_rbf, ctx->desc.r_cut);                                        \
+                         ctx->log2_channels, ctx->desc.n_rbf, ctx->desc.r_cut, call->maxima);                          \
     else                                                                                                               \
       hipLaunchKernelGGL((so2_gather_kernel<L, false>), grid, block, 0, st, g->src, g->dst, rd, x, edge_in, call->b, n, \
-                         ctx->log2_channels, ctx->desc.n_rbf, ctx->desc.r_cut);                                        \
+                         ctx->log2_channels, ctx->desc.n_rbf, ctx->desc.r_cut, call->maxima);                          \
   } while (0)
   switch (lmax) {
     case 0: GATHER(0); break;
@@ -484,7 +530,13 @@ static int so2_transform(egnn_ctx* ctx, const egnn_graph* g, const float* pos, c
   }
 #undef GATHER
   EGNN_LAUNCH_CHECK(ctx, "so2_gather_kernel");
-  const size_t lds = SG_LDS_BYTES;
+  {
+    const long n_w = (long)so2_w_offset(lmax, E, lmax + 1);
+    const unsigned wg = (unsigned)((n_w + 255) / 256 < 256 ? (n_w + 255) / 256 : 256);
+    hipLaunchKernelGGL(so2_wmax_kernel, dim3(wg), dim3(256), 0, st, W_so2, n_w, call->maxima + 1);
+    EGNN_LAUNCH_CHECK(ctx, "so2_wmax_kernel");
+  }
+  const size_t lds = SGH_LDS_BYTES;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(so2_gemm_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(so2_gemm_kernel)");
@@ -492,13 +544,13 @@ static int so2_transform(egnn_ctx* ctx, const egnn_graph* g, const float* pos, c
     const int K = call->b.K[m], N = call->b.N[m], n_steps = so2_steps(K), n_ct = so2_tiles(N);
     const long total = (long)n_ct * n_steps * 64 * 32;
     hipLaunchKernelGGL(so2_pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                       W_so2 + so2_w_offset(lmax, E, m), call->T[m], m, lmax, E, K, N, n_steps, n_ct, full);
+                       W_so2 + so2_w_offset(lmax, E, m), call->T[m], m, lmax, E, K, N, n_steps, n_ct, full, call->maxima + 1);
     EGNN_LAUNCH_CHECK(ctx, "so2_pack_kernel");
     const long rows_per_wg = 64L * SG_WAVES;
     const int n_row_blocks = (int)((n + rows_per_wg - 1) / rows_per_wg);
     const unsigned grid_x = (unsigned)(((n_row_blocks + 7) / 8) * 8 * n_ct);
     hipLaunchKernelGGL(so2_gemm_kernel, dim3(grid_x), dim3(SG_THREADS), lds, st, call->b.A[m], n, K, call->T[m], n_steps,
-                       call->b.Y[m], N, n_ct, n_row_blocks);
+                       call->b.Y[m], N, n_ct, n_row_blocks, call->maxima);
     EGNN_LAUNCH_CHECK(ctx, "so2_gemm_kernel");
   }
   return EGNN_OK;

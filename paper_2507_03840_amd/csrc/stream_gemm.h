@@ -191,3 +191,135 @@ __device__ __forceinline__ void sg_contract(const float* __restrict__ A, long M,
     }
   }
 }
+
+// ---------------------------------------------------------------------------------------------------------------
+// The same streaming contraction on two half-precision pieces per operand and three products per fp32 product
+// (hi*hi + hi*lo + lo*hi; the lo*lo term is 2^-22 of the product).  Half precision has a narrow exponent range, so
+// both operands carry a power-of-two scaling chosen from their largest magnitude (largest piece in [2^13, 2^14)):
+// the small operand is scaled when it is packed, the large one (times a_scale) when it is cut, and the caller undoes
+// both on the accumulators.  Packed small operand: T[step][j][piece][64] halves, 16 uint4 per row j.
+// Dynamic LDS: SGH_LDS_BYTES.
+#define SGH_BROW4 17   // uint4 per staged row: 16 of data (2 pieces x 64 halves) + 1 of padding
+#define SGH_LDS_BYTES ((size_t)2 * 64 * SGH_BROW4 * sizeof(uint4) + (size_t)SG_WAVES * 32 * SG_AROW * sizeof(float))
+typedef _Float16 sgh_h8 __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ sgh_h8 sgh_as_h8(uint4 v) { return __builtin_bit_cast(sgh_h8, v); }
+
+// the power of two that brings a largest magnitude (given as the bits of a non-negative float) into [2^13, 2^14):
+// returned as its exponent; 0 for zero, infinite or NaN input
+__device__ __forceinline__ int sgh_scale_exp(unsigned max_bits) {
+  const float m = __uint_as_float(max_bits);
+  if (!(m > 0.0f && m < 3.0e38f)) return 0;
+  const int e = 13 - ilogbf(m);
+  return e < -60 ? -60 : (e > 60 ? 60 : e);
+}
+
+// eight fp32 values times `scale` -> the two half-precision pieces of an MFMA operand register
+__device__ __forceinline__ void sgh_split8(const float (&x)[8], float scale, uint4& hi, uint4& lo) {
+  uint32_t h[4], l[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const float a0 = x[2 * q] * scale, a1 = x[2 * q + 1] * scale;
+    const _Float16 h0 = (_Float16)a0, h1 = (_Float16)a1;
+    const _Float16 l0 = (_Float16)(a0 - (float)h0), l1 = (_Float16)(a1 - (float)h1);
+    h[q] = (uint32_t)__builtin_bit_cast(unsigned short, h0) | ((uint32_t)__builtin_bit_cast(unsigned short, h1) << 16);
+    l[q] = (uint32_t)__builtin_bit_cast(unsigned short, l0) | ((uint32_t)__builtin_bit_cast(unsigned short, l1) << 16);
+  }
+  hi = make_uint4(h[0], h[1], h[2], h[3]);
+  lo = make_uint4(l[0], l[1], l[2], l[3]);
+}
+
+// acc0 / acc1 += A (pieces ah, al) x B (pieces b0 / b1) for one 16-wide contraction step, two column blocks, the two
+// accumulation chains interleaved; smallest terms first
+__device__ __forceinline__ void sgh_mma3x2(uint4 ah, uint4 al, const uint4 (&b0)[2], const uint4 (&b1)[2],
+                                           float16v& acc0, float16v& acc1) {
+#define SGH_STEP(A, P)                                                                                  \
+  acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(sgh_as_h8(A), sgh_as_h8(b0[P]), acc0, 0, 0, 0);         \
+  acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(sgh_as_h8(A), sgh_as_h8(b1[P]), acc1, 0, 0, 0);
+  SGH_STEP(al, 0) SGH_STEP(ah, 1) SGH_STEP(ah, 0)
+#undef SGH_STEP
+}
+
+__device__ __forceinline__ void sgh_row_block(float* sA, const uint4* bbase, sg_f4 (&nxt)[8], const float* const (&fptr)[8],
+                                              int next_col, int frow, int fcol, int m, int hh, float a_scale,
+                                              float16v& acc0, float16v& acc1) {
+  sg_store8(sA + frow * SG_AROW + fcol, nxt);
+  sg_fetch8(nxt, fptr, next_col);
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+  const float4* arow = reinterpret_cast<const float4*>(sA + m * SG_AROW + hh * 32);
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const uint4* brow0 = bbase + m * SGH_BROW4 + t;
+    const uint4* brow1 = brow0 + 32 * SGH_BROW4;
+    const uint4 b0[2] = {brow0[0], brow0[8]};
+    const uint4 b1[2] = {brow1[0], brow1[8]};
+    const float4 u = arow[2 * t], v = arow[2 * t + 1];
+    const float xv[8] = {u.x, u.y, u.z, u.w, v.x, v.y, v.z, v.w};
+    uint4 ah, al;
+    sgh_split8(xv, a_scale, ah, al);
+    sgh_mma3x2(ah, al, b0, b1, acc0, acc1);
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+  __builtin_amdgcn_wave_barrier();   // reads of the tile are done before the next block overwrites it
+}
+
+// as sg_contract; tsrc: n_steps blocks of 64 x 16 uint4; the accumulators hold a_scale * (scale of the packed operand)
+// times the result
+__device__ __forceinline__ void sgh_contract(const float* __restrict__ A, long M, int K, const uint4* __restrict__ tsrc,
+                                             int n_steps, uint4* smem, long e_base, float a_scale, float16v (&acc)[2][2]) {
+  uint4* sB = smem;                                  // [2][64][SGH_BROW4]
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  float* sA = reinterpret_cast<float*>(sB + 2 * 64 * SGH_BROW4) + (size_t)wave * 32 * SG_AROW;
+  const int m = lane & 31, hh = lane >> 5;
+  const int frow = lane >> 4, fcol = (lane & 15) * 4;
+  const float* fptr0[8];
+  const float* fptr1[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    long e0 = e_base + 4 * i + frow, e1 = e0 + 32;
+    if (e0 >= M) e0 = M - 1;
+    if (e1 >= M) e1 = M - 1;
+    fptr0[i] = A + (size_t)e0 * K;
+    fptr1[i] = A + (size_t)e1 * K;
+  }
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
+  // the 16 KB block of the small operand of a step: two 16-byte pieces per thread
+  sg_u4 bnext[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) bnext[i] = *reinterpret_cast<const sg_u4*>(tsrc + i * SG_THREADS + tid);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int u = i * SG_THREADS + tid, row = u >> 4, c16 = u & 15;
+    *reinterpret_cast<sg_u4*>(sB + row * SGH_BROW4 + c16) = bnext[i];
+  }
+  sg_f4 nxt0[8], nxt1[8];
+  sg_fetch8(nxt0, fptr0, fcol < K ? fcol : K - 4);
+  sg_fetch8(nxt1, fptr1, fcol < K ? fcol : K - 4);
+  for (int s = 0; s < n_steps; ++s) {
+    rb_release_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    const uint4* bbase = sB + (s & 1) * (64 * SGH_BROW4) + hh * 4;
+    const int s_next = s + 1 < n_steps ? s + 1 : s;   // (the last step fetches itself again: no branch around loads)
+    const int n_next = s_next * 64 + fcol;
+    const int next_col = n_next < K ? n_next : K - 4;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      bnext[i] = *reinterpret_cast<const sg_u4*>(tsrc + (size_t)s_next * (64 * 16) + i * SG_THREADS + tid);
+    sgh_row_block(sA, bbase, nxt0, fptr0, next_col, frow, fcol, m, hh, a_scale, acc[0][0], acc[0][1]);
+    sgh_row_block(sA, bbase, nxt1, fptr1, next_col, frow, fcol, m, hh, a_scale, acc[1][0], acc[1][1]);
+    // (after the last step this rewrites a buffer that nobody reads any more)
+    uint4* bdst = sB + ((s + 1) & 1) * (64 * SGH_BROW4);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int u = i * SG_THREADS + tid, row = u >> 4, c16 = u & 15;
+      *reinterpret_cast<sg_u4*>(bdst + row * SGH_BROW4 + c16) = bnext[i];
+    }
+  }
+}

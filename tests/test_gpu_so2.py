@@ -18,12 +18,17 @@ def B():
     return binding
 
 
-def run_case(B, w, seed=0):
+def run_case(B, w, seed=0, x_scale=1.0, w_scale=1.0):
     g = U.oracle_graph(w)
     agg = max(1.0, U.mean_degree(g, w.n_owned))
     rng = np.random.default_rng([w.seed if hasattr(w, "seed") and w.seed else 0, 7, seed])
     x = synth.node_features(rng, w.n_total, w.lmax, w.channels)
     W_e, W0, Wr, Wi = synth.so2_weights(rng, w.lmax, w.channels, w.n_rbf)
+    x = (x * np.float32(x_scale)).astype(np.float32)
+    W_e = (W_e * np.float32(x_scale)).astype(np.float32)
+    W0 = (W0 * np.float32(w_scale)).astype(np.float32)
+    Wr = [(v * np.float32(w_scale)).astype(np.float32) for v in Wr]
+    Wi = [(v * np.float32(w_scale)).astype(np.float32) for v in Wi]
     ref = S.so2_message_sum(g, w.pos, w.box, x, W_e, W0, Wr, Wi, w.lmax, w.channels, w.n_rbf, w.r_cut, agg)
     m = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, agg)
     flat = S.so2_pack(W0, Wr, Wi)
@@ -49,6 +54,18 @@ def test_so2_message_sum_small(B, lmax, E, periodic, n, n_owned, r_cut):
     e = U.rel_err(a, ref)
     print(f"  {n_e} edges, rel err {e:.2e}", flush=True)
     assert e < TOL
+
+
+@pytest.mark.parametrize("x_scale,w_scale", [(1e-7, 1e5), (3e4, 2e-6), (1e-12, 1e-9), (5e8, 40.0)])
+def test_so2_operand_scales(B, x_scale, w_scale):
+    """The GEMMs cut their operands into half-precision pieces after a scaling taken from the largest feature and the
+    largest weight: tiny and huge operands keep the accuracy."""
+    w = synth.small_cluster(100, 70, 3, 16, 6, 4.0, 57, False)
+    a, ref, n_e = run_case(B, w, x_scale=x_scale, w_scale=w_scale)
+    assert n_e > 0 and np.abs(ref).max() > 0
+    e = U.rel_err(a, ref)
+    print(f"  scales {x_scale:g} {w_scale:g}: rel err {e:.2e}", flush=True)
+    assert e < 1e-5
 
 
 def test_so2_message_sum_config1(B):
