@@ -142,7 +142,10 @@ static int layer_backward_impl(egnn_ctx* ctx, const egnn_graph* g, const int32_t
   if ((rc = egnn_launch_mix_wgrad(ctx, dx_out, x_in, dW_self, b.wgrad_partial, n_o, st))) return rc;
   tm.mark(1);
   // messages
-  if ((rc = egnn_launch_tp_backward(ctx, g, col_ptr, perm, b.rhat_d, b.h, w, b.da, b.dh, b.dw, st))) return rc;
+  // (the largest |dw|, kept by the kernel that writes dw, scales the contractions that read it)
+  unsigned* dw_max = egnn_radial_backward_dw_max(b.radial);
+  if ((rc = egnn_launch_fill_int(ctx, (int*)dw_max, 64, 0, st))) return rc;
+  if ((rc = egnn_launch_tp_backward(ctx, g, col_ptr, perm, b.rhat_d, b.h, w, b.da, b.dh, b.dw, dw_max, st))) return rc;
   tm.mark(2);
   // h = W_pre x_in ; owned rows also receive the self term
   if ((rc = egnn_launch_node_mix(ctx, b.dh, W_pre, dx_out, W_self, dx_in, n_o, st, 1))) return rc;
@@ -153,7 +156,7 @@ static int layer_backward_impl(egnn_ctx* ctx, const egnn_graph* g, const int32_t
   if ((rc = egnn_launch_mix_wgrad(ctx, b.dh, x_in, dW_pre, b.wgrad_partial, n_t, st))) return rc;
   tm.mark(3);
   // radial MLP
-  rc = egnn_launch_radial_backward(ctx, 0, b.rhat_d, g->n_edges, W_r1, W_r2, b.dw, dW_r1, dW_r2, b.radial, st);
+  rc = egnn_launch_radial_backward(ctx, 0, b.rhat_d, g->n_edges, W_r1, W_r2, b.dw, dW_r1, dW_r2, b.radial, true, st);
   tm.mark(4);
   return rc;
 }
@@ -253,7 +256,7 @@ static int readout_backward_impl(egnn_ctx* ctx, const egnn_graph* g, const int32
   if ((rc = egnn_launch_mix_wgrad(ctx, b.dzs, x, dW_s, b.wgrad_partial, n_t, st))) return rc;
   if ((rc = egnn_launch_mix_wgrad(ctx, b.dzt, x, dW_t, b.wgrad_partial, n_t, st))) return rc;
   tm.mark(2);
-  rc = egnn_launch_radial_backward(ctx, 1, b.rhat_d, g->n_edges, W_r1, W_r2, b.dw, dW_r1, dW_r2, b.radial, st);
+  rc = egnn_launch_radial_backward(ctx, 1, b.rhat_d, g->n_edges, W_r1, W_r2, b.dw, dW_r1, dW_r2, b.radial, false, st);   // (no running maximum of this dw: bf16 pieces)
   tm.mark(3);
   tm.mark(4);
   return rc;

@@ -61,6 +61,16 @@ struct PathAlpha { float a[EGNN_MAX_PATHS]; };
 int egnn_fail(egnn_ctx* ctx, int code, const std::string& msg);
 int egnn_check_hip(egnn_ctx* ctx, hipError_t e, const char* what);
 
+// A running maximum of non-negative floats kept in a word of device memory as a bit pattern (such floats order like
+// their bit patterns): the atomic is issued only when it would raise the value -- atomics on one address run one
+// after the other, and after the first few thousand wavefronts almost none is needed.
+#ifdef __HIPCC__
+__device__ __forceinline__ void egnn_raise_max(unsigned* target, float v) {
+  const unsigned bits = __float_as_uint(v);
+  if (bits > __atomic_load_n(target, __ATOMIC_RELAXED)) atomicMax(target, bits);
+}
+#endif
+
 #define EGNN_HIP(ctx, call)                                              \
   do {                                                                   \
     hipError_t e__ = (call);                                             \
@@ -86,12 +96,17 @@ int egnn_launch_segsum_rows(egnn_ctx*, const float* rows, const int* ptr, const 
 int egnn_launch_reduce_partials(egnn_ctx*, float* partial /* scratch, may be overwritten */, int n_partials, long n, float* out, float scale,
                                 hipStream_t);
 size_t egnn_transpose_ws_bytes(int64_t n_edges, int32_t n_total);
+// dw_max (may be NULL): a word the caller has set to zero; raised to the bit pattern of the largest |dw| written
 int egnn_launch_tp_backward(egnn_ctx*, const egnn_graph*, const int* col_ptr, const int* perm, const float* rhat_d,
-                            const float* h, const float* w, const float* da, float* dh, float* dw, hipStream_t);
+                            const float* h, const float* w, const float* da, float* dh, float* dw, unsigned* dw_max,
+                            hipStream_t);
 size_t egnn_radial_backward_ws_bytes(const egnn_ctx*, int which, int64_t n_edges);
+// dw_max_valid: the first word of ws (egnn_radial_backward_dw_max) holds the bit pattern of the largest |dw|; the
+// two large contractions then run on half-precision pieces, otherwise on bf16 pieces (which need no scaling)
 int egnn_launch_radial_backward(egnn_ctx*, int which, const float* rhat_d, int64_t n_edges, const float* W_r1,
                                 const float* W_r2, const float* dw, float* dW_r1, float* dW_r2, void* ws,
-                                hipStream_t);
+                                bool dw_max_valid, hipStream_t);
+static inline unsigned* egnn_radial_backward_dw_max(void* ws) { return reinterpret_cast<unsigned*>(ws); }
 size_t egnn_readout_backward_partial_bytes(const egnn_ctx*, int64_t n_edges);
 size_t egnn_readout_backward_lds_bytes(const egnn_ctx*);
 int egnn_launch_readout_backward(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* zs, const float* zt,

@@ -99,6 +99,61 @@ __global__ __launch_bounds__(256) void rb_split_transpose_kernel(const float* __
   }
 }
 
+// The same for the half-precision form of the contractions: src[r][64] times scale[0] (a power of two kept in device
+// memory) -> T[r / 64][j][piece][r % 64] halves, two pieces (stream_gemm.h).
+__global__ __launch_bounds__(256) void rb_split_transpose_half_kernel(const float* __restrict__ src, long n_rows,
+                                                                      uint16_t* __restrict__ T, int log2E, PathAlpha alpha,
+                                                                      int alpha_on, const float* __restrict__ scale) {
+  __shared__ float tile[64][65];
+  const long r0 = (long)blockIdx.x * 64;
+  const float sc = scale[0];
+  for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+    const int rr = i >> 6, j = i & 63;
+    const long r = r0 + rr;
+    tile[rr][j] = r < n_rows ? src[r * EGNN_HIDDEN + j] * (alpha_on ? alpha.a[r >> log2E] : 1.0f) : 0.0f;
+  }
+  __syncthreads();
+  uint32_t* out = reinterpret_cast<uint32_t*>(T) + (size_t)blockIdx.x * 64 * 64;
+  for (int i = threadIdx.x; i < 64 * 32; i += 256) {
+    const int j = i >> 5, rp = i & 31;
+    const float xv[8] = {tile[2 * rp][j], tile[2 * rp + 1][j], 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+    uint4 hi, lo;
+    sgh_split8(xv, sc, hi, lo);
+    uint32_t* o = out + j * 64 + rp;
+    o[0] = hi.x;
+    o[32] = lo.x;
+  }
+}
+
+// dpre on half-precision pieces: W2T = packed (alpha W_r2 s_w), scales = {s_w, s_g, .}, dw_max = bit pattern of the
+// largest |dw|
+__global__ __launch_bounds__(SG_THREADS) void radial_dpre_half_kernel(const float* __restrict__ dw, long n_edges,
+                                                                      const uint16_t* __restrict__ W2T,
+                                                                      float* __restrict__ S, int PE, int n_steps,
+                                                                      const float* __restrict__ scales,
+                                                                      const unsigned* __restrict__ dw_max) {
+  extern __shared__ uint4 rb_smem[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int m = lane & 31, hh = lane >> 5;
+  const long e_base = ((long)blockIdx.x * SG_WAVES + wave) * 64;
+  const int ea = sgh_scale_exp(*dw_max);
+  const float a_scale = ldexpf(1.0f, ea), unscale = ldexpf(1.0f, -ea) / scales[0];
+  float16v acc[2][2];
+  sgh_contract(dw, n_edges, PE, reinterpret_cast<const uint4*>(W2T), n_steps, rb_smem, e_base, a_scale, acc);
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const long e = e_base + rb * 32 + 8 * (i >> 2) + 4 * hh + (i & 3);
+        if (e < n_edges) {
+          const size_t at = (size_t)e * EGNN_HIDDEN + cb * 32 + m;
+          S[at] = S[at] * (unscale * acc[rb][cb][i]);
+        }
+      }
+}
+
 // dpre[k][j] = S[k][j] * sum_n dw[k][n] alpha_n W_r2[n][j]  (in place over S).  W2T = T of (alpha W_r2), contraction
 // index n; the contraction is sg_contract of stream_gemm.h (rows = edges, one 64-column tile = the 64 hidden units).
 __global__ __launch_bounds__(SG_THREADS) void radial_dpre_kernel(const float* __restrict__ dw, long n_edges,
@@ -127,11 +182,16 @@ __global__ __launch_bounds__(SG_THREADS) void radial_dpre_kernel(const float* __
 // Partial dW_r2 over one chunk of RB_KCHUNK edges: partial[chunk][n][j] = alpha_n sum_{k in chunk} dw[k][n] G[k][j].
 // GT = T of G, contraction index k.  grid = (tiles of 32 * RB_WAVES rows n, edge chunks); a compute wave owns 32 rows n
 // and all 64 units; MFMA step t of a 64-edge step contracts k = 64 s + 32 hh + 8 t .. + 7.
+// HALF: GT holds two half-precision pieces of G s_g (scales[1] = s_g), dw is scaled by the power of two that dw_max
+// gives before it is cut into two pieces, three products per fp32 product.
+template <bool HALF>
 __global__ __launch_bounds__(RB_THREADS) void radial_dw2_kernel(const float* __restrict__ dw, long n_edges,
                                                                 const uint16_t* __restrict__ GT,
                                                                 float* __restrict__ partial, int PE, int log2E,
-                                                                PathAlpha alpha) {
-  __shared__ uint4 sB[2 * 64 * RB_BROW4];
+                                                                PathAlpha alpha, const float* __restrict__ scales,
+                                                                const unsigned* __restrict__ dw_max) {
+  constexpr int BROW4 = HALF ? SGH_BROW4 : RB_BROW4;
+  __shared__ uint4 sB[2 * 64 * BROW4];
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   // blockIdx.x = tile of rows n (fastest: the workgroups that read the other columns of the same edges run at the
@@ -141,8 +201,15 @@ __global__ __launch_bounds__(RB_THREADS) void radial_dw2_kernel(const float* __r
   if (k_end > n_edges) k_end = n_edges;
   const int n_steps = (int)((k_end - k_begin + 63) / 64);
   if (wave == RB_WAVES) {
-    rb_loader(GT, k_begin / 64, n_steps, sB, lane);
+    if constexpr (HALF) rbh_loader(GT, k_begin / 64, n_steps, sB, lane);
+    else rb_loader(GT, k_begin / 64, n_steps, sB, lane);
     return;
+  }
+  float a_scale = 1.0f, unscale = 1.0f;
+  if constexpr (HALF) {
+    const int ea = sgh_scale_exp(*dw_max);
+    a_scale = ldexpf(1.0f, ea);
+    unscale = ldexpf(1.0f, -ea) / scales[1];
   }
   const int m = lane & 31, hh = lane >> 5;
   const int n_tile = (blockIdx.x * RB_WAVES + wave) * 32;
@@ -186,20 +253,31 @@ __global__ __launch_bounds__(RB_THREADS) void radial_dw2_kernel(const float* __r
   for (int s = 0; s < n_steps; ++s) {
     const int s_next = s + 1 < n_steps ? s + 1 : s;          // (the last step fetches itself again: no branch)
     rb_barrier_acquire();
-    const uint4* bbase = sB + (s & 1) * (64 * RB_BROW4) + hh * 4;
+    const uint4* bbase = sB + (s & 1) * (64 * BROW4) + hh * 4;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       float x[8];
 #pragma unroll
       for (int q = 0; q < 8; ++q) x[q] = nxt[8 * t + q];
-      uint4 ah, am, al;
-      rb_split8(x, ah, am, al);
-      fetch8(s_next, t);
-      const uint4* brow0 = bbase + m * RB_BROW4 + t;
-      const uint4* brow1 = brow0 + 32 * RB_BROW4;
-      const uint4 b0[3] = {brow0[0], brow0[8], brow0[16]};
-      const uint4 b1[3] = {brow1[0], brow1[8], brow1[16]};
-      rb_mma6x2(ah, am, al, b0, b1, acc[0], acc[1]);
+      if constexpr (HALF) {
+        uint4 ah, al;
+        sgh_split8(x, a_scale, ah, al);
+        fetch8(s_next, t);
+        const uint4* brow0 = bbase + m * BROW4 + t;
+        const uint4* brow1 = brow0 + 32 * BROW4;
+        const uint4 b0[2] = {brow0[0], brow0[8]};
+        const uint4 b1[2] = {brow1[0], brow1[8]};
+        sgh_mma3x2(ah, al, b0, b1, acc[0], acc[1]);
+      } else {
+        uint4 ah, am, al;
+        rb_split8(x, ah, am, al);
+        fetch8(s_next, t);
+        const uint4* brow0 = bbase + m * BROW4 + t;
+        const uint4* brow1 = brow0 + 32 * BROW4;
+        const uint4 b0[3] = {brow0[0], brow0[8], brow0[16]};
+        const uint4 b1[3] = {brow1[0], brow1[8], brow1[16]};
+        rb_mma6x2(ah, am, al, b0, b1, acc[0], acc[1]);
+      }
     }
   }
   float* out = partial + (size_t)blockIdx.y * PE * EGNN_HIDDEN;
@@ -207,7 +285,7 @@ __global__ __launch_bounds__(RB_THREADS) void radial_dw2_kernel(const float* __r
   for (int i = 0; i < 16; ++i) {
     const int n = n_tile + 8 * (i >> 2) + 4 * hh + (i & 3);
     if (n < PE) {
-      const float al = alpha.a[n >> log2E];
+      const float al = alpha.a[n >> log2E] * unscale;
       out[(size_t)n * EGNN_HIDDEN + m] = al * acc[0][i];
       out[(size_t)n * EGNN_HIDDEN + 32 + m] = al * acc[1][i];
     }
@@ -275,14 +353,15 @@ static size_t rb_pad64(size_t n) { return (n + 63) & ~(size_t)63; }
 size_t egnn_radial_backward_ws_bytes(const egnn_ctx* ctx, int which, int64_t n_edges) {
   const size_t PE = (size_t)ctx->n_paths[which] * ctx->desc.channels;
   const size_t kc = (size_t)((n_edges + RB_KCHUNK - 1) / RB_KCHUNK), rc = (size_t)((n_edges + RB_R1CHUNK - 1) / RB_R1CHUNK);
-  return 2 * a256((size_t)n_edges * EGNN_HIDDEN * 4) + a256(kc * PE * EGNN_HIDDEN * 4) +
+  // (the first 512 bytes: the running maximum of |dw| and the scalings of the half-precision form)
+  return 512 + 2 * a256((size_t)n_edges * EGNN_HIDDEN * 4) + a256(kc * PE * EGNN_HIDDEN * 4) +
          a256(rc * EGNN_HIDDEN * ctx->desc.n_rbf * 4) + a256(rb_pad64(PE) * EGNN_HIDDEN * 6) +
          a256(rb_pad64(n_edges) * EGNN_HIDDEN * 6);
 }
 
 int egnn_launch_radial_backward(egnn_ctx* ctx, int which, const float* rhat_d, int64_t n_edges, const float* W_r1,
                                 const float* W_r2, const float* dw, float* dW_r1, float* dW_r2, void* ws,
-                                hipStream_t st) {
+                                bool dw_max_valid, hipStream_t st) {
   const int P = ctx->n_paths[which];
   const int PE = P * ctx->desc.channels, n_rbf = ctx->desc.n_rbf;
   int rc;
@@ -293,7 +372,10 @@ int egnn_launch_radial_backward(egnn_ctx* ctx, int which, const float* rhat_d, i
   PathAlpha al;
   for (int p = 0; p < EGNN_MAX_PATHS; ++p) al.a[p] = p < P ? ctx->alpha[which][p] : 0.0f;
   const int kc = (int)((n_edges + RB_KCHUNK - 1) / RB_KCHUNK), r1c = (int)((n_edges + RB_R1CHUNK - 1) / RB_R1CHUNK);
-  char* base = (char*)ws;
+  const unsigned* dw_max = egnn_radial_backward_dw_max(ws);
+  float* scales = (float*)((char*)ws + 256);
+  const bool half = dw_max_valid;
+  char* base = (char*)ws + 512;
   float* G = (float*)base;
   float* S = (float*)(base + a256((size_t)n_edges * EGNN_HIDDEN * 4));
   float* part2 = (float*)(base + 2 * a256((size_t)n_edges * EGNN_HIDDEN * 4));
@@ -313,27 +395,48 @@ int egnn_launch_radial_backward(egnn_ctx* ctx, int which, const float* rhat_d, i
   RB_BY_NB8(radial_hidden_kernel, dim3((unsigned)((n_edges + RH_EDGES - 1) / RH_EDGES)), rd, (long)n_edges, W_r1, G, S,
             n_rbf, ctx->desc.r_cut);
   EGNN_LAUNCH_CHECK(ctx, "radial_hidden_kernel");
-  hipLaunchKernelGGL(rb_split_transpose_kernel, dim3((unsigned)(ne_pad / 64)), dim3(256), 0, st, G, (long)n_edges, GT, 0,
-                     al, 0);
-  EGNN_LAUNCH_CHECK(ctx, "rb_split_transpose_kernel(G)");
-  hipLaunchKernelGGL(rb_split_transpose_kernel, dim3((unsigned)(pe_pad / 64)), dim3(256), 0, st, W_r2, (long)PE, W2T,
-                     ctx->log2_channels, al, 1);
-  EGNN_LAUNCH_CHECK(ctx, "rb_split_transpose_kernel(W_r2)");
   const int n_tile = 32 * RB_WAVES;
-  hipLaunchKernelGGL(radial_dw2_kernel, dim3((PE + n_tile - 1) / n_tile, kc), dim3(RB_THREADS), 0, st, dw, (long)n_edges, GT,
-                     part2, PE, ctx->log2_channels, al);
-  EGNN_LAUNCH_CHECK(ctx, "radial_dw2_kernel");
-  if ((rc = egnn_launch_reduce_partials(ctx, part2, kc, (long)PE * EGNN_HIDDEN, dW_r2, 1.0f, st))) return rc;
   const long per_wg = 64L * SG_WAVES;
-  const size_t dpre_lds = SG_LDS_BYTES;
-  {
+  const dim3 dw2_grid((PE + n_tile - 1) / n_tile, kc), dpre_grid((unsigned)((n_edges + per_wg - 1) / per_wg));
+  if (half) {
+    // two half-precision pieces per operand, three products: G and alpha W_r2 are scaled by the powers of two that
+    // egnn_launch_half_scales derives from the weights, dw by the one its running maximum gives
+    if ((rc = egnn_launch_half_scales(ctx, which, W_r1, W_r2, scales, st))) return rc;
+    hipLaunchKernelGGL(rb_split_transpose_half_kernel, dim3((unsigned)(ne_pad / 64)), dim3(256), 0, st, G, (long)n_edges,
+                       GT, 0, al, 0, scales + 1);
+    EGNN_LAUNCH_CHECK(ctx, "rb_split_transpose_half_kernel(G)");
+    hipLaunchKernelGGL(rb_split_transpose_half_kernel, dim3((unsigned)(pe_pad / 64)), dim3(256), 0, st, W_r2, (long)PE,
+                       W2T, ctx->log2_channels, al, 1, scales);
+    EGNN_LAUNCH_CHECK(ctx, "rb_split_transpose_half_kernel(W_r2)");
+    hipLaunchKernelGGL(radial_dw2_kernel<true>, dw2_grid, dim3(RB_THREADS), 0, st, dw, (long)n_edges, GT, part2, PE,
+                       ctx->log2_channels, al, scales, dw_max);
+    EGNN_LAUNCH_CHECK(ctx, "radial_dw2_kernel");
+    if ((rc = egnn_launch_reduce_partials(ctx, part2, kc, (long)PE * EGNN_HIDDEN, dW_r2, 1.0f, st))) return rc;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(radial_dpre_half_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)SGH_LDS_BYTES);
+    if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(radial_dpre_half_kernel)");
+    hipLaunchKernelGGL(radial_dpre_half_kernel, dpre_grid, dim3(SG_THREADS), SGH_LDS_BYTES, st, dw, (long)n_edges, W2T, S,
+                       PE, (int)(pe_pad / 64), scales, dw_max);
+    EGNN_LAUNCH_CHECK(ctx, "radial_dpre_half_kernel");
+  } else {
+    hipLaunchKernelGGL(rb_split_transpose_kernel, dim3((unsigned)(ne_pad / 64)), dim3(256), 0, st, G, (long)n_edges, GT, 0,
+                       al, 0);
+    EGNN_LAUNCH_CHECK(ctx, "rb_split_transpose_kernel(G)");
+    hipLaunchKernelGGL(rb_split_transpose_kernel, dim3((unsigned)(pe_pad / 64)), dim3(256), 0, st, W_r2, (long)PE, W2T,
+                       ctx->log2_channels, al, 1);
+    EGNN_LAUNCH_CHECK(ctx, "rb_split_transpose_kernel(W_r2)");
+    hipLaunchKernelGGL(radial_dw2_kernel<false>, dw2_grid, dim3(RB_THREADS), 0, st, dw, (long)n_edges, GT, part2, PE,
+                       ctx->log2_channels, al, scales, dw_max);
+    EGNN_LAUNCH_CHECK(ctx, "radial_dw2_kernel");
+    if ((rc = egnn_launch_reduce_partials(ctx, part2, kc, (long)PE * EGNN_HIDDEN, dW_r2, 1.0f, st))) return rc;
+    const size_t dpre_lds = SG_LDS_BYTES;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(radial_dpre_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)dpre_lds);
     if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(radial_dpre_kernel)");
+    hipLaunchKernelGGL(radial_dpre_kernel, dpre_grid, dim3(SG_THREADS), dpre_lds, st, dw, (long)n_edges, W2T, S, PE,
+                       (int)(pe_pad / 64));
+    EGNN_LAUNCH_CHECK(ctx, "radial_dpre_kernel");
   }
-  hipLaunchKernelGGL(radial_dpre_kernel, dim3((unsigned)((n_edges + per_wg - 1) / per_wg)), dim3(SG_THREADS), dpre_lds, st,
-                     dw, (long)n_edges, W2T, S, PE, (int)(pe_pad / 64));
-  EGNN_LAUNCH_CHECK(ctx, "radial_dpre_kernel");
   RB_BY_NB8(radial_dw1_kernel, dim3((r1c + 3) / 4), rd, (long)n_edges, S, part1, n_rbf, ctx->desc.r_cut);
 #undef RB_BY_NB8
   EGNN_LAUNCH_CHECK(ctx, "radial_dw1_kernel");

@@ -264,6 +264,23 @@ __device__ __forceinline__ void sgh_row_block(float* sA, const uint4* bbase, sg_
   __builtin_amdgcn_wave_barrier();   // reads of the tile are done before the next block overwrites it
 }
 
+// the loader wave of a kernel that keeps one (see rb_loader): block `step` of T (64 rows of 16 uint4) -> sB[step & 1]
+__device__ __forceinline__ void rbh_loader(const uint16_t* __restrict__ T, long first_step, int n_steps, uint4* sB, int lane) {
+  const uint4* src = reinterpret_cast<const uint4*>(T) + first_step * (64 * 16);
+  for (int s = 0; s < n_steps; ++s) {
+    uint4 v[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = src[(size_t)s * (64 * 16) + i * 64 + lane];
+    uint4* dst = sB + (s & 1) * (64 * SGH_BROW4);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int u = i * 64 + lane, row = u >> 4, c16 = u & 15;
+      dst[row * SGH_BROW4 + c16] = v[i];
+    }
+    rb_release_barrier();
+  }
+}
+
 // as sg_contract; tsrc: n_steps blocks of 64 x 16 uint4; the accumulators hold a_scale * (scale of the packed operand)
 // times the result
 __device__ __forceinline__ void sgh_contract(const float* __restrict__ A, long M, int K, const uint4* __restrict__ tsrc,

@@ -18,13 +18,16 @@ template <int LMAX, int L1>
 struct TpBwdDegree {
   using Mid = typename LayerMid<LMAX>::T;
   __device__ __forceinline__ static void run(const float* v, const float* go, float* gv, const float* wr,
-                                             float* __restrict__ dwp, int log2E) {
+                                             float* __restrict__ dwp, int log2E, float& mx) {
     constexpr int first = Mid::CHUNK_FIRST[L1], count = Mid::CHUNK_COUNT[L1];
     float gw[count];
     Mid::template run_bwd_l1<L1>(v + L1 * L1, wr + first, go, gv + L1 * L1, gw);
 #pragma unroll
-    for (int p = 0; p < count; ++p) __builtin_nontemporal_store(gw[p], dwp + ((size_t)(first + p) << log2E));
-    if constexpr (L1 < LMAX) TpBwdDegree<LMAX, L1 + 1>::run(v, go, gv, wr, dwp, log2E);
+    for (int p = 0; p < count; ++p) {
+      __builtin_nontemporal_store(gw[p], dwp + ((size_t)(first + p) << log2E));
+      mx = fmaxf(mx, fabsf(gw[p]));
+    }
+    if constexpr (L1 < LMAX) TpBwdDegree<LMAX, L1 + 1>::run(v, go, gv, wr, dwp, log2E, mx);
   }
 };
 
@@ -35,8 +38,8 @@ __global__ __launch_bounds__(256, 2) void tp_backward_kernel(const int* __restri
                                                              const float4* __restrict__ rhat_d,
                                                              const float* __restrict__ h, const float* __restrict__ w,
                                                              const float* __restrict__ da, float* __restrict__ dh,
-                                                             float* __restrict__ dw, int n_total,
-                                                             int nodes_per_xcd, float scale) {
+                                                             float* __restrict__ dw, unsigned* __restrict__ dw_max,
+                                                             int n_total, int nodes_per_xcd, float scale) {
   constexpr int log2E = LE;
   using Mid = typename LayerMid<LMAX>::T;
   constexpr int D = (LMAX + 1) * (LMAX + 1);
@@ -53,6 +56,7 @@ __global__ __launch_bounds__(256, 2) void tp_backward_kernel(const int* __restri
   const int c0 = col_ptr[i], c1 = col_ptr[i + 1];
 
   float v0[D], acc[D];
+  float mx = 0.0f;      // largest |dw| this thread writes (scaling of the contractions that read dw)
   const float* hp = h + ((size_t)i * D << log2E) + c;
 #pragma unroll
   for (int q = 0; q < D; ++q) {
@@ -79,12 +83,17 @@ __global__ __launch_bounds__(256, 2) void tp_backward_kernel(const int* __restri
     egnn_bond_trig<LMAX>(g.x, g.y, g.z, t);
     egnn_to_bond_frame<LMAX>(v, t);
     egnn_to_bond_frame<LMAX>(go, t);
-    TpBwdDegree<LMAX, 0>::run(v, go, gv, wr, dwp, log2E);
+    TpBwdDegree<LMAX, 0>::run(v, go, gv, wr, dwp, log2E, mx);
     egnn_from_bond_frame<LMAX>(gv, t);
 #pragma unroll
     for (int q = 0; q < D; ++q) acc[q] += gv[q];
   }
 
+  if (dw_max) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+    if ((tid & 63) == 0) egnn_raise_max(dw_max, mx);
+  }
 #pragma unroll
   for (int q = 0; q < D; ++q) red[((slot * D + q) << log2E) + c] = acc[q];
   __syncthreads();
@@ -99,7 +108,7 @@ __global__ __launch_bounds__(256, 2) void tp_backward_kernel(const int* __restri
 
 int egnn_launch_tp_backward(egnn_ctx* ctx, const egnn_graph* g, const int* col_ptr, const int* perm,
                             const float* rhat_d, const float* h, const float* w, const float* da, float* dh,
-                            float* dw, hipStream_t stream) {
+                            float* dw, unsigned* dw_max, hipStream_t stream) {
   const int n = g->n_total;
   if (n == 0) return EGNN_OK;
   const int per_xcd = (n + 7) / 8;
@@ -108,7 +117,7 @@ int egnn_launch_tp_backward(egnn_ctx* ctx, const egnn_graph* g, const int* col_p
   const float4* rd = reinterpret_cast<const float4*>(rhat_d);
 #define LAUNCH(L, LE_)                                                                                          \
   hipLaunchKernelGGL((tp_backward_kernel<L, LE_>), grid, block, 0, stream, col_ptr, perm, g->dst, rd, h, w, da, dh, \
-                     dw, n, per_xcd, scale)
+                     dw, dw_max, n, per_xcd, scale)
 #define CASES(L)                                                                        \
   switch (ctx->log2_channels) {                                                         \
     case 3: LAUNCH(L, 3); break;                                                        \

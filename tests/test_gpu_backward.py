@@ -85,6 +85,26 @@ def test_layer_backward(B, lmax, E, n, n_owned, periodic):
     assert all(np.array_equal(grads[k].cpu().numpy(), grads2[k].cpu().numpy()) for k in grads)
 
 
+@pytest.mark.parametrize("dy_scale,w_scale", [(1e-14, 1.0), (1e11, 1e-5), (3e-7, 2e4)])
+def test_layer_backward_gradient_scales(B, dy_scale, w_scale):
+    """The contractions that read dw cut it into half-precision pieces after a scaling taken from the largest |dw|
+    (kept by the kernel that writes it): tiny and huge gradients keep the accuracy."""
+    lmax, E, n = 3, 16, 80
+    w, g, agg, m, pos, graph, ws, col_ptr, perm = _setup(B, lmax, E, n, n, False, 91)
+    rng = np.random.default_rng(5)
+    W = synth.layer_weights(rng, lmax, E, w.n_rbf, 64, m.n_paths)
+    W["W_r2"] = (W["W_r2"] * np.float32(w_scale)).astype(np.float32)
+    x = synth.node_features(rng, n, lmax, E)
+    dy = (synth.node_features(rng, n, lmax, E) * np.float32(dy_scale)).astype(np.float32)
+    dx, grads = m.egnn_layer_backward(graph, col_ptr, perm, pos, w.box, B.to_device(x), B.to_device(W),
+                                      B.to_device(dy), ws)
+    dx_ref, g_ref = O.layer_backward(g, w.pos, w.box, x, W, lmax, lmax, E, w.n_rbf, w.r_cut, agg, dy.astype(np.float64))
+    errs = {"dx": U.rel_err(dx.cpu().numpy(), dx_ref)}
+    errs.update({k: U.rel_err(grads[k].cpu().numpy(), g_ref[k]) for k in g_ref})
+    print(errs, flush=True)
+    assert all(e < 1e-5 for e in errs.values()), errs
+
+
 @pytest.mark.parametrize("n_rbf", [2, 9, 20, 32])
 def test_layer_backward_basis_counts(B, n_rbf):
     """The reverse pass of the radial MLP pads the number of radial bases to a multiple of 8 at compile time."""
