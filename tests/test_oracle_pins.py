@@ -469,3 +469,33 @@ def test_half_precision_weight_mode_rounds_only_the_weights():
     w_edge = O.radial_weights(dd, W["W_r1"], W["W_r2"], paths, E, n_rbf, r_cut).astype(np.float16).astype(np.float64)
     y_explicit = O.layer_forward(g, cl.pos, cl.box, x, W, lmax, lmax, E, n_rbf, r_cut, 5.0, w_edge=w_edge)
     assert np.array_equal(y_mode, y_explicit)
+
+
+def test_radial_weights_are_shared_by_an_edge_and_its_reverse():
+    # w_k depends on the edge only through its length (radial basis and envelope act on d_k), and between two owned
+    # atoms every edge has its reverse with the opposite image shift: both rows of w are equal.  Edges from halo
+    # atoms have no reverse in the list (destinations are owned atoms only).
+    wl = synth.small_cluster(60, 44, 2, 4, 8, r_cut=3.5, seed=5, periodic=True)
+    src, dst, shift, row_ptr = O.neighbour_list(wl.pos, wl.n_owned, wl.box, wl.pbc, wl.r_cut)
+    index = {(int(i), int(j), tuple(int(s) for s in sh)): k for k, (i, j, sh) in enumerate(zip(src, dst, shift))}
+    d = np.linalg.norm(O.edge_vectors(wl.pos, wl.box, src, dst, shift), axis=1)
+    paths = O.tp_paths(2, 2, 2)
+    rng = np.random.default_rng(7)
+    W_r1 = rng.standard_normal((64, 8))
+    W_r2 = rng.standard_normal((len(paths) * 4, 64)) / 8.0
+    w = O.radial_weights(d, W_r1, W_r2, paths, 4, 8, wl.r_cut)
+    n_pairs = n_halo_edges = 0
+    for (i, j, sh), k in index.items():
+        if i >= wl.n_owned:
+            n_halo_edges += 1
+            assert (j, i, tuple(-s for s in sh)) not in index
+            continue
+        kr = index[(j, i, tuple(-s for s in sh))]            # KeyError = a missing reverse
+        assert abs(d[k] - d[kr]) <= 4e-16 * d[k]
+        np.testing.assert_allclose(w[k], w[kr], rtol=1e-12, atol=1e-15)
+        n_pairs += 1
+    assert n_pairs > 200 and n_halo_edges > 20 and n_pairs % 2 == 0
+    # sorted by source inside a row, each source once: the reverse of an edge is found by a search for src = j in row i
+    for j in range(wl.n_owned):
+        row = src[row_ptr[j]:row_ptr[j + 1]]
+        assert np.all(np.diff(row) > 0)
