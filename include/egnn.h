@@ -69,6 +69,10 @@ typedef struct {
   const int8_t* shift;    /* [n_edges][3], periodic image of the source; may be NULL (all zero) */
   int64_t n_edges;
   int32_t n_owned, n_total;
+  /* Optional, from egnn_edge_pairs (NULL / 0: every edge has its own row of radial weights): */
+  const int32_t* w_row;   /* [n_edges] row of radial weights edge k reads: w_row[k] if >= 0 (the edge owns the row),
+                             ~w_row[k] (bitwise complement) if negative (the row belongs to the reverse edge) */
+  int64_t n_w_rows;       /* number of rows */
 } egnn_graph;
 
 int egnn_create(const egnn_model_desc* desc, egnn_ctx** out);
@@ -96,7 +100,9 @@ int egnn_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, 
  * box, pbc: host arrays of 3.  EGNN_EBOX if a periodic edge is shorter than 2*r_cut.
  * ws: with a workspace of egnn_nlist_workspace_bytes (256-byte aligned) and at most 262,144 atoms the search
  * goes through a cell list (cells of edge >= r_cut, at most 64 per axis); count builds the cells, fill reuses
- * them, so fill must follow count with the same atoms and the same, untouched workspace.  With ws == NULL
+ * them, so fill must follow count with the same atoms and the same, untouched workspace (a different pos or ws
+ * pointer is rejected with EGNN_EINVAL; a workspace overwritten in between gives a wrong list but no access outside
+ * the buffers).  With ws == NULL
  * every destination sweeps all atoms (O(n_owned * n_total), fine for a few thousand atoms).  Both give the
  * same edge list.  count synchronises the stream (twice with a workspace: bounding box, edge count). */
 int egnn_nlist_workspace_bytes(const egnn_ctx* ctx, int32_t n_total, size_t* bytes);
@@ -106,6 +112,22 @@ int egnn_nlist_count(egnn_ctx* ctx, const float* pos, int32_t n_owned, int32_t n
 int egnn_nlist_fill(egnn_ctx* ctx, const float* pos, int32_t n_owned, int32_t n_total,
                     const float box[3], const uint8_t pbc[3], const int32_t* row_ptr, int64_t n_edges,
                     int32_t* src, int32_t* dst, int8_t* shift /* may be NULL */, void* ws, size_t ws_bytes,
+                    void* stream);
+
+/* ---- shared rows of radial weights (Sec. 3 "Initialization": an edge enters the message transform through the
+ *      Gaussian expansion of its length, so an edge and its reverse have the same radial weights) ----
+ * Gives every edge the row of the weight tensor it reads, one row per unordered pair of owned atoms: edge k = (i -> j)
+ * owns a row if i is a halo atom (its reverse is not in the list), if i < j, or if the list holds no reverse (j -> i)
+ * with the opposite image shift; otherwise it reads the row of its reverse.  Rows are numbered in ascending order of
+ * the owning edges' ids.  w_row [n_edges] in the encoding of egnn_graph.w_row; n_rows (host) the number of rows.
+ * A graph with w_row / n_w_rows set makes egnn_layer_forward, egnn_readout_hij, their _save forms and the reverse
+ * pass evaluate and store one row of radial weights per row index instead of one per edge (w_save then has n_w_rows
+ * rows); results are the same numbers as without (the two lengths are bit-identical).  Caller-supplied w_edge and the
+ * stage calls egnn_radial_weights / egnn_tp_segsum stay per edge unless stated.  Needs the list sorted by (dst, src)
+ * with at most one edge per ordered pair (what egnn_nlist_fill produces).  Synchronises the stream (row count).
+ * ws: egnn_edge_pairs_workspace_bytes, 256-byte aligned. */
+int egnn_edge_pairs_workspace_bytes(const egnn_ctx* ctx, int32_t n_owned, size_t* bytes);
+int egnn_edge_pairs(egnn_ctx* ctx, const egnn_graph* g, int32_t* w_row, int64_t* n_rows, void* ws, size_t ws_bytes,
                     void* stream);
 
 /* ---- node initialisation (Sec. 3: the L=0 plane carries the atomic species) ----

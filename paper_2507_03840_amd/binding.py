@@ -26,6 +26,7 @@ SYMBOLS = [
     "egnn_hamiltonian_structure", "egnn_hamiltonian_fill", "egnn_onsite_backward_workspace_bytes", "egnn_onsite_backward",
     "egnn_partition_low_nn", "egnn_pack_rows", "egnn_unpack_rows",
     "egnn_layer_forward_save", "egnn_readout_hij_save", "egnn_layer_backward_saved", "egnn_readout_backward_saved",
+    "egnn_edge_pairs_workspace_bytes", "egnn_edge_pairs",
 ]
 
 
@@ -38,7 +39,8 @@ class ModelDesc(C.Structure):
 
 class GraphDesc(C.Structure):
     _fields_ = [("src", C.c_void_p), ("dst", C.c_void_p), ("row_ptr", C.c_void_p), ("shift", C.c_void_p),
-                ("n_edges", C.c_int64), ("n_owned", C.c_int32), ("n_total", C.c_int32)]
+                ("n_edges", C.c_int64), ("n_owned", C.c_int32), ("n_total", C.c_int32),
+                ("w_row", C.c_void_p), ("n_w_rows", C.c_int64)]
 
 
 class EgnnError(RuntimeError):
@@ -86,11 +88,22 @@ class Graph:
     def __init__(self, src, dst, row_ptr, shift, n_owned, n_total):
         self.src, self.dst, self.row_ptr, self.shift = src, dst, row_ptr, shift
         self.n_edges, self.n_owned, self.n_total = int(src.numel()), int(n_owned), int(n_total)
+        self.w_row, self.n_w_rows = None, 0      # set by Egnn.egnn_edge_pairs: shared rows of radial weights
 
     def desc(self):
         return GraphDesc(_ptr(self.src).value, _ptr(self.dst).value, _ptr(self.row_ptr).value,
                          _ptr(self.shift).value if self.shift is not None else None,
-                         self.n_edges, self.n_owned, self.n_total)
+                         self.n_edges, self.n_owned, self.n_total,
+                         _ptr(self.w_row).value if self.w_row is not None else None, int(self.n_w_rows))
+
+    def per_edge(self):
+        """The same edge list without shared rows of radial weights."""
+        return Graph(self.src, self.dst, self.row_ptr, self.shift, self.n_owned, self.n_total)
+
+    @property
+    def n_weight_rows(self):
+        """Rows of the weight tensor the composite calls write for this graph."""
+        return self.n_w_rows if self.w_row is not None else self.n_edges
 
 
 LAYER_STAGES = ["geometry", "radial_weights", "mix_pre", "tp_segsum", "mix_post"]
@@ -203,6 +216,19 @@ class Egnn:
         self._check(self.lib.egnn_nlist_fill(self.ctx, _ptr(pos), n_owned, n_total, _f3(box), pbc_c, _ptr(row_ptr),
                                              C.c_int64(n), _ptr(src), _ptr(dst), _ptr(shift), _ptr(ws), ws_n, _stream()))
         return Graph(src, dst, row_ptr, shift, n_owned, n_total)
+
+    def egnn_edge_pairs(self, graph):
+        """Sets graph.w_row / graph.n_w_rows (one row of radial weights per unordered pair of owned atoms)."""
+        out = C.c_size_t()
+        self._check(self.lib.egnn_edge_pairs_workspace_bytes(self.ctx, graph.n_owned, C.byref(out)))
+        ws = torch.empty(max(256, out.value), dtype=torch.uint8, device="cuda")
+        w_row = torch.empty(graph.n_edges, dtype=torch.int32, device="cuda")
+        n_rows = C.c_int64()
+        g = graph.per_edge().desc()
+        self._check(self.lib.egnn_edge_pairs(self.ctx, C.byref(g), _ptr(w_row), C.byref(n_rows), _ptr(ws),
+                                             C.c_size_t(ws.numel()), _stream()))
+        graph.w_row, graph.n_w_rows = w_row, n_rows.value
+        return graph
 
     # ---- node init
     def egnn_species_embed(self, species, table, x):
@@ -421,10 +447,11 @@ class Egnn:
 
     # ---- forward calls that leave w (and a) with the caller, reverse calls that take them back
     def egnn_layer_forward_save(self, graph, pos, box, x_in, W, ws, out=None):
-        """Returns (x_out, saved) with saved = (w [n_edges][P][E], a [n_owned][dim][E])."""
+        """Returns (x_out, saved) with saved = (w [rows][P][E], a [n_owned][dim][E]); rows = n_edges, or the
+        graph's n_w_rows when it carries shared rows."""
         x_out = out if out is not None else torch.empty((graph.n_owned, self.dim, self.channels),
                                                         dtype=torch.float32, device="cuda")
-        w = torch.empty((graph.n_edges, self.n_paths, self.channels), dtype=torch.float32, device="cuda")
+        w = torch.empty((graph.n_weight_rows, self.n_paths, self.channels), dtype=torch.float32, device="cuda")
         a = torch.empty((graph.n_owned, self.dim, self.channels), dtype=torch.float32, device="cuda")
         g = graph.desc()
         self._check(self.lib.egnn_layer_forward_save(
@@ -436,7 +463,7 @@ class Egnn:
     def egnn_readout_hij_save(self, graph, pos, box, x, W, ws, out=None):
         H = out if out is not None else torch.empty((graph.n_edges, self.n_orb, self.n_orb), dtype=torch.float32,
                                                     device="cuda")
-        w = torch.empty((graph.n_edges, self.n_paths_readout, self.channels), dtype=torch.float32, device="cuda")
+        w = torch.empty((graph.n_weight_rows, self.n_paths_readout, self.channels), dtype=torch.float32, device="cuda")
         g = graph.desc()
         self._check(self.lib.egnn_readout_hij_save(
             self.ctx, C.byref(g), _ptr(pos), _f3(box), _ptr(x), _ptr(W["W_s"]), _ptr(W["W_t"]), _ptr(W["W_r1"]),

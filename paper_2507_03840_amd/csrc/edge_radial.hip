@@ -54,7 +54,9 @@ __global__ __launch_bounds__(256) void edge_geometry_kernel(const int* __restric
                                                             double by, double bz, long n_edges,
                                                             float4* __restrict__ rhat_d,
                                                             float* __restrict__ Y, float* __restrict__ rbf,
-                                                            float* __restrict__ fc, int n_rbf, float r_cut) {
+                                                            float* __restrict__ fc, int n_rbf, float r_cut,
+                                                            const int* __restrict__ w_row,
+                                                            float4* __restrict__ rd_rows) {
   const long k = (long)blockIdx.x * 256 + threadIdx.x;
   if (k >= n_edges) return;
   const int i = src[k], j = dst[k];
@@ -71,6 +73,11 @@ __global__ __launch_bounds__(256) void edge_geometry_kernel(const int* __restric
   const float x = (float)(dx * inv), y = (float)(dy * inv), z = (float)(dz * inv);
   const float df = (float)d;
   rhat_d[k] = make_float4(x, y, z, df);
+  // shared rows of radial weights: the edge that owns a row leaves its record (of which only the length is used) there
+  if (rd_rows) {
+    const int r = w_row[k];
+    if (r >= 0) rd_rows[r] = make_float4(x, y, z, df);
+  }
   if (Y) {
     constexpr int NY = (LSH + 1) * (LSH + 1);
     float yy[NY];
@@ -86,19 +93,21 @@ __global__ __launch_bounds__(256) void edge_geometry_kernel(const int* __restric
       rbf[k * n_rbf + b] = __expf(-u * u * inv2s2);
     }
   }
-  if (fc) fc[k] = 0.5f * (1.0f + cosf(3.14159265358979323846f * df / r_cut));
+  if (fc) fc[k] = egnn_envelope(df, r_cut);
 }
 
+// rd_rows (may be NULL): [g->n_w_rows] records of the edges that own a row of radial weights (needs g->w_row)
 int egnn_launch_geometry(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3],
-                         float* rhat_d, float* Y, float* rbf, float* fc, hipStream_t stream) {
+                         float* rhat_d, float* Y, float* rbf, float* fc, hipStream_t stream, float* rd_rows) {
   const long n = g->n_edges;
   if (n == 0) return EGNN_OK;
   dim3 grid((unsigned)((n + 255) / 256)), block(256);
   float4* rd = reinterpret_cast<float4*>(rhat_d);
+  float4* rr = g->w_row ? reinterpret_cast<float4*>(rd_rows) : nullptr;
 #define LAUNCH(L)                                                                                          \
   hipLaunchKernelGGL(edge_geometry_kernel<L>, grid, block, 0, stream, g->src, g->dst, g->shift, pos,      \
                      (double)box[0], (double)box[1], (double)box[2], n, rd, Y, rbf, fc, ctx->desc.n_rbf, \
-                     ctx->desc.r_cut)
+                     ctx->desc.r_cut, g->w_row, rr)
   switch (ctx->desc.lmax_sh) {
     case 0: LAUNCH(0); break;
     case 1: LAUNCH(1); break;
@@ -377,7 +386,7 @@ __global__ __launch_bounds__(RW_THREADS, RW_MIN_WG) void radial_weights_kernel(c
 #pragma unroll
       for (int s = 0; s < 32; ++s) pre[s] += wrow[s] * B;
     }
-    const float fc = s_g * 0.5f * (1.0f + cosf(3.14159265358979323846f * d / r_cut));
+    const float fc = s_g * egnn_envelope(d, r_cut);
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       uint32_t ph[4], pl[4];

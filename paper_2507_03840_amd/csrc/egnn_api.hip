@@ -238,6 +238,7 @@ static size_t layer_ws(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, in
   c.take((size_t)n_owned * row);
   if (with_w) c.take(layer_w_bytes(ctx, n_edges, n_total));
   if (with_w) c.take(egnn_radial_ws_bytes(ctx, 0));
+  if (with_w) c.take((size_t)n_edges * 16);   // records of the row-owning edges (graphs with shared rows)
   return c.used;
 }
 
@@ -251,6 +252,7 @@ static size_t readout_ws(const egnn_ctx* ctx, int64_t n_edges, int32_t n_total) 
   c.take(ctx->unc_c.size() * sizeof(float));
   c.take(egnn_w_bytes(ctx, 1, n_edges));
   c.take(egnn_radial_ws_bytes(ctx, 1));
+  c.take((size_t)n_edges * 16);               // records of the row-owning edges (graphs with shared rows)
   return c.used;
 }
 
@@ -269,6 +271,8 @@ static int check_graph(egnn_ctx* ctx, const egnn_graph* g, const char* who) {
     return egnn_fail(ctx, EGNN_EINVAL, std::string(who) + ": bad graph sizes");
   if (!g->row_ptr || (g->n_edges > 0 && (!g->src || !g->dst)))
     return egnn_fail(ctx, EGNN_EINVAL, std::string(who) + ": null graph arrays");
+  if (g->w_row && (g->n_w_rows < 0 || g->n_w_rows > g->n_edges || (g->n_edges > 0 && g->n_w_rows == 0)))
+    return egnn_fail(ctx, EGNN_EINVAL, std::string(who) + ": n_w_rows does not fit the edge count");
   return EGNN_OK;
 }
 
@@ -363,8 +367,11 @@ static int layer_forward_impl(egnn_ctx* ctx, const egnn_graph* g, const float* p
   if (w_save && with_w) w = w_save;
   if (a_save) a = a_save;
   void* w2s = with_w ? c.take(egnn_radial_ws_bytes(ctx, 0)) : nullptr;
+  // shared rows (egnn_edge_pairs): S3 writes one row per row index, from the records of the row-owning edges
+  const bool shared = with_w && g->w_row != nullptr;
+  float* rd_rows = shared ? (float*)c.take((size_t)g->n_edges * 16) : nullptr;
   StageTimer tm(ctx, st, 0);
-  if ((rc = egnn_launch_geometry(ctx, g, pos, box, rhat_d, nullptr, nullptr, nullptr, st))) return rc;
+  if ((rc = egnn_launch_geometry(ctx, g, pos, box, rhat_d, nullptr, nullptr, nullptr, st, rd_rows))) return rc;
   tm.mark(0);
   // Default: S3 writes the weight tensor, S4 reads it.  Opt-in (EGNN_OPT_FUSED): the weights are produced and
   // consumed inside one kernel and never leave the chip.
@@ -375,7 +382,9 @@ static int layer_forward_impl(egnn_ctx* ctx, const egnn_graph* g, const float* p
   if (fused) {
     if (g->n_edges > 0 && (rc = egnn_launch_split_w2(ctx, 0, W_r2, w2s, st))) return rc;
   } else if (with_w) {
-    if ((rc = egnn_launch_radial(ctx, 0, rhat_d, g->n_edges, W_r1, W_r2, w, w2s, st, half))) return rc;
+    if ((rc = egnn_launch_radial(ctx, 0, shared ? rd_rows : rhat_d, shared ? g->n_w_rows : g->n_edges, W_r1, W_r2, w,
+                                 w2s, st, half)))
+      return rc;
   }
   tm.mark(1);
   if ((rc = egnn_launch_node_mix(ctx, x_in, W_pre, nullptr, nullptr, h, g->n_total, st))) return rc;
@@ -385,7 +394,7 @@ static int layer_forward_impl(egnn_ctx* ctx, const egnn_graph* g, const float* p
   } else if (fused) {
     if ((rc = egnn_launch_layer_fused(ctx, g, rhat_d, h, W_r1, w2s, w, w_bytes, a, st))) return rc;
   } else {
-    if ((rc = egnn_launch_tp_segsum(ctx, g, rhat_d, h, with_w ? w : w_edge, a, st, half))) return rc;
+    if ((rc = egnn_launch_tp_segsum(ctx, g, rhat_d, h, with_w ? w : w_edge, a, st, half, shared))) return rc;
   }
   tm.mark(3);
   rc = egnn_launch_node_mix(ctx, a, W_post, x_in, W_self, x_out, g->n_owned, st);
@@ -434,6 +443,8 @@ static int readout_hij_impl(egnn_ctx* ctx, const egnn_graph* g, const float* pos
   float* tab_f = (float*)c.take(ctx->unc_c.size() * sizeof(float));
   float* w = (float*)c.take(egnn_w_bytes(ctx, 1, g->n_edges));
   void* w2s = c.take(egnn_radial_ws_bytes(ctx, 1));
+  const bool shared = g->w_row != nullptr;
+  float* rd_rows = shared ? (float*)c.take((size_t)g->n_edges * 16) : nullptr;
   const bool half = ctx->w_half && !w_save;
   if (w_save) w = w_save;
 
@@ -462,15 +473,17 @@ static int readout_hij_impl(egnn_ctx* ctx, const egnn_graph* g, const float* pos
   EGNN_HIP(ctx, hipMemcpyAsync(tab_f, ctx->unc_c.data(), ctx->unc_c.size() * sizeof(float), hipMemcpyHostToDevice, st));
 
   StageTimer tm(ctx, st, 1);
-  if ((rc = egnn_launch_geometry(ctx, g, pos, box, rhat_d, nullptr, nullptr, nullptr, st))) return rc;
+  if ((rc = egnn_launch_geometry(ctx, g, pos, box, rhat_d, nullptr, nullptr, nullptr, st, rd_rows))) return rc;
   tm.mark(0);
-  if ((rc = egnn_launch_radial(ctx, 1, rhat_d, g->n_edges, W_r1, W_r2, w, w2s, st, half))) return rc;
+  if ((rc = egnn_launch_radial(ctx, 1, shared ? rd_rows : rhat_d, shared ? g->n_w_rows : g->n_edges, W_r1, W_r2, w, w2s,
+                               st, half)))
+    return rc;
   tm.mark(1);
   if ((rc = egnn_launch_node_mix(ctx, x, W_s, nullptr, nullptr, zs, g->n_total, st))) return rc;
   tm.mark(2);
   if ((rc = egnn_launch_node_mix(ctx, x, W_t, nullptr, nullptr, zt, g->n_total, st))) return rc;
   tm.mark(3);
-  rc = egnn_launch_readout(ctx, g, rhat_d, zs, zt, w, V, tab_i, tab_f, H, st, half);
+  rc = egnn_launch_readout(ctx, g, rhat_d, zs, zt, w, V, tab_i, tab_f, H, st, half, shared);
   tm.mark(4);
   return rc;
 }

@@ -27,7 +27,7 @@ static int vrows(const egnn_ctx* ctx) {
 }
 
 struct LayerBwdBufs {
-  float *rhat_d, *h, *a, *w, *da, *dh, *dw, *wgrad_partial;
+  float *rhat_d, *rd_rows, *h, *a, *w, *da, *dh, *dw, *wgrad_partial;
   void *radial, *w2s;
 };
 
@@ -36,6 +36,7 @@ static size_t carve_layer_bwd(const egnn_ctx* ctx, const egnn_graph* g, char* ba
   const size_t wbytes = (size_t)g->n_edges * ctx->n_paths[0] * ctx->desc.channels * sizeof(float);
   Carver2 c{base, 0};
   b->rhat_d = (float*)c.take((size_t)g->n_edges * 16);
+  b->rd_rows = (float*)c.take((size_t)g->n_edges * 16);   // records of the row-owning edges (graphs with shared rows)
   b->h = (float*)c.take((size_t)g->n_total * row);
   b->a = (float*)c.take((size_t)g->n_owned * row);
   b->da = (float*)c.take((size_t)g->n_owned * row);
@@ -49,7 +50,7 @@ static size_t carve_layer_bwd(const egnn_ctx* ctx, const egnn_graph* g, char* ba
 }
 
 struct ReadoutBwdBufs {
-  float *rhat_d, *zs, *zt, *dzs, *dzt, *w, *dw, *dz, *wgrad_partial, *dV_partial, *tab_f;
+  float *rhat_d, *rd_rows, *zs, *zt, *dzs, *dzt, *w, *dw, *dz, *wgrad_partial, *dV_partial, *tab_f;
   int* tab_i;
   void *radial, *w2s;
 };
@@ -64,6 +65,7 @@ static size_t carve_readout_bwd(const egnn_ctx* ctx, const egnn_graph* g, char* 
   const size_t wbytes = (size_t)g->n_edges * ctx->n_paths[1] * ctx->desc.channels * sizeof(float);
   Carver2 c{base, 0};
   b->rhat_d = (float*)c.take((size_t)g->n_edges * 16);
+  b->rd_rows = (float*)c.take((size_t)g->n_edges * 16);   // records of the row-owning edges (graphs with shared rows)
   b->zs = (float*)c.take((size_t)g->n_total * row);
   b->zt = (float*)c.take((size_t)g->n_total * row);
   b->dzs = (float*)c.take((size_t)g->n_total * row);
@@ -101,6 +103,8 @@ static int check_bwd_graph(egnn_ctx* ctx, const egnn_graph* g, const int32_t* co
     return egnn_fail(ctx, EGNN_EINVAL, std::string(who) + ": bad graph sizes");
   if (!g->row_ptr || !col_ptr || (g->n_edges > 0 && (!g->src || !g->dst || !perm)))
     return egnn_fail(ctx, EGNN_EINVAL, std::string(who) + ": null graph arrays");
+  if (g->w_row && (g->n_w_rows < 0 || g->n_w_rows > g->n_edges || (g->n_edges > 0 && g->n_w_rows == 0)))
+    return egnn_fail(ctx, EGNN_EINVAL, std::string(who) + ": n_w_rows does not fit the edge count");
   return EGNN_OK;
 }
 
@@ -128,13 +132,18 @@ static int layer_backward_impl(egnn_ctx* ctx, const egnn_graph* g, const int32_t
   const int n_o = g->n_owned, n_t = g->n_total;
 
   // forward quantities
+  // (graphs with shared rows: the forward weights, recomputed or kept, have one row per row index; dw one per edge)
+  const bool shared = g->w_row != nullptr;
   StageTimer tm(ctx, st, 2);
-  if ((rc = egnn_launch_geometry(ctx, g, pos, box, b.rhat_d, nullptr, nullptr, nullptr, st))) return rc;
+  if ((rc = egnn_launch_geometry(ctx, g, pos, box, b.rhat_d, nullptr, nullptr, nullptr, st, shared ? b.rd_rows : nullptr)))
+    return rc;
   const float* w = w_saved ? w_saved : b.w;
   const float* a = a_saved ? a_saved : b.a;
-  if (!w_saved && (rc = egnn_launch_radial(ctx, 0, b.rhat_d, g->n_edges, W_r1, W_r2, b.w, b.w2s, st))) return rc;
+  if (!w_saved && (rc = egnn_launch_radial(ctx, 0, shared ? b.rd_rows : b.rhat_d, shared ? g->n_w_rows : g->n_edges, W_r1,
+                                           W_r2, b.w, b.w2s, st)))
+    return rc;
   if ((rc = egnn_launch_node_mix(ctx, x_in, W_pre, nullptr, nullptr, b.h, n_t, st))) return rc;
-  if (!a_saved && (rc = egnn_launch_tp_segsum(ctx, g, b.rhat_d, b.h, w, b.a, st))) return rc;
+  if (!a_saved && (rc = egnn_launch_tp_segsum(ctx, g, b.rhat_d, b.h, w, b.a, st, false, shared))) return rc;
   tm.mark(0);
   // x_out = W_post a + W_self x_in[:n_owned]
   if ((rc = egnn_launch_node_mix(ctx, dx_out, W_post, nullptr, nullptr, b.da, n_o, st, 1))) return rc;
@@ -145,7 +154,8 @@ static int layer_backward_impl(egnn_ctx* ctx, const egnn_graph* g, const int32_t
   // (the largest |dw|, kept by the kernel that writes dw, scales the contractions that read it)
   unsigned* dw_max = egnn_radial_backward_dw_max(b.radial);
   if ((rc = egnn_launch_fill_int(ctx, (int*)dw_max, 64, 0, st))) return rc;
-  if ((rc = egnn_launch_tp_backward(ctx, g, col_ptr, perm, b.rhat_d, b.h, w, b.da, b.dh, b.dw, dw_max, st))) return rc;
+  if ((rc = egnn_launch_tp_backward(ctx, g, col_ptr, perm, b.rhat_d, b.h, w, b.da, b.dh, b.dw, dw_max, st, shared)))
+    return rc;
   tm.mark(2);
   // h = W_pre x_in ; owned rows also receive the self term
   if ((rc = egnn_launch_node_mix(ctx, b.dh, W_pre, dx_out, W_self, dx_in, n_o, st, 1))) return rc;
@@ -233,15 +243,19 @@ static int readout_backward_impl(egnn_ctx* ctx, const egnn_graph* g, const int32
   EGNN_HIP(ctx, hipMemcpyAsync(b.tab_i, ti.data(), ti.size() * sizeof(int), hipMemcpyHostToDevice, st));
   EGNN_HIP(ctx, hipMemcpyAsync(b.tab_f, tf.data(), tf.size() * sizeof(float), hipMemcpyHostToDevice, st));
 
+  const bool shared = g->w_row != nullptr;
   StageTimer tm(ctx, st, 3);
-  if ((rc = egnn_launch_geometry(ctx, g, pos, box, b.rhat_d, nullptr, nullptr, nullptr, st))) return rc;
+  if ((rc = egnn_launch_geometry(ctx, g, pos, box, b.rhat_d, nullptr, nullptr, nullptr, st, shared ? b.rd_rows : nullptr)))
+    return rc;
   const float* w = w_saved ? w_saved : b.w;
-  if (!w_saved && (rc = egnn_launch_radial(ctx, 1, b.rhat_d, g->n_edges, W_r1, W_r2, b.w, b.w2s, st))) return rc;
+  if (!w_saved && (rc = egnn_launch_radial(ctx, 1, shared ? b.rd_rows : b.rhat_d, shared ? g->n_w_rows : g->n_edges, W_r1,
+                                           W_r2, b.w, b.w2s, st)))
+    return rc;
   if ((rc = egnn_launch_node_mix(ctx, x, W_s, nullptr, nullptr, b.zs, n_t, st))) return rc;
   if ((rc = egnn_launch_node_mix(ctx, x, W_t, nullptr, nullptr, b.zt, n_t, st))) return rc;
   tm.mark(0);
   if ((rc = egnn_launch_readout_backward(ctx, g, b.rhat_d, b.zs, b.zt, w, V, b.tab_i, b.tab_f, dH, b.dz, b.dw, dV,
-                                         b.dV_partial, st)))
+                                         b.dV_partial, st, shared)))
     return rc;
   tm.mark(1);
   // dz_k feeds the source row (zs) and the destination row (zt, owned nodes only)

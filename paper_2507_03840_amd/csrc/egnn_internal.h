@@ -35,7 +35,9 @@ struct egnn_ctx {
   std::vector<int> ev_kind;              // per recorded call: 0 = layer, 1 = readout, 2 = layer adjoint, 3 = readout adjoint
   int ev_max_calls = 0;
   CellGrid nl_grid;                      // grid of the last egnn_nlist_count that used the cell list
-  int nl_grid_atoms = -1;                //   and the atom count it was built for
+  int nl_grid_atoms = -1;                //   and the atom count, workspace and positions it was built for
+  const void* nl_grid_ws = nullptr;
+  const void* nl_grid_pos = nullptr;
   int use_fused = 0;                     // egnn_set_option(EGNN_OPT_FUSED): 0 two kernels, 1 / 2 the fused designs
   bool w_half = false;                   // egnn_set_option(EGNN_OPT_W_FP16)
   // index tables of the readout / on-site kernels in the order the kernels read them, built on first use and kept:
@@ -65,6 +67,20 @@ int egnn_check_hip(egnn_ctx* ctx, hipError_t e, const char* what);
 // their bit patterns): the atomic is issued only when it would raise the value -- atomics on one address run one
 // after the other, and after the first few thousand wavefronts almost none is needed.
 #ifdef __HIPCC__
+// Row of the radial-weight tensor that edge k reads: k itself without shared rows, else the decoded entry of
+// egnn_graph.w_row (r >= 0: the edge owns row r; r < 0: it reads row ~r, which belongs to its reverse).
+__device__ __forceinline__ long egnn_weight_row(const int* __restrict__ w_row, long k) {
+  if (!w_row) return k;
+  const int r = w_row[k];
+  return r < 0 ? ~r : r;
+}
+// Cosine cutoff f_c(d) = (1 + cos(pi d / r_cut)) / 2, evaluated as sin^2(pi (r_cut - d) / (2 r_cut)): the same function,
+// but near the cutoff, where it tends to zero, 1 + cos(...) loses its relative accuracy to rounding (an absolute error
+// of 6e-8 on a value of 1e-5), while r_cut - d is exact there and the square of a small sine is not.
+__device__ __forceinline__ float egnn_envelope(float d, float r_cut) {
+  const float s = sinf(1.57079632679489662f * (r_cut - d) / r_cut);
+  return s * s;
+}
 __device__ __forceinline__ void egnn_raise_max(unsigned* target, float v) {
   const unsigned bits = __float_as_uint(v);
   if (bits > __atomic_load_n(target, __ATOMIC_RELAXED)) atomicMax(target, bits);
@@ -99,7 +115,7 @@ size_t egnn_transpose_ws_bytes(int64_t n_edges, int32_t n_total);
 // dw_max (may be NULL): a word the caller has set to zero; raised to the bit pattern of the largest |dw| written
 int egnn_launch_tp_backward(egnn_ctx*, const egnn_graph*, const int* col_ptr, const int* perm, const float* rhat_d,
                             const float* h, const float* w, const float* da, float* dh, float* dw, unsigned* dw_max,
-                            hipStream_t);
+                            hipStream_t, bool shared_rows = false);
 size_t egnn_radial_backward_ws_bytes(const egnn_ctx*, int which, int64_t n_edges);
 // dw_max_valid: the first word of ws (egnn_radial_backward_dw_max) holds the bit pattern of the largest |dw|; the
 // two large contractions then run on half-precision pieces, otherwise on bf16 pieces (which need no scaling)
@@ -111,10 +127,12 @@ size_t egnn_readout_backward_partial_bytes(const egnn_ctx*, int64_t n_edges);
 size_t egnn_readout_backward_lds_bytes(const egnn_ctx*);
 int egnn_launch_readout_backward(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* zs, const float* zt,
                                  const float* w, const float* V, const int* tab_i, const float* tab_f,
-                                 const float* dH, float* dz, float* dw, float* dV, float* partial, hipStream_t);
+                                 const float* dH, float* dz, float* dw, float* dV, float* partial, hipStream_t,
+                                 bool shared_rows = false);
 // half = true: `w` holds half-precision weights in the layout of w_half.h (egnn_w_bytes sizes it)
+// shared_rows = true: `w` has one row per entry of g->w_row (egnn_edge_pairs), else one per edge
 int egnn_launch_tp_segsum(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* h, const float* w,
-                          float* a, hipStream_t, bool half = false);
+                          float* a, hipStream_t, bool half = false, bool shared_rows = false);
 int egnn_launch_radial(egnn_ctx*, int which, const float* rhat_d, int64_t n_edges, const float* W_r1,
                        const float* W_r2, float* w, void* scratch, hipStream_t, bool half = false);
 size_t egnn_w_bytes(const egnn_ctx*, int which, int64_t n_edges);   // room for w in either precision
@@ -131,7 +149,7 @@ size_t egnn_fused_scratch_bytes(const egnn_ctx*, int64_t n_edges);
 int egnn_launch_layer_fused(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* h, const float* W_r1,
                             const void* W2s, void* scratch, size_t scratch_bytes, float* a, hipStream_t);
 int egnn_launch_geometry(egnn_ctx*, const egnn_graph*, const float* pos, const float box[3], float* rhat_d,
-                         float* Y, float* rbf, float* fc, hipStream_t);
+                         float* Y, float* rbf, float* fc, hipStream_t, float* rd_rows = nullptr);
 int egnn_launch_readout(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* zs, const float* zt,
                         const float* w, const float* V, const int* tab_i, const float* tab_f, float* H, hipStream_t,
-                        bool half = false);
+                        bool half = false, bool shared_rows = false);

@@ -149,7 +149,7 @@ __device__ __forceinline__ void fp_hidden(const float* sW1, int n_rbf, float r_c
 #pragma unroll
     for (int s = 0; s < 32; ++s) pre[s] += wrow[s] * B;
   }
-  const float fc = 0.5f * (1.0f + cosf(3.14159265358979323846f * d / r_cut));
+  const float fc = egnn_envelope(d, r_cut);
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
     uint32_t ph[4], pm[4], pl[4];

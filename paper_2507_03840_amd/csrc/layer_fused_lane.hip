@@ -205,7 +205,7 @@ __global__ __launch_bounds__(F2_THREADS) void f2_kernel(const int* __restrict__ 
           for (int s = 0; s < 32; ++s) pre[s] += wrow[s] * Bv;
         }
         // (a lane past the node's last edge gets a zero envelope: zero weights, a zero message, nothing to mask later)
-        const float fc = valid ? s_g * 0.5f * (1.0f + cosf(3.14159265358979323846f * g.w / r_cut)) : 0.0f;
+        const float fc = valid ? s_g * egnn_envelope(g.w, r_cut) : 0.0f;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           uint32_t ph[4], pl[4];

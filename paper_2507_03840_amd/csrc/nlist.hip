@@ -51,14 +51,15 @@ __global__ __launch_bounds__(256) void nlist_sweep_kernel(const float* __restric
   if (j >= n_owned) return;
   const double pj[3] = {(double)pos[3 * j], (double)pos[3 * j + 1], (double)pos[3 * j + 2]};
   const long base = FILL ? row_ptr[j] : 0;
+  const long row_end = FILL ? row_ptr[j + 1] : 0;   // the fill pass never writes past the row the count pass sized
   int count = 0;
   for (int i0 = 0; i0 < n_total; i0 += 64) {
     const int i = i0 + lane;
     int sh[3] = {0, 0, 0};
     const bool inside = (i < n_total) && (i != j) && pair_inside(pj, pos, i, g, sh);
     const unsigned long long mask = __ballot(inside);
-    if (FILL && inside) {
-      const long at = base + count + __popcll(mask & ((1ull << lane) - 1ull));
+    const long at = base + count + __popcll(mask & ((1ull << lane) - 1ull));
+    if (FILL && inside && at < row_end) {
       src[at] = i;
       dst[at] = j;
       if (shift) {
@@ -164,7 +165,9 @@ __global__ __launch_bounds__(256) void nlist_cells_kernel(const float* __restric
   __builtin_amdgcn_wave_barrier();
 
   const double pj[3] = {(double)pos[3 * j], (double)pos[3 * j + 1], (double)pos[3 * j + 2]};
-  const int cj = cell_of[j];
+  // indices read back from the workspace are clamped: a workspace overwritten between the count and the fill call
+  // then gives a wrong list, never an access outside the buffers
+  const int cj = min(max(cell_of[j], 0), cg.n_cells - 1);
   const int cz = cj % cg.n[2], cy = (cj / cg.n[2]) % cg.n[1], cx = cj / (cg.n[2] * cg.n[1]);
   int nx[3], ny[3], nz[3];
   const int kx = axis_neighbours(cx, 0, cg, nx), ky = axis_neighbours(cy, 1, cg, ny), kz = axis_neighbours(cz, 2, cg, nz);
@@ -172,11 +175,12 @@ __global__ __launch_bounds__(256) void nlist_cells_kernel(const float* __restric
     for (int iy = 0; iy < ky; ++iy)
       for (int iz = 0; iz < kz; ++iz) {
         const int cell = (nx[ix] * cg.n[1] + ny[iy]) * cg.n[2] + nz[iz];
-        const int a0 = cell_ptr[cell], a1 = cell_ptr[cell + 1];
+        const int a0 = max(cell_ptr[cell], 0), a1 = min(cell_ptr[cell + 1], n_total);
         for (int a = a0 + lane; a < a1; a += 64) {
           const int i = cell_atoms[a];
           int sh[3];
-          if (i != j && pair_inside(pj, pos, i, g, sh)) atomicOr(&bitmap[i >> 5], 1u << (i & 31));
+          if ((unsigned)i < (unsigned)n_total && i != j && pair_inside(pj, pos, i, g, sh))
+            atomicOr(&bitmap[i >> 5], 1u << (i & 31));
         }
       }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
@@ -185,6 +189,7 @@ __global__ __launch_bounds__(256) void nlist_cells_kernel(const float* __restric
 
   // bitmap -> sorted sources
   const long base = FILL ? row_ptr[j] : 0;
+  const long row_end = FILL ? row_ptr[j + 1] : 0;   // the fill pass never writes past the row the count pass sized
   int count = 0;
   for (int w0 = 0; w0 < words; w0 += 64) {
     const int wi = w0 + lane;
@@ -204,12 +209,14 @@ __global__ __launch_bounds__(256) void nlist_cells_kernel(const float* __restric
         const int i = wi * 32 + b;
         int sh[3];
         pair_inside(pj, pos, i, g, sh);
-        src[at] = i;
-        dst[at] = j;
-        if (shift) {
-          shift[3 * at + 0] = (int8_t)sh[0];
-          shift[3 * at + 1] = (int8_t)sh[1];
-          shift[3 * at + 2] = (int8_t)sh[2];
+        if (at < row_end) {
+          src[at] = i;
+          dst[at] = j;
+          if (shift) {
+            shift[3 * at + 0] = (int8_t)sh[0];
+            shift[3 * at + 1] = (int8_t)sh[1];
+            shift[3 * at + 2] = (int8_t)sh[2];
+          }
         }
         ++at;
       }
@@ -352,6 +359,8 @@ extern "C" int egnn_nlist_count(egnn_ctx* ctx, const float* pos, int32_t n_owned
     }
     ctx->nl_grid = cg;          // egnn_nlist_fill walks the same cells
     ctx->nl_grid_atoms = n_total;
+    ctx->nl_grid_ws = ws;
+    ctx->nl_grid_pos = pos;
     if ((rc = egnn_launch_fill_int(ctx, w.cell_ptr, (long)cg.n_cells + 1, 0, st))) return rc;
     if ((rc = egnn_launch_fill_int(ctx, w.cursor, cg.n_cells, 0, st))) return rc;
     const dim3 ga((n_total + 255) / 256), b(256);
@@ -391,7 +400,7 @@ extern "C" int egnn_nlist_fill(egnn_ctx* ctx, const float* pos, int32_t n_owned,
     // the cell lists built by egnn_nlist_count are still in the workspace; their grid is kept in the context
     CellWs w;
     carve_cells((char*)ws, n_total, &w);
-    if (ctx->nl_grid_atoms != n_total)
+    if (ctx->nl_grid_atoms != n_total || ctx->nl_grid_ws != ws || ctx->nl_grid_pos != pos)
       return egnn_fail(ctx, EGNN_EINVAL, "nlist_fill: call egnn_nlist_count with the same atoms and workspace first");
     const CellGrid cg = ctx->nl_grid;
     return launch_cells<true>(ctx, pos, n_owned, n_total, g, cg, w, const_cast<int*>(row_ptr), src, dst, shift, st);

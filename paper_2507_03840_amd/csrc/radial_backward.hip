@@ -44,7 +44,7 @@ __global__ __launch_bounds__(256) void radial_hidden_kernel(const float4* __rest
   }
   if (tid < RH_EDGES) {
     const long k = k0 + tid < n_edges ? k0 + tid : n_edges - 1;
-    sFc[tid] = 0.5f * (1.0f + cosf(3.14159265358979323846f * rhat_d[k].w / r_cut));
+    sFc[tid] = egnn_envelope(rhat_d[k].w, r_cut);
   }
   float w1[NB];
 #pragma unroll

@@ -50,7 +50,8 @@ template <int LMAX, int log2E, bool HALF>
 __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ src, const int* __restrict__ dst,
                                                       const float4* __restrict__ rhat_d,
                                                       const float* __restrict__ zs, const float* __restrict__ zt,
-                                                      const float* __restrict__ w, const float* __restrict__ V,
+                                                      const float* __restrict__ w, const int* __restrict__ w_row,
+                                                      const float* __restrict__ V,
                                                       ReadoutTabs tb, float* __restrict__ H, long n_edges,
                                                       int tiles_per_xcd) {
   using Mid = typename ReadoutMid<LMAX>::T;
@@ -99,13 +100,14 @@ __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ sr
       const float4 g = rhat_d[k];
       const float* zsp = zs + ((size_t)s * D << log2E) + c;
       const float* ztp = zt + ((size_t)d * D << log2E) + c;
+      const size_t kw = (size_t)egnn_weight_row(w_row, k);
       float v[D], wr[P], o[RO_D];
       if constexpr (!HALF) {
-        const float* wp = w + ((size_t)k * P << log2E) + c;
+        const float* wp = w + (kw * P << log2E) + c;
 #pragma unroll
         for (int p = 0; p < P; ++p) wr[p] = __builtin_nontemporal_load(wp + ((size_t)p << log2E));
       } else {
-        w_half_load<P, log2E>(reinterpret_cast<const uint32_t*>(w) + (size_t)k * w_half_row_words(P << log2E), c, wr);
+        w_half_load<P, log2E>(reinterpret_cast<const uint32_t*>(w) + kw * w_half_row_words(P << log2E), c, wr);
       }
 #pragma unroll
       for (int i = 0; i < D; ++i) v[i] = zsp[(size_t)i << log2E] + ztp[(size_t)i << log2E];
@@ -150,7 +152,8 @@ __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ sr
 
 template <int L, int LE, bool HALF>
 static int launch_readout(egnn_ctx* ctx, const egnn_graph* g, const float4* rd, const float* zs, const float* zt,
-                          const float* w, const float* V, const ReadoutTabs& tb, float* H, hipStream_t stream) {
+                          const float* w, const int* w_row, const float* V, const ReadoutTabs& tb, float* H,
+                          hipStream_t stream) {
   constexpr int E = 1 << LE, n_slots = 256 / E;
   const size_t shmem = ((size_t)tb.n_vrows * (E + 4) + (size_t)n_slots * RO_D * (E + 4) + (size_t)n_slots * tb.nq) *
                            sizeof(float) +
@@ -164,16 +167,17 @@ static int launch_readout(egnn_ctx* ctx, const egnn_graph* g, const float4* rd, 
                                        (int)shmem);
     if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(readout_kernel)");
   }
-  hipLaunchKernelGGL(kern, grid, block, shmem, stream, g->src, g->dst, rd, zs, zt, w, V, tb, H, (long)g->n_edges,
-                     tiles_per_xcd);
+  hipLaunchKernelGGL(kern, grid, block, shmem, stream, g->src, g->dst, rd, zs, zt, w, w_row, V, tb, H,
+                     (long)g->n_edges, tiles_per_xcd);
   EGNN_LAUNCH_CHECK(ctx, "readout_kernel");
   return EGNN_OK;
 }
 
 int egnn_launch_readout(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, const float* zs, const float* zt,
                         const float* w, const float* V, const int* tab_i, const float* tab_f, float* H,
-                        hipStream_t stream, bool half) {
+                        hipStream_t stream, bool half, bool shared_rows) {
   const long n = g->n_edges;
+  const int* w_row = shared_rows ? g->w_row : nullptr;
   if (n == 0) return EGNN_OK;
   const int nq = ctx->n_orb * ctx->n_orb;
   ReadoutTabs tb;
@@ -193,8 +197,8 @@ int egnn_launch_readout(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d,
   const float4* rd = reinterpret_cast<const float4*>(rhat_d);
 #define CASE(L, LE)                                                                         \
   if (ctx->desc.lmax == L && ctx->log2_channels == LE)                                      \
-    return half ? launch_readout<L, LE, true>(ctx, g, rd, zs, zt, w, V, tb, H, stream)      \
-                : launch_readout<L, LE, false>(ctx, g, rd, zs, zt, w, V, tb, H, stream);
+    return half ? launch_readout<L, LE, true>(ctx, g, rd, zs, zt, w, w_row, V, tb, H, stream)      \
+                : launch_readout<L, LE, false>(ctx, g, rd, zs, zt, w, w_row, V, tb, H, stream);
 #define CASES(L) CASE(L, 3) CASE(L, 4) CASE(L, 5) CASE(L, 6) CASE(L, 7)
   CASES(0) CASES(1) CASES(2) CASES(3) CASES(4)
 #undef CASES

@@ -134,7 +134,7 @@ template <int LMAX, int LE>
 __global__ __launch_bounds__(256, 3) void readout_backward_kernel(
     const int* __restrict__ src, const int* __restrict__ dst, const float4* __restrict__ rhat_d,
     const float* __restrict__ zs, const float* __restrict__ zt, const float* __restrict__ w,
-    const float* __restrict__ V, ReadoutBwdTabs tb, const float* __restrict__ dH, float* __restrict__ dz,
+    const int* __restrict__ w_row, const float* __restrict__ V, ReadoutBwdTabs tb, const float* __restrict__ dH, float* __restrict__ dz,
     float* __restrict__ dw, float* __restrict__ dV_partial, long n_edges, int iters) {
   constexpr int log2E = LE;
   using Mid = typename ReadoutMid<LMAX>::T;
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(256, 3) void readout_backward_kernel(
     // round trip per edge instead of one for dH and another for the weights.
     const float4 g = rhat_d[k];
     const int s = src[k], d = dst[k];
-    const float* wp = w + ((size_t)k * P << log2E) + c;
+    const float* wp = w + ((size_t)egnn_weight_row(w_row, k) * P << log2E) + c;   // (dw stays one row per edge)
     float wr[P];
 #pragma unroll
     for (int p = 0; p < P; ++p) wr[p] = __builtin_nontemporal_load(wp + ((size_t)p << log2E));
@@ -265,8 +265,9 @@ size_t egnn_readout_backward_partial_bytes(const egnn_ctx* ctx, int64_t n_edges)
 int egnn_launch_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, const float* zs,
                                  const float* zt, const float* w, const float* V, const int* tab_i,
                                  const float* tab_f, const float* dH, float* dz, float* dw, float* dV,
-                                 float* partial, hipStream_t stream) {
+                                 float* partial, hipStream_t stream, bool shared_rows) {
   const long n = g->n_edges;
+  const int* w_row = shared_rows ? g->w_row : nullptr;
   const int E = ctx->desc.channels;
   const int n_vrows = rob_vrows(ctx);
   if (n == 0) return egnn_launch_reduce_partials(ctx, partial, 0, (long)n_vrows * E, dV, 1.0f, stream);
@@ -297,7 +298,7 @@ int egnn_launch_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const float
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);                 \
       if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(readout_backward_kernel)");         \
     }                                                                                                             \
-    hipLaunchKernelGGL(kern, grid, block, shmem, stream, g->src, g->dst, rd, zs, zt, w, V, tb, dH, dz, dw,        \
+    hipLaunchKernelGGL(kern, grid, block, shmem, stream, g->src, g->dst, rd, zs, zt, w, w_row, V, tb, dH, dz, dw, \
                        partial, n, rob_iters(ctx, n));                                                            \
   } while (0)
 #define CASES(L)                                                                \

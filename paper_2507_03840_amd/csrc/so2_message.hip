@@ -324,7 +324,7 @@ __global__ __launch_bounds__(256) void so2_scatter_kernel(const int* __restrict_
     const float4 g = rhat_d[k];
     float o[D];
     so2_load_rotate_back<LMAX>(b, k, c, log2E, g, o);
-    float fc = 0.5f * (1.0f + cosf(3.14159265358979323846f * g.w / r_cut));
+    float fc = egnn_envelope(g.w, r_cut);
     if (alpha) fc *= alpha[k];
 #pragma unroll
     for (int i = 0; i < D; ++i) acc[i] += fc * o[i];
@@ -388,7 +388,7 @@ __global__ __launch_bounds__(256) void so2_edge_update_kernel(const float4* __re
   const float4 g = rhat_d[k];
   float o[D];
   so2_load_rotate_back<LMAX>(b, k, c, log2E, g, o);
-  const float fc = 0.5f * (1.0f + cosf(3.14159265358979323846f * g.w / r_cut));
+  const float fc = egnn_envelope(g.w, r_cut);
   const float* ti = T_in + (((size_t)k * D) << log2E) + c;
   float* to = T_out + (((size_t)k * D) << log2E) + c;
 #pragma unroll

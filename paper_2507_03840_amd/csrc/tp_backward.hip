@@ -37,6 +37,7 @@ __global__ __launch_bounds__(256, 2) void tp_backward_kernel(const int* __restri
                                                              const int* __restrict__ dst,
                                                              const float4* __restrict__ rhat_d,
                                                              const float* __restrict__ h, const float* __restrict__ w,
+                                                             const int* __restrict__ w_row,
                                                              const float* __restrict__ da, float* __restrict__ dh,
                                                              float* __restrict__ dw, unsigned* __restrict__ dw_max,
                                                              int n_total, int nodes_per_xcd, float scale) {
@@ -69,7 +70,7 @@ __global__ __launch_bounds__(256, 2) void tp_backward_kernel(const int* __restri
     const int j = dst[k];
     const float4 g = rhat_d[k];
     const float* gp = da + ((size_t)j * D << log2E) + c;
-    const float* wp = w + ((size_t)k * P << log2E) + c;
+    const float* wp = w + ((size_t)egnn_weight_row(w_row, k) * P << log2E) + c;   // (dw stays one row per edge)
     float* dwp = dw + ((size_t)k * P << log2E) + c;
     float v[D], go[D], gv[D], wr[P];
 #pragma unroll
@@ -108,16 +109,17 @@ __global__ __launch_bounds__(256, 2) void tp_backward_kernel(const int* __restri
 
 int egnn_launch_tp_backward(egnn_ctx* ctx, const egnn_graph* g, const int* col_ptr, const int* perm,
                             const float* rhat_d, const float* h, const float* w, const float* da, float* dh,
-                            float* dw, unsigned* dw_max, hipStream_t stream) {
+                            float* dw, unsigned* dw_max, hipStream_t stream, bool shared_rows) {
   const int n = g->n_total;
+  const int* w_row = shared_rows ? g->w_row : nullptr;
   if (n == 0) return EGNN_OK;
   const int per_xcd = (n + 7) / 8;
   dim3 grid(per_xcd * 8), block(256);
   const float scale = 1.0f / sqrtf(ctx->desc.agg_norm);
   const float4* rd = reinterpret_cast<const float4*>(rhat_d);
 #define LAUNCH(L, LE_)                                                                                          \
-  hipLaunchKernelGGL((tp_backward_kernel<L, LE_>), grid, block, 0, stream, col_ptr, perm, g->dst, rd, h, w, da, dh, \
-                     dw, dw_max, n, per_xcd, scale)
+  hipLaunchKernelGGL((tp_backward_kernel<L, LE_>), grid, block, 0, stream, col_ptr, perm, g->dst, rd, h, w, w_row, da, \
+                     dh, dw, dw_max, n, per_xcd, scale)
 #define CASES(L)                                                                        \
   switch (ctx->log2_channels) {                                                         \
     case 3: LAUNCH(L, 3); break;                                                        \

@@ -24,6 +24,7 @@ __global__ __launch_bounds__(256) void tp_segsum_kernel(const int* __restrict__ 
                                                         const float4* __restrict__ rhat_d,
                                                         const float* __restrict__ h,
                                                         const float* __restrict__ w,
+                                                        const int* __restrict__ w_row,
                                                         float* __restrict__ a, int n_owned, int log2E,
                                                         int nodes_per_xcd, float scale) {
   using Mid = typename LayerMid<LMAX>::T;
@@ -51,13 +52,14 @@ __global__ __launch_bounds__(256) void tp_segsum_kernel(const int* __restrict__ 
     const int s = src[k];
     const float4 g = rhat_d[k];
     const float* hp = h + ((size_t)s * D << log2E) + c;
+    const size_t kw = (size_t)egnn_weight_row(w_row, k);
     float v[D], wr[P], o[D];
     if constexpr (HLE == 0) {
-      const float* wp = w + ((size_t)k * P << log2E) + c;
+      const float* wp = w + (kw * P << log2E) + c;
 #pragma unroll
       for (int p = 0; p < P; ++p) wr[p] = __builtin_nontemporal_load(wp + ((size_t)p << log2E));   // streamed once
     } else {
-      w_half_load<P, HLE>(reinterpret_cast<const uint32_t*>(w) + (size_t)k * w_half_row_words(P << HLE), c, wr);
+      w_half_load<P, HLE>(reinterpret_cast<const uint32_t*>(w) + kw * w_half_row_words(P << HLE), c, wr);
     }
 #pragma unroll
     for (int i = 0; i < D; ++i) v[i] = hp[(size_t)i << log2E];
@@ -83,15 +85,16 @@ __global__ __launch_bounds__(256) void tp_segsum_kernel(const int* __restrict__ 
 }
 
 int egnn_launch_tp_segsum(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, const float* h,
-                          const float* w, float* a, hipStream_t stream, bool half) {
+                          const float* w, float* a, hipStream_t stream, bool half, bool shared_rows) {
   const int n = g->n_owned;
   if (n == 0) return EGNN_OK;
   const int per_xcd = (n + 7) / 8;
   dim3 grid(per_xcd * 8), block(256);
   const float scale = 1.0f / sqrtf(ctx->desc.agg_norm);
   const float4* rd = reinterpret_cast<const float4*>(rhat_d);
-#define LAUNCH(L, H)                                                                                   \
-  hipLaunchKernelGGL((tp_segsum_kernel<L, H>), grid, block, 0, stream, g->row_ptr, g->src, rd, h, w, a, \
+  const int* w_row = shared_rows ? g->w_row : nullptr;
+#define LAUNCH(L, H)                                                                                          \
+  hipLaunchKernelGGL((tp_segsum_kernel<L, H>), grid, block, 0, stream, g->row_ptr, g->src, rd, h, w, w_row, a, \
                      n, ctx->log2_channels, per_xcd, scale)
 #define CASE(L)                                                                                  \
   case L:                                                                                        \

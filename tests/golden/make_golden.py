@@ -3,9 +3,12 @@
 
 Calls only oracle/ (plus the seeded input generators).  The full chains take minutes on the CPU, so the GPU
 tests compare against these stored samples instead of re-running the oracle: every layer's output at a
-fixed random set of owned nodes, the H_ij blocks at a fixed random set of edges, and the max-abs of every
-full tensor (the scale of the relative error).  The work is spread over processes by destination-node
-chunks; each chunk goes through the oracle's own functions unchanged.
+fixed set of owned nodes (random ones plus the first and last node, the nodes of least and greatest degree and
+the owned atoms next to the halo), the H_ij blocks at a fixed set of edges (random ones, the first and the last
+64), and the max-abs of every full tensor, of each of its degrees and of each shell block of H (the scales of
+the relative errors).  The work is spread over processes by destination-node chunks; each chunk goes through the
+oracle's own functions unchanged, and tests/test_golden_writer.py checks on config 1 that the chains composed here
+equal the oracle's own composite calls.
 
     python tests/golden/make_golden.py 3 4 5
     python tests/golden/make_golden.py so2:3 so2:4      (SO(2) message sums at sampled nodes)
@@ -30,6 +33,45 @@ N_NODE_SAMPLES = 48
 N_EDGE_SAMPLES = 256
 CHUNK = 96
 _state = {}
+
+
+def aimed_nodes(w, g, rng, n_rows):
+    """Rows to store: a random set plus the rows where an indexing mistake would show first -- the first and the
+    last owned node, the owned nodes of least and greatest degree, and (with a halo) the owned atoms closest to
+    each face of the owned region along every open axis, i.e. the ones whose sources are mostly halo atoms.
+    n_rows = w.n_owned for layer outputs, w.n_total for gradients w.r.t. the input features (then the first and
+    last halo rows are added too)."""
+    row_ptr = g[3]
+    deg = np.diff(row_ptr)
+    picks = [rng.choice(n_rows, N_NODE_SAMPLES, replace=False), [0, w.n_owned - 1, int(np.argmin(deg)), int(np.argmax(deg))]]
+    if w.n_total > w.n_owned:
+        owned = np.asarray(w.pos[:w.n_owned], np.float64)
+        for a in range(3):
+            if not w.pbc[a]:
+                order = np.argsort(owned[:, a], kind="stable")
+                picks += [order[:4], order[-4:]]
+        if n_rows == w.n_total:
+            picks.append([w.n_owned, w.n_total - 1])
+    return np.unique(np.concatenate([np.asarray(p, np.int64) for p in picks]))
+
+
+def aimed_edges(g, rng):
+    """Edges to store: a random set, the first edge, and the last 64 edges (the ragged tail of every edge tiling)."""
+    n_e = len(g[0])
+    return np.unique(np.concatenate([rng.choice(n_e, N_EDGE_SAMPLES, replace=False), [0],
+                                     np.arange(max(0, n_e - 64), n_e)]).astype(np.int64))
+
+
+def maxabs_per_degree(x, lmax):
+    """Largest magnitude of every degree l of a node tensor [n][(lmax+1)^2][E]: the scale a degree's error is judged by."""
+    return np.array([np.abs(x[:, O.sl(l), :]).max() for l in range(lmax + 1)])
+
+
+def maxabs_per_shell_block(H, orb_l):
+    """Largest magnitude of every (alpha, beta) shell block of H [n][n_orb][n_orb]."""
+    off = np.concatenate([[0], np.cumsum([2 * l + 1 for l in orb_l])])
+    return np.array([[np.abs(H[:, off[a]:off[a + 1], off[b]:off[b + 1]]).max() for b in range(len(orb_l))]
+                     for a in range(len(orb_l))])
 
 
 def _messages_chunk(args):
@@ -106,11 +148,10 @@ def _blocks_edges(edges):
 
 def make_blocks(index, pool_size):
     """Node block at sampled owned nodes and edge block at sampled edges of the full-size configuration, inputs from
-    tests/test_gpu_so2_blocks.block_inputs -> config{index}_so2_blocks_samples.npz."""
-    from tests.test_gpu_so2_blocks import block_inputs
+    tests/gpu_util.block_inputs -> config{index}_so2_blocks_samples.npz."""
     t0 = time.time()
     w = synth.workload(index)
-    g, x, T, Wn, We, w_att = block_inputs(w)
+    g, x, T, Wn, We, w_att = U.block_inputs(w)
     rng = np.random.default_rng([w.seed, 4245])
     nodes = np.sort(rng.choice(w.n_owned, N_NODE_SAMPLES, replace=False))
     edges = np.sort(rng.choice(len(g[0]), N_EDGE_SAMPLES, replace=False))
@@ -185,28 +226,29 @@ def make(index, pool_size):
     g = U.oracle_graph(w)
     agg = U.mean_degree(g, w.n_owned)
     rng = np.random.default_rng([w.seed, 4242])
-    nodes = np.sort(rng.choice(w.n_owned, N_NODE_SAMPLES, replace=False))
+    nodes = aimed_nodes(w, g, rng, w.n_owned)
     out = dict(nodes=nodes, n_edges=len(g[0]), agg=agg)
     x = O.species_embed(wt["x0"], w.species, wt["table"])
     for t in range(w.n_layers):
         y = layer_parallel(pool_size, w, g, x, wt["layers"][t], agg)
         out[f"x{t + 1}_rows"] = y[nodes]
         out[f"x{t + 1}_maxabs"] = np.abs(y).max()
+        out[f"x{t + 1}_maxabs_l"] = maxabs_per_degree(y, w.lmax)
         print(f"config {index}: layer {t} done, max|x| {np.abs(y).max():.4f}, {time.time() - t0:.0f} s", flush=True)
         x = np.concatenate([y, wt["halo"][(t + 1) % w.n_layers].astype(np.float64)], axis=0) \
             if w.n_total > w.n_owned else y
     if w.readout:
-        edges = np.sort(rng.choice(len(g[0]), N_EDGE_SAMPLES, replace=False))
+        edges = aimed_edges(g, rng)
         _state.update(w=w, g=g, x=x, Wr=wt["readout"])
-        H = np.zeros((N_EDGE_SAMPLES, w.n_orb, w.n_orb))
+        H = np.zeros((len(edges), w.n_orb, w.n_orb))
         with ProcessPoolExecutor(pool_size) as ex:
             for i, (k0, part) in enumerate(ex.map(_readout_chunk, [(int(k), int(k) + 1) for k in edges])):
                 H[i] = part[0]
-        # scale of the whole tensor: estimated on a larger random sample of edges
+        # scale of the whole tensor and of every shell block: estimated on a larger random sample of edges
         more = np.sort(rng.choice(len(g[0]), 2048, replace=False))
         with ProcessPoolExecutor(pool_size) as ex:
-            mx = max(np.abs(p).max() for _, p in ex.map(_readout_chunk, [(int(k), int(k) + 1) for k in more]))
-        out.update(edges=edges, H_rows=H, H_maxabs=max(mx, np.abs(H).max()))
+            Hm = np.concatenate([p for _, p in ex.map(_readout_chunk, [(int(k), int(k) + 1) for k in more])] + [H])
+        out.update(edges=edges, H_rows=H, H_maxabs=np.abs(Hm).max(), H_maxabs_blocks=maxabs_per_shell_block(Hm, w.orb_l))
         print(f"config {index}: readout done, {time.time() - t0:.0f} s", flush=True)
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"config{index}_samples.npz")
     np.savez_compressed(path, **out)
@@ -277,18 +319,16 @@ def _readout_fwd_bwd_chunk(args):
     return float(np.sum(diff * diff)), dx, gr, np.abs(H).max()
 
 
-def make_training(index, pool_size):
-    t0 = time.time()
-    w = synth.workload(index)
-    wt = U.model_weights(w)
-    g = U.oracle_graph(w)
-    agg = U.mean_degree(g, w.n_owned)
+def training_parallel(pool_size, w, wt, g, agg, T):
+    """Same chain as tests/gpu_util.oracle_training_step (forward, MSE, reverse pass), the loops over destination
+    nodes and over edges spread over processes.  Returns dict(loss, grads, H_maxabs)."""
     n_e = len(g[0])
-    T = synth.normal(np.random.default_rng([w.seed, 99]), (n_e, w.n_orb, w.n_orb))
     xs = [O.species_embed(wt["x0"], w.species, wt["table"])]
     for t in range(w.n_layers):
-        xs.append(layer_parallel(pool_size, w, g, xs[-1], wt["layers"][t], agg))
-        print(f"config {index}: forward layer {t} done, {time.time() - t0:.0f} s", flush=True)
+        y = layer_parallel(pool_size, w, g, xs[-1], wt["layers"][t], agg)
+        xs.append(np.concatenate([y, wt["halo"][(t + 1) % w.n_layers].astype(np.float64)], axis=0)
+                  if w.n_total > w.n_owned else y)
+        print(f"training chain: forward layer {t} done", flush=True)
     _state.update(w=w, g=g, x=xs[-1], Wr=wt["readout"], T=T, n_values=float(T.size))
     sq, dx, g_ro, hmax = 0.0, np.zeros_like(xs[-1]), None, 0.0
     with ProcessPoolExecutor(pool_size) as ex:
@@ -298,19 +338,34 @@ def make_training(index, pool_size):
             dx += dx_part
             hmax = max(hmax, hm)
             g_ro = gr if g_ro is None else {k: g_ro[k] + gr[k] for k in gr}
-    out = dict(loss=sq / T.size, n_edges=n_e, agg=agg, H_maxabs=hmax)
-    out.update({f"readout.{k}": v for k, v in g_ro.items()})
-    print(f"config {index}: readout forward+backward done, loss {out['loss']:.6f}, {time.time() - t0:.0f} s", flush=True)
+    grads = {f"readout.{k}": v for k, v in g_ro.items()}
+    print(f"training chain: readout forward+backward done, loss {sq / T.size:.6f}", flush=True)
     for t in reversed(range(w.n_layers)):
         dx, g_l = layer_backward_parallel(pool_size, w, g, xs[t], wt["layers"][t], agg, dx[:w.n_owned])
-        out.update({f"layer{t}.{k}": v for k, v in g_l.items()})
-        print(f"config {index}: backward layer {t} done, {time.time() - t0:.0f} s", flush=True)
+        grads.update({f"layer{t}.{k}": v for k, v in g_l.items()})
+        print(f"training chain: backward layer {t} done", flush=True)
+    grads["x0"] = dx
+    return dict(loss=sq / T.size, grads=grads, H_maxabs=hmax)
+
+
+def make_training(index, pool_size):
+    t0 = time.time()
+    w = synth.workload(index)
+    wt = U.model_weights(w)
+    g = U.oracle_graph(w)
+    agg = U.mean_degree(g, w.n_owned)
+    n_e = len(g[0])
+    T = synth.normal(np.random.default_rng([w.seed, 99]), (n_e, w.n_orb, w.n_orb))
+    res = training_parallel(pool_size, w, wt, g, agg, T)
+    out = dict(loss=res["loss"], n_edges=n_e, agg=agg, H_maxabs=res["H_maxabs"])
+    dx = res["grads"].pop("x0")
+    out.update(res["grads"])
     rng = np.random.default_rng([w.seed, 4242])
-    nodes = np.sort(rng.choice(w.n_total, N_NODE_SAMPLES, replace=False))
-    out.update(nodes=nodes, x0_rows=dx[nodes], x0_maxabs=np.abs(dx).max())
+    nodes = aimed_nodes(w, g, rng, w.n_total)
+    out.update(nodes=nodes, x0_rows=dx[nodes], x0_maxabs=np.abs(dx).max(), x0_maxabs_l=maxabs_per_degree(dx, w.lmax))
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"config{index}_training.npz")
     np.savez_compressed(path, **out)
-    print("wrote", path, f"{os.path.getsize(path) / 1e3:.0f} kB", flush=True)
+    print("wrote", path, f"{os.path.getsize(path) / 1e3:.0f} kB, {time.time() - t0:.0f} s", flush=True)
 
 
 if __name__ == "__main__":
@@ -324,7 +379,7 @@ if __name__ == "__main__":
         if a.startswith("blocks:"):
             make_blocks(int(a[7:]), procs)
     for idx in which:
-        if idx in (1, 5):          # training step (1 = small self-check of this script against the oracle's own chain)
+        if idx == 5:               # training step
             make_training(idx, procs)
         else:
             make(idx, procs)

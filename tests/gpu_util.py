@@ -35,6 +35,20 @@ def mean_degree(g, n_owned):
     return float(len(g[0])) / max(1, n_owned)
 
 
+def block_inputs(w, seed=0):
+    """Seeded inputs of both sides: node features, edge embeddings with every plane filled, SO(2) weights of the node
+    and of the edge block, attention vector."""
+    g = oracle_graph(w)
+    rng = np.random.default_rng([w.seed if getattr(w, "seed", 0) else 0, 17, seed])
+    x = synth.node_features(rng, w.n_total, w.lmax, w.channels)
+    # (drawn in fp32 directly: at config 4 this tensor has 3.8e9 entries)
+    T = rng.standard_normal(size=(len(g[0]), (w.lmax + 1) ** 2, w.channels), dtype=np.float32)
+    Wn = synth.so2_weights(rng, w.lmax, w.channels, w.n_rbf)
+    We = synth.so2_weights(rng, w.lmax, w.channels, w.n_rbf)
+    w_att = synth.normal(rng, (w.channels,), 2.0 / np.sqrt(w.channels))
+    return g, x, T, Wn, We, w_att
+
+
 def oracle_forward(w, wt, g, agg_norm, with_readout=True, w_dtype=None):
     """Whole model on the oracle: species embedding, n_layers layers, readout.  Returns (xs, H).
     w_dtype: storage precision of the per-edge path weights (None: not rounded)."""
@@ -54,8 +68,9 @@ def oracle_forward(w, wt, g, agg_norm, with_readout=True, w_dtype=None):
     return xs, H
 
 
-def gpu_forward(w, wt, agg_norm, with_readout=True, fused=False, w_fp16=False):
-    """Same model through the C ABI.  Returns (model, graph, xs (device tensors), H)."""
+def gpu_forward(w, wt, agg_norm, with_readout=True, fused=False, w_fp16=False, shared_rows=False):
+    """Same model through the C ABI.  Returns (model, graph, xs (device tensors), H).
+    shared_rows: one row of radial weights per unordered pair of owned atoms (egnn_edge_pairs)."""
     import torch
     from paper_2507_03840_amd import binding as B
     m = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, agg_norm, n_layers=w.n_layers, orb_l=w.orb_l)
@@ -65,6 +80,8 @@ def gpu_forward(w, wt, agg_norm, with_readout=True, fused=False, w_fp16=False):
         m.egnn_set_option(B.OPT_W_FP16, 1)
     pos = B.to_device(w.pos)
     graph = m.egnn_nlist(pos, w.n_owned, w.box, w.pbc)
+    if shared_rows:
+        m.egnn_edge_pairs(graph)
     ws = m.workspace(graph)
     x = B.to_device(wt["x0"])
     m.egnn_species_embed(B.to_device(w.species), B.to_device(wt["table"]), x)
@@ -104,7 +121,7 @@ def oracle_training_step(w, wt, g, agg, T):
     return dict(loss=loss, grads=grads)
 
 
-def gpu_training_step(w, wt, agg, T, repeats=1, timing=None, keep=False):
+def gpu_training_step(w, wt, agg, T, repeats=1, timing=None, keep=False, shared_rows=False):
     """The same step through the C ABI.  Layer inputs are kept; everything else is recomputed in the reverse pass, or
     (keep=True) the radial weights and summed messages of the forward pass are kept and handed back."""
     import torch
@@ -112,6 +129,8 @@ def gpu_training_step(w, wt, agg, T, repeats=1, timing=None, keep=False):
     m = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, agg, n_layers=w.n_layers, orb_l=w.orb_l)
     pos = B.to_device(w.pos)
     graph = m.egnn_nlist(pos, w.n_owned, w.box, w.pbc)
+    if shared_rows:
+        m.egnn_edge_pairs(graph)
     ws = torch.empty(max(m.egnn_backward_workspace_bytes(graph.n_edges, graph.n_owned, graph.n_total),
                          m.egnn_workspace_bytes(graph.n_edges, graph.n_owned, graph.n_total)),
                      dtype=torch.uint8, device="cuda")

@@ -72,6 +72,37 @@ def test_nlist_rejects_small_periodic_box(B):
     assert e.value.code == -2
 
 
+def test_nlist_fill_rejects_another_workspace(B):
+    """The fill pass reuses the cells the count pass left in the workspace: a different workspace or position
+    pointer is refused (EGNN_EINVAL) instead of walking cells that were never built."""
+    import ctypes as C
+    import torch
+    w = _cluster(300, 300, 1, 8, r_cut=4.0, seed=2)
+    m = B.Egnn(1, 8, 8, w.r_cut, 1.0)
+    pos = B.to_device(w.pos)
+    n = w.n_total
+    nbytes = m.egnn_nlist_workspace_bytes(n)
+    ws1 = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    ws2 = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    row_ptr = torch.empty(n + 1, dtype=torch.int32, device="cuda")
+    n_edges = C.c_int64()
+    box = (C.c_float * 3)(*[float(v) for v in w.box])
+    pbc = (C.c_uint8 * 3)(*[int(v) for v in w.pbc])
+    ptr = lambda t: C.c_void_p(t.data_ptr())
+    assert m.lib.egnn_nlist_count(m.ctx, ptr(pos), n, n, box, pbc, ptr(row_ptr), C.byref(n_edges), ptr(ws1),
+                                  C.c_size_t(nbytes), None) == 0
+    src = torch.empty(n_edges.value, dtype=torch.int32, device="cuda")
+    dst = torch.empty_like(src)
+    args = lambda ws, p: (m.ctx, ptr(p), n, n, box, pbc, ptr(row_ptr), C.c_int64(n_edges.value), ptr(src), ptr(dst),
+                          None, ptr(ws), C.c_size_t(nbytes), None)
+    assert m.lib.egnn_nlist_fill(*args(ws2, pos)) == -1
+    assert m.lib.egnn_nlist_fill(*args(ws1, pos.clone())) == -1
+    assert m.lib.egnn_nlist_fill(*args(ws1, pos)) == 0
+    torch.cuda.synchronize()
+    g = U.oracle_graph(w)
+    assert np.array_equal(src.cpu().numpy(), g[0]) and np.array_equal(dst.cpu().numpy(), g[1])
+
+
 # ------------------------------------------------------------------------------------------ S2
 @pytest.mark.parametrize("lmax", [0, 1, 2, 3, 4])
 def test_edge_geometry(B, lmax):

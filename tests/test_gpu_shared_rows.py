@@ -1,0 +1,152 @@
+"""GPU tests of the shared rows of radial weights (egnn_edge_pairs): one row per unordered pair of owned atoms.
+
+The row index is integer work: it is compared entry for entry with a plain numpy construction of the same rule.
+The composite calls on a graph that carries the index must give the same numbers as on the plain graph (the lengths
+of an edge and its reverse are bit-identical, so are their weights) and match the oracle, which knows nothing of
+the sharing: it evaluates the weights of every edge from that edge's own length."""
+import numpy as np
+import pytest
+
+from oracle import egnn_oracle as O
+from paper_2507_03840_amd import synth
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2507_03840_amd import binding
+    binding.load_library()
+    return binding
+
+
+def reference_rows(g, n_owned, n_total):
+    """The rule written out with numpy: edge (i -> j) owns a row if i is a halo atom, if i < j, or if the list has no
+    (j -> i) with the opposite shift; rows numbered in ascending order of the owning edges; the others take the row of
+    their reverse.  Returns (row per edge, owner flag per edge, number of rows)."""
+    src, dst, shift, row_ptr = (np.asarray(a) for a in g)
+    n_e = len(src)
+    key = dst.astype(np.int64) * n_total + src                  # ascending: the list is sorted by (dst, src)
+    rev_key = src.astype(np.int64) * n_total + dst
+    at = np.searchsorted(key, rev_key)
+    at_c = np.minimum(at, max(n_e - 1, 0))
+    found = (at < n_e) & (key[at_c] == rev_key) if n_e else np.zeros(0, bool)
+    if n_e:
+        found &= np.all(shift[at_c].astype(np.int64) == -shift.astype(np.int64), axis=1)
+    owner = (src >= n_owned) | (src < dst) | ~found
+    row = np.full(n_e, -1, np.int64)
+    row[owner] = np.arange(int(owner.sum()))
+    row[~owner] = row[at_c[~owner]]
+    return row, owner, int(owner.sum())
+
+
+def decode(w_row):
+    w_row = np.asarray(w_row, np.int64)
+    return np.where(w_row < 0, ~w_row, w_row), w_row >= 0
+
+
+CASES = {
+    "open-halo": lambda: synth.small_cluster(200, 120, 2, 8, 8, 4.5, 11, False),
+    "periodic": lambda: synth.small_cluster(180, 180, 1, 8, 8, 4.0, 12, True),
+    "periodic-halo": lambda: synth.small_cluster(260, 150, 1, 8, 8, 4.0, 13, True),
+    "config1": lambda: synth.workload(1),
+    "config2": lambda: synth.workload(2),
+    "config3": lambda: synth.workload(3),
+    "config4": lambda: synth.workload(4),
+    "no-owned": lambda: synth.small_cluster(5, 0, 1, 8, 8, 4.0, 3, False),
+    "no-edges": lambda: synth.small_cluster(6, 6, 1, 8, 8, 0.3, 4, False),
+}
+
+
+@pytest.mark.parametrize("case", list(CASES))
+def test_edge_pairs_index_bit_exact(B, case):
+    print("case", case, flush=True)
+    w = CASES[case]()
+    m = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, 1.0)
+    graph = m.egnn_nlist(B.to_device(w.pos), w.n_owned, w.box, w.pbc)
+    m.egnn_edge_pairs(graph)
+    g = (graph.src.cpu().numpy(), graph.dst.cpu().numpy(), graph.shift.cpu().numpy().reshape(-1, 3),
+         graph.row_ptr.cpu().numpy())
+    ref_row, ref_owner, ref_n = reference_rows(g, w.n_owned, w.n_total)
+    assert graph.n_w_rows == ref_n
+    if graph.n_edges == 0:
+        return
+    row, owner = decode(graph.w_row.cpu().numpy())
+    assert np.array_equal(owner, ref_owner) and np.array_equal(row, ref_row)
+    # what the rule is for: the two edges of a row have the same length; halo sources always own their row;
+    # no row serves more than two edges; rows ascend along the list among their owners
+    r = O.edge_vectors(w.pos, w.box, g[0], g[1], g[2])
+    d = np.sqrt((r * r).sum(axis=1))
+    first = np.zeros(ref_n)
+    first[row[owner]] = d[owner]
+    assert np.array_equal(first[row], d)
+    assert np.all(owner[g[0] >= w.n_owned]) and np.bincount(row, minlength=ref_n).max() <= 2
+    assert np.all(np.diff(row[owner]) == 1)
+    if w.n_total == w.n_owned:
+        assert ref_n * 2 == graph.n_edges          # every edge between owned atoms has its reverse
+
+
+def _same(a, b):
+    import torch
+    return torch.equal(a, b)
+
+
+@pytest.mark.parametrize("index", [1, 2])
+@pytest.mark.parametrize("w_fp16", [False, True])
+def test_forward_with_shared_rows_configs(B, index, w_fp16):
+    w = synth.workload(index)
+    wt = U.model_weights(w)
+    g = U.oracle_graph(w)
+    agg = U.mean_degree(g, w.n_owned)
+    m1, g1, xs1, H1 = U.gpu_forward(w, wt, agg, w_fp16=w_fp16)
+    m2, g2, xs2, H2 = U.gpu_forward(w, wt, agg, w_fp16=w_fp16, shared_rows=True)
+    assert g2.w_row is not None and g2.n_w_rows * 2 == g2.n_edges
+    for a, b in zip(xs1, xs2):
+        assert _same(a, b)
+    assert _same(H1, H2)
+    if not w_fp16:
+        xs_ref, H_ref = U.oracle_forward(w, wt, g, agg)
+        assert U.rel_err(xs2[-1].cpu().numpy(), xs_ref[-1]) < U.TOL and U.rel_err(H2.cpu().numpy(), H_ref) < U.TOL
+
+
+@pytest.mark.parametrize("lmax,E,periodic,n,n_owned", [(0, 8, False, 50, 30), (1, 16, True, 150, 90), (2, 32, False, 120, 70),
+                                                      (3, 8, True, 160, 160), (4, 64, False, 90, 40), (4, 128, False, 70, 50)])
+def test_forward_with_shared_rows_small_shapes(B, lmax, E, periodic, n, n_owned):
+    """Halo sources (edges without a reverse), periodic images, every channel count, a part without owned nodes."""
+    print("case", lmax, E, periodic, n, n_owned, flush=True)
+    w = synth.small_cluster(n, n_owned, lmax, E, 8, 4.0, 40 + lmax, periodic)
+    w.n_layers = 2
+    wt = U.model_weights(w)
+    g = U.oracle_graph(w)
+    agg = max(1.0, U.mean_degree(g, w.n_owned))
+    m1, g1, xs1, H1 = U.gpu_forward(w, wt, agg)
+    m2, g2, xs2, H2 = U.gpu_forward(w, wt, agg, shared_rows=True)
+    for a, b in zip(xs1, xs2):
+        assert _same(a, b)
+    assert _same(H1, H2)
+    assert g2.n_w_rows < g2.n_edges
+    xs_ref, H_ref = U.oracle_forward(w, wt, g, agg)
+    assert U.rel_err(xs2[-1].cpu().numpy(), xs_ref[-1]) < U.TOL and U.rel_err(H2.cpu().numpy(), H_ref) < U.TOL
+
+
+@pytest.mark.parametrize("index", [1, 2])
+@pytest.mark.parametrize("keep", [False, True])
+def test_training_step_with_shared_rows(B, index, keep):
+    """Loss and every gradient on a graph with shared rows: identical to the plain graph (the forward weights are the
+    same numbers, the weight gradient dw stays one row per edge) and within the bar of the oracle's reverse pass."""
+    w = synth.workload(index)
+    wt = U.model_weights(w)
+    g = U.oracle_graph(w)
+    agg = U.mean_degree(g, w.n_owned)
+    T = synth.normal(np.random.default_rng([w.seed, 99]), (len(g[0]), w.n_orb, w.n_orb))
+    a = U.gpu_training_step(w, wt, agg, T, keep=keep)
+    b = U.gpu_training_step(w, wt, agg, T, keep=keep, shared_rows=True)
+    assert a["loss"] == b["loss"]
+    for k in a["grads"]:
+        assert np.array_equal(a["grads"][k], b["grads"][k]), k
+    if index == 1:
+        ref = U.oracle_training_step(w, wt, g, agg, T)
+        assert abs(b["loss"] / ref["loss"] - 1) < 1e-5
+        for k, v in ref["grads"].items():
+            assert U.rel_err(b["grads"][k], v) < U.TOL, k

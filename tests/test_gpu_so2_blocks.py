@@ -21,18 +21,7 @@ def B():
     return binding
 
 
-def block_inputs(w, seed=0):
-    """Seeded inputs of both sides: node features, edge embeddings with every plane filled, SO(2) weights of the node
-    and of the edge block, attention vector."""
-    g = U.oracle_graph(w)
-    rng = np.random.default_rng([w.seed if getattr(w, "seed", 0) else 0, 17, seed])
-    x = synth.node_features(rng, w.n_total, w.lmax, w.channels)
-    # (drawn in fp32 directly: at config 4 this tensor has 3.8e9 entries)
-    T = rng.standard_normal(size=(len(g[0]), (w.lmax + 1) ** 2, w.channels), dtype=np.float32)
-    Wn = synth.so2_weights(rng, w.lmax, w.channels, w.n_rbf)
-    We = synth.so2_weights(rng, w.lmax, w.channels, w.n_rbf)
-    w_att = synth.normal(rng, (w.channels,), 2.0 / np.sqrt(w.channels))
-    return g, x, T, Wn, We, w_att
+block_inputs = U.block_inputs
 
 
 def run_blocks(B, w, seed=0):
