@@ -499,3 +499,68 @@ def test_radial_weights_are_shared_by_an_edge_and_its_reverse():
     for j in range(wl.n_owned):
         row = src[row_ptr[j]:row_ptr[j + 1]]
         assert np.all(np.diff(row) > 0)
+
+
+# ------------------------------------------------------------------ node initialisation, row order of the radial output layer
+def test_species_embed_hand_value_touches_only_the_scalar_plane():
+    """Sec. 3 "Initialization", Fig. 2(a): the species enters the (L=0, M=0) plane and nothing else.  Three atoms,
+    two species, l_max 1, two channels, worked by hand."""
+    x = np.arange(3 * 4 * 2, dtype=np.float64).reshape(3, 4, 2)
+    table = np.array([[100.0, 200.0], [-1.0, -2.0]])
+    y = O.species_embed(x, np.array([1, 0, 1]), table)
+    assert y.shape == x.shape and x[0, 0, 0] == 0.0            # the input is not modified
+    expect = x.copy()
+    expect[0, 0] += [-1.0, -2.0]
+    expect[1, 0] += [100.0, 200.0]
+    expect[2, 0] += [-1.0, -2.0]
+    assert np.array_equal(y, expect)
+    assert np.array_equal(y[:, 1:, :], x[:, 1:, :])            # planes with l >= 1 untouched
+    assert y[1, 0, 1] == x[1, 0, 1] + 200.0                    # table[species][channel], not [channel][species]
+
+
+def test_radial_weights_row_order_is_path_major_channel_minor():
+    """Row p*E + c of W_r2 feeds w[k, p, c].  One hidden unit, W_r2 row r = r + 1: every output then names its row,
+    w[0, p, c] = f_c alpha_p g (p E + c + 1).  A (E, P) reading of the rows would give (c P + p + 1) instead."""
+    paths = O.tp_paths(2, 2, 2)
+    P, E, n_rbf, r_cut = len(paths), 3, 2, 6.0
+    W_r1 = np.ones((1, n_rbf))
+    W_r2 = (np.arange(P * E, dtype=np.float64) + 1.0).reshape(P * E, 1)
+    d = np.array([3.0, 1.0])
+    w = O.radial_weights(d, W_r1, W_r2, paths, E, n_rbf, r_cut)
+    assert w.shape == (2, P, E)
+    alpha = O.path_norm(paths)
+    for k, dk in enumerate(d):
+        pre = np.exp(-dk ** 2 / 72.0) + np.exp(-(dk - 6.0) ** 2 / 72.0)      # centres 0 and 6, sigma 6
+        g = pre / (1.0 + np.exp(-pre))
+        fc = 0.5 * (1.0 + np.cos(pi * dk / 6.0))
+        rows = np.arange(P)[:, None] * E + np.arange(E)[None, :] + 1.0
+        assert np.allclose(w[k], fc * g * alpha[:, None] * rows, rtol=1e-13, atol=0)
+    # the wrong reading differs (so the assertion above can fail)
+    wrong = (np.arange(E)[None, :] * P + np.arange(P)[:, None] + 1.0)
+    assert not np.allclose(w[0], 0.5 * alpha[:, None] * wrong * (w[0, 0, 0] / (0.5 * alpha[0])))
+
+
+def test_radial_weights_backward_one_hot_dw_lands_in_row_pE_plus_c():
+    """Adjoint of the same layout: a gradient on w[k, p, c] alone reaches row p*E + c of dW_r2 and no other, with
+    the value f_c alpha_p g_j; and dW_r1 = sum over that row's hidden units of W_r2[pE+c, j] SiLU'(pre_j) B."""
+    paths = O.tp_paths(2, 2, 2)
+    P, E, n_rbf, r_cut, n_hid = len(paths), 3, 2, 6.0, 2
+    rng = np.random.default_rng(11)
+    W_r1 = rng.standard_normal((n_hid, n_rbf))
+    W_r2 = rng.standard_normal((P * E, n_hid))
+    d = np.array([2.5])
+    alpha = O.path_norm(paths)
+    B = np.array([np.exp(-d[0] ** 2 / 72.0), np.exp(-(d[0] - 6.0) ** 2 / 72.0)])
+    pre = W_r1 @ B
+    sig = 1.0 / (1.0 + np.exp(-pre))
+    fc = 0.5 * (1.0 + np.cos(pi * d[0] / 6.0))
+    for (p, c) in [(0, 0), (4, 2), (P - 1, 1)]:
+        dw = np.zeros((1, P, E))
+        dw[0, p, c] = 1.0
+        dW_r1, dW_r2 = O.radial_weights_backward(d, W_r1, W_r2, paths, E, n_rbf, r_cut, dw)
+        expect2 = np.zeros((P * E, n_hid))
+        expect2[p * E + c] = fc * alpha[p] * pre * sig
+        assert np.allclose(dW_r2, expect2, rtol=1e-13, atol=1e-16)
+        dsilu = sig * (1.0 + pre * (1.0 - sig))
+        expect1 = (fc * alpha[p] * W_r2[p * E + c] * dsilu)[:, None] * B[None, :]
+        assert np.allclose(dW_r1, expect1, rtol=1e-13, atol=1e-16)
