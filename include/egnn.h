@@ -149,6 +149,18 @@ int egnn_edge_geometry(egnn_ctx* ctx, const egnn_graph* g, const float* pos, con
 int egnn_radial_weights(egnn_ctx* ctx, int which, const float* rhat_d, int64_t n_edges,
                         const float* W_r1, const float* W_r2, float* w, void* ws, size_t ws_bytes, void* stream);
 
+/* egnn_radial_weights without a workspace argument, for callers that cannot allocate device memory (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation): the scratch that egnn_radial_weights
+ * takes from the caller (scalings and half-precision pieces of W_r2) lives in a device array built into the
+ * library, 2,064,384 bytes per GPU (the largest supported shape: 42 paths x 128 channels), held until the process
+ * ends.  The call allocates and frees nothing and enqueues kernels only; it computes exactly what
+ * egnn_radial_weights computes (bit-identical).  Shapes with paths * channels > 5,376 are rejected with EGNN_EWS.
+ * All calls on one GPU share that array: calls that overlap in time on one GPU (different streams or threads) race;
+ * calls on one stream are safe.  The array's address is looked up per device in egnn_create (or on the first call
+ * on a device, which should then not be under capture).  rhat_d and w may be NULL when n_edges is 0. */
+int egnn_radial_weights_static(egnn_ctx* ctx, int which, const float* rhat_d, int64_t n_edges, const float* W_r1,
+                               const float* W_r2, float* w, void* stream);
+
 /* ---- S4  tensor-product messages summed over incoming edges (Sec. 3 "Message passing";
  *          Sec. 2.1, 2.2, Eq. 1 for the coupling) ----
  * a[j][(l3,m3)][c] = agg_norm^-1/2 * sum_{k: dst(k)=j} sum_p w[k][p][c] *

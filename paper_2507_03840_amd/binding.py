@@ -26,7 +26,7 @@ SYMBOLS = [
     "egnn_hamiltonian_structure", "egnn_hamiltonian_fill", "egnn_onsite_backward_workspace_bytes", "egnn_onsite_backward",
     "egnn_partition_low_nn", "egnn_pack_rows", "egnn_unpack_rows",
     "egnn_layer_forward_save", "egnn_readout_hij_save", "egnn_layer_backward_saved", "egnn_readout_backward_saved",
-    "egnn_edge_pairs_workspace_bytes", "egnn_edge_pairs",
+    "egnn_radial_weights_static", "egnn_edge_pairs_workspace_bytes", "egnn_edge_pairs",
 ]
 
 
@@ -256,6 +256,13 @@ class Egnn:
         self._check(self.lib.egnn_radial_weights(self.ctx, which, _ptr(rhat_d), C.c_int64(n), _ptr(W_r1), _ptr(W_r2),
                                                  _ptr(w), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
         return w
+
+    def egnn_radial_weights_static(self, which, rhat_d, W_r1, W_r2, out):
+        """The same weights through the entry point that allocates nothing: `out` must be preallocated."""
+        n = rhat_d.shape[0]
+        self._check(self.lib.egnn_radial_weights_static(self.ctx, which, _ptr(rhat_d), C.c_int64(n), _ptr(W_r1),
+                                                        _ptr(W_r2), _ptr(out), _stream()))
+        return out
 
     def egnn_radial_weights_f16(self, which, rhat_d, W_r1, W_r2):
         """Half-precision weights, packed: int32 tensor [n_edges][32 * ceil(P * channels / 64)]."""

@@ -106,6 +106,7 @@ extern "C" int egnn_create(const egnn_model_desc* d, egnn_ctx** out) {
       ctx->unc_c.push_back(e.second);
     }
   }
+  egnn_static_scratch_prepare();   // set-up step of egnn_radial_weights_static (does nothing without a GPU)
   *out = ctx;
   return EGNN_OK;
 }

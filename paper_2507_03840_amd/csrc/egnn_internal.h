@@ -135,6 +135,8 @@ int egnn_launch_tp_segsum(egnn_ctx*, const egnn_graph*, const float* rhat_d, con
                           float* a, hipStream_t, bool half = false, bool shared_rows = false);
 int egnn_launch_radial(egnn_ctx*, int which, const float* rhat_d, int64_t n_edges, const float* W_r1,
                        const float* W_r2, float* w, void* scratch, hipStream_t, bool half = false);
+// looks up the address of the built-in scratch array of egnn_radial_weights_static on the current device, if there is one
+void egnn_static_scratch_prepare();
 size_t egnn_w_bytes(const egnn_ctx*, int which, int64_t n_edges);   // room for w in either precision
 size_t egnn_radial_ws_bytes(const egnn_ctx*, int which);
 int egnn_launch_split_w2(egnn_ctx*, int which, const float* W_r2, void* scratch, hipStream_t);
