@@ -92,15 +92,27 @@ __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ sr
   // serves their rows of zs and zt
   const long tile = (long)(blockIdx.x & 7) * tiles_per_xcd + (blockIdx.x >> 3);
   const long k_base = tile * n_slots * RO_ITERS;
+  // The indices of an edge (source, destination, weight row) and its unit vector are fetched one edge ahead, so that
+  // the loads of the rows they address start at once.
+  int s_nx = 0, d_nx = 0;
+  size_t kw_nx = 0;
+  float4 g_nx = make_float4(0.0f, 0.0f, 1.0f, 1.0f);
+  if (k_base + slot < n_edges) {
+    const long k = k_base + slot;
+    s_nx = src[k];
+    d_nx = dst[k];
+    g_nx = rhat_d[k];
+    kw_nx = (size_t)egnn_weight_row(w_row, k);
+  }
   for (int it = 0; it < RO_ITERS; ++it) {
     const long k = k_base + (long)it * n_slots + slot;
     const bool live = k < n_edges;
     if (live) {
-      const int s = src[k], d = dst[k];
-      const float4 g = rhat_d[k];
+      const int s = s_nx, d = d_nx;
+      const float4 g = g_nx;
+      const size_t kw = kw_nx;
       const float* zsp = zs + ((size_t)s * D << log2E) + c;
       const float* ztp = zt + ((size_t)d * D << log2E) + c;
-      const size_t kw = (size_t)egnn_weight_row(w_row, k);
       float v[D], wr[P], o[RO_D];
       if constexpr (!HALF) {
         const float* wp = w + (kw * P << log2E) + c;
@@ -111,6 +123,13 @@ __global__ __launch_bounds__(256) void readout_kernel(const int* __restrict__ sr
       }
 #pragma unroll
       for (int i = 0; i < D; ++i) v[i] = zsp[(size_t)i << log2E] + ztp[(size_t)i << log2E];
+      const long kn = k + n_slots;
+      if (it + 1 < RO_ITERS && kn < n_edges) {
+        s_nx = src[kn];
+        d_nx = dst[kn];
+        g_nx = rhat_d[kn];
+        kw_nx = (size_t)egnn_weight_row(w_row, kn);
+      }
       BondTrig t;
       egnn_bond_trig<4>(g.x, g.y, g.z, t);
       egnn_to_bond_frame<LMAX>(v, t);

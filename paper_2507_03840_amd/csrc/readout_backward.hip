@@ -167,6 +167,12 @@ __global__ __launch_bounds__(256, 3) void readout_backward_kernel(
   __syncthreads();
 
   const long k_base = (long)blockIdx.x * n_slots * iters;
+  // (the weight row of an edge is looked up one edge ahead: its loads then do not wait for the index)
+  size_t kw_nx;
+  {
+    const long k_first = k_base + slot;
+    kw_nx = (size_t)egnn_weight_row(w_row, k_first < n_edges ? k_first : n_edges - 1);
+  }
   for (int it = 0; it < iters; ++it) {
     // A slot past the end works on the last edge with dH = 0 (every lane takes part in the butterflies) and
     // stores nothing.
@@ -178,10 +184,14 @@ __global__ __launch_bounds__(256, 3) void readout_backward_kernel(
     // round trip per edge instead of one for dH and another for the weights.
     const float4 g = rhat_d[k];
     const int s = src[k], d = dst[k];
-    const float* wp = w + ((size_t)egnn_weight_row(w_row, k) * P << log2E) + c;   // (dw stays one row per edge)
+    const float* wp = w + (kw_nx * P << log2E) + c;   // (dw stays one row per edge)
     float wr[P];
 #pragma unroll
     for (int p = 0; p < P; ++p) wr[p] = __builtin_nontemporal_load(wp + ((size_t)p << log2E));
+    {
+      const long k_next = k_own + n_slots;
+      kw_nx = (size_t)egnn_weight_row(w_row, k_next < n_edges ? k_next : n_edges - 1);
+    }
     {
       const float* hrow = dH + (size_t)k * tb.nq;
       for (int q = c; q < tb.nq; q += E) sh[q] = live ? hrow[q] : 0.0f;

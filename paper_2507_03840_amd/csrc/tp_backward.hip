@@ -65,12 +65,24 @@ __global__ __launch_bounds__(256, 2) void tp_backward_kernel(const int* __restri
     acc[q] = 0.0f;
   }
 
+  // The edge id, its destination, weight row and unit vector are fetched one edge ahead (a chain of three dependent
+  // loads: position in the source's list -> edge -> destination / weight row), so that the row loads of an edge start
+  // as soon as its turn comes.
+  int k_nx = 0, j_nx = 0;
+  size_t kw_nx = 0;
+  float4 g_nx = make_float4(0.0f, 0.0f, 1.0f, 1.0f);
+  if (c0 + slot < c1) {
+    k_nx = perm[c0 + slot];
+    j_nx = dst[k_nx];
+    g_nx = rhat_d[k_nx];
+    kw_nx = (size_t)egnn_weight_row(w_row, k_nx);
+  }
   for (int idx = c0 + slot; idx < c1; idx += n_slots) {
-    const int k = perm[idx];
-    const int j = dst[k];
-    const float4 g = rhat_d[k];
+    const int k = k_nx;
+    const int j = j_nx;
+    const float4 g = g_nx;
     const float* gp = da + ((size_t)j * D << log2E) + c;
-    const float* wp = w + ((size_t)egnn_weight_row(w_row, k) * P << log2E) + c;   // (dw stays one row per edge)
+    const float* wp = w + (kw_nx * P << log2E) + c;   // (dw stays one row per edge)
     float* dwp = dw + ((size_t)k * P << log2E) + c;
     float v[D], go[D], gv[D], wr[P];
 #pragma unroll
@@ -79,6 +91,12 @@ __global__ __launch_bounds__(256, 2) void tp_backward_kernel(const int* __restri
     for (int q = 0; q < D; ++q) {
       v[q] = v0[q];
       go[q] = scale * gp[(size_t)q << log2E];
+    }
+    if (idx + n_slots < c1) {
+      k_nx = perm[idx + n_slots];
+      j_nx = dst[k_nx];
+      g_nx = rhat_d[k_nx];
+      kw_nx = (size_t)egnn_weight_row(w_row, k_nx);
     }
     BondTrig t;
     egnn_bond_trig<LMAX>(g.x, g.y, g.z, t);

@@ -48,11 +48,19 @@ __global__ __launch_bounds__(256) void tp_segsum_kernel(const int* __restrict__ 
 #pragma unroll
   for (int i = 0; i < D; ++i) acc[i] = 0.0f;
 
-  for (int k = k0 + slot; k < k1; k += n_slots) {
-    const int s = src[k];
-    const float4 g = rhat_d[k];
+  // The indices of an edge (source, weight row) and its unit vector are fetched one edge ahead: the loads of the rows
+  // they address then start at once instead of waiting out a second memory round trip per edge.
+  int k = k0 + slot;
+  int s = 0;
+  size_t kw = 0;
+  float4 g = make_float4(0.0f, 0.0f, 1.0f, 1.0f);
+  if (k < k1) {
+    s = src[k];
+    g = rhat_d[k];
+    kw = (size_t)egnn_weight_row(w_row, k);
+  }
+  for (; k < k1; k += n_slots) {
     const float* hp = h + ((size_t)s * D << log2E) + c;
-    const size_t kw = (size_t)egnn_weight_row(w_row, k);
     float v[D], wr[P], o[D];
     if constexpr (HLE == 0) {
       const float* wp = w + (kw * P << log2E) + c;
@@ -63,8 +71,15 @@ __global__ __launch_bounds__(256) void tp_segsum_kernel(const int* __restrict__ 
     }
 #pragma unroll
     for (int i = 0; i < D; ++i) v[i] = hp[(size_t)i << log2E];
+    const float4 g_now = g;
+    const int kn = k + n_slots;
+    if (kn < k1) {
+      s = src[kn];
+      g = rhat_d[kn];
+      kw = (size_t)egnn_weight_row(w_row, kn);
+    }
     BondTrig t;
-    egnn_bond_trig<LMAX>(g.x, g.y, g.z, t);
+    egnn_bond_trig<LMAX>(g_now.x, g_now.y, g_now.z, t);
     egnn_to_bond_frame<LMAX>(v, t);
     Mid::run(v, wr, o);
     egnn_from_bond_frame<LMAX>(o, t);
