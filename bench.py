@@ -318,6 +318,7 @@ def run_config(args, index, extras):
                           dtype=torch.uint8, device="cuda")
         graph = build_graph()
         col_ptr, perm = m.egnn_graph_transpose(graph, bws)
+        m.egnn_length_bins(graph, pos, w.box)      # (with the transpose: the per-graph indices of the reverse pass)
         target = B.to_device(synth.normal(np.random.default_rng([w.seed, 99]), (n_edges, w.n_orb, w.n_orb)))
 
         def train_step(keep=False):

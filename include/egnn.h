@@ -73,6 +73,9 @@ typedef struct {
   const int32_t* w_row;   /* [n_edges] row of radial weights edge k reads: w_row[k] if >= 0 (the edge owns the row),
                              ~w_row[k] (bitwise complement) if negative (the row belongs to the reverse edge) */
   int64_t n_w_rows;       /* number of rows */
+  /* Optional, from egnn_length_bins (NULL: the reverse pass builds them in every call that needs them): */
+  const int32_t* len_ptr;  /* [EGNN_LENGTH_BINS + 1] */
+  const int32_t* len_perm; /* [n_edges] edge ids grouped by length interval, ascending inside an interval */
 } egnn_graph;
 
 int egnn_create(const egnn_model_desc* desc, egnn_ctx** out);
@@ -129,6 +132,17 @@ int egnn_nlist_fill(egnn_ctx* ctx, const float* pos, int32_t n_owned, int32_t n_
 int egnn_edge_pairs_workspace_bytes(const egnn_ctx* ctx, int32_t n_owned, size_t* bytes);
 int egnn_edge_pairs(egnn_ctx* ctx, const egnn_graph* g, int32_t* w_row, int64_t* n_rows, void* ws, size_t ws_bytes,
                     void* stream);
+
+/* ---- edges grouped by length (an index of the reverse pass, like egnn_graph_transpose) ----
+ * Interval m of EGNN_LENGTH_BINS holds the edges with |r_k| in [m, m+1) * r_cut / EGNN_LENGTH_BINS; len_perm lists
+ * the edge ids interval by interval (len_ptr[m] .. len_ptr[m+1]), ascending inside an interval.  The reverse pass of
+ * the radial MLP in its grid form (EGNN_OPT_RADIAL_BWD) adds the rows of dw in this order; a graph that carries the
+ * two arrays saves every backward call from building them (they depend on the geometry only).
+ * ws: egnn_length_bins_workspace_bytes, 256-byte aligned. */
+#define EGNN_LENGTH_BINS 2048
+int egnn_length_bins_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, size_t* bytes);
+int egnn_length_bins(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3], int32_t* len_ptr,
+                     int32_t* len_perm, void* ws, size_t ws_bytes, void* stream);
 
 /* ---- node initialisation (Sec. 3: the L=0 plane carries the atomic species) ----
  * x[i][0][c] += table[species[i]][c]. */
@@ -203,6 +217,14 @@ int egnn_node_mix(egnn_ctx* ctx, const float* x1, const float* W1, const float* 
  * calls at a relative rounding error of 2^-12 per weight: a reduced-precision mode, not covered by the fp32 accuracy
  * statement of the default.  Caller-supplied w_edge and the reverse pass always use fp32 weights. */
 #define EGNN_OPT_W_FP16 2
+/* EGNN_OPT_RADIAL_BWD (default 0): how egnn_layer_backward / egnn_readout_backward (and their _saved forms) turn the
+ * gradient dw of the radial weights into dW_r1 and dW_r2.  1: two contractions on the matrix cores, each streaming dw.
+ * 2: one pass over dw that bins its rows on a grid of 2,048 distances with six-point Lagrange weights, followed by two
+ * small dense products over the grid points (everything but dw depends on the edge through its length only);
+ * interpolation error below 1e-8 of the result while the absolute row sums of W_r1 stay below 100, 1e-6 at 256.
+ * 0: decided on the device per call: route 2 if max_j sum_b |W_r1[j][b]| <= 256, else route 1.  Both are
+ * deterministic. */
+#define EGNN_OPT_RADIAL_BWD 3
 int egnn_set_option(egnn_ctx* ctx, int32_t option, int32_t value);
 
 /* ---- one message-passing layer, forward: S2 -> S5(pre) -> S3+S4 fused (or S3 -> S4) -> S5(post) ----

@@ -13,6 +13,8 @@ LIB_PATH = os.path.join(_HERE, "libegnn_hip.so")
 MAX_SHELLS = 8
 OPT_FUSED = 1
 OPT_W_FP16 = 2
+LENGTH_BINS = 2048
+OPT_RADIAL_BWD = 3   # 0: route chosen on the device, 1: exact (matrix cores, two passes over dw), 2: grid of distances (one pass)
 
 SYMBOLS = [
     "egnn_create", "egnn_destroy", "egnn_last_error", "egnn_path_count", "egnn_readout_widths",
@@ -27,6 +29,7 @@ SYMBOLS = [
     "egnn_partition_low_nn", "egnn_pack_rows", "egnn_unpack_rows",
     "egnn_layer_forward_save", "egnn_readout_hij_save", "egnn_layer_backward_saved", "egnn_readout_backward_saved",
     "egnn_radial_weights_static", "egnn_edge_pairs_workspace_bytes", "egnn_edge_pairs",
+    "egnn_length_bins_workspace_bytes", "egnn_length_bins",
 ]
 
 
@@ -40,7 +43,7 @@ class ModelDesc(C.Structure):
 class GraphDesc(C.Structure):
     _fields_ = [("src", C.c_void_p), ("dst", C.c_void_p), ("row_ptr", C.c_void_p), ("shift", C.c_void_p),
                 ("n_edges", C.c_int64), ("n_owned", C.c_int32), ("n_total", C.c_int32),
-                ("w_row", C.c_void_p), ("n_w_rows", C.c_int64)]
+                ("w_row", C.c_void_p), ("n_w_rows", C.c_int64), ("len_ptr", C.c_void_p), ("len_perm", C.c_void_p)]
 
 
 class EgnnError(RuntimeError):
@@ -89,16 +92,21 @@ class Graph:
         self.src, self.dst, self.row_ptr, self.shift = src, dst, row_ptr, shift
         self.n_edges, self.n_owned, self.n_total = int(src.numel()), int(n_owned), int(n_total)
         self.w_row, self.n_w_rows = None, 0      # set by Egnn.egnn_edge_pairs: shared rows of radial weights
+        self.len_ptr, self.len_perm = None, None # set by Egnn.egnn_length_bins: edges grouped by length (reverse pass)
 
     def desc(self):
         return GraphDesc(_ptr(self.src).value, _ptr(self.dst).value, _ptr(self.row_ptr).value,
                          _ptr(self.shift).value if self.shift is not None else None,
                          self.n_edges, self.n_owned, self.n_total,
-                         _ptr(self.w_row).value if self.w_row is not None else None, int(self.n_w_rows))
+                         _ptr(self.w_row).value if self.w_row is not None else None, int(self.n_w_rows),
+                         _ptr(self.len_ptr).value if self.len_ptr is not None else None,
+                         _ptr(self.len_perm).value if self.len_perm is not None else None)
 
     def per_edge(self):
         """The same edge list without shared rows of radial weights."""
-        return Graph(self.src, self.dst, self.row_ptr, self.shift, self.n_owned, self.n_total)
+        g = Graph(self.src, self.dst, self.row_ptr, self.shift, self.n_owned, self.n_total)
+        g.len_ptr, g.len_perm = self.len_ptr, self.len_perm
+        return g
 
     @property
     def n_weight_rows(self):
@@ -228,6 +236,19 @@ class Egnn:
         self._check(self.lib.egnn_edge_pairs(self.ctx, C.byref(g), _ptr(w_row), C.byref(n_rows), _ptr(ws),
                                              C.c_size_t(ws.numel()), _stream()))
         graph.w_row, graph.n_w_rows = w_row, n_rows.value
+        return graph
+
+    def egnn_length_bins(self, graph, pos, box):
+        """Sets graph.len_ptr / graph.len_perm (edges grouped by length interval, for the reverse pass)."""
+        out = C.c_size_t()
+        self._check(self.lib.egnn_length_bins_workspace_bytes(self.ctx, C.c_int64(graph.n_edges), C.byref(out)))
+        ws = torch.empty(max(256, out.value), dtype=torch.uint8, device="cuda")
+        len_ptr = torch.empty(LENGTH_BINS + 1, dtype=torch.int32, device="cuda")
+        len_perm = torch.empty(graph.n_edges, dtype=torch.int32, device="cuda")
+        g = graph.desc()
+        self._check(self.lib.egnn_length_bins(self.ctx, C.byref(g), _ptr(pos), _f3(box), _ptr(len_ptr), _ptr(len_perm),
+                                              _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+        graph.len_ptr, graph.len_perm = len_ptr, len_perm
         return graph
 
     # ---- node init

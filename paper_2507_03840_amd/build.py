@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libegnn_hip.so")
 SOURCES = ["egnn_api.hip", "egnn_api_backward.hip", "nlist.hip", "edge_radial.hip", "node_mix.hip", "tp_segsum.hip",
            "readout.hip", "layer_fused.hip", "layer_fused_lane.hip", "graph_util.hip", "tp_backward.hip", "radial_backward.hip", "readout_backward.hip",
-           "so2_message.hip", "hamiltonian.hip", "partition.hip", "static_scratch.hip", "edge_pairs.hip"]
+           "so2_message.hip", "hamiltonian.hip", "partition.hip", "static_scratch.hip", "edge_pairs.hip", "radial_grid.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          # keep the compiler from forming packed fp32 instructions

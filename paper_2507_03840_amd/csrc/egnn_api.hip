@@ -179,6 +179,11 @@ extern "C" int egnn_set_option(egnn_ctx* ctx, int32_t option, int32_t value) {
     ctx->w_half = value != 0;
     return EGNN_OK;
   }
+  if (option == EGNN_OPT_RADIAL_BWD) {
+    if (value < 0 || value > 2) return egnn_fail(ctx, EGNN_EINVAL, "set_option: EGNN_OPT_RADIAL_BWD takes 0, 1 or 2");
+    ctx->radial_bwd_route = value;
+    return EGNN_OK;
+  }
   return egnn_fail(ctx, EGNN_EINVAL, "set_option: unknown option");
 }
 

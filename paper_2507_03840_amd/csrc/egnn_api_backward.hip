@@ -166,7 +166,8 @@ static int layer_backward_impl(egnn_ctx* ctx, const egnn_graph* g, const int32_t
   if ((rc = egnn_launch_mix_wgrad(ctx, b.dh, x_in, dW_pre, b.wgrad_partial, n_t, st))) return rc;
   tm.mark(3);
   // radial MLP
-  rc = egnn_launch_radial_backward(ctx, 0, b.rhat_d, g->n_edges, W_r1, W_r2, b.dw, dW_r1, dW_r2, b.radial, true, st);
+  rc = egnn_launch_radial_backward(ctx, 0, b.rhat_d, g->n_edges, W_r1, W_r2, b.dw, dW_r1, dW_r2, b.radial, true, st,
+                                   g->len_ptr, g->len_perm);
   tm.mark(4);
   return rc;
 }
@@ -270,7 +271,8 @@ static int readout_backward_impl(egnn_ctx* ctx, const egnn_graph* g, const int32
   if ((rc = egnn_launch_mix_wgrad(ctx, b.dzs, x, dW_s, b.wgrad_partial, n_t, st))) return rc;
   if ((rc = egnn_launch_mix_wgrad(ctx, b.dzt, x, dW_t, b.wgrad_partial, n_t, st))) return rc;
   tm.mark(2);
-  rc = egnn_launch_radial_backward(ctx, 1, b.rhat_d, g->n_edges, W_r1, W_r2, b.dw, dW_r1, dW_r2, b.radial, false, st);   // (no running maximum of this dw: bf16 pieces)
+  rc = egnn_launch_radial_backward(ctx, 1, b.rhat_d, g->n_edges, W_r1, W_r2, b.dw, dW_r1, dW_r2, b.radial, false, st,
+                                   g->len_ptr, g->len_perm);   // (no running maximum of this dw: bf16 pieces on the exact route)
   tm.mark(3);
   tm.mark(4);
   return rc;

@@ -40,6 +40,7 @@ struct egnn_ctx {
   const void* nl_grid_pos = nullptr;
   int use_fused = 0;                     // egnn_set_option(EGNN_OPT_FUSED): 0 two kernels, 1 / 2 the fused designs
   bool w_half = false;                   // egnn_set_option(EGNN_OPT_W_FP16)
+  int radial_bwd_route = 0;              // egnn_set_option(EGNN_OPT_RADIAL_BWD): 0 decided on the device, 1 exact, 2 grid
   // index tables of the readout / on-site kernels in the order the kernels read them, built on first use and kept:
   // the asynchronous uploads into the caller's workspace read this memory, which lives as long as the context
   std::vector<int> tab_ro_i, tab_rob_i, tab_on_i, tab_onb_i;
@@ -109,8 +110,19 @@ int egnn_launch_row_scan(egnn_ctx*, int* row_ptr, int n, hipStream_t);
 int egnn_launch_fill_int(egnn_ctx*, int* p, long n, int v, hipStream_t);
 int egnn_launch_segsum_rows(egnn_ctx*, const float* rows, const int* ptr, const int* perm, float* out, int n_segments,
                             int row_len, hipStream_t);
+// skip (may be NULL): a device word; the kernels return at once if it is non-zero
 int egnn_launch_reduce_partials(egnn_ctx*, float* partial /* scratch, may be overwritten */, int n_partials, long n, float* out, float scale,
-                                hipStream_t);
+                                hipStream_t, const int* skip = nullptr);
+// the radial MLP's reverse pass by interpolation on a grid of distances (radial_grid.hip)
+size_t egnn_radial_grid_ws_bytes(const egnn_ctx*, int which, int64_t n_edges);
+int egnn_launch_radial_route(egnn_ctx*, const float* W_r1, int* route, hipStream_t);
+int egnn_launch_length_bins(egnn_ctx*, const float4* rd, int64_t n_edges, int* bin_ptr, int* perm, int* key, int* bucket,
+                            int* cursor, const int* route, hipStream_t);
+int egnn_launch_radial_grid(egnn_ctx*, int which, const float* rhat_d, int64_t n_edges, const int* len_ptr,
+                            const int* len_perm, const float* W_r1,
+                            const float* W_r2, const float* dw, float* dW_r1, float* dW_r2, void* ws, const int* route,
+                            int (*hidden_launch)(egnn_ctx*, const float*, long, const float*, float*, float*, hipStream_t),
+                            hipStream_t);
 size_t egnn_transpose_ws_bytes(int64_t n_edges, int32_t n_total);
 // dw_max (may be NULL): a word the caller has set to zero; raised to the bit pattern of the largest |dw| written
 int egnn_launch_tp_backward(egnn_ctx*, const egnn_graph*, const int* col_ptr, const int* perm, const float* rhat_d,
@@ -119,9 +131,11 @@ int egnn_launch_tp_backward(egnn_ctx*, const egnn_graph*, const int* col_ptr, co
 size_t egnn_radial_backward_ws_bytes(const egnn_ctx*, int which, int64_t n_edges);
 // dw_max_valid: the first word of ws (egnn_radial_backward_dw_max) holds the bit pattern of the largest |dw|; the
 // two large contractions then run on half-precision pieces, otherwise on bf16 pieces (which need no scaling)
+// len_ptr / len_perm (may be NULL): the edges grouped by length interval (egnn_length_bins), for the grid route
 int egnn_launch_radial_backward(egnn_ctx*, int which, const float* rhat_d, int64_t n_edges, const float* W_r1,
                                 const float* W_r2, const float* dw, float* dW_r1, float* dW_r2, void* ws,
-                                bool dw_max_valid, hipStream_t);
+                                bool dw_max_valid, hipStream_t, const int* len_ptr = nullptr,
+                                const int* len_perm = nullptr);
 static inline unsigned* egnn_radial_backward_dw_max(void* ws) { return reinterpret_cast<unsigned*>(ws); }
 size_t egnn_readout_backward_partial_bytes(const egnn_ctx*, int64_t n_edges);
 size_t egnn_readout_backward_lds_bytes(const egnn_ctx*);

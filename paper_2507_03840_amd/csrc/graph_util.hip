@@ -71,7 +71,8 @@ __global__ __launch_bounds__(256) void edge_rows_segsum_kernel(const float* __re
 // out[i] = scale * sum_b partial[b * stride][i] in a fixed order: eight interleaved running sums (b mod 8), so that
 // eight loads are in flight per thread, combined pairwise at the end.
 __global__ void reduce_partials_kernel(const float* __restrict__ partial, int n_partials, long stride, long n,
-                                       float* __restrict__ out, float scale) {
+                                       float* __restrict__ out, float scale, const int* __restrict__ skip) {
+  if (skip && skip[0]) return;   // (a caller whose result another route computes: radial_grid.hip)
   const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
   float acc[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
@@ -91,7 +92,9 @@ __global__ void reduce_partials_kernel(const float* __restrict__ partial, int n_
 // First level for long lists of partials: blockIdx.y takes RP_CHUNK consecutive rows and leaves their sum in the
 // first of them (every element of the buffer is read and written by one thread only).
 #define RP_CHUNK 32
-__global__ void reduce_partials_chunk_kernel(float* __restrict__ partial, int n_partials, long n) {
+__global__ void reduce_partials_chunk_kernel(float* __restrict__ partial, int n_partials, long n,
+                                             const int* __restrict__ skip) {
+  if (skip && skip[0]) return;
   const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
   const int b0 = blockIdx.y * RP_CHUNK;
@@ -165,7 +168,7 @@ int egnn_launch_segsum_rows(egnn_ctx* ctx, const float* rows, const int* ptr, co
 
 // `partial` is scratch: long lists are summed in two levels, the first one in place.
 int egnn_launch_reduce_partials(egnn_ctx* ctx, float* partial, int n_partials, long n, float* out, float scale,
-                                hipStream_t st) {
+                                hipStream_t st, const int* skip) {
   if (n <= 0) return EGNN_OK;
   const unsigned gx = (unsigned)((n + 255) / 256);
   long stride = 1;
@@ -173,12 +176,13 @@ int egnn_launch_reduce_partials(egnn_ctx* ctx, float* partial, int n_partials, l
     const int n_chunks = (n_partials + RP_CHUNK - 1) / RP_CHUNK;
     if (n_chunks > 65535) return egnn_fail(ctx, EGNN_EINVAL, "reduce_partials: too many partial results");
     hipLaunchKernelGGL(reduce_partials_chunk_kernel, dim3(gx, (unsigned)n_chunks), dim3(256), 0, st, partial,
-                       n_partials, n);
+                       n_partials, n, skip);
     EGNN_LAUNCH_CHECK(ctx, "reduce_partials_chunk_kernel");
     n_partials = n_chunks;
     stride = RP_CHUNK;
   }
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3(gx), dim3(256), 0, st, partial, n_partials, stride, n, out, scale);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(gx), dim3(256), 0, st, partial, n_partials, stride, n, out, scale,
+                     skip);
   EGNN_LAUNCH_CHECK(ctx, "reduce_partials_kernel");
   return EGNN_OK;
 }

@@ -28,7 +28,9 @@ __device__ __forceinline__ float rb_basis(float d, int b, float step, float inv2
 template <int NB8>
 __global__ __launch_bounds__(256) void radial_hidden_kernel(const float4* __restrict__ rhat_d, long n_edges,
                                                             const float* __restrict__ W_r1, float* __restrict__ G,
-                                                            float* __restrict__ S, int n_rbf, float r_cut) {
+                                                            float* __restrict__ S, int n_rbf, float r_cut,
+                                                            const int* __restrict__ skip) {
+  if (skip && skip[0]) return;   // (the grid route has taken the call: radial_grid.hip)
   __shared__ float sBas[RH_EDGES][33];
   __shared__ float sFc[RH_EDGES];
   const int tid = threadIdx.x;
@@ -78,7 +80,8 @@ __global__ __launch_bounds__(256) void radial_hidden_kernel(const float4* __rest
 // One workgroup per block of 64 rows; the 64 x 64 tile is turned in LDS so that both sides are contiguous.
 __global__ __launch_bounds__(256) void rb_split_transpose_kernel(const float* __restrict__ src, long n_rows,
                                                                  uint16_t* __restrict__ T, int log2E, PathAlpha alpha,
-                                                                 int scale_on) {
+                                                                 int scale_on, const int* __restrict__ skip) {
+  if (skip && skip[0]) return;
   __shared__ float tile[64][65];
   const long r0 = (long)blockIdx.x * 64;
   for (int i = threadIdx.x; i < 64 * 64; i += 256) {
@@ -103,7 +106,9 @@ __global__ __launch_bounds__(256) void rb_split_transpose_kernel(const float* __
 // memory) -> T[r / 64][j][piece][r % 64] halves, two pieces (stream_gemm.h).
 __global__ __launch_bounds__(256) void rb_split_transpose_half_kernel(const float* __restrict__ src, long n_rows,
                                                                       uint16_t* __restrict__ T, int log2E, PathAlpha alpha,
-                                                                      int alpha_on, const float* __restrict__ scale) {
+                                                                      int alpha_on, const float* __restrict__ scale,
+                                                                      const int* __restrict__ skip) {
+  if (skip && skip[0]) return;
   __shared__ float tile[64][65];
   const long r0 = (long)blockIdx.x * 64;
   const float sc = scale[0];
@@ -131,7 +136,9 @@ __global__ __launch_bounds__(SG_THREADS) void radial_dpre_half_kernel(const floa
                                                                       const uint16_t* __restrict__ W2T,
                                                                       float* __restrict__ S, int PE, int n_steps,
                                                                       const float* __restrict__ scales,
-                                                                      const unsigned* __restrict__ dw_max) {
+                                                                      const unsigned* __restrict__ dw_max,
+                                                                      const int* __restrict__ skip) {
+  if (skip && skip[0]) return;
   extern __shared__ uint4 rb_smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int m = lane & 31, hh = lane >> 5;
@@ -158,7 +165,9 @@ __global__ __launch_bounds__(SG_THREADS) void radial_dpre_half_kernel(const floa
 // index n; the contraction is sg_contract of stream_gemm.h (rows = edges, one 64-column tile = the 64 hidden units).
 __global__ __launch_bounds__(SG_THREADS) void radial_dpre_kernel(const float* __restrict__ dw, long n_edges,
                                                                  const uint16_t* __restrict__ W2T,
-                                                                 float* __restrict__ S, int PE, int n_steps) {
+                                                                 float* __restrict__ S, int PE, int n_steps,
+                                                                 const int* __restrict__ skip) {
+  if (skip && skip[0]) return;
   extern __shared__ uint4 rb_smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int m = lane & 31, hh = lane >> 5;
@@ -189,7 +198,9 @@ __global__ __launch_bounds__(RB_THREADS) void radial_dw2_kernel(const float* __r
                                                                 const uint16_t* __restrict__ GT,
                                                                 float* __restrict__ partial, int PE, int log2E,
                                                                 PathAlpha alpha, const float* __restrict__ scales,
-                                                                const unsigned* __restrict__ dw_max) {
+                                                                const unsigned* __restrict__ dw_max,
+                                                                const int* __restrict__ skip) {
+  if (skip && skip[0]) return;   // (whole workgroup, before any barrier)
   constexpr int BROW4 = HALF ? SGH_BROW4 : RB_BROW4;
   __shared__ uint4 sB[2 * 64 * BROW4];
   const int tid = threadIdx.x;
@@ -300,7 +311,8 @@ __global__ __launch_bounds__(RB_THREADS) void radial_dw2_kernel(const float* __r
 template <int NB8>
 __global__ __launch_bounds__(256) void radial_dw1_kernel(const float4* __restrict__ rhat_d, long n_edges,
                                                          const float* __restrict__ dpre, float* __restrict__ partial,
-                                                         int n_rbf, float r_cut) {
+                                                         int n_rbf, float r_cut, const int* __restrict__ skip) {
+  if (skip && skip[0]) return;
   __shared__ float sBas_all[4][RB_R1TILE][33];
   const int tid = threadIdx.x;
   const int j = tid & 63, w = tid >> 6;
@@ -350,7 +362,7 @@ __global__ __launch_bounds__(256) void radial_dw1_kernel(const float4* __restric
 static size_t a256(size_t n) { return (n + 255) & ~(size_t)255; }
 static size_t rb_pad64(size_t n) { return (n + 63) & ~(size_t)63; }
 
-size_t egnn_radial_backward_ws_bytes(const egnn_ctx* ctx, int which, int64_t n_edges) {
+static size_t rb_exact_ws_bytes(const egnn_ctx* ctx, int which, int64_t n_edges) {
   const size_t PE = (size_t)ctx->n_paths[which] * ctx->desc.channels;
   const size_t kc = (size_t)((n_edges + RB_KCHUNK - 1) / RB_KCHUNK), rc = (size_t)((n_edges + RB_R1CHUNK - 1) / RB_R1CHUNK);
   // (the first 512 bytes: the running maximum of |dw| and the scalings of the half-precision form)
@@ -359,9 +371,31 @@ size_t egnn_radial_backward_ws_bytes(const egnn_ctx* ctx, int which, int64_t n_e
          a256(rb_pad64(n_edges) * EGNN_HIDDEN * 6);
 }
 
+// the exact route's buffers, then the grid route's (radial_grid.hip): which of the two runs is decided on the device
+size_t egnn_radial_backward_ws_bytes(const egnn_ctx* ctx, int which, int64_t n_edges) {
+  return rb_exact_ws_bytes(ctx, which, n_edges) + egnn_radial_grid_ws_bytes(ctx, which, n_edges);
+}
+
+// G and S at the given edge records (for the grid route: the records of its grid points)
+static int rb_launch_hidden(egnn_ctx* ctx, const float* rhat_d, long n, const float* W_r1, float* G, float* S,
+                            hipStream_t st) {
+  const int n_rbf = ctx->desc.n_rbf, nb8 = (n_rbf + 7) / 8;
+  const float4* rd = reinterpret_cast<const float4*>(rhat_d);
+  const dim3 grid((unsigned)((n + RH_EDGES - 1) / RH_EDGES));
+  const int* never = nullptr;
+  switch (nb8) {
+    case 1: hipLaunchKernelGGL(radial_hidden_kernel<1>, grid, dim3(256), 0, st, rd, n, W_r1, G, S, n_rbf, ctx->desc.r_cut, never); break;
+    case 2: hipLaunchKernelGGL(radial_hidden_kernel<2>, grid, dim3(256), 0, st, rd, n, W_r1, G, S, n_rbf, ctx->desc.r_cut, never); break;
+    case 3: hipLaunchKernelGGL(radial_hidden_kernel<3>, grid, dim3(256), 0, st, rd, n, W_r1, G, S, n_rbf, ctx->desc.r_cut, never); break;
+    default: hipLaunchKernelGGL(radial_hidden_kernel<4>, grid, dim3(256), 0, st, rd, n, W_r1, G, S, n_rbf, ctx->desc.r_cut, never); break;
+  }
+  EGNN_LAUNCH_CHECK(ctx, "radial_hidden_kernel(grid points)");
+  return EGNN_OK;
+}
+
 int egnn_launch_radial_backward(egnn_ctx* ctx, int which, const float* rhat_d, int64_t n_edges, const float* W_r1,
                                 const float* W_r2, const float* dw, float* dW_r1, float* dW_r2, void* ws,
-                                bool dw_max_valid, hipStream_t st) {
+                                bool dw_max_valid, hipStream_t st, const int* len_ptr, const int* len_perm) {
   const int P = ctx->n_paths[which];
   const int PE = P * ctx->desc.channels, n_rbf = ctx->desc.n_rbf;
   int rc;
@@ -374,6 +408,11 @@ int egnn_launch_radial_backward(egnn_ctx* ctx, int which, const float* rhat_d, i
   const int kc = (int)((n_edges + RB_KCHUNK - 1) / RB_KCHUNK), r1c = (int)((n_edges + RB_R1CHUNK - 1) / RB_R1CHUNK);
   const unsigned* dw_max = egnn_radial_backward_dw_max(ws);
   float* scales = (float*)((char*)ws + 256);
+  // Which route computes the gradients is decided on the device from W_r1 (or forced by EGNN_OPT_RADIAL_BWD): the
+  // kernels of both are enqueued, those of the route that is not taken return at once.
+  int* route = (int*)((char*)ws + 384);
+  if ((rc = egnn_launch_radial_route(ctx, W_r1, route, st))) return rc;
+  const int* skip = route;
   const bool half = dw_max_valid;
   char* base = (char*)ws + 512;
   float* G = (float*)base;
@@ -393,7 +432,7 @@ int egnn_launch_radial_backward(egnn_ctx* ctx, int which, const float* rhat_d, i
     default: hipLaunchKernelGGL(KERNEL<4>, GRID, dim3(256), 0, st, __VA_ARGS__); break;              \
   }
   RB_BY_NB8(radial_hidden_kernel, dim3((unsigned)((n_edges + RH_EDGES - 1) / RH_EDGES)), rd, (long)n_edges, W_r1, G, S,
-            n_rbf, ctx->desc.r_cut);
+            n_rbf, ctx->desc.r_cut, skip);
   EGNN_LAUNCH_CHECK(ctx, "radial_hidden_kernel");
   const int n_tile = 32 * RB_WAVES;
   const long per_wg = 64L * SG_WAVES;
@@ -403,42 +442,45 @@ int egnn_launch_radial_backward(egnn_ctx* ctx, int which, const float* rhat_d, i
     // egnn_launch_half_scales derives from the weights, dw by the one its running maximum gives
     if ((rc = egnn_launch_half_scales(ctx, which, W_r1, W_r2, scales, st))) return rc;
     hipLaunchKernelGGL(rb_split_transpose_half_kernel, dim3((unsigned)(ne_pad / 64)), dim3(256), 0, st, G, (long)n_edges,
-                       GT, 0, al, 0, scales + 1);
+                       GT, 0, al, 0, scales + 1, skip);
     EGNN_LAUNCH_CHECK(ctx, "rb_split_transpose_half_kernel(G)");
     hipLaunchKernelGGL(rb_split_transpose_half_kernel, dim3((unsigned)(pe_pad / 64)), dim3(256), 0, st, W_r2, (long)PE,
-                       W2T, ctx->log2_channels, al, 1, scales);
+                       W2T, ctx->log2_channels, al, 1, scales, skip);
     EGNN_LAUNCH_CHECK(ctx, "rb_split_transpose_half_kernel(W_r2)");
     hipLaunchKernelGGL(radial_dw2_kernel<true>, dw2_grid, dim3(RB_THREADS), 0, st, dw, (long)n_edges, GT, part2, PE,
-                       ctx->log2_channels, al, scales, dw_max);
+                       ctx->log2_channels, al, scales, dw_max, skip);
     EGNN_LAUNCH_CHECK(ctx, "radial_dw2_kernel");
-    if ((rc = egnn_launch_reduce_partials(ctx, part2, kc, (long)PE * EGNN_HIDDEN, dW_r2, 1.0f, st))) return rc;
+    if ((rc = egnn_launch_reduce_partials(ctx, part2, kc, (long)PE * EGNN_HIDDEN, dW_r2, 1.0f, st, skip))) return rc;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(radial_dpre_half_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)SGH_LDS_BYTES);
     if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(radial_dpre_half_kernel)");
     hipLaunchKernelGGL(radial_dpre_half_kernel, dpre_grid, dim3(SG_THREADS), SGH_LDS_BYTES, st, dw, (long)n_edges, W2T, S,
-                       PE, (int)(pe_pad / 64), scales, dw_max);
+                       PE, (int)(pe_pad / 64), scales, dw_max, skip);
     EGNN_LAUNCH_CHECK(ctx, "radial_dpre_half_kernel");
   } else {
     hipLaunchKernelGGL(rb_split_transpose_kernel, dim3((unsigned)(ne_pad / 64)), dim3(256), 0, st, G, (long)n_edges, GT, 0,
-                       al, 0);
+                       al, 0, skip);
     EGNN_LAUNCH_CHECK(ctx, "rb_split_transpose_kernel(G)");
     hipLaunchKernelGGL(rb_split_transpose_kernel, dim3((unsigned)(pe_pad / 64)), dim3(256), 0, st, W_r2, (long)PE, W2T,
-                       ctx->log2_channels, al, 1);
+                       ctx->log2_channels, al, 1, skip);
     EGNN_LAUNCH_CHECK(ctx, "rb_split_transpose_kernel(W_r2)");
     hipLaunchKernelGGL(radial_dw2_kernel<false>, dw2_grid, dim3(RB_THREADS), 0, st, dw, (long)n_edges, GT, part2, PE,
-                       ctx->log2_channels, al, scales, dw_max);
+                       ctx->log2_channels, al, scales, dw_max, skip);
     EGNN_LAUNCH_CHECK(ctx, "radial_dw2_kernel");
-    if ((rc = egnn_launch_reduce_partials(ctx, part2, kc, (long)PE * EGNN_HIDDEN, dW_r2, 1.0f, st))) return rc;
+    if ((rc = egnn_launch_reduce_partials(ctx, part2, kc, (long)PE * EGNN_HIDDEN, dW_r2, 1.0f, st, skip))) return rc;
     const size_t dpre_lds = SG_LDS_BYTES;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(radial_dpre_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)dpre_lds);
     if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(radial_dpre_kernel)");
     hipLaunchKernelGGL(radial_dpre_kernel, dpre_grid, dim3(SG_THREADS), dpre_lds, st, dw, (long)n_edges, W2T, S, PE,
-                       (int)(pe_pad / 64));
+                       (int)(pe_pad / 64), skip);
     EGNN_LAUNCH_CHECK(ctx, "radial_dpre_kernel");
   }
-  RB_BY_NB8(radial_dw1_kernel, dim3((r1c + 3) / 4), rd, (long)n_edges, S, part1, n_rbf, ctx->desc.r_cut);
+  RB_BY_NB8(radial_dw1_kernel, dim3((r1c + 3) / 4), rd, (long)n_edges, S, part1, n_rbf, ctx->desc.r_cut, skip);
 #undef RB_BY_NB8
   EGNN_LAUNCH_CHECK(ctx, "radial_dw1_kernel");
-  return egnn_launch_reduce_partials(ctx, part1, r1c, (long)EGNN_HIDDEN * n_rbf, dW_r1, 1.0f, st);
+  if ((rc = egnn_launch_reduce_partials(ctx, part1, r1c, (long)EGNN_HIDDEN * n_rbf, dW_r1, 1.0f, st, skip))) return rc;
+  // the grid route (its kernels run only if route[0] is 1)
+  return egnn_launch_radial_grid(ctx, which, rhat_d, n_edges, len_ptr, len_perm, W_r1, W_r2, dw, dW_r1, dW_r2,
+                                 (char*)ws + rb_exact_ws_bytes(ctx, which, n_edges), route, rb_launch_hidden, st);
 }

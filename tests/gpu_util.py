@@ -121,7 +121,7 @@ def oracle_training_step(w, wt, g, agg, T):
     return dict(loss=loss, grads=grads)
 
 
-def gpu_training_step(w, wt, agg, T, repeats=1, timing=None, keep=False, shared_rows=False):
+def gpu_training_step(w, wt, agg, T, repeats=1, timing=None, keep=False, shared_rows=False, length_bins=None):
     """The same step through the C ABI.  Layer inputs are kept; everything else is recomputed in the reverse pass, or
     (keep=True) the radial weights and summed messages of the forward pass are kept and handed back."""
     import torch
@@ -131,6 +131,8 @@ def gpu_training_step(w, wt, agg, T, repeats=1, timing=None, keep=False, shared_
     graph = m.egnn_nlist(pos, w.n_owned, w.box, w.pbc)
     if shared_rows:
         m.egnn_edge_pairs(graph)
+    if shared_rows if length_bins is None else length_bins:
+        m.egnn_length_bins(graph, pos, w.box)      # the per-graph index of the radial MLP's reverse pass
     ws = torch.empty(max(m.egnn_backward_workspace_bytes(graph.n_edges, graph.n_owned, graph.n_total),
                          m.egnn_workspace_bytes(graph.n_edges, graph.n_owned, graph.n_total)),
                      dtype=torch.uint8, device="cuda")

@@ -60,11 +60,15 @@ def test_loss_mse(B):
     assert U.rel_err(dH.cpu().numpy(), O.loss_mse_backward(H, T)) < 1e-6
 
 
+@pytest.mark.parametrize("route", [1, 2])
 @pytest.mark.parametrize("lmax,E,n,n_owned,periodic", [(0, 8, 40, 40, False), (1, 16, 90, 60, True),
                                                        (2, 32, 80, 80, False), (3, 64, 70, 50, False),
                                                        (4, 32, 120, 90, True), (4, 128, 40, 30, False)])
-def test_layer_backward(B, lmax, E, n, n_owned, periodic):
+def test_layer_backward(B, lmax, E, n, n_owned, periodic, route):
+    """route: how dw becomes dW_r1 / dW_r2 -- 1 two contractions on the matrix cores, 2 one binning pass on a grid of
+    distances (the default picks between them on the device)."""
     w, g, agg, m, pos, graph, ws, col_ptr, perm = _setup(B, lmax, E, n, n_owned, periodic, 50 + lmax)
+    m.egnn_set_option(B.OPT_RADIAL_BWD, route)
     rng = np.random.default_rng(lmax)
     W = synth.layer_weights(rng, lmax, E, w.n_rbf, 64, m.n_paths)
     x = synth.node_features(rng, n, lmax, E)
@@ -85,12 +89,15 @@ def test_layer_backward(B, lmax, E, n, n_owned, periodic):
     assert all(np.array_equal(grads[k].cpu().numpy(), grads2[k].cpu().numpy()) for k in grads)
 
 
+@pytest.mark.parametrize("route", [1, 2])
 @pytest.mark.parametrize("dy_scale,w_scale", [(1e-14, 1.0), (1e11, 1e-5), (3e-7, 2e4)])
-def test_layer_backward_gradient_scales(B, dy_scale, w_scale):
+def test_layer_backward_gradient_scales(B, dy_scale, w_scale, route):
     """The contractions that read dw cut it into half-precision pieces after a scaling taken from the largest |dw|
-    (kept by the kernel that writes it): tiny and huge gradients keep the accuracy."""
+    (kept by the kernel that writes it): tiny and huge gradients keep the accuracy.  (The grid route is linear in dw
+    in plain fp32 and needs no scaling.)"""
     lmax, E, n = 3, 16, 80
     w, g, agg, m, pos, graph, ws, col_ptr, perm = _setup(B, lmax, E, n, n, False, 91)
+    m.egnn_set_option(B.OPT_RADIAL_BWD, route)
     rng = np.random.default_rng(5)
     W = synth.layer_weights(rng, lmax, E, w.n_rbf, 64, m.n_paths)
     W["W_r2"] = (W["W_r2"] * np.float32(w_scale)).astype(np.float32)
@@ -105,11 +112,13 @@ def test_layer_backward_gradient_scales(B, dy_scale, w_scale):
     assert all(e < 1e-5 for e in errs.values()), errs
 
 
+@pytest.mark.parametrize("route", [1, 2])
 @pytest.mark.parametrize("n_rbf", [2, 9, 20, 32])
-def test_layer_backward_basis_counts(B, n_rbf):
+def test_layer_backward_basis_counts(B, n_rbf, route):
     """The reverse pass of the radial MLP pads the number of radial bases to a multiple of 8 at compile time."""
     lmax, E, n = 2, 16, 60
     w, g, agg, m, pos, graph, ws, col_ptr, perm = _setup(B, lmax, E, n, n, False, 70 + n_rbf, n_rbf=n_rbf)
+    m.egnn_set_option(B.OPT_RADIAL_BWD, route)
     rng = np.random.default_rng(n_rbf)
     W = synth.layer_weights(rng, lmax, E, n_rbf, 64, m.n_paths)
     x = synth.node_features(rng, n, lmax, E)
@@ -123,12 +132,84 @@ def test_layer_backward_basis_counts(B, n_rbf):
     assert all(e < TOL for e in errs.values()), errs
 
 
+@pytest.mark.parametrize("case", ["open", "periodic-halo", "empty"])
+def test_length_bins_exact_and_reused(B, case):
+    """Edges grouped by length interval: every edge once, in the interval its fp32 length falls in, ascending edge id
+    inside an interval; a graph that carries the index gives the same gradients, bit for bit, as one that leaves the
+    reverse pass to build it."""
+    if case == "empty":
+        w, g, agg, m, pos, graph, ws, col_ptr, perm = _setup(B, 1, 8, 6, 6, False, 4, r_cut=0.3)
+    else:
+        w, g, agg, m, pos, graph, ws, col_ptr, perm = _setup(B, 2, 16, 150, 150 if case == "open" else 90,
+                                                            case != "open", 8)
+    m.egnn_length_bins(graph, pos, w.box)
+    lp, lperm = graph.len_ptr.cpu().numpy(), graph.len_perm.cpu().numpy()
+    assert lp.shape == (B.LENGTH_BINS + 1,) and lp[0] == 0 and lp[-1] == graph.n_edges and np.all(np.diff(lp) >= 0)
+    if graph.n_edges == 0:
+        return
+    rhat_d, *_ = m.egnn_edge_geometry(graph, pos, w.box)
+    d = rhat_d.cpu().numpy()[:, 3]
+    inv_h = np.float32(B.LENGTH_BINS) / np.float32(w.r_cut)
+    key = np.clip(np.floor(d * inv_h), 0, B.LENGTH_BINS - 1).astype(np.int64)
+    assert np.array_equal(np.sort(lperm), np.arange(graph.n_edges))
+    assert np.array_equal(np.diff(lp), np.bincount(key, minlength=B.LENGTH_BINS))
+    order = np.lexsort((np.arange(graph.n_edges), key))           # by interval, then by edge id
+    assert np.array_equal(lperm, order)
+    rng = np.random.default_rng(3)
+    W = synth.layer_weights(rng, w.lmax, w.channels, w.n_rbf, 64, m.n_paths)
+    x = synth.node_features(rng, w.n_total, w.lmax, w.channels)
+    dy = synth.node_features(rng, w.n_owned, w.lmax, w.channels)
+    m.egnn_set_option(B.OPT_RADIAL_BWD, 2)
+    dx1, g1 = m.egnn_layer_backward(graph, col_ptr, perm, pos, w.box, B.to_device(x), B.to_device(W), B.to_device(dy), ws)
+    plain = graph.per_edge()
+    plain.len_ptr = plain.len_perm = None
+    dx2, g2 = m.egnn_layer_backward(plain, col_ptr, perm, pos, w.box, B.to_device(x), B.to_device(W), B.to_device(dy), ws)
+    assert all(np.array_equal(g1[k].cpu().numpy(), g2[k].cpu().numpy()) for k in g1)
+
+
+@pytest.mark.parametrize("w1_scale,expect_route", [(1.0, 2), (30.0, 2), (3000.0, 1)])
+def test_radial_backward_route_is_chosen_from_the_weights(B, w1_scale, expect_route):
+    """Default: the grid route while the hidden layer's input varies slowly enough with the distance for the six-point
+    interpolation (absolute row sums of W_r1 up to 256 at 16 bases), the exact route beyond.  The choice is made on
+    the device; it shows in the result being bit-identical to the forced route's.  Both match the oracle."""
+    lmax, E, n = 2, 16, 90
+    w, g, agg, m, pos, graph, ws, col_ptr, perm = _setup(B, lmax, E, n, n, False, 93, n_rbf=16, r_cut=5.0)
+    rng = np.random.default_rng(17)
+    W = synth.layer_weights(rng, lmax, E, w.n_rbf, 64, m.n_paths)
+    W["W_r1"] = (W["W_r1"] * np.float32(w1_scale)).astype(np.float32)
+    x = synth.node_features(rng, n, lmax, E)
+    dy = synth.node_features(rng, n, lmax, E)
+    out = {}
+    for route in (0, 1, 2):
+        m.egnn_set_option(B.OPT_RADIAL_BWD, route)
+        dx, grads = m.egnn_layer_backward(graph, col_ptr, perm, pos, w.box, B.to_device(x), B.to_device(W),
+                                          B.to_device(dy), ws)
+        out[route] = {k: v.cpu().numpy() for k, v in grads.items()}
+    l1 = np.abs(W["W_r1"]).sum(axis=1).max()
+    print(f"largest absolute row sum of W_r1: {l1:.1f}", flush=True)
+    assert (l1 <= 256.0) == (expect_route == 2)
+    for k in ("W_r1", "W_r2"):
+        assert np.array_equal(out[0][k], out[expect_route][k]), k
+        assert not np.array_equal(out[1][k], out[2][k])
+    dx_ref, g_ref = O.layer_backward(g, w.pos, w.box, x, W, lmax, lmax, E, w.n_rbf, w.r_cut, agg, dy.astype(np.float64))
+    errs = {(r, k): U.rel_err(out[r][k], g_ref[k]) for r in (0, 1, 2) for k in ("W_r1", "W_r2")}
+    print({k: f"{v:.1e}" for k, v in errs.items()}, flush=True)
+    # (at the largest scale the hidden layer's input reaches thousands and fp32 itself loses a digit)
+    bar = 1e-5 if w1_scale <= 30.0 else TOL
+    assert all(errs[(0, k)] < bar for k in ("W_r1", "W_r2")), errs
+    assert all(errs[(1, k)] < bar for k in ("W_r1", "W_r2")), errs
+    if expect_route == 2:
+        assert all(errs[(2, k)] < 1e-5 for k in ("W_r1", "W_r2")), errs
+
+
+@pytest.mark.parametrize("route", [1, 2])
 @pytest.mark.parametrize("lmax,E,n,n_owned,periodic", [(0, 8, 40, 40, False), (2, 16, 90, 60, True),
                                                        (3, 32, 70, 70, False), (4, 32, 100, 70, False),
                                                        (4, 64, 50, 50, True), (4, 8, 45, 45, True),
                                                        (1, 128, 40, 30, False)])
-def test_readout_backward(B, lmax, E, n, n_owned, periodic):
+def test_readout_backward(B, lmax, E, n, n_owned, periodic, route):
     w, g, agg, m, pos, graph, ws, col_ptr, perm = _setup(B, lmax, E, n, n_owned, periodic, 60 + lmax)
+    m.egnn_set_option(B.OPT_RADIAL_BWD, route)
     rng = np.random.default_rng(10 + lmax)
     Wr = synth.readout_weights(rng, lmax, E, w.n_rbf, 64, m.n_paths_readout, sum(m.n_out))
     x = synth.node_features(rng, n, lmax, E)
