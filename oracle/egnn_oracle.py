@@ -360,8 +360,8 @@ def loss_mse(H, T):
 
 
 # --------------------------------------------------------------------------------------
-# O7  reverse pass (training step: "torch's computational graph constructs gradients", Sec. 4.1;
-#     here written out by hand, adjoint of each function above in reverse order)
+# O7  reverse pass (training step; the paper leaves the gradients to its framework's automatic differentiation,
+#     Sec. 4.1; here they are written out by hand, the adjoint of each function above in reverse order)
 # --------------------------------------------------------------------------------------
 def loss_mse_backward(H, T):
     """dL/dH for L = mean (H - T)^2."""

@@ -1,8 +1,10 @@
 // Low-NN partitioner (host) and the pack / unpack of node embeddings that cross a partition boundary.
 //
-// Sec. 4.4 and Appendix A (Algorithm 1): recursive bisection of the atoms into 2^l parts that balances the summed node
-// degree of the two sides of every cut, treats the structure as periodic, and cuts the dimension in which a cut is
-// expected to add the fewest neighbouring parts.  Sec. 4.3 / Fig. 4(b): per neighbouring part the rows a rank has to
+// Sec. 4.4 and Appendix A (Algorithm 1): bisection of the atoms into 2^l parts that balances the summed node degree
+// of the two sides of every cut, treats the structure as periodic, and cuts the dimension in which a cut is expected
+// to add the fewest neighbouring parts.  Here: one permutation of the atoms in which every sub-domain is a contiguous
+// range, a work stack of sub-domains (range + cut state) in place of recursion, the opening of periodic rings as a
+// pre-pass of its own, and a scored choice of the axis.  Sec. 4.3 / Fig. 4(b): per neighbouring part the rows a rank has to
 // send are gathered by index into one contiguous buffer (pack), the received rows are put behind the rank's own rows
 // (unpack); the payload may be half precision (Sec. 4.1).
 //
@@ -15,110 +17,170 @@
 
 namespace {
 
-// a mod b with the sign of b (b > 0): the coordinate of a point on a ring of length b
-double ring_mod(double a, double b) {
-  double m = std::fmod(a, b);
-  if (m != 0.0 && m < 0.0) m += b;
-  return m;
-}
+// One sub-domain waiting to be bisected: a contiguous range of the atom permutation plus its cut state.
+struct SubDomain {
+  int begin, end;     // range of `order_`
+  int levels_left;    // bisections still to make below this sub-domain (2^levels_left parts)
+  int n_cuts[3];      // cuts made so far along each axis (an axis that is not periodic starts with one)
+  double origin[3];   // where the coordinate along each axis starts (for a periodic axis: where its ring was opened)
+};
 
-struct Partitioner {
-  const std::vector<double>& x;   // [n][3]
-  const std::vector<double>& nd;  // [n]
-  double box[3];
-  bool pbc[3];
-  double r_cut;
-  int32_t* part;
-  int32_t* cut_log;   // [max][4] (level, dimension, atoms, atoms on the left) or NULL
-  int n_cuts = 0, max_cuts = 0, counter = 0;
-
-  double coord(int atom, int d, double origin) const {
-    const double v = x[3 * (size_t)atom + d] - origin;
-    return pbc[d] ? ring_mod(v, box[d]) : v;
+class LowNNBisection {
+ public:
+  LowNNBisection(const float* pos, const int32_t* degree, int n_atoms, const float box[3], const uint8_t pbc[3],
+                 double r_cut, int32_t* part, int32_t* cut_log, int max_log)
+      : n_(n_atoms), r_cut_(r_cut), part_(part), cut_log_(cut_log), max_log_(max_log) {
+    xyz_.resize((size_t)n_ * 3);
+    weight_.resize(n_);
+    for (size_t i = 0; i < xyz_.size(); ++i) xyz_[i] = (double)pos[i];
+    for (int i = 0; i < n_; ++i) weight_[i] = (double)degree[i];
+    for (int a = 0; a < 3; ++a) {
+      box_[a] = (double)box[a];
+      periodic_[a] = pbc[a] != 0;
+    }
+    order_.resize(n_);
+    std::iota(order_.begin(), order_.end(), 0);
   }
 
-  // Orders `idx` along dimension d; returns the number of atoms on the left of the balanced cut and its position.
-  int get_cut(std::vector<int>& idx, int d, double origin, double* p) const {
-    const size_t n = idx.size();
-    std::vector<double> c(n);
-    for (size_t t = 0; t < n; ++t) c[t] = coord(idx[t], d, origin);
-    std::vector<int> order(n);
-    std::iota(order.begin(), order.end(), 0);
-    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return c[a] < c[b]; });
-    std::vector<int> sorted(n);
-    for (size_t t = 0; t < n; ++t) sorted[t] = idx[order[t]];
-    if (n < 2) {
-      *p = n ? c[order[0]] : 0.0;
-      idx.swap(sorted);
-      return (int)n;
+  int cuts_made() const { return cuts_made_; }
+
+  // Depth first, left half before right half: an explicit stack instead of recursion (the right half is pushed first).
+  void run(int levels) {
+    SubDomain root{0, n_, levels, {0, 0, 0}, {0.0, 0.0, 0.0}};
+    for (int a = 0; a < 3; ++a) {
+      if (periodic_[a]) continue;
+      root.n_cuts[a] = 1;   // an open axis needs no ring opening: it starts at its smallest coordinate
+      if (n_ > 0) {
+        double lo = xyz_[a];
+        for (int i = 1; i < n_; ++i) lo = std::min(lo, xyz_[3 * (size_t)i + a]);
+        root.origin[a] = lo;
+      }
     }
-    double total = 0.0;
-    for (size_t t = 0; t < n; ++t) total += nd[sorted[t]];
-    double run = 0.0, best = 0.0;
-    int n_left = 1;
-    for (size_t t = 0; t + 1 < n; ++t) {
-      run += nd[sorted[t]];
-      const double diff = std::fabs(2.0 * run - total);
-      if (t == 0 || diff < best) { best = diff; n_left = (int)t + 1; }
+    std::vector<SubDomain> todo{root};
+    while (!todo.empty()) {
+      SubDomain dom = todo.back();
+      todo.pop_back();
+      if (dom.levels_left == 0) {           // a finished part
+        for (int t = dom.begin; t < dom.end; ++t) part_[order_[t]] = next_part_;
+        ++next_part_;
+        continue;
+      }
+      if (dom.begin == dom.end) {           // nothing to divide: its parts stay empty but keep their numbers
+        next_part_ += 1 << dom.levels_left;
+        continue;
+      }
+      open_rings(dom);
+      const int axis = axis_with_fewest_neighbours(dom);
+      double where;
+      const int n_left = balanced_split(dom.begin, dom.end, axis, dom.origin[axis], /*reorder=*/true, &where);
+      if (cut_log_ && cuts_made_ < max_log_) {
+        int32_t* e = cut_log_ + 4 * (size_t)cuts_made_;
+        e[0] = dom.levels_left;
+        e[1] = axis;
+        e[2] = dom.end - dom.begin;
+        e[3] = n_left;
+      }
+      ++cuts_made_;
+      SubDomain left = dom, right = dom;
+      left.n_cuts[axis] = right.n_cuts[axis] = dom.n_cuts[axis] + 1;
+      left.levels_left = right.levels_left = dom.levels_left - 1;
+      left.end = right.begin = dom.begin + n_left;
+      todo.push_back(right);
+      todo.push_back(left);
     }
-    *p = c[order[n_left]];
-    idx.swap(sorted);
+  }
+
+ private:
+  // coordinate of an atom along an axis, measured from `origin` (on a ring for a periodic axis)
+  double along(int atom, int axis, double origin) const {
+    const double v = xyz_[3 * (size_t)atom + axis] - origin;
+    if (!periodic_[axis]) return v;
+    double m = std::fmod(v, box_[axis]);
+    if (m < 0.0) m += box_[axis];
+    return m;
+  }
+
+  // Orders the atoms of [begin, end) along `axis` (atoms at equal coordinate keep their order) and finds the split
+  // into a left and a right group whose summed weights differ least (fewest atoms on the left among equals; both
+  // groups non-empty).  Returns the size of the left group and, in *where, the coordinate of the first atom on the
+  // right.  reorder = false leaves the range as it was (ring opening only asks where the split would be).
+  int balanced_split(int begin, int end, int axis, double origin, bool reorder, double* where) {
+    const int n = end - begin;
+    key_.resize(n);
+    rank_.resize(n);
+    for (int t = 0; t < n; ++t) key_[t] = along(order_[begin + t], axis, origin);
+    std::iota(rank_.begin(), rank_.end(), 0);
+    std::stable_sort(rank_.begin(), rank_.end(), [&](int a, int b) { return key_[a] < key_[b]; });
+    int n_left = n;
+    *where = n ? key_[rank_[0]] : 0.0;
+    if (n >= 2) {
+      double total = 0.0;
+      for (int t = 0; t < n; ++t) total += weight_[order_[begin + t]];
+      double left_sum = 0.0, least = 0.0;
+      n_left = 1;
+      for (int t = 0; t + 1 < n; ++t) {
+        left_sum += weight_[order_[begin + rank_[t]]];
+        const double imbalance = std::fabs(2.0 * left_sum - total);
+        if (t == 0 || imbalance < least) {
+          least = imbalance;
+          n_left = t + 1;
+        }
+      }
+      *where = key_[rank_[n_left]];
+    }
+    if (reorder) {
+      moved_.resize(n);
+      for (int t = 0; t < n; ++t) moved_[t] = order_[begin + rank_[t]];
+      std::copy(moved_.begin(), moved_.end(), order_.begin() + begin);
+    }
     return n_left;
   }
 
-  void cut_domain(int l, std::vector<int> idx, std::array<int, 3> cuts, std::array<double, 3> origin) {
-    if (l == 0) {
-      for (int a : idx) part[a] = counter;
-      ++counter;
-      return;
+  // Pre-pass: one cut through a periodic ring divides nothing, it only fixes where the ring is opened.  Every axis
+  // of the sub-domain that has no cut yet is opened at its balanced position; the atoms stay together.
+  void open_rings(SubDomain& dom) {
+    for (int a = 0; a < 3; ++a) {
+      if (dom.n_cuts[a] != 0) continue;
+      double where;
+      balanced_split(dom.begin, dom.end, a, dom.origin[a], /*reorder=*/false, &where);
+      dom.origin[a] += where;
+      dom.n_cuts[a] = 1;
     }
-    if (idx.empty()) {
-      counter += 1 << l;
-      return;
-    }
-    // a dimension without a cut: open the ring at the balanced position, the atoms stay together
-    for (;;) {
-      int dim = -1;
-      for (int d = 0; d < 3; ++d)
-        if (cuts[d] == 0) { dim = d; break; }
-      if (dim < 0) break;
-      double p;
-      std::vector<int> tmp = idx;
-      get_cut(tmp, dim, origin[dim], &p);
-      origin[dim] += p;
-      cuts[dim] += 1;
-    }
-    int nn[3];
-    for (int d = 0; d < 3; ++d) {
-      if (cuts[d] == 1) {
-        nn[d] = 1;
-      } else {
+  }
+
+  // Score of an axis = neighbouring parts a cut along it is expected to add: 1 while the axis has been cut once
+  // (two slabs of a ring see each other and nothing else), else the number of slabs of the sub-domain's extent that
+  // the interaction range 2 r_cut spans.  Lowest score wins, the highest axis among equals.
+  int axis_with_fewest_neighbours(const SubDomain& dom) const {
+    int best_axis = 0, best_score = 0;
+    for (int a = 0; a < 3; ++a) {
+      int score = 1;
+      if (dom.n_cuts[a] != 1) {
         double lo = 0.0, hi = 0.0;
-        for (size_t t = 0; t < idx.size(); ++t) {
-          const double v = coord(idx[t], d, origin[d]);
-          if (t == 0 || v < lo) lo = v;
-          if (t == 0 || v > hi) hi = v;
+        for (int t = dom.begin; t < dom.end; ++t) {
+          const double v = along(order_[t], a, dom.origin[a]);
+          if (t == dom.begin || v < lo) lo = v;
+          if (t == dom.begin || v > hi) hi = v;
         }
-        const double L = hi - lo;
-        nn[d] = L > 0.0 ? (int)std::min(std::ceil(2.0 * r_cut / L), 1073741824.0) : (1 << 30);
+        const double extent = hi - lo;
+        score = extent > 0.0 ? (int)std::min(std::ceil(2.0 * r_cut_ / extent), 1073741824.0) : (1 << 30);
+      }
+      if (a == 0 || score <= best_score) {
+        best_axis = a;
+        best_score = score;
       }
     }
-    int dim = 0;
-    for (int d = 1; d < 3; ++d)
-      if (nn[d] <= nn[dim]) dim = d;          // lowest count, highest index among equals
-    double p;
-    const int n_left = get_cut(idx, dim, origin[dim], &p);
-    if (cut_log && n_cuts < max_cuts) {
-      int32_t* e = cut_log + 4 * (size_t)n_cuts;
-      e[0] = l; e[1] = dim; e[2] = (int32_t)idx.size(); e[3] = n_left;
-    }
-    ++n_cuts;
-    cuts[dim] += 1;
-    std::vector<int> left(idx.begin(), idx.begin() + n_left), right(idx.begin() + n_left, idx.end());
-    std::vector<int>().swap(idx);
-    cut_domain(l - 1, std::move(left), cuts, origin);
-    cut_domain(l - 1, std::move(right), cuts, origin);
+    return best_axis;
   }
+
+  int n_;
+  double r_cut_, box_[3];
+  bool periodic_[3];
+  std::vector<double> xyz_, weight_, key_;
+  std::vector<int> order_, rank_, moved_;
+  int32_t* part_;
+  int32_t* cut_log_;
+  int max_log_, cuts_made_ = 0, next_part_ = 0;
 };
 
 }  // namespace
@@ -130,27 +192,9 @@ extern "C" int egnn_partition_low_nn(const float* pos, const int32_t* degree, in
     return EGNN_EINVAL;
   for (int d = 0; d < 3; ++d)
     if (pbc[d] && !(box[d] > 0.0f)) return EGNN_EINVAL;
-  std::vector<double> x((size_t)n_atoms * 3), nd(n_atoms);
-  for (size_t i = 0; i < x.size(); ++i) x[i] = (double)pos[i];
-  for (int i = 0; i < n_atoms; ++i) nd[i] = (double)degree[i];
-  Partitioner P{x, nd, {(double)box[0], (double)box[1], (double)box[2]}, {pbc[0] != 0, pbc[1] != 0, pbc[2] != 0}, r_cut, part,
-                cut_log};
-  P.max_cuts = (1 << levels) - 1;
-  std::array<int, 3> cuts;
-  std::array<double, 3> origin;
-  for (int d = 0; d < 3; ++d) {
-    cuts[d] = pbc[d] ? 0 : 1;
-    origin[d] = 0.0;
-    if (!pbc[d] && n_atoms > 0) {
-      double lo = x[d];
-      for (int i = 1; i < n_atoms; ++i) lo = std::min(lo, x[3 * (size_t)i + d]);
-      origin[d] = lo;
-    }
-  }
-  std::vector<int> idx(n_atoms);
-  std::iota(idx.begin(), idx.end(), 0);
-  P.cut_domain(levels, std::move(idx), cuts, origin);
-  if (n_cuts) *n_cuts = P.n_cuts;
+  LowNNBisection bisection(pos, degree, n_atoms, box, pbc, r_cut, part, cut_log, (1 << levels) - 1);
+  bisection.run(levels);
+  if (n_cuts) *n_cuts = bisection.cuts_made();
   return EGNN_OK;
 }
 
