@@ -370,13 +370,13 @@ def run_config(args, index, extras):
             m.egnn_timing_enable(0)
             # stages of the reverse pass (HIP events of the library on the launch stream) with the bytes each one
             # has to move at least: tp_backward reads w and writes dw; the readout adjoint reads w and dH and writes
-            # dw and dz; the radial MLP's reverse pass reads dw twice
+            # dw and dz; the radial MLP's reverse pass reads dw once (grid route; the exact route reads it twice)
             wbytes = 4 * n_edges * m.n_paths * w.channels
             wbytes_ro = 4 * n_edges * m.n_paths_readout * w.channels
             row = 4 * m.dim * w.channels
             adj = {n: ms_k[10 + i] / max(1, calls_k[2]) for i, n in enumerate(B.LAYER_ADJOINT_STAGES)}
             adj_ro = {n: ms_k[15 + i] / max(1, calls_k[3]) for i, n in enumerate(B.READOUT_ADJOINT_STAGES)}
-            stage_bytes = dict(tp_backward=2 * wbytes, radial_backward=2 * wbytes,
+            stage_bytes = dict(tp_backward=2 * wbytes, radial_backward=wbytes,
                                readout_backward=2 * wbytes_ro + n_edges * (row + 4 * w.n_orb * w.n_orb))
             reverse = dict(layer_ms=adj, readout_ms=adj_ro,
                            tp_backward_GBs=stage_bytes["tp_backward"] / adj["tp_backward"] / 1e6,

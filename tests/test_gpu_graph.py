@@ -17,8 +17,9 @@ def B():
     return binding
 
 
-@pytest.mark.parametrize("fused", [0, 1, 2])
+@pytest.mark.parametrize("fused", [0, "shared", 1, 2])
 def test_layers_replay_from_a_graph(B, fused):
+    """fused: 0 = S3 then S4, "shared" = the same on a graph with shared rows of radial weights, 1 / 2 = fused designs."""
     import torch
     w = synth.small_cluster(150, 110, 3, 32, 6, 4.0, 41, False, 0.05)
     w.n_layers = 2
@@ -26,9 +27,13 @@ def test_layers_replay_from_a_graph(B, fused):
     g = U.oracle_graph(w)
     agg = max(1.0, U.mean_degree(g, w.n_owned))
     m = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, agg, n_layers=w.n_layers, orb_l=w.orb_l)
+    shared = fused == "shared"
+    fused = 0 if shared else fused
     m.egnn_set_option(B.OPT_FUSED, fused)
     pos = B.to_device(w.pos)
     graph = m.egnn_nlist(pos, w.n_owned, w.box, w.pbc)
+    if shared:
+        m.egnn_edge_pairs(graph)          # (before the capture: it reads the row count back)
     ws = m.workspace(graph)
     Wd = [B.to_device(wt["layers"][t]) for t in range(2)]
     halo1 = B.to_device(wt["halo"][1])
