@@ -154,6 +154,7 @@ __global__ __launch_bounds__(HS_THREADS) void half_scales_kernel(const float* __
   __shared__ float red[HS_THREADS];
   float mw = 0.0f;
   const float4* W4 = reinterpret_cast<const float4*>(W_r2);
+#pragma unroll 4   // (several loads in flight: the kernel is one workgroup, its time is load latency)
   for (int i = threadIdx.x; i < PE * (EGNN_HIDDEN / 4); i += HS_THREADS) {
     const float4 v = W4[i];
     const float al = fabsf(alpha.a[(i / (EGNN_HIDDEN / 4)) >> log2E]);

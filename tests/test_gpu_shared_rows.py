@@ -150,3 +150,36 @@ def test_training_step_with_shared_rows(B, index, keep):
         assert abs(b["loss"] / ref["loss"] - 1) < 1e-5
         for k, v in ref["grads"].items():
             assert U.rel_err(b["grads"][k], v) < U.TOL, k
+
+
+def test_edge_pairs_on_a_list_with_missing_reverses(B):
+    """A caller-made list in which some edges between owned atoms have lost their reverse (e.g. a directed pruning):
+    those edges own a row of their own, the layer still matches the oracle on the same list, and weights supplied per
+    edge by the caller are read per edge whatever the graph carries."""
+    w = synth.small_cluster(70, 70, 2, 16, 8, 4.0, 77, False)
+    src, dst, shift, row_ptr = U.oracle_graph(w)
+    rng = np.random.default_rng(1)
+    drop = rng.random(len(src)) < 0.15                       # remove 15 % of the directed edges
+    keep = ~drop
+    src2, dst2, shift2 = src[keep], dst[keep], shift[keep]
+    row_ptr2 = np.concatenate([[0], np.cumsum(np.bincount(dst2, minlength=w.n_owned))]).astype(np.int32)
+    g2 = (src2, dst2, shift2, row_ptr2)
+    m = B.Egnn(2, 16, 8, w.r_cut, 6.0)
+    graph = B.Graph(B.to_device(src2), B.to_device(dst2), B.to_device(row_ptr2), B.to_device(shift2), 70, 70)
+    m.egnn_edge_pairs(graph)
+    ref_row, ref_owner, ref_n = reference_rows(g2, 70, 70)
+    row, owner = decode(graph.w_row.cpu().numpy())
+    assert graph.n_w_rows == ref_n and np.array_equal(owner, ref_owner) and np.array_equal(row, ref_row)
+    n_unpaired = int((owner & (src2 > dst2)).sum())
+    assert n_unpaired > 20 and ref_n * 2 > len(src2)         # edges with src > dst that had to keep a row
+    W = synth.layer_weights(rng, 2, 16, 8, 64, m.n_paths)
+    x = synth.node_features(rng, 70, 2, 16)
+    pos = B.to_device(w.pos)
+    ws = m.workspace(graph)
+    y = m.egnn_layer_forward(graph, pos, w.box, B.to_device(x), B.to_device(W), ws)
+    ref = O.layer_forward(g2, w.pos, w.box, x, W, 2, 2, 16, 8, w.r_cut, 6.0)
+    assert U.rel_err(y.cpu().numpy(), ref) < U.TOL
+    we = synth.normal(rng, (len(src2), m.n_paths, 16))
+    y2 = m.egnn_layer_forward(graph, pos, w.box, B.to_device(x), B.to_device(W), ws, w_edge=B.to_device(we))
+    ref2 = O.layer_forward(g2, w.pos, w.box, x, W, 2, 2, 16, 8, w.r_cut, 6.0, w_edge=we)
+    assert U.rel_err(y2.cpu().numpy(), ref2) < U.TOL
