@@ -144,6 +144,76 @@ def so2_message_sum(graph, pos, box, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut, 
     return a / sqrt(agg_norm)
 
 
+def so2_linear_backward(Xp, gYp, W0, Wr, Wi, lmax, E):
+    """Adjoint of so2_linear: (gXp, dW0, [dWr_m], [dWi_m]) from the bond-frame inputs Xp and the gradient gYp of the
+    outputs.  With y_{+m} = Wr x_{+m} - Wi x_{-m}, y_{-m} = Wi x_{+m} + Wr x_{-m}:
+        gx_{+m} = Wr^T gy_{+m} + Wi^T gy_{-m},   gx_{-m} = -Wi^T gy_{+m} + Wr^T gy_{-m},
+        dWr = gy_{+m} x_{+m}^T + gy_{-m} x_{-m}^T,   dWi = -gy_{+m} x_{-m}^T + gy_{-m} x_{+m}^T   (summed over the edges)."""
+    n = Xp.shape[0]
+    gXp = np.zeros_like(Xp)
+    ls0 = np.arange(lmax + 1)
+    i0 = ls0 * ls0 + ls0
+    x0 = Xp[:, i0, :].reshape(n, -1)
+    g0 = gYp[:, i0, :].reshape(n, -1)
+    gXp[:, i0, :] = (g0 @ np.asarray(W0, F64)).reshape(n, lmax + 1, -1)
+    dW0 = g0.T @ x0
+    dWr, dWi = [], []
+    for m in range(1, lmax + 1):
+        ls = np.arange(m, lmax + 1)
+        ip, im = ls * ls + ls + m, ls * ls + ls - m
+        xp, xm = Xp[:, ip, :].reshape(n, -1), Xp[:, im, :].reshape(n, -1)
+        gp, gm = gYp[:, ip, :].reshape(n, -1), gYp[:, im, :].reshape(n, -1)
+        A, B = np.asarray(Wr[m - 1], F64), np.asarray(Wi[m - 1], F64)
+        gXp[:, ip, :] = (gp @ A + gm @ B).reshape(n, len(ls), -1)
+        gXp[:, im, :] = (gm @ A - gp @ B).reshape(n, len(ls), -1)
+        dWr.append(gp.T @ xp + gm.T @ xm)
+        dWi.append(gm.T @ xp - gp.T @ xm)
+    return gXp, dW0, dWr, dWi
+
+
+def so2_message_sum_backward(graph, pos, box, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut, agg_norm, da, chunk=4096):
+    """Adjoint of so2_message_sum with respect to the node embeddings and the weights (positions are data):
+    from da [n_owned][(lmax+1)^2][E] returns (dx [n_total][(lmax+1)^2][E], dW_e, dW0, [dWr_m], [dWi_m]).
+    Every step of so2_messages is linear in (x, e) for fixed weights and linear in the weights for fixed inputs; the
+    steps are undone in reverse order: the scale and the envelope, the rotation back (adjoint: D), the per-|m| linear
+    layers (so2_linear_backward), the rotation into the bond frame (adjoint: D^T), the concatenation (its three
+    column groups go to x[src], x[dst] and, through the L = 0 plane only, to W_e)."""
+    src, dst, shift, row_ptr = graph
+    x = np.asarray(x, F64)
+    da = np.asarray(da, F64)
+    dx = np.zeros_like(x)
+    dW_e = np.zeros((E, n_rbf), F64)
+    shapes = so2_shapes(lmax, E)
+    dW0 = np.zeros(shapes[0], F64)
+    dWr = [np.zeros(s, F64) for s in shapes[1:]]
+    dWi = [np.zeros(s, F64) for s in shapes[1:]]
+    dim = (lmax + 1) ** 2
+    for k0 in range(0, len(src), chunk):
+        k1 = min(len(src), k0 + chunk)
+        s_, d_ = src[k0:k1], dst[k0:k1]
+        r = O.edge_vectors(pos, box, s_, d_, shift[k0:k1])
+        d = np.sqrt(np.einsum("ka,ka->k", r, r))
+        D = wigner_blocks(lmax, bond_rotations(r / d[:, None]))
+        B = O.radial_basis(d, n_rbf, r_cut)
+        M = np.zeros((k1 - k0, dim, 3 * E), F64)
+        M[:, :, :E] = x[s_]
+        M[:, :, E:2 * E] = x[d_]
+        M[:, 0, 2 * E:] = B @ np.asarray(W_e, F64).T
+        Xp = np.einsum("kab,kbc->kac", D, M)
+        gY = da[d_] * (O.envelope(d, r_cut) / sqrt(agg_norm))[:, None, None]
+        gYp = np.einsum("kab,kbc->kac", D, gY)
+        gXp, g0, gr, gi = so2_linear_backward(Xp, gYp, W0, Wr, Wi, lmax, E)
+        gM = np.einsum("kba,kbc->kac", D, gXp)
+        np.add.at(dx, s_, gM[:, :, :E])
+        np.add.at(dx, d_, gM[:, :, E:2 * E])
+        dW_e += gM[:, 0, 2 * E:].T @ B
+        dW0 += g0
+        for m in range(lmax):
+            dWr[m] += gr[m]
+            dWi[m] += gi[m]
+    return dx, dW_e, dW0, dWr, dWi
+
+
 # --------------------------------------------------------------------------------------
 # The two blocks of a layer with the full message content (Sec. 3 "Message passing", Fig. 2(b), 2(c)): persistent edge
 # embeddings, a node block that ends in an attention-weighted sum over incoming edges, an edge block without the sum.

@@ -174,3 +174,41 @@ def test_so2_pack_order():
     flat = S.so2_pack(W0, Wr, Wi)
     assert flat.dtype == np.float32 and flat.size == 108 + 2 * 48 + 2 * 12
     assert flat[19] == 19 and flat[108] == 10 and flat[108 + 48] == 20 and flat[108 + 96] == 11 and flat[-1] == 21
+
+
+def test_message_sum_backward_is_the_derivative_of_the_forward():
+    """Central differences of L = <a, da> along random directions of every argument (the map is linear in x and in each
+    weight group, so the difference quotient is exact up to rounding), and one entry of every group on its own."""
+    lmax, E, n_rbf, r_cut, agg = 3, 4, 6, 4.0, 5.0
+    w, g, x, W_e, W0, Wr, Wi = _setup(lmax, E, n_rbf=n_rbf, r_cut=r_cut, seed=3)
+    rng = np.random.default_rng(9)
+    da = rng.standard_normal((w.n_owned, (lmax + 1) ** 2, E))
+
+    def loss(x=x, W_e=W_e, W0=W0, Wr=Wr, Wi=Wi):
+        return float((S.so2_message_sum(g, w.pos, w.box, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut, agg) * da).sum())
+
+    dx, dW_e, dW0, dWr, dWi = S.so2_message_sum_backward(g, w.pos, w.box, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut, agg, da)
+    assert dx.shape == x.shape and dW_e.shape == W_e.shape and dW0.shape == W0.shape
+    h = 1e-3
+
+    def check(grad, name, make):
+        v = rng.standard_normal(grad.shape)
+        fd = (loss(**{name: make(+h * v)}) - loss(**{name: make(-h * v)})) / (2 * h)
+        assert fd == pytest.approx(float((grad * v).sum()), rel=1e-8, abs=1e-9), name
+        # one entry alone: a misplaced index that a random direction could average out
+        idx = tuple(rng.integers(0, s) for s in grad.shape)
+        e = np.zeros(grad.shape)
+        e[idx] = 1.0
+        fd = (loss(**{name: make(+h * e)}) - loss(**{name: make(-h * e)})) / (2 * h)
+        assert fd == pytest.approx(float(grad[idx]), rel=1e-8, abs=1e-9), (name, idx)
+
+    check(dx, "x", lambda t: x + t)
+    check(dW_e, "W_e", lambda t: W_e + t)
+    check(dW0, "W0", lambda t: W0 + t)
+    for m in range(lmax):
+        check(dWr[m], "Wr", lambda t, m=m: [a + (t if i == m else 0) for i, a in enumerate(Wr)])
+        check(dWi[m], "Wi", lambda t, m=m: [a + (t if i == m else 0) for i, a in enumerate(Wi)])
+    # halo atoms receive a gradient through the source side only; an atom with no edge at all receives none
+    src = g[0]
+    untouched = np.setdiff1d(np.arange(len(x)), np.concatenate([src, g[1]]))
+    assert np.all(dx[untouched] == 0)
