@@ -332,6 +332,20 @@ int egnn_so2_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, size_t* bytes
 int egnn_so2_message_sum(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3], const float* x,
                          const float* W_e, const float* W_so2, float* a, void* ws, size_t ws_bytes, void* stream);
 
+/* Adjoint of egnn_so2_message_sum with respect to the node embeddings and the weights (Sec. 4.1: training needs the
+ * gradients of the forward pass; positions are data).  da [n_owned][(lmax+1)^2][channels] is the gradient with respect
+ * to a.  Outputs are overwritten, not accumulated: dx [n_total][(lmax+1)^2][channels] (halo rows included: they
+ * receive the source side of their outgoing edges), dW_e [channels][n_rbf], dW_so2 in the layout of W_so2 (the
+ * columns g = 2 of l_in > 0, which multiply planes of the edge embedding that are zero on this path, get zero).
+ * col_ptr, perm: the source-sorted index of egnn_graph_transpose.  The forward operands are recomputed from the inputs;
+ * all sums over edges are taken in a fixed order (no floating-point atomics).  ws: at least
+ * egnn_so2_backward_workspace_bytes, 256-byte aligned; EGNN_EWS if too small.  Needs 8 .. 128 channels, n_rbf <= 32. */
+int egnn_so2_backward_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, size_t* bytes);
+int egnn_so2_message_sum_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm,
+                                  const float* pos, const float box[3], const float* x, const float* W_e,
+                                  const float* W_so2, const float* da, float* dx, float* dW_e, float* dW_so2, void* ws,
+                                  size_t ws_bytes, void* stream);
+
 /* ---- the two blocks of a layer with the full message content (Sec. 3 "Message passing"; Fig. 2(b), 2(c)) ----
  * Edge embeddings T_edge [n_edges][(lmax+1)^2][channels] are persistent tensors that rotate like node embeddings;
  * the message of edge k is [x_src | x_dst | T_edge_k] in every degree (3 * channels), transformed as in

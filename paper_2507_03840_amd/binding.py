@@ -23,7 +23,8 @@ SYMBOLS = [
     "egnn_layer_forward", "egnn_readout_hij", "egnn_timing_enable", "egnn_timing_read",
     "egnn_backward_workspace_bytes", "egnn_graph_transpose", "egnn_loss_mse", "egnn_layer_backward",
     "egnn_readout_backward", "egnn_set_option", "egnn_radial_weights_f16", "egnn_tp_segsum_f16", "egnn_so2_weight_count", "egnn_so2_workspace_bytes",
-    "egnn_so2_message_sum", "egnn_so2_blocks_workspace_bytes", "egnn_edge_embed_init", "egnn_so2_node_block",
+    "egnn_so2_message_sum", "egnn_so2_backward_workspace_bytes", "egnn_so2_message_sum_backward",
+    "egnn_so2_blocks_workspace_bytes", "egnn_edge_embed_init", "egnn_so2_node_block",
     "egnn_so2_edge_block", "egnn_gate", "egnn_hamiltonian_workspace_bytes", "egnn_onsite_hii", "egnn_apply_padding", "egnn_loss_l1l2",
     "egnn_hamiltonian_structure", "egnn_hamiltonian_fill", "egnn_onsite_backward_workspace_bytes", "egnn_onsite_backward",
     "egnn_partition_low_nn", "egnn_pack_rows", "egnn_unpack_rows",
@@ -337,6 +338,22 @@ class Egnn:
         self._check(self.lib.egnn_so2_message_sum(self.ctx, C.byref(g), _ptr(pos), _f3(box), _ptr(x), _ptr(W_e),
                                                   _ptr(W_so2), _ptr(a), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
         return a
+
+    def egnn_so2_backward_workspace_bytes(self, n_edges, n_owned):
+        out = C.c_size_t()
+        self._check(self.lib.egnn_so2_backward_workspace_bytes(self.ctx, C.c_int64(n_edges), C.c_int32(n_owned),
+                                                               C.byref(out)))
+        return out.value
+
+    def egnn_so2_message_sum_backward(self, graph, col_ptr, perm, pos, box, x, W_e, W_so2, da, ws):
+        """(dx [n_total][dim][channels], dW_e, dW_so2) from da [n_owned][dim][channels]."""
+        dx = torch.empty((graph.n_total, self.dim, self.channels), dtype=torch.float32, device="cuda")
+        dW_e, dW_so2 = torch.empty_like(W_e), torch.empty_like(W_so2)
+        g = graph.desc()
+        self._check(self.lib.egnn_so2_message_sum_backward(
+            self.ctx, C.byref(g), _ptr(col_ptr), _ptr(perm), _ptr(pos), _f3(box), _ptr(x), _ptr(W_e), _ptr(W_so2),
+            _ptr(da), _ptr(dx), _ptr(dW_e), _ptr(dW_so2), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+        return dx, dW_e, dW_so2
 
     def egnn_so2_blocks_workspace_bytes(self, n_edges):
         out = C.c_size_t()

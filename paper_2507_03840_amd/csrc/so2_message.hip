@@ -224,7 +224,7 @@ __device__ __forceinline__ float so2_b_value(const float* __restrict__ W, int m,
 // T[ct][step][j][piece][64] halves (two pieces: see stream_gemm.h): thread -> (ct, step, j, pair of contraction indices)
 __global__ __launch_bounds__(256) void so2_pack_kernel(const float* __restrict__ W, uint16_t* __restrict__ T, int m, int lmax,
                                                        int E, int K, int N, int n_steps, int n_ct, bool full,
-                                                       const unsigned* __restrict__ w_max) {
+                                                       const unsigned* __restrict__ w_max, bool transposed) {
   const long i = (long)blockIdx.x * 256 + threadIdx.x;
   const long total = (long)n_ct * n_steps * 64 * 32;
   if (i >= total) return;
@@ -233,7 +233,10 @@ __global__ __launch_bounds__(256) void so2_pack_kernel(const float* __restrict__
   const int step = (int)(blk % n_steps), ct = (int)(blk / n_steps);
   const int n = ct * 64 + j, k = step * 64 + 2 * rp;
   const float sc = ldexpf(1.0f, sgh_scale_exp(*w_max));
-  const float xv[8] = {so2_b_value(W, m, lmax, E, k, n, K, N, full), so2_b_value(W, m, lmax, E, k + 1, n, K, N, full),
+  // transposed: the operand is B_m^T (contraction over the columns of Y_m, one output column per column of A_m)
+  const float xv[8] = {transposed ? so2_b_value(W, m, lmax, E, n, k, K, N, full) : so2_b_value(W, m, lmax, E, k, n, K, N, full),
+                       transposed ? so2_b_value(W, m, lmax, E, n, k + 1, K, N, full)
+                                  : so2_b_value(W, m, lmax, E, k + 1, n, K, N, full),
                        0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
   uint4 hi, lo;
   sgh_split8(xv, sc, hi, lo);
@@ -544,7 +547,8 @@ static int so2_transform(egnn_ctx* ctx, const egnn_graph* g, const float* pos, c
     const int K = call->b.K[m], N = call->b.N[m], n_steps = so2_steps(K), n_ct = so2_tiles(N);
     const long total = (long)n_ct * n_steps * 64 * 32;
     hipLaunchKernelGGL(so2_pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                       W_so2 + so2_w_offset(lmax, E, m), call->T[m], m, lmax, E, K, N, n_steps, n_ct, full, call->maxima + 1);
+                       W_so2 + so2_w_offset(lmax, E, m), call->T[m], m, lmax, E, K, N, n_steps, n_ct, full, call->maxima + 1,
+                       false);
     EGNN_LAUNCH_CHECK(ctx, "so2_pack_kernel");
     const long rows_per_wg = 64L * SG_WAVES;
     const int n_row_blocks = (int)((n + rows_per_wg - 1) / rows_per_wg);
@@ -669,5 +673,433 @@ extern "C" int egnn_gate(egnn_ctx* ctx, const float* x, const float* W_g, float*
   hipLaunchKernelGGL(so2_gate_kernel, dim3(n_nodes), dim3(256), 0, (hipStream_t)stream, x, W_g, y, ctx->desc.lmax,
                      ctx->log2_channels);
   EGNN_LAUNCH_CHECK(ctx, "so2_gate_kernel");
+  return EGNN_OK;
+}
+
+// =====================================================================================================================
+// Reverse pass of egnn_so2_message_sum (adjoint with respect to the node embeddings and the weights; positions are
+// data).  Every step of the forward pass is linear in (x, W_e) for fixed weights and linear in the weights for fixed
+// inputs, so the reverse pass is the same chain read backwards:
+//   1. so2_gather_kernel       the operands A_m of the forward pass again (they are the inputs of the weight gradient);
+//   2. so2_dy_kernel           dY_m[k] = bond-frame rotation of  agg_norm^-1/2 f_c(d_k) da[dst(k)], m-major like Y_m;
+//   3. so2_wgrad_kernel        dB_m = A_m^T dY_m, a contraction over the edges: exact fp32 matrix-core products
+//                              (v_mfma_f32_32x32x2_f32, both operands read in memory order: the contraction index is
+//                              the row index of both), partial sums per chunk of edges added in a fixed order;
+//      so2_unpack_wgrad_kernel dB_m = [[dWr^T, dWi^T], [-dWi^T, dWr^T]] folded back into the layout of the weights;
+//   4. so2_gemm_kernel         dA_m = dY_m B_m^T with the packed operand transposed, written over A_m;
+//   5. so2_dx_kernel           one workgroup per destination node: the two node parts of dA_m[k] rotated back to the
+//                              lab frame; the destination part is summed over the node's incoming edges, the source
+//                              part goes to a per-edge row that a segmented sum over the source-sorted index adds up;
+//      so2_dwe_kernel          dW_e[c][q] = sum_k dA_0[k][edge column c] B_q(d_k).
+// ---------------------------------------------------------------------------------------------------------------------
+template <int LMAX>
+__global__ __launch_bounds__(256) void so2_dy_kernel(const int* __restrict__ dst, const float4* __restrict__ rhat_d,
+                                                     const float* __restrict__ da, So2Bufs b, long n_edges, int log2E,
+                                                     float scale, float r_cut, unsigned* __restrict__ y_max) {
+  constexpr int D = (LMAX + 1) * (LMAX + 1);
+  const int E = 1 << log2E;
+  const int c = threadIdx.x & (E - 1);
+  const long k_own = (long)blockIdx.x * (256 >> log2E) + (threadIdx.x >> log2E);
+  const bool live = k_own < n_edges;
+  const long k = live ? k_own : n_edges - 1;   // (as in the gather kernel: every lane takes part in the reduction)
+  const float4 g = rhat_d[k];
+  const float f = scale * egnn_envelope(g.w, r_cut);
+  const float* dj = da + (((size_t)dst[k] * D) << log2E) + c;
+  float v[D];
+#pragma unroll
+  for (int i = 0; i < D; ++i) v[i] = f * dj[(size_t)i << log2E];
+  BondTrig t;
+  egnn_bond_trig<LMAX>(g.x, g.y, g.z, t);
+  egnn_to_bond_frame<LMAX>(v, t);            // Y = D^T Y' in the forward pass, so dY' = D dY
+  float amax = 0.0f;
+#pragma unroll
+  for (int i = 0; i < D; ++i) amax = fmaxf(amax, fabsf(v[i]));
+  if (live) {
+    float* y0 = b.Y[0] + (size_t)k * b.N[0] + c;
+#pragma unroll
+    for (int l = 0; l <= LMAX; ++l) __builtin_nontemporal_store(v[l * l + l], y0 + (l << log2E));
+#pragma unroll
+    for (int m = 1; m <= LMAX; ++m) {
+      const int nl = LMAX + 1 - m;
+      float* ym = b.Y[m] + (size_t)k * b.N[m] + c;
+#pragma unroll
+      for (int l = m; l <= LMAX; ++l) {
+        __builtin_nontemporal_store(v[l * l + l + m], ym + ((l - m) << log2E));
+        __builtin_nontemporal_store(v[l * l + l - m], ym + ((nl + l - m) << log2E));
+      }
+    }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+  if ((threadIdx.x & 63) == 0) so2_raise_max(y_max, amax);
+}
+
+// partial[chunk][k][n] = sum over the edges e of the chunk of A[e][k] Y[e][n].  Workgroup = (128 x 128 tile of the
+// result, chunk of edges); each of its four waves owns a 64 x 64 quarter as 2 x 2 accumulators of 32 x 32.  One
+// matrix-core instruction contracts two edges: lane (i, h) feeds A[e + h][k0 + i] and Y[e + h][n0 + i].  Columns past
+// the last one are clamped (their results are not stored), edges past the chunk feed zeros.
+#define SW_UNROLL 8
+__global__ __launch_bounds__(256) void so2_wgrad_kernel(const float* __restrict__ A, int K, const float* __restrict__ Y,
+                                                        int N, long n_edges, long per_chunk, int tiles_n,
+                                                        float* __restrict__ partial) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int i32 = lane & 31, hh = lane >> 5;
+  const int tk = blockIdx.x / tiles_n, tn = blockIdx.x - tk * tiles_n;
+  const int k0 = tk * 128 + (wave >> 1) * 64, n0 = tn * 128 + (wave & 1) * 64;
+  if (k0 >= K || n0 >= N) return;            // (no barrier in this kernel)
+  const long e_begin = (long)blockIdx.y * per_chunk;
+  long e_end = e_begin + per_chunk;
+  if (e_end > n_edges) e_end = n_edges;
+  const int ka[2] = {k0 + i32 < K ? k0 + i32 : K - 1, k0 + 32 + i32 < K ? k0 + 32 + i32 : K - 1};
+  const int nb[2] = {n0 + i32 < N ? n0 + i32 : N - 1, n0 + 32 + i32 < N ? n0 + 32 + i32 : N - 1};
+  float16v acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][q][i] = 0.0f;
+  for (long e = e_begin; e < e_end; e += 2 * SW_UNROLL) {
+    float av[SW_UNROLL][2], yv[SW_UNROLL][2];
+#pragma unroll
+    for (int u = 0; u < SW_UNROLL; ++u) {
+      const long ee = e + 2 * u + hh;
+      const bool ok = ee < e_end;
+      const long er = ok ? ee : e_end - 1;   // (e_begin < e_end inside the loop)
+      const float* ar = A + (size_t)er * K;
+      const float* yr = Y + (size_t)er * N;
+      av[u][0] = ok ? ar[ka[0]] : 0.0f;
+      av[u][1] = ok ? ar[ka[1]] : 0.0f;
+      yv[u][0] = ok ? yr[nb[0]] : 0.0f;
+      yv[u][1] = ok ? yr[nb[1]] : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < SW_UNROLL; ++u)
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+          acc[a][q] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u][a], yv[u][q], acc[a][q], 0, 0, 0);
+  }
+  float* out = partial + (size_t)blockIdx.y * K * N;
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int nn = n0 + q * 32 + i32;
+      if (nn < N) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int kk = k0 + a * 32 + 8 * (i >> 2) + 4 * hh + (i & 3);
+          if (kk < K) out[(size_t)kk * N + nn] = acc[a][q][i];
+        }
+      }
+    }
+}
+
+// dB_m [K][N] (column orders of A_m and Y_m, without persistent edge embeddings) -> gradient of W_0 (m = 0) or of
+// (Wr_m, Wi_m), row-major like the weights.  Weight columns that multiply the planes l > 0 of the edge embedding, which
+// are zero in this path, have gradient zero.  One thread per weight element of W_0 / Wr_m.
+__global__ __launch_bounds__(256) void so2_unpack_wgrad_kernel(const float* __restrict__ dB, float* __restrict__ dW, int m,
+                                                               int lmax, int E, int N) {
+  const int nl = lmax + 1 - m;
+  const int rows = nl * E, cols = nl * 3 * E;
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long)rows * cols) return;
+  const int row = (int)(idx / cols), col = (int)(idx - (long)row * cols);
+  const int li = col / (3 * E), rem = col - li * 3 * E;
+  const int gsel = rem / E, c = rem - gsel * E;
+  if (m == 0) {
+    int k = -1;
+    if (gsel < 2) k = li * 2 * E + gsel * E + c;
+    else if (li == 0) k = (lmax + 1) * 2 * E + c;
+    dW[idx] = k >= 0 ? dB[(size_t)k * N + row] : 0.0f;
+    return;
+  }
+  float gr = 0.0f, gi = 0.0f;
+  if (gsel < 2) {
+    const int kr = li * 2 * E + gsel * E + c, half_k = nl * 2 * E, half_n = nl * E;
+    const float pp = dB[(size_t)kr * N + row], mm = dB[(size_t)(half_k + kr) * N + half_n + row];
+    const float pm = dB[(size_t)kr * N + half_n + row], mp = dB[(size_t)(half_k + kr) * N + row];
+    gr = pp + mm;     // Wr takes x_{+m} to y_{+m} and x_{-m} to y_{-m}
+    gi = pm - mp;     // Wi takes x_{+m} to y_{-m} and, with a minus sign, x_{-m} to y_{+m}
+  }
+  dW[idx] = gr;
+  dW[(size_t)rows * cols + idx] = gi;
+}
+
+// One workgroup per destination node j, lane = (edge slot, channel): the node parts of dA_m[k] back in (l, m) order and
+// in the lab frame (X' = D M in the forward pass, so dM = D^T dX').  Source part -> rows[k], destination part summed
+// over the incoming edges of j in a fixed order -> dxd[j].
+template <int LMAX>
+__global__ __launch_bounds__(256) void so2_dx_kernel(const int* __restrict__ row_ptr, const float4* __restrict__ rhat_d,
+                                                     So2Bufs b, float* __restrict__ rows, float* __restrict__ dxd,
+                                                     int n_owned, int log2E, int nodes_per_xcd) {
+  constexpr int D = (LMAX + 1) * (LMAX + 1);
+  __shared__ float red[256 * D];
+  const int j = (blockIdx.x & 7) * nodes_per_xcd + (blockIdx.x >> 3);
+  if (j >= n_owned || (int)(blockIdx.x >> 3) >= nodes_per_xcd) return;
+  const int E = 1 << log2E;
+  const int tid = threadIdx.x;
+  const int c = tid & (E - 1), slot = tid >> log2E, n_slots = 256 >> log2E;
+  const int k0 = row_ptr[j], k1 = row_ptr[j + 1];
+  float acc[D];
+#pragma unroll
+  for (int i = 0; i < D; ++i) acc[i] = 0.0f;
+  for (int k = k0 + slot; k < k1; k += n_slots) {
+    const float4 g = rhat_d[k];
+    float vs[D], vd[D];
+    const float* a0 = b.A[0] + (size_t)k * b.K[0] + c;
+#pragma unroll
+    for (int l = 0; l <= LMAX; ++l) {
+      vs[l * l + l] = __builtin_nontemporal_load(a0 + ((2 * l) << log2E));
+      vd[l * l + l] = __builtin_nontemporal_load(a0 + ((2 * l + 1) << log2E));
+    }
+#pragma unroll
+    for (int m = 1; m <= LMAX; ++m) {
+      const int nl = LMAX + 1 - m;
+      const float* am = b.A[m] + (size_t)k * b.K[m] + c;
+#pragma unroll
+      for (int l = m; l <= LMAX; ++l) {
+        const int col = (2 * (l - m)) << log2E, neg = (2 * nl) << log2E;
+        vs[l * l + l + m] = __builtin_nontemporal_load(am + col);
+        vd[l * l + l + m] = __builtin_nontemporal_load(am + col + E);
+        vs[l * l + l - m] = __builtin_nontemporal_load(am + neg + col);
+        vd[l * l + l - m] = __builtin_nontemporal_load(am + neg + col + E);
+      }
+    }
+    BondTrig t;
+    egnn_bond_trig<LMAX>(g.x, g.y, g.z, t);
+    egnn_from_bond_frame<LMAX>(vs, t);
+    egnn_from_bond_frame<LMAX>(vd, t);
+    float* rk = rows + (((size_t)k * D) << log2E) + c;
+#pragma unroll
+    for (int i = 0; i < D; ++i) {
+      __builtin_nontemporal_store(vs[i], rk + ((size_t)i << log2E));
+      acc[i] += vd[i];
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < D; ++i) red[((slot * D + i) << log2E) + c] = acc[i];
+  __syncthreads();
+  const int row = D << log2E;
+  float* out = dxd + (size_t)j * row;
+  for (int idx = tid; idx < row; idx += 256) {
+    float sum = 0.0f;
+    for (int s = 0; s < n_slots; ++s) sum += red[s * row + idx];
+    out[idx] = sum;
+  }
+}
+
+// dx[i] += dxd[i] for the owned nodes (dx holds the sums over outgoing edges of all nodes)
+__global__ __launch_bounds__(256) void so2_add_kernel(float* __restrict__ dx, const float* __restrict__ dxd, long n) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dx[i] += dxd[i];
+}
+
+// partial[chunk][c][q] = sum over the edges k of the chunk of de[k][c] B_q(d_k), de = the edge columns of dA_0.
+// A thread owns the outputs o = tid + 256 s (c = o mod E: neighbouring threads read neighbouring columns).
+#define SO2_DWE_CHUNKS 256
+__global__ __launch_bounds__(256) void so2_dwe_kernel(const float4* __restrict__ rhat_d, const float* __restrict__ A0, int K0,
+                                                      int edge_col0, long n_edges, long per_chunk, int log2E, int n_rbf,
+                                                      float r_cut, float* __restrict__ partial) {
+  const int E = 1 << log2E, n_out = n_rbf << log2E;
+  const long e_begin = (long)blockIdx.x * per_chunk;
+  long e_end = e_begin + per_chunk;
+  if (e_end > n_edges) e_end = n_edges;
+  const float step = r_cut / (float)(n_rbf - 1);
+  const float inv2s2 = 0.5f / (step * step);
+  float acc[16];    // E n_rbf <= 128 * 32 = 16 * 256
+#pragma unroll
+  for (int s = 0; s < 16; ++s) acc[s] = 0.0f;
+  for (long k = e_begin; k < e_end; ++k) {
+    const float d = rhat_d[k].w;
+    const float* de = A0 + (size_t)k * K0 + edge_col0;
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+      const int o = threadIdx.x + 256 * s;
+      if (o < n_out) {
+        const float u = d - (float)(o >> log2E) * step;
+        acc[s] += de[o & (E - 1)] * __expf(-u * u * inv2s2);
+      }
+    }
+  }
+  float* out = partial + (size_t)blockIdx.x * n_out;
+#pragma unroll
+  for (int s = 0; s < 16; ++s) {
+    const int o = threadIdx.x + 256 * s;
+    if (o < n_out) out[(o & (E - 1)) * n_rbf + (o >> log2E)] = acc[s];
+  }
+}
+
+// chunks of edges of the weight gradient of one order: enough workgroups for two per compute unit, at most 128 chunks,
+// every chunk a multiple of 2 * SW_UNROLL edges
+static void so2_wgrad_split(long n, int K, int N, int* chunks, long* per_chunk) {
+  const int tiles = ((K + 127) / 128) * ((N + 127) / 128);
+  long c = (512 + tiles - 1) / tiles;
+  if (c > 128) c = 128;
+  long per = (n + c - 1) / c;
+  per = (per + 2 * SW_UNROLL - 1) / (2 * SW_UNROLL) * (2 * SW_UNROLL);
+  if (per < 2 * SW_UNROLL) per = 2 * SW_UNROLL;
+  *per_chunk = per;
+  *chunks = (int)((n + per - 1) / per);
+}
+
+struct So2Bwd {
+  float* rows;      // [n_edges][D][E] source parts of dM
+  float* dxd;       // [n_owned][D][E]
+  float* partial;   // partial weight gradients of one order
+  float* dB;        // [K_m][N_m] of one order
+  float* dwe;       // [SO2_DWE_CHUNKS][E][n_rbf]
+};
+
+static size_t so2_bwd_ws(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, bool carve, char* base, So2Bwd* out) {
+  const int lmax = ctx->desc.lmax, E = ctx->desc.channels, D = (lmax + 1) * (lmax + 1);
+  size_t used = so2_ws(ctx, n_edges, false, false, nullptr, nullptr, nullptr, nullptr, nullptr);
+  auto take = [&](size_t bytes) { char* p = carve ? base + used : nullptr; used += so2_a256(bytes); return p; };
+  size_t part = 0, db = 0;
+  for (int m = 0; m <= lmax; ++m) {
+    const int K = so2_K(lmax, E, m), N = so2_N(lmax, E, m);
+    int chunks;
+    long per;
+    so2_wgrad_split(n_edges > 0 ? n_edges : 1, K, N, &chunks, &per);
+    part = std::max(part, (size_t)chunks * K * N);
+    db = std::max(db, (size_t)K * N);
+  }
+  So2Bwd w;
+  w.rows = (float*)take((size_t)n_edges * D * E * sizeof(float));
+  w.dxd = (float*)take((size_t)n_owned * D * E * sizeof(float));
+  w.partial = (float*)take(part * sizeof(float));
+  w.dB = (float*)take(db * sizeof(float));
+  w.dwe = (float*)take((size_t)SO2_DWE_CHUNKS * E * ctx->desc.n_rbf * sizeof(float));
+  if (out) *out = w;
+  return used;
+}
+
+extern "C" int egnn_so2_backward_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, size_t* bytes) {
+  if (!ctx || !bytes || n_edges < 0 || n_owned < 0) return EGNN_EINVAL;
+  *bytes = so2_bwd_ws(ctx, n_edges, n_owned, false, nullptr, nullptr) + 256;
+  return EGNN_OK;
+}
+
+extern "C" int egnn_so2_message_sum_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr,
+                                             const int32_t* perm, const float* pos, const float box[3], const float* x,
+                                             const float* W_e, const float* W_so2, const float* da, float* dx,
+                                             float* dW_e, float* dW_so2, void* ws, size_t ws_bytes, void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  if (!pos || !box || !x || !W_e || !W_so2 || !dW_e || !dW_so2 || !col_ptr)
+    return egnn_fail(ctx, EGNN_EINVAL, "so2_message_sum_backward: null pointer");
+  int rc = so2_check(ctx, g, ws, ws_bytes, false, "so2_message_sum_backward");
+  if (rc) return rc;
+  if (ctx->desc.channels > 128 || ctx->desc.n_rbf > 32)
+    return egnn_fail(ctx, EGNN_EINVAL, "so2_message_sum_backward: needs <= 128 channels and <= 32 radial bases");
+  if ((g->n_total > 0 && !dx) || (g->n_owned > 0 && !da) || (g->n_edges > 0 && !perm))
+    return egnn_fail(ctx, EGNN_EINVAL, "so2_message_sum_backward: null pointer");
+  if (ws_bytes < so2_bwd_ws(ctx, g->n_edges, g->n_owned, false, nullptr, nullptr))
+    return egnn_fail(ctx, EGNN_EWS, "so2_message_sum_backward: workspace too small");
+  hipStream_t st = (hipStream_t)stream;
+  const int lmax = ctx->desc.lmax, E = ctx->desc.channels, D = (lmax + 1) * (lmax + 1), n_rbf = ctx->desc.n_rbf;
+  const long n = g->n_edges;
+  const long n_w = (long)so2_w_offset(lmax, E, lmax + 1);
+  if (n == 0) {
+    // no message: every gradient is zero (a float zero is the integer zero)
+    if ((rc = egnn_launch_fill_int(ctx, (int*)dx, (long)g->n_total * D * E, 0, st))) return rc;
+    if ((rc = egnn_launch_fill_int(ctx, (int*)dW_e, (long)E * n_rbf, 0, st))) return rc;
+    return egnn_launch_fill_int(ctx, (int*)dW_so2, n_w, 0, st);
+  }
+  So2Call call;
+  for (int m = 0; m < 5; ++m) { call.b.A[m] = call.b.Y[m] = nullptr; call.b.K[m] = call.b.N[m] = 0; call.T[m] = nullptr; }
+  call.alpha = nullptr;
+  so2_ws(ctx, n, false, true, (char*)ws, &call.rhat_d, &call.b, call.T, &call.alpha, &call.maxima);
+  So2Bwd w;
+  so2_bwd_ws(ctx, n, g->n_owned, true, (char*)ws, &w);
+  // maxima[0]: largest |dY| (operand of the GEMMs of step 4), [1]: largest weight, [2]: largest |A| (not used here)
+  if ((rc = egnn_launch_fill_int(ctx, (int*)call.maxima, 64, 0, st))) return rc;
+  if ((rc = egnn_launch_geometry(ctx, g, pos, box, call.rhat_d, nullptr, nullptr, nullptr, st))) return rc;
+  const float4* rd = reinterpret_cast<const float4*>(call.rhat_d);
+  const int per_wg = 256 / E;
+  const dim3 egrid((unsigned)((n + per_wg - 1) / per_wg)), block(256);
+  const float scale = 1.0f / sqrtf(ctx->desc.agg_norm);
+#define SO2_BY_LMAX(STMT)          \
+  switch (lmax) {                  \
+    case 0: { STMT(0); } break;    \
+    case 1: { STMT(1); } break;    \
+    case 2: { STMT(2); } break;    \
+    case 3: { STMT(3); } break;    \
+    default: { STMT(4); } break;   \
+  }
+#define GATHER(L)                                                                                                    \
+  hipLaunchKernelGGL((so2_gather_kernel<L, false>), egrid, block, 0, st, g->src, g->dst, rd, x, W_e, call.b, n,      \
+                     ctx->log2_channels, n_rbf, ctx->desc.r_cut, call.maxima + 2)
+  SO2_BY_LMAX(GATHER)
+#undef GATHER
+  EGNN_LAUNCH_CHECK(ctx, "so2_gather_kernel");
+#define DY(L)                                                                                                        \
+  hipLaunchKernelGGL(so2_dy_kernel<L>, egrid, block, 0, st, g->dst, rd, da, call.b, n, ctx->log2_channels, scale,    \
+                     ctx->desc.r_cut, call.maxima)
+  SO2_BY_LMAX(DY)
+#undef DY
+  EGNN_LAUNCH_CHECK(ctx, "so2_dy_kernel");
+  {
+    const unsigned wg = (unsigned)((n_w + 255) / 256 < 256 ? (n_w + 255) / 256 : 256);
+    hipLaunchKernelGGL(so2_wmax_kernel, dim3(wg), dim3(256), 0, st, W_so2, n_w, call.maxima + 1);
+    EGNN_LAUNCH_CHECK(ctx, "so2_wmax_kernel");
+  }
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(so2_gemm_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)SGH_LDS_BYTES);
+  if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(so2_gemm_kernel)");
+  for (int m = 0; m <= lmax; ++m) {
+    const int K = call.b.K[m], N = call.b.N[m];
+    int chunks;
+    long per;
+    so2_wgrad_split(n, K, N, &chunks, &per);
+    const int tiles_n = (N + 127) / 128, tiles_k = (K + 127) / 128;
+    hipLaunchKernelGGL(so2_wgrad_kernel, dim3(tiles_k * tiles_n, chunks), dim3(256), 0, st, call.b.A[m], K, call.b.Y[m], N,
+                       n, per, tiles_n, w.partial);
+    EGNN_LAUNCH_CHECK(ctx, "so2_wgrad_kernel");
+    if ((rc = egnn_launch_reduce_partials(ctx, w.partial, chunks, (long)K * N, w.dB, 1.0f, st))) return rc;
+    const int nl = lmax + 1 - m;
+    const long n_el = (long)nl * E * nl * 3 * E;
+    hipLaunchKernelGGL(so2_unpack_wgrad_kernel, dim3((unsigned)((n_el + 255) / 256)), dim3(256), 0, st, w.dB,
+                       dW_so2 + so2_w_offset(lmax, E, m), m, lmax, E, N);
+    EGNN_LAUNCH_CHECK(ctx, "so2_unpack_wgrad_kernel");
+    // dA_m = dY_m B_m^T over A_m: contraction over the N columns of Y_m, one output column per column of A_m
+    const int n_steps = so2_steps(N), n_ct = so2_tiles(K);
+    const long total = (long)n_ct * n_steps * 64 * 32;
+    hipLaunchKernelGGL(so2_pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       W_so2 + so2_w_offset(lmax, E, m), call.T[m], m, lmax, E, K, N, n_steps, n_ct, false, call.maxima + 1,
+                       true);
+    EGNN_LAUNCH_CHECK(ctx, "so2_pack_kernel");
+    const long rows_per_wg = 64L * SG_WAVES;
+    const int n_row_blocks = (int)((n + rows_per_wg - 1) / rows_per_wg);
+    const unsigned grid_x = (unsigned)(((n_row_blocks + 7) / 8) * 8 * n_ct);
+    hipLaunchKernelGGL(so2_gemm_kernel, dim3(grid_x), dim3(SG_THREADS), SGH_LDS_BYTES, st, call.b.Y[m], n, N, call.T[m],
+                       n_steps, call.b.A[m], K, n_ct, n_row_blocks, call.maxima);
+    EGNN_LAUNCH_CHECK(ctx, "so2_gemm_kernel");
+  }
+  {
+    const long per = (n + SO2_DWE_CHUNKS - 1) / SO2_DWE_CHUNKS;
+    const int chunks = (int)((n + per - 1) / per);
+    hipLaunchKernelGGL(so2_dwe_kernel, dim3(chunks), dim3(256), 0, st, rd, call.b.A[0], call.b.K[0], (lmax + 1) * 2 * E, n,
+                       per, ctx->log2_channels, n_rbf, ctx->desc.r_cut, w.dwe);
+    EGNN_LAUNCH_CHECK(ctx, "so2_dwe_kernel");
+    if ((rc = egnn_launch_reduce_partials(ctx, w.dwe, chunks, (long)E * n_rbf, dW_e, 1.0f, st))) return rc;
+  }
+  if (g->n_owned > 0) {
+    const int per_xcd = (g->n_owned + 7) / 8;
+#define DX(L)                                                                                                       \
+  hipLaunchKernelGGL(so2_dx_kernel<L>, dim3(per_xcd * 8), dim3(256), 0, st, g->row_ptr, rd, call.b, w.rows, w.dxd,   \
+                     g->n_owned, ctx->log2_channels, per_xcd)
+    SO2_BY_LMAX(DX)
+#undef DX
+    EGNN_LAUNCH_CHECK(ctx, "so2_dx_kernel");
+  }
+#undef SO2_BY_LMAX
+  if ((rc = egnn_launch_segsum_rows(ctx, w.rows, col_ptr, perm, dx, g->n_total, D * E, st))) return rc;
+  const long n_own = (long)g->n_owned * D * E;
+  if (n_own > 0) {
+    hipLaunchKernelGGL(so2_add_kernel, dim3((unsigned)((n_own + 255) / 256)), dim3(256), 0, st, dx, w.dxd, n_own);
+    EGNN_LAUNCH_CHECK(ctx, "so2_add_kernel");
+  }
   return EGNN_OK;
 }

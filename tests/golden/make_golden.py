@@ -12,6 +12,7 @@ equal the oracle's own composite calls.
 
     python tests/golden/make_golden.py 3 4 5
     python tests/golden/make_golden.py so2:3 so2:4      (SO(2) message sums at sampled nodes)
+    python tests/golden/make_golden.py so2bwd:3         (adjoint of the SO(2) message sum: weight gradients, rows of dx)
     python tests/golden/make_golden.py w16:3 w16:4      (first layer and readout with half-precision path weights)
     python tests/golden/make_golden.py blocks:3 blocks:4  (node block and edge block with full message content)
 """
@@ -131,6 +132,56 @@ def make_so2(index, pool_size):
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"config{index}_so2_samples.npz")
     np.savez_compressed(path, nodes=nodes, rows=rows, agg=agg, n_edges=len(g[0]))
     print(f"config {index} so2: wrote {path}, max|a| over samples {np.abs(rows).max():.4f}, {time.time() - t0:.0f} s", flush=True)
+
+
+def _so2_backward_chunk(k_range):
+    """Edges k_range of the adjoint of the SO(2) message sum (it is a sum over the edges)."""
+    from oracle import so2_oracle as S
+    w, g, x, Wso2, agg, da = _state["w"], _state["g"], _state["x"], _state["Wso2"], _state["agg"], _state["da"]
+    W_e, W0, Wr, Wi = Wso2
+    k0, k1 = k_range
+    sub = (g[0][k0:k1], g[1][k0:k1], g[2][k0:k1], g[3])
+    return S.so2_message_sum_backward(sub, w.pos, w.box, x, W_e, W0, Wr, Wi, w.lmax, w.channels, w.n_rbf, w.r_cut, agg, da)
+
+
+def make_so2_backward(index, pool_size):
+    """Adjoint of the SO(2) message sum of the full-size configuration -> config{index}_so2_backward.npz: all weight
+    gradients and the rows of dx at aimed nodes.  Inputs as make_so2; da ~ N(0, 1) from seed [w.seed, 778]."""
+    t0 = time.time()
+    w = synth.workload(index)
+    wt = U.model_weights(w)
+    g = U.oracle_graph(w)
+    agg = U.mean_degree(g, w.n_owned)
+    x = O.species_embed(wt["x0"], w.species, wt["table"])
+    Wso2 = synth.so2_weights(np.random.default_rng([w.seed, 777]), w.lmax, w.channels, w.n_rbf)
+    da = U.so2_da(w)
+    _state.update(w=w, g=g, x=x, Wso2=Wso2, agg=agg, da=da)
+    n_e = len(g[0])
+    step = 8192
+    jobs = [(k0, min(n_e, k0 + step)) for k0 in range(0, n_e, step)]
+    total = None
+    with ProcessPoolExecutor(pool_size) as ex:
+        for part in ex.map(_so2_backward_chunk, jobs):
+            flat = [part[0], part[1], part[2]] + list(part[3]) + list(part[4])
+            if total is None:
+                total = flat
+            else:
+                for acc, v in zip(total, flat):
+                    acc += v
+    dx, dW_e, dW0 = total[0], total[1], total[2]
+    dWr, dWi = total[3:3 + w.lmax], total[3 + w.lmax:]
+    from oracle import so2_oracle as S
+    rng = np.random.default_rng([w.seed, 4244])
+    nodes = aimed_nodes(w, g, rng, w.n_total)
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"config{index}_so2_backward.npz")
+    out = dict(nodes=nodes, dx_rows=dx[nodes], dx_maxabs=np.abs(dx).max(), dx_maxabs_l=maxabs_per_degree(dx, w.lmax),
+               dW_e=dW_e, dW0=dW0, agg=agg, n_edges=n_e)
+    for m in range(w.lmax):
+        out[f"dWr{m + 1}"] = dWr[m]
+        out[f"dWi{m + 1}"] = dWi[m]
+    np.savez_compressed(path, **out)
+    print(f"config {index} so2 backward: wrote {path}, {os.path.getsize(path) / 1e3:.0f} kB, max|dx| {np.abs(dx).max():.4f}, "
+          f"{time.time() - t0:.0f} s", flush=True)
 
 
 def _blocks_nodes(nodes):
@@ -374,6 +425,8 @@ if __name__ == "__main__":
     for a in sys.argv[1:]:
         if a.startswith("so2:"):   # e.g. so2:3 so2:4
             make_so2(int(a[4:]), procs)
+        if a.startswith("so2bwd:"):
+            make_so2_backward(int(a[7:]), procs)
         if a.startswith("w16:"):
             make_w16(int(a[4:]), procs)
         if a.startswith("blocks:"):

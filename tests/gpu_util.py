@@ -49,6 +49,12 @@ def block_inputs(w, seed=0):
     return g, x, T, Wn, We, w_att
 
 
+def so2_da(w):
+    """Seeded gradient with respect to the SO(2) message sums of a workload (input of both sides of the adjoint test)."""
+    rng = np.random.default_rng([w.seed if getattr(w, "seed", 0) else 0, 778])
+    return rng.standard_normal(size=(w.n_owned, (w.lmax + 1) ** 2, w.channels), dtype=np.float32)
+
+
 def oracle_forward(w, wt, g, agg_norm, with_readout=True, w_dtype=None):
     """Whole model on the oracle: species embedding, n_layers layers, readout.  Returns (xs, H).
     w_dtype: storage precision of the per-edge path weights (None: not rounded)."""

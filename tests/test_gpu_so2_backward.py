@@ -1,0 +1,198 @@
+"""GPU parity of the adjoint of the SO(2) message sum (egnn_so2_message_sum_backward) against
+oracle/so2_oracle.so2_message_sum_backward, which tests/test_oracle_so2.py pins to central differences of the forward."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import so2_oracle as S
+from paper_2507_03840_amd import synth
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+TOL = U.TOL
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2507_03840_amd import binding
+    binding.load_library()
+    return binding
+
+
+def unpack(flat, lmax, E):
+    """W_0, [Wr_m], [Wi_m] from the flat layout of the C ABI."""
+    shapes = S.so2_shapes(lmax, E)
+    at = shapes[0][0] * shapes[0][1]
+    W0 = flat[:at].reshape(shapes[0])
+    Wr, Wi = [], []
+    for s in shapes[1:]:
+        n = s[0] * s[1]
+        Wr.append(flat[at:at + n].reshape(s))
+        Wi.append(flat[at + n:at + 2 * n].reshape(s))
+        at += 2 * n
+    assert at == flat.size
+    return W0, Wr, Wi
+
+
+def gpu_backward(B, w, x, W_e, flat, da, agg):
+    import torch
+    m = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, agg)
+    pos = B.to_device(w.pos)
+    graph = m.egnn_nlist(pos, w.n_owned, w.box, w.pbc)
+    ws = torch.empty(max(m.egnn_so2_backward_workspace_bytes(graph.n_edges, graph.n_owned),
+                         m.egnn_backward_workspace_bytes(graph.n_edges, graph.n_owned, graph.n_total)),
+                     dtype=torch.uint8, device="cuda")
+    col_ptr, perm = m.egnn_graph_transpose(graph, ws)
+    args = (graph, col_ptr, perm, pos, w.box, B.to_device(x), B.to_device(W_e), B.to_device(flat), B.to_device(da), ws)
+    return m, args, m.egnn_so2_message_sum_backward(*args)
+
+
+def run_case(B, w, seed=0, x_scale=1.0, w_scale=1.0, da_scale=1.0):
+    g = U.oracle_graph(w)
+    agg = max(1.0, U.mean_degree(g, w.n_owned))
+    rng = np.random.default_rng([w.seed if getattr(w, "seed", 0) else 0, 8, seed])
+    x = (synth.node_features(rng, w.n_total, w.lmax, w.channels) * np.float32(x_scale)).astype(np.float32)
+    W_e, W0, Wr, Wi = synth.so2_weights(rng, w.lmax, w.channels, w.n_rbf)
+    W_e = (W_e * np.float32(x_scale)).astype(np.float32)
+    W0 = (W0 * np.float32(w_scale)).astype(np.float32)
+    Wr = [(v * np.float32(w_scale)).astype(np.float32) for v in Wr]
+    Wi = [(v * np.float32(w_scale)).astype(np.float32) for v in Wi]
+    da = (rng.standard_normal((w.n_owned, (w.lmax + 1) ** 2, w.channels)) * da_scale).astype(np.float32)
+    ref = S.so2_message_sum_backward(g, w.pos, w.box, x, W_e, W0, Wr, Wi, w.lmax, w.channels, w.n_rbf, w.r_cut, agg, da)
+    _, _, (dx, dW_e, dW) = gpu_backward(B, w, x, W_e, S.so2_pack(W0, Wr, Wi), da, agg)
+    g0, gr, gi = unpack(dW.cpu().numpy(), w.lmax, w.channels)
+    got = dict(dx=dx.cpu().numpy(), dW_e=dW_e.cpu().numpy(), dW0=g0)
+    want = dict(dx=ref[0], dW_e=ref[1], dW0=ref[2])
+    for i in range(w.lmax):
+        got[f"dWr{i + 1}"], got[f"dWi{i + 1}"] = gr[i], gi[i]
+        want[f"dWr{i + 1}"], want[f"dWi{i + 1}"] = ref[3][i], ref[4][i]
+    return got, want, len(g[0])
+
+
+def check(got, want, tol):
+    worst = 0.0
+    for name in want:
+        assert got[name].shape == want[name].shape, name
+        scale = np.abs(want[name]).max()
+        assert scale > 0, name
+        e = np.abs(got[name].astype(np.float64) - want[name]).max() / scale
+        worst = max(worst, e)
+        assert e < tol, (name, e)
+    return worst
+
+
+@pytest.mark.parametrize("lmax,E,periodic,n,n_owned,r_cut", [
+    (0, 8, False, 40, 40, 4.0), (1, 16, True, 120, 120, 4.0), (2, 32, False, 100, 60, 4.0), (3, 8, True, 150, 90, 4.0),
+    (4, 16, False, 70, 70, 4.0), (4, 32, False, 90, 50, 4.0), (2, 64, False, 60, 40, 4.0),
+    # many incoming edges per node, several edge chunks of the weight gradient with a ragged last one
+    (3, 16, False, 330, 12, 9.5), (1, 128, False, 40, 25, 4.0)])
+def test_so2_backward_small(B, lmax, E, periodic, n, n_owned, r_cut):
+    print("case", lmax, E, periodic, n, n_owned, r_cut, flush=True)
+    w = synth.small_cluster(n, n_owned, lmax, E, 6, r_cut, 60 + lmax, periodic)
+    got, want, n_e = run_case(B, w)
+    assert n_e > 0
+    worst = check(got, want, TOL)
+    print(f"  {n_e} edges, worst rel err {worst:.2e}", flush=True)
+    if lmax > 0:
+        # weight columns that multiply the zero planes of the edge embedding: exact zeros
+        _, gr, _ = got["dW0"], got["dWr1"], got["dWi1"]
+        cols = np.arange(gr.shape[1]) % (3 * E) >= 2 * E
+        assert np.all(gr[:, cols] == 0.0)
+        l_in = np.arange(got["dW0"].shape[1]) // (3 * E)
+        edge = np.arange(got["dW0"].shape[1]) % (3 * E) >= 2 * E
+        assert np.all(got["dW0"][:, edge & (l_in > 0)] == 0.0)
+        assert np.any(got["dW0"][:, edge & (l_in == 0)] != 0.0)
+
+
+@pytest.mark.parametrize("x_scale,w_scale,da_scale", [(1e-7, 1e5, 1.0), (3e4, 2e-6, 1e-9), (1e-10, 1e-8, 1e6), (5e6, 40.0, 1e4)])
+def test_so2_backward_operand_scales(B, x_scale, w_scale, da_scale):
+    w = synth.small_cluster(100, 70, 3, 16, 6, 4.0, 58, False)
+    got, want, n_e = run_case(B, w, x_scale=x_scale, w_scale=w_scale, da_scale=da_scale)
+    worst = check(got, want, 1e-5)
+    print(f"  scales {x_scale:g} {w_scale:g} {da_scale:g}: worst rel err {worst:.2e}", flush=True)
+
+
+def test_so2_backward_config1_reproducible(B):
+    import torch
+    w = synth.workload(1)
+    got, want, n_e = run_case(B, w)
+    worst = check(got, want, TOL)
+    print(f"config 1: {n_e} edges, worst rel err {worst:.2e}", flush=True)
+    # the same call twice: bit-identical (every sum over edges has a fixed order)
+    g = U.oracle_graph(w)
+    rng = np.random.default_rng(5)
+    x = synth.node_features(rng, w.n_total, w.lmax, w.channels)
+    W_e, W0, Wr, Wi = synth.so2_weights(rng, w.lmax, w.channels, w.n_rbf)
+    da = rng.standard_normal((w.n_owned, (w.lmax + 1) ** 2, w.channels)).astype(np.float32)
+    m, args, first = gpu_backward(B, w, x, W_e, S.so2_pack(W0, Wr, Wi), da, 10.0)
+    first = [t.clone() for t in first]
+    second = m.egnn_so2_message_sum_backward(*args)
+    torch.cuda.synchronize()
+    for a, b in zip(first, second):
+        assert torch.equal(a, b)
+
+
+def test_so2_backward_empty_graph_and_errors(B):
+    import torch
+    w = synth.small_cluster(5, 5, 2, 8, 6, 0.5, 3)          # cutoff shorter than any distance: no edges
+    rng = np.random.default_rng(0)
+    x = synth.node_features(rng, 5, 2, 8)
+    W_e, W0, Wr, Wi = synth.so2_weights(rng, 2, 8, 6)
+    da = rng.standard_normal((5, 9, 8)).astype(np.float32)
+    _, _, (dx, dW_e, dW) = gpu_backward(B, w, x, W_e, S.so2_pack(W0, Wr, Wi), da, 1.0)
+    assert dx.shape == (5, 9, 8) and not dx.any() and not dW_e.any() and not dW.any()
+    w2 = synth.small_cluster(30, 30, 2, 8, 6, 4.0, 4)
+    x2 = synth.node_features(rng, 30, 2, 8)
+    da2 = rng.standard_normal((30, 9, 8)).astype(np.float32)
+    m, args, _ = gpu_backward(B, w2, x2, W_e, S.so2_pack(W0, Wr, Wi), da2, 1.0)
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.EgnnError) as err:
+        m.egnn_so2_message_sum_backward(*args[:-1], small)
+    assert err.value.code == -3        # workspace too small
+
+
+def test_so2_backward_fullsize_config3(B):
+    """Config 3 in full (625,262 edges) against the oracle's gradients stored by tests/golden/make_golden.py so2bwd:3:
+    every weight gradient in full, dx at aimed rows (per degree, on the scale of that degree over all rows)."""
+    import time
+    import torch
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "config3_so2_backward.npz")
+    assert os.path.exists(path), "run tests/golden/make_golden.py so2bwd:3"
+    gold = np.load(path)
+    w = synth.workload(3)
+    wt = U.model_weights(w)
+    agg = float(gold["agg"])
+    m = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, agg)
+    pos = B.to_device(w.pos)
+    graph = m.egnn_nlist(pos, w.n_owned, w.box, w.pbc)
+    assert graph.n_edges == int(gold["n_edges"])
+    x = B.to_device(wt["x0"]).clone()
+    m.egnn_species_embed(B.to_device(w.species), B.to_device(wt["table"]), x)
+    W_e, W0, Wr, Wi = synth.so2_weights(np.random.default_rng([w.seed, 777]), w.lmax, w.channels, w.n_rbf)
+    flat = B.to_device(S.so2_pack(W0, Wr, Wi))
+    ws = torch.empty(max(m.egnn_so2_backward_workspace_bytes(graph.n_edges, graph.n_owned),
+                         m.egnn_backward_workspace_bytes(graph.n_edges, graph.n_owned, graph.n_total)),
+                     dtype=torch.uint8, device="cuda")
+    print(f"config 3: workspace {ws.numel() / 1e9:.2f} GB", flush=True)
+    col_ptr, perm = m.egnn_graph_transpose(graph, ws)
+    args = (graph, col_ptr, perm, pos, w.box, x, B.to_device(W_e), flat, B.to_device(U.so2_da(w)), ws)
+    dx, dW_e, dW = m.egnn_so2_message_sum_backward(*args)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(3):
+        m.egnn_so2_message_sum_backward(*args)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / 3
+    g0, gr, gi = unpack(dW.cpu().numpy(), w.lmax, w.channels)
+    got = dict(dW_e=dW_e.cpu().numpy(), dW0=g0)
+    for i in range(w.lmax):
+        got[f"dWr{i + 1}"], got[f"dWi{i + 1}"] = gr[i], gi[i]
+    worst = check(got, {k: gold[k] for k in got}, TOL)
+    rows = dx[torch.from_numpy(gold["nodes"]).cuda()].cpu().numpy().astype(np.float64)
+    for l in range(w.lmax + 1):
+        sl = slice(l * l, (l + 1) ** 2)
+        e = np.abs(rows[:, sl] - gold["dx_rows"][:, sl]).max() / gold["dx_maxabs_l"][l]
+        worst = max(worst, e)
+        assert e < TOL, (l, e)
+    print(f"config 3: SO(2) message sum adjoint {dt * 1e3:.2f} ms per call, worst rel err {worst:.2e}", flush=True)
