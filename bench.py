@@ -431,6 +431,16 @@ def run_config(args, index, extras):
                    workspace_GB=ws2.numel() / 1e9,
                    note="gather+rotate, five GEMMs on half-precision pieces of the fp32 operands (three products per fp32 product), rotate back + segmented sum")
         del ws2
+        # its reverse pass (gradients of the node embeddings, W_e and the per-order weights)
+        ws2b = torch.empty(max(m.egnn_so2_backward_workspace_bytes(n_edges, w.n_owned),
+                               m.egnn_backward_workspace_bytes(n_edges, w.n_owned, w.n_total)),
+                           dtype=torch.uint8, device="cuda")
+        cp2, pm2 = m.egnn_graph_transpose(graph, ws2b)
+        da2 = torch.ones((w.n_owned, (L_ + 1) ** 2, E_), dtype=torch.float32, device="cuda")
+        so2_bwd_ms = timed(lambda: m.egnn_so2_message_sum_backward(graph, cp2, pm2, pos, w.box, x0, We, flat, da2, ws2b), 3)
+        so2["backward_ms"] = so2_bwd_ms
+        so2["backward_workspace_GB"] = ws2b.numel() / 1e9
+        del ws2b, cp2, pm2, da2
         # the same transform with the full message content: persistent edge embeddings, attention-weighted node block,
         # gate, edge block (one layer in the shape the paper describes)
         ws3 = torch.empty(m.egnn_so2_blocks_workspace_bytes(n_edges), dtype=torch.uint8, device="cuda")

@@ -16,6 +16,7 @@
 //                          workgroup, the 64-column tiles of an edge block running side by side;
 //   4. so2_scatter_kernel  one workgroup per destination node, lane = (edge slot, channel): m-major rows of Y back to
 //                          (l, m) order, rotated back, times f_c, summed; slots added in fixed order (no atomics).
+#include <type_traits>
 #include "egnn_internal.h"
 #include "bond_frame.h"
 #include "stream_gemm.h"
@@ -23,8 +24,14 @@
 struct So2Bufs {
   float* A[5];
   float* Y[5];
-  int K[5], N[5];   // columns of A_m and of Y_m
+  int K[5], N[5];       // columns of A_m and of Y_m
+  int ldA[5], ldY[5];   // floats from one row to the next (so2_ld)
 };
+
+// Row pitch of the per-edge operands: the rows lie back to back.  (A pitch padded to an odd number of 128-byte lines,
+// so that the same columns of consecutive rows fall into different channels of the L2 where the shapes of this layer
+// give pitches of 8 or 16 lines, was measured: no gain for the weight gradient, 3-4 % slower forward.)
+__host__ __device__ inline int so2_ld(int cols) { return cols; }
 
 // columns of A_m: without persistent edge embeddings the edge slot exists only for l = 0 (its other planes are zero);
 // with them (full) every degree carries [source | destination | edge]
@@ -88,7 +95,7 @@ __global__ __launch_bounds__(256) void so2_gather_kernel(const int* __restrict__
 #pragma unroll
     for (int i = 0; i < D; ++i) amax = fmaxf(amax, fabsf(ve[i]));
     if (live) {
-      float* a0 = b.A[0] + (size_t)k * b.K[0] + c;
+      float* a0 = b.A[0] + (size_t)k * b.ldA[0] + c;
 #pragma unroll
       for (int l = 0; l <= LMAX; ++l) {
         __builtin_nontemporal_store(vs[l * l + l], a0 + ((3 * l) << log2E));
@@ -98,7 +105,7 @@ __global__ __launch_bounds__(256) void so2_gather_kernel(const int* __restrict__
 #pragma unroll
       for (int m = 1; m <= LMAX; ++m) {
         const int nl = LMAX + 1 - m;
-        float* am = b.A[m] + (size_t)k * b.K[m] + c;
+        float* am = b.A[m] + (size_t)k * b.ldA[m] + c;
 #pragma unroll
         for (int l = m; l <= LMAX; ++l) {
           const int col = (3 * (l - m)) << log2E, neg = (3 * nl) << log2E;
@@ -122,7 +129,7 @@ __global__ __launch_bounds__(256) void so2_gather_kernel(const int* __restrict__
     }
     amax = fmaxf(amax, fabsf(e0));
     if (live) {
-      float* a0 = b.A[0] + (size_t)k * b.K[0] + c;
+      float* a0 = b.A[0] + (size_t)k * b.ldA[0] + c;
 #pragma unroll
       for (int l = 0; l <= LMAX; ++l) {
         __builtin_nontemporal_store(vs[l * l + l], a0 + ((2 * l) << log2E));
@@ -132,7 +139,7 @@ __global__ __launch_bounds__(256) void so2_gather_kernel(const int* __restrict__
 #pragma unroll
       for (int m = 1; m <= LMAX; ++m) {
         const int nl = LMAX + 1 - m;
-        float* am = b.A[m] + (size_t)k * b.K[m] + c;
+        float* am = b.A[m] + (size_t)k * b.ldA[m] + c;
 #pragma unroll
         for (int l = m; l <= LMAX; ++l) {
           const int col = (2 * (l - m)) << log2E;
@@ -252,8 +259,9 @@ __global__ __launch_bounds__(256) void so2_pack_kernel(const float* __restrict__
 // of one block of rows sit on the same XCD with consecutive dispatch slots: they read the same rows of A, once from
 // HBM and then from that L2.  A compute wave owns 64 rows; its 64 x 64 tile of A is fetched in memory order and turned
 // to operand order through a private LDS tile.
-__global__ __launch_bounds__(SG_THREADS) void so2_gemm_kernel(const float* __restrict__ A, long M, int K, const uint16_t* __restrict__ T,
-                                                              int n_steps, float* __restrict__ C, int N, int n_ct,
+__global__ __launch_bounds__(SG_THREADS) void so2_gemm_kernel(const float* __restrict__ A, long M, int K, int lda,
+                                                              const uint16_t* __restrict__ T, int n_steps,
+                                                              float* __restrict__ C, int N, int ldc, int n_ct,
                                                               int n_row_blocks, const unsigned* __restrict__ maxima) {
   extern __shared__ uint4 so2_smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -267,7 +275,7 @@ __global__ __launch_bounds__(SG_THREADS) void so2_gemm_kernel(const float* __res
   const float a_scale = ldexpf(1.0f, ea), unscale = ldexpf(1.0f, -ea - eb);
   float16v acc[2][2];
   sgh_contract(A, M, K, reinterpret_cast<const uint4*>(T) + (long)ct * n_steps * (64 * 16), n_steps, so2_smem, e_base,
-               a_scale, acc);
+               a_scale, acc, lda);
   const int m = lane & 31, hh = lane >> 5;
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb)
@@ -278,7 +286,7 @@ __global__ __launch_bounds__(SG_THREADS) void so2_gemm_kernel(const float* __res
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const long e = e_base + rb * 32 + 8 * (i >> 2) + 4 * hh + (i & 3);
-          if (e < M) C[(size_t)e * N + col] = unscale * acc[rb][cb][i];
+          if (e < M) C[(size_t)e * ldc + col] = unscale * acc[rb][cb][i];
         }
       }
     }
@@ -288,13 +296,13 @@ __global__ __launch_bounds__(SG_THREADS) void so2_gemm_kernel(const float* __res
 // bond-frame rows of Y (m-major) of edge k, channel c -> o[(l, m)] in the lab frame
 template <int LMAX>
 __device__ __forceinline__ void so2_load_rotate_back(const So2Bufs& b, long k, int c, int log2E, const float4& g, float* o) {
-  const float* y0 = b.Y[0] + (size_t)k * b.N[0] + c;
+  const float* y0 = b.Y[0] + (size_t)k * b.ldY[0] + c;
 #pragma unroll
   for (int l = 0; l <= LMAX; ++l) o[l * l + l] = __builtin_nontemporal_load(y0 + (l << log2E));
 #pragma unroll
   for (int m = 1; m <= LMAX; ++m) {
     const int nl = LMAX + 1 - m;
-    const float* ym = b.Y[m] + (size_t)k * b.N[m] + c;
+    const float* ym = b.Y[m] + (size_t)k * b.ldY[m] + c;
 #pragma unroll
     for (int l = m; l <= LMAX; ++l) {
       o[l * l + l + m] = __builtin_nontemporal_load(ym + ((l - m) << log2E));
@@ -453,10 +461,10 @@ static size_t so2_ws(const egnn_ctx* ctx, int64_t n_edges, bool full, bool carve
   if (maxima) *maxima = mx;
   for (int m = 0; m <= lmax; ++m) {
     const int K = so2_K(lmax, E, m, full), N = so2_N(lmax, E, m);
-    float* A = (float*)take((size_t)n_edges * K * sizeof(float));
-    float* Y = (float*)take((size_t)n_edges * N * sizeof(float));
+    float* A = (float*)take((size_t)n_edges * so2_ld(K) * sizeof(float));
+    float* Y = (float*)take((size_t)n_edges * so2_ld(N) * sizeof(float));
     uint16_t* t = (uint16_t*)take((size_t)so2_tiles(N) * so2_steps(K) * 64 * 3 * 64 * sizeof(uint16_t));
-    if (b) { b->A[m] = A; b->Y[m] = Y; b->K[m] = K; b->N[m] = N; }
+    if (b) { b->A[m] = A; b->Y[m] = Y; b->K[m] = K; b->N[m] = N; b->ldA[m] = so2_ld(K); b->ldY[m] = so2_ld(N); }
     if (T) T[m] = t;
   }
   if (full) {
@@ -503,7 +511,7 @@ static int so2_check(egnn_ctx* ctx, const egnn_graph* g, const void* ws, size_t 
 static int so2_transform(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3], const float* x,
                          const float* edge_in, bool full, const float* W_so2, void* ws, So2Call* call, hipStream_t st) {
   const int lmax = ctx->desc.lmax, E = ctx->desc.channels;
-  for (int m = 0; m < 5; ++m) { call->b.A[m] = call->b.Y[m] = nullptr; call->b.K[m] = call->b.N[m] = 0; call->T[m] = nullptr; }
+  for (int m = 0; m < 5; ++m) { call->b.A[m] = call->b.Y[m] = nullptr; call->b.K[m] = call->b.N[m] = call->b.ldA[m] = call->b.ldY[m] = 0; call->T[m] = nullptr; }
   call->alpha = nullptr;
   so2_ws(ctx, g->n_edges, full, true, (char*)ws, &call->rhat_d, &call->b, call->T, &call->alpha, &call->maxima);
   const long n = g->n_edges;
@@ -553,8 +561,8 @@ static int so2_transform(egnn_ctx* ctx, const egnn_graph* g, const float* pos, c
     const long rows_per_wg = 64L * SG_WAVES;
     const int n_row_blocks = (int)((n + rows_per_wg - 1) / rows_per_wg);
     const unsigned grid_x = (unsigned)(((n_row_blocks + 7) / 8) * 8 * n_ct);
-    hipLaunchKernelGGL(so2_gemm_kernel, dim3(grid_x), dim3(SG_THREADS), lds, st, call->b.A[m], n, K, call->T[m], n_steps,
-                       call->b.Y[m], N, n_ct, n_row_blocks, call->maxima);
+    hipLaunchKernelGGL(so2_gemm_kernel, dim3(grid_x), dim3(SG_THREADS), lds, st, call->b.A[m], n, K, call->b.ldA[m],
+                       call->T[m], n_steps, call->b.Y[m], N, call->b.ldY[m], n_ct, n_row_blocks, call->maxima);
     EGNN_LAUNCH_CHECK(ctx, "so2_gemm_kernel");
   }
   return EGNN_OK;
@@ -627,7 +635,7 @@ extern "C" int egnn_so2_node_block(egnn_ctx* ctx, const egnn_graph* g, const flo
   if (g->n_owned == 0) return EGNN_OK;
   if (g->n_edges > 0) {
     hipLaunchKernelGGL(so2_attention_kernel, dim3((g->n_owned + 3) / 4), dim3(256), 0, st, g->row_ptr, call.b.Y[0],
-                       call.b.N[0], w_att, call.alpha, g->n_owned, ctx->desc.channels);
+                       call.b.ldY[0], w_att, call.alpha, g->n_owned, ctx->desc.channels);
     EGNN_LAUNCH_CHECK(ctx, "so2_attention_kernel");
   }
   return so2_scatter(ctx, g, call, call.alpha, 1.0f, a, st);
@@ -715,13 +723,13 @@ __global__ __launch_bounds__(256) void so2_dy_kernel(const int* __restrict__ dst
 #pragma unroll
   for (int i = 0; i < D; ++i) amax = fmaxf(amax, fabsf(v[i]));
   if (live) {
-    float* y0 = b.Y[0] + (size_t)k * b.N[0] + c;
+    float* y0 = b.Y[0] + (size_t)k * b.ldY[0] + c;
 #pragma unroll
     for (int l = 0; l <= LMAX; ++l) __builtin_nontemporal_store(v[l * l + l], y0 + (l << log2E));
 #pragma unroll
     for (int m = 1; m <= LMAX; ++m) {
       const int nl = LMAX + 1 - m;
-      float* ym = b.Y[m] + (size_t)k * b.N[m] + c;
+      float* ym = b.Y[m] + (size_t)k * b.ldY[m] + c;
 #pragma unroll
       for (int l = m; l <= LMAX; ++l) {
         __builtin_nontemporal_store(v[l * l + l + m], ym + ((l - m) << log2E));
@@ -734,20 +742,25 @@ __global__ __launch_bounds__(256) void so2_dy_kernel(const int* __restrict__ dst
   if ((threadIdx.x & 63) == 0) so2_raise_max(y_max, amax);
 }
 
-// partial[chunk][k][n] = sum over the edges e of the chunk of A[e][k] Y[e][n].  Workgroup = (128 x 128 tile of the
-// result, chunk of edges); each of its four waves owns a 64 x 64 quarter as 2 x 2 accumulators of 32 x 32.  One
+// partial[chunk][k][n] = sum over the edges e of the chunk of A[e][k] Y[e][n].  Workgroup = (chunk of edges, 128 x 128
+// tile of the result); each of its four waves owns a 64 x 64 quarter as 2 x 2 accumulators of 32 x 32.  One
 // matrix-core instruction contracts two edges: lane (i, h) feeds A[e + h][k0 + i] and Y[e + h][n0 + i].  Columns past
 // the last one are clamped (their results are not stored), edges past the chunk feed zeros.
 #define SW_UNROLL 8
-__global__ __launch_bounds__(256) void so2_wgrad_kernel(const float* __restrict__ A, int K, const float* __restrict__ Y,
-                                                        int N, long n_edges, long per_chunk, int tiles_n,
-                                                        float* __restrict__ partial) {
+__global__ __launch_bounds__(256) void so2_wgrad_kernel(const float* __restrict__ A, int K, int lda,
+                                                        const float* __restrict__ Y, int N, int ldy, long n_edges,
+                                                        long per_chunk, int tiles_n, float* __restrict__ partial) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i32 = lane & 31, hh = lane >> 5;
+  // (tiles of one chunk of edges are neighbours in the grid and land on different XCDs: putting them on one XCD, so
+  // that its L2 serves the rows they share, was measured slower)
+  const int chunk = blockIdx.y;
   const int tk = blockIdx.x / tiles_n, tn = blockIdx.x - tk * tiles_n;
   const int k0 = tk * 128 + (wave >> 1) * 64, n0 = tn * 128 + (wave & 1) * 64;
   if (k0 >= K || n0 >= N) return;            // (no barrier in this kernel)
-  const long e_begin = (long)blockIdx.y * per_chunk;
+  // 32 x 32 blocks of this wave's quarter that lie past the last row or column are skipped
+  const bool use_a[2] = {true, k0 + 32 < K}, use_q[2] = {true, n0 + 32 < N};
+  const long e_begin = (long)chunk * per_chunk;
   long e_end = e_begin + per_chunk;
   if (e_end > n_edges) e_end = n_edges;
   const int ka[2] = {k0 + i32 < K ? k0 + i32 : K - 1, k0 + 32 + i32 < K ? k0 + 32 + i32 : K - 1};
@@ -759,29 +772,77 @@ __global__ __launch_bounds__(256) void so2_wgrad_kernel(const float* __restrict_
     for (int q = 0; q < 2; ++q)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][q][i] = 0.0f;
-  for (long e = e_begin; e < e_end; e += 2 * SW_UNROLL) {
-    float av[SW_UNROLL][2], yv[SW_UNROLL][2];
+  // Two register sets: the loads of the next block of 2 * SW_UNROLL edges are issued before the products of the
+  // current one.  The loop runs over the full blocks of the chunk with no mask and no branch around a load (the
+  // block after the last one is the last one again, loaded and not used); what is left of the chunk comes after it.
+  float av0[SW_UNROLL][2], yv0[SW_UNROLL][2], av1[SW_UNROLL][2], yv1[SW_UNROLL][2];
+  // addresses: a row pointer that is the same for the whole wave (scalar arithmetic) plus a per-lane offset that never
+  // changes (its half-wave's row and its column) -- no vector arithmetic per load
+  const unsigned oa[2] = {(unsigned)(hh * lda + ka[0]) * 4u, (unsigned)(hh * lda + ka[1]) * 4u};   // bytes
+  const unsigned oy[2] = {(unsigned)(hh * ldy + nb[0]) * 4u, (unsigned)(hh * ldy + nb[1]) * 4u};
+  auto at = [](const float* row, unsigned byte_offset) {
+    return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(row) + byte_offset);
+  };
+  auto fetch = [&](float (&av)[SW_UNROLL][2], float (&yv)[SW_UNROLL][2], long e) {
 #pragma unroll
     for (int u = 0; u < SW_UNROLL; ++u) {
-      const long ee = e + 2 * u + hh;
-      const bool ok = ee < e_end;
-      const long er = ok ? ee : e_end - 1;   // (e_begin < e_end inside the loop)
-      const float* ar = A + (size_t)er * K;
-      const float* yr = Y + (size_t)er * N;
-      av[u][0] = ok ? ar[ka[0]] : 0.0f;
-      av[u][1] = ok ? ar[ka[1]] : 0.0f;
-      yv[u][0] = ok ? yr[nb[0]] : 0.0f;
-      yv[u][1] = ok ? yr[nb[1]] : 0.0f;
+      const float* ar = A + (size_t)(e + 2 * u) * lda;
+      const float* yr = Y + (size_t)(e + 2 * u) * ldy;
+      av[u][0] = at(ar, oa[0]);
+      av[u][1] = at(ar, oa[1]);
+      yv[u][0] = at(yr, oy[0]);
+      yv[u][1] = at(yr, oy[1]);
     }
+  };
+  // WHOLE: all four 32 x 32 blocks of the wave's quarter exist (no test around a matrix-core instruction)
+  auto products = [&](auto whole, const float (&av)[SW_UNROLL][2], const float (&yv)[SW_UNROLL][2]) {
 #pragma unroll
     for (int u = 0; u < SW_UNROLL; ++u)
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int q = 0; q < 2; ++q)
+        for (int q = 0; q < 2; ++q) {
+          if constexpr (!decltype(whole)::value) {
+            if (!(use_a[a] && use_q[q])) continue;          // (the same for the whole wave)
+          }
           acc[a][q] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u][a], yv[u][q], acc[a][q], 0, 0, 0);
-  }
-  float* out = partial + (size_t)blockIdx.y * K * N;
+        }
+  };
+  constexpr long BLOCK = 2 * SW_UNROLL;
+  const long n_blocks = (e_end - e_begin) / BLOCK;
+  auto run = [&](auto whole) {
+    if (n_blocks > 0) {
+      const long last = e_begin + (n_blocks - 1) * BLOCK;
+      fetch(av0, yv0, e_begin);
+      for (long blk = 0; blk < n_blocks; blk += 2) {
+        const long e1 = e_begin + (blk + 1) * BLOCK, e2 = e1 + BLOCK;
+        fetch(av1, yv1, e1 < last ? e1 : last);
+        products(whole, av0, yv0);
+        fetch(av0, yv0, e2 < last ? e2 : last);
+        if (blk + 1 < n_blocks) products(whole, av1, yv1);
+      }
+    }
+    // the ragged end of the last chunk: fewer than 2 * SW_UNROLL edges, zeros past the end
+    const long e = e_begin + n_blocks * BLOCK;
+    if (e < e_end) {
+#pragma unroll
+      for (int u = 0; u < SW_UNROLL; ++u) {
+        const long ee = e + 2 * u + hh;
+        const bool ok = ee < e_end;
+        const long er = ok ? ee : e_end - 1;
+        const float a0 = A[(size_t)er * lda + ka[0]], a1 = A[(size_t)er * lda + ka[1]];
+        const float y0 = Y[(size_t)er * ldy + nb[0]], y1 = Y[(size_t)er * ldy + nb[1]];
+        av0[u][0] = ok ? a0 : 0.0f;
+        av0[u][1] = ok ? a1 : 0.0f;
+        yv0[u][0] = ok ? y0 : 0.0f;
+        yv0[u][1] = ok ? y1 : 0.0f;
+      }
+      products(whole, av0, yv0);
+    }
+  };
+  if (use_a[1] && use_q[1]) run(std::true_type{});
+  else run(std::false_type{});
+  float* out = partial + (size_t)chunk * K * N;
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -849,7 +910,7 @@ __global__ __launch_bounds__(256) void so2_dx_kernel(const int* __restrict__ row
   for (int k = k0 + slot; k < k1; k += n_slots) {
     const float4 g = rhat_d[k];
     float vs[D], vd[D];
-    const float* a0 = b.A[0] + (size_t)k * b.K[0] + c;
+    const float* a0 = b.A[0] + (size_t)k * b.ldA[0] + c;
 #pragma unroll
     for (int l = 0; l <= LMAX; ++l) {
       vs[l * l + l] = __builtin_nontemporal_load(a0 + ((2 * l) << log2E));
@@ -858,7 +919,7 @@ __global__ __launch_bounds__(256) void so2_dx_kernel(const int* __restrict__ row
 #pragma unroll
     for (int m = 1; m <= LMAX; ++m) {
       const int nl = LMAX + 1 - m;
-      const float* am = b.A[m] + (size_t)k * b.K[m] + c;
+      const float* am = b.A[m] + (size_t)k * b.ldA[m] + c;
 #pragma unroll
       for (int l = m; l <= LMAX; ++l) {
         const int col = (2 * (l - m)) << log2E, neg = (2 * nl) << log2E;
@@ -899,7 +960,7 @@ __global__ __launch_bounds__(256) void so2_add_kernel(float* __restrict__ dx, co
 
 // partial[chunk][c][q] = sum over the edges k of the chunk of de[k][c] B_q(d_k), de = the edge columns of dA_0.
 // A thread owns the outputs o = tid + 256 s (c = o mod E: neighbouring threads read neighbouring columns).
-#define SO2_DWE_CHUNKS 256
+#define SO2_DWE_CHUNKS 2048
 __global__ __launch_bounds__(256) void so2_dwe_kernel(const float4* __restrict__ rhat_d, const float* __restrict__ A0, int K0,
                                                       int edge_col0, long n_edges, long per_chunk, int log2E, int n_rbf,
                                                       float r_cut, float* __restrict__ partial) {
@@ -912,15 +973,30 @@ __global__ __launch_bounds__(256) void so2_dwe_kernel(const float4* __restrict__
   float acc[16];    // E n_rbf <= 128 * 32 = 16 * 256
 #pragma unroll
   for (int s = 0; s < 16; ++s) acc[s] = 0.0f;
-  for (long k = e_begin; k < e_end; ++k) {
-    const float d = rhat_d[k].w;
-    const float* de = A0 + (size_t)k * K0 + edge_col0;
+  for (long k = e_begin; k < e_end; k += 4) {
+    // four edges at a time: their loads are independent (edges past the chunk repeat its last edge with weight zero)
+    float d[4], live[4];
+    const float* de[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const long ku = k + u < e_end ? k + u : e_end - 1;
+      live[u] = k + u < e_end ? 1.0f : 0.0f;
+      d[u] = rhat_d[ku].w;
+      de[u] = A0 + (size_t)ku * K0 + edge_col0;
+    }
 #pragma unroll
     for (int s = 0; s < 16; ++s) {
       const int o = threadIdx.x + 256 * s;
       if (o < n_out) {
-        const float u = d - (float)(o >> log2E) * step;
-        acc[s] += de[o & (E - 1)] * __expf(-u * u * inv2s2);
+        const float centre = (float)(o >> log2E) * step;
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = live[u] * de[u][o & (E - 1)];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const float t = d[u] - centre;
+          acc[s] += v[u] * __expf(-t * t * inv2s2);
+        }
       }
     }
   }
@@ -932,12 +1008,14 @@ __global__ __launch_bounds__(256) void so2_dwe_kernel(const float4* __restrict__
   }
 }
 
-// chunks of edges of the weight gradient of one order: enough workgroups for two per compute unit, at most 128 chunks,
-// every chunk a multiple of 2 * SW_UNROLL edges
+// chunks of edges of the weight gradient of one order.  All workgroups of a launch take the same time, so their number
+// should fill the slots of the chip once, not one and a third times: 256 compute units x 3 workgroups (what the
+// kernel's registers allow).  Every chunk is a multiple of 2 * SW_UNROLL edges.
+#define SW_SLOTS 768
 static void so2_wgrad_split(long n, int K, int N, int* chunks, long* per_chunk) {
   const int tiles = ((K + 127) / 128) * ((N + 127) / 128);
-  long c = (512 + tiles - 1) / tiles;
-  if (c > 128) c = 128;
+  long c = SW_SLOTS / tiles;
+  if (c < 1) c = 1;
   long per = (n + c - 1) / c;
   per = (per + 2 * SW_UNROLL - 1) / (2 * SW_UNROLL) * (2 * SW_UNROLL);
   if (per < 2 * SW_UNROLL) per = 2 * SW_UNROLL;
@@ -1008,7 +1086,7 @@ extern "C" int egnn_so2_message_sum_backward(egnn_ctx* ctx, const egnn_graph* g,
     return egnn_launch_fill_int(ctx, (int*)dW_so2, n_w, 0, st);
   }
   So2Call call;
-  for (int m = 0; m < 5; ++m) { call.b.A[m] = call.b.Y[m] = nullptr; call.b.K[m] = call.b.N[m] = 0; call.T[m] = nullptr; }
+  for (int m = 0; m < 5; ++m) { call.b.A[m] = call.b.Y[m] = nullptr; call.b.K[m] = call.b.N[m] = call.b.ldA[m] = call.b.ldY[m] = 0; call.T[m] = nullptr; }
   call.alpha = nullptr;
   so2_ws(ctx, n, false, true, (char*)ws, &call.rhat_d, &call.b, call.T, &call.alpha, &call.maxima);
   So2Bwd w;
@@ -1054,8 +1132,8 @@ extern "C" int egnn_so2_message_sum_backward(egnn_ctx* ctx, const egnn_graph* g,
     long per;
     so2_wgrad_split(n, K, N, &chunks, &per);
     const int tiles_n = (N + 127) / 128, tiles_k = (K + 127) / 128;
-    hipLaunchKernelGGL(so2_wgrad_kernel, dim3(tiles_k * tiles_n, chunks), dim3(256), 0, st, call.b.A[m], K, call.b.Y[m], N,
-                       n, per, tiles_n, w.partial);
+    hipLaunchKernelGGL(so2_wgrad_kernel, dim3(tiles_k * tiles_n, chunks), dim3(256), 0, st, call.b.A[m], K, call.b.ldA[m],
+                       call.b.Y[m], N, call.b.ldY[m], n, per, tiles_n, w.partial);
     EGNN_LAUNCH_CHECK(ctx, "so2_wgrad_kernel");
     if ((rc = egnn_launch_reduce_partials(ctx, w.partial, chunks, (long)K * N, w.dB, 1.0f, st))) return rc;
     const int nl = lmax + 1 - m;
@@ -1073,14 +1151,14 @@ extern "C" int egnn_so2_message_sum_backward(egnn_ctx* ctx, const egnn_graph* g,
     const long rows_per_wg = 64L * SG_WAVES;
     const int n_row_blocks = (int)((n + rows_per_wg - 1) / rows_per_wg);
     const unsigned grid_x = (unsigned)(((n_row_blocks + 7) / 8) * 8 * n_ct);
-    hipLaunchKernelGGL(so2_gemm_kernel, dim3(grid_x), dim3(SG_THREADS), SGH_LDS_BYTES, st, call.b.Y[m], n, N, call.T[m],
-                       n_steps, call.b.A[m], K, n_ct, n_row_blocks, call.maxima);
+    hipLaunchKernelGGL(so2_gemm_kernel, dim3(grid_x), dim3(SG_THREADS), SGH_LDS_BYTES, st, call.b.Y[m], n, N,
+                       call.b.ldY[m], call.T[m], n_steps, call.b.A[m], K, call.b.ldA[m], n_ct, n_row_blocks, call.maxima);
     EGNN_LAUNCH_CHECK(ctx, "so2_gemm_kernel");
   }
   {
     const long per = (n + SO2_DWE_CHUNKS - 1) / SO2_DWE_CHUNKS;
     const int chunks = (int)((n + per - 1) / per);
-    hipLaunchKernelGGL(so2_dwe_kernel, dim3(chunks), dim3(256), 0, st, rd, call.b.A[0], call.b.K[0], (lmax + 1) * 2 * E, n,
+    hipLaunchKernelGGL(so2_dwe_kernel, dim3(chunks), dim3(256), 0, st, rd, call.b.A[0], call.b.ldA[0], (lmax + 1) * 2 * E, n,
                        per, ctx->log2_channels, n_rbf, ctx->desc.r_cut, w.dwe);
     EGNN_LAUNCH_CHECK(ctx, "so2_dwe_kernel");
     if ((rc = egnn_launch_reduce_partials(ctx, w.dwe, chunks, (long)E * n_rbf, dW_e, 1.0f, st))) return rc;

@@ -283,8 +283,11 @@ __device__ __forceinline__ void rbh_loader(const uint16_t* __restrict__ T, long 
 
 // as sg_contract; tsrc: n_steps blocks of 64 x 16 uint4; the accumulators hold a_scale * (scale of the packed operand)
 // times the result
+// lda: floats from one row of A to the next (0: K, rows back to back)
 __device__ __forceinline__ void sgh_contract(const float* __restrict__ A, long M, int K, const uint4* __restrict__ tsrc,
-                                             int n_steps, uint4* smem, long e_base, float a_scale, float16v (&acc)[2][2]) {
+                                             int n_steps, uint4* smem, long e_base, float a_scale, float16v (&acc)[2][2],
+                                             int lda = 0) {
+  if (lda == 0) lda = K;
   uint4* sB = smem;                                  // [2][64][SGH_BROW4]
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -298,8 +301,8 @@ __device__ __forceinline__ void sgh_contract(const float* __restrict__ A, long M
     long e0 = e_base + 4 * i + frow, e1 = e0 + 32;
     if (e0 >= M) e0 = M - 1;
     if (e1 >= M) e1 = M - 1;
-    fptr0[i] = A + (size_t)e0 * K;
-    fptr1[i] = A + (size_t)e1 * K;
+    fptr0[i] = A + (size_t)e0 * lda;
+    fptr1[i] = A + (size_t)e1 * lda;
   }
 #pragma unroll
   for (int a = 0; a < 2; ++a)
