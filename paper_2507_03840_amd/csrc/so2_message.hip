@@ -742,32 +742,43 @@ __global__ __launch_bounds__(256) void so2_dy_kernel(const int* __restrict__ dst
   if ((threadIdx.x & 63) == 0) so2_raise_max(y_max, amax);
 }
 
-// partial[chunk][k][n] = sum over the edges e of the chunk of A[e][k] Y[e][n].  Workgroup = (chunk of edges, 128 x 128
-// tile of the result); each of its four waves owns a 64 x 64 quarter as 2 x 2 accumulators of 32 x 32.  One
-// matrix-core instruction contracts two edges: lane (i, h) feeds A[e + h][k0 + i] and Y[e + h][n0 + i].  Columns past
-// the last one are clamped (their results are not stored), edges past the chunk feed zeros.
+// partial[chunk][k][n] = sum over the edges e of the chunk of A[e][k] Y[e][n].  Workgroup = (chunk of edges, four
+// neighbouring 128 x 64 quarters of the result), one quarter per wave as 4 x 2 accumulators of 32 x 32.  One matrix-core
+// instruction contracts two edges.  A lane fetches 16 bytes of A and 8 bytes of Y per pair of edges, so that a
+// half-wave reads 512 and 256 contiguous bytes of one row: lane (i, h) holds A[e + h][k0 + 4 i + a] for a < 4 and
+// Y[e + h][n0 + 2 i + q] for q < 2, and accumulator (a, q) therefore holds the rows k0 + 4 r + a and the columns
+// n0 + 2 i + q of the result -- a permutation that only the final store has to know.  Columns past the last one are
+// clamped (K and N are multiples of 8: a lane's group is valid or not as a whole; invalid ones are not stored).
 #define SW_UNROLL 8
-__global__ __launch_bounds__(256) void so2_wgrad_kernel(const float* __restrict__ A, int K, int lda,
-                                                        const float* __restrict__ Y, int N, int ldy, long n_edges,
-                                                        long per_chunk, int tiles_n, float* __restrict__ partial) {
+typedef float sw_f4 __attribute__((ext_vector_type(4)));
+typedef float sw_f2 __attribute__((ext_vector_type(2)));
+__global__ __launch_bounds__(256, 2) void so2_wgrad_kernel(const float* __restrict__ A, int K, int lda,
+                                                           const float* __restrict__ Y, int N, int ldy, long n_edges,
+                                                           long per_chunk, int quarters_n, float* __restrict__ partial) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i32 = lane & 31, hh = lane >> 5;
   // (tiles of one chunk of edges are neighbours in the grid and land on different XCDs: putting them on one XCD, so
   // that its L2 serves the rows they share, was measured slower)
   const int chunk = blockIdx.y;
-  const int tk = blockIdx.x / tiles_n, tn = blockIdx.x - tk * tiles_n;
-  const int k0 = tk * 128 + (wave >> 1) * 64, n0 = tn * 128 + (wave & 1) * 64;
-  if (k0 >= K || n0 >= N) return;            // (no barrier in this kernel)
-  // 32 x 32 blocks of this wave's quarter that lie past the last row or column are skipped
-  const bool use_a[2] = {true, k0 + 32 < K}, use_q[2] = {true, n0 + 32 < N};
+  // the 128 x 64 quarters of the result are numbered row by row and dealt out four to a workgroup: only the last
+  // workgroup of a chunk can have waves without work (a wave that ends early does not make room for another one
+  // in practice)
+  const int quarter = blockIdx.x * (blockDim.x >> 6) + wave;   // (a result of fewer than four quarters: smaller workgroups)
+  const int kq = quarter / quarters_n, nq = quarter - kq * quarters_n;
+  const int k0 = kq * 128, n0 = nq * 64;
+  if (k0 >= K) return;                       // (no barrier in this kernel)
   const long e_begin = (long)chunk * per_chunk;
   long e_end = e_begin + per_chunk;
   if (e_end > n_edges) e_end = n_edges;
-  const int ka[2] = {k0 + i32 < K ? k0 + i32 : K - 1, k0 + 32 + i32 < K ? k0 + 32 + i32 : K - 1};
-  const int nb[2] = {n0 + i32 < N ? n0 + i32 : N - 1, n0 + 32 + i32 < N ? n0 + 32 + i32 : N - 1};
-  float16v acc[2][2];
+  const int ca = k0 + 4 * i32, cy = n0 + 2 * i32;
+  const bool a_ok = ca < K, y_ok = cy < N;
+  // addresses: a row pointer that is the same for the whole wave (scalar arithmetic) plus a per-lane byte offset that
+  // never changes (its half-wave's row and its columns) -- no vector arithmetic per load
+  const unsigned oa = (unsigned)(hh * lda + (a_ok ? ca : K - 4)) * 4u;
+  const unsigned oy = (unsigned)(hh * ldy + (y_ok ? cy : N - 2)) * 4u;
+  float16v acc[4][2];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < 4; ++a)
 #pragma unroll
     for (int q = 0; q < 2; ++q)
 #pragma unroll
@@ -775,87 +786,71 @@ __global__ __launch_bounds__(256) void so2_wgrad_kernel(const float* __restrict_
   // Two register sets: the loads of the next block of 2 * SW_UNROLL edges are issued before the products of the
   // current one.  The loop runs over the full blocks of the chunk with no mask and no branch around a load (the
   // block after the last one is the last one again, loaded and not used); what is left of the chunk comes after it.
-  float av0[SW_UNROLL][2], yv0[SW_UNROLL][2], av1[SW_UNROLL][2], yv1[SW_UNROLL][2];
-  // addresses: a row pointer that is the same for the whole wave (scalar arithmetic) plus a per-lane offset that never
-  // changes (its half-wave's row and its column) -- no vector arithmetic per load
-  const unsigned oa[2] = {(unsigned)(hh * lda + ka[0]) * 4u, (unsigned)(hh * lda + ka[1]) * 4u};   // bytes
-  const unsigned oy[2] = {(unsigned)(hh * ldy + nb[0]) * 4u, (unsigned)(hh * ldy + nb[1]) * 4u};
-  auto at = [](const float* row, unsigned byte_offset) {
-    return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(row) + byte_offset);
-  };
-  auto fetch = [&](float (&av)[SW_UNROLL][2], float (&yv)[SW_UNROLL][2], long e) {
+  sw_f4 av0[SW_UNROLL], av1[SW_UNROLL];
+  sw_f2 yv0[SW_UNROLL], yv1[SW_UNROLL];
+  auto fetch = [&](sw_f4 (&av)[SW_UNROLL], sw_f2 (&yv)[SW_UNROLL], long e) {
 #pragma unroll
     for (int u = 0; u < SW_UNROLL; ++u) {
-      const float* ar = A + (size_t)(e + 2 * u) * lda;
-      const float* yr = Y + (size_t)(e + 2 * u) * ldy;
-      av[u][0] = at(ar, oa[0]);
-      av[u][1] = at(ar, oa[1]);
-      yv[u][0] = at(yr, oy[0]);
-      yv[u][1] = at(yr, oy[1]);
+      const char* ar = reinterpret_cast<const char*>(A + (size_t)(e + 2 * u) * lda);
+      const char* yr = reinterpret_cast<const char*>(Y + (size_t)(e + 2 * u) * ldy);
+      av[u] = *reinterpret_cast<const sw_f4*>(ar + oa);
+      yv[u] = *reinterpret_cast<const sw_f2*>(yr + oy);
     }
   };
-  // WHOLE: all four 32 x 32 blocks of the wave's quarter exist (no test around a matrix-core instruction)
-  auto products = [&](auto whole, const float (&av)[SW_UNROLL][2], const float (&yv)[SW_UNROLL][2]) {
+  auto products = [&](const sw_f4 (&av)[SW_UNROLL], const sw_f2 (&yv)[SW_UNROLL]) {
 #pragma unroll
     for (int u = 0; u < SW_UNROLL; ++u)
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
+      for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-          if constexpr (!decltype(whole)::value) {
-            if (!(use_a[a] && use_q[q])) continue;          // (the same for the whole wave)
-          }
+        for (int q = 0; q < 2; ++q)
           acc[a][q] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u][a], yv[u][q], acc[a][q], 0, 0, 0);
-        }
   };
   constexpr long BLOCK = 2 * SW_UNROLL;
   const long n_blocks = (e_end - e_begin) / BLOCK;
-  auto run = [&](auto whole) {
-    if (n_blocks > 0) {
-      const long last = e_begin + (n_blocks - 1) * BLOCK;
-      fetch(av0, yv0, e_begin);
-      for (long blk = 0; blk < n_blocks; blk += 2) {
-        const long e1 = e_begin + (blk + 1) * BLOCK, e2 = e1 + BLOCK;
-        fetch(av1, yv1, e1 < last ? e1 : last);
-        products(whole, av0, yv0);
-        fetch(av0, yv0, e2 < last ? e2 : last);
-        if (blk + 1 < n_blocks) products(whole, av1, yv1);
-      }
+  if (n_blocks > 0) {
+    const long last = e_begin + (n_blocks - 1) * BLOCK;
+    fetch(av0, yv0, e_begin);
+    for (long blk = 0; blk < n_blocks; blk += 2) {
+      const long e1 = e_begin + (blk + 1) * BLOCK, e2 = e1 + BLOCK;
+      fetch(av1, yv1, e1 < last ? e1 : last);
+      products(av0, yv0);
+      fetch(av0, yv0, e2 < last ? e2 : last);
+      if (blk + 1 < n_blocks) products(av1, yv1);
     }
+  }
+  {
     // the ragged end of the last chunk: fewer than 2 * SW_UNROLL edges, zeros past the end
     const long e = e_begin + n_blocks * BLOCK;
     if (e < e_end) {
 #pragma unroll
       for (int u = 0; u < SW_UNROLL; ++u) {
-        const long ee = e + 2 * u + hh;
-        const bool ok = ee < e_end;
-        const long er = ok ? ee : e_end - 1;
-        const float a0 = A[(size_t)er * lda + ka[0]], a1 = A[(size_t)er * lda + ka[1]];
-        const float y0 = Y[(size_t)er * ldy + nb[0]], y1 = Y[(size_t)er * ldy + nb[1]];
-        av0[u][0] = ok ? a0 : 0.0f;
-        av0[u][1] = ok ? a1 : 0.0f;
-        yv0[u][0] = ok ? y0 : 0.0f;
-        yv0[u][1] = ok ? y1 : 0.0f;
+        const long ee = e + 2 * u;               // (+ hh through the lane offsets)
+        const bool ok = ee + hh < e_end;
+        const long er = ok ? ee : e_end - 1 - hh;  // a row whose lane offset stays inside the matrix: e_end - 1 at most
+        const sw_f4 a4 = *reinterpret_cast<const sw_f4*>(reinterpret_cast<const char*>(A + (size_t)er * lda) + oa);
+        const sw_f2 y2 = *reinterpret_cast<const sw_f2*>(reinterpret_cast<const char*>(Y + (size_t)er * ldy) + oy);
+        const sw_f4 z4 = {0.0f, 0.0f, 0.0f, 0.0f};
+        const sw_f2 z2 = {0.0f, 0.0f};
+        av0[u] = ok ? a4 : z4;
+        yv0[u] = ok ? y2 : z2;
       }
-      products(whole, av0, yv0);
+      products(av0, yv0);
     }
-  };
-  if (use_a[1] && use_q[1]) run(std::true_type{});
-  else run(std::false_type{});
+  }
   float* out = partial + (size_t)chunk * K * N;
+  if (y_ok) {
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < 4; ++a)
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int nn = n0 + q * 32 + i32;
-      if (nn < N) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int kk = k0 + a * 32 + 8 * (i >> 2) + 4 * hh + (i & 3);
-          if (kk < K) out[(size_t)kk * N + nn] = acc[a][q][i];
+      for (int i = 0; i < 16; ++i) {
+        const int kk = k0 + 4 * (8 * (i >> 2) + 4 * hh + (i & 3)) + a;
+        if (kk < K) {
+          const sw_f2 v = {acc[a][0][i], acc[a][1][i]};
+          *reinterpret_cast<sw_f2*>(out + (size_t)kk * N + cy) = v;
         }
       }
-    }
+  }
 }
 
 // dB_m [K][N] (column orders of A_m and Y_m, without persistent edge embeddings) -> gradient of W_0 (m = 0) or of
@@ -1008,13 +1003,17 @@ __global__ __launch_bounds__(256) void so2_dwe_kernel(const float4* __restrict__
   }
 }
 
-// chunks of edges of the weight gradient of one order.  All workgroups of a launch take the same time, so their number
-// should fill the slots of the chip once, not one and a third times: 256 compute units x 3 workgroups (what the
-// kernel's registers allow).  Every chunk is a multiple of 2 * SW_UNROLL edges.
-#define SW_SLOTS 768
+// chunks of edges of the weight gradient of one order.  All waves of a launch take the same time, so their number
+// should fill the chip's places once (256 compute units x 4 SIMDs x 2 waves, what the kernel's registers allow), not
+// one and a third times.  Every chunk is a multiple of 2 * SW_UNROLL edges.
+#define SW_WAVE_SLOTS 2048
+static int so2_wgrad_quarters(int K, int N) { return ((K + 127) / 128) * ((N + 63) / 64); }
+static int so2_wgrad_waves(int K, int N) { const int q = so2_wgrad_quarters(K, N); return q < 4 ? q : 4; }   // per workgroup
+static int so2_wgrad_groups(int K, int N) {                                                                  // workgroups per chunk
+  return (so2_wgrad_quarters(K, N) + so2_wgrad_waves(K, N) - 1) / so2_wgrad_waves(K, N);
+}
 static void so2_wgrad_split(long n, int K, int N, int* chunks, long* per_chunk) {
-  const int tiles = ((K + 127) / 128) * ((N + 127) / 128);
-  long c = SW_SLOTS / tiles;
+  long c = SW_WAVE_SLOTS / (so2_wgrad_waves(K, N) * so2_wgrad_groups(K, N));
   if (c < 1) c = 1;
   long per = (n + c - 1) / c;
   per = (per + 2 * SW_UNROLL - 1) / (2 * SW_UNROLL) * (2 * SW_UNROLL);
@@ -1131,9 +1130,8 @@ extern "C" int egnn_so2_message_sum_backward(egnn_ctx* ctx, const egnn_graph* g,
     int chunks;
     long per;
     so2_wgrad_split(n, K, N, &chunks, &per);
-    const int tiles_n = (N + 127) / 128, tiles_k = (K + 127) / 128;
-    hipLaunchKernelGGL(so2_wgrad_kernel, dim3(tiles_k * tiles_n, chunks), dim3(256), 0, st, call.b.A[m], K, call.b.ldA[m],
-                       call.b.Y[m], N, call.b.ldY[m], n, per, tiles_n, w.partial);
+    hipLaunchKernelGGL(so2_wgrad_kernel, dim3(so2_wgrad_groups(K, N), chunks), dim3(64 * so2_wgrad_waves(K, N)), 0, st, call.b.A[m], K,
+                       call.b.ldA[m], call.b.Y[m], N, call.b.ldY[m], n, per, (N + 63) / 64, w.partial);
     EGNN_LAUNCH_CHECK(ctx, "so2_wgrad_kernel");
     if ((rc = egnn_launch_reduce_partials(ctx, w.partial, chunks, (long)K * N, w.dB, 1.0f, st))) return rc;
     const int nl = lmax + 1 - m;
