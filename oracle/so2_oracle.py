@@ -289,3 +289,122 @@ def gate(x, W_g, lmax):
         g = 1.0 / (1.0 + np.exp(-(x0 @ np.asarray(W_g[l - 1], F64).T)))
         out[:, O.sl(l), :] = x[:, O.sl(l), :] * g[:, None, :]
     return out
+
+
+# --------------------------------------------------------------------------------------
+# Adjoints of the two blocks and of the gate (Sec. 4.1: training needs the gradients of the forward pass).  Positions
+# are data.  Each function undoes the steps of its forward function in reverse order; tests/test_oracle_so2_blocks.py
+# pins them to central differences of the forward functions.
+# --------------------------------------------------------------------------------------
+def so2_messages_backward(src, dst, r, x, T_edge, W0, Wr, Wi, lmax, E, gY):
+    """Adjoint of so2_messages(..., T_edge=T_edge, envelope=False) for the edges given: from gY [n][(lmax+1)^2][E]
+    (gradient of the transformed messages, lab frame) returns (gM [n][(lmax+1)^2][3E], dW0, [dWr_m], [dWi_m]); the
+    three column groups of gM belong to x[src], x[dst] and T_edge."""
+    x = np.asarray(x, F64)
+    d = np.sqrt(np.einsum("ka,ka->k", r, r))
+    D = wigner_blocks(lmax, bond_rotations(r / d[:, None]))
+    n, dim = len(src), (lmax + 1) ** 2
+    M = np.zeros((n, dim, 3 * E), F64)
+    M[:, :, :E] = x[src]
+    M[:, :, E:2 * E] = x[dst]
+    M[:, :, 2 * E:] = np.asarray(T_edge, F64)
+    Xp = np.einsum("kab,kbc->kac", D, M)
+    gYp = np.einsum("kab,kbc->kac", D, np.asarray(gY, F64))      # Y = D^T Y'
+    gXp, dW0, dWr, dWi = so2_linear_backward(Xp, gYp, W0, Wr, Wi, lmax, E)
+    return np.einsum("kba,kbc->kac", D, gXp), dW0, dWr, dWi      # X' = D M
+
+
+def so2_edge_block_backward(graph, pos, box, x, T_edge, W0, Wr, Wi, lmax, E, r_cut, dT_out, chunk=4096):
+    """Adjoint of so2_edge_block: from dT_out [n_edges][(lmax+1)^2][E] returns (dx [n_total][...], dT_in, dW0, [dWr_m],
+    [dWi_m]).  T' = T + f_c y: the identity term passes dT_out on, the message term goes through so2_messages_backward
+    with gY = f_c dT_out."""
+    src, dst, shift, row_ptr = graph
+    x = np.asarray(x, F64)
+    dT_out = np.asarray(dT_out, F64)
+    dx = np.zeros_like(x)
+    dT_in = dT_out.copy()
+    shapes = so2_shapes(lmax, E)
+    dW0 = np.zeros(shapes[0], F64)
+    dWr = [np.zeros(s, F64) for s in shapes[1:]]
+    dWi = [np.zeros(s, F64) for s in shapes[1:]]
+    for k0 in range(0, len(src), chunk):
+        k1 = min(len(src), k0 + chunk)
+        s_, d_ = src[k0:k1], dst[k0:k1]
+        r = O.edge_vectors(pos, box, s_, d_, shift[k0:k1])
+        fc = O.envelope(np.sqrt(np.einsum("ka,ka->k", r, r)), r_cut)
+        gM, g0, gr, gi = so2_messages_backward(s_, d_, r, x, T_edge[k0:k1], W0, Wr, Wi, lmax, E,
+                                               dT_out[k0:k1] * fc[:, None, None])
+        np.add.at(dx, s_, gM[:, :, :E])
+        np.add.at(dx, d_, gM[:, :, E:2 * E])
+        dT_in[k0:k1] += gM[:, :, 2 * E:]
+        dW0 += g0
+        for m in range(lmax):
+            dWr[m] += gr[m]
+            dWi[m] += gi[m]
+    return dx, dT_in, dW0, dWr, dWi
+
+
+def so2_node_block_backward(graph, pos, box, x, T_edge, W0, Wr, Wi, w_att, lmax, E, r_cut, da, slope=0.2):
+    """Adjoint of so2_node_block: from da [n_owned][(lmax+1)^2][E] returns (dx, dT_edge, dW0, [dWr_m], [dWi_m], dw_att).
+    Per destination node j with incoming edges k: a_j = sum_k alpha_k f_c,k y_k, alpha = softmax(s), s_k = w_att .
+    LeakyReLU(y_k[L = 0]).  Backwards: t_k = f_c,k <da_j, y_k> is the gradient of alpha_k; the softmax gives
+    ds_k = alpha_k (t_k - sum_k' alpha_k' t_k'); the score gives dw_att += ds_k LeakyReLU(y0_k) and
+    gY_k[L = 0] += ds_k w_att LeakyReLU'(y0_k); the weighted sum gives gY_k += alpha_k f_c,k da_j."""
+    src, dst, shift, row_ptr = graph
+    x = np.asarray(x, F64)
+    da = np.asarray(da, F64)
+    w_att = np.asarray(w_att, F64)
+    n_owned = len(row_ptr) - 1
+    dx = np.zeros_like(x)
+    dT = np.zeros((len(src), (lmax + 1) ** 2, E), F64)
+    shapes = so2_shapes(lmax, E)
+    dW0 = np.zeros(shapes[0], F64)
+    dWr = [np.zeros(s, F64) for s in shapes[1:]]
+    dWi = [np.zeros(s, F64) for s in shapes[1:]]
+    dw_att = np.zeros(E, F64)
+    for j in range(n_owned):
+        k0, k1 = int(row_ptr[j]), int(row_ptr[j + 1])
+        if k1 == k0:
+            continue
+        s_, d_ = src[k0:k1], dst[k0:k1]
+        r = O.edge_vectors(pos, box, s_, d_, shift[k0:k1])
+        Y = so2_messages(s_, d_, r, x, None, W0, Wr, Wi, lmax, E, 0, r_cut, T_edge=T_edge[k0:k1], envelope=False)
+        y0 = Y[:, 0, :]
+        alpha = attention_weights(y0, w_att, np.array([0, k1 - k0]), slope)
+        fc = O.envelope(np.sqrt(np.einsum("ka,ka->k", r, r)), r_cut)
+        t = fc * np.einsum("ac,kac->k", da[j], Y)
+        ds = alpha * (t - np.dot(alpha, t))
+        act = np.where(y0 > 0, y0, slope * y0)
+        dw_att += ds @ act
+        gY = (alpha * fc)[:, None, None] * da[j][None, :, :]
+        gY[:, 0, :] += ds[:, None] * w_att[None, :] * np.where(y0 > 0, 1.0, slope)
+        gM, g0, gr, gi = so2_messages_backward(s_, d_, r, x, T_edge[k0:k1], W0, Wr, Wi, lmax, E, gY)
+        np.add.at(dx, s_, gM[:, :, :E])
+        np.add.at(dx, d_, gM[:, :, E:2 * E])
+        dT[k0:k1] = gM[:, :, 2 * E:]
+        dW0 += g0
+        for m in range(lmax):
+            dWr[m] += gr[m]
+            dWi[m] += gi[m]
+    return dx, dT, dW0, dWr, dWi, dw_att
+
+
+def gate_backward(x, W_g, lmax, dy):
+    """Adjoint of gate: (dx, dW_g).  y[L=0] = SiLU(x0); y_l = x_l * g_l with g_l = sigmoid(W_g[l-1] x0), so
+    dx_l = dy_l g_l, dg_l[c] = sum_m dy_l[m][c] x_l[m][c], dz_l = dg_l g_l (1 - g_l), dW_g[l-1] = sum_nodes dz_l x0^T,
+    dx0 = dy0 SiLU'(x0) + sum_l W_g[l-1]^T dz_l."""
+    x = np.asarray(x, F64)
+    dy = np.asarray(dy, F64)
+    x0 = x[:, 0, :]
+    sg = 1.0 / (1.0 + np.exp(-x0))
+    dx = np.zeros_like(x)
+    dx[:, 0, :] = dy[:, 0, :] * (sg * (1.0 + x0 * (1.0 - sg)))
+    dW = np.zeros((max(lmax, 0), x.shape[2], x.shape[2]), F64)
+    for l in range(1, lmax + 1):
+        Wl = np.asarray(W_g[l - 1], F64)
+        g = 1.0 / (1.0 + np.exp(-(x0 @ Wl.T)))
+        dx[:, O.sl(l), :] = dy[:, O.sl(l), :] * g[:, None, :]
+        dz = np.einsum("nmc,nmc->nc", dy[:, O.sl(l), :], x[:, O.sl(l), :]) * g * (1.0 - g)
+        dW[l - 1] = dz.T @ x0
+        dx[:, 0, :] += dz @ Wl
+    return dx, dW

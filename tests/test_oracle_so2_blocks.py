@@ -116,3 +116,96 @@ def test_gate_closed_forms_and_equivariance():
     assert np.allclose(y[n, O.sl(l), c], x[n, O.sl(l), c] * gate)
     Dm = O.wigner_d_block(lmax, _rot(rng))
     assert np.allclose(S.gate(np.einsum("ab,nbc->nac", Dm, x), W_g, lmax), np.einsum("ab,nbc->nac", Dm, y), atol=1e-12)
+
+
+def _fd_check(loss, grads, values, rng, h=1e-4, rel=2e-7):
+    """Central differences of a scalar loss along a random direction and along one entry of every argument.
+    grads / values: dicts by argument name (a value may be a list of arrays: then one member at a time)."""
+    for name, grad in grads.items():
+        members = list(range(len(grad))) if isinstance(grad, list) else [None]
+        for mem in members:
+            g = grad[mem] if mem is not None else grad
+            base = values[name][mem] if mem is not None else values[name]
+
+            def moved(t):
+                if mem is None:
+                    return {name: base + t}
+                return {name: [v + (t if i == mem else 0) for i, v in enumerate(values[name])]}
+
+            v = rng.standard_normal(g.shape)
+            idx = tuple(rng.integers(0, s) for s in g.shape)
+            e = np.zeros(g.shape)
+            e[idx] = 1.0
+            for direction, expect in ((v, float((g * v).sum())), (e, float(g[idx]))):
+                fd = (loss(**moved(h * direction)) - loss(**moved(-h * direction))) / (2 * h)
+                assert fd == pytest.approx(expect, rel=rel, abs=1e-8), (name, mem)
+
+
+def _block_setup(lmax, E, seed):
+    w, g, x, W_e, W0, Wr, Wi = _setup(lmax, E, seed=seed)
+    rng = np.random.default_rng(40 + seed)
+    T = rng.standard_normal((len(g[0]), (lmax + 1) ** 2, E))
+    return w, g, x, T, W0, Wr, Wi, rng
+
+
+def test_edge_block_backward_is_the_derivative_of_the_forward():
+    lmax, E, r_cut = 2, 4, 4.0
+    w, g, x, T, W0, Wr, Wi, rng = _block_setup(lmax, E, 5)
+    dT_out = rng.standard_normal(T.shape)
+    vals = dict(x=x, T=T, W0=W0, Wr=Wr, Wi=Wi)
+
+    def loss(**kw):
+        a = dict(vals, **kw)
+        return float((S.so2_edge_block(g, w.pos, w.box, a["x"], a["T"], a["W0"], a["Wr"], a["Wi"], lmax, E, r_cut) * dT_out).sum())
+
+    dx, dT_in, dW0, dWr, dWi = S.so2_edge_block_backward(g, w.pos, w.box, x, T, W0, Wr, Wi, lmax, E, r_cut, dT_out)
+    # the map is linear in (x, T) and in each weight group: the difference quotient is exact up to rounding
+    _fd_check(loss, dict(x=dx, T=dT_in, W0=dW0, Wr=dWr, Wi=dWi), vals, rng, h=1e-3, rel=1e-8)
+    # zero weights: the block is the identity on T, and so is its adjoint
+    z = S.so2_edge_block_backward(g, w.pos, w.box, x, T, 0 * W0, [0 * a for a in Wr], [0 * a for a in Wi], lmax, E, r_cut, dT_out)
+    assert np.array_equal(z[1], dT_out) and not z[0].any()
+
+
+def test_node_block_backward_is_the_derivative_of_the_forward():
+    lmax, E, r_cut = 2, 4, 4.0
+    w, g, x, T, W0, Wr, Wi, rng = _block_setup(lmax, E, 6)
+    w_att = rng.standard_normal(E)
+    da = rng.standard_normal((w.n_owned, (lmax + 1) ** 2, E))
+    vals = dict(x=x, T=T, W0=W0, Wr=Wr, Wi=Wi, w_att=w_att)
+
+    def loss(**kw):
+        a = dict(vals, **kw)
+        return float((S.so2_node_block(g, w.pos, w.box, a["x"], a["T"], a["W0"], a["Wr"], a["Wi"], a["w_att"], lmax, E,
+                                       r_cut) * da).sum())
+
+    dx, dT, dW0, dWr, dWi, dw_att = S.so2_node_block_backward(g, w.pos, w.box, x, T, W0, Wr, Wi, w_att, lmax, E, r_cut, da)
+    # not linear (softmax, LeakyReLU): small steps; a kink of the LeakyReLU inside a step would show as a 1e-4 mismatch
+    _fd_check(loss, dict(x=dx, T=dT, W0=dW0, Wr=dWr, Wi=dWi, w_att=dw_att), vals, rng, h=1e-5, rel=2e-6)
+    # with w_att = 0 the weights are 1 / degree whatever the messages: no gradient flows through the scores
+    dx0, dT0, *_rest, dw0 = S.so2_node_block_backward(g, w.pos, w.box, x, T, W0, Wr, Wi, 0 * w_att, lmax, E, r_cut, da)
+    deg = np.diff(g[3])
+    gY_scale = np.repeat(1.0 / deg, deg)
+    lin = S.so2_edge_block_backward(g, w.pos, w.box, x, T, W0, Wr, Wi, lmax, E, r_cut, da[g[1]] * gY_scale[:, None, None])
+    assert np.allclose(dx0, lin[0], atol=1e-12) and np.allclose(dT0, lin[1] - da[g[1]] * gY_scale[:, None, None], atol=1e-12)
+    assert np.abs(dw0).max() > 0          # (the scores still depend on w_att to first order)
+
+
+def test_gate_backward_is_the_derivative_of_the_forward():
+    lmax, E = 3, 5
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((6, (lmax + 1) ** 2, E))
+    W_g = rng.standard_normal((lmax, E, E)) / np.sqrt(E)
+    dy = rng.standard_normal(x.shape)
+    vals = dict(x=x, W_g=W_g)
+
+    def loss(**kw):
+        a = dict(vals, **kw)
+        return float((S.gate(a["x"], a["W_g"], lmax) * dy).sum())
+
+    dx, dW = S.gate_backward(x, W_g, lmax, dy)
+    _fd_check(loss, dict(x=dx, W_g=dW), vals, rng, h=1e-5, rel=1e-6)
+    # lmax = 0: SiLU alone, derivative sigma(x) (1 + x (1 - sigma(x)))
+    x0 = rng.standard_normal((4, 1, E))
+    d0, _ = S.gate_backward(x0, np.zeros((0, E, E)), 0, np.ones_like(x0))
+    s = 1 / (1 + np.exp(-x0))
+    assert np.allclose(d0, s * (1 + x0 * (1 - s)), atol=1e-14)
