@@ -369,6 +369,33 @@ int egnn_so2_edge_block(egnn_ctx* ctx, const egnn_graph* g, const float* pos, co
                         void* stream);
 int egnn_gate(egnn_ctx* ctx, const float* x, const float* W_g, float* y, int32_t n_nodes, void* stream);
 
+/* Adjoints of the two blocks and of the gate with respect to node embeddings, edge embeddings and weights (Sec. 4.1:
+ * training needs the gradients of the forward pass; positions are data).  Outputs are overwritten, not accumulated;
+ * forward quantities are recomputed from the inputs; all sums are taken in a fixed order (no floating-point atomics).
+ * col_ptr, perm: the source-sorted index of egnn_graph_transpose.  dx [n_total][(lmax+1)^2][channels] (halo rows
+ * included), dW_so2 in the layout of W_so2.
+ * egnn_so2_node_block_backward: da [n_owned][...] is the gradient with respect to a; dT_edge [n_edges][...] the gradient
+ *   with respect to the edge embeddings; dw_att [channels].  The attention weights are differentiated through (softmax
+ *   over the incoming edges, LeakyReLU score; at a score input of exactly zero the slope 0.2 is taken).
+ * egnn_so2_edge_block_backward: dT_out [n_edges][...] is the gradient with respect to T_edge_out; dT_in receives
+ *   dT_out + the part through the messages and may alias dT_out.
+ * egnn_gate_backward: dy, dx [n_nodes][...]; dW_g [lmax][channels][channels]; ws: egnn_gate_backward_workspace_bytes
+ *   (not needed for lmax = 0).
+ * ws of the block calls: at least egnn_so2_blocks_backward_workspace_bytes, 256-byte aligned; EGNN_EWS if too small.
+ * 8 .. 128 channels. */
+int egnn_so2_blocks_backward_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, size_t* bytes);
+int egnn_so2_node_block_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm,
+                                 const float* pos, const float box[3], const float* x, const float* T_edge,
+                                 const float* W_so2, const float* w_att, const float* da, float* dx, float* dT_edge,
+                                 float* dW_so2, float* dw_att, void* ws, size_t ws_bytes, void* stream);
+int egnn_so2_edge_block_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm,
+                                 const float* pos, const float box[3], const float* x, const float* T_edge_in,
+                                 const float* W_so2, const float* dT_out, float* dx, float* dT_in, float* dW_so2,
+                                 void* ws, size_t ws_bytes, void* stream);
+int egnn_gate_backward_workspace_bytes(const egnn_ctx* ctx, int32_t n_nodes, size_t* bytes);
+int egnn_gate_backward(egnn_ctx* ctx, const float* x, const float* W_g, const float* dy, float* dx, float* dW_g,
+                       int32_t n_nodes, void* ws, size_t ws_bytes, void* stream);
+
 /* ---- assembly of the predicted Hamiltonian (Sec. 3, end of "Message passing": nodes give the diagonal blocks, edges the
  *      off-diagonal ones; Fig. 2(e): collapse E -> 1, padded outputs; Sec. 2.2 / Eq. 1: the coupled basis and its
  *      inverse; Sec. 6: combined L1 + L2 loss over the elements of H) ----

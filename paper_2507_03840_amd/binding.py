@@ -24,6 +24,8 @@ SYMBOLS = [
     "egnn_backward_workspace_bytes", "egnn_graph_transpose", "egnn_loss_mse", "egnn_layer_backward",
     "egnn_readout_backward", "egnn_set_option", "egnn_radial_weights_f16", "egnn_tp_segsum_f16", "egnn_so2_weight_count", "egnn_so2_workspace_bytes",
     "egnn_so2_message_sum", "egnn_so2_backward_workspace_bytes", "egnn_so2_message_sum_backward",
+    "egnn_so2_blocks_backward_workspace_bytes", "egnn_so2_node_block_backward", "egnn_so2_edge_block_backward",
+    "egnn_gate_backward_workspace_bytes", "egnn_gate_backward",
     "egnn_so2_blocks_workspace_bytes", "egnn_edge_embed_init", "egnn_so2_node_block",
     "egnn_so2_edge_block", "egnn_gate", "egnn_hamiltonian_workspace_bytes", "egnn_onsite_hii", "egnn_apply_padding", "egnn_loss_l1l2",
     "egnn_hamiltonian_structure", "egnn_hamiltonian_fill", "egnn_onsite_backward_workspace_bytes", "egnn_onsite_backward",
@@ -354,6 +356,43 @@ class Egnn:
             self.ctx, C.byref(g), _ptr(col_ptr), _ptr(perm), _ptr(pos), _f3(box), _ptr(x), _ptr(W_e), _ptr(W_so2),
             _ptr(da), _ptr(dx), _ptr(dW_e), _ptr(dW_so2), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
         return dx, dW_e, dW_so2
+
+    def egnn_so2_blocks_backward_workspace_bytes(self, n_edges, n_owned):
+        out = C.c_size_t()
+        self._check(self.lib.egnn_so2_blocks_backward_workspace_bytes(self.ctx, C.c_int64(n_edges), C.c_int32(n_owned),
+                                                                      C.byref(out)))
+        return out.value
+
+    def egnn_so2_node_block_backward(self, graph, col_ptr, perm, pos, box, x, T_edge, W_so2, w_att, da, ws):
+        """(dx, dT_edge, dW_so2, dw_att) from da [n_owned][dim][channels]."""
+        dx = torch.empty((graph.n_total, self.dim, self.channels), dtype=torch.float32, device="cuda")
+        dT, dW, dw_att = torch.empty_like(T_edge), torch.empty_like(W_so2), torch.empty_like(w_att)
+        g = graph.desc()
+        self._check(self.lib.egnn_so2_node_block_backward(
+            self.ctx, C.byref(g), _ptr(col_ptr), _ptr(perm), _ptr(pos), _f3(box), _ptr(x), _ptr(T_edge), _ptr(W_so2),
+            _ptr(w_att), _ptr(da), _ptr(dx), _ptr(dT), _ptr(dW), _ptr(dw_att), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+        return dx, dT, dW, dw_att
+
+    def egnn_so2_edge_block_backward(self, graph, col_ptr, perm, pos, box, x, T_edge_in, W_so2, dT_out, ws, dT_in=None):
+        """(dx, dT_in, dW_so2) from dT_out [n_edges][dim][channels]; dT_in may be dT_out itself."""
+        dx = torch.empty((graph.n_total, self.dim, self.channels), dtype=torch.float32, device="cuda")
+        dT = dT_in if dT_in is not None else torch.empty_like(dT_out)
+        dW = torch.empty_like(W_so2)
+        g = graph.desc()
+        self._check(self.lib.egnn_so2_edge_block_backward(
+            self.ctx, C.byref(g), _ptr(col_ptr), _ptr(perm), _ptr(pos), _f3(box), _ptr(x), _ptr(T_edge_in), _ptr(W_so2),
+            _ptr(dT_out), _ptr(dx), _ptr(dT), _ptr(dW), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+        return dx, dT, dW
+
+    def egnn_gate_backward(self, x, W_g, dy):
+        """(dx, dW_g) of the gate."""
+        out = C.c_size_t()
+        self._check(self.lib.egnn_gate_backward_workspace_bytes(self.ctx, C.c_int32(x.shape[0]), C.byref(out)))
+        ws = torch.empty(out.value, dtype=torch.uint8, device="cuda")
+        dx, dW = torch.empty_like(x), torch.empty_like(W_g)
+        self._check(self.lib.egnn_gate_backward(self.ctx, _ptr(x), _ptr(W_g), _ptr(dy), _ptr(dx), _ptr(dW),
+                                                C.c_int32(x.shape[0]), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+        return dx, dW
 
     def egnn_so2_blocks_workspace_bytes(self, n_edges):
         out = C.c_size_t()

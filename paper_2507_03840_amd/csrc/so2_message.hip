@@ -508,8 +508,10 @@ static int so2_check(egnn_ctx* ctx, const egnn_graph* g, const void* ws, size_t 
 }
 
 // geometry, gather into the m-major operands, weight packing and the GEMMs: Y_m of every edge in the workspace
+// (gemms = false: operands only -- the reverse passes that do not need Y)
 static int so2_transform(egnn_ctx* ctx, const egnn_graph* g, const float* pos, const float box[3], const float* x,
-                         const float* edge_in, bool full, const float* W_so2, void* ws, So2Call* call, hipStream_t st) {
+                         const float* edge_in, bool full, const float* W_so2, void* ws, So2Call* call, hipStream_t st,
+                         bool gemms = true) {
   const int lmax = ctx->desc.lmax, E = ctx->desc.channels;
   for (int m = 0; m < 5; ++m) { call->b.A[m] = call->b.Y[m] = nullptr; call->b.K[m] = call->b.N[m] = call->b.ldA[m] = call->b.ldY[m] = 0; call->T[m] = nullptr; }
   call->alpha = nullptr;
@@ -551,7 +553,7 @@ static int so2_transform(egnn_ctx* ctx, const egnn_graph* g, const float* pos, c
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(so2_gemm_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(so2_gemm_kernel)");
-  for (int m = 0; m <= lmax; ++m) {
+  for (int m = 0; gemms && m <= lmax; ++m) {
     const int K = call->b.K[m], N = call->b.N[m], n_steps = so2_steps(K), n_ct = so2_tiles(N);
     const long total = (long)n_ct * n_steps * 64 * 32;
     hipLaunchKernelGGL(so2_pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
@@ -700,9 +702,16 @@ extern "C" int egnn_gate(egnn_ctx* ctx, const float* x, const float* W_g, float*
 //                              part goes to a per-edge row that a segmented sum over the source-sorted index adds up;
 //      so2_dwe_kernel          dW_e[c][q] = sum_k dA_0[k][edge column c] B_q(d_k).
 // ---------------------------------------------------------------------------------------------------------------------
+// Gradient of the bond-frame results, written m-major over Y_m.  The lab-frame gradient of edge k is
+//   scale f_c(d_k) [alpha_k] rows[per_edge ? k : dst(k)]      (the sum over incoming edges, weighted if alpha != NULL, or
+//                                                              the edge update)
+// plus, for the node block (ds != NULL), ds_k w_att[c] LeakyReLU'(y_k[L = 0][c]) in the L = 0 plane -- the part that
+// reaches the messages through the attention scores; y_k[L = 0] is read from Y_0 before it is overwritten.
 template <int LMAX>
 __global__ __launch_bounds__(256) void so2_dy_kernel(const int* __restrict__ dst, const float4* __restrict__ rhat_d,
-                                                     const float* __restrict__ da, So2Bufs b, long n_edges, int log2E,
+                                                     const float* __restrict__ rows, bool per_edge,
+                                                     const float* __restrict__ alpha, const float* __restrict__ ds,
+                                                     const float* __restrict__ w_att, So2Bufs b, long n_edges, int log2E,
                                                      float scale, float r_cut, unsigned* __restrict__ y_max) {
   constexpr int D = (LMAX + 1) * (LMAX + 1);
   const int E = 1 << log2E;
@@ -711,11 +720,17 @@ __global__ __launch_bounds__(256) void so2_dy_kernel(const int* __restrict__ dst
   const bool live = k_own < n_edges;
   const long k = live ? k_own : n_edges - 1;   // (as in the gather kernel: every lane takes part in the reduction)
   const float4 g = rhat_d[k];
-  const float f = scale * egnn_envelope(g.w, r_cut);
-  const float* dj = da + (((size_t)dst[k] * D) << log2E) + c;
+  float f = scale * egnn_envelope(g.w, r_cut);
+  if (alpha) f *= alpha[k];
+  const float* dj = rows + (((size_t)(per_edge ? k : (long)dst[k]) * D) << log2E) + c;
   float v[D];
 #pragma unroll
   for (int i = 0; i < D; ++i) v[i] = f * dj[(size_t)i << log2E];
+  float* y0 = b.Y[0] + (size_t)k * b.ldY[0] + c;
+  if (ds) {
+    const float y = y0[0];                     // L = 0 plane of the transformed message (the same in both frames)
+    v[0] += ds[k] * w_att[c] * (y > 0.0f ? 1.0f : 0.2f);
+  }
   BondTrig t;
   egnn_bond_trig<LMAX>(g.x, g.y, g.z, t);
   egnn_to_bond_frame<LMAX>(v, t);            // Y = D^T Y' in the forward pass, so dY' = D dY
@@ -723,7 +738,6 @@ __global__ __launch_bounds__(256) void so2_dy_kernel(const int* __restrict__ dst
 #pragma unroll
   for (int i = 0; i < D; ++i) amax = fmaxf(amax, fabsf(v[i]));
   if (live) {
-    float* y0 = b.Y[0] + (size_t)k * b.ldY[0] + c;
 #pragma unroll
     for (int l = 0; l <= LMAX; ++l) __builtin_nontemporal_store(v[l * l + l], y0 + (l << log2E));
 #pragma unroll
@@ -740,6 +754,81 @@ __global__ __launch_bounds__(256) void so2_dy_kernel(const int* __restrict__ dst
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
   if ((threadIdx.x & 63) == 0) so2_raise_max(y_max, amax);
+}
+
+// Adjoint of the attention weights of the node block, one workgroup per destination node j (lane = (edge slot,
+// channel)):  t_k = f_c(d_k) <da_j, y_k> is the gradient of alpha_k; the softmax gives ds_k = alpha_k (t_k - sum alpha t)
+// (written over t); the score s_k = w_att . LeakyReLU(y_k[L = 0]) gives dw_att += ds_k LeakyReLU(y_k[L = 0]), kept per
+// node in dwatt_part[j][E] and added up afterwards.  All sums in a fixed order.
+template <int LMAX>
+__global__ __launch_bounds__(256) void so2_attention_adjoint_kernel(const int* __restrict__ row_ptr,
+                                                                    const float4* __restrict__ rhat_d, So2Bufs b,
+                                                                    const float* __restrict__ alpha,
+                                                                    const float* __restrict__ da, float* __restrict__ tds,
+                                                                    float* __restrict__ dwatt_part, int n_owned, int log2E,
+                                                                    float r_cut) {
+  constexpr int D = (LMAX + 1) * (LMAX + 1);
+  __shared__ float red[256];
+  __shared__ float s_sum;
+  const int j = blockIdx.x;
+  if (j >= n_owned) return;
+  const int E = 1 << log2E;
+  const int tid = threadIdx.x;
+  const int c = tid & (E - 1), slot = tid >> log2E, n_slots = 256 >> log2E;
+  const int k0 = row_ptr[j], k1 = row_ptr[j + 1];
+  float daj[D];
+#pragma unroll
+  for (int i = 0; i < D; ++i) daj[i] = da[(((size_t)j * D + i) << log2E) + c];
+  // pass 1: t_k (every thread runs the same number of rounds: there is a barrier in each)
+  const int rounds = (k1 - k0 + n_slots - 1) / n_slots;
+  for (int r = 0; r < rounds; ++r) {
+    const int k = k0 + r * n_slots + slot;
+    float p = 0.0f;
+    float fc = 0.0f;
+    if (k < k1) {
+      const float4 g = rhat_d[k];
+      float o[D];
+      so2_load_rotate_back<LMAX>(b, k, c, log2E, g, o);
+#pragma unroll
+      for (int i = 0; i < D; ++i) p += daj[i] * o[i];
+      fc = egnn_envelope(g.w, r_cut);
+    }
+    red[tid] = p;
+    __syncthreads();
+    if (c == 0 && k < k1) {
+      float sum = 0.0f;
+      for (int q = 0; q < E; ++q) sum += red[(slot << log2E) + q];
+      tds[k] = fc * sum;
+    }
+    __syncthreads();
+  }
+  // pass 2: sum_k alpha_k t_k (this workgroup wrote t itself: visible after the barrier above)
+  float part = 0.0f;
+  for (int k = k0 + tid; k < k1; k += 256) part += alpha[k] * tds[k];
+  red[tid] = part;
+  __syncthreads();
+  if (tid == 0) {
+    float sum = 0.0f;
+    for (int q = 0; q < 256; ++q) sum += red[q];
+    s_sum = sum;
+  }
+  __syncthreads();
+  const float mean = s_sum;
+  for (int k = k0 + tid; k < k1; k += 256) tds[k] = alpha[k] * (tds[k] - mean);
+  __syncthreads();
+  // pass 3: this node's part of dw_att
+  float acc = 0.0f;
+  for (int k = k0 + slot; k < k1; k += n_slots) {
+    const float y = b.Y[0][(size_t)k * b.ldY[0] + c];
+    acc += tds[k] * (y > 0.0f ? y : 0.2f * y);
+  }
+  red[tid] = acc;
+  __syncthreads();
+  if (tid < E) {
+    float sum = 0.0f;
+    for (int q = 0; q < n_slots; ++q) sum += red[(q << log2E) + tid];
+    dwatt_part[((size_t)j << log2E) + tid] = sum;
+  }
 }
 
 // partial[chunk][k][n] = sum over the edges e of the chunk of A[e][k] Y[e][n].  Workgroup = (chunk of edges, four
@@ -853,11 +942,12 @@ __global__ __launch_bounds__(256, 2) void so2_wgrad_kernel(const float* __restri
   }
 }
 
-// dB_m [K][N] (column orders of A_m and Y_m, without persistent edge embeddings) -> gradient of W_0 (m = 0) or of
-// (Wr_m, Wi_m), row-major like the weights.  Weight columns that multiply the planes l > 0 of the edge embedding, which
-// are zero in this path, have gradient zero.  One thread per weight element of W_0 / Wr_m.
+// dB_m [K][N] (column orders of A_m and Y_m) -> gradient of W_0 (m = 0) or of (Wr_m, Wi_m), row-major like the weights.
+// Without persistent edge embeddings (full = false) the weight columns that multiply the planes l > 0 of the edge
+// embedding, which are zero on that path, have gradient zero; with them the columns of A_m are in the column order of
+// the weights.  One thread per weight element of W_0 / Wr_m.
 __global__ __launch_bounds__(256) void so2_unpack_wgrad_kernel(const float* __restrict__ dB, float* __restrict__ dW, int m,
-                                                               int lmax, int E, int N) {
+                                                               int lmax, int E, int N, bool full) {
   const int nl = lmax + 1 - m;
   const int rows = nl * E, cols = nl * 3 * E;
   const long idx = (long)blockIdx.x * 256 + threadIdx.x;
@@ -865,16 +955,18 @@ __global__ __launch_bounds__(256) void so2_unpack_wgrad_kernel(const float* __re
   const int row = (int)(idx / cols), col = (int)(idx - (long)row * cols);
   const int li = col / (3 * E), rem = col - li * 3 * E;
   const int gsel = rem / E, c = rem - gsel * E;
+  // column of A_m (its +m half) that this weight column multiplies, -1: none
+  int kr = -1;
+  if (full) kr = col;
+  else if (gsel < 2) kr = li * 2 * E + gsel * E + c;
+  else if (m == 0 && li == 0) kr = (lmax + 1) * 2 * E + c;
   if (m == 0) {
-    int k = -1;
-    if (gsel < 2) k = li * 2 * E + gsel * E + c;
-    else if (li == 0) k = (lmax + 1) * 2 * E + c;
-    dW[idx] = k >= 0 ? dB[(size_t)k * N + row] : 0.0f;
+    dW[idx] = kr >= 0 ? dB[(size_t)kr * N + row] : 0.0f;
     return;
   }
   float gr = 0.0f, gi = 0.0f;
-  if (gsel < 2) {
-    const int kr = li * 2 * E + gsel * E + c, half_k = nl * 2 * E, half_n = nl * E;
+  if (kr >= 0) {
+    const int half_k = full ? nl * 3 * E : nl * 2 * E, half_n = nl * E;
     const float pp = dB[(size_t)kr * N + row], mm = dB[(size_t)(half_k + kr) * N + half_n + row];
     const float pm = dB[(size_t)kr * N + half_n + row], mp = dB[(size_t)(half_k + kr) * N + row];
     gr = pp + mm;     // Wr takes x_{+m} to y_{+m} and x_{-m} to y_{-m}
@@ -884,14 +976,17 @@ __global__ __launch_bounds__(256) void so2_unpack_wgrad_kernel(const float* __re
   dW[(size_t)rows * cols + idx] = gi;
 }
 
-// One workgroup per destination node j, lane = (edge slot, channel): the node parts of dA_m[k] back in (l, m) order and
+// One workgroup per destination node j, lane = (edge slot, channel): the parts of dA_m[k] back in (l, m) order and
 // in the lab frame (X' = D M in the forward pass, so dM = D^T dX').  Source part -> rows[k], destination part summed
-// over the incoming edges of j in a fixed order -> dxd[j].
-template <int LMAX>
+// over the incoming edges of j in a fixed order -> dxd[j].  FULL (persistent edge embeddings): the edge part
+// -> dT[k], plus dT_add[k] if that is given (the identity term of the edge update; dT may be dT_add).
+template <int LMAX, bool FULL>
 __global__ __launch_bounds__(256) void so2_dx_kernel(const int* __restrict__ row_ptr, const float4* __restrict__ rhat_d,
                                                      So2Bufs b, float* __restrict__ rows, float* __restrict__ dxd,
-                                                     int n_owned, int log2E, int nodes_per_xcd) {
+                                                     float* dT, const float* dT_add, int n_owned, int log2E,
+                                                     int nodes_per_xcd) {
   constexpr int D = (LMAX + 1) * (LMAX + 1);
+  constexpr int G = FULL ? 3 : 2;            // column groups per degree
   __shared__ float red[256 * D];
   const int j = (blockIdx.x & 7) * nodes_per_xcd + (blockIdx.x >> 3);
   if (j >= n_owned || (int)(blockIdx.x >> 3) >= nodes_per_xcd) return;
@@ -904,35 +999,43 @@ __global__ __launch_bounds__(256) void so2_dx_kernel(const int* __restrict__ row
   for (int i = 0; i < D; ++i) acc[i] = 0.0f;
   for (int k = k0 + slot; k < k1; k += n_slots) {
     const float4 g = rhat_d[k];
-    float vs[D], vd[D];
-    const float* a0 = b.A[0] + (size_t)k * b.ldA[0] + c;
-#pragma unroll
-    for (int l = 0; l <= LMAX; ++l) {
-      vs[l * l + l] = __builtin_nontemporal_load(a0 + ((2 * l) << log2E));
-      vd[l * l + l] = __builtin_nontemporal_load(a0 + ((2 * l + 1) << log2E));
-    }
-#pragma unroll
-    for (int m = 1; m <= LMAX; ++m) {
-      const int nl = LMAX + 1 - m;
-      const float* am = b.A[m] + (size_t)k * b.ldA[m] + c;
-#pragma unroll
-      for (int l = m; l <= LMAX; ++l) {
-        const int col = (2 * (l - m)) << log2E, neg = (2 * nl) << log2E;
-        vs[l * l + l + m] = __builtin_nontemporal_load(am + col);
-        vd[l * l + l + m] = __builtin_nontemporal_load(am + col + E);
-        vs[l * l + l - m] = __builtin_nontemporal_load(am + neg + col);
-        vd[l * l + l - m] = __builtin_nontemporal_load(am + neg + col + E);
-      }
-    }
     BondTrig t;
     egnn_bond_trig<LMAX>(g.x, g.y, g.z, t);
-    egnn_from_bond_frame<LMAX>(vs, t);
-    egnn_from_bond_frame<LMAX>(vd, t);
-    float* rk = rows + (((size_t)k * D) << log2E) + c;
+    // one column group at a time (0 source, 1 destination, 2 edge): 25 values in registers
 #pragma unroll
-    for (int i = 0; i < D; ++i) {
-      __builtin_nontemporal_store(vs[i], rk + ((size_t)i << log2E));
-      acc[i] += vd[i];
+    for (int grp = 0; grp < G; ++grp) {
+      float v[D];
+      const float* a0 = b.A[0] + (size_t)k * b.ldA[0] + c;
+#pragma unroll
+      for (int l = 0; l <= LMAX; ++l) v[l * l + l] = __builtin_nontemporal_load(a0 + ((G * l + grp) << log2E));
+#pragma unroll
+      for (int m = 1; m <= LMAX; ++m) {
+        const int nl = LMAX + 1 - m;
+        const float* am = b.A[m] + (size_t)k * b.ldA[m] + c;
+#pragma unroll
+        for (int l = m; l <= LMAX; ++l) {
+          const int col = (G * (l - m) + grp) << log2E, neg = (G * nl) << log2E;
+          v[l * l + l + m] = __builtin_nontemporal_load(am + col);
+          v[l * l + l - m] = __builtin_nontemporal_load(am + neg + col);
+        }
+      }
+      egnn_from_bond_frame<LMAX>(v, t);
+      if (grp == 0) {
+        float* rk = rows + (((size_t)k * D) << log2E) + c;
+#pragma unroll
+        for (int i = 0; i < D; ++i) __builtin_nontemporal_store(v[i], rk + ((size_t)i << log2E));
+      } else if (grp == 1) {
+#pragma unroll
+        for (int i = 0; i < D; ++i) acc[i] += v[i];
+      } else {
+        float* tk = dT + (((size_t)k * D) << log2E) + c;
+        const float* ta = dT_add ? dT_add + (((size_t)k * D) << log2E) + c : nullptr;
+#pragma unroll
+        for (int i = 0; i < D; ++i) {
+          const float add = ta ? ta[(size_t)i << log2E] : 0.0f;
+          tk[(size_t)i << log2E] = v[i] + add;
+        }
+      }
     }
   }
 #pragma unroll
@@ -1027,16 +1130,19 @@ struct So2Bwd {
   float* dxd;       // [n_owned][D][E]
   float* partial;   // partial weight gradients of one order
   float* dB;        // [K_m][N_m] of one order
-  float* dwe;       // [SO2_DWE_CHUNKS][E][n_rbf]
+  float* dwe;       // [SO2_DWE_CHUNKS][E][n_rbf]   (message sum)
+  float* tds;       // [n_edges] gradient of the attention weights, then of the scores   (node block)
+  float* dwatt;     // [n_owned][E] per-node parts of dw_att                             (node block)
 };
 
-static size_t so2_bwd_ws(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, bool carve, char* base, So2Bwd* out) {
+static size_t so2_bwd_ws(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, bool full, bool carve, char* base,
+                         So2Bwd* out) {
   const int lmax = ctx->desc.lmax, E = ctx->desc.channels, D = (lmax + 1) * (lmax + 1);
-  size_t used = so2_ws(ctx, n_edges, false, false, nullptr, nullptr, nullptr, nullptr, nullptr);
+  size_t used = so2_ws(ctx, n_edges, full, false, nullptr, nullptr, nullptr, nullptr, nullptr);
   auto take = [&](size_t bytes) { char* p = carve ? base + used : nullptr; used += so2_a256(bytes); return p; };
   size_t part = 0, db = 0;
   for (int m = 0; m <= lmax; ++m) {
-    const int K = so2_K(lmax, E, m), N = so2_N(lmax, E, m);
+    const int K = so2_K(lmax, E, m, full), N = so2_N(lmax, E, m);
     int chunks;
     long per;
     so2_wgrad_split(n_edges > 0 ? n_edges : 1, K, N, &chunks, &per);
@@ -1048,56 +1154,27 @@ static size_t so2_bwd_ws(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, 
   w.dxd = (float*)take((size_t)n_owned * D * E * sizeof(float));
   w.partial = (float*)take(part * sizeof(float));
   w.dB = (float*)take(db * sizeof(float));
-  w.dwe = (float*)take((size_t)SO2_DWE_CHUNKS * E * ctx->desc.n_rbf * sizeof(float));
+  w.dwe = full ? nullptr : (float*)take((size_t)SO2_DWE_CHUNKS * E * ctx->desc.n_rbf * sizeof(float));
+  w.tds = full ? (float*)take((size_t)n_edges * sizeof(float)) : nullptr;
+  w.dwatt = full ? (float*)take((size_t)n_owned * E * sizeof(float)) : nullptr;
   if (out) *out = w;
   return used;
 }
 
 extern "C" int egnn_so2_backward_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned, size_t* bytes) {
   if (!ctx || !bytes || n_edges < 0 || n_owned < 0) return EGNN_EINVAL;
-  *bytes = so2_bwd_ws(ctx, n_edges, n_owned, false, nullptr, nullptr) + 256;
+  *bytes = so2_bwd_ws(ctx, n_edges, n_owned, false, false, nullptr, nullptr) + 256;
   return EGNN_OK;
 }
 
-extern "C" int egnn_so2_message_sum_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr,
-                                             const int32_t* perm, const float* pos, const float box[3], const float* x,
-                                             const float* W_e, const float* W_so2, const float* da, float* dx,
-                                             float* dW_e, float* dW_so2, void* ws, size_t ws_bytes, void* stream) {
-  if (!ctx) return EGNN_EINVAL;
-  if (!pos || !box || !x || !W_e || !W_so2 || !dW_e || !dW_so2 || !col_ptr)
-    return egnn_fail(ctx, EGNN_EINVAL, "so2_message_sum_backward: null pointer");
-  int rc = so2_check(ctx, g, ws, ws_bytes, false, "so2_message_sum_backward");
-  if (rc) return rc;
-  if (ctx->desc.channels > 128 || ctx->desc.n_rbf > 32)
-    return egnn_fail(ctx, EGNN_EINVAL, "so2_message_sum_backward: needs <= 128 channels and <= 32 radial bases");
-  if ((g->n_total > 0 && !dx) || (g->n_owned > 0 && !da) || (g->n_edges > 0 && !perm))
-    return egnn_fail(ctx, EGNN_EINVAL, "so2_message_sum_backward: null pointer");
-  if (ws_bytes < so2_bwd_ws(ctx, g->n_edges, g->n_owned, false, nullptr, nullptr))
-    return egnn_fail(ctx, EGNN_EWS, "so2_message_sum_backward: workspace too small");
-  hipStream_t st = (hipStream_t)stream;
-  const int lmax = ctx->desc.lmax, E = ctx->desc.channels, D = (lmax + 1) * (lmax + 1), n_rbf = ctx->desc.n_rbf;
-  const long n = g->n_edges;
-  const long n_w = (long)so2_w_offset(lmax, E, lmax + 1);
-  if (n == 0) {
-    // no message: every gradient is zero (a float zero is the integer zero)
-    if ((rc = egnn_launch_fill_int(ctx, (int*)dx, (long)g->n_total * D * E, 0, st))) return rc;
-    if ((rc = egnn_launch_fill_int(ctx, (int*)dW_e, (long)E * n_rbf, 0, st))) return rc;
-    return egnn_launch_fill_int(ctx, (int*)dW_so2, n_w, 0, st);
-  }
-  So2Call call;
-  for (int m = 0; m < 5; ++m) { call.b.A[m] = call.b.Y[m] = nullptr; call.b.K[m] = call.b.N[m] = call.b.ldA[m] = call.b.ldY[m] = 0; call.T[m] = nullptr; }
-  call.alpha = nullptr;
-  so2_ws(ctx, n, false, true, (char*)ws, &call.rhat_d, &call.b, call.T, &call.alpha, &call.maxima);
-  So2Bwd w;
-  so2_bwd_ws(ctx, n, g->n_owned, true, (char*)ws, &w);
-  // maxima[0]: largest |dY| (operand of the GEMMs of step 4), [1]: largest weight, [2]: largest |A| (not used here)
-  if ((rc = egnn_launch_fill_int(ctx, (int*)call.maxima, 64, 0, st))) return rc;
-  if ((rc = egnn_launch_geometry(ctx, g, pos, box, call.rhat_d, nullptr, nullptr, nullptr, st))) return rc;
-  const float4* rd = reinterpret_cast<const float4*>(call.rhat_d);
-  const int per_wg = 256 / E;
-  const dim3 egrid((unsigned)((n + per_wg - 1) / per_wg)), block(256);
-  const float scale = 1.0f / sqrtf(ctx->desc.agg_norm);
-#define SO2_BY_LMAX(STMT)          \
+extern "C" int egnn_so2_blocks_backward_workspace_bytes(const egnn_ctx* ctx, int64_t n_edges, int32_t n_owned,
+                                                        size_t* bytes) {
+  if (!ctx || !bytes || n_edges < 0 || n_owned < 0) return EGNN_EINVAL;
+  *bytes = so2_bwd_ws(ctx, n_edges, n_owned, true, false, nullptr, nullptr) + 256;
+  return EGNN_OK;
+}
+
+#define SO2_BY_LMAX(lmax, STMT)    \
   switch (lmax) {                  \
     case 0: { STMT(0); } break;    \
     case 1: { STMT(1); } break;    \
@@ -1105,21 +1182,40 @@ extern "C" int egnn_so2_message_sum_backward(egnn_ctx* ctx, const egnn_graph* g,
     case 3: { STMT(3); } break;    \
     default: { STMT(4); } break;   \
   }
-#define GATHER(L)                                                                                                    \
-  hipLaunchKernelGGL((so2_gather_kernel<L, false>), egrid, block, 0, st, g->src, g->dst, rd, x, W_e, call.b, n,      \
-                     ctx->log2_channels, n_rbf, ctx->desc.r_cut, call.maxima + 2)
-  SO2_BY_LMAX(GATHER)
-#undef GATHER
-  EGNN_LAUNCH_CHECK(ctx, "so2_gather_kernel");
-#define DY(L)                                                                                                        \
-  hipLaunchKernelGGL(so2_dy_kernel<L>, egrid, block, 0, st, g->dst, rd, da, call.b, n, ctx->log2_channels, scale,    \
-                     ctx->desc.r_cut, call.maxima)
-  SO2_BY_LMAX(DY)
+
+// what the lab-frame gradient of the transformed messages is made of (so2_dy_kernel)
+struct So2Grad {
+  const float* rows;     // da [n_owned][D][E] (read at dst(k)) or, per_edge, dT_out [n_edges][D][E]
+  bool per_edge;
+  float scale;           // factor besides f_c
+  const float* alpha;    // node block: attention weights, gradient of the scores, attention vector
+  const float* ds;
+  const float* w_att;
+};
+
+// The part every reverse pass shares, after the operands A_m are in the workspace (so2_transform): dY_m over Y_m, then
+// per order the weight gradient and dA_m over A_m, then the rotation back with the sums over the two node roles.
+// dT / dT_add: gradient of the edge embeddings (full only).  maxima[2], [3] must be zero on entry.
+static int so2_backward_tail(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm, bool full,
+                             const float* W_so2, const So2Grad& grad, So2Call& call, So2Bwd& w, float* dx,
+                             float* dW_so2, float* dT, const float* dT_add, hipStream_t st) {
+  const int lmax = ctx->desc.lmax, E = ctx->desc.channels, D = (lmax + 1) * (lmax + 1);
+  const long n = g->n_edges;
+  const long n_w = (long)so2_w_offset(lmax, E, lmax + 1);
+  int rc;
+  const float4* rd = reinterpret_cast<const float4*>(call.rhat_d);
+  const int per_wg = 256 / E;
+  const dim3 egrid((unsigned)((n + per_wg - 1) / per_wg)), block(256);
+  unsigned* bmax = call.maxima + 2;   // [0]: largest |dY| (operand of the GEMMs below), [1]: largest weight
+#define DY(L)                                                                                                          \
+  hipLaunchKernelGGL(so2_dy_kernel<L>, egrid, block, 0, st, g->dst, rd, grad.rows, grad.per_edge, grad.alpha, grad.ds, \
+                     grad.w_att, call.b, n, ctx->log2_channels, grad.scale, ctx->desc.r_cut, bmax)
+  SO2_BY_LMAX(lmax, DY)
 #undef DY
   EGNN_LAUNCH_CHECK(ctx, "so2_dy_kernel");
   {
     const unsigned wg = (unsigned)((n_w + 255) / 256 < 256 ? (n_w + 255) / 256 : 256);
-    hipLaunchKernelGGL(so2_wmax_kernel, dim3(wg), dim3(256), 0, st, W_so2, n_w, call.maxima + 1);
+    hipLaunchKernelGGL(so2_wmax_kernel, dim3(wg), dim3(256), 0, st, W_so2, n_w, bmax + 1);
     EGNN_LAUNCH_CHECK(ctx, "so2_wmax_kernel");
   }
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(so2_gemm_kernel),
@@ -1130,47 +1226,43 @@ extern "C" int egnn_so2_message_sum_backward(egnn_ctx* ctx, const egnn_graph* g,
     int chunks;
     long per;
     so2_wgrad_split(n, K, N, &chunks, &per);
-    hipLaunchKernelGGL(so2_wgrad_kernel, dim3(so2_wgrad_groups(K, N), chunks), dim3(64 * so2_wgrad_waves(K, N)), 0, st, call.b.A[m], K,
-                       call.b.ldA[m], call.b.Y[m], N, call.b.ldY[m], n, per, (N + 63) / 64, w.partial);
+    hipLaunchKernelGGL(so2_wgrad_kernel, dim3(so2_wgrad_groups(K, N), chunks), dim3(64 * so2_wgrad_waves(K, N)), 0, st,
+                       call.b.A[m], K, call.b.ldA[m], call.b.Y[m], N, call.b.ldY[m], n, per, (N + 63) / 64, w.partial);
     EGNN_LAUNCH_CHECK(ctx, "so2_wgrad_kernel");
     if ((rc = egnn_launch_reduce_partials(ctx, w.partial, chunks, (long)K * N, w.dB, 1.0f, st))) return rc;
     const int nl = lmax + 1 - m;
     const long n_el = (long)nl * E * nl * 3 * E;
     hipLaunchKernelGGL(so2_unpack_wgrad_kernel, dim3((unsigned)((n_el + 255) / 256)), dim3(256), 0, st, w.dB,
-                       dW_so2 + so2_w_offset(lmax, E, m), m, lmax, E, N);
+                       dW_so2 + so2_w_offset(lmax, E, m), m, lmax, E, N, full);
     EGNN_LAUNCH_CHECK(ctx, "so2_unpack_wgrad_kernel");
     // dA_m = dY_m B_m^T over A_m: contraction over the N columns of Y_m, one output column per column of A_m
     const int n_steps = so2_steps(N), n_ct = so2_tiles(K);
     const long total = (long)n_ct * n_steps * 64 * 32;
     hipLaunchKernelGGL(so2_pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                       W_so2 + so2_w_offset(lmax, E, m), call.T[m], m, lmax, E, K, N, n_steps, n_ct, false, call.maxima + 1,
-                       true);
+                       W_so2 + so2_w_offset(lmax, E, m), call.T[m], m, lmax, E, K, N, n_steps, n_ct, full, bmax + 1, true);
     EGNN_LAUNCH_CHECK(ctx, "so2_pack_kernel");
     const long rows_per_wg = 64L * SG_WAVES;
     const int n_row_blocks = (int)((n + rows_per_wg - 1) / rows_per_wg);
     const unsigned grid_x = (unsigned)(((n_row_blocks + 7) / 8) * 8 * n_ct);
     hipLaunchKernelGGL(so2_gemm_kernel, dim3(grid_x), dim3(SG_THREADS), SGH_LDS_BYTES, st, call.b.Y[m], n, N,
-                       call.b.ldY[m], call.T[m], n_steps, call.b.A[m], K, call.b.ldA[m], n_ct, n_row_blocks, call.maxima);
+                       call.b.ldY[m], call.T[m], n_steps, call.b.A[m], K, call.b.ldA[m], n_ct, n_row_blocks, bmax);
     EGNN_LAUNCH_CHECK(ctx, "so2_gemm_kernel");
-  }
-  {
-    const long per = (n + SO2_DWE_CHUNKS - 1) / SO2_DWE_CHUNKS;
-    const int chunks = (int)((n + per - 1) / per);
-    hipLaunchKernelGGL(so2_dwe_kernel, dim3(chunks), dim3(256), 0, st, rd, call.b.A[0], call.b.ldA[0], (lmax + 1) * 2 * E, n,
-                       per, ctx->log2_channels, n_rbf, ctx->desc.r_cut, w.dwe);
-    EGNN_LAUNCH_CHECK(ctx, "so2_dwe_kernel");
-    if ((rc = egnn_launch_reduce_partials(ctx, w.dwe, chunks, (long)E * n_rbf, dW_e, 1.0f, st))) return rc;
   }
   if (g->n_owned > 0) {
     const int per_xcd = (g->n_owned + 7) / 8;
-#define DX(L)                                                                                                       \
-  hipLaunchKernelGGL(so2_dx_kernel<L>, dim3(per_xcd * 8), dim3(256), 0, st, g->row_ptr, rd, call.b, w.rows, w.dxd,   \
-                     g->n_owned, ctx->log2_channels, per_xcd)
-    SO2_BY_LMAX(DX)
+#define DX(L)                                                                                                        \
+  do {                                                                                                               \
+    if (full)                                                                                                        \
+      hipLaunchKernelGGL((so2_dx_kernel<L, true>), dim3(per_xcd * 8), dim3(256), 0, st, g->row_ptr, rd, call.b,      \
+                         w.rows, w.dxd, dT, dT_add, g->n_owned, ctx->log2_channels, per_xcd);                        \
+    else                                                                                                             \
+      hipLaunchKernelGGL((so2_dx_kernel<L, false>), dim3(per_xcd * 8), dim3(256), 0, st, g->row_ptr, rd, call.b,     \
+                         w.rows, w.dxd, dT, dT_add, g->n_owned, ctx->log2_channels, per_xcd);                        \
+  } while (0)
+    SO2_BY_LMAX(lmax, DX)
 #undef DX
     EGNN_LAUNCH_CHECK(ctx, "so2_dx_kernel");
   }
-#undef SO2_BY_LMAX
   if ((rc = egnn_launch_segsum_rows(ctx, w.rows, col_ptr, perm, dx, g->n_total, D * E, st))) return rc;
   const long n_own = (long)g->n_owned * D * E;
   if (n_own > 0) {
@@ -1178,4 +1270,246 @@ extern "C" int egnn_so2_message_sum_backward(egnn_ctx* ctx, const egnn_graph* g,
     EGNN_LAUNCH_CHECK(ctx, "so2_add_kernel");
   }
   return EGNN_OK;
+}
+
+static int so2_backward_check(egnn_ctx* ctx, const egnn_graph* g, const void* ws, size_t ws_bytes, bool full,
+                              const char* who) {
+  int rc = so2_check(ctx, g, ws, ws_bytes, full, who);
+  if (rc) return rc;
+  if (ctx->desc.channels > 128 || ctx->desc.n_rbf > 32)
+    return egnn_fail(ctx, EGNN_EINVAL, std::string(who) + ": needs <= 128 channels and <= 32 radial bases");
+  if (ws_bytes < so2_bwd_ws(ctx, g->n_edges, g->n_owned, full, false, nullptr, nullptr))
+    return egnn_fail(ctx, EGNN_EWS, std::string(who) + ": workspace too small");
+  return EGNN_OK;
+}
+
+extern "C" int egnn_so2_message_sum_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr,
+                                             const int32_t* perm, const float* pos, const float box[3], const float* x,
+                                             const float* W_e, const float* W_so2, const float* da, float* dx,
+                                             float* dW_e, float* dW_so2, void* ws, size_t ws_bytes, void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  if (!pos || !box || !x || !W_e || !W_so2 || !dW_e || !dW_so2 || !col_ptr)
+    return egnn_fail(ctx, EGNN_EINVAL, "so2_message_sum_backward: null pointer");
+  int rc = so2_backward_check(ctx, g, ws, ws_bytes, false, "so2_message_sum_backward");
+  if (rc) return rc;
+  if ((g->n_total > 0 && !dx) || (g->n_owned > 0 && !da) || (g->n_edges > 0 && !perm))
+    return egnn_fail(ctx, EGNN_EINVAL, "so2_message_sum_backward: null pointer");
+  hipStream_t st = (hipStream_t)stream;
+  const int lmax = ctx->desc.lmax, E = ctx->desc.channels, D = (lmax + 1) * (lmax + 1), n_rbf = ctx->desc.n_rbf;
+  const long n = g->n_edges;
+  if (n == 0) {
+    // no message: every gradient is zero (a float zero is the integer zero)
+    if ((rc = egnn_launch_fill_int(ctx, (int*)dx, (long)g->n_total * D * E, 0, st))) return rc;
+    if ((rc = egnn_launch_fill_int(ctx, (int*)dW_e, (long)E * n_rbf, 0, st))) return rc;
+    return egnn_launch_fill_int(ctx, (int*)dW_so2, (long)so2_w_offset(lmax, E, lmax + 1), 0, st);
+  }
+  So2Call call;
+  if ((rc = so2_transform(ctx, g, pos, box, x, W_e, false, W_so2, ws, &call, st, false))) return rc;
+  So2Bwd w;
+  so2_bwd_ws(ctx, n, g->n_owned, false, true, (char*)ws, &w);
+  const So2Grad grad = {da, false, 1.0f / sqrtf(ctx->desc.agg_norm), nullptr, nullptr, nullptr};
+  if ((rc = so2_backward_tail(ctx, g, col_ptr, perm, false, W_so2, grad, call, w, dx, dW_so2, nullptr, nullptr, st)))
+    return rc;
+  // (the edge columns of dA_0 are still in place: the rotation back reads the node columns only)
+  const long per = (n + SO2_DWE_CHUNKS - 1) / SO2_DWE_CHUNKS;
+  const int chunks = (int)((n + per - 1) / per);
+  hipLaunchKernelGGL(so2_dwe_kernel, dim3(chunks), dim3(256), 0, st, reinterpret_cast<const float4*>(call.rhat_d),
+                     call.b.A[0], call.b.ldA[0], (lmax + 1) * 2 * E, n, per, ctx->log2_channels, n_rbf, ctx->desc.r_cut,
+                     w.dwe);
+  EGNN_LAUNCH_CHECK(ctx, "so2_dwe_kernel");
+  return egnn_launch_reduce_partials(ctx, w.dwe, chunks, (long)E * n_rbf, dW_e, 1.0f, st);
+}
+
+extern "C" int egnn_so2_edge_block_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr,
+                                            const int32_t* perm, const float* pos, const float box[3], const float* x,
+                                            const float* T_edge_in, const float* W_so2, const float* dT_out, float* dx,
+                                            float* dT_in, float* dW_so2, void* ws, size_t ws_bytes, void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  if (!pos || !box || !x || !W_so2 || !dW_so2 || !col_ptr)
+    return egnn_fail(ctx, EGNN_EINVAL, "so2_edge_block_backward: null pointer");
+  int rc = so2_backward_check(ctx, g, ws, ws_bytes, true, "so2_edge_block_backward");
+  if (rc) return rc;
+  if ((g->n_total > 0 && !dx) || (g->n_edges > 0 && (!perm || !T_edge_in || !dT_out || !dT_in)))
+    return egnn_fail(ctx, EGNN_EINVAL, "so2_edge_block_backward: null pointer");
+  hipStream_t st = (hipStream_t)stream;
+  const int lmax = ctx->desc.lmax, E = ctx->desc.channels, D = (lmax + 1) * (lmax + 1);
+  const long n = g->n_edges;
+  if (n == 0) {
+    if ((rc = egnn_launch_fill_int(ctx, (int*)dx, (long)g->n_total * D * E, 0, st))) return rc;
+    return egnn_launch_fill_int(ctx, (int*)dW_so2, (long)so2_w_offset(lmax, E, lmax + 1), 0, st);
+  }
+  So2Call call;
+  if ((rc = so2_transform(ctx, g, pos, box, x, T_edge_in, true, W_so2, ws, &call, st, false))) return rc;
+  So2Bwd w;
+  so2_bwd_ws(ctx, n, g->n_owned, true, true, (char*)ws, &w);
+  // T' = T + f_c y: the message term has gradient f_c dT', the identity term passes dT' on (added by so2_dx_kernel)
+  const So2Grad grad = {dT_out, true, 1.0f, nullptr, nullptr, nullptr};
+  return so2_backward_tail(ctx, g, col_ptr, perm, true, W_so2, grad, call, w, dx, dW_so2, dT_in, dT_out, st);
+}
+
+extern "C" int egnn_so2_node_block_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr,
+                                            const int32_t* perm, const float* pos, const float box[3], const float* x,
+                                            const float* T_edge, const float* W_so2, const float* w_att, const float* da,
+                                            float* dx, float* dT_edge, float* dW_so2, float* dw_att, void* ws,
+                                            size_t ws_bytes, void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  if (!pos || !box || !x || !W_so2 || !w_att || !dW_so2 || !dw_att || !col_ptr)
+    return egnn_fail(ctx, EGNN_EINVAL, "so2_node_block_backward: null pointer");
+  int rc = so2_backward_check(ctx, g, ws, ws_bytes, true, "so2_node_block_backward");
+  if (rc) return rc;
+  if ((g->n_total > 0 && !dx) || (g->n_owned > 0 && !da) || (g->n_edges > 0 && (!perm || !T_edge || !dT_edge)))
+    return egnn_fail(ctx, EGNN_EINVAL, "so2_node_block_backward: null pointer");
+  hipStream_t st = (hipStream_t)stream;
+  const int lmax = ctx->desc.lmax, E = ctx->desc.channels, D = (lmax + 1) * (lmax + 1);
+  const long n = g->n_edges;
+  if (n == 0) {
+    if ((rc = egnn_launch_fill_int(ctx, (int*)dx, (long)g->n_total * D * E, 0, st))) return rc;
+    if ((rc = egnn_launch_fill_int(ctx, (int*)dw_att, E, 0, st))) return rc;
+    return egnn_launch_fill_int(ctx, (int*)dW_so2, (long)so2_w_offset(lmax, E, lmax + 1), 0, st);
+  }
+  // the forward pass up to the attention weights: Y_m and alpha in the workspace
+  So2Call call;
+  if ((rc = so2_transform(ctx, g, pos, box, x, T_edge, true, W_so2, ws, &call, st))) return rc;
+  hipLaunchKernelGGL(so2_attention_kernel, dim3((g->n_owned + 3) / 4), dim3(256), 0, st, g->row_ptr, call.b.Y[0],
+                     call.b.ldY[0], w_att, call.alpha, g->n_owned, E);
+  EGNN_LAUNCH_CHECK(ctx, "so2_attention_kernel");
+  So2Bwd w;
+  so2_bwd_ws(ctx, n, g->n_owned, true, true, (char*)ws, &w);
+  const float4* rd = reinterpret_cast<const float4*>(call.rhat_d);
+#define ATT(L)                                                                                                     \
+  hipLaunchKernelGGL(so2_attention_adjoint_kernel<L>, dim3(g->n_owned), dim3(256), 0, st, g->row_ptr, rd, call.b,  \
+                     call.alpha, da, w.tds, w.dwatt, g->n_owned, ctx->log2_channels, ctx->desc.r_cut)
+  SO2_BY_LMAX(lmax, ATT)
+#undef ATT
+  EGNN_LAUNCH_CHECK(ctx, "so2_attention_adjoint_kernel");
+  if ((rc = egnn_launch_reduce_partials(ctx, w.dwatt, g->n_owned, (long)E, dw_att, 1.0f, st))) return rc;
+  const So2Grad grad = {da, false, 1.0f, call.alpha, w.tds, w_att};
+  return so2_backward_tail(ctx, g, col_ptr, perm, true, W_so2, grad, call, w, dx, dW_so2, dT_edge, nullptr, st);
+}
+
+// ---------------------------------------------------------------------------------------------- gate, reverse pass
+// One workgroup per node.  With g_l = sigmoid(W_g[l-1] x0):  dx_l = dy_l g_l;  dz_l[c] = g_l (1 - g_l) sum_m dy_l[m][c]
+// x_l[m][c] (kept in dz [n][lmax][E] for the weight gradient);  dx0 = dy0 SiLU'(x0) + sum_l W_g[l-1]^T dz_l.
+__global__ __launch_bounds__(256) void so2_gate_backward_kernel(const float* __restrict__ x, const float* __restrict__ W_g,
+                                                                const float* __restrict__ dy, float* __restrict__ dx,
+                                                                float* __restrict__ dz, int lmax, int log2E) {
+  __shared__ float s_x0[128];
+  __shared__ float s_gate[4 * 128];
+  __shared__ float s_dz[4 * 128];
+  const int E = 1 << log2E, D = (lmax + 1) * (lmax + 1), tid = threadIdx.x;
+  const float* xi = x + (((size_t)blockIdx.x * D) << log2E);
+  const float* dyi = dy + (((size_t)blockIdx.x * D) << log2E);
+  float* dxi = dx + (((size_t)blockIdx.x * D) << log2E);
+  if (tid < E) s_x0[tid] = xi[tid];
+  __syncthreads();
+  for (int t = tid; t < (lmax << log2E); t += 256) {
+    const float* wrow = W_g + ((size_t)t << log2E);     // row (l-1) * E + c
+    float sc = 0.0f;
+    for (int cc = 0; cc < E; ++cc) sc += wrow[cc] * s_x0[cc];
+    const float gt = 1.0f / (1.0f + __expf(-sc));
+    const int l = (t >> log2E) + 1, c = t & (E - 1);
+    float dot = 0.0f;
+    for (int q = l * l; q < (l + 1) * (l + 1); ++q) dot += dyi[(q << log2E) + c] * xi[(q << log2E) + c];
+    const float v = dot * gt * (1.0f - gt);
+    s_gate[t] = gt;
+    s_dz[t] = v;
+    dz[(((size_t)blockIdx.x * lmax) << log2E) + t] = v;
+  }
+  __syncthreads();
+  for (int idx = tid; idx < (D << log2E); idx += 256) {
+    const int q = idx >> log2E, c = idx & (E - 1);
+    if (q == 0) {
+      const float v = xi[idx];
+      const float sg = 1.0f / (1.0f + __expf(-v));
+      float sum = dyi[idx] * (sg * (1.0f + v * (1.0f - sg)));
+      for (int t = 0; t < (lmax << log2E); ++t) sum += W_g[((size_t)t << log2E) + c] * s_dz[t];
+      dxi[idx] = sum;
+    } else {
+      int l = 1;
+      while ((l + 1) * (l + 1) <= q) ++l;
+      dxi[idx] = dyi[idx] * s_gate[((l - 1) << log2E) + c];
+    }
+  }
+}
+
+// partial[chunk][l-1][c][c'] = sum over the nodes n of the chunk of dz[n][l-1][c] x[n][L = 0][c'].  grid = (chunks, lmax);
+// a thread owns the outputs o = tid + 256 s (c' = o mod E: neighbouring threads, neighbouring columns).
+#define GATE_WGRAD_CHUNKS 64
+#define GATE_WGRAD_BATCH 8
+__global__ __launch_bounds__(256) void so2_gate_wgrad_kernel(const float* __restrict__ dz, const float* __restrict__ x,
+                                                             float* __restrict__ partial, int n_nodes, int per_chunk,
+                                                             int lmax, int D, int log2E) {
+  __shared__ float s_dz[GATE_WGRAD_BATCH * 128];
+  __shared__ float s_x0[GATE_WGRAD_BATCH * 128];
+  const int E = 1 << log2E, l1 = blockIdx.y, tid = threadIdx.x;
+  const int n_begin = blockIdx.x * per_chunk;
+  const int n_end = n_begin + per_chunk < n_nodes ? n_begin + per_chunk : n_nodes;
+  float acc[64];     // E * E <= 128 * 128 = 64 * 256
+#pragma unroll
+  for (int s = 0; s < 64; ++s) acc[s] = 0.0f;
+  for (int n0 = n_begin; n0 < n_end; n0 += GATE_WGRAD_BATCH) {
+    __syncthreads();
+    for (int i = tid; i < (GATE_WGRAD_BATCH << log2E); i += 256) {
+      const int nn = n0 + (i >> log2E), c = i & (E - 1);
+      const bool ok = nn < n_end;
+      s_dz[i] = ok ? dz[((((size_t)nn * lmax) + l1) << log2E) + c] : 0.0f;
+      s_x0[i] = ok ? x[(((size_t)nn * D) << log2E) + c] : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < 64; ++s) {
+      const int o = tid + 256 * s;
+      if (o < (E << log2E)) {
+        const int c = o >> log2E, cp = o & (E - 1);
+        float sum = acc[s];
+#pragma unroll
+        for (int b = 0; b < GATE_WGRAD_BATCH; ++b) sum += s_dz[(b << log2E) + c] * s_x0[(b << log2E) + cp];
+        acc[s] = sum;
+      }
+    }
+  }
+  float* out = partial + (((size_t)blockIdx.x * lmax + l1) << (2 * log2E));
+#pragma unroll
+  for (int s = 0; s < 64; ++s) {
+    const int o = tid + 256 * s;
+    if (o < (E << log2E)) out[o] = acc[s];
+  }
+}
+
+static size_t so2_gate_bwd_ws(const egnn_ctx* ctx, int32_t n_nodes) {
+  const size_t E = ctx->desc.channels, lmax = ctx->desc.lmax;
+  return so2_a256((size_t)n_nodes * lmax * E * sizeof(float)) + so2_a256((size_t)GATE_WGRAD_CHUNKS * lmax * E * E * sizeof(float));
+}
+
+extern "C" int egnn_gate_backward_workspace_bytes(const egnn_ctx* ctx, int32_t n_nodes, size_t* bytes) {
+  if (!ctx || !bytes || n_nodes < 0) return EGNN_EINVAL;
+  *bytes = so2_gate_bwd_ws(ctx, n_nodes) + 256;
+  return EGNN_OK;
+}
+
+extern "C" int egnn_gate_backward(egnn_ctx* ctx, const float* x, const float* W_g, const float* dy, float* dx, float* dW_g,
+                                  int32_t n_nodes, void* ws, size_t ws_bytes, void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  const int lmax = ctx->desc.lmax, E = ctx->desc.channels;
+  if (n_nodes < 0 || (n_nodes > 0 && (!x || !dy || !dx)) || (lmax > 0 && (!W_g || !dW_g)))
+    return egnn_fail(ctx, EGNN_EINVAL, "gate_backward: bad argument");
+  if (E > 128 || lmax > 4) return egnn_fail(ctx, EGNN_EINVAL, "gate_backward: unsupported shape");
+  if (lmax > 0 && (!ws || ((uintptr_t)ws & 255) != 0 || ws_bytes < so2_gate_bwd_ws(ctx, n_nodes)))
+    return egnn_fail(ctx, EGNN_EWS, "gate_backward: workspace missing, misaligned or too small");
+  hipStream_t st = (hipStream_t)stream;
+  const long n_w = (long)lmax * E * E;
+  if (n_nodes == 0) return egnn_launch_fill_int(ctx, (int*)dW_g, n_w, 0, st);
+  float* dz = (float*)ws;
+  float* partial = (float*)((char*)ws + so2_a256((size_t)n_nodes * lmax * E * sizeof(float)));
+  hipLaunchKernelGGL(so2_gate_backward_kernel, dim3(n_nodes), dim3(256), 0, st, x, W_g, dy, dx, dz, lmax,
+                     ctx->log2_channels);
+  EGNN_LAUNCH_CHECK(ctx, "so2_gate_backward_kernel");
+  if (lmax == 0) return EGNN_OK;
+  int chunks = n_nodes < GATE_WGRAD_CHUNKS ? n_nodes : GATE_WGRAD_CHUNKS;
+  const int per = (n_nodes + chunks - 1) / chunks;
+  chunks = (n_nodes + per - 1) / per;
+  hipLaunchKernelGGL(so2_gate_wgrad_kernel, dim3(chunks, lmax), dim3(256), 0, st, dz, x, partial, n_nodes, per, lmax,
+                     (lmax + 1) * (lmax + 1), ctx->log2_channels);
+  EGNN_LAUNCH_CHECK(ctx, "so2_gate_wgrad_kernel");
+  return egnn_launch_reduce_partials(ctx, partial, chunks, n_w, dW_g, 1.0f, st);
 }
