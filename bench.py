@@ -454,8 +454,21 @@ def run_config(args, index, extras):
         t_node = timed(lambda: m.egnn_so2_node_block(graph, pos, w.box, xb, T_edge, Wn, w_att, ws3, out=x_out[0]), 3)
         t_gate = timed(lambda: m.egnn_gate(x_out[0], W_g, out=x_out[1]), 3)
         t_edge = timed(lambda: m.egnn_so2_edge_block(graph, pos, w.box, xb, T_edge, Wed, ws3, out=T_edge), 3)
+        # their reverse passes
+        ws3b = torch.empty(max(m.egnn_so2_blocks_backward_workspace_bytes(n_edges, w.n_owned),
+                               m.egnn_backward_workspace_bytes(n_edges, w.n_owned, w.n_total)),
+                           dtype=torch.uint8, device="cuda")
+        cp3, pm3 = m.egnn_graph_transpose(graph, ws3b)
+        da3 = torch.ones((w.n_owned, (L_ + 1) ** 2, E_), dtype=torch.float32, device="cuda")
+        dT3 = torch.ones_like(T_edge)
+        t_node_b = timed(lambda: m.egnn_so2_node_block_backward(graph, cp3, pm3, pos, w.box, xb, T_edge, Wn, w_att, da3, ws3b), 3)
+        t_edge_b = timed(lambda: m.egnn_so2_edge_block_backward(graph, cp3, pm3, pos, w.box, xb, T_edge, Wed, dT3, ws3b, dT_in=dT3), 3)
+        t_gate_b = timed(lambda: m.egnn_gate_backward(x_out[0], W_g, x_out[1]), 3)
+        del ws3b, cp3, pm3, da3, dT3
         macs_full = sum((1 if q == 0 else 4) * ((L_ + 1 - q) * E_) * ((L_ + 1 - q) * 3 * E_) for q in range(L_ + 1))
         so2["full_content"] = dict(node_block_ms=t_node, gate_ms=t_gate, edge_block_ms=t_edge,
+                                   node_block_backward_ms=t_node_b, gate_backward_ms=t_gate_b,
+                                   edge_block_backward_ms=t_edge_b,
                                    layer_ms=t_node + t_gate + t_edge,
                                    messages_per_s=2 * n_edges / (t_node + t_edge) * 1e3,
                                    floats_per_message=3 * (L_ + 1) ** 2 * E_, flop_per_message=2 * macs_full,

@@ -344,12 +344,15 @@ def so2_edge_block_backward(graph, pos, box, x, T_edge, W0, Wr, Wi, lmax, E, r_c
     return dx, dT_in, dW0, dWr, dWi
 
 
-def so2_node_block_backward(graph, pos, box, x, T_edge, W0, Wr, Wi, w_att, lmax, E, r_cut, da, slope=0.2):
+def so2_node_block_backward(graph, pos, box, x, T_edge, W0, Wr, Wi, w_att, lmax, E, r_cut, da, slope=0.2,
+                            near_kink=None, kink_eps=0.0):
     """Adjoint of so2_node_block: from da [n_owned][(lmax+1)^2][E] returns (dx, dT_edge, dW0, [dWr_m], [dWi_m], dw_att).
     Per destination node j with incoming edges k: a_j = sum_k alpha_k f_c,k y_k, alpha = softmax(s), s_k = w_att .
     LeakyReLU(y_k[L = 0]).  Backwards: t_k = f_c,k <da_j, y_k> is the gradient of alpha_k; the softmax gives
     ds_k = alpha_k (t_k - sum_k' alpha_k' t_k'); the score gives dw_att += ds_k LeakyReLU(y0_k) and
-    gY_k[L = 0] += ds_k w_att LeakyReLU'(y0_k); the weighted sum gives gY_k += alpha_k f_c,k da_j."""
+    gY_k[L = 0] += ds_k w_att LeakyReLU'(y0_k); the weighted sum gives gY_k += alpha_k f_c,k da_j.
+    near_kink: if a list is given, the ids of the edges that have a score input |y0_k[c]| < kink_eps are appended to it
+    (LeakyReLU' jumps at zero: there a comparison in lower precision may legitimately take the other branch)."""
     src, dst, shift, row_ptr = graph
     x = np.asarray(x, F64)
     da = np.asarray(da, F64)
@@ -374,6 +377,8 @@ def so2_node_block_backward(graph, pos, box, x, T_edge, W0, Wr, Wi, w_att, lmax,
         fc = O.envelope(np.sqrt(np.einsum("ka,ka->k", r, r)), r_cut)
         t = fc * np.einsum("ac,kac->k", da[j], Y)
         ds = alpha * (t - np.dot(alpha, t))
+        if near_kink is not None:
+            near_kink.extend((k0 + np.nonzero((np.abs(y0) < kink_eps).any(axis=1))[0]).tolist())
         act = np.where(y0 > 0, y0, slope * y0)
         dw_att += ds @ act
         gY = (alpha * fc)[:, None, None] * da[j][None, :, :]

@@ -13,6 +13,7 @@ equal the oracle's own composite calls.
     python tests/golden/make_golden.py 3 4 5
     python tests/golden/make_golden.py so2:3 so2:4      (SO(2) message sums at sampled nodes)
     python tests/golden/make_golden.py so2bwd:3         (adjoint of the SO(2) message sum: weight gradients, rows of dx)
+    python tests/golden/make_golden.py blocksbwd:3      (adjoints of the node block and of the edge block)
     python tests/golden/make_golden.py w16:3 w16:4      (first layer and readout with half-precision path weights)
     python tests/golden/make_golden.py blocks:3 blocks:4  (node block and edge block with full message content)
 """
@@ -21,7 +22,13 @@ import sys
 import time
 from concurrent.futures import ProcessPoolExecutor
 
-import numpy as np
+if __name__ == "__main__":
+    # one BLAS thread per worker process: the pool already uses every core, and oversubscribed BLAS threads make the
+    # many small products of the per-node loops an order of magnitude slower
+    for _v in ("OMP_NUM_THREADS", "OPENBLAS_NUM_THREADS", "MKL_NUM_THREADS"):
+        os.environ.setdefault(_v, "1")
+
+import numpy as np                                       # noqa: E402
 
 ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 sys.path.insert(0, ROOT)
@@ -218,6 +225,88 @@ def make_blocks(index, pool_size):
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"config{index}_so2_blocks_samples.npz")
     np.savez_compressed(path, nodes=nodes, edges=edges, a_rows=a_rows, T_rows=T_rows, n_edges=len(g[0]))
     print(f"config {index} blocks: wrote {path}, max|a| {np.abs(a_rows).max():.4f}, {time.time() - t0:.0f} s", flush=True)
+
+
+def _blocks_backward_nodes(j_range):
+    """Destination nodes j_range of the node block's adjoint (a sum over destination nodes)."""
+    from oracle import so2_oracle as S
+    w, g, x, T, Wn, w_att, da, edges = (_state[k] for k in ("w", "g", "x", "T", "Wn", "w_att", "da", "edges"))
+    j0, j1 = j_range
+    src, dst, shift, row_ptr = g
+    k0, k1 = int(row_ptr[j0]), int(row_ptr[j1])
+    sub = (src[k0:k1], dst[k0:k1], shift[k0:k1], row_ptr[j0:j1 + 1] - k0)
+    kink = []
+    dx, dT, dW0, dWr, dWi, dw_att = S.so2_node_block_backward(sub, w.pos, w.box, x, T[k0:k1], Wn[1], Wn[2], Wn[3], w_att,
+                                                              w.lmax, w.channels, w.r_cut, da[j0:j1], near_kink=kink,
+                                                              kink_eps=KINK_EPS)
+    pick = edges[(edges >= k0) & (edges < k1)]
+    return dx, (pick, dT[pick - k0]), [dW0] + list(dWr) + list(dWi) + [dw_att, np.asarray(kink, np.int64) + k0]
+
+
+# score inputs closer to zero than this are where an fp32 evaluation may take the other branch of LeakyReLU'
+KINK_EPS = 4e-6
+
+
+def _blocks_backward_edges(k_range):
+    """Edges k_range of the edge block's adjoint (a sum over the edges)."""
+    from oracle import so2_oracle as S
+    w, g, x, T, We, dT_out, edges = (_state[k] for k in ("w", "g", "x", "T", "We", "dT_out", "edges"))
+    k0, k1 = k_range
+    sub = (g[0][k0:k1], g[1][k0:k1], g[2][k0:k1], g[3])
+    dx, dT_in, dW0, dWr, dWi = S.so2_edge_block_backward(sub, w.pos, w.box, x, T[k0:k1], We[1], We[2], We[3], w.lmax,
+                                                         w.channels, w.r_cut, dT_out[k0:k1])
+    pick = edges[(edges >= k0) & (edges < k1)]
+    return dx, (pick, dT_in[pick - k0]), [dW0] + list(dWr) + list(dWi)
+
+
+def make_blocks_backward(index, pool_size):
+    """Adjoints of the node block and of the edge block of the full-size configuration ->
+    config{index}_so2_blocks_backward.npz: all weight gradients (and dw_att), dx at aimed nodes, the gradient of the
+    edge embeddings at aimed edges.  Inputs from tests/gpu_util.block_inputs; da and dT_out from tests/gpu_util
+    (so2_da, blocks_dT_out)."""
+    t0 = time.time()
+    w = synth.workload(index)
+    g, x, T, Wn, We, w_att = U.block_inputs(w)
+    n_e = len(g[0])
+    rng = np.random.default_rng([w.seed, 4246])
+    nodes = aimed_nodes(w, g, rng, w.n_total)
+    edges = aimed_edges(g, rng)
+    _state.update(w=w, g=g, x=x, T=T, Wn=Wn, We=We, w_att=w_att, da=U.so2_da(w), dT_out=U.blocks_dT_out(w, n_e), edges=edges)
+    out = dict(nodes=nodes, edges=edges, n_edges=n_e)
+    jobs_n = [(j0, min(w.n_owned, j0 + 32)) for j0 in range(0, w.n_owned, 32)]
+    jobs_e = [(k0, min(n_e, k0 + 8192)) for k0 in range(0, n_e, 8192)]
+    for tag, fn, jobs, names in (("node", _blocks_backward_nodes, jobs_n, ["dW0", "dWr", "dWi", "dw_att"]),
+                                 ("edge", _blocks_backward_edges, jobs_e, ["dW0", "dWr", "dWi"])):
+        dx, flat, kinks = None, None, []
+        dT_rows = np.zeros((len(edges),) + T.shape[1:])
+        with ProcessPoolExecutor(pool_size) as ex:
+            for part_dx, (pick, rows), part_w in ex.map(fn, jobs):
+                if tag == "node":
+                    kinks.append(part_w.pop())
+                if dx is None:
+                    dx, flat = part_dx, part_w
+                else:
+                    dx += part_dx
+                    for acc, v in zip(flat, part_w):
+                        acc += v
+                dT_rows[np.searchsorted(edges, pick)] = rows
+        out[f"{tag}_dx_rows"] = dx[nodes]
+        out[f"{tag}_dx_maxabs_l"] = maxabs_per_degree(dx, w.lmax)
+        out[f"{tag}_dT_rows"] = dT_rows
+        out[f"{tag}_dW0"] = flat[0]
+        for m in range(w.lmax):
+            out[f"{tag}_dWr{m + 1}"] = flat[1 + m]
+            out[f"{tag}_dWi{m + 1}"] = flat[1 + w.lmax + m]
+        if tag == "node":
+            out["node_dw_att"] = flat[-1]
+            # edges with a score input within KINK_EPS of zero, and the nodes whose rows of dx they reach
+            kink_edges = np.unique(np.concatenate(kinks)) if kinks else np.zeros(0, np.int64)
+            out["node_kink_edges"] = kink_edges
+            out["node_kink_nodes"] = np.unique(np.concatenate([g[0][kink_edges], g[1][kink_edges]])).astype(np.int64)
+        print(f"config {index} blocks backward: {tag} block done, {time.time() - t0:.0f} s", flush=True)
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"config{index}_so2_blocks_backward.npz")
+    np.savez_compressed(path, **out)
+    print(f"config {index} blocks backward: wrote {path}, {os.path.getsize(path) / 1e3:.0f} kB, {time.time() - t0:.0f} s", flush=True)
 
 
 def _w16_node(j):
@@ -427,6 +516,8 @@ if __name__ == "__main__":
             make_so2(int(a[4:]), procs)
         if a.startswith("so2bwd:"):
             make_so2_backward(int(a[7:]), procs)
+        if a.startswith("blocksbwd:"):
+            make_blocks_backward(int(a[10:]), procs)
         if a.startswith("w16:"):
             make_w16(int(a[4:]), procs)
         if a.startswith("blocks:"):

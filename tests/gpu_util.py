@@ -55,6 +55,12 @@ def so2_da(w):
     return rng.standard_normal(size=(w.n_owned, (w.lmax + 1) ** 2, w.channels), dtype=np.float32)
 
 
+def blocks_dT_out(w, n_edges):
+    """Seeded gradient with respect to the output of the edge block (input of both sides of the adjoint test)."""
+    rng = np.random.default_rng([w.seed if getattr(w, "seed", 0) else 0, 779])
+    return rng.standard_normal(size=(n_edges, (w.lmax + 1) ** 2, w.channels), dtype=np.float32)
+
+
 def oracle_forward(w, wt, g, agg_norm, with_readout=True, w_dtype=None):
     """Whole model on the oracle: species embedding, n_layers layers, readout.  Returns (xs, H).
     w_dtype: storage precision of the per-edge path weights (None: not rounded)."""
