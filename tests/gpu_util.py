@@ -61,6 +61,27 @@ def blocks_dT_out(w, n_edges):
     return rng.standard_normal(size=(n_edges, (w.lmax + 1) ** 2, w.channels), dtype=np.float32)
 
 
+def oracle_so2_layer_step(w, g, x, T, Wn, We, w_att, W_g, target_h, target_T, grads=True):
+    """One training step of a layer built from the SO(2) blocks, on the oracle: h = gate(node_block(x, T)),
+    T' = edge_block(x, T), loss = MSE(h, target_h) + MSE(T', target_T); with grads, the chain of the oracle's adjoints
+    back to x, T and every weight.  (A composition of oracle functions for the tests; the order of the steps is the one
+    of Sec. 3 "Message passing": node block, non-linearity, edge block.)"""
+    from oracle import so2_oracle as S
+    L, E = w.lmax, w.channels
+    a = S.so2_node_block(g, w.pos, w.box, x, T, Wn[1], Wn[2], Wn[3], w_att, L, E, w.r_cut)
+    h = S.gate(a, W_g, L)
+    T2 = S.so2_edge_block(g, w.pos, w.box, x, T, We[1], We[2], We[3], L, E, w.r_cut)
+    loss = O.loss_mse(h, target_h) + O.loss_mse(T2, target_T)
+    if not grads:
+        return loss
+    da, dW_g = S.gate_backward(a, W_g, L, O.loss_mse_backward(h, target_h))
+    dx1, dT1, n0, nr, ni, dw_att = S.so2_node_block_backward(g, w.pos, w.box, x, T, Wn[1], Wn[2], Wn[3], w_att, L, E,
+                                                            w.r_cut, da)
+    dx2, dT2, e0, er, ei = S.so2_edge_block_backward(g, w.pos, w.box, x, T, We[1], We[2], We[3], L, E, w.r_cut,
+                                                     O.loss_mse_backward(T2, target_T))
+    return loss, dict(x=dx1 + dx2, T=dT1 + dT2, Wn=(n0, nr, ni), We=(e0, er, ei), w_att=dw_att, W_g=dW_g)
+
+
 def oracle_forward(w, wt, g, agg_norm, with_readout=True, w_dtype=None):
     """Whole model on the oracle: species embedding, n_layers layers, readout.  Returns (xs, H).
     w_dtype: storage precision of the per-edge path weights (None: not rounded)."""

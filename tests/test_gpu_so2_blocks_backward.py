@@ -223,3 +223,43 @@ def test_blocks_backward_fullsize_config3(B):
     e_edge = compare("edge", dx, dT, dW, {})
     print(f"config 3: node block adjoint {t_node * 1e3:.2f} ms ({e_node:.2e}), edge block adjoint {t_edge * 1e3:.2f} ms "
           f"({e_edge:.2e})", flush=True)
+
+
+@pytest.mark.parametrize("case", ["config1", "halo"])
+def test_so2_layer_training_step(B, case):
+    """A training step of a layer built from the SO(2) blocks -- h = gate(node_block(x, T)), T' = edge_block(x, T),
+    loss = MSE(h, target) + MSE(T', target) -- run call by call through the C ABI (forward, loss, every reverse pass,
+    gradients added where two calls feed the same tensor) against the same chain on the oracle
+    (tests/gpu_util.oracle_so2_layer_step, pinned by central differences in tests/test_oracle_so2_blocks.py)."""
+    import torch
+    w = synth.workload(1) if case == "config1" else synth.small_cluster(110, 70, 3, 16, 6, 4.0, 190, False)
+    g, x, T, Wn, We, w_att, m, pos, graph, ws, col_ptr, perm = setup(B, w)
+    L, E = w.lmax, w.channels
+    rng = np.random.default_rng(21)
+    W_g = synth.normal(rng, (L, E, E), E ** -0.5)
+    th = rng.standard_normal((w.n_owned, (L + 1) ** 2, E)).astype(np.float32)
+    tT = rng.standard_normal(T.shape).astype(np.float32)
+    ref_loss, ref = U.oracle_so2_layer_step(w, g, x, T, Wn, We, w_att, W_g, th, tT)
+    xd, Td, Wnd, Wed = B.to_device(x), B.to_device(T), B.to_device(S.so2_pack(*Wn[1:])), B.to_device(S.so2_pack(*We[1:]))
+    wad, Wgd = B.to_device(w_att), B.to_device(W_g)
+    # forward
+    a = m.egnn_so2_node_block(graph, pos, w.box, xd, Td, Wnd, wad, ws)
+    h = m.egnn_gate(a, Wgd)
+    T2 = m.egnn_so2_edge_block(graph, pos, w.box, xd, Td, Wed, ws)
+    # loss and its gradients
+    lws = torch.empty(8 * (max(h.numel(), T2.numel()) // 4096 + 1) + 256, dtype=torch.uint8, device="cuda")
+    loss_h, dh = m.egnn_loss_mse(h, B.to_device(th), lws)
+    loss_T, dT2 = m.egnn_loss_mse(T2, B.to_device(tT), lws)
+    loss = float(loss_h.cpu()) + float(loss_T.cpu())
+    assert loss == pytest.approx(ref_loss, rel=1e-5)
+    # reverse passes
+    da, dW_g = m.egnn_gate_backward(a, Wgd, dh)
+    dx1, dT1, dWn, dw_att = m.egnn_so2_node_block_backward(graph, col_ptr, perm, pos, w.box, xd, Td, Wnd, wad, da, ws)
+    dx2, dTin, dWe = m.egnn_so2_edge_block_backward(graph, col_ptr, perm, pos, w.box, xd, Td, Wed, dT2, ws)
+    got = dict(x=(dx1 + dx2).cpu().numpy(), T=(dT1 + dTin).cpu().numpy(), w_att=dw_att.cpu().numpy(),
+               W_g=dW_g.cpu().numpy(), **weight_grads(dWn.cpu().numpy(), L, E, "n_"),
+               **weight_grads(dWe.cpu().numpy(), L, E, "e_"))
+    want = dict(x=ref["x"], T=ref["T"], w_att=ref["w_att"], W_g=ref["W_g"], **oracle_weight_grads(*ref["Wn"], prefix="n_"),
+                **oracle_weight_grads(*ref["We"], prefix="e_"))
+    worst = check(got, want, TOL)
+    print(f"{case}: loss {loss:.6f} (oracle {ref_loss:.6f}), worst gradient rel err {worst:.2e}", flush=True)

@@ -209,3 +209,38 @@ def test_gate_backward_is_the_derivative_of_the_forward():
     d0, _ = S.gate_backward(x0, np.zeros((0, E, E)), 0, np.ones_like(x0))
     s = 1 / (1 + np.exp(-x0))
     assert np.allclose(d0, s * (1 + x0 * (1 - s)), atol=1e-14)
+
+
+def test_layer_step_chain_is_the_derivative_of_the_loss():
+    """The chain of adjoints that the GPU training-step test compares against (tests/gpu_util.oracle_so2_layer_step):
+    central differences of the composed loss with respect to x, T and one weight of every group."""
+    from tests import gpu_util as U
+    lmax, E = 2, 4
+    w, g, x, T, W0, Wr, Wi, rng = _block_setup(lmax, E, 8)
+    Wn = (None, W0, Wr, Wi)
+    We = (None,) + tuple(S_ for S_ in (rng.standard_normal(W0.shape) / 6, [rng.standard_normal(a.shape) / 6 for a in Wr],
+                                       [rng.standard_normal(a.shape) / 6 for a in Wi]))
+    w_att = rng.standard_normal(E)
+    W_g = rng.standard_normal((lmax, E, E)) / 2
+    th = rng.standard_normal((w.n_owned, (lmax + 1) ** 2, E))
+    tT = rng.standard_normal(T.shape)
+    loss, gr = U.oracle_so2_layer_step(w, g, x, T, Wn, We, w_att, W_g, th, tT)
+    h = 1e-5
+
+    def fd(make):
+        return (U.oracle_so2_layer_step(*make(+h), grads=False) - U.oracle_so2_layer_step(*make(-h), grads=False)) / (2 * h)
+
+    v = rng.standard_normal(x.shape)
+    assert fd(lambda t: (w, g, x + t * v, T, Wn, We, w_att, W_g, th, tT)) == pytest.approx((gr["x"] * v).sum(), rel=1e-6)
+    v = rng.standard_normal(T.shape)
+    assert fd(lambda t: (w, g, x, T + t * v, Wn, We, w_att, W_g, th, tT)) == pytest.approx((gr["T"] * v).sum(), rel=1e-6)
+    v = rng.standard_normal(W0.shape)
+    assert fd(lambda t: (w, g, x, T, (None, W0 + t * v, Wr, Wi), We, w_att, W_g, th, tT)) == pytest.approx(
+        (gr["Wn"][0] * v).sum(), rel=1e-6)
+    v = rng.standard_normal(We[2][0].shape)
+    assert fd(lambda t: (w, g, x, T, Wn, (None, We[1], [We[2][0] + t * v] + list(We[2][1:]), We[3]), w_att, W_g, th,
+                         tT)) == pytest.approx((gr["We"][1][0] * v).sum(), rel=1e-6)
+    v = rng.standard_normal(E)
+    assert fd(lambda t: (w, g, x, T, Wn, We, w_att + t * v, W_g, th, tT)) == pytest.approx((gr["w_att"] * v).sum(), rel=1e-6)
+    v = rng.standard_normal(W_g.shape)
+    assert fd(lambda t: (w, g, x, T, Wn, We, w_att, W_g + t * v, th, tT)) == pytest.approx((gr["W_g"] * v).sum(), rel=1e-6)
