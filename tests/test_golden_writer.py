@@ -72,3 +72,58 @@ def test_aimed_samples_cover_the_rows_named():
     assert MG.maxabs_per_degree(x, 2).tolist() == [2.0, 0.0, 7.0]
     H = np.zeros((2, 4, 4)); H[1, 0, 3] = 5.0; H[0, 2, 0] = -3.0
     assert MG.maxabs_per_shell_block(H, [0, 1]).tolist() == [[0.0, 5.0], [3.0, 0.0]]
+
+
+def _sum_parts(parts):
+    total = None
+    for p in parts:
+        if total is None:
+            total = [np.array(v, dtype=np.float64, copy=True) for v in p]
+        else:
+            for acc, v in zip(total, p):
+                acc += v
+    return total
+
+
+def test_so2_backward_chunks_sum_to_the_oracle_adjoints():
+    """The writers of config3_so2_backward.npz and config3_so2_blocks_backward.npz split the adjoints over edge ranges
+    (message sum, edge block) and destination-node ranges (node block) and add the parts up: on config 1 the sums equal
+    the oracle's own calls over the whole graph."""
+    from oracle import so2_oracle as S
+    w, wt, g, agg = _config1()
+    L, E = w.lmax, w.channels
+    x = O.species_embed(wt["x0"], w.species, wt["table"])
+    Wso2 = synth.so2_weights(np.random.default_rng([w.seed, 777]), L, E, w.n_rbf)
+    da = U.so2_da(w)
+    n_e = len(g[0])
+    # message sum: edge ranges with a ragged last one
+    MG._state.update(w=w, g=g, x=x, Wso2=Wso2, agg=agg, da=da)
+    parts = [MG._so2_backward_chunk((k0, min(n_e, k0 + 500))) for k0 in range(0, n_e, 500)]
+    flat = _sum_parts([[p[0], p[1], p[2]] + list(p[3]) + list(p[4]) for p in parts])
+    ref = S.so2_message_sum_backward(g, w.pos, w.box, x, *Wso2, L, E, w.n_rbf, w.r_cut, agg, da)
+    ref_flat = [ref[0], ref[1], ref[2]] + list(ref[3]) + list(ref[4])
+    for a, b in zip(flat, ref_flat):
+        assert np.abs(a - b).max() <= 1e-12 * np.abs(b).max()
+    # the two blocks
+    gg, xb, T, Wn, We, w_att = U.block_inputs(w)
+    edges = MG.aimed_edges(g, np.random.default_rng(1))
+    dT_out = U.blocks_dT_out(w, n_e)
+    MG._state.update(w=w, g=g, x=xb, T=T, Wn=Wn, We=We, w_att=w_att, da=da, dT_out=dT_out, edges=edges)
+    node_parts = [MG._blocks_backward_nodes((j0, min(w.n_owned, j0 + 10))) for j0 in range(0, w.n_owned, 10)]
+    ref = S.so2_node_block_backward(g, w.pos, w.box, xb, T, Wn[1], Wn[2], Wn[3], w_att, L, E, w.r_cut, da)
+    dx = _sum_parts([[p[0]] for p in node_parts])[0]
+    assert np.abs(dx - ref[0]).max() <= 1e-12 * np.abs(ref[0]).max()
+    wsum = _sum_parts([p[2][:-1] for p in node_parts])          # (the last member lists the edges at the kink)
+    for a, b in zip(wsum, [ref[2]] + list(ref[3]) + list(ref[4]) + [ref[5]]):
+        assert np.abs(a - b).max() <= 1e-12 * np.abs(b).max()
+    for pick, rows in (p[1] for p in node_parts):
+        assert np.array_equal(rows, ref[1][pick])
+    assert sorted(np.concatenate([p[1][0] for p in node_parts]).tolist()) == edges.tolist()
+    edge_parts = [MG._blocks_backward_edges((k0, min(n_e, k0 + 500))) for k0 in range(0, n_e, 500)]
+    ref = S.so2_edge_block_backward(g, w.pos, w.box, xb, T, We[1], We[2], We[3], L, E, w.r_cut, dT_out)
+    dx = _sum_parts([[p[0]] for p in edge_parts])[0]
+    assert np.abs(dx - ref[0]).max() <= 1e-12 * np.abs(ref[0]).max()
+    for a, b in zip(_sum_parts([p[2] for p in edge_parts]), [ref[2]] + list(ref[3]) + list(ref[4])):
+        assert np.abs(a - b).max() <= 1e-12 * np.abs(b).max()
+    for pick, rows in (p[1] for p in edge_parts):
+        assert np.abs(rows - ref[1][pick]).max() <= 1e-13 * np.abs(ref[1]).max()
