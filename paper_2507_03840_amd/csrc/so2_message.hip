@@ -10,10 +10,11 @@
 // dense contraction shared by all edges, so it runs as five GEMMs, one per |m|:
 //   1. so2_gather_kernel   lane = (edge, channel): both node rows rotated into the bond frame in registers, written
 //                          m-major: A_0[k] = (x_{l,0} of both nodes for all l, then e_k), A_m[k] = [x_{+m} | x_{-m}];
-//   2. so2_pack_kernel     the weights of order m as one matrix B_m = [[Wr^T, Wi^T], [-Wi^T, Wr^T]], cut into bf16
-//                          pieces and stored in the operand order of the streaming GEMM (stream_gemm.h);
-//   3. so2_gemm_kernel     Y_m = A_m B_m on split-bf16 MFMA (six products per fp32 product), 448 edges x 64 columns per
-//                          workgroup, the 64-column tiles of an edge block running side by side;
+//   2. so2_pack_kernel     the weights of order m as one matrix B_m = [[Wr^T, Wi^T], [-Wi^T, Wr^T]], scaled and cut
+//                          into two half-precision pieces, stored in the operand order of the streaming GEMM
+//                          (stream_gemm.h);
+//   3. so2_gemmw_kernel    Y_m = A_m B_m on half-precision MFMA (three products per fp32 product), 256 edges x up to
+//                          192 columns per workgroup: a row of A is fetched and cut once for all its column blocks;
 //   4. so2_scatter_kernel  one workgroup per destination node, lane = (edge slot, channel): m-major rows of Y back to
 //                          (l, m) order, rotated back, times f_c, summed; slots added in fixed order (no atomics).
 #include <type_traits>
@@ -253,43 +254,70 @@ __global__ __launch_bounds__(256) void so2_pack_kernel(const float* __restrict__
 }
 
 // ---------------------------------------------------------------------------------------------- 3. GEMM
-// C[e][ct*64 + j] = sum_k A[e][k] B[k][ct*64 + j].  A workgroup = (block of 64 * SG_WAVES rows, 64-column tile ct);
-// the contraction itself is sg_contract of stream_gemm.h.
-// Workgroup ids go round-robin over the 8 XCDs, each with its own L2, so the id is decoded such that the column tiles
-// of one block of rows sit on the same XCD with consecutive dispatch slots: they read the same rows of A, once from
-// HBM and then from that L2.  A compute wave owns 64 rows; its 64 x 64 tile of A is fetched in memory order and turned
-// to operand order through a private LDS tile.
-__global__ __launch_bounds__(SG_THREADS) void so2_gemm_kernel(const float* __restrict__ A, long M, int K, int lda,
-                                                              const uint16_t* __restrict__ T, int n_steps,
-                                                              float* __restrict__ C, int N, int ldc, int n_ct,
-                                                              int n_row_blocks, const unsigned* __restrict__ maxima) {
+// C[e][n] = sum_k A[e][k] B[k][n] with wide column tiles (sghw_contract of stream_gemm.h): a workgroup = (block of
+// 32 * SG_WAVES rows, wide tile of NCB / 2 packed 64-column tiles); a wave owns 32 rows, whose 32 x 64 tile of A per
+// step is fetched in memory order, turned to operand order through a private LDS tile and cut into pieces once for
+// all column blocks.  Workgroup ids go round-robin over the 8 XCDs, each with its own L2, so the id is decoded such
+// that the wide tiles of one block of rows (there is more than one only beyond 192 columns) sit on the same XCD with
+// consecutive dispatch slots: they read the same rows of A, once from HBM and then from that L2.
+template <int NCB>
+__global__ __launch_bounds__(SG_THREADS) void so2_gemmw_kernel(const float* __restrict__ A, long M, int K, int lda,
+                                                               const uint16_t* __restrict__ T, int n_steps,
+                                                               float* __restrict__ C, int N, int ldc, int n_ct, int n_wt,
+                                                               int n_row_blocks, const unsigned* __restrict__ maxima) {
   extern __shared__ uint4 so2_smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
-  const int ct = idx % n_ct;
-  const int row_block = (idx / n_ct) * 8 + xcd;
+  const int wt = idx % n_wt;
+  const int row_block = (idx / n_wt) * 8 + xcd;
   if (row_block >= n_row_blocks) return;   // (whole workgroup: the grid is rounded up to a multiple of 8 row blocks)
-  const long e_base = ((long)row_block * SG_WAVES + wave) * 64;
-  // scalings of the two operands (maxima[0]: largest |A| written by the gather kernel, maxima[1]: largest weight)
+  const long e_base = ((long)row_block * SG_WAVES + wave) * 32;
+  const int ct0 = wt * (NCB / 2);
   const int ea = sgh_scale_exp(maxima[0]), eb = sgh_scale_exp(maxima[1]);
   const float a_scale = ldexpf(1.0f, ea), unscale = ldexpf(1.0f, -ea - eb);
-  float16v acc[2][2];
-  sgh_contract(A, M, K, reinterpret_cast<const uint4*>(T) + (long)ct * n_steps * (64 * 16), n_steps, so2_smem, e_base,
-               a_scale, acc, lda);
+  float16v acc[NCB];
+  const long tile_stride = (long)n_steps * (64 * 16);
+  sghw_contract<NCB>(A, M, K, lda, reinterpret_cast<const uint4*>(T) + (long)ct0 * tile_stride, tile_stride, n_ct - ct0,
+                     n_steps, so2_smem, e_base, a_scale, acc);
   const int m = lane & 31, hh = lane >> 5;
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb)
+  for (int cb = 0; cb < NCB; ++cb) {
+    const int col = ct0 * 64 + cb * 32 + m;
+    if (col < N) {
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
-      const int col = ct * 64 + cb * 32 + m;
-      if (col < N) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const long e = e_base + rb * 32 + 8 * (i >> 2) + 4 * hh + (i & 3);
-          if (e < M) C[(size_t)e * ldc + col] = unscale * acc[rb][cb][i];
-        }
+      for (int i = 0; i < 16; ++i) {
+        const long e = e_base + 8 * (i >> 2) + 4 * hh + (i & 3);
+        if (e < M) C[(size_t)e * ldc + col] = unscale * acc[cb][i];
       }
     }
+  }
+}
+
+// launches the wide-tile product: NCB from the number of 64-column tiles (at most 6 column blocks per wave)
+static int so2_launch_gemm(egnn_ctx* ctx, const float* A, long n, int K, int lda, const uint16_t* T, float* C, int N,
+                           int ldc, const unsigned* maxima, hipStream_t st) {
+  const int n_steps = (K + 63) / 64, n_ct = (N + 63) / 64;
+  const int n_wt = (n_ct + 2) / 3;                // wide tiles of at most three 64-column tiles, evenly filled
+  const int nt = (n_ct + n_wt - 1) / n_wt;
+  const long rows_per_wg = 32L * SG_WAVES;
+  const int n_row_blocks = (int)((n + rows_per_wg - 1) / rows_per_wg);
+  const unsigned grid_x = (unsigned)(((n_row_blocks + 7) / 8) * 8 * n_wt);
+#define SO2_GEMMW(NCB)                                                                                               \
+  do {                                                                                                               \
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(so2_gemmw_kernel<NCB>),                         \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)SGHW_LDS_BYTES(NCB));        \
+    if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(so2_gemmw_kernel)");                     \
+    hipLaunchKernelGGL(so2_gemmw_kernel<NCB>, dim3(grid_x), dim3(SG_THREADS), SGHW_LDS_BYTES(NCB), st, A, n, K, lda,  \
+                       T, n_steps, C, N, ldc, n_ct, n_wt, n_row_blocks, maxima);                                     \
+  } while (0)
+  switch (nt) {
+    case 1: SO2_GEMMW(2); break;
+    case 2: SO2_GEMMW(4); break;
+    default: SO2_GEMMW(6); break;
+  }
+#undef SO2_GEMMW
+  EGNN_LAUNCH_CHECK(ctx, "so2_gemmw_kernel");
+  return EGNN_OK;
 }
 
 // ---------------------------------------------------------------------------------------------- 4. scatter
@@ -549,10 +577,6 @@ static int so2_transform(egnn_ctx* ctx, const egnn_graph* g, const float* pos, c
     hipLaunchKernelGGL(so2_wmax_kernel, dim3(wg), dim3(256), 0, st, W_so2, n_w, call->maxima + 1);
     EGNN_LAUNCH_CHECK(ctx, "so2_wmax_kernel");
   }
-  const size_t lds = SGH_LDS_BYTES;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(so2_gemm_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(so2_gemm_kernel)");
   for (int m = 0; gemms && m <= lmax; ++m) {
     const int K = call->b.K[m], N = call->b.N[m], n_steps = so2_steps(K), n_ct = so2_tiles(N);
     const long total = (long)n_ct * n_steps * 64 * 32;
@@ -560,12 +584,9 @@ static int so2_transform(egnn_ctx* ctx, const egnn_graph* g, const float* pos, c
                        W_so2 + so2_w_offset(lmax, E, m), call->T[m], m, lmax, E, K, N, n_steps, n_ct, full, call->maxima + 1,
                        false);
     EGNN_LAUNCH_CHECK(ctx, "so2_pack_kernel");
-    const long rows_per_wg = 64L * SG_WAVES;
-    const int n_row_blocks = (int)((n + rows_per_wg - 1) / rows_per_wg);
-    const unsigned grid_x = (unsigned)(((n_row_blocks + 7) / 8) * 8 * n_ct);
-    hipLaunchKernelGGL(so2_gemm_kernel, dim3(grid_x), dim3(SG_THREADS), lds, st, call->b.A[m], n, K, call->b.ldA[m],
-                       call->T[m], n_steps, call->b.Y[m], N, call->b.ldY[m], n_ct, n_row_blocks, call->maxima);
-    EGNN_LAUNCH_CHECK(ctx, "so2_gemm_kernel");
+    if ((rc = so2_launch_gemm(ctx, call->b.A[m], n, K, call->b.ldA[m], call->T[m], call->b.Y[m], N, call->b.ldY[m],
+                              call->maxima, st)))
+      return rc;
   }
   return EGNN_OK;
 }
@@ -696,7 +717,7 @@ extern "C" int egnn_gate(egnn_ctx* ctx, const float* x, const float* W_g, float*
 //                              (v_mfma_f32_32x32x2_f32, both operands read in memory order: the contraction index is
 //                              the row index of both), partial sums per chunk of edges added in a fixed order;
 //      so2_unpack_wgrad_kernel dB_m = [[dWr^T, dWi^T], [-dWi^T, dWr^T]] folded back into the layout of the weights;
-//   4. so2_gemm_kernel         dA_m = dY_m B_m^T with the packed operand transposed, written over A_m;
+//   4. so2_gemmw_kernel        dA_m = dY_m B_m^T with the packed operand transposed, written over A_m;
 //   5. so2_dx_kernel           one workgroup per destination node: the two node parts of dA_m[k] rotated back to the
 //                              lab frame; the destination part is summed over the node's incoming edges, the source
 //                              part goes to a per-edge row that a segmented sum over the source-sorted index adds up;
@@ -1218,9 +1239,6 @@ static int so2_backward_tail(egnn_ctx* ctx, const egnn_graph* g, const int32_t* 
     hipLaunchKernelGGL(so2_wmax_kernel, dim3(wg), dim3(256), 0, st, W_so2, n_w, bmax + 1);
     EGNN_LAUNCH_CHECK(ctx, "so2_wmax_kernel");
   }
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(so2_gemm_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)SGH_LDS_BYTES);
-  if (e != hipSuccess) return egnn_check_hip(ctx, e, "hipFuncSetAttribute(so2_gemm_kernel)");
   for (int m = 0; m <= lmax; ++m) {
     const int K = call.b.K[m], N = call.b.N[m];
     int chunks;
@@ -1241,12 +1259,8 @@ static int so2_backward_tail(egnn_ctx* ctx, const egnn_graph* g, const int32_t* 
     hipLaunchKernelGGL(so2_pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                        W_so2 + so2_w_offset(lmax, E, m), call.T[m], m, lmax, E, K, N, n_steps, n_ct, full, bmax + 1, true);
     EGNN_LAUNCH_CHECK(ctx, "so2_pack_kernel");
-    const long rows_per_wg = 64L * SG_WAVES;
-    const int n_row_blocks = (int)((n + rows_per_wg - 1) / rows_per_wg);
-    const unsigned grid_x = (unsigned)(((n_row_blocks + 7) / 8) * 8 * n_ct);
-    hipLaunchKernelGGL(so2_gemm_kernel, dim3(grid_x), dim3(SG_THREADS), SGH_LDS_BYTES, st, call.b.Y[m], n, N,
-                       call.b.ldY[m], call.T[m], n_steps, call.b.A[m], K, call.b.ldA[m], n_ct, n_row_blocks, bmax);
-    EGNN_LAUNCH_CHECK(ctx, "so2_gemm_kernel");
+    if ((rc = so2_launch_gemm(ctx, call.b.Y[m], n, N, call.b.ldY[m], call.T[m], call.b.A[m], K, call.b.ldA[m], bmax, st)))
+      return rc;
   }
   if (g->n_owned > 0) {
     const int per_xcd = (g->n_owned + 7) / 8;

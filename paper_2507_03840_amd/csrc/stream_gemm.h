@@ -343,3 +343,105 @@ __device__ __forceinline__ void sgh_contract(const float* __restrict__ A, long M
     }
   }
 }
+
+// ---------------------------------------------------------------------------------------------------------------
+// The streaming contraction with wide column tiles: a wave owns one 32-row block of A and NCB column blocks of 32
+// (NCB = 2, 4 or 6: up to 192 columns; 8 would not fit the register file), so that a row of A is fetched, turned and cut into pieces once for all of
+// them.  With 64-column tiles every tile's workgroup fetched the rows again (from L2, at the same moment as its
+// neighbours) and cut them again.  acc[cb] = rows (e_base ..+31) x columns (32 cb ..+31) of the wide tile.
+// tsrc: packed blocks of the wide tile's first 64-column tile; the blocks of the next tiles follow at distances of
+// tile_stride uint4 (tiles past the last one are read from the last one: the caller does not store their columns).
+// The block of the small operand of a step (NCB / 2 tiles of 16 KB) is single-buffered in LDS: loaded into registers
+// during step s - 1, written between two barriers at the top of step s.  SG_WAVES waves per workgroup.
+// Dynamic LDS: SGHW_LDS_BYTES(NCB).
+#define SGHW_LDS_BYTES(NCB) ((size_t)((NCB) / 2) * 64 * SGH_BROW4 * sizeof(uint4) + (size_t)SG_WAVES * 32 * SG_AROW * sizeof(float))
+template <int NCB>
+__device__ __forceinline__ void sghw_contract(const float* __restrict__ A, long M, int K, int lda,
+                                              const uint4* __restrict__ tsrc, long tile_stride, int n_tiles_left,
+                                              int n_steps, uint4* smem, long e_base, float a_scale,
+                                              float16v (&acc)[NCB]) {
+  constexpr int NT = NCB / 2;
+  uint4* sB = smem;                                  // [NT * 64][SGH_BROW4]
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  float* sA = reinterpret_cast<float*>(sB + NT * 64 * SGH_BROW4) + (size_t)wave * 32 * SG_AROW;
+  const int m = lane & 31, hh = lane >> 5;
+  const int frow = lane >> 4, fcol = (lane & 15) * 4;
+  const float* fptr[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    long e0 = e_base + 4 * i + frow;
+    if (e0 >= M) e0 = M - 1;
+    fptr[i] = A + (size_t)e0 * lda;
+  }
+#pragma unroll
+  for (int b = 0; b < NCB; ++b)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[b][i] = 0.0f;
+  // the 64-column tiles of this wide tile (clamped to the last existing one)
+  const uint4* tile[NT];
+#pragma unroll
+  for (int c = 0; c < NT; ++c) tile[c] = tsrc + (long)(c < n_tiles_left ? c : n_tiles_left - 1) * tile_stride;
+  sg_u4 bnext[NT][2];
+#pragma unroll
+  for (int c = 0; c < NT; ++c)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) bnext[c][i] = *reinterpret_cast<const sg_u4*>(tile[c] + i * SG_THREADS + tid);
+  sg_f4 nxt[8];
+  sg_fetch8(nxt, fptr, fcol < K ? fcol : K - 4);
+  for (int s = 0; s < n_steps; ++s) {
+    rb_release_barrier();                            // every wave has finished reading the block of step s - 1
+#pragma unroll
+    for (int c = 0; c < NT; ++c)
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int u = i * SG_THREADS + tid, row = c * 64 + (u >> 4), c16 = u & 15;
+        *reinterpret_cast<sg_u4*>(sB + row * SGH_BROW4 + c16) = bnext[c][i];
+      }
+    rb_release_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    const int s_next = s + 1 < n_steps ? s + 1 : s;   // (the last step fetches itself again: no branch around loads)
+    const int n_next = s_next * 64 + fcol;
+    const int next_col = n_next < K ? n_next : K - 4;
+    sg_store8(sA + frow * SG_AROW + fcol, nxt);
+    sg_fetch8(nxt, fptr, next_col);
+#pragma unroll
+    for (int c = 0; c < NT; ++c)
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        bnext[c][i] = *reinterpret_cast<const sg_u4*>(tile[c] + (size_t)s_next * (64 * 16) + i * SG_THREADS + tid);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+    const float4* arow = reinterpret_cast<const float4*>(sA + m * SG_AROW + hh * 32);
+    const uint4* bbase = sB + hh * 4;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const float4 u = arow[2 * t], v = arow[2 * t + 1];
+      const float xv[8] = {u.x, u.y, u.z, u.w, v.x, v.y, v.z, v.w};
+      // the first pair of column blocks' pieces of the small operand are requested before A is cut, every further
+      // pair before the products of the pair in front of it: their LDS latency passes behind other work
+      uint4 b0[2], b1[2];
+      {
+        const uint4* brow0 = bbase + m * SGH_BROW4 + t;
+        const uint4* brow1 = brow0 + 32 * SGH_BROW4;
+        b0[0] = brow0[0]; b0[1] = brow0[8]; b1[0] = brow1[0]; b1[1] = brow1[8];
+      }
+      uint4 ah, al;
+      sgh_split8(xv, a_scale, ah, al);
+#pragma unroll
+      for (int cb = 0; cb < NCB; cb += 2) {
+        uint4 n0[2], n1[2];
+        if (cb + 2 < NCB) {
+          const uint4* brow0 = bbase + ((cb + 2) * 32 + m) * SGH_BROW4 + t;
+          const uint4* brow1 = brow0 + 32 * SGH_BROW4;
+          n0[0] = brow0[0]; n0[1] = brow0[8]; n1[0] = brow1[0]; n1[1] = brow1[8];
+        }
+        sgh_mma3x2(ah, al, b0, b1, acc[cb], acc[cb + 1]);
+        if (cb + 2 < NCB) { b0[0] = n0[0]; b0[1] = n0[1]; b1[0] = n1[0]; b1[1] = n1[1]; }
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_wave_barrier();   // reads of the tile are done before the next step overwrites it
+  }
+}
