@@ -105,6 +105,16 @@ def test_so2_backward_small(B, lmax, E, periodic, n, n_owned, r_cut):
         assert np.any(got["dW0"][:, edge & (l_in == 0)] != 0.0)
 
 
+@pytest.mark.parametrize("lmax,E,n_rbf", [(4, 8, 6), (2, 16, 32), (0, 128, 2), (4, 64, 20)])
+def test_so2_backward_corner_shapes(B, lmax, E, n_rbf):
+    """Operand widths that are not multiples of the tiles of the weight gradient (l_max 4 with 8 channels: 88 x 40),
+    the largest and smallest radial bases, the widest rows."""
+    w = synth.small_cluster(80, 55, lmax, E, n_rbf, 4.0, 70 + lmax, False)
+    got, want, n_e = run_case(B, w)
+    worst = check(got, want, TOL)
+    print(f"  lmax {lmax} E {E} n_rbf {n_rbf}: {n_e} edges, worst rel err {worst:.2e}", flush=True)
+
+
 @pytest.mark.parametrize("x_scale,w_scale,da_scale", [(1e-7, 1e5, 1.0), (3e4, 2e-6, 1e-9), (1e-10, 1e-8, 1e6), (5e6, 40.0, 1e4)])
 def test_so2_backward_operand_scales(B, x_scale, w_scale, da_scale):
     w = synth.small_cluster(100, 70, 3, 16, 6, 4.0, 58, False)
