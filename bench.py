@@ -413,6 +413,20 @@ def run_config(args, index, extras):
                        note="torch elementwise copy (1 GiB read + 1 GiB write) and fill (1 GiB write)")
     del a, b
 
+    # ---- S4 on half-precision weights, with the gathered features in fp32 and in half precision (stage calls, one
+    #      weight row per edge; the paper's runs keep embeddings in half precision and aggregate in fp32, Sec. 4.1) ----
+    s4_half = None
+    if extras and 8 <= w.channels <= 128:
+        graph = m.egnn_nlist(pos, w.n_owned, w.box, w.pbc)
+        rhat_d = m.egnn_edge_geometry(graph, pos, w.box)[0]
+        w16 = m.egnn_radial_weights_f16(0, rhat_d, layers[0]["W_r1"], layers[0]["W_r2"])
+        h16 = m.egnn_pack_rows(x0, torch.arange(w.n_total, dtype=torch.int32, device="cuda"), half=True)
+        t16 = timed(lambda: m.egnn_tp_segsum_f16(graph, rhat_d, x0, w16, out=x_out[0]), 10)
+        t16h = timed(lambda: m.egnn_tp_segsum_f16h(graph, rhat_d, h16, w16, out=x_out[0]), 10)
+        s4_half = dict(w_half_features_fp32_ms=t16, w_half_features_half_ms=t16h, rows="one weight row per edge",
+                       note="egnn_tp_segsum_f16 / egnn_tp_segsum_f16h: storage precision only, products and sums in fp32")
+        del w16, h16, rhat_d
+
     # ---- the message transform in its SO(2) form (dense per-m linear layers, 3E -> E), same graph and features ----
     so2 = None
     if extras and not args.no_so2 and w.channels >= 8:
@@ -640,6 +654,8 @@ def run_config(args, index, extras):
     }
     out["training_step"] = training
     out["w_fp16_storage"] = w_fp16
+    if s4_half is not None:
+        out["s4_half_precision_storage"] = s4_half
     out["s3_s4_fused_in_registers"] = fused_lane
     out["hbm_calibration"] = calibration
     if so2 is not None:

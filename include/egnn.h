@@ -194,6 +194,11 @@ int egnn_radial_weights_f16(egnn_ctx* ctx, int which, const float* rhat_d, int64
                             void* stream);
 int egnn_tp_segsum_f16(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, const float* h,
                        const uint32_t* w16, float* a, void* stream);
+/* The same with the gathered features in half precision as well (Sec. 4.1: the paper's runs keep embeddings and
+ * communication buffers in half precision and aggregate in fp32): h16 [n_total][(lmax+1)^2][channels] IEEE half
+ * precision, e.g. written by egnn_pack_rows with half != 0 and the identity index list.  Sums and output in fp32. */
+int egnn_tp_segsum_f16h(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, const uint16_t* h16,
+                        const uint32_t* w16, float* a, void* stream);
 
 /* ---- S5  per-degree channel mix (the per-l linear of Fig. 2(d)) ----
  * y[n][(l,m)][c] = sum_c' W1[l][c][c'] x1[n][(l,m)][c'] (+ sum_c' W2[l][c][c'] x2[n][(l,m)][c'] if W2 != NULL). */

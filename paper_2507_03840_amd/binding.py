@@ -22,7 +22,7 @@ SYMBOLS = [
     "egnn_edge_geometry", "egnn_radial_weights", "egnn_tp_segsum", "egnn_node_mix",
     "egnn_layer_forward", "egnn_readout_hij", "egnn_timing_enable", "egnn_timing_read",
     "egnn_backward_workspace_bytes", "egnn_graph_transpose", "egnn_loss_mse", "egnn_layer_backward",
-    "egnn_readout_backward", "egnn_set_option", "egnn_radial_weights_f16", "egnn_tp_segsum_f16", "egnn_so2_weight_count", "egnn_so2_workspace_bytes",
+    "egnn_readout_backward", "egnn_set_option", "egnn_radial_weights_f16", "egnn_tp_segsum_f16", "egnn_tp_segsum_f16h", "egnn_so2_weight_count", "egnn_so2_workspace_bytes",
     "egnn_so2_message_sum", "egnn_so2_backward_workspace_bytes", "egnn_so2_message_sum_backward",
     "egnn_so2_blocks_backward_workspace_bytes", "egnn_so2_node_block_backward", "egnn_so2_edge_block_backward",
     "egnn_gate_backward_workspace_bytes", "egnn_gate_backward",
@@ -305,6 +305,15 @@ class Egnn:
         g = graph.desc()
         self._check(self.lib.egnn_tp_segsum_f16(self.ctx, C.byref(g), _ptr(rhat_d), _ptr(h), _ptr(w16), _ptr(a),
                                                 _stream()))
+        return a
+
+    def egnn_tp_segsum_f16h(self, graph, rhat_d, h16, w16, out=None):
+        """h16: torch.float16 tensor [n_total][dim][channels]."""
+        a = out if out is not None else torch.empty((graph.n_owned, self.dim, self.channels), dtype=torch.float32,
+                                                    device="cuda")
+        g = graph.desc()
+        self._check(self.lib.egnn_tp_segsum_f16h(self.ctx, C.byref(g), _ptr(rhat_d), _ptr(h16), _ptr(w16), _ptr(a),
+                                                 _stream()))
         return a
 
     # ---- S4

@@ -334,6 +334,16 @@ extern "C" int egnn_tp_segsum_f16(egnn_ctx* ctx, const egnn_graph* g, const floa
   return egnn_launch_tp_segsum(ctx, g, rhat_d, h, reinterpret_cast<const float*>(w16), a, (hipStream_t)stream, true);
 }
 
+extern "C" int egnn_tp_segsum_f16h(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, const uint16_t* h16,
+                                   const uint32_t* w16, float* a, void* stream) {
+  if (!ctx) return EGNN_EINVAL;
+  int rc = check_graph(ctx, g, "tp_segsum_f16h");
+  if (rc) return rc;
+  if (!rhat_d || !h16 || !w16 || !a) return egnn_fail(ctx, EGNN_EINVAL, "tp_segsum_f16h: null pointer");
+  return egnn_launch_tp_segsum(ctx, g, rhat_d, reinterpret_cast<const float*>(h16), reinterpret_cast<const float*>(w16), a,
+                               (hipStream_t)stream, true, false, true);
+}
+
 extern "C" int egnn_node_mix(egnn_ctx* ctx, const float* x1, const float* W1, const float* x2, const float* W2,
                              float* y, int32_t n_nodes, void* stream) {
   if (!ctx) return EGNN_EINVAL;

@@ -145,8 +145,9 @@ int egnn_launch_readout_backward(egnn_ctx*, const egnn_graph*, const float* rhat
                                  bool shared_rows = false);
 // half = true: `w` holds half-precision weights in the layout of w_half.h (egnn_w_bytes sizes it)
 // shared_rows = true: `w` has one row per entry of g->w_row (egnn_edge_pairs), else one per edge
+// h_half = true (needs half): `h` holds half-precision values
 int egnn_launch_tp_segsum(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* h, const float* w,
-                          float* a, hipStream_t, bool half = false, bool shared_rows = false);
+                          float* a, hipStream_t, bool half = false, bool shared_rows = false, bool h_half = false);
 int egnn_launch_radial(egnn_ctx*, int which, const float* rhat_d, int64_t n_edges, const float* W_r1,
                        const float* W_r2, float* w, void* scratch, hipStream_t, bool half = false);
 // looks up the address of the built-in scratch array of egnn_radial_weights_static on the current device, if there is one

@@ -17,8 +17,9 @@
 #include "w_half.h"
 
 // HLE = 0: w in fp32, any channel count (log2E at run time).  HLE > 0: w in half precision (layout of w_half.h)
-// for 2^HLE channels.
-template <int LMAX, int HLE>
+// for 2^HLE channels.  H16 (with HLE > 0): h holds IEEE half-precision values, same [node][(l,m)][channel] order
+// (the paper's mixed-precision mode keeps the embeddings in half precision and the sums in fp32, Sec. 4.1).
+template <int LMAX, int HLE, bool H16 = false>
 __global__ __launch_bounds__(256) void tp_segsum_kernel(const int* __restrict__ row_ptr,
                                                         const int* __restrict__ src,
                                                         const float4* __restrict__ rhat_d,
@@ -60,7 +61,6 @@ __global__ __launch_bounds__(256) void tp_segsum_kernel(const int* __restrict__ 
     kw = (size_t)egnn_weight_row(w_row, k);
   }
   for (; k < k1; k += n_slots) {
-    const float* hp = h + ((size_t)s * D << log2E) + c;
     float v[D], wr[P], o[D];
     if constexpr (HLE == 0) {
       const float* wp = w + (kw * P << log2E) + c;
@@ -69,8 +69,15 @@ __global__ __launch_bounds__(256) void tp_segsum_kernel(const int* __restrict__ 
     } else {
       w_half_load<P, HLE>(reinterpret_cast<const uint32_t*>(w) + kw * w_half_row_words(P << HLE), c, wr);
     }
+    if constexpr (H16) {
+      const _Float16* hp = reinterpret_cast<const _Float16*>(h) + ((size_t)s * D << log2E) + c;
 #pragma unroll
-    for (int i = 0; i < D; ++i) v[i] = hp[(size_t)i << log2E];
+      for (int i = 0; i < D; ++i) v[i] = (float)hp[(size_t)i << log2E];
+    } else {
+      const float* hp = h + ((size_t)s * D << log2E) + c;
+#pragma unroll
+      for (int i = 0; i < D; ++i) v[i] = hp[(size_t)i << log2E];
+    }
     const float4 g_now = g;
     const int kn = k + n_slots;
     if (kn < k1) {
@@ -100,7 +107,7 @@ __global__ __launch_bounds__(256) void tp_segsum_kernel(const int* __restrict__ 
 }
 
 int egnn_launch_tp_segsum(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, const float* h,
-                          const float* w, float* a, hipStream_t stream, bool half, bool shared_rows) {
+                          const float* w, float* a, hipStream_t stream, bool half, bool shared_rows, bool h_half) {
   const int n = g->n_owned;
   if (n == 0) return EGNN_OK;
   const int per_xcd = (n + 7) / 8;
@@ -108,9 +115,16 @@ int egnn_launch_tp_segsum(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_
   const float scale = 1.0f / sqrtf(ctx->desc.agg_norm);
   const float4* rd = reinterpret_cast<const float4*>(rhat_d);
   const int* w_row = shared_rows ? g->w_row : nullptr;
-#define LAUNCH(L, H)                                                                                          \
-  hipLaunchKernelGGL((tp_segsum_kernel<L, H>), grid, block, 0, stream, g->row_ptr, g->src, rd, h, w, w_row, a, \
-                     n, ctx->log2_channels, per_xcd, scale)
+  if (h_half && !half) return egnn_fail(ctx, EGNN_EINVAL, "tp_segsum: half-precision features need half-precision weights");
+#define LAUNCH(L, H)                                                                                                  \
+  do {                                                                                                                \
+    if (h_half && H > 0)                                                                                              \
+      hipLaunchKernelGGL((tp_segsum_kernel<L, H, (H > 0)>), grid, block, 0, stream, g->row_ptr, g->src, rd, h, w, w_row, \
+                         a, n, ctx->log2_channels, per_xcd, scale);                                                   \
+    else                                                                                                              \
+      hipLaunchKernelGGL((tp_segsum_kernel<L, H, false>), grid, block, 0, stream, g->row_ptr, g->src, rd, h, w, w_row, \
+                         a, n, ctx->log2_channels, per_xcd, scale);                                                   \
+  } while (0)
 #define CASE(L)                                                                                  \
   case L:                                                                                        \
     switch (half ? ctx->log2_channels : 0) {                                                     \

@@ -110,6 +110,43 @@ def test_tp_segsum_f16_with_oracle_made_codes(B, lmax, E, n, n_owned):
     assert U.rel_err(a.cpu().numpy(), ref) < 2e-5
 
 
+@pytest.mark.parametrize("lmax,E,n,n_owned", [(2, 8, 70, 50), (1, 16, 60, 60), (3, 32, 150, 100), (4, 32, 100, 100),
+                                              (4, 64, 100, 80), (2, 128, 60, 60), (0, 16, 40, 40)])
+def test_tp_segsum_f16h_features_and_weights_in_half_precision(B, lmax, E, n, n_owned):
+    """S4 with the gathered features in half precision as well (egnn_tp_segsum_f16h).  The features are rounded on the
+    device by egnn_pack_rows(half) with the identity index list -- bit-exact against numpy's rounding -- and the
+    weights are packed from the oracle's rounded values, so both sides use identical inputs: fp32 bar against the
+    oracle run on the rounded features and weights."""
+    import torch
+    from oracle import egnn_oracle as O
+    w, g, m, gd, pos, rhat_d, W, w64, paths = _edge_setup(B, lmax, E, n, n_owned, 8, 4.0, 90 + lmax, 0)
+    wr = w64.astype(np.float16).astype(np.float64)
+    rng = np.random.default_rng(10)
+    h = synth.node_features(rng, n, lmax, E)
+    h[0, 0, 0] = 70000.0          # beyond the half-precision range: infinity on both sides of the rounding test
+    h[1, 0, 0] = 3.0e-8           # below the smallest subnormal's half: zero
+    h[2, 0, 0] = 6.1e-5           # subnormal range
+    h16 = m.egnn_pack_rows(B.to_device(h), torch.arange(n, dtype=torch.int32, device="cuda"), half=True)
+    assert h16.dtype == torch.float16
+    with np.errstate(over="ignore"):
+        expect = h.astype(np.float16)
+    assert np.array_equal(h16.cpu().numpy().view(np.uint16), expect.view(np.uint16))
+    h16[0, 0, 0] = 1.5            # (a finite value again for the sums)
+    hr = h16.cpu().numpy().astype(np.float64)
+    a = m.egnn_tp_segsum_f16h(gd, rhat_d, h16, B.to_device(pack_w16(wr, fill=np.nan)))
+    ref = O.edge_messages_sum(g, w.pos, w.box, hr, lambda d, k0, k1, p: wr[k0:k1].reshape(k1 - k0, len(paths), E),
+                              lmax, lmax, 4.0)
+    e = U.rel_err(a.cpu().numpy(), ref)
+    # what the rounding of the features itself costs, for the record (not a bar)
+    h_full = h.astype(np.float64)
+    h_full[0, 0, 0] = 1.5
+    full = O.edge_messages_sum(g, w.pos, w.box, h_full, lambda d, k0, k1, p: wr[k0:k1].reshape(k1 - k0, len(paths), E),
+                               lmax, lmax, 4.0)
+    print(f"  lmax {lmax} E {E}: rel err {e:.2e} (rounding the features moves the result by "
+          f"{np.abs(ref - full).max() / np.abs(full).max():.1e})", flush=True)
+    assert e < 2e-5
+
+
 def _rms(a):
     return float(np.sqrt(np.mean(np.square(a))))
 
