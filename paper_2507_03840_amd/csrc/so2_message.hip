@@ -713,9 +713,9 @@ extern "C" int egnn_gate(egnn_ctx* ctx, const float* x, const float* W_g, float*
 // inputs, so the reverse pass is the same chain read backwards:
 //   1. so2_gather_kernel       the operands A_m of the forward pass again (they are the inputs of the weight gradient);
 //   2. so2_dy_kernel           dY_m[k] = bond-frame rotation of  agg_norm^-1/2 f_c(d_k) da[dst(k)], m-major like Y_m;
-//   3. so2_wgrad_kernel        dB_m = A_m^T dY_m, a contraction over the edges: exact fp32 matrix-core products
-//                              (v_mfma_f32_32x32x2_f32, both operands read in memory order: the contraction index is
-//                              the row index of both), partial sums per chunk of edges added in a fixed order;
+//   3. so2_wgrad_kernel        dB_m = A_m^T dY_m, a contraction over the edges on half-precision pieces (three
+//                              products per fp32 product); both operands are read in memory order: the contraction
+//                              index is the row index of both; partial sums per chunk of edges added in a fixed order;
 //      so2_unpack_wgrad_kernel dB_m = [[dWr^T, dWi^T], [-dWi^T, dWr^T]] folded back into the layout of the weights;
 //   4. so2_gemmw_kernel        dA_m = dY_m B_m^T with the packed operand transposed, written over A_m;
 //   5. so2_dx_kernel           one workgroup per destination node: the two node parts of dA_m[k] rotated back to the
@@ -853,18 +853,25 @@ __global__ __launch_bounds__(256) void so2_attention_adjoint_kernel(const int* _
 }
 
 // partial[chunk][k][n] = sum over the edges e of the chunk of A[e][k] Y[e][n].  Workgroup = (chunk of edges, four
-// neighbouring 128 x 64 quarters of the result), one quarter per wave as 4 x 2 accumulators of 32 x 32.  One matrix-core
-// instruction contracts two edges.  A lane fetches 16 bytes of A and 8 bytes of Y per pair of edges, so that a
-// half-wave reads 512 and 256 contiguous bytes of one row: lane (i, h) holds A[e + h][k0 + 4 i + a] for a < 4 and
-// Y[e + h][n0 + 2 i + q] for q < 2, and accumulator (a, q) therefore holds the rows k0 + 4 r + a and the columns
-// n0 + 2 i + q of the result -- a permutation that only the final store has to know.  Columns past the last one are
-// clamped (K and N are multiples of 8: a lane's group is valid or not as a whole; invalid ones are not stored).
-#define SW_UNROLL 8
+// neighbouring 128 x 64 quarters of the result), one quarter per wave as 4 x 2 accumulators of 32 x 32.  The products
+// run on half-precision pieces like the GEMMs (two pieces per operand after a power-of-two scaling from its largest
+// magnitude, three products per fp32 product: v_mfma_f32_32x32x16_f16 contracts 16 edges per instruction; the first
+// version used exact fp32 products, v_mfma_f32_32x32x2_f32, at a sixteenth of the rate).  Both operands are read
+// in memory order, because the contraction index is the row index of both: per block of 16 edges a lane fetches, for
+// the eight edges of its half-wave, 16 bytes of A and 8 bytes of Y each -- a half-wave reads 512 and 256 contiguous
+// bytes of a row -- and finds the eight consecutive edges that one operand register wants, for each of its 4 + 2
+// columns, in one component of those eight registers: lane (i, h) holds A[e + 8 h + r][k0 + 4 i + a] and
+// Y[e + 8 h + r][n0 + 2 i + q], so accumulator (a, q) holds the rows k0 + 4 r' + a and the columns n0 + 2 i + q of the
+// result -- a permutation that only the final store has to know.  Columns past the last one are clamped (K and N are
+// multiples of 8: a lane's group is valid or not as a whole; invalid ones are not stored).
+#define SW_BLOCK 16
 typedef float sw_f4 __attribute__((ext_vector_type(4)));
 typedef float sw_f2 __attribute__((ext_vector_type(2)));
 __global__ __launch_bounds__(256, 2) void so2_wgrad_kernel(const float* __restrict__ A, int K, int lda,
                                                            const float* __restrict__ Y, int N, int ldy, long n_edges,
-                                                           long per_chunk, int quarters_n, float* __restrict__ partial) {
+                                                           long per_chunk, int quarters_n, float* __restrict__ partial,
+                                                           const unsigned* __restrict__ a_max,
+                                                           const unsigned* __restrict__ y_max) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i32 = lane & 31, hh = lane >> 5;
   // (tiles of one chunk of edges are neighbours in the grid and land on different XCDs: putting them on one XCD, so
@@ -882,10 +889,12 @@ __global__ __launch_bounds__(256, 2) void so2_wgrad_kernel(const float* __restri
   if (e_end > n_edges) e_end = n_edges;
   const int ca = k0 + 4 * i32, cy = n0 + 2 * i32;
   const bool a_ok = ca < K, y_ok = cy < N;
+  const int ea = sgh_scale_exp(*a_max), ey = sgh_scale_exp(*y_max);
+  const float a_scale = ldexpf(1.0f, ea), y_scale = ldexpf(1.0f, ey), unscale = ldexpf(1.0f, -ea - ey);
   // addresses: a row pointer that is the same for the whole wave (scalar arithmetic) plus a per-lane byte offset that
-  // never changes (its half-wave's row and its columns) -- no vector arithmetic per load
-  const unsigned oa = (unsigned)(hh * lda + (a_ok ? ca : K - 4)) * 4u;
-  const unsigned oy = (unsigned)(hh * ldy + (y_ok ? cy : N - 2)) * 4u;
+  // never changes (its half-wave's first row and its columns) -- no vector arithmetic per load
+  const unsigned oa = (unsigned)(8 * hh * lda + (a_ok ? ca : K - 4)) * 4u;
+  const unsigned oy = (unsigned)(8 * hh * ldy + (y_ok ? cy : N - 2)) * 4u;
   float16v acc[4][2];
 #pragma unroll
   for (int a = 0; a < 4; ++a)
@@ -893,59 +902,79 @@ __global__ __launch_bounds__(256, 2) void so2_wgrad_kernel(const float* __restri
     for (int q = 0; q < 2; ++q)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][q][i] = 0.0f;
-  // Two register sets: the loads of the next block of 2 * SW_UNROLL edges are issued before the products of the
-  // current one.  The loop runs over the full blocks of the chunk with no mask and no branch around a load (the
-  // block after the last one is the last one again, loaded and not used); what is left of the chunk comes after it.
-  sw_f4 av0[SW_UNROLL], av1[SW_UNROLL];
-  sw_f2 yv0[SW_UNROLL], yv1[SW_UNROLL];
-  auto fetch = [&](sw_f4 (&av)[SW_UNROLL], sw_f2 (&yv)[SW_UNROLL], long e) {
+  sw_f4 ra[8];
+  sw_f2 ry[8];
+  // a full block: rows e .. e + 15 exist; no mask and no branch around a load
+  auto fetch = [&](long e) {
 #pragma unroll
-    for (int u = 0; u < SW_UNROLL; ++u) {
-      const char* ar = reinterpret_cast<const char*>(A + (size_t)(e + 2 * u) * lda);
-      const char* yr = reinterpret_cast<const char*>(Y + (size_t)(e + 2 * u) * ldy);
-      av[u] = *reinterpret_cast<const sw_f4*>(ar + oa);
-      yv[u] = *reinterpret_cast<const sw_f2*>(yr + oy);
+    for (int r = 0; r < 8; ++r) {
+      ra[r] = *reinterpret_cast<const sw_f4*>(reinterpret_cast<const char*>(A + (size_t)(e + r) * lda) + oa);
+      ry[r] = *reinterpret_cast<const sw_f2*>(reinterpret_cast<const char*>(Y + (size_t)(e + r) * ldy) + oy);
     }
   };
-  auto products = [&](const sw_f4 (&av)[SW_UNROLL], const sw_f2 (&yv)[SW_UNROLL]) {
+  uint4 ah[4], al[4], yh[2], yl[2];
+  auto cut = [&]() {
 #pragma unroll
-    for (int u = 0; u < SW_UNROLL; ++u)
+    for (int a = 0; a < 4; ++a) {
+      const float x[8] = {ra[0][a], ra[1][a], ra[2][a], ra[3][a], ra[4][a], ra[5][a], ra[6][a], ra[7][a]};
+      sgh_split8(x, a_scale, ah[a], al[a]);
+    }
 #pragma unroll
-      for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int q = 0; q < 2; ++q)
-          acc[a][q] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u][a], yv[u][q], acc[a][q], 0, 0, 0);
+    for (int q = 0; q < 2; ++q) {
+      const float x[8] = {ry[0][q], ry[1][q], ry[2][q], ry[3][q], ry[4][q], ry[5][q], ry[6][q], ry[7][q]};
+      sgh_split8(x, y_scale, yh[q], yl[q]);
+    }
   };
-  constexpr long BLOCK = 2 * SW_UNROLL;
-  const long n_blocks = (e_end - e_begin) / BLOCK;
+  auto products = [&]() {
+    // smallest terms first; the eight accumulation chains are independent
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+        acc[a][q] = __builtin_amdgcn_mfma_f32_32x32x16_f16(sgh_as_h8(al[a]), sgh_as_h8(yh[q]), acc[a][q], 0, 0, 0);
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+        acc[a][q] = __builtin_amdgcn_mfma_f32_32x32x16_f16(sgh_as_h8(ah[a]), sgh_as_h8(yl[q]), acc[a][q], 0, 0, 0);
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+        acc[a][q] = __builtin_amdgcn_mfma_f32_32x32x16_f16(sgh_as_h8(ah[a]), sgh_as_h8(yh[q]), acc[a][q], 0, 0, 0);
+  };
+  // The full blocks of the chunk: the block's registers are cut into pieces, then refilled with the next block while
+  // the products of this one run (the block after the last one is the last one again, loaded and not used).
+  const long n_blocks = (e_end - e_begin) / SW_BLOCK;
   if (n_blocks > 0) {
-    const long last = e_begin + (n_blocks - 1) * BLOCK;
-    fetch(av0, yv0, e_begin);
-    for (long blk = 0; blk < n_blocks; blk += 2) {
-      const long e1 = e_begin + (blk + 1) * BLOCK, e2 = e1 + BLOCK;
-      fetch(av1, yv1, e1 < last ? e1 : last);
-      products(av0, yv0);
-      fetch(av0, yv0, e2 < last ? e2 : last);
-      if (blk + 1 < n_blocks) products(av1, yv1);
+    const long last = e_begin + (n_blocks - 1) * SW_BLOCK;
+    fetch(e_begin);
+    for (long blk = 0; blk < n_blocks; ++blk) {
+      cut();
+      const long e1 = e_begin + (blk + 1) * SW_BLOCK;
+      fetch(e1 < last ? e1 : last);
+      products();
     }
   }
   {
-    // the ragged end of the last chunk: fewer than 2 * SW_UNROLL edges, zeros past the end
-    const long e = e_begin + n_blocks * BLOCK;
+    // the ragged end of the last chunk: fewer than 16 edges, zeros past the end
+    const long e = e_begin + n_blocks * SW_BLOCK;
     if (e < e_end) {
 #pragma unroll
-      for (int u = 0; u < SW_UNROLL; ++u) {
-        const long ee = e + 2 * u;               // (+ hh through the lane offsets)
-        const bool ok = ee + hh < e_end;
-        const long er = ok ? ee : e_end - 1 - hh;  // a row whose lane offset stays inside the matrix: e_end - 1 at most
+      for (int r = 0; r < 8; ++r) {
+        const long ee = e + 8 * hh + r;
+        const bool ok = ee < e_end;
+        // a row whose lane offset (8 hh rows further) stays inside the matrix: e_end - 1 at most
+        const long er = ok ? e + r : e_end - 1 - 8 * hh;
         const sw_f4 a4 = *reinterpret_cast<const sw_f4*>(reinterpret_cast<const char*>(A + (size_t)er * lda) + oa);
         const sw_f2 y2 = *reinterpret_cast<const sw_f2*>(reinterpret_cast<const char*>(Y + (size_t)er * ldy) + oy);
         const sw_f4 z4 = {0.0f, 0.0f, 0.0f, 0.0f};
         const sw_f2 z2 = {0.0f, 0.0f};
-        av0[u] = ok ? a4 : z4;
-        yv0[u] = ok ? y2 : z2;
+        ra[r] = ok ? a4 : z4;
+        ry[r] = ok ? y2 : z2;
       }
-      products(av0, yv0);
+      cut();
+      products();
     }
   }
   float* out = partial + (size_t)chunk * K * N;
@@ -956,7 +985,7 @@ __global__ __launch_bounds__(256, 2) void so2_wgrad_kernel(const float* __restri
       for (int i = 0; i < 16; ++i) {
         const int kk = k0 + 4 * (8 * (i >> 2) + 4 * hh + (i & 3)) + a;
         if (kk < K) {
-          const sw_f2 v = {acc[a][0][i], acc[a][1][i]};
+          const sw_f2 v = {unscale * acc[a][0][i], unscale * acc[a][1][i]};
           *reinterpret_cast<sw_f2*>(out + (size_t)kk * N + cy) = v;
         }
       }
@@ -1130,6 +1159,7 @@ __global__ __launch_bounds__(256) void so2_dwe_kernel(const float4* __restrict__
 // chunks of edges of the weight gradient of one order.  All waves of a launch take the same time, so their number
 // should fill the chip's places once (256 compute units x 4 SIMDs x 2 waves, what the kernel's registers allow), not
 // one and a third times.  Every chunk is a multiple of 2 * SW_UNROLL edges.
+#define SW_UNROLL 8   // (chunks are multiples of 2 * SW_UNROLL = SW_BLOCK edges)
 #define SW_WAVE_SLOTS 2048
 static int so2_wgrad_quarters(int K, int N) { return ((K + 127) / 128) * ((N + 63) / 64); }
 static int so2_wgrad_waves(int K, int N) { const int q = so2_wgrad_quarters(K, N); return q < 4 ? q : 4; }   // per workgroup
@@ -1245,7 +1275,8 @@ static int so2_backward_tail(egnn_ctx* ctx, const egnn_graph* g, const int32_t* 
     long per;
     so2_wgrad_split(n, K, N, &chunks, &per);
     hipLaunchKernelGGL(so2_wgrad_kernel, dim3(so2_wgrad_groups(K, N), chunks), dim3(64 * so2_wgrad_waves(K, N)), 0, st,
-                       call.b.A[m], K, call.b.ldA[m], call.b.Y[m], N, call.b.ldY[m], n, per, (N + 63) / 64, w.partial);
+                       call.b.A[m], K, call.b.ldA[m], call.b.Y[m], N, call.b.ldY[m], n, per, (N + 63) / 64, w.partial,
+                       call.maxima, bmax);
     EGNN_LAUNCH_CHECK(ctx, "so2_wgrad_kernel");
     if ((rc = egnn_launch_reduce_partials(ctx, w.partial, chunks, (long)K * N, w.dB, 1.0f, st))) return rc;
     const int nl = lmax + 1 - m;
