@@ -718,9 +718,10 @@ extern "C" int egnn_gate(egnn_ctx* ctx, const float* x, const float* W_g, float*
 //                              index is the row index of both; partial sums per chunk of edges added in a fixed order;
 //      so2_unpack_wgrad_kernel dB_m = [[dWr^T, dWi^T], [-dWi^T, dWr^T]] folded back into the layout of the weights;
 //   4. so2_gemmw_kernel        dA_m = dY_m B_m^T with the packed operand transposed, written over A_m;
-//   5. so2_dx_kernel           one workgroup per destination node: the two node parts of dA_m[k] rotated back to the
-//                              lab frame; the destination part is summed over the node's incoming edges, the source
-//                              part goes to a per-edge row that a segmented sum over the source-sorted index adds up;
+//   5. so2_dx_edge_kernel      lane = (edge, channel): the source part of dA_m[k] rotated back to the lab frame, to a
+//                              per-edge row that a segmented sum over the source-sorted index adds up;
+//      so2_dx_kernel           one workgroup per destination node: the destination part rotated back and summed over
+//                              the node's incoming edges;
 //      so2_dwe_kernel          dW_e[c][q] = sum_k dA_0[k][edge column c] B_q(d_k).
 // ---------------------------------------------------------------------------------------------------------------------
 // Gradient of the bond-frame results, written m-major over Y_m.  The lab-frame gradient of edge k is
@@ -1026,14 +1027,67 @@ __global__ __launch_bounds__(256) void so2_unpack_wgrad_kernel(const float* __re
   dW[(size_t)rows * cols + idx] = gi;
 }
 
-// One workgroup per destination node j, lane = (edge slot, channel): the parts of dA_m[k] back in (l, m) order and
-// in the lab frame (X' = D M in the forward pass, so dM = D^T dX').  Source part -> rows[k], destination part summed
-// over the incoming edges of j in a fixed order -> dxd[j].  FULL (persistent edge embeddings): the edge part
-// -> dT[k], plus dT_add[k] if that is given (the identity term of the edge update; dT may be dT_add).
+// Column group grp (0 source, 1 destination, 2 edge) of dA_m[k], channel c, back in (l, m) order (bond frame);
+// G = column groups per degree (3 with persistent edge embeddings, else 2).
+template <int LMAX, int G>
+__device__ __forceinline__ void so2_load_group(const So2Bufs& b, long k, int c, int log2E, int grp, float* v) {
+  const float* a0 = b.A[0] + (size_t)k * b.ldA[0] + c;
+#pragma unroll
+  for (int l = 0; l <= LMAX; ++l) v[l * l + l] = __builtin_nontemporal_load(a0 + ((G * l + grp) << log2E));
+#pragma unroll
+  for (int m = 1; m <= LMAX; ++m) {
+    const int nl = LMAX + 1 - m;
+    const float* am = b.A[m] + (size_t)k * b.ldA[m] + c;
+#pragma unroll
+    for (int l = m; l <= LMAX; ++l) {
+      const int col = (G * (l - m) + grp) << log2E, neg = (G * nl) << log2E;
+      v[l * l + l + m] = __builtin_nontemporal_load(am + col);
+      v[l * l + l - m] = __builtin_nontemporal_load(am + neg + col);
+    }
+  }
+}
+
+// The per-edge parts of the gradient of the messages, lane = (edge, channel): the source part of dA_m[k] rotated back
+// to the lab frame (X' = D M in the forward pass, so dM = D^T dX') -> rows[k], which a segmented sum over the
+// source-sorted index adds up afterwards; FULL (persistent edge embeddings): the edge part -> dT[k], plus dT_add[k] if
+// that is given (the identity term of the edge update; dT may be dT_add).
+template <int LMAX, bool FULL>
+__global__ __launch_bounds__(256) void so2_dx_edge_kernel(const float4* __restrict__ rhat_d, So2Bufs b,
+                                                          float* __restrict__ rows, float* dT, const float* dT_add,
+                                                          long n_edges, int log2E) {
+  constexpr int D = (LMAX + 1) * (LMAX + 1);
+  constexpr int G = FULL ? 3 : 2;
+  const int E = 1 << log2E;
+  const int c = threadIdx.x & (E - 1);
+  const long k = (long)blockIdx.x * (256 >> log2E) + (threadIdx.x >> log2E);
+  if (k >= n_edges) return;
+  const float4 g = rhat_d[k];
+  BondTrig t;
+  egnn_bond_trig<LMAX>(g.x, g.y, g.z, t);
+  float v[D];
+  so2_load_group<LMAX, G>(b, k, c, log2E, 0, v);
+  egnn_from_bond_frame<LMAX>(v, t);
+  float* rk = rows + (((size_t)k * D) << log2E) + c;
+#pragma unroll
+  for (int i = 0; i < D; ++i) __builtin_nontemporal_store(v[i], rk + ((size_t)i << log2E));
+  if constexpr (FULL) {
+    so2_load_group<LMAX, G>(b, k, c, log2E, 2, v);
+    egnn_from_bond_frame<LMAX>(v, t);
+    float* tk = dT + (((size_t)k * D) << log2E) + c;
+    const float* ta = dT_add ? dT_add + (((size_t)k * D) << log2E) + c : nullptr;
+#pragma unroll
+    for (int i = 0; i < D; ++i) {
+      const float add = ta ? ta[(size_t)i << log2E] : 0.0f;
+      tk[(size_t)i << log2E] = v[i] + add;
+    }
+  }
+}
+
+// One workgroup per destination node j, lane = (edge slot, channel): the destination part of dA_m[k] rotated back and
+// summed over the incoming edges of j in a fixed order -> dxd[j].
 template <int LMAX, bool FULL>
 __global__ __launch_bounds__(256) void so2_dx_kernel(const int* __restrict__ row_ptr, const float4* __restrict__ rhat_d,
-                                                     So2Bufs b, float* __restrict__ rows, float* __restrict__ dxd,
-                                                     float* dT, const float* dT_add, int n_owned, int log2E,
+                                                     So2Bufs b, float* __restrict__ dxd, int n_owned, int log2E,
                                                      int nodes_per_xcd) {
   constexpr int D = (LMAX + 1) * (LMAX + 1);
   constexpr int G = FULL ? 3 : 2;            // column groups per degree
@@ -1051,42 +1105,11 @@ __global__ __launch_bounds__(256) void so2_dx_kernel(const int* __restrict__ row
     const float4 g = rhat_d[k];
     BondTrig t;
     egnn_bond_trig<LMAX>(g.x, g.y, g.z, t);
-    // one column group at a time (0 source, 1 destination, 2 edge): 25 values in registers
+    float v[D];
+    so2_load_group<LMAX, G>(b, k, c, log2E, 1, v);
+    egnn_from_bond_frame<LMAX>(v, t);
 #pragma unroll
-    for (int grp = 0; grp < G; ++grp) {
-      float v[D];
-      const float* a0 = b.A[0] + (size_t)k * b.ldA[0] + c;
-#pragma unroll
-      for (int l = 0; l <= LMAX; ++l) v[l * l + l] = __builtin_nontemporal_load(a0 + ((G * l + grp) << log2E));
-#pragma unroll
-      for (int m = 1; m <= LMAX; ++m) {
-        const int nl = LMAX + 1 - m;
-        const float* am = b.A[m] + (size_t)k * b.ldA[m] + c;
-#pragma unroll
-        for (int l = m; l <= LMAX; ++l) {
-          const int col = (G * (l - m) + grp) << log2E, neg = (G * nl) << log2E;
-          v[l * l + l + m] = __builtin_nontemporal_load(am + col);
-          v[l * l + l - m] = __builtin_nontemporal_load(am + neg + col);
-        }
-      }
-      egnn_from_bond_frame<LMAX>(v, t);
-      if (grp == 0) {
-        float* rk = rows + (((size_t)k * D) << log2E) + c;
-#pragma unroll
-        for (int i = 0; i < D; ++i) __builtin_nontemporal_store(v[i], rk + ((size_t)i << log2E));
-      } else if (grp == 1) {
-#pragma unroll
-        for (int i = 0; i < D; ++i) acc[i] += v[i];
-      } else {
-        float* tk = dT + (((size_t)k * D) << log2E) + c;
-        const float* ta = dT_add ? dT_add + (((size_t)k * D) << log2E) + c : nullptr;
-#pragma unroll
-        for (int i = 0; i < D; ++i) {
-          const float add = ta ? ta[(size_t)i << log2E] : 0.0f;
-          tk[(size_t)i << log2E] = v[i] + add;
-        }
-      }
-    }
+    for (int i = 0; i < D; ++i) acc[i] += v[i];
   }
 #pragma unroll
   for (int i = 0; i < D; ++i) red[((slot * D + i) << log2E) + c] = acc[i];
@@ -1293,16 +1316,30 @@ static int so2_backward_tail(egnn_ctx* ctx, const egnn_graph* g, const int32_t* 
     if ((rc = so2_launch_gemm(ctx, call.b.Y[m], n, N, call.b.ldY[m], call.T[m], call.b.A[m], K, call.b.ldA[m], bmax, st)))
       return rc;
   }
+  {
+#define DXE(L)                                                                                                       \
+  do {                                                                                                               \
+    if (full)                                                                                                        \
+      hipLaunchKernelGGL((so2_dx_edge_kernel<L, true>), egrid, block, 0, st, rd, call.b, w.rows, dT, dT_add, n,      \
+                         ctx->log2_channels);                                                                        \
+    else                                                                                                             \
+      hipLaunchKernelGGL((so2_dx_edge_kernel<L, false>), egrid, block, 0, st, rd, call.b, w.rows, dT, dT_add, n,     \
+                         ctx->log2_channels);                                                                        \
+  } while (0)
+    SO2_BY_LMAX(lmax, DXE)
+#undef DXE
+    EGNN_LAUNCH_CHECK(ctx, "so2_dx_edge_kernel");
+  }
   if (g->n_owned > 0) {
     const int per_xcd = (g->n_owned + 7) / 8;
 #define DX(L)                                                                                                        \
   do {                                                                                                               \
     if (full)                                                                                                        \
       hipLaunchKernelGGL((so2_dx_kernel<L, true>), dim3(per_xcd * 8), dim3(256), 0, st, g->row_ptr, rd, call.b,      \
-                         w.rows, w.dxd, dT, dT_add, g->n_owned, ctx->log2_channels, per_xcd);                        \
+                         w.dxd, g->n_owned, ctx->log2_channels, per_xcd);                                            \
     else                                                                                                             \
       hipLaunchKernelGGL((so2_dx_kernel<L, false>), dim3(per_xcd * 8), dim3(256), 0, st, g->row_ptr, rd, call.b,     \
-                         w.rows, w.dxd, dT, dT_add, g->n_owned, ctx->log2_channels, per_xcd);                        \
+                         w.dxd, g->n_owned, ctx->log2_channels, per_xcd);                                            \
   } while (0)
     SO2_BY_LMAX(lmax, DX)
 #undef DX
