@@ -164,7 +164,8 @@ def make_so2_backward(index, pool_size):
     da = U.so2_da(w)
     _state.update(w=w, g=g, x=x, Wso2=Wso2, agg=agg, da=da)
     n_e = len(g[0])
-    step = 8192
+    # (few large ranges: every job returns a full dx, 0.26 GB at config 4)
+    step = max(8192, -(-n_e // (2 * pool_size)))
     jobs = [(k0, min(n_e, k0 + step)) for k0 in range(0, n_e, step)]
     total = None
     with ProcessPoolExecutor(pool_size) as ex:
@@ -181,11 +182,13 @@ def make_so2_backward(index, pool_size):
     rng = np.random.default_rng([w.seed, 4244])
     nodes = aimed_nodes(w, g, rng, w.n_total)
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"config{index}_so2_backward.npz")
+    # (weight gradients in fp32 beyond config 3: 1e6 entries, and 6e-8 of rounding is far below the bar they are held to)
+    wdt = np.float64 if index <= 3 else np.float32
     out = dict(nodes=nodes, dx_rows=dx[nodes], dx_maxabs=np.abs(dx).max(), dx_maxabs_l=maxabs_per_degree(dx, w.lmax),
-               dW_e=dW_e, dW0=dW0, agg=agg, n_edges=n_e)
+               dW_e=dW_e, dW0=dW0.astype(wdt), agg=agg, n_edges=n_e)
     for m in range(w.lmax):
-        out[f"dWr{m + 1}"] = dWr[m]
-        out[f"dWi{m + 1}"] = dWi[m]
+        out[f"dWr{m + 1}"] = dWr[m].astype(wdt)
+        out[f"dWi{m + 1}"] = dWi[m].astype(wdt)
     np.savez_compressed(path, **out)
     print(f"config {index} so2 backward: wrote {path}, {os.path.getsize(path) / 1e3:.0f} kB, max|dx| {np.abs(dx).max():.4f}, "
           f"{time.time() - t0:.0f} s", flush=True)

@@ -162,15 +162,17 @@ def test_so2_backward_empty_graph_and_errors(B):
     assert err.value.code == -3        # workspace too small
 
 
-def test_so2_backward_fullsize_config3(B):
-    """Config 3 in full (625,262 edges) against the oracle's gradients stored by tests/golden/make_golden.py so2bwd:3:
-    every weight gradient in full, dx at aimed rows (per degree, on the scale of that degree over all rows)."""
+@pytest.mark.parametrize("index", [3, 4])
+def test_so2_backward_fullsize(B, index):
+    """Configs 3 and 4 in full (625,262 and 2,350,179 edges) against the oracle's gradients stored by
+    tests/golden/make_golden.py so2bwd:3 so2bwd:4: every weight gradient in full, dx at aimed rows (per degree, on the
+    scale of that degree over all rows)."""
     import time
     import torch
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "config3_so2_backward.npz")
-    assert os.path.exists(path), "run tests/golden/make_golden.py so2bwd:3"
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", f"config{index}_so2_backward.npz")
+    assert os.path.exists(path), "run tests/golden/make_golden.py so2bwd:3 so2bwd:4"
     gold = np.load(path)
-    w = synth.workload(3)
+    w = synth.workload(index)
     wt = U.model_weights(w)
     agg = float(gold["agg"])
     m = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, agg)
@@ -184,7 +186,7 @@ def test_so2_backward_fullsize_config3(B):
     ws = torch.empty(max(m.egnn_so2_backward_workspace_bytes(graph.n_edges, graph.n_owned),
                          m.egnn_backward_workspace_bytes(graph.n_edges, graph.n_owned, graph.n_total)),
                      dtype=torch.uint8, device="cuda")
-    print(f"config 3: workspace {ws.numel() / 1e9:.2f} GB", flush=True)
+    print(f"config {index}: workspace {ws.numel() / 1e9:.2f} GB", flush=True)
     col_ptr, perm = m.egnn_graph_transpose(graph, ws)
     args = (graph, col_ptr, perm, pos, w.box, x, B.to_device(W_e), flat, B.to_device(U.so2_da(w)), ws)
     dx, dW_e, dW = m.egnn_so2_message_sum_backward(*args)
@@ -205,4 +207,4 @@ def test_so2_backward_fullsize_config3(B):
         e = np.abs(rows[:, sl] - gold["dx_rows"][:, sl]).max() / gold["dx_maxabs_l"][l]
         worst = max(worst, e)
         assert e < TOL, (l, e)
-    print(f"config 3: SO(2) message sum adjoint {dt * 1e3:.2f} ms per call, worst rel err {worst:.2e}", flush=True)
+    print(f"config {index}: SO(2) message sum adjoint {dt * 1e3:.2f} ms per call, worst rel err {worst:.2e}", flush=True)
