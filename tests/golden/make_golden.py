@@ -248,6 +248,7 @@ def _blocks_backward_nodes(j_range):
 
 # score inputs closer to zero than this are where an fp32 evaluation may take the other branch of LeakyReLU'
 KINK_EPS = 4e-6
+EDGE_PIECE = 8192     # edges per oracle call inside a job of the edge block's adjoint
 
 
 def _blocks_backward_edges(k_range):
@@ -255,11 +256,23 @@ def _blocks_backward_edges(k_range):
     from oracle import so2_oracle as S
     w, g, x, T, We, dT_out, edges = (_state[k] for k in ("w", "g", "x", "T", "We", "dT_out", "edges"))
     k0, k1 = k_range
-    sub = (g[0][k0:k1], g[1][k0:k1], g[2][k0:k1], g[3])
-    dx, dT_in, dW0, dWr, dWi = S.so2_edge_block_backward(sub, w.pos, w.box, x, T[k0:k1], We[1], We[2], We[3], w.lmax,
-                                                         w.channels, w.r_cut, dT_out[k0:k1])
     pick = edges[(edges >= k0) & (edges < k1)]
-    return dx, (pick, dT_in[pick - k0]), [dW0] + list(dWr) + list(dWi)
+    dx, flat, rows = None, None, []
+    for a in range(k0, k1, EDGE_PIECE):      # (small pieces: the oracle call holds several fp64 copies of its range)
+        b = min(k1, a + EDGE_PIECE)
+        sub = (g[0][a:b], g[1][a:b], g[2][a:b], g[3])
+        pdx, dT_in, dW0, dWr, dWi = S.so2_edge_block_backward(sub, w.pos, w.box, x, T[a:b], We[1], We[2], We[3], w.lmax,
+                                                              w.channels, w.r_cut, dT_out[a:b])
+        part = [dW0] + list(dWr) + list(dWi)
+        if dx is None:
+            dx, flat = pdx, part
+        else:
+            dx += pdx
+            for acc, v in zip(flat, part):
+                acc += v
+        here = pick[(pick >= a) & (pick < b)]
+        rows.append(dT_in[here - a])
+    return dx, (pick, np.concatenate(rows)), flat
 
 
 def make_blocks_backward(index, pool_size):
@@ -276,8 +289,12 @@ def make_blocks_backward(index, pool_size):
     edges = aimed_edges(g, rng)
     _state.update(w=w, g=g, x=x, T=T, Wn=Wn, We=We, w_att=w_att, da=U.so2_da(w), dT_out=U.blocks_dT_out(w, n_e), edges=edges)
     out = dict(nodes=nodes, edges=edges, n_edges=n_e)
-    jobs_n = [(j0, min(w.n_owned, j0 + 32)) for j0 in range(0, w.n_owned, 32)]
-    jobs_e = [(k0, min(n_e, k0 + 8192)) for k0 in range(0, n_e, 8192)]
+    # (few large ranges: every job returns a full dx, 0.26 GB at config 4; a node job also holds the gradient of the
+    # edge embeddings of its range)
+    step_n = max(32, -(-w.n_owned // (4 * pool_size)))
+    step_e = max(8192, -(-n_e // (2 * pool_size)))
+    jobs_n = [(j0, min(w.n_owned, j0 + step_n)) for j0 in range(0, w.n_owned, step_n)]
+    jobs_e = [(k0, min(n_e, k0 + step_e)) for k0 in range(0, n_e, step_e)]
     for tag, fn, jobs, names in (("node", _blocks_backward_nodes, jobs_n, ["dW0", "dWr", "dWi", "dw_att"]),
                                  ("edge", _blocks_backward_edges, jobs_e, ["dW0", "dWr", "dWi"])):
         dx, flat, kinks = None, None, []
@@ -293,13 +310,14 @@ def make_blocks_backward(index, pool_size):
                     for acc, v in zip(flat, part_w):
                         acc += v
                 dT_rows[np.searchsorted(edges, pick)] = rows
-        out[f"{tag}_dx_rows"] = dx[nodes]
+        wdt = np.float64 if index <= 3 else np.float32   # (as in make_so2_backward; the stored rows likewise)
+        out[f"{tag}_dx_rows"] = dx[nodes].astype(wdt)
         out[f"{tag}_dx_maxabs_l"] = maxabs_per_degree(dx, w.lmax)
-        out[f"{tag}_dT_rows"] = dT_rows
-        out[f"{tag}_dW0"] = flat[0]
+        out[f"{tag}_dT_rows"] = dT_rows.astype(wdt)
+        out[f"{tag}_dW0"] = flat[0].astype(wdt)
         for m in range(w.lmax):
-            out[f"{tag}_dWr{m + 1}"] = flat[1 + m]
-            out[f"{tag}_dWi{m + 1}"] = flat[1 + w.lmax + m]
+            out[f"{tag}_dWr{m + 1}"] = flat[1 + m].astype(wdt)
+            out[f"{tag}_dWi{m + 1}"] = flat[1 + w.lmax + m].astype(wdt)
         if tag == "node":
             out["node_dw_att"] = flat[-1]
             # edges with a score input within KINK_EPS of zero, and the nodes whose rows of dx they reach

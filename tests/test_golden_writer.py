@@ -85,7 +85,7 @@ def _sum_parts(parts):
     return total
 
 
-def test_so2_backward_chunks_sum_to_the_oracle_adjoints():
+def test_so2_backward_chunks_sum_to_the_oracle_adjoints(monkeypatch):
     """The writers of config3_so2_backward.npz and config3_so2_blocks_backward.npz split the adjoints over edge ranges
     (message sum, edge block) and destination-node ranges (node block) and add the parts up: on config 1 the sums equal
     the oracle's own calls over the whole graph."""
@@ -119,6 +119,7 @@ def test_so2_backward_chunks_sum_to_the_oracle_adjoints():
     for pick, rows in (p[1] for p in node_parts):
         assert np.array_equal(rows, ref[1][pick])
     assert sorted(np.concatenate([p[1][0] for p in node_parts]).tolist()) == edges.tolist()
+    monkeypatch.setattr(MG, "EDGE_PIECE", 120)     # several oracle calls per job, a ragged last one
     edge_parts = [MG._blocks_backward_edges((k0, min(n_e, k0 + 500))) for k0 in range(0, n_e, 500)]
     ref = S.so2_edge_block_backward(g, w.pos, w.box, xb, T, We[1], We[2], We[3], L, E, w.r_cut, dT_out)
     dx = _sum_parts([[p[0]] for p in edge_parts])[0]

@@ -156,20 +156,21 @@ def test_gate_backward(B, lmax, E, n):
         assert U.rel_err(dW.cpu().numpy(), ref_dW) < 1e-5
 
 
-def test_blocks_backward_fullsize_config3(B):
-    """Config 3 in full (625,262 edges) against the oracle's gradients stored by tests/golden/make_golden.py
-    blocksbwd:3: every weight gradient (and dw_att) in full, dx at aimed nodes per degree, the gradient of the edge
-    embeddings at aimed edges."""
+@pytest.mark.parametrize("index", [3, 4])
+def test_blocks_backward_fullsize(B, index):
+    """Configs 3 and 4 in full (625,262 and 2,350,179 edges) against the oracle's gradients stored by
+    tests/golden/make_golden.py blocksbwd:3 blocksbwd:4: every weight gradient (and dw_att) in full, dx at aimed nodes
+    per degree, the gradient of the edge embeddings at aimed edges."""
     import os
     import time
     import torch
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "config3_so2_blocks_backward.npz")
-    assert os.path.exists(path), "run tests/golden/make_golden.py blocksbwd:3"
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", f"config{index}_so2_blocks_backward.npz")
+    assert os.path.exists(path), "run tests/golden/make_golden.py blocksbwd:3 blocksbwd:4"
     gold = np.load(path)
-    w = synth.workload(3)
+    w = synth.workload(index)
     g, x, T, Wn, We, w_att, m, pos, graph, ws, col_ptr, perm = setup(B, w)
     assert graph.n_edges == int(gold["n_edges"])
-    print(f"config 3: workspace {ws.numel() / 1e9:.2f} GB", flush=True)
+    print(f"config {index}: workspace {ws.numel() / 1e9:.2f} GB", flush=True)
     nodes, edges = torch.from_numpy(gold["nodes"]).cuda(), torch.from_numpy(gold["edges"]).cuda()
     xd, Td = B.to_device(x), B.to_device(T)
 
@@ -178,7 +179,20 @@ def test_blocks_backward_fullsize_config3(B):
         got.update(extra)
         errs = {k: float(np.abs(got[k].astype(np.float64) - gold[k]).max() / np.abs(gold[k]).max()) for k in got}
         print(f"  {tag}: " + ", ".join(f"{k.split('_', 1)[1]} {v:.1e}" for k, v in errs.items()), flush=True)
-        worst = check(got, {k: gold[k] for k in got}, TOL)
+        want = {k: gold[k] for k in got}
+        if tag == "node":
+            # The branch of LeakyReLU' taken at a score input next to zero (see below) enters the weight gradients only
+            # through the L = 0 plane of the message gradient, i.e. the rows l_out = 0 of dW_0 (its first E rows): those
+            # rows are held to the looser bar, all other rows and all other matrices to the element-wise one.
+            E = w.channels
+            full = got.pop(tag + "_dW0")
+            ref = want.pop(tag + "_dW0")
+            scale = np.abs(ref).max()
+            e_kink = np.abs(full[:E].astype(np.float64) - ref[:E]).max() / scale
+            e_rest = np.abs(full[E:].astype(np.float64) - ref[E:]).max() / scale if full.shape[0] > E else 0.0
+            print(f"  {tag}: dW0 rows l_out = 0: {e_kink:.1e}, other rows {e_rest:.1e}", flush=True)
+            assert e_rest < TOL and e_kink < 20 * TOL, (e_rest, e_kink)
+        worst = check(got, want, TOL)
         # LeakyReLU' jumps at zero: where the oracle found a score input within 4e-6 of zero (fp32 rounding of the
         # messages is 1e-6 here) the kernel may take the other branch, as any fp32 evaluation may.  The rows of dx and
         # of dT that such an edge reaches are held to a looser bar; everything else to the element-wise one.
@@ -221,7 +235,7 @@ def test_blocks_backward_fullsize_config3(B):
     edge_args = (graph, col_ptr, perm, pos, w.box, xd, Td, B.to_device(S.so2_pack(*We[1:])), dT_out, ws)
     (dx, dT, dW), t_edge = timed(lambda: m.egnn_so2_edge_block_backward(*edge_args))
     e_edge = compare("edge", dx, dT, dW, {})
-    print(f"config 3: node block adjoint {t_node * 1e3:.2f} ms ({e_node:.2e}), edge block adjoint {t_edge * 1e3:.2f} ms "
+    print(f"config {index}: node block adjoint {t_node * 1e3:.2f} ms ({e_node:.2e}), edge block adjoint {t_edge * 1e3:.2f} ms "
           f"({e_edge:.2e})", flush=True)
 
 
