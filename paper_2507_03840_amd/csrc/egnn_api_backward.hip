@@ -57,7 +57,9 @@ struct ReadoutBwdBufs {
 
 static size_t readout_bwd_tab_ints(const egnn_ctx* ctx) {
   const int nq = ctx->n_orb * ctx->n_orb;
-  return (size_t)nq + 1 + ctx->unc_q.size() + 2 * ctx->n_slots + vrows(ctx);
+  int q_off[EGNN_L_READOUT + 2], nqp;
+  egnn_readout_backward_q_layout(ctx, q_off, &nqp);
+  return (size_t)(nqp > nq ? nqp : nq) + 1 + ctx->unc_q.size() + 2 * ctx->n_slots;
 }
 
 static size_t carve_readout_bwd(const egnn_ctx* ctx, const egnn_graph* g, char* base, ReadoutBwdBufs* b) {
@@ -206,7 +208,7 @@ static int readout_backward_impl(egnn_ctx* ctx, const egnn_graph* g, const int32
       !dW_r1 || !dW_r2 || !dV || !ws)
     return egnn_fail(ctx, EGNN_EINVAL, "readout_backward: null pointer");
   if (((uintptr_t)ws & 255) != 0) return egnn_fail(ctx, EGNN_EINVAL, "readout_backward: workspace not 256-byte aligned");
-  const int nq = ctx->n_orb * ctx->n_orb, nv = vrows(ctx);
+  const int nq = ctx->n_orb * ctx->n_orb;
   if (egnn_readout_backward_lds_bytes(ctx) > 160 * 1024)
     return egnn_fail(ctx, EGNN_EINVAL, "readout_backward: orbital basis too large for the LDS tiles");
   ReadoutBwdBufs b;
@@ -216,29 +218,38 @@ static int readout_backward_impl(egnn_ctx* ctx, const egnn_graph* g, const int32
   const int n_t = g->n_total;
   const int row_len = (int)(row_bytes(ctx) / sizeof(float));
 
-  // tables: transposed uncoupling (q <- H), slots, and the q offset of every row of V
+  // tables: transposed uncoupling (q <- H) and slots.  The collapsed values are numbered by the row of V that produces
+  // them, as egnn_readout_backward_q_layout lays them out (rows of one coupled degree consecutive, so the kernel finds
+  // the values of a row without a table); the numbers that stand for no value have an empty list.
   std::vector<int>& ti = ctx->tab_rob_i;
   std::vector<float>& tf = ctx->tab_rob_f;
   if (ti.empty()) {
     std::vector<std::vector<std::pair<int, float>>> byq(nq);
     for (int hidx = 0; hidx < nq; ++hidx)
       for (int n = ctx->unc_ptr[hidx]; n < ctx->unc_ptr[hidx + 1]; ++n) byq[ctx->unc_q[n]].push_back({hidx, ctx->unc_c[n]});
+    int v_off[EGNN_L_READOUT + 2] = {0}, q_off[EGNN_L_READOUT + 2], nqp;
+    for (int L = 0; L <= EGNN_L_READOUT; ++L) v_off[L + 1] = v_off[L] + ctx->n_out[L];
+    egnn_readout_backward_q_layout(ctx, q_off, &nqp);
+    std::vector<int> by_row(nqp, -1);   // by_row[new number] = number of the value in the forward pass
+    for (int s = 0; s < ctx->n_slots; ++s) {
+      const int L = ctx->slot_L[s];
+      for (int M = 0; M < 2 * L + 1; ++M)
+        by_row[q_off[L] + (ctx->slot_vrow[s] - v_off[L]) * (2 * L + 1) + M] = ctx->slot_qoff[s] + M;
+    }
     int run = 0;
     ti.push_back(0);
-    for (int q = 0; q < nq; ++q) {
-      run += (int)byq[q].size();
+    for (int q = 0; q < nqp; ++q) {
+      if (by_row[q] >= 0) run += (int)byq[by_row[q]].size();
       ti.push_back(run);
     }
-    for (int q = 0; q < nq; ++q)
-      for (auto& e : byq[q]) {
-        ti.push_back(e.first);
-        tf.push_back(e.second);
-      }
+    for (int q = 0; q < nqp; ++q)
+      if (by_row[q] >= 0)
+        for (auto& e : byq[by_row[q]]) {
+          ti.push_back(e.first);
+          tf.push_back(e.second);
+        }
     ti.insert(ti.end(), ctx->slot_L.begin(), ctx->slot_L.end());
     ti.insert(ti.end(), ctx->slot_qoff.begin(), ctx->slot_qoff.end());
-    std::vector<int> vq(nv, 0);
-    for (int s = 0; s < ctx->n_slots; ++s) vq[ctx->slot_vrow[s]] = ctx->slot_qoff[s];
-    ti.insert(ti.end(), vq.begin(), vq.end());
   }
   // (sources owned by the context: no need to wait for the copies)
   EGNN_HIP(ctx, hipMemcpyAsync(b.tab_i, ti.data(), ti.size() * sizeof(int), hipMemcpyHostToDevice, st));

@@ -139,6 +139,7 @@ int egnn_launch_radial_backward(egnn_ctx*, int which, const float* rhat_d, int64
 static inline unsigned* egnn_radial_backward_dw_max(void* ws) { return reinterpret_cast<unsigned*>(ws); }
 size_t egnn_readout_backward_partial_bytes(const egnn_ctx*, int64_t n_edges);
 size_t egnn_readout_backward_lds_bytes(const egnn_ctx*);
+void egnn_readout_backward_q_layout(const egnn_ctx*, int* q_off, int* nqp);   // q_off[EGNN_L_READOUT + 2]
 int egnn_launch_readout_backward(egnn_ctx*, const egnn_graph*, const float* rhat_d, const float* zs, const float* zt,
                                  const float* w, const float* V, const int* tab_i, const float* tab_f,
                                  const float* dH, float* dz, float* dw, float* dV, float* partial, hipStream_t,

@@ -15,6 +15,7 @@
 #define ROB_MAX_WG 8192   // workgroups (= partial results of dV): many short ones, so that the last round of
                           // resident workgroups is nearly as full as the others
 #define ROB_D 25
+#define ROB_R 4            // rows of V per group of the collapse adjoint
 
 struct ReadoutBwdTabs {
   const int* uncT_ptr;   // [nq+1]  CSR over collapsed values q: which H entries they feed
@@ -22,9 +23,11 @@ struct ReadoutBwdTabs {
   const float* uncT_c;   // [nnz]
   const int* slot_L;     // [n_slots]
   const int* slot_qoff;  // [n_slots]
-  const int* vrow_qoff;  // [n_vrows] offset of the (2L+1) values of the slot that uses row o of V
   int nq, n_slots, n_vrows, nnz;
-  int v_off[EGNN_L_READOUT + 2];
+  int nqp;                         // length of the array of collapsed values (= nq)
+  int v_off[EGNN_L_READOUT + 2];   // first row of V of every coupled degree
+  int q_off[EGNN_L_READOUT + 2];   // first collapsed value of every coupled degree: the values are numbered by row of
+                                   // V, (row o of degree L, M) at q_off[L] + (o - v_off[L]) (2L+1) + M
 };
 
 // Synchronisation among the lanes of a slot: up to 64 channels the slot lies inside one wavefront, whose LDS accesses
@@ -39,47 +42,74 @@ __device__ __forceinline__ void rob_slot_sync(int log2E) {
   }
 }
 
-// Adjoint of the collapse for the rows o of V that belong to coupled degree L.  The partial dV of the wavefront is
-// kept in LDS, one value per (row, channel): the slots of a wavefront (same channel, different edges) add their
-// contributions with a fixed-order butterfly first, then the first slot updates the sum.
+// Adjoint of the collapse for the rows o of V that belong to coupled degree L.  V, the collapsed gradients dq of the
+// slot's edge (numbered by row of V) and the partial dV of the wavefront (one value per (row, channel)) all sit in
+// LDS, and every address is the lane's base plus a scalar: no look-up stands between a row and its values.  Up to 32
+// channels a wavefront holds several edges of the same channel: their contributions to dV are added first (a
+// butterfly below 32 lanes, then one exchange of the wavefront's halves that leaves the total of one row in the lower
+// half and the total of the next row in the upper half), and both halves update the sum, each its own row.  Rows are
+// taken four at a time; rows past the end of the degree repeat its last row with weight zero and are not written.
 template <int L>
-__device__ __forceinline__ void collapse_adjoint(const ReadoutBwdTabs& tb, const float* __restrict__ V,
-                                                 const float* __restrict__ sq, const int* __restrict__ s_vq,
-                                                 float* __restrict__ sdVw, const float* u, float* du, int c, int wl,
-                                                 int log2E) {
+__device__ __forceinline__ void collapse_adjoint(const ReadoutBwdTabs& tb, const float* __restrict__ sV,
+                                                 const float* __restrict__ sq, float* __restrict__ sdVw,
+                                                 const float* u, float* du, int c, int wl, int log2E) {
+  constexpr int W = 2 * L + 1;
+  constexpr int R = ROB_R;
   const int E = 1 << log2E;
   const int log2Ew = log2E < 6 ? log2E : 6;
-  const bool writer = wl < (1 << log2Ew);
-  // four rows at a time, so that four butterflies and four LDS updates are in flight (rows past the end of the
-  // degree repeat its last row with weight zero and are not written)
-  const int o_end = tb.v_off[L + 1];
-  for (int o0 = tb.v_off[L]; o0 < o_end; o0 += 4) {
-    float dot[4];
+  const bool paired = log2E < 6;
+  const int n = tb.v_off[L + 1] - tb.v_off[L];
+  const float* q0 = sq + tb.q_off[L];
+  const float* Vp = sV + (tb.v_off[L] << log2E) + c;
+  // the lane's own element of the partial sum: its channel, and for the halves of a wavefront that share channels
+  // the row that half ends up with
+  const int half = paired ? wl >> 5 : 0;
+  const bool writer = paired ? (wl & 31) < E : true;
+  float* dvp = sdVw + (tb.v_off[L] << log2Ew) + (paired ? (wl & 31) : wl);
+  for (int r0 = 0; r0 < n; r0 += R) {
+    float dot[R];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const bool ok = o0 + r < o_end;
-      const int o = ok ? o0 + r : o_end - 1;
-      const float* q = sq + s_vq[o];
-      const float vv = ok ? V[((size_t)o << log2E) + c] : 0.0f;
+    for (int r = 0; r < R; ++r) {
+      const bool ok = r0 + r < n;
+      const int rr = ok ? r0 + r : n - 1;
+      const float* q = q0 + rr * W;
+      const float vl = Vp[rr << log2E];
+      const float v = ok ? vl : 0.0f;
       float dsum = 0.0f;
 #pragma unroll
-      for (int M = 0; M < 2 * L + 1; ++M) {
+      for (int M = 0; M < W; ++M) {
         const float qv = q[M];
         dsum += qv * u[L * L + M];
-        du[L * L + M] += vv * qv;
+        du[L * L + M] += v * qv;
       }
       dot[r] = dsum;
     }
-    for (int off = E; off < 64; off <<= 1) {
+    if (paired) {
+      for (int off = E; off < 32; off <<= 1) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) dot[r] += __shfl_xor(dot[r], off);
-    }
-    if (writer) {
+        for (int r = 0; r < R; ++r) dot[r] += __shfl_xor(dot[r], off);
+      }
 #pragma unroll
-      for (int r = 0; r < 4; ++r)
-        if (o0 + r < o_end) sdVw[((o0 + r) << log2Ew) + wl] += dot[r];
+      for (int r = 0; r < R; r += 2) {
+        // lower half: dot[r] of both halves; upper half: dot[r + 1] of both halves
+        const auto x = __builtin_amdgcn_permlane32_swap(__float_as_uint(dot[r]), __float_as_uint(dot[r + 1]), false, false);
+        const float sum = __uint_as_float(x[0]) + __uint_as_float(x[1]);
+        const int row = r0 + r + half;
+        if (writer && row < n) dvp[row << log2Ew] += sum;
+      }
+    } else {
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+        if (r0 + r < n) dvp[(r0 + r) << log2Ew] += dot[r];
     }
   }
+}
+
+// Numbering of the collapsed values of one edge in LDS and in the transposed uncoupling table: by row of V.
+void egnn_readout_backward_q_layout(const egnn_ctx* ctx, int* q_off, int* nqp) {
+  q_off[0] = 0;
+  for (int L = 0; L <= EGNN_L_READOUT; ++L) q_off[L + 1] = q_off[L] + ctx->n_out[L] * (2 * L + 1);
+  *nqp = q_off[EGNN_L_READOUT + 1];
 }
 
 // The bond-frame product and its adjoint, one input degree at a time.  The rows of z of a degree, of the rotated
@@ -148,22 +178,24 @@ __global__ __launch_bounds__(256, 3) void readout_backward_kernel(
   const int n_slots = 256 >> log2E;
   const int log2Ew = log2E < 6 ? log2E : 6;                  // channels of a slot that one wavefront covers
   const int nvw = tb.n_vrows << log2Ew;
-  float* sq = smem + (size_t)slot * tb.nq;                   // [nq] per slot: dq
-  float* sh = smem + (size_t)(n_slots + slot) * tb.nq;       // [nq] per slot: the edge's block of dH
-  float* sdV_all = smem + (size_t)2 * n_slots * tb.nq;       // [4 waves][n_vrows][2^log2Ew]
+  float* sq = smem + (size_t)slot * tb.nqp;                                  // [nqp] per slot: dq
+  float* sh = smem + (size_t)n_slots * tb.nqp + (size_t)slot * tb.nq;        // [nq] per slot: the edge's block of dH
+  float* sdV_all = smem + (size_t)n_slots * (tb.nqp + tb.nq);                // [4 waves][n_vrows][2^log2Ew]
   float* sdVw = sdV_all + (size_t)wave * nvw;
   for (int i = wl; i < nvw; i += 64) sdVw[i] = 0.0f;
   // the index tables, once per workgroup
-  int* s_ptr = reinterpret_cast<int*>(sdV_all + (size_t)4 * nvw);  // [nq + 1]
-  int* s_h = s_ptr + tb.nq + 1;                            // [nnz]
+  int* s_ptr = reinterpret_cast<int*>(sdV_all + (size_t)4 * nvw);  // [nqp + 1]
+  int* s_h = s_ptr + tb.nqp + 1;                           // [nnz]
   float* s_c = reinterpret_cast<float*>(s_h + tb.nnz);     // [nnz]
-  int* s_vq = reinterpret_cast<int*>(s_c + tb.nnz);        // [n_vrows]
-  for (int i = tid; i <= tb.nq; i += 256) s_ptr[i] = tb.uncT_ptr[i];
+  for (int i = tid; i <= tb.nqp; i += 256) s_ptr[i] = tb.uncT_ptr[i];
   for (int i = tid; i < tb.nnz; i += 256) {
     s_h[i] = tb.uncT_h[i];
     s_c[i] = tb.uncT_c[i];
   }
-  for (int i = tid; i < tb.n_vrows; i += 256) s_vq[i] = tb.vrow_qoff[i];
+  // V too: read from memory inside the loop over its rows, every group of rows would wait for a round trip to the
+  // cache behind the stores of the edge before
+  float* sV = s_c + tb.nnz;                                // [n_vrows][E]
+  for (int i = tid; i < (tb.n_vrows << log2E); i += 256) sV[i] = V[i];
   __syncthreads();
 
   const long k_base = (long)blockIdx.x * n_slots * iters;
@@ -197,7 +229,7 @@ __global__ __launch_bounds__(256, 3) void readout_backward_kernel(
       for (int q = c; q < tb.nq; q += E) sh[q] = live ? hrow[q] : 0.0f;
     }
     rob_slot_sync(log2E);
-    for (int q = c; q < tb.nq; q += E) {
+    for (int q = c; q < tb.nqp; q += E) {
       float sum = 0.0f;
       for (int n = s_ptr[q]; n < s_ptr[q + 1]; ++n) sum += s_c[n] * sh[s_h[n]];
       sq[q] = sum;
@@ -215,11 +247,11 @@ __global__ __launch_bounds__(256, 3) void readout_backward_kernel(
       egnn_from_bond_frame<4>(u, t);
 #pragma unroll
       for (int i = 0; i < ROB_D; ++i) du[i] = 0.0f;
-      collapse_adjoint<0>(tb, V, sq, s_vq, sdVw, u, du, c, wl, log2E);
-      collapse_adjoint<1>(tb, V, sq, s_vq, sdVw, u, du, c, wl, log2E);
-      collapse_adjoint<2>(tb, V, sq, s_vq, sdVw, u, du, c, wl, log2E);
-      collapse_adjoint<3>(tb, V, sq, s_vq, sdVw, u, du, c, wl, log2E);
-      collapse_adjoint<4>(tb, V, sq, s_vq, sdVw, u, du, c, wl, log2E);
+      collapse_adjoint<0>(tb, sV, sq, sdVw, u, du, c, wl, log2E);
+      collapse_adjoint<1>(tb, sV, sq, sdVw, u, du, c, wl, log2E);
+      collapse_adjoint<2>(tb, sV, sq, sdVw, u, du, c, wl, log2E);
+      collapse_adjoint<3>(tb, sV, sq, sdVw, u, du, c, wl, log2E);
+      collapse_adjoint<4>(tb, sV, sq, sdVw, u, du, c, wl, log2E);
       egnn_to_bond_frame<4>(du, t);
       RobBwdDegree<LMAX, 0>::run(zsp, ztp, t, du, wr, dw + ((size_t)k * P << log2E) + c,
                                  dz + ((size_t)k * D << log2E) + c, live, log2E);
@@ -260,18 +292,21 @@ static int rob_vrows(const egnn_ctx* ctx) {
   return n;
 }
 
-// dynamic LDS of the kernel: dq and the block of dH per slot, one partial dV per wavefront, the index tables
+// dynamic LDS of the kernel: dq and the block of dH per slot, one partial dV per wavefront, V, the index tables
 size_t egnn_readout_backward_lds_bytes(const egnn_ctx* ctx) {
   const int E = ctx->desc.channels, n_slots = 256 / E, Ew = E < 64 ? E : 64;
   const size_t nq = (size_t)ctx->n_orb * ctx->n_orb, nnz = ctx->unc_q.size(), n_vrows = (size_t)rob_vrows(ctx);
-  return (2 * n_slots * nq + 4 * n_vrows * Ew) * sizeof(float) + (nq + 1 + 2 * nnz + n_vrows) * sizeof(int);
+  int q_off[EGNN_L_READOUT + 2], nqp;
+  egnn_readout_backward_q_layout(ctx, q_off, &nqp);
+  return (n_slots * (nqp + nq) + 4 * n_vrows * Ew + n_vrows * E) * sizeof(float) + ((size_t)nqp + 1 + 2 * nnz) * sizeof(int);
 }
 
 size_t egnn_readout_backward_partial_bytes(const egnn_ctx* ctx, int64_t n_edges) {
   return (size_t)rob_grid(ctx, n_edges) * rob_vrows(ctx) * ctx->desc.channels * sizeof(float);
 }
 
-// tab_i layout: uncT_ptr[nq+1] uncT_h[nnz] slot_L[n_slots] slot_qoff[n_slots] vrow_qoff[n_vrows]; tab_f: uncT_c[nnz]
+// tab_i layout: uncT_ptr[nqp+1] uncT_h[nnz] slot_L[n_slots] slot_qoff[n_slots]; tab_f: uncT_c[nnz]; the collapsed
+// values are numbered as egnn_readout_backward_q_layout lays them out
 int egnn_launch_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, const float* zs,
                                  const float* zt, const float* w, const float* V, const int* tab_i,
                                  const float* tab_f, const float* dH, float* dz, float* dw, float* dV,
@@ -290,11 +325,11 @@ int egnn_launch_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const float
   tb.nnz = nnz;
   tb.v_off[0] = 0;
   for (int L = 0; L <= EGNN_L_READOUT; ++L) tb.v_off[L + 1] = tb.v_off[L] + ctx->n_out[L];
+  egnn_readout_backward_q_layout(ctx, tb.q_off, &tb.nqp);
   tb.uncT_ptr = tab_i;
-  tb.uncT_h = tab_i + nq + 1;
+  tb.uncT_h = tab_i + tb.nqp + 1;
   tb.slot_L = tb.uncT_h + nnz;
   tb.slot_qoff = tb.slot_L + ctx->n_slots;
-  tb.vrow_qoff = tb.slot_qoff + ctx->n_slots;
   tb.uncT_c = tab_f;
   const size_t shmem = egnn_readout_backward_lds_bytes(ctx);
   const long grid_x = rob_grid(ctx, n);
