@@ -224,6 +224,42 @@ def test_readout_backward(B, lmax, E, n, n_owned, periodic, route):
     assert all(e < TOL for e in errs.values()), errs
 
 
+@pytest.mark.parametrize("orb_l,lmax,E", [((0, 1), 2, 32), ((1, 2), 4, 32), ((0, 0, 0, 1, 1, 1, 2, 2), 4, 32),
+                                          ((2, 0, 1), 3, 64), ((0, 1, 1), 2, 16)])
+def test_readout_and_its_adjoint_with_other_orbital_bases(B, orb_l, lmax, E):
+    """Bases other than the default (s, s, p, p, d): the numbers of rows of V per coupled degree, the uncoupling table
+    and the numbering of the collapsed values all change with the basis (one basis has degrees with more than 32 rows
+    and degrees with none)."""
+    n, n_rbf, r_cut = 60, 6, 4.0
+    w = synth.small_cluster(n, n, lmax, E, n_rbf, r_cut, 77, False, 0.05)
+    g = U.oracle_graph(w)
+    m = B.Egnn(lmax, E, n_rbf, r_cut, 1.0, orb_l=orb_l)
+    _, n_out = O.readout_slots(orb_l)
+    assert list(m.n_out) == list(n_out)
+    n_orb = sum(2 * l + 1 for l in orb_l)
+    pos = B.to_device(w.pos)
+    graph = m.egnn_nlist(pos, n, w.box, w.pbc)
+    assert graph.n_edges == len(g[0])
+    ws = m.backward_workspace(graph)
+    col_ptr, perm = m.egnn_graph_transpose(graph, ws)
+    rng = np.random.default_rng(5)
+    Wr = synth.readout_weights(rng, lmax, E, n_rbf, 64, m.n_paths_readout, sum(n_out))
+    x = synth.node_features(rng, n, lmax, E)
+    H = m.egnn_readout_hij(graph, pos, w.box, B.to_device(x), B.to_device(Wr), ws).cpu().numpy()
+    H_ref = O.readout_hij(g, w.pos, w.box, x, Wr, lmax, lmax, E, n_rbf, r_cut, orb_l)
+    assert H.shape == (len(g[0]), n_orb, n_orb)
+    assert U.rel_err(H, H_ref) < TOL
+    dH = synth.normal(rng, (len(g[0]), n_orb, n_orb))
+    dx, grads = m.egnn_readout_backward(graph, col_ptr, perm, pos, w.box, B.to_device(x), B.to_device(Wr),
+                                        B.to_device(dH), ws)
+    dx_ref, g_ref = O.readout_backward(g, w.pos, w.box, x, Wr, lmax, lmax, E, n_rbf, r_cut, orb_l,
+                                       dH.astype(np.float64))
+    errs = {"dx": U.rel_err(dx.cpu().numpy(), dx_ref)}
+    errs.update({k: U.rel_err(grads[k].cpu().numpy(), g_ref[k]) for k in g_ref})
+    print(orb_l, list(n_out), errs, flush=True)
+    assert all(e < TOL for e in errs.values()), errs
+
+
 def test_graph_without_edges(B):
     """No edges at all: no blocks (the block buffers may be NULL), the readout has zero gradients, and the layer and
     its adjoint reduce to the self term."""
