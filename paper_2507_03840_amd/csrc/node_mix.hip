@@ -108,32 +108,51 @@ __global__ __launch_bounds__(256) void node_mix_mfma_kernel(const float* __restr
     if (W2) smem[E * E + at] = W2[(size_t)l * E * E + i];
   }
   __syncthreads();
+  // Items = (row tile, input) pairs in order; the half row of the next item is requested before the matrix-core
+  // instructions of the current one are issued, so that a wave's loads and its arithmetic overlap.
+  auto row_offset = [&](int t, bool& valid) -> size_t {
+    const long r0 = (((long)blockIdx.x * tiles + t) * 4 + wave) * 32;
+    valid = t < tiles && r0 < n_rows;
+    long r = r0 + m;
+    if (r >= n_rows) r = n_rows - 1;
+    if (!valid) r = 0;
+    const long node = r / nm;
+    return (((size_t)node * D + l * l + (int)(r - node * nm)) << LOG2E) + hh * KH;
+  };
+  auto fetch = [&](const float* x, size_t off, float* a) {
+    const float4* xr = reinterpret_cast<const float4*>(x + off);
+#pragma unroll
+    for (int q = 0; q < KH / 4; ++q) {
+      const float4 v = xr[q];
+      a[4 * q] = v.x; a[4 * q + 1] = v.y; a[4 * q + 2] = v.z; a[4 * q + 3] = v.w;
+    }
+  };
+  bool valid;
+  size_t off = row_offset(0, valid);
+  if (!valid) return;
+  float a[KH], an[KH];
+  fetch(x1, off, a);
   for (int t = 0; t < tiles; ++t) {
     const long r0 = (((long)blockIdx.x * tiles + t) * 4 + wave) * 32;
-    if (r0 >= n_rows) break;
+    bool valid_next;
+    const size_t off_next = row_offset(t + 1, valid_next);
     mix_float16v acc[NCB];
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[cb][i] = 0.0f;
-    long r = r0 + m;
-    if (r >= n_rows) r = n_rows - 1;
-    const long node = r / nm;
-    const size_t off = (((size_t)node * D + l * l + (int)(r - node * nm)) << LOG2E) + hh * KH;
     for (int in = 0; in < n_in; ++in) {
-      const float4* xr = reinterpret_cast<const float4*>((in ? x2 : x1) + off);
-      float a[KH];
-#pragma unroll
-      for (int q = 0; q < KH / 4; ++q) {
-        const float4 v = xr[q];
-        a[4 * q] = v.x; a[4 * q + 1] = v.y; a[4 * q + 2] = v.z; a[4 * q + 3] = v.w;
-      }
+      // next item: the second input of this tile, or the first input of the next tile
+      const bool more = in + 1 < n_in || valid_next;
+      if (more) fetch(in + 1 < n_in ? x2 : x1, in + 1 < n_in ? off : off_next, an);
       const float* wt = smem + (size_t)in * E * E + (size_t)(hh * KH) * E + m;
 #pragma unroll
       for (int s = 0; s < KH; ++s)
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb)
           acc[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s], wt[s * E + 32 * cb], acc[cb], 0, 0, 0);
+#pragma unroll
+      for (int s = 0; s < KH; ++s) a[s] = an[s];
     }
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -145,6 +164,8 @@ __global__ __launch_bounds__(256) void node_mix_mfma_kernel(const float* __restr
         for (int cb = 0; cb < NCB; ++cb) out[32 * cb] = acc[cb][i];
       }
     }
+    if (!valid_next) break;
+    off = off_next;
   }
 }
 
@@ -155,7 +176,9 @@ static int launch_node_mix_mfma(egnn_ctx* ctx, const float* x1, const float* W1,
   const int lmax = ctx->desc.lmax;
   const long max_rows = (long)n_nodes * (2 * lmax + 1);
   const long n_tiles = (max_rows + 127) / 128;                 // 4 waves x 32 rows
-  long tiles = n_tiles / 2048;
+  // several tiles per workgroup once there are enough of them to fill the chip (the next tile's rows are in flight
+  // while the current one is multiplied; measured at 500,000 rows of 64 channels: 0.120 -> 0.103 ms)
+  long tiles = n_tiles / 256;
   tiles = tiles < 1 ? 1 : (tiles > 8 ? 8 : tiles);
   dim3 grid((unsigned)((n_tiles + tiles - 1) / tiles), lmax + 1), block(256);
   const size_t shmem = (size_t)(W2 ? 2 : 1) * E * E * sizeof(float);
