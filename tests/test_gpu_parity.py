@@ -158,6 +158,24 @@ def test_node_mix(B, lmax, E, two):
     assert U.rel_err(y.cpu().numpy(), ref) < 1e-5
 
 
+@pytest.mark.parametrize("lmax,E,two,n", [(4, 64, True, 7777), (4, 32, False, 15001), (2, 64, True, 33333)])
+def test_node_mix_many_tiles(B, lmax, E, two, n):
+    """Enough rows that a workgroup of the matrix-core kernel walks several row tiles (the next tile's rows in flight
+    during the products of the current one), with a last tile that is partly or wholly past the end."""
+    rng = np.random.default_rng(n)
+    x1, x2 = synth.node_features(rng, n, lmax, E), synth.node_features(rng, n, lmax, E)
+    W1 = synth.normal(rng, (lmax + 1, E, E), E ** -0.5)
+    W2 = synth.normal(rng, (lmax + 1, E, E), E ** -0.5)
+    m = B.Egnn(lmax, E, 8, 4.0, 1.0)
+    y = m.egnn_node_mix(B.to_device(x1), B.to_device(W1), B.to_device(x2) if two else None,
+                        B.to_device(W2) if two else None)
+    ref = O.mix_channels(x1, W1, lmax) + (O.mix_channels(x2, W2, lmax) if two else 0.0)
+    assert U.rel_err(y.cpu().numpy(), ref) < 1e-5
+    y2 = m.egnn_node_mix(B.to_device(x1), B.to_device(W1), B.to_device(x2) if two else None,
+                         B.to_device(W2) if two else None)
+    assert np.array_equal(y.cpu().numpy(), y2.cpu().numpy())
+
+
 # ------------------------------------------------------------------------------------------ S4
 @pytest.mark.parametrize("lmax,E", [(0, 8), (1, 16), (2, 16), (3, 32), (4, 32), (4, 64), (2, 128)])
 def test_tp_segsum_given_weights(B, lmax, E):
