@@ -59,7 +59,7 @@ static size_t readout_bwd_tab_ints(const egnn_ctx* ctx) {
   const int nq = ctx->n_orb * ctx->n_orb;
   int q_off[EGNN_L_READOUT + 2], nqp;
   egnn_readout_backward_q_layout(ctx, q_off, &nqp);
-  return (size_t)(nqp > nq ? nqp : nq) + 1 + ctx->unc_q.size() + 2 * ctx->n_slots;
+  return (size_t)(nqp > nq ? nqp : nq) + 1 + ctx->unc_q.size();
 }
 
 static size_t carve_readout_bwd(const egnn_ctx* ctx, const egnn_graph* g, char* base, ReadoutBwdBufs* b) {
@@ -218,7 +218,7 @@ static int readout_backward_impl(egnn_ctx* ctx, const egnn_graph* g, const int32
   const int n_t = g->n_total;
   const int row_len = (int)(row_bytes(ctx) / sizeof(float));
 
-  // tables: transposed uncoupling (q <- H) and slots.  The collapsed values are numbered by the row of V that produces
+  // table: transposed uncoupling (q <- H).  The collapsed values are numbered by the row of V that produces
   // them, as egnn_readout_backward_q_layout lays them out (rows of one coupled degree consecutive, so the kernel finds
   // the values of a row without a table); the numbers that stand for no value have an empty list.
   std::vector<int>& ti = ctx->tab_rob_i;
@@ -248,8 +248,6 @@ static int readout_backward_impl(egnn_ctx* ctx, const egnn_graph* g, const int32
           ti.push_back(e.first);
           tf.push_back(e.second);
         }
-    ti.insert(ti.end(), ctx->slot_L.begin(), ctx->slot_L.end());
-    ti.insert(ti.end(), ctx->slot_qoff.begin(), ctx->slot_qoff.end());
   }
   // (sources owned by the context: no need to wait for the copies)
   EGNN_HIP(ctx, hipMemcpyAsync(b.tab_i, ti.data(), ti.size() * sizeof(int), hipMemcpyHostToDevice, st));

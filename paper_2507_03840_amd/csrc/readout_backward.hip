@@ -21,9 +21,7 @@ struct ReadoutBwdTabs {
   const int* uncT_ptr;   // [nq+1]  CSR over collapsed values q: which H entries they feed
   const int* uncT_h;     // [nnz]
   const float* uncT_c;   // [nnz]
-  const int* slot_L;     // [n_slots]
-  const int* slot_qoff;  // [n_slots]
-  int nq, n_slots, n_vrows, nnz;
+  int nq, n_vrows, nnz;
   int nqp;                         // length of the array of collapsed values (= nq)
   int v_off[EGNN_L_READOUT + 2];   // first row of V of every coupled degree
   int q_off[EGNN_L_READOUT + 2];   // first collapsed value of every coupled degree: the values are numbered by row of
@@ -305,7 +303,7 @@ size_t egnn_readout_backward_partial_bytes(const egnn_ctx* ctx, int64_t n_edges)
   return (size_t)rob_grid(ctx, n_edges) * rob_vrows(ctx) * ctx->desc.channels * sizeof(float);
 }
 
-// tab_i layout: uncT_ptr[nqp+1] uncT_h[nnz] slot_L[n_slots] slot_qoff[n_slots]; tab_f: uncT_c[nnz]; the collapsed
+// tab_i layout: uncT_ptr[nqp+1] uncT_h[nnz]; tab_f: uncT_c[nnz]; the collapsed
 // values are numbered as egnn_readout_backward_q_layout lays them out
 int egnn_launch_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const float* rhat_d, const float* zs,
                                  const float* zt, const float* w, const float* V, const int* tab_i,
@@ -320,7 +318,6 @@ int egnn_launch_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const float
   const int nnz = (int)ctx->unc_q.size();
   ReadoutBwdTabs tb;
   tb.nq = nq;
-  tb.n_slots = ctx->n_slots;
   tb.n_vrows = n_vrows;
   tb.nnz = nnz;
   tb.v_off[0] = 0;
@@ -328,8 +325,6 @@ int egnn_launch_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const float
   egnn_readout_backward_q_layout(ctx, tb.q_off, &tb.nqp);
   tb.uncT_ptr = tab_i;
   tb.uncT_h = tab_i + tb.nqp + 1;
-  tb.slot_L = tb.uncT_h + nnz;
-  tb.slot_qoff = tb.slot_L + ctx->n_slots;
   tb.uncT_c = tab_f;
   const size_t shmem = egnn_readout_backward_lds_bytes(ctx);
   const long grid_x = rob_grid(ctx, n);
