@@ -158,7 +158,8 @@ struct RobBwdDegree {
 };
 
 // LE = log2(channels): a template parameter so that the row offsets of w, z, dw and dz are immediates.
-template <int LMAX, int LE>
+// VLDS: V staged in LDS (whenever it fits beside the other tiles); otherwise its rows are read through the cache.
+template <int LMAX, int LE, bool VLDS>
 __global__ __launch_bounds__(256, 3) void readout_backward_kernel(
     const int* __restrict__ src, const int* __restrict__ dst, const float4* __restrict__ rhat_d,
     const float* __restrict__ zs, const float* __restrict__ zt, const float* __restrict__ w,
@@ -193,7 +194,8 @@ __global__ __launch_bounds__(256, 3) void readout_backward_kernel(
   // V too: read from memory inside the loop over its rows, every group of rows would wait for a round trip to the
   // cache behind the stores of the edge before
   float* sV = s_c + tb.nnz;                                // [n_vrows][E]
-  for (int i = tid; i < (tb.n_vrows << log2E); i += 256) sV[i] = V[i];
+  if (VLDS)
+    for (int i = tid; i < (tb.n_vrows << log2E); i += 256) sV[i] = V[i];
   __syncthreads();
 
   const long k_base = (long)blockIdx.x * n_slots * iters;
@@ -245,11 +247,11 @@ __global__ __launch_bounds__(256, 3) void readout_backward_kernel(
       egnn_from_bond_frame<4>(u, t);
 #pragma unroll
       for (int i = 0; i < ROB_D; ++i) du[i] = 0.0f;
-      collapse_adjoint<0>(tb, sV, sq, sdVw, u, du, c, wl, log2E);
-      collapse_adjoint<1>(tb, sV, sq, sdVw, u, du, c, wl, log2E);
-      collapse_adjoint<2>(tb, sV, sq, sdVw, u, du, c, wl, log2E);
-      collapse_adjoint<3>(tb, sV, sq, sdVw, u, du, c, wl, log2E);
-      collapse_adjoint<4>(tb, sV, sq, sdVw, u, du, c, wl, log2E);
+      collapse_adjoint<0>(tb, VLDS ? sV : V, sq, sdVw, u, du, c, wl, log2E);
+      collapse_adjoint<1>(tb, VLDS ? sV : V, sq, sdVw, u, du, c, wl, log2E);
+      collapse_adjoint<2>(tb, VLDS ? sV : V, sq, sdVw, u, du, c, wl, log2E);
+      collapse_adjoint<3>(tb, VLDS ? sV : V, sq, sdVw, u, du, c, wl, log2E);
+      collapse_adjoint<4>(tb, VLDS ? sV : V, sq, sdVw, u, du, c, wl, log2E);
       egnn_to_bond_frame<4>(du, t);
       RobBwdDegree<LMAX, 0>::run(zsp, ztp, t, du, wr, dw + ((size_t)k * P << log2E) + c,
                                  dz + ((size_t)k * D << log2E) + c, live, log2E);
@@ -290,14 +292,19 @@ static int rob_vrows(const egnn_ctx* ctx) {
   return n;
 }
 
-// dynamic LDS of the kernel: dq and the block of dH per slot, one partial dV per wavefront, V, the index tables
-size_t egnn_readout_backward_lds_bytes(const egnn_ctx* ctx) {
+// dynamic LDS of the kernel: dq and the block of dH per slot, one partial dV per wavefront, the index tables, and V
+// if it is staged
+static size_t rob_lds_bytes(const egnn_ctx* ctx, bool with_v) {
   const int E = ctx->desc.channels, n_slots = 256 / E, Ew = E < 64 ? E : 64;
   const size_t nq = (size_t)ctx->n_orb * ctx->n_orb, nnz = ctx->unc_q.size(), n_vrows = (size_t)rob_vrows(ctx);
   int q_off[EGNN_L_READOUT + 2], nqp;
   egnn_readout_backward_q_layout(ctx, q_off, &nqp);
-  return (n_slots * (nqp + nq) + 4 * n_vrows * Ew + n_vrows * E) * sizeof(float) + ((size_t)nqp + 1 + 2 * nnz) * sizeof(int);
+  return (n_slots * (nqp + nq) + 4 * n_vrows * Ew + (with_v ? n_vrows * E : 0)) * sizeof(float) +
+         ((size_t)nqp + 1 + 2 * nnz) * sizeof(int);
 }
+
+// what the kernel needs at least (a basis that needs more than a compute unit has cannot be served)
+size_t egnn_readout_backward_lds_bytes(const egnn_ctx* ctx) { return rob_lds_bytes(ctx, false); }
 
 size_t egnn_readout_backward_partial_bytes(const egnn_ctx* ctx, int64_t n_edges) {
   return (size_t)rob_grid(ctx, n_edges) * rob_vrows(ctx) * ctx->desc.channels * sizeof(float);
@@ -326,13 +333,14 @@ int egnn_launch_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const float
   tb.uncT_ptr = tab_i;
   tb.uncT_h = tab_i + tb.nqp + 1;
   tb.uncT_c = tab_f;
-  const size_t shmem = egnn_readout_backward_lds_bytes(ctx);
+  const bool vlds = rob_lds_bytes(ctx, true) <= 160 * 1024;
+  const size_t shmem = rob_lds_bytes(ctx, vlds);
   const long grid_x = rob_grid(ctx, n);
   dim3 grid((unsigned)grid_x), block(256);
   const float4* rd = reinterpret_cast<const float4*>(rhat_d);
 #define LAUNCH(L, LE_)                                                                                            \
   do {                                                                                                            \
-    auto kern = readout_backward_kernel<L, LE_>;                                                                  \
+    auto kern = vlds ? readout_backward_kernel<L, LE_, true> : readout_backward_kernel<L, LE_, false>;            \
     if (shmem > 64 * 1024) {                                                                                      \
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                     \
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);                 \

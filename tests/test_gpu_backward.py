@@ -225,11 +225,12 @@ def test_readout_backward(B, lmax, E, n, n_owned, periodic, route):
 
 
 @pytest.mark.parametrize("orb_l,lmax,E", [((0, 1), 2, 32), ((1, 2), 4, 32), ((0, 0, 0, 1, 1, 1, 2, 2), 4, 32),
-                                          ((2, 0, 1), 3, 64), ((0, 1, 1), 2, 16)])
+                                          ((2, 0, 1), 3, 64), ((0, 1, 1), 2, 16), ((0, 0, 0, 1, 1, 1, 2, 2), 2, 64)])
 def test_readout_and_its_adjoint_with_other_orbital_bases(B, orb_l, lmax, E):
     """Bases other than the default (s, s, p, p, d): the numbers of rows of V per coupled degree, the uncoupling table
     and the numbering of the collapsed values all change with the basis (one basis has degrees with more than 32 rows
-    and degrees with none)."""
+    and degrees with none; with 64 channels its V no longer fits the adjoint kernel's LDS beside the other tiles and
+    is read through the cache)."""
     n, n_rbf, r_cut = 60, 6, 4.0
     w = synth.small_cluster(n, n, lmax, E, n_rbf, r_cut, 77, False, 0.05)
     g = U.oracle_graph(w)
