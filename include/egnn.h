@@ -311,7 +311,9 @@ int egnn_readout_backward_saved(egnn_ctx* ctx, const egnn_graph* g, const int32_
                                 float* dW_r1, float* dW_r2, float* dV, void* ws, size_t ws_bytes, void* stream);
 
 /* Adjoint of egnn_readout_hij.  dH [n_edges][n_orb][n_orb]; dx [n_total][...]; dV packed like V.
- */
+ * EGNN_EINVAL if the orbital basis is so large that the kernel's tiles (per wavefront one partial dV, per edge in
+ * flight its block of dH and the collapsed gradients) exceed the 160 KB of LDS of a compute unit: the default basis
+ * needs 37-54 KB, eight shells (s, s, s, p, p, p, d, d) 103-149 KB. */
 int egnn_readout_backward(egnn_ctx* ctx, const egnn_graph* g, const int32_t* col_ptr, const int32_t* perm,
                           const float* pos, const float box[3], const float* x, const float* W_s,
                           const float* W_t, const float* W_r1, const float* W_r2, const float* V,
