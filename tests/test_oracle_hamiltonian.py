@@ -106,6 +106,12 @@ def test_loss_l1l2_hand_values_and_padding():
     assert np.allclose(g[0], [[(1 + 2) / 2, 0], [(1 + 1) / 2, 0]])
     loss_all, _ = Hm.loss_l1l2(H, T, row, np.array([0b11], np.uint32))
     assert loss_all == pytest.approx((1 + 2 + 0.5 + 100 + 1 + 4 + 0.25 + 1e4) / 4)
+    # a target that is not zero: the loss measures H - T (zero at H = T, not at H = -T)
+    T[0] = [[0.5, 1.0], [0.5, -3.0]]
+    loss_t, g_t = Hm.loss_l1l2(H, T, row, col)
+    assert loss_t == pytest.approx((0.5 + 0.0 + 0.25 + 0.0) / 2)
+    assert np.allclose(g_t[0], [[(1 + 1) / 2, 0], [0, 0]])
+    assert Hm.loss_l1l2(T, T, row, col)[0] == 0.0 and Hm.loss_l1l2(-T, T, row, col)[0] > 0.0
 
 
 def test_loss_l1l2_gradient_by_central_differences():

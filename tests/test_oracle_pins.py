@@ -242,6 +242,51 @@ def test_neighbour_list_vs_python_brute_force(periodic):
         assert np.any(shift != 0)
 
 
+def test_cutoff_is_strict():
+    """An atom at exactly the cutoff distance is not a neighbour (|r| < r_cut, Sec. 3 "Initialization": atoms within the
+    cutoff); 3-4-5 triangle, every number exact in fp32."""
+    pos = np.array([[0, 0, 0], [3, 4, 0], [0, 0, 4.5]], np.float32)
+    box, pbc = np.array([100.0] * 3, np.float32), np.zeros(3, np.uint8)
+    src, dst, _, _ = O.neighbour_list(pos, 3, box, pbc, 5.0)
+    assert sorted(zip(src.tolist(), dst.tolist())) == [(0, 2), (2, 0)]
+    src, dst, _, _ = O.neighbour_list(pos, 3, box, pbc, np.nextafter(np.float32(5.0), np.float32(6.0)))
+    assert sorted(zip(src.tolist(), dst.tolist())) == [(0, 1), (0, 2), (1, 0), (2, 0)]
+
+
+def test_edge_vectors_are_the_short_image():
+    """r_k = r_src + shift * box - r_dst is the image of the source that lies inside the cutoff sphere of the
+    destination: found here by trying all 27 images, without using the stored shift."""
+    w = synth.small_cluster(50, 50, 1, 4, 4, r_cut=3.0, seed=4, periodic=True, density=0.08)
+    src, dst, shift, _ = O.neighbour_list(w.pos, 50, w.box, w.pbc, w.r_cut)
+    r = O.edge_vectors(w.pos, w.box, src, dst, shift)
+    assert np.any(shift != 0) and np.all(np.linalg.norm(r, axis=1) < w.r_cut)
+    p, b = w.pos.astype(np.float64), w.box.astype(np.float64)
+    for k in range(0, len(src), 7):
+        cands = [p[src[k]] + np.array(n) * b - p[dst[k]] for n in itertools.product((-1, 0, 1), repeat=3)]
+        best = min(cands, key=lambda v: float(v @ v))
+        assert np.array_equal(best, r[k])
+
+
+def test_edge_messages_sum_does_not_depend_on_the_node_chunks():
+    """The sum over incoming edges is evaluated in chunks of destination nodes: any chunk size gives the sum of
+    tensor_product over each node's own edges."""
+    lmax, E = 2, 3
+    w = synth.small_cluster(30, 22, lmax, E, 4, r_cut=3.0, seed=5, periodic=False, density=0.08)
+    g = O.neighbour_list(w.pos, w.n_owned, w.box, w.pbc, w.r_cut)
+    src, dst, shift, row_ptr = g
+    rng = np.random.default_rng(0)
+    h = rng.standard_normal((30, (lmax + 1) ** 2, E))
+    paths = O.tp_paths(lmax, lmax, lmax)
+    w_all = rng.standard_normal((len(src), len(paths), E))
+    fn = lambda d, k0, k1, paths_: w_all[k0:k1]
+    a1 = O.edge_messages_sum(g, w.pos, w.box, h, fn, lmax, lmax, 4.0, chunk_nodes=5)
+    a2 = O.edge_messages_sum(g, w.pos, w.box, h, fn, lmax, lmax, 4.0, chunk_nodes=1000)
+    r = O.edge_vectors(w.pos, w.box, src, dst, shift)
+    u = O.tensor_product(h[src], O.sph_harm_real(lmax, r / np.linalg.norm(r, axis=1)[:, None]), w_all, paths, lmax)
+    ref = np.stack([u[row_ptr[j]:row_ptr[j + 1]].sum(axis=0) for j in range(w.n_owned)]) / 2.0
+    assert np.abs(a1 - ref).max() < 1e-12 and np.abs(a2 - ref).max() < 1e-12 and np.abs(ref).max() > 0.1
+
+
 def test_neighbour_list_perfect_diamond_shells():
     # perfect diamond: 4 neighbours at a sqrt3/4, 12 at a/sqrt2, 12 at a sqrt11/4, 6 at a, 12 at a sqrt19/4
     rng = np.random.default_rng(0)

@@ -244,3 +244,62 @@ def test_layer_step_chain_is_the_derivative_of_the_loss():
     assert fd(lambda t: (w, g, x, T, Wn, We, w_att + t * v, W_g, th, tT)) == pytest.approx((gr["w_att"] * v).sum(), rel=1e-6)
     v = rng.standard_normal(W_g.shape)
     assert fd(lambda t: (w, g, x, T, Wn, We, w_att, W_g + t * v, th, tT)) == pytest.approx((gr["W_g"] * v).sum(), rel=1e-6)
+
+
+def test_chunks_node_subsets_and_edge_ranges_do_not_change_the_results():
+    """The oracle walks the edges in chunks, and the full-size tests ask it for a few destination nodes or a range of
+    edges only: every such call returns the rows of the one-piece result."""
+    lmax, E, r_cut, n_rbf = 2, 3, 4.0, 6
+    w, g, x, W_e, W0, Wr, Wi = _setup(lmax, E, n=16, n_owned=11, seed=9)
+    rng = np.random.default_rng(2)
+    n_e = len(g[0])
+    assert n_e > 40
+    T = rng.standard_normal((n_e, (lmax + 1) ** 2, E))
+    w_att = rng.standard_normal(E)
+    # message sum: chunks of 7 edges, and a subset of nodes (one of them asked for twice)
+    a = S.so2_message_sum(g, w.pos, w.box, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut, 3.0)
+    a7 = S.so2_message_sum(g, w.pos, w.box, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut, 3.0, chunk=7)
+    nodes = [10, 0, 4, 4]
+    an = S.so2_message_sum(g, w.pos, w.box, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut, 3.0, nodes=nodes)
+    assert np.abs(a7 - a).max() < 1e-13 and an.shape == (4,) + a.shape[1:] and np.abs(an - a[nodes]).max() < 1e-13
+    assert np.abs(a[nodes]).min(axis=(1, 2)).max() > 0
+    # its adjoint in chunks of 7 edges
+    da = rng.standard_normal(a.shape)
+    full = S.so2_message_sum_backward(g, w.pos, w.box, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut, 3.0, da)
+    part = S.so2_message_sum_backward(g, w.pos, w.box, x, W_e, W0, Wr, Wi, lmax, E, n_rbf, r_cut, 3.0, da, chunk=7)
+    flat = lambda t: np.concatenate([np.ravel(v) for v in (t if isinstance(t, (list, tuple)) else [t])])
+    for u, v in zip(full, part):
+        assert np.abs(flat(u) - flat(v)).max() < 1e-12 * max(1.0, np.abs(flat(u)).max())
+    # node block on a subset of nodes; edge block in chunks and on a range of edges
+    nb = S.so2_node_block(g, w.pos, w.box, x, T, W0, Wr, Wi, w_att, lmax, E, r_cut)
+    nbn = S.so2_node_block(g, w.pos, w.box, x, T, W0, Wr, Wi, w_att, lmax, E, r_cut, nodes=nodes)
+    assert np.abs(nbn - nb[nodes]).max() < 1e-13
+    eb = S.so2_edge_block(g, w.pos, w.box, x, T, W0, Wr, Wi, lmax, E, r_cut)
+    eb7 = S.so2_edge_block(g, w.pos, w.box, x, T, W0, Wr, Wi, lmax, E, r_cut, chunk=7)
+    ebr = S.so2_edge_block(g, w.pos, w.box, x, T, W0, Wr, Wi, lmax, E, r_cut, k_range=(13, 37), chunk=5)
+    assert np.abs(eb7 - eb).max() < 1e-13 and ebr.shape[0] == 24 and np.abs(ebr - eb[13:37]).max() < 1e-13
+    dT_out = rng.standard_normal(T.shape)
+    full = S.so2_edge_block_backward(g, w.pos, w.box, x, T, W0, Wr, Wi, lmax, E, r_cut, dT_out)
+    part = S.so2_edge_block_backward(g, w.pos, w.box, x, T, W0, Wr, Wi, lmax, E, r_cut, dT_out, chunk=7)
+    for u, v in zip(full, part):
+        assert np.abs(flat(u) - flat(v)).max() < 1e-12 * max(1.0, np.abs(flat(u)).max())
+
+
+def test_near_kink_lists_the_edges_whose_score_inputs_are_within_the_margin():
+    """so2_node_block_backward reports the edges with a scalar message channel closer to zero than kink_eps (where
+    LeakyReLU' is a discrete decision): checked against the scalar channels of the messages themselves."""
+    lmax, E, r_cut = 1, 4, 4.0
+    w, g, x, T, W0, Wr, Wi, rng = _block_setup(lmax, E, 8)
+    w_att = rng.standard_normal(E)
+    da = rng.standard_normal((w.n_owned, (lmax + 1) ** 2, E))
+    src, dst, shift, row_ptr = g
+    r = O.edge_vectors(w.pos, w.box, src, dst, shift)
+    y0 = S.so2_messages(src, dst, r, x, None, W0, Wr, Wi, lmax, E, 0, r_cut, T_edge=T, envelope=False)[:, 0, :]
+    eps = float(np.sort(np.abs(y0).min(axis=1))[5]) * 1.0001      # six edges fall inside the margin
+    want = np.nonzero((np.abs(y0) < eps).any(axis=1))[0].tolist()
+    got = []
+    S.so2_node_block_backward(g, w.pos, w.box, x, T, W0, Wr, Wi, w_att, lmax, E, r_cut, da, near_kink=got, kink_eps=eps)
+    assert sorted(got) == want and len(want) == 6 and max(want) > row_ptr[1]
+    none = []
+    S.so2_node_block_backward(g, w.pos, w.box, x, T, W0, Wr, Wi, w_att, lmax, E, r_cut, da, near_kink=none, kink_eps=0.0)
+    assert none == []
