@@ -584,6 +584,8 @@ def run_config(args, index, extras):
             n = min(n, w.n_owned)
             k = int(row[n])
             sub = B.Graph(graph.src[:k], graph.dst[:k], graph.row_ptr[:n + 1], graph.shift[:3 * k], n, w.n_total)
+            if not args.per_edge_rows:
+                sub = m.egnn_edge_pairs(sub)       # (sources beyond the prefix count as halo atoms: no reverse edge)
             t_ms = timed(lambda: m.egnn_layer_forward(sub, pos, w.box, x_full, layers[0], ws, out=x_out[0][:n]), 10)
             sweep.append(dict(n_dst=n, n_edges=k, ms=t_ms, edges_per_s=k / t_ms * 1e3))
             if n == w.n_owned:
