@@ -40,15 +40,16 @@ __device__ __forceinline__ void rob_slot_sync(int log2E) {
   }
 }
 
-// Adjoint of the collapse for the rows o of V that belong to coupled degree L.  V, the collapsed gradients dq of the
-// slot's edge (numbered by row of V) and the partial dV of the wavefront (one value per (row, channel)) all sit in
-// LDS, and every address is the lane's base plus a scalar: no look-up stands between a row and its values.  Up to 32
+// Adjoint of the collapse for the rows o of V that belong to coupled degree L.  V (when it fits: the kernel's VLDS),
+// the collapsed gradients dq of the slot's edge (numbered by row of V) and the partial dV of the wavefront (one value
+// per (row, channel)) sit in LDS, and every address is the lane's base plus a scalar: no look-up stands between a
+// row and its values.  Up to 32
 // channels a wavefront holds several edges of the same channel: their contributions to dV are added first (a
 // butterfly below 32 lanes, then one exchange of the wavefront's halves that leaves the total of one row in the lower
 // half and the total of the next row in the upper half), and both halves update the sum, each its own row.  Rows are
 // taken four at a time; rows past the end of the degree repeat its last row with weight zero and are not written.
 template <int L>
-__device__ __forceinline__ void collapse_adjoint(const ReadoutBwdTabs& tb, const float* __restrict__ sV,
+__device__ __forceinline__ void collapse_adjoint(const ReadoutBwdTabs& tb, const float* __restrict__ Vrows,
                                                  const float* __restrict__ sq, float* __restrict__ sdVw,
                                                  const float* u, float* du, int c, int wl, int log2E) {
   constexpr int W = 2 * L + 1;
@@ -58,7 +59,7 @@ __device__ __forceinline__ void collapse_adjoint(const ReadoutBwdTabs& tb, const
   const bool paired = log2E < 6;
   const int n = tb.v_off[L + 1] - tb.v_off[L];
   const float* q0 = sq + tb.q_off[L];
-  const float* Vp = sV + (tb.v_off[L] << log2E) + c;
+  const float* Vp = Vrows + (tb.v_off[L] << log2E) + c;
   // the lane's own element of the partial sum: its channel, and for the halves of a wavefront that share channels
   // the row that half ends up with
   const int half = paired ? wl >> 5 : 0;
