@@ -462,9 +462,19 @@ int egnn_hamiltonian_fill(egnn_ctx* ctx, const egnn_graph* g, const int32_t* spe
  *   the order the parts are finished (left before right).  cut_log (may be NULL): [2^levels - 1][4] = (level,
  *   dimension, atoms in the sub-domain, atoms on the left) for every bisection in depth-first order; n_cuts (may be
  *   NULL): how many were made (empty sub-domains make none).  levels <= 20.
+ * egnn_spatial_order: HOST function, host pointers, needs no context and no GPU.  A numbering of the atoms that keeps
+ *   neighbours in space close in index, for callers whose atoms come in no particular order (the kernels that gather
+ *   node rows process destination nodes in index order and re-use the rows that neighbouring destinations share: with
+ *   atoms in random order the message kernel of this library runs a quarter slower at the largest configuration).
+ *   pos [n_total][3]; atoms are binned into cubes of edge cell > 0 (a good choice: half the cutoff) counted from the
+ *   smallest coordinates, at most 1024 cubes per axis, the cubes are walked along a Morton curve, atoms of a cube
+ *   keep their order; perm [n_total] out: perm[new index] = old index, the owned atoms (old indices < n_owned) first,
+ *   then the halo atoms, each group in that order.  The caller permutes positions, species and features with it
+ *   before building the graph.  This changes no result beyond the numbering (and the order of floating-point sums).
  * egnn_pack_rows: out[r] = x[idx[r]] for r < n_idx (rows of (lmax+1)^2 * channels floats; idx clamped to
  *   0 .. n_rows_x - 1); half != 0: the buffer holds IEEE half precision (round to nearest even), else fp32.
  * egnn_unpack_rows: x_full[first_row + r] = buf[r] for r < n_rows (converted back to fp32 if half != 0). */
+int egnn_spatial_order(const float* pos, int32_t n_owned, int32_t n_total, float cell, int32_t* perm);
 int egnn_partition_low_nn(const float* pos, const int32_t* degree, int32_t n_atoms, const float box[3],
                           const uint8_t pbc[3], double r_cut, int32_t levels, int32_t* part, int32_t* cut_log,
                           int32_t* n_cuts);

@@ -29,7 +29,7 @@ SYMBOLS = [
     "egnn_so2_blocks_workspace_bytes", "egnn_edge_embed_init", "egnn_so2_node_block",
     "egnn_so2_edge_block", "egnn_gate", "egnn_hamiltonian_workspace_bytes", "egnn_onsite_hii", "egnn_apply_padding", "egnn_loss_l1l2",
     "egnn_hamiltonian_structure", "egnn_hamiltonian_fill", "egnn_onsite_backward_workspace_bytes", "egnn_onsite_backward",
-    "egnn_partition_low_nn", "egnn_pack_rows", "egnn_unpack_rows",
+    "egnn_partition_low_nn", "egnn_spatial_order", "egnn_pack_rows", "egnn_unpack_rows",
     "egnn_layer_forward_save", "egnn_readout_hij_save", "egnn_layer_backward_saved", "egnn_readout_backward_saved",
     "egnn_radial_weights_static", "egnn_edge_pairs_workspace_bytes", "egnn_edge_pairs",
     "egnn_length_bins_workspace_bytes", "egnn_length_bins",
@@ -121,6 +121,18 @@ LAYER_STAGES = ["geometry", "radial_weights", "mix_pre", "tp_segsum", "mix_post"
 READOUT_STAGES = ["geometry", "radial_weights", "mix_src", "mix_dst", "readout"]
 LAYER_ADJOINT_STAGES = ["forward_quantities", "mix_post_adjoint", "tp_backward", "mix_pre_adjoint", "radial_backward"]
 READOUT_ADJOINT_STAGES = ["forward_quantities", "readout_backward", "row_sums_and_mix_adjoints", "radial_backward"]
+
+
+def egnn_spatial_order(pos, n_owned, cell):
+    """Host call (numpy in, numpy out; no GPU needed): perm [n_total] with perm[new index] = old index."""
+    lib = load_library()
+    pos = np.ascontiguousarray(pos, np.float32)
+    perm = np.zeros(pos.shape[0], np.int32)
+    lib.egnn_spatial_order.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p]
+    rc = lib.egnn_spatial_order(pos.ctypes.data, int(n_owned), pos.shape[0], float(cell), perm.ctypes.data)
+    if rc:
+        raise EgnnError(rc, "egnn_spatial_order: bad argument")
+    return perm
 
 
 def egnn_partition_low_nn(pos, degree, box, pbc, r_cut, levels):

@@ -14,6 +14,7 @@
 #include <array>
 #include <cmath>
 #include <numeric>
+#include <vector>
 
 namespace {
 
@@ -195,6 +196,37 @@ extern "C" int egnn_partition_low_nn(const float* pos, const int32_t* degree, in
   LowNNBisection bisection(pos, degree, n_atoms, box, pbc, r_cut, part, cut_log, (1 << levels) - 1);
   bisection.run(levels);
   if (n_cuts) *n_cuts = bisection.cuts_made();
+  return EGNN_OK;
+}
+
+// A spatially coherent numbering of the atoms, for callers whose atoms come in no particular order: the gathering
+// kernels process destination nodes in index order and re-use the node rows that neighbouring destinations share,
+// which works as far as consecutive indices are close in space.  Atoms are binned into cubes of edge `cell` (counted
+// from the smallest coordinate of all atoms, at most 1024 per axis: the last cube takes the rest), the cubes are
+// walked along a Morton (Z-order) curve, atoms of a cube stay in their order of arrival; the owned atoms come first,
+// then the halo atoms, each group ordered in this way.
+extern "C" int egnn_spatial_order(const float* pos, int32_t n_owned, int32_t n_total, float cell, int32_t* perm) {
+  if (n_owned < 0 || n_total < n_owned || !(cell > 0.0f) || (n_total > 0 && (!pos || !perm))) return EGNN_EINVAL;
+  if (n_total == 0) return EGNN_OK;
+  double lo[3];
+  for (int a = 0; a < 3; ++a) {
+    lo[a] = pos[a];
+    for (int i = 1; i < n_total; ++i) lo[a] = std::min(lo[a], (double)pos[3 * (size_t)i + a]);
+  }
+  std::vector<uint32_t> key(n_total);
+  for (int i = 0; i < n_total; ++i) {
+    uint32_t k = 0;
+    for (int a = 0; a < 3; ++a) {
+      const double q = std::floor(((double)pos[3 * (size_t)i + a] - lo[a]) / (double)cell);
+      const uint32_t c = !(q >= 0.0) ? 0u : (q > 1023.0 ? 1023u : (uint32_t)q);   // (a NaN coordinate lands in cube 0)
+      for (int b = 0; b < 10; ++b) k |= ((c >> b) & 1u) << (3 * b + a);
+    }
+    key[i] = k;
+  }
+  std::iota(perm, perm + n_total, 0);
+  auto by_key = [&](int32_t x, int32_t y) { return key[x] < key[y]; };
+  std::stable_sort(perm, perm + n_owned, by_key);
+  std::stable_sort(perm + n_owned, perm + n_total, by_key);
   return EGNN_OK;
 }
 

@@ -61,3 +61,48 @@ def test_config4_structure_into_64_parts():
     part, log = _compare(w.pos, deg, w.box, w.pbc, w.r_cut, 6)
     sums = np.array([deg[part == q].sum() for q in range(64)])
     assert sums.max() / sums.mean() < 1.02
+
+
+def _morton_reference(pos, n_owned, cell):
+    """The definition written out with numpy: cube of every atom, bits of the three cube indices interleaved (x lowest),
+    stable sort of the owned atoms and of the halo atoms by that key."""
+    p = np.asarray(pos, np.float32).astype(np.float64)
+    q = np.clip(np.floor((p - p.min(axis=0)) / float(np.float32(cell))), 0, 1023).astype(np.int64)
+    key = np.zeros(len(p), np.int64)
+    for b in range(10):
+        for a in range(3):
+            key |= ((q[:, a] >> b) & 1) << (3 * b + a)
+    own = np.argsort(key[:n_owned], kind="stable")
+    halo = np.argsort(key[n_owned:], kind="stable") + n_owned
+    return np.concatenate([own, halo]).astype(np.int32)
+
+
+@pytest.mark.parametrize("n,n_owned,cell", [(500, 500, 2.0), (700, 450, 1.5), (64, 0, 3.0), (1, 1, 1.0), (300, 300, 0.01)])
+def test_spatial_order_is_the_morton_walk_of_the_cubes(n, n_owned, cell):
+    rng = np.random.default_rng(n)
+    pos = (rng.random((n, 3)) * np.array([20.0, 12.0, 7.0]) - 3.0).astype(np.float32)
+    pos[n // 2:n // 2 + 3] = pos[0]                               # atoms of one cube keep their order of arrival
+    perm = B.egnn_spatial_order(pos, n_owned, cell)
+    assert np.array_equal(np.sort(perm), np.arange(n))
+    assert np.all(perm[:n_owned] < n_owned) and np.all(perm[n_owned:] >= n_owned)
+    assert np.array_equal(perm, _morton_reference(pos, n_owned, cell))
+
+
+def test_spatial_order_brings_neighbours_close_in_index():
+    w = synth.small_cluster(4000, 4000, 1, 8, 4, 4.0, 3, periodic=False)
+    rng = np.random.default_rng(0)
+    pos = w.pos[rng.permutation(4000)]
+    src, dst, _, _ = O.neighbour_list(pos[:1500], 1500, w.box, w.pbc, 3.0)     # (pairs among the first atoms: a sample)
+    full = B.egnn_spatial_order(pos, 4000, 2.0)
+    new_index = np.empty(4000, np.int64); new_index[full] = np.arange(4000)
+    before = np.median(np.abs(src.astype(np.int64) - dst))
+    after = np.median(np.abs(new_index[src] - new_index[dst]))        # (the curve has jumps: the median, not the mean)
+    assert len(src) > 1000 and after < 0.1 * before
+
+
+def test_spatial_order_rejects_bad_arguments():
+    pos = np.zeros((4, 3), np.float32)
+    for n_owned, cell in [(5, 1.0), (-1, 1.0), (2, 0.0), (2, -1.0), (2, float("nan"))]:
+        with pytest.raises(B.EgnnError):
+            B.egnn_spatial_order(pos, n_owned, cell)
+    assert len(B.egnn_spatial_order(np.zeros((0, 3), np.float32), 0, 1.0)) == 0
