@@ -144,6 +144,8 @@ def main():
                          "between an edge and its reverse")
     ap.add_argument("--forward-only", action="store_true",
                     help="only the timed forward steps (no variants, no training step, no extra timings): for profiling runs")
+    ap.add_argument("--spatial-order", action="store_true",
+                    help="relabel the atoms with egnn_spatial_order first (cubes of r_cut / 2 along a Morton curve)")
     ap.add_argument("--no-partition", action="store_true",
                     help="skip the extra timing of the Low-NN partitioner and of the halo pack / unpack")
     ap.add_argument("--no-hamiltonian", action="store_true",
@@ -195,6 +197,12 @@ def run_config(args, index, extras):
     assert torch.cuda.is_available(), "bench.py needs an MI355X"
     B.load_library()
     w = synth.workload(index, check_cutoff=False)
+    if args.spatial_order:
+        # the same structure with its atoms relabelled along a Morton curve (egnn_spatial_order): what a caller whose
+        # atoms come unordered would do before building the graph; not the default (the parity tests use the
+        # generators' numbering)
+        perm = B.egnn_spatial_order(w.pos, w.n_owned, w.r_cut / 2)
+        w.pos, w.species = np.ascontiguousarray(w.pos[perm]), np.ascontiguousarray(w.species[perm])
     # weights sized from the library's own path and readout-slot counts (nothing of the oracle runs in this leg)
     sizes = B.Egnn(w.lmax, w.channels, w.n_rbf, w.r_cut, 1.0, orb_l=w.orb_l)
     wt = model_weights(w, synth, sizes.n_paths, sizes.n_paths_readout, sum(sizes.egnn_readout_widths()))
@@ -650,6 +658,7 @@ def run_config(args, index, extras):
                    "step": "nlist + species embed + %d layers fwd" % w.n_layers + (" + H_ij readout" if w.readout else
                            " (messages only into owned nodes; halo rows are read-only inputs; no readout in this configuration)")},
         "roofline": dominant, "roofline_others": other,
+        "atom_order": "egnn_spatial_order (cubes of r_cut / 2 along a Morton curve)" if args.spatial_order else "as generated",
         "stage_ms": {"layer": layer_ms, "readout": ro_ms if w.readout else None,
                      "layer_total": sum(layer_ms.values()),
                      "layer_edges_per_s": n_edges / (sum(layer_ms.values()) * 1e-3)},
