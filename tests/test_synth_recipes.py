@@ -1,0 +1,82 @@
+"""The synthetic workloads have the shapes the benchmark's configs state (sizes, densities, species, cutoffs, mean
+numbers of neighbours, model sizes), are deterministic in their index, and keep the properties the recipes promise
+(minimum distance of the amorphous structure, halo shell of the slab, no pair within rounding of the cutoff)."""
+import numpy as np
+import pytest
+
+from oracle import egnn_oracle as O
+from paper_2507_03840_amd import synth
+
+
+def _mean_degree(w, sample=None):
+    n = w.n_owned if sample is None else sample
+    # (the first `sample` owned atoms as destinations: a brute-force count over all atoms)
+    _, _, _, row_ptr = O.neighbour_list(w.pos, n, w.box, w.pbc, w.r_cut)
+    return row_ptr[-1] / n, np.diff(row_ptr)
+
+
+def test_config1_tiny_diamond():
+    w = synth.workload(1)
+    assert (w.n_owned, w.n_total, w.lmax, w.channels, w.n_rbf, w.n_layers, w.r_cut) == (64, 64, 2, 16, 8, 1, 6.0)
+    assert not w.pbc.any() and set(np.unique(w.species)) == {0, 1} and w.pos.dtype == np.float32
+    # 2 x 2 x 2 conventional cells of a = 5.43 A with a jitter of 0.05 A: nearest neighbours near a sqrt(3) / 4
+    d = np.linalg.norm(w.pos[:, None, :].astype(np.float64) - w.pos[None, :, :], axis=2) + 10.0 * np.eye(64)
+    assert abs(d.min(axis=1).mean() - synth.DIAMOND_A * np.sqrt(3) / 4) < 0.1
+    deg, _ = _mean_degree(w)
+    assert 15 < deg < 30                                        # (1,388 edges in the survey's count)
+
+
+def test_config2_diamond_1000():
+    w = synth.workload(2)
+    assert (w.n_owned, w.n_total, w.lmax, w.channels, w.n_rbf, w.n_layers, w.r_cut) == (1000, 1000, 3, 32, 16, 2, 8.0)
+    assert w.pbc.all() and set(np.unique(w.species)) == {0, 1, 2} and w.readout
+    assert np.all(np.bincount(w.species) > 250)                 # three species, uniform
+    deg, _ = _mean_degree(w)
+    assert 100 < deg < 120                                      # "~110 neighbours/atom"
+
+
+def test_config3_amorphous_3000():
+    w = synth.workload(3)
+    assert (w.n_owned, w.n_total, w.lmax, w.channels, w.n_rbf, w.n_layers, w.r_cut) == (3000, 3000, 4, 32, 16, 3, 10.0)
+    assert w.pbc.all() and set(np.unique(w.species)) == {0, 1} and w.readout and w.orb_l == (0, 0, 1, 1, 2)
+    assert abs(3000 / float(np.prod(w.box.astype(np.float64))) - 0.05) < 1e-4        # 0.05 atoms per cubic Angstrom
+    p = w.pos.astype(np.float64)
+    dmin = np.inf
+    for j in range(0, 3000, 500):
+        d = p[None, :, :] - p[j:j + 500, None, :]
+        d -= w.box * np.rint(d / w.box)
+        r2 = np.einsum("jia,jia->ji", d, d)
+        r2[np.arange(len(r2)), np.arange(j, j + len(r2))] = np.inf
+        dmin = min(dmin, float(np.sqrt(r2.min())))
+    assert dmin >= 2.0 - 1e-5                                   # 2.0 A minimum-distance rejection
+    deg, degs = _mean_degree(w)
+    assert 200 < deg < 220 and 600_000 < deg * 3000 < 650_000   # "~210 neighbours/atom, ~630k edges"
+    assert degs.min() > 150
+
+
+def test_config4_slab_with_halo():
+    w = synth.workload(4)
+    assert (w.n_owned, w.lmax, w.channels, w.n_rbf, w.n_layers, w.r_cut, w.readout) == (12000, 4, 64, 16, 3, 10.0, False)
+    assert 7000 <= w.n_total - w.n_owned <= 9000                # "~8,000 halo atoms"
+    # every halo atom lies within the cutoff of the owned region's bounding box along the open axes, none inside it
+    own, halo = w.pos[:w.n_owned].astype(np.float64), w.pos[w.n_owned:].astype(np.float64)
+    lo, hi = own.min(axis=0), own.max(axis=0)
+    for a in range(3):
+        if not w.pbc[a]:
+            assert halo[:, a].min() > lo[a] - w.r_cut - 1.0 and halo[:, a].max() < hi[a] + w.r_cut + 1.0
+    deg, degs = _mean_degree(w, sample=400)
+    assert 185 < deg < 215                                       # hundreds of neighbours per atom, as in the paper's runs
+
+
+def test_config5_is_config3_with_a_training_step():
+    w3, w5 = synth.workload(3), synth.workload(5)
+    assert np.array_equal(w3.pos, w5.pos) and np.array_equal(w3.species, w5.species)
+    assert (w5.lmax, w5.channels, w5.n_layers, w5.readout) == (w3.lmax, w3.channels, w3.n_layers, True)
+
+
+@pytest.mark.parametrize("index", [1, 2, 3])
+def test_workloads_are_deterministic_and_clear_of_the_cutoff(index):
+    a, b = synth.workload(index), synth.workload(index)
+    assert np.array_equal(a.pos, b.pos) and np.array_equal(a.species, b.species) and np.array_equal(a.box, b.box)
+    # no pair so close to the cutoff that two fp64 evaluations of the fp32 data could disagree on it
+    assert synth.closest_to_cutoff(a.pos, a.n_owned, a.box, a.pbc, a.r_cut) > synth.CUTOFF_SAFETY
