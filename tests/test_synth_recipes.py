@@ -1,4 +1,4 @@
-"""The synthetic workloads have the shapes the benchmark's configs state (sizes, densities, species, cutoffs, mean
+"""The synthetic workloads have the shapes that the five benchmark configurations state (sizes, densities, species, cutoffs, mean
 numbers of neighbours, model sizes), are deterministic in their index, and keep the properties the recipes promise
 (minimum distance of the amorphous structure, halo shell of the slab, no pair within rounding of the cutoff)."""
 import numpy as np
@@ -23,7 +23,7 @@ def test_config1_tiny_diamond():
     d = np.linalg.norm(w.pos[:, None, :].astype(np.float64) - w.pos[None, :, :], axis=2) + 10.0 * np.eye(64)
     assert abs(d.min(axis=1).mean() - synth.DIAMOND_A * np.sqrt(3) / 4) < 0.1
     deg, _ = _mean_degree(w)
-    assert 15 < deg < 30                                        # (1,388 edges in the survey's count)
+    assert 15 < deg < 30                                        # (about 1,400 edges)
 
 
 def test_config2_diamond_1000():
